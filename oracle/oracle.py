@@ -1,0 +1,362 @@
+"""MuKV CPU oracle (Python side) -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+
+Composes the plain fp64 loops of ``mukv_oracle.c`` into the two halves of the
+method in the order the paper gives them:
+
+* offline, per chunk of frames (Sec. 3.3): attention indicator (Eq. 1),
+  frequency indicator (Eq. 2-3), min-max fusion (Eq. 4), per-frame keep of the
+  kappa best tokens, storage of the kept K/V rows of every layer, and the
+  block keys of Eq. 5 at super-patch, frame and segment level;
+* online, per question (Sec. 3.4): Eq. 6 question pooling, Eq. 7 cosine
+  scoring, stage-1 candidates, the global query and Eq. 8 rerank, final
+  selection, and the concatenation of the selected blocks' KV (Sec. 3.5).
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this module.  It imports nothing from the HIP package.
+bfloat16 data is carried as ``numpy.uint16`` bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mukv_oracle.c")
+_LIB = os.path.join(_HERE, "libmukv_oracle.so")
+
+BF16, F32 = 0, 1
+SEMI, HIER, PARALLEL = 0, 1, 2
+TEMPORAL, AS_GIVEN = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the C half with gcc (-O2, OpenMP on the outer loops only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.orc_cos.restype = ctypes.c_double
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.uint16:
+        return BF16
+    if a.dtype == np.float32:
+        return F32
+    raise TypeError(f"oracle takes uint16 (bf16 bits) or float32, got {a.dtype}")
+
+
+def _c(a: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(a)
+
+
+def kappa_of(keep_ratio: float, unit: int) -> int:
+    """kappa = floor(rho * |unit|) (Sec. 3.3); 1e-9 guards ratios such as 0.29*100."""
+    return int(math.floor(keep_ratio * unit + 1e-9))
+
+
+def superpatch_bounds(P: int, S: int):
+    """Index-contiguous super-patches of length floor(P/S) (Sec. 3.2); the last
+    one takes the remainder so the S groups partition the frame."""
+    n = P // S
+    return [(s * n, (s + 1) * n if s < S - 1 else P) for s in range(S)]
+
+
+# ----------------------------------------------------------------------------
+# thin typed wrappers over the C loops
+# ----------------------------------------------------------------------------
+def att_signal(q, k, n_frames, P, causal=True):
+    q, k = _c(q), _c(k)
+    Hq, T, D = q.shape
+    Hkv = k.shape[0]
+    assert T == n_frames * P and k.shape == (Hkv, T, D)
+    out = np.empty((n_frames, P), np.float64)
+    rc = lib().orc_att_signal(_p(q), _p(k), _dtype_code(k), n_frames, Hq, Hkv, P, D, int(causal), _p(out))
+    assert rc == 0
+    return out
+
+
+def fft_signal(k, n_frames, P):
+    k = _c(k)
+    Hkv, T, D = k.shape
+    assert T == n_frames * P
+    out = np.empty((n_frames, P), np.float64)
+    rc = lib().orc_fft_signal(_p(k), _dtype_code(k), n_frames, Hkv, P, D, _p(out))
+    assert rc == 0
+    return out
+
+
+def fuse(att, fft, alpha):
+    ref = att if att is not None else fft
+    n_frames, P = ref.shape
+    out = np.empty((n_frames, P), np.float64)
+    a = None if att is None else _c(att.astype(np.float64))
+    b = None if fft is None else _c(fft.astype(np.float64))
+    rc = lib().orc_fuse(_p(a), _p(b), n_frames, P, ctypes.c_double(alpha), _p(out))
+    assert rc == 0
+    return out
+
+
+def topk(scores, k, mask=None):
+    s = _c(np.asarray(scores, np.float64))
+    m = None if mask is None else _c(np.asarray(mask, np.uint8))
+    idx = np.empty(max(k, 1), np.int32)
+    found = lib().orc_topk(_p(s), _p(m), s.shape[0], k, _p(idx))
+    return idx[:k], found
+
+
+def keep(fused, kappa):
+    fused = _c(np.asarray(fused, np.float64))
+    n_frames, P = fused.shape
+    kept = np.empty((n_frames, kappa), np.int32)
+    rc = lib().orc_keep(_p(fused), n_frames, P, kappa, _p(kept))
+    assert rc == 0
+    return kept
+
+
+def compact(src, n_frames, P, kept):
+    src = _c(src)
+    L, Hkv, T, D = src.shape
+    assert T == n_frames * P
+    kappa = kept.shape[1]
+    kept = _c(kept.astype(np.int32))
+    dst = np.empty((L, Hkv, n_frames * kappa, D), src.dtype)
+    rc = lib().orc_compact(_p(src), src.dtype.itemsize, L, Hkv, n_frames, P, D, _p(kept), kappa, _p(dst))
+    assert rc == 0
+    return dst
+
+
+def pool_rows(x, rows):
+    x = _c(x)
+    Hkv, T, D = x.shape
+    rows = _c(np.asarray(rows, np.int64))
+    out = np.empty(Hkv * D, np.float64)
+    rc = lib().orc_pool_rows(_p(x), _dtype_code(x), Hkv, ctypes.c_int64(T), D, _p(rows), rows.shape[0], _p(out))
+    assert rc == 0
+    return out
+
+
+def pool_question(q_tokens):
+    q_tokens = _c(q_tokens)
+    Nq, Hq, D = q_tokens.shape
+    out = np.empty(Hq * D, np.float64)
+    rc = lib().orc_pool_question(_p(q_tokens), _dtype_code(q_tokens), Nq, Hq, D, _p(out))
+    assert rc == 0
+    return out
+
+
+def score_blocks(q, reps32, Hq, Hkv, D):
+    q = _c(np.asarray(q, np.float64))
+    reps32 = _c(np.asarray(reps32, np.float32))
+    N = reps32.shape[0]
+    out = np.empty(N, np.float64)
+    if N:
+        rc = lib().orc_score_blocks(_p(q), _p(reps32), N, Hq, Hkv, D, _p(out))
+        assert rc == 0
+    return out
+
+
+def consistency(g_vec, reps32, cand):
+    g_vec = _c(np.asarray(g_vec, np.float64))
+    reps32 = _c(np.asarray(reps32, np.float32))
+    cand = _c(np.asarray(cand, np.int32))
+    out = np.empty(cand.shape[0], np.float64)
+    if cand.shape[0]:
+        rc = lib().orc_consistency(_p(g_vec), _p(reps32), ctypes.c_int64(reps32.shape[1]), _p(cand), cand.shape[0], _p(out))
+        assert rc == 0
+    return out
+
+
+# ----------------------------------------------------------------------------
+# the method, step by step
+# ----------------------------------------------------------------------------
+@dataclass
+class OracleConfig:
+    n_layers: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    tokens_per_frame: int
+    frames_per_segment: int
+    superpatches_per_frame: int = 4
+    keep_ratio: float = 0.25
+    alpha: float = 0.7
+    causal: bool = True
+    score_layer: int = -1
+
+
+@dataclass
+class RetrieveParams:
+    mode: int = SEMI
+    k_seg: int = 8
+    k_frame: int = 32
+    lambda_frame: float = 0.3
+    n_global: int = 0          # 0 -> k_seg
+    n_visible_frames: int = -1  # -1 -> every ingested frame
+
+
+class OracleMuKV:
+    """Streaming state of the method on the host: the compact store, the kept
+    positions (timestamps are the frame numbers) and the Eq. 5 block keys."""
+
+    def __init__(self, cfg: OracleConfig):
+        self.cfg = cfg
+        self.kappa = kappa_of(cfg.keep_ratio, cfg.tokens_per_frame)
+        assert 1 <= self.kappa <= cfg.tokens_per_frame
+        self.ls = cfg.score_layer if cfg.score_layer >= 0 else cfg.n_layers - 1
+        self.n_frames = 0
+        self._store_k, self._store_v = [], []
+        self.kept = np.empty((0, self.kappa), np.int32)
+        C = cfg.n_kv_heads * cfg.head_dim
+        self.rep_frame_k = np.empty((0, C), np.float64)
+        self.rep_frame_v = np.empty((0, C), np.float64)
+        self.rep_patch_k = np.empty((0, C), np.float64)
+        self.rep_patch_v = np.empty((0, C), np.float64)
+        self.cnt_patch = np.empty((0,), np.int32)
+
+    # -- offline ------------------------------------------------------------
+    def compress_chunk(self, k, v, q_last=None, att=None):
+        """k, v: [L][Hkv][n*P][D]; q_last: [Hq][n*P][D] of the scoring layer, or
+        att: [n][P] attention received, handed over by the caller's prefill."""
+        c = self.cfg
+        P, S = c.tokens_per_frame, c.superpatches_per_frame
+        n = k.shape[2] // P
+        assert k.shape == v.shape == (c.n_layers, c.n_kv_heads, n * P, c.head_dim)
+        k_s, v_s = k[self.ls], v[self.ls]
+        a = None
+        if c.alpha != 0.0:
+            a = att if att is not None else att_signal(q_last, k_s, n, P, c.causal)
+        fq = fft_signal(k_s, n, P) if c.alpha != 1.0 else None
+        fused = fuse(a, fq, c.alpha)
+        kept = keep(fused, self.kappa)
+        self._store_k.append(compact(k, n, P, kept))
+        self._store_v.append(compact(v, n, P, kept))
+        C = c.n_kv_heads * c.head_dim
+        rfk, rfv = np.empty((n, C)), np.empty((n, C))
+        rpk, rpv = np.empty((n * S, C)), np.empty((n * S, C))
+        cnt = np.empty(n * S, np.int32)
+        bounds = superpatch_bounds(P, S)
+        for f in range(n):
+            rows = f * P + kept[f].astype(np.int64)
+            rfk[f], rfv[f] = pool_rows(k_s, rows), pool_rows(v_s, rows)
+            for s, (lo, hi) in enumerate(bounds):
+                sel = rows[(kept[f] >= lo) & (kept[f] < hi)]
+                rpk[f * S + s], rpv[f * S + s] = pool_rows(k_s, sel), pool_rows(v_s, sel)
+                cnt[f * S + s] = sel.shape[0]
+        self.kept = np.concatenate([self.kept, kept])
+        self.rep_frame_k = np.concatenate([self.rep_frame_k, rfk])
+        self.rep_frame_v = np.concatenate([self.rep_frame_v, rfv])
+        self.rep_patch_k = np.concatenate([self.rep_patch_k, rpk])
+        self.rep_patch_v = np.concatenate([self.rep_patch_v, rpv])
+        self.cnt_patch = np.concatenate([self.cnt_patch, cnt])
+        self.n_frames += n
+        return {"att": a, "fft": fq, "fused": fused, "kept": kept}
+
+    def store(self):
+        """Compact store so far: (K, V), each [L][Hkv][n_frames*kappa][D]."""
+        if len(self._store_k) > 1:
+            self._store_k = [np.concatenate(self._store_k, axis=2)]
+            self._store_v = [np.concatenate(self._store_v, axis=2)]
+        return self._store_k[0], self._store_v[0]
+
+    def n_segments(self, n_visible=None):
+        nv = self.n_frames if n_visible is None else n_visible
+        F = self.cfg.frames_per_segment
+        return (nv + F - 1) // F
+
+    def seg_reps(self, n_visible=None, which="k"):
+        """Eq. 5 at segment level: mean over the kept tokens of the segment's
+        visible frames, scoring layer.  [n_segments][Hkv*D] float64."""
+        nv = self.n_frames if n_visible is None else n_visible
+        F, kap = self.cfg.frames_per_segment, self.kappa
+        sk, sv = self.store()
+        x = (sk if which == "k" else sv)[self.ls]
+        out = np.empty((self.n_segments(nv), x.shape[0] * x.shape[2]), np.float64)
+        for s in range(out.shape[0]):
+            f0, f1 = s * F, min((s + 1) * F, nv)
+            out[s] = pool_rows(x, np.arange(f0 * kap, f1 * kap, dtype=np.int64))
+        return out
+
+    # -- online -------------------------------------------------------------
+    def retrieve(self, q_tokens, prm: RetrieveParams):
+        """q_tokens: [Nq][Hq][D] scoring-layer query states of one question."""
+        c = self.cfg
+        Hq, Hkv, D = c.n_q_heads, c.n_kv_heads, c.head_dim
+        nv = self.n_frames if prm.n_visible_frames < 0 else min(prm.n_visible_frames, self.n_frames)
+        F = c.frames_per_segment
+        # the cache stores block keys as float32
+        frm32 = self.rep_frame_k[:nv].astype(np.float32)
+        seg32 = self.seg_reps(nv).astype(np.float32) if nv > 0 else np.empty((0, Hkv * D), np.float32)
+        q = pool_question(q_tokens)                               # Eq. 6
+        s_seg = score_blocks(q, seg32, Hq, Hkv, D)                # Eq. 7
+        s_frm = score_blocks(q, frm32, Hq, Hkv, D)
+        ks, kf = prm.k_seg, prm.k_frame
+        res = {"s_seg": s_seg, "s_frm": s_frm}
+        if prm.mode == PARALLEL:
+            seg_idx, ns = topk(s_seg, ks)
+            frm_idx, nf = topk(s_frm, kf)
+            frm_score = s_frm
+        elif prm.mode == HIER:
+            seg_idx, ns = topk(s_seg, ks)
+            mask = np.zeros(nv, np.uint8)
+            for s in seg_idx[:ns]:
+                mask[s * F:min((s + 1) * F, nv)] = 1
+            frm_idx, nf = topk(s_frm, kf, mask)
+            frm_score = s_frm
+        else:
+            cand_seg, ncs = topk(s_seg, 2 * ks)                   # stage 1
+            cand_frm, ncf = topk(s_frm, 2 * kf)
+            n_glob = min(prm.n_global if prm.n_global > 0 else ks, ncs)
+            g_vec = seg32[cand_seg[:n_glob]].astype(np.float64).mean(axis=0) if n_glob else np.zeros(Hkv * D)
+            gamma = consistency(g_vec, frm32, cand_frm[:ncf])     # stage 2
+            s_tilde = np.full(nv, -np.inf)
+            s_tilde[cand_frm[:ncf]] = (1.0 - prm.lambda_frame) * s_frm[cand_frm[:ncf]] + prm.lambda_frame * gamma  # Eq. 8
+            mask = np.zeros(nv, np.uint8)
+            mask[cand_frm[:ncf]] = 1
+            frm_idx, nf = topk(s_tilde, kf, mask)
+            seg_idx, ns = cand_seg[:ks].copy(), min(ks, ncs)      # lambda = 0 for segments
+            frm_score = s_tilde
+            res.update({"cand_seg": cand_seg, "cand_frm": cand_frm, "g": g_vec, "gamma": gamma})
+        seg_score = np.zeros(ks)
+        seg_score[:ns] = s_seg[seg_idx[:ns]]
+        frame_score = np.zeros(kf)
+        frame_score[:nf] = frm_score[frm_idx[:nf]]
+        res.update({"seg_idx": seg_idx, "seg_score": seg_score, "frame_idx": frm_idx, "frame_score": frame_score})
+        return res
+
+    def gather(self, frame_idx, order=TEMPORAL):
+        """Concatenate the stored K,V of the selected frames (Sec. 3.5): returns
+        (K, V, n_tokens), K and V [L][Hkv][len(frame_idx)*kappa][D] with the
+        unused tail zero.  Entries equal to -1 are skipped."""
+        sk, sv = self.store()
+        kap = self.kappa
+        sel = [int(f) for f in frame_idx if f >= 0]
+        if order == TEMPORAL:
+            sel = sorted(sel)
+        L, Hkv, _, D = sk.shape
+        ko = np.zeros((L, Hkv, len(frame_idx) * kap, D), sk.dtype)
+        vo = np.zeros_like(ko)
+        for slot, f in enumerate(sel):
+            ko[:, :, slot * kap:(slot + 1) * kap] = sk[:, :, f * kap:(f + 1) * kap]
+            vo[:, :, slot * kap:(slot + 1) * kap] = sv[:, :, f * kap:(f + 1) * kap]
+        return ko, vo, len(sel) * kap

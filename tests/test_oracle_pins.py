@@ -1,0 +1,475 @@
+"""Pins for the CPU oracle: every oracle function is checked against something
+other than itself -- closed forms, invariants, numpy library routines used as
+textbook special cases, brute force, and the token counts the paper prints.
+None of these tests touches the HIP path."""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2605_22269_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+rng = np.random.default_rng(20260522)
+
+
+def bf16_bits(x):
+    """float array -> bf16 bit patterns (round to nearest even), via torch."""
+    return synth.as_numpy(torch.from_numpy(np.asarray(x, np.float32)).to(torch.bfloat16))
+
+
+def bf16_value(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+# ---------------------------------------------------------------- Eq. 2-3 ----
+class TestFrequencySignal:
+    D = 64
+
+    def _one(self, vec):
+        k = np.asarray(vec, np.float32).reshape(1, 1, -1)
+        return orc.fft_signal(k, 1, 1)[0, 0]
+
+    def test_constant_key_has_only_dc(self):
+        # k = c*1 -> Z[0] = D*c, all other bins 0 -> mean |Z| = |c|
+        assert self._one(np.full(self.D, -2.5)) == pytest.approx(2.5, abs=1e-12)
+
+    def test_delta_key_has_flat_spectrum(self):
+        v = np.zeros(self.D)
+        v[5] = 3.0
+        assert self._one(v) == pytest.approx(3.0, abs=1e-12)
+
+    def test_cosine_key_has_two_bins(self):
+        d = np.arange(self.D)
+        v = 1.75 * np.cos(2 * np.pi * 7 * d / self.D)  # bins 7 and D-7, each D*A/2
+        got = orc.fft_signal(v.astype(np.float64).astype(np.float32).reshape(1, 1, -1), 1, 1)[0, 0]
+        exact = np.abs(np.fft.fft(v.astype(np.float32).astype(np.float64))).mean()
+        assert got == pytest.approx(exact, abs=1e-12)
+        assert got == pytest.approx(1.75, abs=1e-6)
+
+    def test_sine_key_sign_and_parseval(self):
+        # Parseval: sum |Z|^2 = D * sum k^2 -- checked through a 2-bin signal
+        d = np.arange(self.D)
+        v = (0.5 * np.sin(2 * np.pi * 3 * d / self.D)).astype(np.float32)
+        assert self._one(v) == pytest.approx(0.5, abs=1e-6)
+
+    @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+    def test_matches_numpy_fft_along_feature_axis(self, dtype):
+        Hkv, n, P, D = 3, 2, 5, 32
+        x = rng.standard_normal((Hkv, n * P, D)).astype(np.float32)
+        if dtype == "bf16":
+            bits = bf16_bits(x)
+            val = bf16_value(bits)
+            got = orc.fft_signal(bits, n, P)
+        else:
+            val = x.astype(np.float64)
+            got = orc.fft_signal(x, n, P)
+        want = np.abs(np.fft.fft(val, axis=-1)).mean(axis=(0, 2)).reshape(n, P)
+        np.testing.assert_allclose(got, want, rtol=0, atol=1e-12)
+        # a transform along the token axis would give something else entirely
+        wrong = np.abs(np.fft.fft(val.reshape(Hkv, n, P, D), axis=2)).mean(axis=(0, 3))
+        assert np.abs(wrong - want).max() > 1e-2
+
+    def test_heads_are_averaged(self):
+        D = 16
+        k = np.zeros((2, 1, D), np.float32)
+        k[0, 0, :] = 4.0       # constant -> 4
+        k[1, 0, 3] = -1.0      # delta -> 1
+        assert orc.fft_signal(k, 1, 1)[0, 0] == pytest.approx(2.5, abs=1e-12)
+
+
+# ------------------------------------------------------------------ Eq. 1 ----
+def numpy_att(q, k, n, P, causal):
+    Hq, T, D = q.shape
+    Hkv = k.shape[0]
+    G = Hq // Hkv
+    out = np.zeros((n, P))
+    for f in range(n):
+        for h in range(Hq):
+            qq = q[h, f * P:(f + 1) * P].astype(np.float64)
+            kk = k[h // G, f * P:(f + 1) * P].astype(np.float64)
+            s = qq @ kk.T / math.sqrt(D)
+            if causal:
+                s = np.where(np.tril(np.ones((P, P), bool)), s, -np.inf)
+            a = np.exp(s - s.max(axis=1, keepdims=True))
+            a /= a.sum(axis=1, keepdims=True)
+            out[f] += a.sum(axis=0)
+    return out / (Hq * P)
+
+
+class TestAttentionSignal:
+    def test_two_token_closed_form(self):
+        # P=2, H=1, D=1, causal: row 0 = [1, 0]; row 1 = softmax(q1*k0, q1*k1)
+        q = np.array([[[0.3], [1.7]]], np.float32)
+        k = np.array([[[0.9], [-0.4]]], np.float32)
+        sig = 1.0 / (1.0 + math.exp(-float(q[0, 1, 0]) * (float(k[0, 0, 0]) - float(k[0, 1, 0]))))
+        got = orc.att_signal(q, k, 1, 2, causal=True)[0]
+        np.testing.assert_allclose(got, [(1 + sig) / 2, (1 - sig) / 2], atol=1e-14)
+
+    def test_scale_is_inverse_sqrt_head_dim(self):
+        D = 4
+        q = np.zeros((1, 2, D), np.float32)
+        k = np.zeros((1, 2, D), np.float32)
+        q[0, 1] = [1, 2, 0, -1]
+        k[0, 0] = [0.5, 0.5, 3, 0]
+        k[0, 1] = [-1, 0.25, 1, 2]
+        dot = float(q[0, 1] @ (k[0, 0] - k[0, 1])) / math.sqrt(D)
+        sig = 1 / (1 + math.exp(-dot))
+        got = orc.att_signal(q, k, 1, 2, causal=True)[0]
+        np.testing.assert_allclose(got, [(1 + sig) / 2, (1 - sig) / 2], atol=1e-14)
+
+    def test_identical_keys_non_causal_is_uniform(self):
+        P, D = 7, 8
+        q = rng.standard_normal((2, P, D)).astype(np.float32)
+        k = np.tile(rng.standard_normal((1, 1, D)).astype(np.float32), (1, P, 1))
+        np.testing.assert_allclose(orc.att_signal(q, k, 1, P, causal=False)[0], 1.0 / P, atol=1e-15)
+
+    def test_zero_keys_causal_gives_harmonic_tail(self):
+        P, D = 9, 4
+        q = rng.standard_normal((3, P, D)).astype(np.float32)
+        k = np.zeros((1, P, D), np.float32)
+        want = [sum(1.0 / (i + 1) for i in range(j, P)) / P for j in range(P)]
+        got = orc.att_signal(q, k, 1, P, causal=True)[0]
+        np.testing.assert_allclose(got, want, atol=1e-15)
+        assert np.all(np.diff(got) < 0)  # earlier tokens receive more attention
+
+    @pytest.mark.parametrize("causal", [True, False])
+    @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+    def test_matches_numpy_softmax_with_grouped_heads(self, causal, dtype):
+        Hq, Hkv, n, P, D = 6, 3, 3, 11, 16
+        q = rng.standard_normal((Hq, n * P, D)).astype(np.float32) * 2
+        k = rng.standard_normal((Hkv, n * P, D)).astype(np.float32) * 2
+        if dtype == "bf16":
+            qb, kb = bf16_bits(q), bf16_bits(k)
+            got = orc.att_signal(qb, kb, n, P, causal)
+            want = numpy_att(bf16_value(qb), bf16_value(kb), n, P, causal)
+        else:
+            got = orc.att_signal(q, k, n, P, causal)
+            want = numpy_att(q, k, n, P, causal)
+        np.testing.assert_allclose(got, want, atol=1e-13)
+        np.testing.assert_allclose(got.sum(axis=1), 1.0, atol=1e-13)  # rows of A sum to 1
+
+
+# ------------------------------------------------------------------ Eq. 4 ----
+class TestFusion:
+    def test_hand_worked(self):
+        att = np.array([[1.0, 2.0, 3.0]])
+        fft = np.array([[30.0, 10.0, 20.0]])
+        np.testing.assert_allclose(orc.fuse(att, fft, 0.7), [[0.3, 0.35, 0.85]], atol=1e-15)
+
+    def test_positive_affine_invariance_and_range(self):
+        att, fft = rng.random((4, 13)), rng.random((4, 13)) * 9 + 2
+        base = orc.fuse(att, fft, 0.6)
+        np.testing.assert_allclose(orc.fuse(att * 7 + 3, fft * 0.01 - 5, 0.6), base, atol=1e-12)
+        assert base.min() >= 0 and base.max() <= 1
+        a1 = orc.fuse(att, fft, 1.0)
+        assert np.all(a1.min(axis=1) == 0) and np.all(a1.max(axis=1) == 1)
+
+    def test_single_signal_modes_and_constant_signal(self):
+        att, fft = rng.random((2, 9)), rng.random((2, 9))
+        np.testing.assert_array_equal(orc.fuse(att, None, 1.0), orc.fuse(att, fft, 1.0))
+        np.testing.assert_array_equal(orc.fuse(None, fft, 0.0), orc.fuse(att, fft, 0.0))
+        lo, hi = fft.min(axis=1, keepdims=True), fft.max(axis=1, keepdims=True)
+        np.testing.assert_allclose(orc.fuse(None, fft, 0.0), (fft - lo) / (hi - lo), atol=1e-15)
+        const = np.full((1, 9), 3.3)
+        np.testing.assert_array_equal(orc.fuse(const, fft[:1], 0.5), 0.5 * orc.fuse(None, fft[:1], 0.0))
+
+
+# ---------------------------------------------------------- top-k and keep ---
+class TestSelection:
+    def test_brute_force_with_ties(self):
+        for _ in range(50):
+            n = int(rng.integers(1, 40))
+            k = int(rng.integers(0, n + 3))
+            s = rng.integers(0, 6, n).astype(np.float64)  # many exact ties
+            idx, found = orc.topk(s, k)
+            order = sorted(range(n), key=lambda i: (-s[i], i))[:k]
+            assert found == min(k, n)
+            assert list(idx[:found]) == order
+            assert np.all(idx[found:] == -1)
+
+    def test_all_equal_keeps_first(self):
+        idx, found = orc.topk(np.zeros(10), 4)
+        assert list(idx) == [0, 1, 2, 3] and found == 4
+
+    def test_mask(self):
+        s = np.array([5.0, 9.0, 7.0, 9.0, 1.0])
+        idx, found = orc.topk(s, 3, mask=[1, 0, 1, 1, 0])
+        assert list(idx) == [3, 2, 0] and found == 3
+
+    def test_keep_is_ascending_topk_and_identity_at_ratio_one(self):
+        fused = rng.random((5, 21))
+        kept = orc.keep(fused, 6)
+        for f in range(5):
+            want = sorted(sorted(range(21), key=lambda i: (-fused[f, i], i))[:6])
+            assert list(kept[f]) == want
+        np.testing.assert_array_equal(orc.keep(fused, 21), np.tile(np.arange(21), (5, 1)))
+
+    def test_kappa_floor_against_paper_token_counts(self):
+        g = json.load(open(os.path.join(GOLDEN, "paper_token_counts.json")))
+        hp = g["hyper_parameters"]
+        P, F, S = hp["P"], hp["F"], hp["S"]
+        unit = {"segment": P * F, "frame": P, "patch": P // S}
+        kap = {n: orc.kappa_of(hp["rho"][n], unit[n]) for n in unit}
+        assert kap == {"segment": 627, "frame": 19, "patch": 4}
+        inf = sum(hp["k_g"][n] * kap[n] for n in unit)
+        assert inf == 8212
+        assert abs(inf / 1000 - g["inference_tokens"]["mukv_printed_K"]) / 8.3 < 0.02
+        assert g["inference_tokens"]["rekv_blocks"] * P == 12544  # printed as 12.5K
+        # memory per 300 frames: each granularity covers 196*300 tokens before pruning
+        per_gran = P * 300
+        assert round(3 * per_gran / 1000) in (176, 177)
+        assert sum(hp["rho"].values()) * per_gran == pytest.approx(58800)  # printed as 59K
+        assert orc.kappa_of(0.25, 49) == 12 and orc.kappa_of(0.125, 196) == 24
+        assert orc.kappa_of(0.29, 100) == 29 and orc.kappa_of(1.0, 196) == 196
+
+    def test_store_size_is_linear_in_kept_fraction(self):
+        g = json.load(open(os.path.join(GOLDEN, "paper_token_counts.json")))["cache_size_G_per_hour"]
+        for name, frac in (("ratio_1_2", 1 / 2), ("ratio_2_3", 1 / 3), ("ratio_3_4", 1 / 4)):
+            assert g["ratio_0"] * frac == pytest.approx(g[name], abs=0.025)
+
+
+# --------------------------------------------- compaction, pooling, whole path
+def tiny_cfg(**kw):
+    base = dict(n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=16, tokens_per_frame=13,
+                frames_per_segment=3, superpatches_per_frame=4, keep_ratio=0.4, alpha=0.7)
+    base.update(kw)
+    return orc.OracleConfig(**base)
+
+
+def tiny_stream(cfg, n_frames, dtype="f32", seed=1):
+    w = synth.Workload("t", cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, dtype, n_frames,
+                       cfg.tokens_per_frame, cfg.frames_per_segment, spike_prob=0.1)
+    k, v, q = synth.SynthStream(w, seed).next_chunk(n_frames)
+    return synth.as_numpy(k), synth.as_numpy(v), synth.as_numpy(q)
+
+
+def run_stream(cfg, k, v, q, chunk):
+    o = orc.OracleMuKV(cfg)
+    P = cfg.tokens_per_frame
+    n = k.shape[2] // P
+    for f0 in range(0, n, chunk):
+        f1 = min(f0 + chunk, n)
+        o.compress_chunk(k[:, :, f0 * P:f1 * P], v[:, :, f0 * P:f1 * P], q[:, f0 * P:f1 * P])
+    return o
+
+
+class TestCompactionAndPooling:
+    @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+    def test_store_equals_fancy_index(self, dtype):
+        cfg = tiny_cfg()
+        k, v, q = tiny_stream(cfg, 7, dtype)
+        o = run_stream(cfg, k, v, q, 3)
+        P, kap = cfg.tokens_per_frame, o.kappa
+        assert kap == 5
+        rows = (np.arange(7)[:, None] * P + o.kept).reshape(-1)
+        sk, sv = o.store()
+        assert sk.shape == (2, 2, 7 * kap, 16) and sk.dtype == k.dtype
+        np.testing.assert_array_equal(sk, k[:, :, rows])
+        np.testing.assert_array_equal(sv, v[:, :, rows])
+
+    def test_keep_ratio_one_is_identity(self):
+        cfg = tiny_cfg(keep_ratio=1.0)
+        k, v, q = tiny_stream(cfg, 4)
+        o = run_stream(cfg, k, v, q, 2)
+        sk, sv = o.store()
+        np.testing.assert_array_equal(sk, k)
+        np.testing.assert_array_equal(sv, v)
+        # mean over all tokens of a frame
+        want = k[-1].astype(np.float64).reshape(2, 4, 13, 16).mean(axis=2).transpose(1, 0, 2).reshape(4, -1)
+        np.testing.assert_allclose(o.rep_frame_k, want, atol=1e-14)
+
+    def test_mean_of_identical_tokens_is_the_token(self):
+        x = np.tile(rng.standard_normal((2, 1, 8)).astype(np.float32), (1, 6, 1))
+        np.testing.assert_array_equal(orc.pool_rows(x, [1, 3, 4]), x[:, 0].reshape(-1).astype(np.float64))
+        np.testing.assert_array_equal(orc.pool_rows(x, []), np.zeros(16))
+
+    def test_pool_rows_matches_numpy_mean_bf16(self):
+        x = bf16_bits(rng.standard_normal((3, 10, 8)))
+        rows = [7, 0, 2, 9]
+        want = bf16_value(x)[:, rows].mean(axis=1).reshape(-1)
+        np.testing.assert_allclose(orc.pool_rows(x, rows), want, atol=1e-15)
+
+    def test_block_hierarchy_consistency(self):
+        cfg = tiny_cfg()
+        k, v, q = tiny_stream(cfg, 8)
+        o = run_stream(cfg, k, v, q, 8)
+        S, F, kap = 4, 3, o.kappa
+        # frame key = count-weighted mean of its super-patch keys
+        cnt = o.cnt_patch.reshape(8, S)
+        assert np.all(cnt.sum(axis=1) == kap)
+        recon = (o.rep_patch_k.reshape(8, S, -1) * cnt[:, :, None]).sum(axis=1) / kap
+        np.testing.assert_allclose(recon, o.rep_frame_k, atol=1e-14)
+        # super-patch membership follows the index-contiguous partition 3,3,3,4
+        assert orc.superpatch_bounds(13, 4) == [(0, 3), (3, 6), (6, 9), (9, 13)]
+        assert orc.superpatch_bounds(49, 4) == [(0, 12), (12, 24), (24, 36), (36, 49)]
+        # segment key = mean of its frame keys (kappa is the same for every frame)
+        seg = o.seg_reps()
+        assert seg.shape[0] == 3  # 3 + 3 + 2 frames
+        for s in range(3):
+            np.testing.assert_allclose(seg[s], o.rep_frame_k[s * F:min((s + 1) * F, 8)].mean(axis=0), atol=1e-14)
+        segv = o.seg_reps(which="v")
+        np.testing.assert_allclose(segv[2], o.rep_frame_v[6:8].mean(axis=0), atol=1e-14)
+        # a question asked before the end of the stream sees only earlier frames
+        np.testing.assert_allclose(o.seg_reps(n_visible=5)[1], o.rep_frame_k[3:5].mean(axis=0), atol=1e-14)
+
+    def test_chunking_invariance(self):
+        cfg = tiny_cfg()
+        k, v, q = tiny_stream(cfg, 9)
+        ref = run_stream(cfg, k, v, q, 9)
+        for chunk in (1, 2, 4):
+            o = run_stream(cfg, k, v, q, chunk)
+            np.testing.assert_array_equal(o.kept, ref.kept)
+            np.testing.assert_array_equal(o.store()[0], ref.store()[0])
+            np.testing.assert_allclose(o.rep_frame_k, ref.rep_frame_k, atol=1e-14)
+            np.testing.assert_allclose(o.seg_reps(), ref.seg_reps(), atol=1e-14)
+
+    def test_attention_handed_over_equals_attention_recomputed(self):
+        cfg = tiny_cfg()
+        k, v, q = tiny_stream(cfg, 3)
+        a = orc.att_signal(q, k[-1], 3, 13, True)
+        o1 = orc.OracleMuKV(cfg)
+        r1 = o1.compress_chunk(k, v, q_last=q)
+        o2 = orc.OracleMuKV(cfg)
+        r2 = o2.compress_chunk(k, v, att=a)
+        np.testing.assert_array_equal(r1["kept"], r2["kept"])
+
+    def test_spiked_tokens_are_kept_by_the_frequency_signal(self):
+        # |Z| scales with the key, so a token whose key is 3x larger must win
+        cfg = tiny_cfg(alpha=0.0, keep_ratio=0.1)
+        k, v, q = tiny_stream(cfg, 2)
+        k = k.copy()
+        k[:, :, 4] *= 25
+        k[:, :, 13 + 9] *= 25
+        o = orc.OracleMuKV(cfg)
+        r = o.compress_chunk(k, v, None)
+        assert o.kappa == 1 and list(r["kept"][:, 0]) == [4, 9]
+
+
+# ------------------------------------------------------------- Eq. 6, 7, 8 ---
+class TestRetrieval:
+    def test_question_pooling_is_token_mean(self):
+        qt = rng.standard_normal((5, 3, 4)).astype(np.float32)
+        np.testing.assert_allclose(orc.pool_question(qt), qt.astype(np.float64).mean(axis=0).reshape(-1), atol=1e-15)
+
+    def test_cosine_against_closed_form_and_numpy(self):
+        Hq, Hkv, D, N = 6, 2, 8, 9
+        G = Hq // Hkv
+        q = rng.standard_normal(Hq * D)
+        reps = rng.standard_normal((N, Hkv * D)).astype(np.float32)
+        got = orc.score_blocks(q, reps, Hq, Hkv, D)
+        # closed form: group-sum of q against the un-expanded key
+        qg = q.reshape(Hkv, G, D).sum(axis=1).reshape(-1)
+        r64 = reps.astype(np.float64)
+        want = (r64 @ qg) / (np.linalg.norm(q) * math.sqrt(G) * np.linalg.norm(r64, axis=1))
+        np.testing.assert_allclose(got, want, atol=1e-14)
+        assert np.all(np.abs(got) <= 1 + 1e-15)
+        # invariant to positive scaling of either side
+        np.testing.assert_allclose(orc.score_blocks(q * 3.5, reps * np.float32(0.25), Hq, Hkv, D), got, atol=1e-14)
+        # no grouping: plain cosine
+        q2 = rng.standard_normal(Hkv * D)
+        plain = (r64 @ q2) / (np.linalg.norm(q2) * np.linalg.norm(r64, axis=1))
+        np.testing.assert_allclose(orc.score_blocks(q2, reps, Hkv, Hkv, D), plain, atol=1e-14)
+        # head h must read KV head h // G, not h % Hkv
+        wrong = r64.reshape(N, Hkv, 1, D).repeat(G, axis=2).transpose(0, 2, 1, 3).reshape(N, -1)
+        wrong = (wrong @ q) / (np.linalg.norm(q) * np.linalg.norm(wrong, axis=1))
+        assert np.abs(wrong - got).max() > 1e-3
+
+    def test_zero_key_scores_zero(self):
+        reps = np.zeros((1, 8), np.float32)
+        assert orc.score_blocks(np.ones(16), reps, 4, 2, 4)[0] == 0.0
+
+    def test_consistency_is_one_for_the_global_query_itself(self):
+        reps = rng.standard_normal((4, 12)).astype(np.float32)
+        g = reps[2].astype(np.float64) * 5
+        got = orc.consistency(g, reps, [2, 0])
+        assert got[0] == pytest.approx(1.0, abs=1e-15)
+        want = reps[0].astype(np.float64) @ g / np.linalg.norm(reps[0].astype(np.float64)) / np.linalg.norm(g)
+        assert got[1] == pytest.approx(want, abs=1e-15)
+
+    def _state(self, n_frames=24, **kw):
+        cfg = tiny_cfg(frames_per_segment=4, **kw)
+        k, v, q = tiny_stream(cfg, n_frames, seed=3)
+        return cfg, run_stream(cfg, k, v, q, 8)
+
+    def test_lambda_zero_semi_equals_parallel(self):
+        cfg, o = self._state()
+        qt = rng.standard_normal((6, 4, 16)).astype(np.float32)
+        a = o.retrieve(qt, orc.RetrieveParams(orc.SEMI, 2, 5, lambda_frame=0.0))
+        b = o.retrieve(qt, orc.RetrieveParams(orc.PARALLEL, 2, 5))
+        np.testing.assert_array_equal(a["frame_idx"], b["frame_idx"])
+        np.testing.assert_array_equal(a["seg_idx"], b["seg_idx"])
+        np.testing.assert_allclose(a["frame_score"], b["frame_score"], atol=1e-15)
+
+    def test_semi_rerank_by_hand(self):
+        cfg, o = self._state()
+        qt = rng.standard_normal((6, 4, 16)).astype(np.float32)
+        prm = orc.RetrieveParams(orc.SEMI, 2, 3, lambda_frame=0.3)
+        r = o.retrieve(qt, prm)
+        # segments keep their stage-1 order
+        par = o.retrieve(qt, orc.RetrieveParams(orc.PARALLEL, 2, 3))
+        np.testing.assert_array_equal(r["seg_idx"], par["seg_idx"])
+        # redo stage 2 with numpy on the stage-1 candidates
+        s = r["s_frm"]
+        cand = sorted(range(24), key=lambda i: (-s[i], i))[:6]
+        assert list(r["cand_frm"]) == cand
+        sseg = r["s_seg"]
+        top_seg = sorted(range(6), key=lambda i: (-sseg[i], i))[:2]
+        g = o.seg_reps().astype(np.float32).astype(np.float64)[top_seg].mean(axis=0)
+        reps = o.rep_frame_k.astype(np.float32).astype(np.float64)
+        gam = [reps[j] @ g / np.linalg.norm(reps[j]) / np.linalg.norm(g) for j in cand]
+        st = [0.7 * s[j] + 0.3 * gm for j, gm in zip(cand, gam)]
+        order = sorted(range(6), key=lambda c: (-st[c], cand[c]))[:3]
+        assert list(r["frame_idx"]) == [cand[c] for c in order]
+        np.testing.assert_allclose(r["frame_score"], [st[c] for c in order], atol=1e-14)
+
+    def test_hier_frames_lie_in_chosen_segments(self):
+        cfg, o = self._state()
+        qt = rng.standard_normal((6, 4, 16)).astype(np.float32)
+        r = o.retrieve(qt, orc.RetrieveParams(orc.HIER, 2, 5))
+        segs = set(int(s) for s in r["seg_idx"])
+        assert all(int(f) // 4 in segs for f in r["frame_idx"])
+        s = r["s_frm"]
+        allowed = [i for i in range(24) if i // 4 in segs]
+        assert list(r["frame_idx"]) == sorted(allowed, key=lambda i: (-s[i], i))[:5]
+
+    def test_k_larger_than_available_pads_with_minus_one(self):
+        cfg, o = self._state(n_frames=6)
+        qt = rng.standard_normal((2, 4, 16)).astype(np.float32)
+        for mode in (orc.SEMI, orc.HIER, orc.PARALLEL):
+            r = o.retrieve(qt, orc.RetrieveParams(mode, 3, 8))
+            assert list(r["seg_idx"][2:]) == [-1] and sorted(r["seg_idx"][:2]) == [0, 1]
+            assert list(r["frame_idx"][6:]) == [-1, -1] and sorted(r["frame_idx"][:6]) == list(range(6))
+
+    def test_timestamp_constraint(self):
+        cfg, o = self._state()
+        qt = rng.standard_normal((3, 4, 16)).astype(np.float32)
+        r = o.retrieve(qt, orc.RetrieveParams(orc.SEMI, 2, 4, n_visible_frames=10))
+        assert all(0 <= f < 10 for f in r["frame_idx"]) and all(0 <= s < 3 for s in r["seg_idx"])
+        assert r["s_seg"].shape == (3,) and r["s_frm"].shape == (10,)
+
+    def test_planted_targets_are_retrieved(self):
+        cfg, o = self._state(n_frames=40)
+        w = synth.Workload("t", 2, 4, 2, 16, "f32", 40, 13, 4)
+        targets = [5, 17, 33]
+        qt = synth.as_numpy(synth.planted_question(w, torch.from_numpy(o.rep_frame_k[targets]), 12, seed=9, cosine=0.8))
+        r = o.retrieve(qt, orc.RetrieveParams(orc.PARALLEL, 3, 3))
+        assert sorted(int(f) for f in r["frame_idx"]) == targets
+
+    def test_gather_is_temporal_concatenation(self):
+        cfg, o = self._state()
+        sk, sv = o.store()
+        kap = o.kappa
+        ko, vo, n = o.gather(np.array([9, 2, -1, 4], np.int32))
+        assert n == 3 * kap
+        rows = np.concatenate([np.arange(f * kap, (f + 1) * kap) for f in (2, 4, 9)])
+        np.testing.assert_array_equal(ko[:, :, :n], sk[:, :, rows])
+        np.testing.assert_array_equal(vo[:, :, :n], sv[:, :, rows])
+        assert not ko[:, :, n:].any()
+        ko2, _, _ = o.gather(np.array([9, 2, -1, 4], np.int32), order=orc.AS_GIVEN)
+        rows2 = np.concatenate([np.arange(f * kap, (f + 1) * kap) for f in (9, 2, 4)])
+        np.testing.assert_array_equal(ko2[:, :, :n], sk[:, :, rows2])
