@@ -1,0 +1,230 @@
+/*
+ * mukv.h -- C ABI of the MuKV hot path for AMD MI355X (gfx950).
+ *
+ * MuKV ("Multi-Grained KV Cache Compression for Long Streaming Video
+ * Question-Answering") keeps a compact multi-grained KV cache of a video stream
+ * offline and retrieves question-relevant parts of it online.  This library is
+ * the data-parallel part of that method, as HIP kernels:
+ *
+ *   offline, per chunk of frames  : mukv_compress_chunk   (Sec. 3.3, Eq. 1-5)
+ *   online, per batch of questions: mukv_retrieve          (Sec. 3.4, Eq. 6-8)
+ *                                   mukv_gather_kv         (Sec. 3.5, Eq. 9 context)
+ *
+ * The Video-LLM itself is not part of the library: the caller hands over the
+ * K/V tensors of a prefill, the scoring layer's query states (or the attention
+ * it already computed) and, online, the question's query states.
+ *
+ * General rules
+ *  - Every function returns MUKV_OK (0) or a negative mukv_status.  No C++
+ *    exception crosses this boundary.  Arguments are validated on the host
+ *    before anything is launched, so a failed call has no device side effects.
+ *  - "device" pointers are HIP device pointers valid on the context's device;
+ *    "host" pointers are ordinary process memory.  The caller owns every buffer
+ *    it passes in; the context owns the cache.  Inputs may be reused as soon as
+ *    the stream has passed the call.
+ *  - Work is enqueued on the hipStream_t passed as `stream` (void*, NULL = the
+ *    default stream) and is never synchronised by the library.  Calls on one
+ *    context must be issued in stream order; the context is not thread-safe.
+ *  - After mukv_create no device memory is allocated or freed until
+ *    mukv_destroy.
+ *  - Inputs must be finite.  Non-finite values give unspecified selections.
+ */
+#ifndef MUKV_H
+#define MUKV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mukv_ctx mukv_ctx;
+
+typedef enum mukv_status {
+    MUKV_OK = 0,
+    MUKV_ERR_INVALID_ARG = -1, /* null pointer, value out of range            */
+    MUKV_ERR_SHAPE = -2,       /* sizes inconsistent with the configuration   */
+    MUKV_ERR_CAPACITY = -3,    /* more frames / questions than reserved       */
+    MUKV_ERR_UNSUPPORTED = -4, /* shape or alignment no kernel is built for   */
+    MUKV_ERR_HIP = -5          /* a HIP runtime call failed                   */
+} mukv_status;
+
+typedef enum mukv_dtype { MUKV_BF16 = 0, MUKV_F32 = 1 } mukv_dtype;
+
+/* Retrieval strategies compared in the paper's retrieval ablation (Sec. 4.3):
+ * SEMI is the method of Sec. 3.4 (parallel stage 1 + Eq. 8 rerank), PARALLEL
+ * returns the stage-1 ranking, HIER searches frames only inside the chosen
+ * segments with the question as query at both levels. */
+typedef enum mukv_mode { MUKV_SEMI = 0, MUKV_HIER = 1, MUKV_PARALLEL = 2 } mukv_mode;
+
+typedef enum mukv_order { MUKV_TEMPORAL = 0, MUKV_AS_GIVEN = 1 } mukv_order;
+
+typedef enum mukv_att_path { MUKV_ATT_AUTO = 0, MUKV_ATT_GENERIC = 1, MUKV_ATT_MFMA = 2 } mukv_att_path;
+
+/*
+ * Static description of the stream and the cache (Sec. 3.2-3.3 notation:
+ * L layers, P tokens per frame, F frames per segment, S super-patches per
+ * frame, rho keep ratio, alpha signal mix).
+ */
+typedef struct mukv_config {
+    int32_t n_layers;               /* L                                               */
+    int32_t n_q_heads;              /* H_q, a multiple of n_kv_heads                   */
+    int32_t n_kv_heads;             /* H_kv                                            */
+    int32_t head_dim;               /* D: a power of two in 16..128                    */
+    int32_t tokens_per_frame;       /* P, 1..256                                       */
+    int32_t frames_per_segment;     /* F >= 1                                          */
+    int32_t superpatches_per_frame; /* S, 1..P: index-contiguous groups of floor(P/S)
+                                       tokens, the last one takes the remainder        */
+    int32_t dtype;                  /* mukv_dtype of K, V, Q payloads                  */
+    double keep_ratio;              /* rho in (0,1]; kappa = floor(rho*P + 1e-9) >= 1  */
+    double alpha;                   /* weight of the attention signal in Eq. 4, [0,1]  */
+    int32_t causal;                 /* 1: query i attends keys j <= i inside its frame */
+    int32_t score_layer;            /* layer that supplies Eq. 1-3, 5-7; -1 = last     */
+    int32_t max_frames;             /* capacity of the cache in frames                 */
+    int32_t max_chunk_frames;       /* largest n_frames of one mukv_compress_chunk     */
+    int32_t max_questions;          /* largest batch of one mukv_retrieve / gather     */
+    int32_t device_id;              /* HIP device ordinal                              */
+    int32_t att_path;               /* mukv_att_path; AUTO picks MFMA when supported   */
+    int32_t reserved0;
+    double refine_margin;           /* frames whose selection margin (gap between the
+                                       last kept and first dropped fused score) is
+                                       below this are re-scored in fp64 before the
+                                       keep; < 0 = library default, 0 = never          */
+} mukv_config;
+
+/* Element strides (not bytes) of a [layer][head][token][dim] tensor; dim is
+ * contiguous.  `layer` is ignored for the single-layer q_last tensor. */
+typedef struct mukv_strides {
+    int64_t layer;
+    int64_t head;
+    int64_t token;
+} mukv_strides;
+
+/* Optional per-chunk outputs of the scoring stage, device float [n_frames][P]
+ * each, any may be NULL: raw Eq. 1 signal, raw Eq. 3 signal, fused Eq. 4 score
+ * (as used for the keep, i.e. after fp64 re-scoring where that happened). */
+typedef struct mukv_signals_out {
+    float *att;
+    float *fft;
+    float *fused;
+} mukv_signals_out;
+
+typedef struct mukv_retrieve_params {
+    int32_t mode;             /* mukv_mode                                            */
+    int32_t k_seg;            /* k_g at segment level, 1..512                         */
+    int32_t k_frame;          /* k_g at frame level, 1..512                           */
+    int32_t n_global;         /* N segments averaged into the global query; 0 = k_seg */
+    int32_t n_visible_frames; /* question timestamp: only frames < this are searched;
+                                 < 0 = every ingested frame                           */
+    int32_t reserved0;
+    double lambda_frame;      /* lambda_g of Eq. 8 for frames (segments use 0)        */
+} mukv_retrieve_params;
+
+/* Read-only view of the context's state; device pointers stay valid until
+ * mukv_destroy.  Tables are valid for frames < n_frames once the stream has
+ * passed the calls that produced them. */
+typedef struct mukv_state {
+    int64_t n_frames;          /* frames ingested                                     */
+    int64_t n_segments;        /* ceil(n_frames / F); the last may be partial         */
+    int64_t n_kept_tokens;     /* n_frames * kappa                                    */
+    int64_t store_token_capacity; /* max_frames * kappa                               */
+    int32_t kappa;
+    int32_t c_kv;              /* H_kv * D                                            */
+    const void *store_k;       /* [L][H_kv][store_token_capacity][D], payload dtype   */
+    const void *store_v;
+    const int32_t *kept_idx;   /* [max_frames][kappa] kept positions, ascending       */
+    const float *rep_frame_k;  /* [max_frames][c_kv] Eq. 5 block keys, float32        */
+    const float *rep_frame_v;  /* same pooling applied to V                           */
+    const float *rep_patch_k;  /* [max_frames*S][c_kv]; zero rows where count is 0    */
+    const float *rep_patch_v;
+    const int32_t *cnt_patch;  /* [max_frames*S] kept tokens in each super-patch      */
+    const float *rep_seg_k;    /* [ceil(max_frames/F)][c_kv]                          */
+    const float *rep_seg_v;
+    const float *margin;       /* [max_frames] selection margin of each frame         */
+    const int32_t *refined;    /* [max_frames] 1 where the fp64 re-scoring ran        */
+} mukv_state;
+
+/* Allocates the cache on cfg->device_id.  *out is set only on success. */
+int mukv_create(const mukv_config *cfg, mukv_ctx **out);
+
+/* Frees everything the context owns.  The caller must have synchronised the
+ * streams it used.  NULL is accepted. */
+int mukv_destroy(mukv_ctx *ctx);
+
+/* Forgets the stream (n_frames = 0) without freeing memory. */
+int mukv_reset(mukv_ctx *ctx);
+
+/*
+ * Offline step for n_frames new frames (Sec. 3.3).  For every frame: Eq. 1
+ * attention received (from q_last and the scoring layer's K, softmax over the
+ * frame's own keys, scale 1/sqrt(D)) or the caller's att_signal; Eq. 2-3
+ * frequency score (length-D DFT of each token's key per KV head, mean
+ * magnitude); Eq. 4 min-max fusion; keep of the kappa best tokens (ties: lowest
+ * position; emitted ascending); copy of the kept K and V rows of all L layers
+ * into the store; Eq. 5 block keys (and the same means of V) per super-patch,
+ * frame and segment.  Frames are appended at the context's current time.
+ *
+ *   k, v        device, logical [L][H_kv][n_frames*P][D] with kv_strides
+ *   q_last      device, logical [H_q][n_frames*P][D] with q_strides, or NULL
+ *   att_signal  device float [n_frames][P], or NULL
+ *               alpha > 0 needs exactly one of q_last / att_signal;
+ *               alpha == 0 ignores both
+ *   sig         optional outputs, may be NULL
+ *
+ * Errors: INVALID_ARG (null k/v, missing or doubled attention source),
+ * SHAPE (n_frames < 1), CAPACITY (n_frames > max_chunk_frames or the cache is
+ * full), UNSUPPORTED (strides or pointers not 16-byte aligned).
+ */
+int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_strides *kv_strides,
+                        const void *q_last, const mukv_strides *q_strides, const float *att_signal,
+                        int32_t n_frames, void *stream, const mukv_signals_out *sig);
+
+/*
+ * Online retrieval for a batch of B questions (Sec. 3.4).  Eq. 6 mean of each
+ * question's query tokens; Eq. 7 cosine with every visible segment and frame
+ * key (keys expanded over their query-head group); stage-1 top-2k; global query
+ * = mean of the top-N segment keys; Eq. 8 rerank of the frame candidates;
+ * final top-k.  Scores are evaluated in fp64 from the float32 key tables.
+ *
+ *   q_tokens   device, [sum of lengths][H_q][D] dense, payload dtype
+ *   q_offsets  device int32 [B+1], question b owns tokens q_offsets[b] ..
+ *              q_offsets[b+1]-1
+ *   outputs    device; indices in rank order (best first; ties: lowest index),
+ *              padded with -1 / score 0 when fewer blocks are visible:
+ *              seg_idx_out [B][k_seg], seg_score_out [B][k_seg] (Eq. 7),
+ *              frame_idx_out [B][k_frame], frame_score_out [B][k_frame]
+ *              (Eq. 8 score in SEMI mode, Eq. 7 otherwise).  Score outputs may
+ *              be NULL.
+ *
+ * Errors: INVALID_ARG, CAPACITY (B > max_questions), UNSUPPORTED (k > 512).
+ */
+int mukv_retrieve(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, int32_t B,
+                  const mukv_retrieve_params *params, int32_t *seg_idx_out, float *seg_score_out,
+                  int32_t *frame_idx_out, float *frame_score_out, void *stream);
+
+/*
+ * Packs the stored K,V of the selected frames of each question into a dense
+ * decode context (the retrieved part of R_k, R_v in Eq. 9).
+ *
+ *   frame_idx     device int32 [B][k_frame]; -1 entries are skipped
+ *   order         MUKV_TEMPORAL: ascending frame number; MUKV_AS_GIVEN
+ *   k_out, v_out  device [B][L][H_kv][k_frame*kappa][D], payload dtype; slots
+ *                 past the last selected frame are zero-filled
+ *   n_tokens_out  device int32 [B] = selected frames * kappa, may be NULL
+ *
+ * Frame numbers must be < n_frames (larger ones are skipped like -1).
+ * Errors: INVALID_ARG, CAPACITY (B > max_questions), UNSUPPORTED (k_frame > 1024).
+ */
+int mukv_gather_kv(mukv_ctx *ctx, const int32_t *frame_idx, int32_t B, int32_t k_frame, int32_t order,
+                   void *k_out, void *v_out, int32_t *n_tokens_out, void *stream);
+
+/* Fills *out (host).  Does not synchronise. */
+int mukv_get_state(const mukv_ctx *ctx, mukv_state *out);
+
+/* Static, never-NULL description of a status code. */
+const char *mukv_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MUKV_H */

@@ -1,0 +1,299 @@
+"""ctypes binding of libmukv.so -- argument marshalling only.
+
+The functions carry the names of the C ABI in ``include/mukv.h``.  ``MuKV`` is a
+small convenience object that owns a context and passes torch tensors' device
+pointers, strides and the current HIP stream through; every step of the method
+runs inside the library's kernels.  There is no CPU fallback: if the library
+has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmukv.so")
+
+MUKV_OK, MUKV_ERR_INVALID_ARG, MUKV_ERR_SHAPE, MUKV_ERR_CAPACITY, MUKV_ERR_UNSUPPORTED, MUKV_ERR_HIP = 0, -1, -2, -3, -4, -5
+MUKV_BF16, MUKV_F32 = 0, 1
+MUKV_SEMI, MUKV_HIER, MUKV_PARALLEL = 0, 1, 2
+MUKV_TEMPORAL, MUKV_AS_GIVEN = 0, 1
+MUKV_ATT_AUTO, MUKV_ATT_GENERIC, MUKV_ATT_MFMA = 0, 1, 2
+
+
+class mukv_config(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("tokens_per_frame", C.c_int32), ("frames_per_segment", C.c_int32), ("superpatches_per_frame", C.c_int32),
+        ("dtype", C.c_int32), ("keep_ratio", C.c_double), ("alpha", C.c_double), ("causal", C.c_int32),
+        ("score_layer", C.c_int32), ("max_frames", C.c_int32), ("max_chunk_frames", C.c_int32),
+        ("max_questions", C.c_int32), ("device_id", C.c_int32), ("att_path", C.c_int32), ("reserved0", C.c_int32),
+        ("refine_margin", C.c_double),
+    ]
+
+
+class mukv_strides(C.Structure):
+    _fields_ = [("layer", C.c_int64), ("head", C.c_int64), ("token", C.c_int64)]
+
+
+class mukv_signals_out(C.Structure):
+    _fields_ = [("att", C.c_void_p), ("fft", C.c_void_p), ("fused", C.c_void_p)]
+
+
+class mukv_retrieve_params(C.Structure):
+    _fields_ = [
+        ("mode", C.c_int32), ("k_seg", C.c_int32), ("k_frame", C.c_int32), ("n_global", C.c_int32),
+        ("n_visible_frames", C.c_int32), ("reserved0", C.c_int32), ("lambda_frame", C.c_double),
+    ]
+
+
+class mukv_state(C.Structure):
+    _fields_ = [
+        ("n_frames", C.c_int64), ("n_segments", C.c_int64), ("n_kept_tokens", C.c_int64),
+        ("store_token_capacity", C.c_int64), ("kappa", C.c_int32), ("c_kv", C.c_int32),
+        ("store_k", C.c_void_p), ("store_v", C.c_void_p), ("kept_idx", C.c_void_p),
+        ("rep_frame_k", C.c_void_p), ("rep_frame_v", C.c_void_p), ("rep_patch_k", C.c_void_p),
+        ("rep_patch_v", C.c_void_p), ("cnt_patch", C.c_void_p), ("rep_seg_k", C.c_void_p),
+        ("rep_seg_v", C.c_void_p), ("margin", C.c_void_p), ("refined", C.c_void_p),
+    ]
+
+
+EXPORTS = ("mukv_create", "mukv_destroy", "mukv_reset", "mukv_compress_chunk", "mukv_retrieve",
+           "mukv_gather_kv", "mukv_get_state", "mukv_strerror")
+
+_lib = None
+
+
+def load():
+    """Loads libmukv.so (built by ``paper_2605_22269_amd.build``); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2605_22269_amd.build` "
+                           "(or __graft_entry__.build()) first; there is no fallback path")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32 = C.c_void_p, C.c_int32
+    lib.mukv_create.argtypes = [C.POINTER(mukv_config), C.POINTER(vp)]
+    lib.mukv_destroy.argtypes = [vp]
+    lib.mukv_reset.argtypes = [vp]
+    lib.mukv_compress_chunk.argtypes = [vp, vp, vp, C.POINTER(mukv_strides), vp, C.POINTER(mukv_strides), vp, i32, vp,
+                                        C.POINTER(mukv_signals_out)]
+    lib.mukv_retrieve.argtypes = [vp, vp, vp, i32, C.POINTER(mukv_retrieve_params), vp, vp, vp, vp, vp]
+    lib.mukv_gather_kv.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
+    lib.mukv_get_state.argtypes = [vp, C.POINTER(mukv_state)]
+    lib.mukv_strerror.argtypes = [i32]
+    lib.mukv_strerror.restype = C.c_char_p
+    for name in EXPORTS[:-1]:
+        getattr(lib, name).restype = i32
+    _lib = lib
+    return lib
+
+
+class MuKVError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {load().mukv_strerror(status).decode()} ({status})")
+
+
+def _check(status: int, where: str):
+    if status != MUKV_OK:
+        raise MuKVError(status, where)
+
+
+# ---- functions named after the C ABI -------------------------------------------------------
+def mukv_create(cfg: mukv_config) -> C.c_void_p:
+    h = C.c_void_p()
+    _check(load().mukv_create(C.byref(cfg), C.byref(h)), "mukv_create")
+    return h
+
+
+def mukv_destroy(h):
+    _check(load().mukv_destroy(h), "mukv_destroy")
+
+
+def mukv_reset(h):
+    _check(load().mukv_reset(h), "mukv_reset")
+
+
+def mukv_compress_chunk(h, k_ptr, v_ptr, kv_strides, q_ptr, q_strides, att_ptr, n_frames, stream, sig=None):
+    _check(load().mukv_compress_chunk(h, k_ptr, v_ptr, C.byref(kv_strides), q_ptr,
+                                      C.byref(q_strides) if q_strides is not None else None, att_ptr, n_frames,
+                                      stream, C.byref(sig) if sig is not None else None), "mukv_compress_chunk")
+
+
+def mukv_retrieve(h, q_ptr, off_ptr, B, params, seg_idx, seg_score, frm_idx, frm_score, stream):
+    _check(load().mukv_retrieve(h, q_ptr, off_ptr, B, C.byref(params), seg_idx, seg_score, frm_idx, frm_score, stream),
+           "mukv_retrieve")
+
+
+def mukv_gather_kv(h, idx_ptr, B, k_frame, order, k_out, v_out, n_tok, stream):
+    _check(load().mukv_gather_kv(h, idx_ptr, B, k_frame, order, k_out, v_out, n_tok, stream), "mukv_gather_kv")
+
+
+def mukv_get_state(h) -> mukv_state:
+    s = mukv_state()
+    _check(load().mukv_get_state(h, C.byref(s)), "mukv_get_state")
+    return s
+
+
+# ---- convenience object ----------------------------------------------------------------------
+_hip = None
+
+
+def _hip_rt():
+    global _hip
+    if _hip is None:
+        _hip = C.CDLL("libamdhip64.so")
+        _hip.hipMemcpyAsync.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]
+        _hip.hipMemcpyAsync.restype = C.c_int
+    return _hip
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+class MuKV:
+    """Owns one mukv_ctx.  All tensors must live on the context's device."""
+
+    def __init__(self, *, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, frames_per_segment,
+                 superpatches_per_frame=4, dtype=torch.bfloat16, keep_ratio=0.25, alpha=0.7, causal=True,
+                 score_layer=-1, max_frames=4096, max_chunk_frames=8, max_questions=1, device_id=0,
+                 att_path=MUKV_ATT_AUTO, refine_margin=-1.0):
+        self.cfg = mukv_config(n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, frames_per_segment,
+                               superpatches_per_frame, MUKV_BF16 if dtype == torch.bfloat16 else MUKV_F32,
+                               keep_ratio, alpha, int(causal), score_layer, max_frames, max_chunk_frames,
+                               max_questions, device_id, att_path, 0, refine_margin)
+        self.dtype = dtype
+        self.device = torch.device("cuda", device_id)
+        self.h = mukv_create(self.cfg)
+        st = mukv_get_state(self.h)
+        self.kappa, self.c_kv = st.kappa, st.c_kv
+
+    def close(self):
+        if self.h is not None:
+            mukv_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def reset(self):
+        mukv_reset(self.h)
+
+    @property
+    def n_frames(self):
+        return mukv_get_state(self.h).n_frames
+
+    def compress_chunk(self, k, v, q_last=None, att_signal=None, want_signals=False):
+        """k, v: [L][Hkv][n*P][D] (any layer/head/token strides, D contiguous);
+        q_last: [Hq][n*P][D]; att_signal: float32 [n][P]."""
+        P = self.cfg.tokens_per_frame
+        assert k.dim() == 4 and k.shape == v.shape and k.stride() == v.stride() and k.stride(3) == 1
+        assert k.dtype == self.dtype and k.shape[2] % P == 0
+        n = k.shape[2] // P
+        kvs = mukv_strides(k.stride(0), k.stride(1), k.stride(2))
+        qs = None
+        if q_last is not None:
+            assert q_last.dim() == 3 and q_last.stride(2) == 1 and q_last.dtype == self.dtype
+            assert q_last.shape[1] == k.shape[2]
+            qs = mukv_strides(0, q_last.stride(0), q_last.stride(1))
+        sig, outs = None, None
+        if want_signals:
+            outs = {n_: torch.zeros(n, P, dtype=torch.float32, device=k.device) for n_ in ("att", "fft", "fused")}
+            sig = mukv_signals_out(outs["att"].data_ptr(), outs["fft"].data_ptr(), outs["fused"].data_ptr())
+        if att_signal is not None:
+            assert att_signal.dtype == torch.float32 and att_signal.is_contiguous() and att_signal.shape == (n, P)
+        mukv_compress_chunk(self.h, _ptr(k), _ptr(v), kvs, _ptr(q_last), qs, _ptr(att_signal), n, _stream(), sig)
+        return outs
+
+    def retrieve(self, q_tokens, q_offsets, *, mode=MUKV_SEMI, k_seg=8, k_frame=32, lambda_frame=0.3, n_global=0,
+                 n_visible_frames=-1, out=None):
+        """q_tokens: [sum Nq][Hq][D] contiguous; q_offsets: int32 [B+1] on the device."""
+        assert q_tokens.is_contiguous() and q_tokens.dtype == self.dtype
+        assert q_offsets.dtype == torch.int32 and q_offsets.is_cuda
+        B = q_offsets.numel() - 1
+        prm = mukv_retrieve_params(mode, k_seg, k_frame, n_global, n_visible_frames, 0, lambda_frame)
+        if out is None:
+            dev = q_tokens.device
+            out = {
+                "seg_idx": torch.empty(B, k_seg, dtype=torch.int32, device=dev),
+                "seg_score": torch.empty(B, k_seg, dtype=torch.float32, device=dev),
+                "frame_idx": torch.empty(B, k_frame, dtype=torch.int32, device=dev),
+                "frame_score": torch.empty(B, k_frame, dtype=torch.float32, device=dev),
+            }
+        mukv_retrieve(self.h, _ptr(q_tokens), _ptr(q_offsets), B, prm, _ptr(out["seg_idx"]), _ptr(out["seg_score"]),
+                      _ptr(out["frame_idx"]), _ptr(out["frame_score"]), _stream())
+        return out
+
+    def gather_kv(self, frame_idx, order=MUKV_TEMPORAL, out=None):
+        """frame_idx: int32 [B][k_frame] on the device.  Returns (k_out, v_out,
+        n_tokens) with k_out, v_out [B][L][Hkv][k_frame*kappa][D]."""
+        assert frame_idx.dtype == torch.int32 and frame_idx.is_contiguous() and frame_idx.dim() == 2
+        B, kf = frame_idx.shape
+        c = self.cfg
+        if out is None:
+            shape = (B, c.n_layers, c.n_kv_heads, kf * self.kappa, c.head_dim)
+            out = (torch.empty(shape, dtype=self.dtype, device=frame_idx.device),
+                   torch.empty(shape, dtype=self.dtype, device=frame_idx.device),
+                   torch.empty(B, dtype=torch.int32, device=frame_idx.device))
+        mukv_gather_kv(self.h, _ptr(frame_idx), B, kf, order, _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _stream())
+        return out
+
+    # -- read-only copies of the context's tables (tests, inspection) ----------------------
+    def _copy(self, ptr, shape, dtype):
+        t = torch.empty(shape, dtype=dtype, device=self.device)
+        if t.numel():
+            rc = _hip_rt().hipMemcpyAsync(t.data_ptr(), ptr, t.numel() * t.element_size(), 3, _stream())
+            if rc != 0:
+                raise RuntimeError(f"hipMemcpyAsync failed ({rc})")
+        return t
+
+    def state(self):
+        """Copies of the tables for the frames ingested so far (device tensors)."""
+        s = mukv_get_state(self.h)
+        c = self.cfg
+        n, S, Ckv, kap = s.n_frames, c.superpatches_per_frame, s.c_kv, s.kappa
+        out = {
+            "n_frames": n, "n_segments": s.n_segments, "kappa": kap,
+            "kept_idx": self._copy(s.kept_idx, (n, kap), torch.int32),
+            "rep_frame_k": self._copy(s.rep_frame_k, (n, Ckv), torch.float32),
+            "rep_frame_v": self._copy(s.rep_frame_v, (n, Ckv), torch.float32),
+            "rep_patch_k": self._copy(s.rep_patch_k, (n * S, Ckv), torch.float32),
+            "rep_patch_v": self._copy(s.rep_patch_v, (n * S, Ckv), torch.float32),
+            "cnt_patch": self._copy(s.cnt_patch, (n * S,), torch.int32),
+            "rep_seg_k": self._copy(s.rep_seg_k, (s.n_segments, Ckv), torch.float32),
+            "rep_seg_v": self._copy(s.rep_seg_v, (s.n_segments, Ckv), torch.float32),
+            "margin": self._copy(s.margin, (n,), torch.float32),
+            "refined": self._copy(s.refined, (n,), torch.int32),
+        }
+        return out
+
+    def store_rows(self, row0, row1):
+        """Copy of store rows [row0, row1) of every (layer, head): (K, V), each
+        [L][Hkv][row1-row0][D]."""
+        s = mukv_get_state(self.h)
+        c = self.cfg
+        esz = 2 if self.dtype == torch.bfloat16 else 4
+        row_b = c.head_dim * esz
+        n = row1 - row0
+        k = torch.empty(c.n_layers, c.n_kv_heads, n, c.head_dim, dtype=self.dtype, device=self.device)
+        v = torch.empty_like(k)
+        for dst, base in ((k, s.store_k), (v, s.store_v)):
+            for l in range(c.n_layers):
+                for g in range(c.n_kv_heads):
+                    off = ((l * c.n_kv_heads + g) * s.store_token_capacity + row0) * row_b
+                    rc = _hip_rt().hipMemcpyAsync(dst[l, g].data_ptr(), base + off, n * row_b, 3, _stream())
+                    if rc != 0:
+                        raise RuntimeError(f"hipMemcpyAsync failed ({rc})")
+        return k, v

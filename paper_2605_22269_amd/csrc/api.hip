@@ -1,0 +1,280 @@
+// C ABI of libmukv (declared in include/mukv.h): argument validation, context lifetime,
+// and dispatch to the kernel launchers.  No torch types, no exceptions across the boundary.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "mukv_internal.h"
+
+using mukv::Ctx;
+
+struct mukv_ctx {
+    Ctx c;
+};
+
+namespace {
+
+constexpr double kDefaultRefineMargin = 1e-4;
+
+bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+template <typename T>
+hipError_t dalloc(T **p, size_t count) {
+    *p = nullptr;
+    if (count == 0) count = 1;
+    return hipMalloc(reinterpret_cast<void **>(p), count * sizeof(T));
+}
+
+int validate_config(const mukv_config *cfg) {
+    if (!cfg) return MUKV_ERR_INVALID_ARG;
+    if (cfg->n_layers < 1 || cfg->n_q_heads < 1 || cfg->n_kv_heads < 1 || cfg->head_dim < 1 ||
+        cfg->tokens_per_frame < 1 || cfg->frames_per_segment < 1 || cfg->superpatches_per_frame < 1 ||
+        cfg->max_frames < 1 || cfg->max_chunk_frames < 1 || cfg->max_questions < 1 || cfg->device_id < 0)
+        return MUKV_ERR_INVALID_ARG;
+    if (cfg->dtype != MUKV_BF16 && cfg->dtype != MUKV_F32) return MUKV_ERR_INVALID_ARG;
+    if (!(cfg->keep_ratio > 0.0) || cfg->keep_ratio > 1.0) return MUKV_ERR_INVALID_ARG;
+    if (!(cfg->alpha >= 0.0) || cfg->alpha > 1.0) return MUKV_ERR_INVALID_ARG;
+    if (cfg->n_q_heads % cfg->n_kv_heads) return MUKV_ERR_SHAPE;
+    if (cfg->superpatches_per_frame > cfg->tokens_per_frame) return MUKV_ERR_SHAPE;
+    if (cfg->score_layer < -1 || cfg->score_layer >= cfg->n_layers) return MUKV_ERR_SHAPE;
+    if (cfg->att_path < MUKV_ATT_AUTO || cfg->att_path > MUKV_ATT_MFMA) return MUKV_ERR_INVALID_ARG;
+    const int kappa = (int)std::floor(cfg->keep_ratio * cfg->tokens_per_frame + 1e-9);
+    if (kappa < 1) return MUKV_ERR_INVALID_ARG;
+    if (!pow2(cfg->head_dim) || cfg->head_dim < 16 || cfg->head_dim > 128) return MUKV_ERR_UNSUPPORTED;
+    if (cfg->tokens_per_frame > mukv::kMaxP) return MUKV_ERR_UNSUPPORTED;
+    if ((int64_t)cfg->n_kv_heads * cfg->head_dim > 1024) return MUKV_ERR_UNSUPPORTED;
+    const int esz = cfg->dtype == MUKV_BF16 ? 2 : 4;
+    if (mukv::att_generic_lds_bytes(cfg->tokens_per_frame, cfg->head_dim, sizeof(double)) > 160 * 1024)
+        return MUKV_ERR_UNSUPPORTED;
+    if ((cfg->head_dim * esz) % 16) return MUKV_ERR_UNSUPPORTED;
+    if (((int64_t)cfg->max_frames + cfg->frames_per_segment - 1) / cfg->frames_per_segment > 65536)
+        return MUKV_ERR_UNSUPPORTED;
+    return MUKV_OK;
+}
+
+bool mfma_supported(const mukv_config &c) {
+    (void)c;
+    return false;
+}
+
+void free_all(Ctx &c) {
+    void *ptrs[] = {c.store_k,    c.store_v,    c.kept_idx,  c.rep_frame_k, c.rep_frame_v, c.rep_patch_k,
+                    c.rep_patch_v, c.rep_seg_k, c.rep_seg_v, c.cnt_patch,   c.fsum_k,      c.fsum_v,
+                    c.margin,      c.refined,   c.att_part,  c.fft_sig,     c.att64,       c.fft64,
+                    c.src_tok,     c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+}
+
+} // namespace
+
+extern "C" {
+
+const char *mukv_strerror(int status) {
+    switch (status) {
+    case MUKV_OK: return "ok";
+    case MUKV_ERR_INVALID_ARG: return "invalid argument";
+    case MUKV_ERR_SHAPE: return "shape inconsistent with the configuration";
+    case MUKV_ERR_CAPACITY: return "capacity exceeded";
+    case MUKV_ERR_UNSUPPORTED: return "unsupported shape or alignment";
+    case MUKV_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
+    if (!out) return MUKV_ERR_INVALID_ARG;
+    int rc = validate_config(cfg);
+    if (rc != MUKV_OK) return rc;
+    if (cfg->att_path == MUKV_ATT_MFMA && !mfma_supported(*cfg)) return MUKV_ERR_UNSUPPORTED;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || cfg->device_id >= n_dev) return MUKV_ERR_HIP;
+    if (hipSetDevice(cfg->device_id) != hipSuccess) return MUKV_ERR_HIP;
+
+    mukv_ctx *h = new (std::nothrow) mukv_ctx();
+    if (!h) return MUKV_ERR_HIP;
+    Ctx &c = h->c;
+    std::memset(&c, 0, sizeof(c));
+    c.cfg = *cfg;
+    c.kappa = (int)std::floor(cfg->keep_ratio * cfg->tokens_per_frame + 1e-9);
+    c.ls = cfg->score_layer < 0 ? cfg->n_layers - 1 : cfg->score_layer;
+    c.c_kv = cfg->n_kv_heads * cfg->head_dim;
+    c.group = cfg->n_q_heads / cfg->n_kv_heads;
+    c.esz = cfg->dtype == MUKV_BF16 ? 2 : 4;
+    c.max_segments = (cfg->max_frames + cfg->frames_per_segment - 1) / cfg->frames_per_segment;
+    c.use_mfma = cfg->att_path != MUKV_ATT_GENERIC && mfma_supported(*cfg);
+    c.margin_thr = cfg->refine_margin < 0.0 ? kDefaultRefineMargin : cfg->refine_margin;
+    c.n_frames = 0;
+    c.store_cap = (int64_t)cfg->max_frames * c.kappa;
+
+    const size_t store_bytes = (size_t)cfg->n_layers * cfg->n_kv_heads * c.store_cap * cfg->head_dim * c.esz;
+    const size_t MF = cfg->max_frames, C = c.c_kv, S = cfg->superpatches_per_frame, P = cfg->tokens_per_frame;
+    const size_t MC = cfg->max_chunk_frames, MQ = cfg->max_questions, Hq = cfg->n_q_heads;
+    hipError_t e = hipSuccess;
+    auto ok = [&](hipError_t r) {
+        if (e == hipSuccess) e = r;
+    };
+    ok(dalloc(reinterpret_cast<unsigned char **>(&c.store_k), store_bytes));
+    ok(dalloc(reinterpret_cast<unsigned char **>(&c.store_v), store_bytes));
+    ok(dalloc(&c.kept_idx, MF * c.kappa));
+    ok(dalloc(&c.rep_frame_k, MF * C));
+    ok(dalloc(&c.rep_frame_v, MF * C));
+    ok(dalloc(&c.rep_patch_k, MF * S * C));
+    ok(dalloc(&c.rep_patch_v, MF * S * C));
+    ok(dalloc(&c.rep_seg_k, (size_t)c.max_segments * C));
+    ok(dalloc(&c.rep_seg_v, (size_t)c.max_segments * C));
+    ok(dalloc(&c.cnt_patch, MF * S));
+    ok(dalloc(&c.fsum_k, MF * C));
+    ok(dalloc(&c.fsum_v, MF * C));
+    ok(dalloc(&c.margin, MF));
+    ok(dalloc(&c.refined, MF));
+    ok(dalloc(&c.att_part, MC * Hq * P));
+    ok(dalloc(&c.fft_sig, MC * P));
+    ok(dalloc(&c.att64, MC * Hq * P));
+    ok(dalloc(&c.fft64, MC * P));
+    ok(dalloc(&c.src_tok, MC * c.kappa));
+    ok(dalloc(&c.qbar, MQ * C));
+    ok(dalloc(&c.qq, MQ * cfg->n_kv_heads));
+    ok(dalloc(&c.s_frm, MQ * MF));
+    ok(dalloc(&c.s_seg, MQ * (size_t)c.max_segments));
+    ok(dalloc(&c.seg_tail, 2 * C));
+    if (e != hipSuccess) {
+        free_all(c);
+        delete h;
+        (void)hipGetLastError();
+        return MUKV_ERR_HIP;
+    }
+    *out = h;
+    return MUKV_OK;
+}
+
+int mukv_destroy(mukv_ctx *ctx) {
+    if (!ctx) return MUKV_OK;
+    (void)hipSetDevice(ctx->c.cfg.device_id);
+    free_all(ctx->c);
+    delete ctx;
+    return MUKV_OK;
+}
+
+int mukv_reset(mukv_ctx *ctx) {
+    if (!ctx) return MUKV_ERR_INVALID_ARG;
+    ctx->c.n_frames = 0;
+    return MUKV_OK;
+}
+
+int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_strides *kv_strides,
+                        const void *q_last, const mukv_strides *q_strides, const float *att_signal,
+                        int32_t n_frames, void *stream, const mukv_signals_out *sig) {
+    if (!ctx || !k || !v || !kv_strides) return MUKV_ERR_INVALID_ARG;
+    Ctx &c = ctx->c;
+    if (c.cfg.alpha != 0.0) {
+        if ((q_last != nullptr) == (att_signal != nullptr)) return MUKV_ERR_INVALID_ARG;
+        if (q_last && !q_strides) return MUKV_ERR_INVALID_ARG;
+    }
+    if (n_frames < 1) return MUKV_ERR_SHAPE;
+    if (n_frames > c.cfg.max_chunk_frames) return MUKV_ERR_CAPACITY;
+    if (c.n_frames + n_frames > c.cfg.max_frames) return MUKV_ERR_CAPACITY;
+    const int64_t D = c.cfg.head_dim;
+    if (kv_strides->token < D || kv_strides->head < 0 || kv_strides->layer < 0) return MUKV_ERR_SHAPE;
+    const int64_t unit = 16 / c.esz; // elements per 16 bytes
+    if (kv_strides->token % unit || kv_strides->head % unit || kv_strides->layer % unit ||
+        (reinterpret_cast<uintptr_t>(k) & 15) || (reinterpret_cast<uintptr_t>(v) & 15))
+        return MUKV_ERR_UNSUPPORTED;
+    mukv::ChunkArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.k = k;
+    a.v = v;
+    a.kv_sl = kv_strides->layer;
+    a.kv_sh = kv_strides->head;
+    a.kv_st = kv_strides->token;
+    if (c.cfg.alpha != 0.0 && q_last) {
+        if (q_strides->token < D || q_strides->head < 0) return MUKV_ERR_SHAPE;
+        if (q_strides->token % unit || q_strides->head % unit || (reinterpret_cast<uintptr_t>(q_last) & 15))
+            return MUKV_ERR_UNSUPPORTED;
+        a.q = q_last;
+        a.q_sh = q_strides->head;
+        a.q_st = q_strides->token;
+    }
+    a.att_in = (c.cfg.alpha != 0.0) ? att_signal : nullptr;
+    a.n_frames = n_frames;
+    a.frame0 = c.n_frames;
+    if (sig) a.sig = *sig;
+    if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
+    hipError_t e = mukv::launch_compress(c, a, reinterpret_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return MUKV_ERR_HIP;
+    c.n_frames += n_frames;
+    return MUKV_OK;
+}
+
+int mukv_retrieve(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, int32_t B,
+                  const mukv_retrieve_params *params, int32_t *seg_idx_out, float *seg_score_out,
+                  int32_t *frame_idx_out, float *frame_score_out, void *stream) {
+    if (!ctx || !q_tokens || !q_offsets || !params || !seg_idx_out || !frame_idx_out) return MUKV_ERR_INVALID_ARG;
+    Ctx &c = ctx->c;
+    if (B < 1) return MUKV_ERR_INVALID_ARG;
+    if (B > c.cfg.max_questions) return MUKV_ERR_CAPACITY;
+    if (params->mode < MUKV_SEMI || params->mode > MUKV_PARALLEL) return MUKV_ERR_INVALID_ARG;
+    if (params->k_seg < 1 || params->k_frame < 1 || params->n_global < 0) return MUKV_ERR_INVALID_ARG;
+    if (!(params->lambda_frame >= 0.0) || params->lambda_frame > 1.0) return MUKV_ERR_INVALID_ARG;
+    if (2 * params->k_seg > mukv::kMaxCand || 2 * params->k_frame > mukv::kMaxCand) return MUKV_ERR_UNSUPPORTED;
+    mukv::RetrieveArgs a;
+    a.q_tokens = q_tokens;
+    a.q_offsets = q_offsets;
+    a.B = B;
+    a.p = *params;
+    int64_t nv = params->n_visible_frames < 0 ? c.n_frames : params->n_visible_frames;
+    if (nv > c.n_frames) nv = c.n_frames;
+    a.nv = (int)nv;
+    a.ns = (int)((nv + c.cfg.frames_per_segment - 1) / c.cfg.frames_per_segment);
+    a.seg_idx = seg_idx_out;
+    a.seg_score = seg_score_out;
+    a.frm_idx = frame_idx_out;
+    a.frm_score = frame_score_out;
+    if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
+    return mukv::launch_retrieve(c, a, reinterpret_cast<hipStream_t>(stream)) == hipSuccess ? MUKV_OK : MUKV_ERR_HIP;
+}
+
+int mukv_gather_kv(mukv_ctx *ctx, const int32_t *frame_idx, int32_t B, int32_t k_frame, int32_t order,
+                   void *k_out, void *v_out, int32_t *n_tokens_out, void *stream) {
+    if (!ctx || !frame_idx || !k_out || !v_out) return MUKV_ERR_INVALID_ARG;
+    Ctx &c = ctx->c;
+    if (B < 1 || k_frame < 1) return MUKV_ERR_INVALID_ARG;
+    if (order != MUKV_TEMPORAL && order != MUKV_AS_GIVEN) return MUKV_ERR_INVALID_ARG;
+    if (B > c.cfg.max_questions) return MUKV_ERR_CAPACITY;
+    if (k_frame > mukv::kMaxGatherK) return MUKV_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(k_out) & 15) || (reinterpret_cast<uintptr_t>(v_out) & 15))
+        return MUKV_ERR_UNSUPPORTED;
+    if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
+    return mukv::launch_gather(c, frame_idx, B, k_frame, order, k_out, v_out, n_tokens_out,
+                               reinterpret_cast<hipStream_t>(stream)) == hipSuccess
+               ? MUKV_OK
+               : MUKV_ERR_HIP;
+}
+
+int mukv_get_state(const mukv_ctx *ctx, mukv_state *out) {
+    if (!ctx || !out) return MUKV_ERR_INVALID_ARG;
+    const Ctx &c = ctx->c;
+    const int F = c.cfg.frames_per_segment;
+    out->n_frames = c.n_frames;
+    out->n_segments = (c.n_frames + F - 1) / F;
+    out->n_kept_tokens = c.n_frames * c.kappa;
+    out->store_token_capacity = c.store_cap;
+    out->kappa = c.kappa;
+    out->c_kv = c.c_kv;
+    out->store_k = c.store_k;
+    out->store_v = c.store_v;
+    out->kept_idx = c.kept_idx;
+    out->rep_frame_k = c.rep_frame_k;
+    out->rep_frame_v = c.rep_frame_v;
+    out->rep_patch_k = c.rep_patch_k;
+    out->rep_patch_v = c.rep_patch_v;
+    out->cnt_patch = c.cnt_patch;
+    out->rep_seg_k = c.rep_seg_k;
+    out->rep_seg_v = c.rep_seg_v;
+    out->margin = c.margin;
+    out->refined = c.refined;
+    return MUKV_OK;
+}
+
+} // extern "C"

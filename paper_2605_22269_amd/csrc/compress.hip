@@ -1,0 +1,582 @@
+// Offline half of MuKV (Sec. 3.3 of the paper): token scoring, per-frame keep,
+// KV compaction and block-key pooling for one chunk of frames.
+//
+// Kernel chain enqueued by launch_compress (all on the caller's stream):
+//   att_generic<float> | att_mfma      Eq. 1   partial attention received per (frame, head group)
+//   freq_signal<float>                 Eq. 2-3 length-D DFT magnitudes of every key
+//   select_pool<float>                 Eq. 4 fusion, keep of the kappa best, Eq. 5 frame / super-patch keys
+//   att_generic<double>, freq_signal<double>, select_pool<double>
+//                                      the same three steps in fp64, only for frames whose
+//                                      fp32 selection margin is below the threshold
+//   compact                            copy of the kept rows of all layers; segment keys
+#include "mukv_internal.h"
+
+namespace mukv {
+
+// ------------------------------------------------------------------------------------------
+// Eq. 2-3: frequency indicator.  A real length-D transform is done as a complex transform of
+// length N = D/2 spread over N lanes (lane p holds x[2p] + i*x[2p+1]), radix-2 decimation in
+// frequency with lane exchanges, then the usual split into the spectra of the even and odd
+// samples.  Bins m and D-m have equal magnitude, so sum_m |X[m]| = |X[0]| + |X[D/2]| +
+// 2*sum_{0<m<D/2} |X[m]|.  One wave handles 64/N tokens at a time and loops over the KV heads.
+// R is the arithmetic type (float for the main path, double for re-scored frames).
+// ------------------------------------------------------------------------------------------
+template <int N>
+__device__ __forceinline__ int bitrev(int x) {
+    int r = 0;
+#pragma unroll
+    for (int b = 1; b < N; b <<= 1) {
+        r = (r << 1) | (x & 1);
+        x >>= 1;
+    }
+    return r;
+}
+
+__device__ __forceinline__ void sincospi_t(float x, float *s, float *c) { sincospif(x, s, c); }
+__device__ __forceinline__ void sincospi_t(double x, double *s, double *c) { sincospi(x, s, c); }
+__device__ __forceinline__ float sqrt_t(float x) { return sqrtf(x); }
+__device__ __forceinline__ double sqrt_t(double x) { return sqrt(x); }
+__device__ __forceinline__ float abs_t(float x) { return fabsf(x); }
+__device__ __forceinline__ double abs_t(double x) { return fabs(x); }
+
+template <typename T, typename R, int D>
+__global__ __launch_bounds__(256) void freq_signal_kernel(const T *__restrict__ k, int64_t sh, int64_t st, int Hkv,
+                                                          int P, int n_tok, int64_t frame0,
+                                                          const int32_t *__restrict__ only_flagged,
+                                                          R *__restrict__ out) {
+    constexpr int N = D / 2;
+    constexpr int GROUPS = kWave / N;
+    constexpr int LOG = (N == 64) ? 6 : (N == 32) ? 5 : (N == 16) ? 4 : 3;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int p = lane % N, sub = lane / N;
+    const int64_t tok = ((int64_t)blockIdx.x * 4 + wave) * GROUPS + sub;
+    bool valid = tok < n_tok;
+    if (valid && only_flagged) valid = only_flagged[frame0 + tok / P] != 0;
+
+    R twr[LOG], twi[LOG];
+#pragma unroll
+    for (int s = 0; s < LOG; ++s) {
+        const int h = N >> (s + 1);
+        sincospi_t(-(R)(p & (h - 1)) / (R)h, &twi[s], &twr[s]);
+    }
+    const int kb = bitrev<N>(p);
+    const int partner = bitrev<N>((N - kb) & (N - 1)) + sub * N;
+    R uwr, uwi;
+    sincospi_t(-(R)kb / (R)N, &uwi, &uwr);
+
+    R total = 0;
+    for (int g = 0; g < Hkv; ++g) {
+        R zr = 0, zi = 0;
+        if (valid) {
+            const T *row = k + (int64_t)g * sh + tok * st + 2 * p;
+            zr = (R)to_float(row[0]);
+            zi = (R)to_float(row[1]);
+        }
+#pragma unroll
+        for (int s = 0; s < LOG; ++s) {
+            const int h = N >> (s + 1);
+            const R pr = __shfl_xor(zr, h), pi = __shfl_xor(zi, h);
+            if (p & h) {
+                const R dr = pr - zr, di = pi - zi;
+                zr = dr * twr[s] - di * twi[s];
+                zi = dr * twi[s] + di * twr[s];
+            } else {
+                zr += pr;
+                zi += pi;
+            }
+        }
+        // lane p now holds Z[kb]; fetch Z[(N-kb) mod N]
+        const R pr = __shfl(zr, partner), pi = __shfl(zi, partner);
+        R c;
+        if (kb == 0) {
+            c = abs_t(zr + zi) + abs_t(zr - zi); // X[0] and X[D/2]
+        } else {
+            const R er = (R)0.5 * (zr + pr), ei = (R)0.5 * (zi - pi);
+            const R odr = (R)0.5 * (zi + pi), odi = (R)-0.5 * (zr - pr);
+            const R xr = er + (odr * uwr - odi * uwi);
+            const R xi = ei + (odr * uwi + odi * uwr);
+            c = (R)2 * sqrt_t(xr * xr + xi * xi);
+        }
+        total += c;
+    }
+#pragma unroll
+    for (int o = N / 2; o > 0; o >>= 1) total += __shfl_xor(total, o);
+    if (p == 0 && valid) out[tok] = total / (R)(Hkv * D);
+}
+
+// ------------------------------------------------------------------------------------------
+// Eq. 1, generic path (any dtype, any D, P <= 256): one workgroup per (frame, query head).
+// The frame's keys sit in LDS as float (exact for bf16 and fp32 payloads); a wave takes one
+// query row at a time, lanes own keys j = lane + 64*t, the row softmax uses wave reductions,
+// and each lane accumulates the probabilities of its keys.  Per-wave partial column sums are
+// combined in a fixed order, so results are run-to-run identical.
+// out: [frame][Hq][P] (R) partial sums over the query rows of one head, not yet divided.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ float exp_t(float x) { return expf(x); }
+__device__ __forceinline__ double exp_t(double x) { return exp(x); }
+
+template <typename T, typename R>
+__global__ __launch_bounds__(256) void att_generic_kernel(const T *__restrict__ q, int64_t q_sh, int64_t q_st,
+                                                          const T *__restrict__ k, int64_t k_sh, int64_t k_st,
+                                                          int P, int D, int G, int Hq, int causal, int64_t frame0,
+                                                          const int32_t *__restrict__ only_flagged,
+                                                          R *__restrict__ out) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const int f = blockIdx.x, h = blockIdx.y;
+    if (only_flagged && only_flagged[frame0 + f] == 0) return;
+    const int ldk = D + 1;
+    float *Ks = reinterpret_cast<float *>(smem_raw);   // [P][D+1]
+    float *qs = Ks + (size_t)P * ldk;                   // [4][D]
+    size_t n_fl = (size_t)P * ldk + 4 * D;
+    n_fl += n_fl & 1;
+    R *part = reinterpret_cast<R *>(Ks + n_fl);        // [4][P], 8-byte aligned
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const T *kf = k + (int64_t)(h / G) * k_sh + (int64_t)f * P * k_st;
+    const T *qf = q + (int64_t)h * q_sh + (int64_t)f * P * q_st;
+    for (int e = tid; e < P * D; e += 256) {
+        const int j = e / D, d = e - j * D;
+        Ks[j * ldk + d] = to_float(kf[(int64_t)j * k_st + d]);
+    }
+    const R scale = (R)1 / sqrt_t((R)D);
+    R acc[4] = {0, 0, 0, 0};
+    const int n_it = (P + 3) / 4;
+    for (int it = 0; it < n_it; ++it) {
+        const int i = it * 4 + wave;
+        __syncthreads();
+        if (i < P)
+            for (int d = lane; d < D; d += 64) qs[wave * D + d] = to_float(qf[(int64_t)i * q_st + d]);
+        __syncthreads();
+        if (i >= P) continue;
+        const int nj = causal ? i + 1 : P;
+        R s[4];
+        R m = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int j = lane + 64 * t;
+            s[t] = -INFINITY;
+            if (j < nj) {
+                R dot = 0;
+                const float *kr = Ks + j * ldk;
+                const float *qr = qs + wave * D;
+                for (int d = 0; d < D; ++d) dot += (R)qr[d] * (R)kr[d];
+                s[t] = dot * scale;
+            }
+            m = s[t] > m ? s[t] : m;
+        }
+        m = wave_max(m);
+        R z = 0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int j = lane + 64 * t;
+            s[t] = (j < nj) ? exp_t(s[t] - m) : (R)0;
+            z += s[t];
+        }
+        z = wave_sum(z);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[t] += s[t] / z;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int j = lane + 64 * t;
+        if (j < P) part[wave * P + j] = acc[t];
+    }
+    __syncthreads();
+    for (int j = tid; j < P; j += 256)
+        out[((int64_t)f * Hq + h) * P + j] = ((part[j] + part[P + j]) + part[2 * P + j]) + part[3 * P + j];
+}
+
+// ------------------------------------------------------------------------------------------
+// Eq. 4 fusion, per-frame keep (Sec. 3.3, granularity-adaptive compression with the frame as
+// the unit) and Eq. 5 block keys for the frame and its super-patches.  One workgroup of 256
+// threads per frame, thread j owns token j (P <= 256).
+// Ranking is by counting: rank(j) = #{i : I[i] > I[j] or (I[i] == I[j] and i < j)}, so equal
+// scores resolve to the lowest position; token j is kept iff rank(j) < kappa.
+// Pooled sums are accumulated in fp64 (exact for bf16 / fp32 payloads of ordinary dynamic
+// range), divided once and rounded once to float.
+// ------------------------------------------------------------------------------------------
+template <typename R>
+struct SelectArgs {
+    const R *att;       // [n_frames][n_part][P] partial sums, or NULL (alpha == 0)
+    int n_part;
+    R att_scale;        // 1/(Hq*P) for partial sums, 1 for a caller-supplied signal
+    const float *att_in; // caller-supplied [n_frames][P], or NULL
+    const R *fft;       // [n_frames][P], or NULL (alpha == 1)
+    R alpha;
+    int P, kappa, S, Hkv, D;
+    int64_t frame0;
+    const void *k, *v;  // scoring layer base of the chunk
+    int64_t sh, st;
+    R margin_thr;
+    int pass2;          // 1: only frames flagged by pass 1
+    int32_t *kept_idx;
+    int32_t *src_tok;
+    float *rep_frame_k, *rep_frame_v, *rep_patch_k, *rep_patch_v;
+    int32_t *cnt_patch;
+    double *fsum_k, *fsum_v;
+    float *margin;
+    int32_t *refined;
+    float *dbg_att, *dbg_fft, *dbg_fused;
+};
+
+template <typename R>
+__device__ __forceinline__ void block_minmax(R v, bool valid, R *red, R &lo, R &hi) {
+    R mn = valid ? v : (R)INFINITY, mx = valid ? v : (R)-INFINITY;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const R a = __shfl_xor(mn, o), b = __shfl_xor(mx, o);
+        mn = a < mn ? a : mn;
+        mx = b > mx ? b : mx;
+    }
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+        red[wave] = mn;
+        red[4 + wave] = mx;
+    }
+    __syncthreads();
+    lo = red[0];
+    hi = red[4];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+        lo = red[w] < lo ? red[w] : lo;
+        hi = red[4 + w] > hi ? red[4 + w] : hi;
+    }
+}
+
+template <typename T, typename R>
+__global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
+    __shared__ R sc[kMaxP];
+    __shared__ R red[8];
+    __shared__ R vk[2];
+    __shared__ int kl[kMaxP];
+    __shared__ unsigned char keepf[kMaxP];
+    const int f = blockIdx.x, j = threadIdx.x;
+    const int64_t gf = a.frame0 + f;
+    const int P = a.P, kappa = a.kappa;
+    if (a.pass2 && a.refined[gf] == 0) return;
+    const bool valid = j < P;
+
+    R av = 0, fv = 0;
+    if (valid && a.alpha != (R)0) {
+        if (a.att_in) {
+            av = (R)a.att_in[(int64_t)f * P + j];
+        } else {
+            const R *pp = a.att + (int64_t)f * a.n_part * P + j;
+            for (int n = 0; n < a.n_part; ++n) av += pp[(int64_t)n * P];
+            av *= a.att_scale;
+        }
+    }
+    if (valid && a.alpha != (R)1) fv = a.fft[(int64_t)f * P + j];
+    if (valid && a.dbg_att) a.dbg_att[(int64_t)f * P + j] = (float)av;
+    if (valid && a.dbg_fft) a.dbg_fft[(int64_t)f * P + j] = (float)fv;
+
+    R lo, hi;
+    R fused = 0;
+    if (a.alpha != (R)0) {
+        block_minmax(av, valid, red, lo, hi);
+        const R an = (hi > lo) ? (av - lo) / (hi - lo) : (R)0;
+        fused = a.alpha * an;
+    }
+    if (a.alpha != (R)1) {
+        block_minmax(fv, valid, red, lo, hi);
+        const R fn = (hi > lo) ? (fv - lo) / (hi - lo) : (R)0;
+        fused += ((R)1 - a.alpha) * fn;
+    }
+    if (valid) {
+        sc[j] = fused;
+        if (a.dbg_fused) a.dbg_fused[(int64_t)f * P + j] = (float)fused;
+    }
+    if (j < 2) vk[j] = 0;
+    __syncthreads();
+
+    int rank = 0;
+    if (valid) {
+        for (int i = 0; i < P; ++i) {
+            const R o = sc[i];
+            rank += (o > fused) || (o == fused && i < j);
+        }
+        keepf[j] = rank < kappa;
+        if (rank == kappa - 1) vk[0] = fused;
+        if (rank == kappa) vk[1] = fused;
+    }
+    __syncthreads();
+    if (valid && rank < kappa) {
+        int pos = 0;
+        for (int i = 0; i < j; ++i) pos += keepf[i];
+        kl[pos] = j;
+        a.kept_idx[gf * kappa + pos] = j;
+        a.src_tok[(int64_t)f * kappa + pos] = f * P + j;
+    }
+    if (j == 0) {
+        const R mg = (kappa < P) ? vk[0] - vk[1] : (R)INFINITY;
+        a.margin[gf] = (float)mg;
+        a.refined[gf] = a.pass2 ? 1 : ((a.margin_thr > (R)0 && mg < a.margin_thr) ? 1 : 0);
+    }
+    __syncthreads();
+
+    // Eq. 5 for the frame and its S super-patches, K then V
+    const int C = a.Hkv * a.D;
+    const int len = P / a.S;
+    for (int which = 0; which < 2; ++which) {
+        const T *x = reinterpret_cast<const T *>(which ? a.v : a.k);
+        float *rep_frame = which ? a.rep_frame_v : a.rep_frame_k;
+        float *rep_patch = which ? a.rep_patch_v : a.rep_patch_k;
+        double *fsum = which ? a.fsum_v : a.fsum_k;
+        for (int c = j; c < C; c += 256) {
+            const int g = c / a.D, d = c - g * a.D;
+            const T *col = x + (int64_t)g * a.sh + d;
+            int r = 0;
+            double tot = 0.0;
+            for (int s = 0; s < a.S; ++s) {
+                const int end = (s == a.S - 1) ? P : (s + 1) * len;
+                double run = 0.0;
+                int cnt = 0;
+                while (r < kappa && kl[r] < end) {
+                    run += (double)to_float(col[((int64_t)f * P + kl[r]) * a.st]);
+                    ++cnt;
+                    ++r;
+                }
+                rep_patch[(gf * a.S + s) * C + c] = cnt ? (float)(run / (double)cnt) : 0.0f;
+                if (which == 0 && c == 0) a.cnt_patch[gf * a.S + s] = cnt;
+                tot += run;
+            }
+            fsum[gf * C + c] = tot;
+            rep_frame[gf * C + c] = (float)(tot / (double)kappa);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Storage of the kept KV rows of every layer (Sec. 3.3, last paragraph) and segment keys.
+// grid.y < n_slab: slab (layer, K|V, KV head); the slab's destination is one dense run of
+// n_frames*kappa rows, so unit u of the slab goes to dst + u*VEC and comes from the row
+// src_tok[u / units_per_row] of the chunk.  Each thread moves ITER units: loads first, then
+// stores.  grid.y >= n_slab: one workgroup per segment touched by the chunk recomputes that
+// segment's keys from the exact per-frame sums (any chunking gives the same bits).
+// ------------------------------------------------------------------------------------------
+struct CompactArgs {
+    const unsigned char *k, *v;  // chunk base, bytes
+    int64_t sl_b, sh_b, st_b;    // byte strides layer / head / token
+    unsigned char *store_k, *store_v;
+    int64_t slab_b;              // bytes of one (layer, head) slab of the store
+    int64_t dst_off_b;           // byte offset of frame0's first row inside a slab
+    const int32_t *src_tok;
+    int n_units;                 // units per slab = n_frames*kappa*units_per_row
+    int log_upr;                 // log2(units per row)
+    int Hkv, n_slab;
+    // segment update
+    int seg_first, F, kappa, C;
+    int64_t n_total;             // frames in the cache after this chunk
+    const double *fsum_k, *fsum_v;
+    float *rep_seg_k, *rep_seg_v;
+};
+
+template <typename V, int ITER>
+__global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
+    const int y = blockIdx.y;
+    if (y >= a.n_slab) {
+        if (blockIdx.x != 0) return;
+        const int s = a.seg_first + (y - a.n_slab);
+        const int64_t f0 = (int64_t)s * a.F;
+        const int64_t f1 = (f0 + a.F < a.n_total) ? f0 + a.F : a.n_total;
+        const double inv_n = (double)(f1 - f0) * (double)a.kappa;
+        for (int c = threadIdx.x; c < a.C; c += 256) {
+            double sk = 0.0, sv = 0.0;
+            for (int64_t f = f0; f < f1; ++f) {
+                sk += a.fsum_k[f * a.C + c];
+                sv += a.fsum_v[f * a.C + c];
+            }
+            a.rep_seg_k[(int64_t)s * a.C + c] = (float)(sk / inv_n);
+            a.rep_seg_v[(int64_t)s * a.C + c] = (float)(sv / inv_n);
+        }
+        return;
+    }
+    const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
+    const int kv = rem / a.Hkv, g = rem - kv * a.Hkv;
+    const unsigned char *src = (kv ? a.v : a.k) + (int64_t)l * a.sl_b + (int64_t)g * a.sh_b;
+    unsigned char *dst = (kv ? a.store_v : a.store_k) + ((int64_t)l * a.Hkv + g) * a.slab_b + a.dst_off_b;
+    const int mask = (1 << a.log_upr) - 1;
+    V tmp[ITER];
+    const int u0 = blockIdx.x * (256 * ITER) + threadIdx.x;
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        const int u = u0 + it * 256;
+        if (u < a.n_units) {
+            const int row = u >> a.log_upr, part = u & mask;
+            tmp[it] = *reinterpret_cast<const V *>(src + (int64_t)a.src_tok[row] * a.st_b + (int64_t)part * sizeof(V));
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        const int u = u0 + it * 256;
+        if (u < a.n_units) *reinterpret_cast<V *>(dst + (int64_t)u * sizeof(V)) = tmp[it];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------
+template <typename T, typename R>
+static hipError_t launch_freq(const Ctx &c, const ChunkArgs &a, const int32_t *flags, R *out, hipStream_t st) {
+    const T *k = reinterpret_cast<const T *>(a.k) + (int64_t)c.ls * a.kv_sl;
+    const int P = c.cfg.tokens_per_frame, D = c.cfg.head_dim, Hkv = c.cfg.n_kv_heads;
+    const int n_tok = a.n_frames * P;
+    const int groups = kWave / (D / 2);
+    const int n_blk = (n_tok + 4 * groups - 1) / (4 * groups);
+#define MUKV_FREQ(DD)                                                                                        \
+    hipLaunchKernelGGL((freq_signal_kernel<T, R, DD>), dim3(n_blk), dim3(256), 0, st, k, a.kv_sh, a.kv_st, \
+                       Hkv, P, n_tok, a.frame0, flags, out)
+    switch (D) {
+    case 128: MUKV_FREQ(128); break;
+    case 64: MUKV_FREQ(64); break;
+    case 32: MUKV_FREQ(32); break;
+    case 16: MUKV_FREQ(16); break;
+    default: return hipErrorInvalidValue;
+    }
+#undef MUKV_FREQ
+    return hipGetLastError();
+}
+
+size_t att_generic_lds_bytes(int P, int D, size_t r_size) {
+    size_t floats = (size_t)P * (D + 1) + 4 * D;
+    floats += floats & 1;
+    return floats * 4 + (size_t)4 * P * r_size;
+}
+
+template <typename T, typename R>
+static hipError_t launch_att_generic(const Ctx &c, const ChunkArgs &a, const int32_t *flags, R *out, hipStream_t st) {
+    const int P = c.cfg.tokens_per_frame, D = c.cfg.head_dim;
+    const T *k = reinterpret_cast<const T *>(a.k) + (int64_t)c.ls * a.kv_sl;
+    const T *q = reinterpret_cast<const T *>(a.q);
+    const size_t lds = att_generic_lds_bytes(P, D, sizeof(R));
+    static bool attr_set = false; // per instantiation
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&att_generic_kernel<T, R>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((att_generic_kernel<T, R>), dim3(a.n_frames, c.cfg.n_q_heads), dim3(256), lds, st, q, a.q_sh,
+                       a.q_st, k, a.kv_sh, a.kv_st, P, D, c.group, c.cfg.n_q_heads, c.cfg.causal, a.frame0, flags,
+                       out);
+    return hipGetLastError();
+}
+
+hipError_t launch_att_mfma(const Ctx &c, const ChunkArgs &a, float *out, int *n_part, hipStream_t st);
+
+template <typename T, typename R>
+static hipError_t launch_select(const Ctx &c, const ChunkArgs &a, const R *att, int n_part, const R *fft, int pass2,
+                                hipStream_t st) {
+    SelectArgs<R> s;
+    const bool need_att = c.cfg.alpha != 0.0;
+    s.att = (need_att && !a.att_in) ? att : nullptr;
+    s.n_part = n_part;
+    s.att_scale = (R)(1.0 / ((double)c.cfg.n_q_heads * (double)c.cfg.tokens_per_frame));
+    s.att_in = need_att ? a.att_in : nullptr;
+    s.fft = (c.cfg.alpha != 1.0) ? fft : nullptr;
+    s.alpha = (R)c.cfg.alpha;
+    s.P = c.cfg.tokens_per_frame;
+    s.kappa = c.kappa;
+    s.S = c.cfg.superpatches_per_frame;
+    s.Hkv = c.cfg.n_kv_heads;
+    s.D = c.cfg.head_dim;
+    s.frame0 = a.frame0;
+    s.k = reinterpret_cast<const T *>(a.k) + (int64_t)c.ls * a.kv_sl;
+    s.v = reinterpret_cast<const T *>(a.v) + (int64_t)c.ls * a.kv_sl;
+    s.sh = a.kv_sh;
+    s.st = a.kv_st;
+    s.margin_thr = (R)c.margin_thr;
+    s.pass2 = pass2;
+    s.kept_idx = c.kept_idx;
+    s.src_tok = c.src_tok;
+    s.rep_frame_k = c.rep_frame_k;
+    s.rep_frame_v = c.rep_frame_v;
+    s.rep_patch_k = c.rep_patch_k;
+    s.rep_patch_v = c.rep_patch_v;
+    s.cnt_patch = c.cnt_patch;
+    s.fsum_k = c.fsum_k;
+    s.fsum_v = c.fsum_v;
+    s.margin = c.margin;
+    s.refined = c.refined;
+    s.dbg_att = a.sig.att;
+    s.dbg_fft = a.sig.fft;
+    s.dbg_fused = a.sig.fused;
+    hipLaunchKernelGGL((select_pool_kernel<T, R>), dim3(a.n_frames), dim3(256), 0, st, s);
+    return hipGetLastError();
+}
+
+static int ilog2(int x) {
+    int l = 0;
+    while ((1 << l) < x) ++l;
+    return l;
+}
+
+static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, hipStream_t st) {
+    CompactArgs k;
+    const int esz = c.esz, D = c.cfg.head_dim;
+    const int row_b = D * esz;
+    k.k = reinterpret_cast<const unsigned char *>(a.k);
+    k.v = reinterpret_cast<const unsigned char *>(a.v);
+    k.sl_b = a.kv_sl * esz;
+    k.sh_b = a.kv_sh * esz;
+    k.st_b = a.kv_st * esz;
+    k.store_k = reinterpret_cast<unsigned char *>(c.store_k);
+    k.store_v = reinterpret_cast<unsigned char *>(c.store_v);
+    k.slab_b = c.store_cap * row_b;
+    k.dst_off_b = a.frame0 * c.kappa * (int64_t)row_b;
+    k.src_tok = c.src_tok;
+    const int upr = row_b / 16; // rows are whole 16-byte units (validated at create)
+    k.log_upr = ilog2(upr);
+    k.n_units = a.n_frames * c.kappa * upr;
+    k.Hkv = c.cfg.n_kv_heads;
+    k.n_slab = c.cfg.n_layers * 2 * c.cfg.n_kv_heads;
+    k.F = c.cfg.frames_per_segment;
+    k.kappa = c.kappa;
+    k.C = c.c_kv;
+    k.n_total = a.frame0 + a.n_frames;
+    k.seg_first = (int)(a.frame0 / k.F);
+    const int seg_last = (int)((k.n_total - 1) / k.F);
+    k.fsum_k = c.fsum_k;
+    k.fsum_v = c.fsum_v;
+    k.rep_seg_k = c.rep_seg_k;
+    k.rep_seg_v = c.rep_seg_v;
+    constexpr int ITER = 4;
+    const int gx = (k.n_units + 256 * ITER - 1) / (256 * ITER);
+    const int gy = k.n_slab + (seg_last - k.seg_first + 1);
+    hipLaunchKernelGGL((compact_kernel<uint4, ITER>), dim3(gx, gy), dim3(256), 0, st, k);
+    return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
+    hipError_t e;
+    const bool need_att = c.cfg.alpha != 0.0 && !a.att_in;
+    const bool need_fft = c.cfg.alpha != 1.0;
+    int n_part = c.cfg.n_q_heads;
+    if (need_att) {
+        if (c.use_mfma) {
+            if ((e = launch_att_mfma(c, a, c.att_part, &n_part, st)) != hipSuccess) return e;
+        } else {
+            if ((e = launch_att_generic<T, float>(c, a, nullptr, c.att_part, st)) != hipSuccess) return e;
+        }
+    }
+    if (need_fft)
+        if ((e = launch_freq<T, float>(c, a, nullptr, c.fft_sig, st)) != hipSuccess) return e;
+    if ((e = launch_select<T, float>(c, a, c.att_part, n_part, c.fft_sig, 0, st)) != hipSuccess) return e;
+    if (c.margin_thr > 0.0) {
+        // frames with a near-tie at the keep boundary: redo Eq. 1-4 in fp64 and select again
+        if (need_att)
+            if ((e = launch_att_generic<T, double>(c, a, c.refined, c.att64, st)) != hipSuccess) return e;
+        if (need_fft)
+            if ((e = launch_freq<T, double>(c, a, c.refined, c.fft64, st)) != hipSuccess) return e;
+        if ((e = launch_select<T, double>(c, a, c.att64, c.cfg.n_q_heads, c.fft64, 1, st)) != hipSuccess) return e;
+    }
+    return launch_compact(c, a, st);
+}
+
+hipError_t launch_compress(Ctx &c, const ChunkArgs &a, hipStream_t st) {
+    return c.cfg.dtype == MUKV_BF16 ? compress_typed<uint16_t>(c, a, st) : compress_typed<float>(c, a, st);
+}
+
+} // namespace mukv

@@ -1,0 +1,106 @@
+// Internal declarations shared by the HIP translation units of libmukv.
+// Nothing here is part of the public ABI (see include/mukv.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mukv.h"
+
+namespace mukv {
+
+constexpr int kWave = 64;
+constexpr int kMaxP = 256;        // tokens per frame the per-frame kernels are built for
+constexpr int kMaxCand = 1024;    // stage-1 candidates (2*k) held in LDS by the rerank kernel
+constexpr int kMaxGatherK = 1024; // selected frames per question the gather kernel can plan
+
+struct Ctx {
+    mukv_config cfg;
+    int kappa, ls, c_kv, group, esz, max_segments;
+    bool use_mfma;
+    double margin_thr;
+    int64_t n_frames;  // host-side append position
+    int64_t store_cap; // tokens per (layer, head) slab of the store
+    // cache (device)
+    void *store_k, *store_v;
+    int32_t *kept_idx;
+    float *rep_frame_k, *rep_frame_v, *rep_patch_k, *rep_patch_v, *rep_seg_k, *rep_seg_v;
+    int32_t *cnt_patch;
+    double *fsum_k, *fsum_v; // [max_frames][c_kv] exact sums of the kept scoring-layer rows
+    float *margin;
+    int32_t *refined;
+    // per-chunk scratch (device)
+    float *att_part;  // [max_chunk_frames][n_part][P]
+    float *fft_sig;   // [max_chunk_frames][P]
+    double *att64;    // [max_chunk_frames][Hq][P] partial fp64 attention of re-scored frames
+    double *fft64;    // [max_chunk_frames][P]
+    int32_t *src_tok; // [max_chunk_frames*kappa] chunk-local token of every kept row
+    // retrieval scratch (device)
+    double *qbar;    // [max_questions][c_kv]  group-summed mean query
+    double *qq;      // [max_questions][Hkv]   partial squared norms of the mean query
+    double *s_frm;   // [max_questions][max_frames]
+    double *s_seg;   // [max_questions][max_segments]
+    float *seg_tail; // [2][c_kv] key (K, V) of a segment cut by the question's timestamp
+};
+
+// ---- launchers (defined in the .hip files; all enqueue on `st`, never sync) ----
+struct ChunkArgs {
+    const void *k, *v, *q;
+    const float *att_in;
+    int64_t kv_sl, kv_sh, kv_st; // element strides layer / head / token
+    int64_t q_sh, q_st;
+    int n_frames;
+    int64_t frame0;
+    mukv_signals_out sig;
+};
+
+hipError_t launch_compress(Ctx &c, const ChunkArgs &a, hipStream_t st);
+
+struct RetrieveArgs {
+    const void *q_tokens;
+    const int32_t *q_offsets;
+    int B;
+    mukv_retrieve_params p;
+    int nv;      // visible frames
+    int ns;      // visible segments
+    int32_t *seg_idx;
+    float *seg_score;
+    int32_t *frm_idx;
+    float *frm_score;
+};
+
+hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st);
+
+hipError_t launch_gather(Ctx &c, const int32_t *frame_idx, int B, int k_frame, int order, void *k_out,
+                         void *v_out, int32_t *n_tokens_out, hipStream_t st);
+
+// LDS bytes the generic attention kernel needs for P tokens of D features when it accumulates
+// in a type of r_size bytes.
+size_t att_generic_lds_bytes(int P, int D, size_t r_size);
+
+// ---- small device helpers ----
+__device__ __forceinline__ float to_float(uint16_t bits) { return __uint_as_float((uint32_t)bits << 16); }
+__device__ __forceinline__ float to_float(float x) { return x; }
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+__device__ __forceinline__ double wave_max(double x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = fmax(x, __shfl_xor(x, o));
+    return x;
+}
+
+} // namespace mukv

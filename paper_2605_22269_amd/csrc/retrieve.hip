@@ -1,0 +1,550 @@
+// Online half of MuKV (Sec. 3.4-3.5 of the paper): question pooling, cosine scoring of the
+// block keys, two-stage semi-hierarchical selection, and the gather of the selected KV.
+//
+// Kernel chain of launch_retrieve:
+//   pool_question   Eq. 6   mean query per question, summed over each KV head's query group
+//   score_blocks    Eq. 7   cosine of every visible frame / segment key with every question
+//   select_rerank   stage-1 top-2k, global query, Eq. 8, final top-k   (one workgroup / question)
+// launch_gather: gather_kv  copies the kept rows of the selected frames into the decode context.
+//
+// All scores are evaluated in fp64 from the float32 key tables, so that the selections agree
+// with an fp64 evaluation of the same definitions except for ties closer than ~1e-15.
+#include "mukv_internal.h"
+
+namespace mukv {
+
+constexpr int kSelThreads = 512;
+
+// ------------------------------------------------------------------------------------------
+// Eq. 6.  grid (B, Hkv).  Each workgroup averages the question's tokens for the G query heads
+// of one KV head, then sums those heads: with keys repeated G times over their group (grouped
+// query attention), q . expand(r) = sum_g (sum_{h in g} q_h) . r_g.  Also the group's share of
+// |q|^2.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void pool_question_kernel(const T *__restrict__ q_tokens,
+                                                            const int32_t *__restrict__ q_off, int Hq, int Hkv, int D,
+                                                            int G, double *__restrict__ qbar,
+                                                            double *__restrict__ qq) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    double *qm = reinterpret_cast<double *>(smem_raw); // [G*D]
+    __shared__ double red[4];
+    const int b = blockIdx.x, g = blockIdx.y, tid = threadIdx.x;
+    const int t0 = q_off[b], t1 = q_off[b + 1];
+    const int nq = t1 - t0;
+    double sq = 0.0;
+    for (int e = tid; e < G * D; e += 256) {
+        const T *p = q_tokens + ((int64_t)t0 * Hq + (int64_t)g * G) * D + e;
+        double s = 0.0;
+        for (int t = 0; t < nq; ++t) s += (double)to_float(p[(int64_t)t * Hq * D]);
+        const double m = nq > 0 ? s / (double)nq : 0.0;
+        qm[e] = m;
+        sq += m * m;
+    }
+    sq = wave_sum(sq);
+    if ((tid & 63) == 0) red[tid >> 6] = sq;
+    __syncthreads();
+    if (tid == 0) qq[(int64_t)b * Hkv + g] = ((red[0] + red[1]) + red[2]) + red[3];
+    for (int d = tid; d < D; d += 256) {
+        double s = 0.0;
+        for (int hl = 0; hl < G; ++hl) s += qm[hl * D + d];
+        qbar[((int64_t)b * Hkv + g) * D + d] = s;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Eq. 7.  One wave per block key (frames first, then segments).  The key row stays in
+// registers while the wave loops over the questions.  cos(q, expand(r)) =
+// (qbar . r) / (|q| * sqrt(G) * |r|); a zero key or zero query scores 0.
+// A segment cut by the question's timestamp (only the last visible one can be) gets its key
+// from the exact per-frame sums of its visible frames; that key is also left in seg_tail for
+// the rerank kernel.
+// ------------------------------------------------------------------------------------------
+struct ScoreArgs {
+    const float *rep_frame, *rep_seg;
+    const double *fsum;
+    const double *qbar, *qq;
+    double *s_frm, *s_seg;
+    float *seg_tail;
+    int nv, ns, B, C, Hkv, G, F, kappa;
+    int tail_cut; // 1: segment ns-1 must be rebuilt from frames [ (ns-1)*F, nv )
+    int64_t ld_frm, ld_seg;
+};
+
+__global__ __launch_bounds__(256) void score_blocks_kernel(ScoreArgs a) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = blockIdx.x * 4 + wave;
+    if (r >= a.nv + a.ns) return;
+    const bool is_seg = r >= a.nv;
+    const int idx = is_seg ? r - a.nv : r;
+    const int C = a.C;
+    float row[16];
+    if (is_seg && a.tail_cut && idx == a.ns - 1) {
+        const int f0 = idx * a.F;
+        const double den = (double)(a.nv - f0) * (double)a.kappa;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const int c = lane + 64 * t;
+            row[t] = 0.f;
+            if (c < C) {
+                double s = 0.0;
+                for (int f = f0; f < a.nv; ++f) s += a.fsum[(int64_t)f * C + c];
+                row[t] = (float)(s / den);
+                a.seg_tail[c] = row[t];
+            }
+        }
+    } else {
+        const float *src = (is_seg ? a.rep_seg : a.rep_frame) + (int64_t)idx * C;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const int c = lane + 64 * t;
+            row[t] = (c < C) ? src[c] : 0.f;
+        }
+    }
+    double rr = 0.0;
+#pragma unroll
+    for (int t = 0; t < 16; ++t) rr += (double)row[t] * (double)row[t];
+    rr = wave_sum(rr);
+    for (int b = 0; b < a.B; ++b) {
+        const double *qb = a.qbar + (int64_t)b * C;
+        double dot = 0.0;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const int c = lane + 64 * t;
+            if (c < C) dot += (double)row[t] * qb[c];
+        }
+        dot = wave_sum(dot);
+        if (lane == 0) {
+            double qn = 0.0;
+            for (int g = 0; g < a.Hkv; ++g) qn += a.qq[(int64_t)b * a.Hkv + g];
+            double s = 0.0;
+            if (rr > 0.0 && qn > 0.0) s = dot / (sqrt(qn) * sqrt((double)a.G * rr));
+            if (is_seg)
+                a.s_seg[(int64_t)b * a.ld_seg + idx] = s;
+            else
+                a.s_frm[(int64_t)b * a.ld_frm + idx] = s;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Selection helpers.  Scores map to 64-bit keys whose unsigned order is "better first"
+// (descending score); ~0 marks an entry that may not be chosen.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t desc_key(double s) {
+    if (s == 0.0) s = 0.0; // -0 and +0 are the same score
+    const uint64_t u = (uint64_t)__double_as_longlong(s);
+    const uint64_t asc = (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+    return ~asc;
+}
+constexpr uint64_t kNoKey = ~0ull;
+
+struct SelShared {
+    unsigned hist[256];
+    uint64_t sel_key[kMaxCand];
+    int sel_idx[kMaxCand];
+    int wtot[kSelThreads / 64];
+    int count;
+    int need;
+    unsigned digit;
+};
+
+// Chooses the m best of entries 0..n-1 (smallest key; equal keys: lowest entry number) and
+// writes their entry numbers to out[0..m_eff) in rank order.  Returns m_eff = min(m, number of
+// entries whose key is not kNoKey).  All threads of the workgroup must call it.
+// Method: 8-bit radix select of the m-th key (8 passes of LDS histograms), one pass collecting
+// everything better than it, an ordered scan handing the remaining places to the first
+// entries equal to it, then a rank-by-counting sort of the <= kMaxCand survivors.
+template <typename KeyFn>
+__device__ int block_topk(KeyFn key, int n, int m, int *out, SelShared &sh) {
+    const int tid = threadIdx.x;
+    __syncthreads();
+    if (tid == 0) sh.count = 0;
+    __syncthreads();
+    int mine = 0;
+    for (int i = tid; i < n; i += kSelThreads) mine += key(i) != kNoKey;
+    if (mine) atomicAdd(&sh.count, mine);
+    __syncthreads();
+    const int m_eff = min(m, sh.count);
+    __syncthreads();
+    if (m_eff == 0) return 0;
+
+    uint64_t prefix = 0;
+    if (tid == 0) sh.need = m_eff;
+    for (int pb = 7; pb >= 0; --pb) {
+        for (int d = tid; d < 256; d += kSelThreads) sh.hist[d] = 0;
+        __syncthreads();
+        for (int i = tid; i < n; i += kSelThreads) {
+            const uint64_t k = key(i);
+            if (k == kNoKey) continue;
+            const bool match = (pb == 7) || ((k >> (8 * (pb + 1))) == prefix);
+            if (match) atomicAdd(&sh.hist[(unsigned)(k >> (8 * pb)) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int need = sh.need, cum = 0;
+            unsigned d = 0;
+            for (; d < 256; ++d) {
+                const int h = (int)sh.hist[d];
+                if (cum + h >= need) break;
+                cum += h;
+            }
+            sh.digit = d;
+            sh.need = need - cum;
+        }
+        __syncthreads();
+        prefix = (prefix << 8) | sh.digit;
+    }
+    const uint64_t thr = prefix;      // the m_eff-th best key
+    const int n_equal = sh.need;      // how many entries equal to it are still wanted (>= 1)
+    const int n_less = m_eff - n_equal;
+    __syncthreads();
+    if (tid == 0) sh.count = 0;
+    __syncthreads();
+    for (int i = tid; i < n; i += kSelThreads) {
+        const uint64_t k = key(i);
+        if (k < thr) {
+            const int pos = atomicAdd(&sh.count, 1);
+            sh.sel_key[pos] = k;
+            sh.sel_idx[pos] = i;
+        }
+    }
+    // entries equal to the threshold, in entry order
+    int running = 0;
+    const int lane = tid & 63, wave = tid >> 6;
+    for (int base = 0; base < n && running < n_equal; base += kSelThreads) {
+        const int i = base + tid;
+        const bool flag = i < n && key(i) == thr;
+        const uint64_t bal = __ballot(flag);
+        const int below = __popcll(bal & ((1ull << lane) - 1ull));
+        __syncthreads();
+        if (lane == 0) sh.wtot[wave] = __popcll(bal);
+        __syncthreads();
+        int before = 0, total = 0;
+        for (int w = 0; w < kSelThreads / 64; ++w) {
+            if (w < wave) before += sh.wtot[w];
+            total += sh.wtot[w];
+        }
+        const int ord = running + before + below;
+        if (flag && ord < n_equal) {
+            sh.sel_key[n_less + ord] = thr;
+            sh.sel_idx[n_less + ord] = i;
+        }
+        running += total;
+    }
+    __syncthreads();
+    // order the m_eff survivors by (key, entry)
+    int my_rank[kMaxCand / kSelThreads], my_idx[kMaxCand / kSelThreads];
+#pragma unroll
+    for (int s = 0; s < kMaxCand / kSelThreads; ++s) {
+        const int t = tid + s * kSelThreads;
+        my_rank[s] = -1;
+        if (t < m_eff) {
+            const uint64_t kt = sh.sel_key[t];
+            const int it = sh.sel_idx[t];
+            int rank = 0;
+            for (int u = 0; u < m_eff; ++u) {
+                const uint64_t ku = sh.sel_key[u];
+                rank += (ku < kt) || (ku == kt && sh.sel_idx[u] < it);
+            }
+            my_rank[s] = rank;
+            my_idx[s] = it;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < kMaxCand / kSelThreads; ++s)
+        if (my_rank[s] >= 0) out[my_rank[s]] = my_idx[s];
+    __syncthreads();
+    return m_eff;
+}
+
+// ------------------------------------------------------------------------------------------
+// Stage 1 / stage 2 of Sec. 3.4 for one question per workgroup.
+// ------------------------------------------------------------------------------------------
+struct RerankArgs {
+    const double *s_frm, *s_seg;
+    int64_t ld_frm, ld_seg;
+    const float *rep_frame, *rep_seg, *seg_tail;
+    int nv, ns, C, F, tail_cut;
+    int mode, k_seg, k_frame, n_global;
+    double lambda;
+    int32_t *seg_idx, *frm_idx;
+    float *seg_score, *frm_score;
+};
+
+constexpr int kMaxSegBitmapWords = 2048; // HIER mode: segments 0..65535
+
+__global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a) {
+    __shared__ SelShared sh;
+    __shared__ int cand_seg[kMaxCand];
+    __shared__ int cand_frm[kMaxCand];
+    __shared__ int order[kMaxCand];
+    __shared__ double st[kMaxCand];
+    __shared__ double gvec[1024];
+    __shared__ unsigned seg_ok[kMaxSegBitmapWords];
+    __shared__ double gg_sh;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const double *s_frm = a.s_frm + (int64_t)b * a.ld_frm;
+    const double *s_seg = a.s_seg + (int64_t)b * a.ld_seg;
+    int32_t *seg_out = a.seg_idx + (int64_t)b * a.k_seg;
+    int32_t *frm_out = a.frm_idx + (int64_t)b * a.k_frame;
+    float *seg_sc = a.seg_score ? a.seg_score + (int64_t)b * a.k_seg : nullptr;
+    float *frm_sc = a.frm_score ? a.frm_score + (int64_t)b * a.k_frame : nullptr;
+
+    auto seg_key = [&](int i) { return desc_key(s_seg[i]); };
+    auto frm_key = [&](int i) { return desc_key(s_frm[i]); };
+
+    if (a.mode != MUKV_SEMI) {
+        const int m_s = block_topk(seg_key, a.ns, a.k_seg, cand_seg, sh);
+        for (int r = tid; r < a.k_seg; r += kSelThreads) {
+            seg_out[r] = r < m_s ? cand_seg[r] : -1;
+            if (seg_sc) seg_sc[r] = r < m_s ? (float)s_seg[cand_seg[r]] : 0.f;
+        }
+        int m_f;
+        if (a.mode == MUKV_HIER) {
+            for (int w = tid; w < kMaxSegBitmapWords; w += kSelThreads) seg_ok[w] = 0u;
+            __syncthreads();
+            for (int r = tid; r < m_s; r += kSelThreads) atomicOr(&seg_ok[cand_seg[r] >> 5], 1u << (cand_seg[r] & 31));
+            __syncthreads();
+            auto hier_key = [&](int i) {
+                const int s = i / a.F;
+                return ((seg_ok[s >> 5] >> (s & 31)) & 1u) ? desc_key(s_frm[i]) : kNoKey;
+            };
+            m_f = block_topk(hier_key, a.nv, a.k_frame, cand_frm, sh);
+        } else {
+            m_f = block_topk(frm_key, a.nv, a.k_frame, cand_frm, sh);
+        }
+        for (int r = tid; r < a.k_frame; r += kSelThreads) {
+            frm_out[r] = r < m_f ? cand_frm[r] : -1;
+            if (frm_sc) frm_sc[r] = r < m_f ? (float)s_frm[cand_frm[r]] : 0.f;
+        }
+        return;
+    }
+
+    // ---- semi-hierarchical ----
+    const int m_s = block_topk(seg_key, a.ns, 2 * a.k_seg, cand_seg, sh);
+    for (int r = tid; r < a.k_seg; r += kSelThreads) { // lambda = 0 for segments: stage-1 order stands
+        seg_out[r] = r < m_s ? cand_seg[r] : -1;
+        if (seg_sc) seg_sc[r] = r < m_s ? (float)s_seg[cand_seg[r]] : 0.f;
+    }
+    const int m_f = block_topk(frm_key, a.nv, 2 * a.k_frame, order, sh);
+    // candidates in ascending frame order, so that equal reranked scores resolve to the lowest frame
+    for (int t = tid; t < m_f; t += kSelThreads) {
+        const int me = order[t];
+        int pos = 0;
+        for (int u = 0; u < m_f; ++u) pos += order[u] < me;
+        cand_frm[pos] = me;
+    }
+    // global query: mean of the first n_glob stage-1 segment keys
+    int n_glob = a.n_global > 0 ? a.n_global : a.k_seg;
+    n_glob = min(n_glob, m_s);
+    for (int c = tid; c < a.C; c += kSelThreads) {
+        double s = 0.0;
+        for (int r = 0; r < n_glob; ++r) {
+            const int sgi = cand_seg[r];
+            const float *rep = (a.tail_cut && sgi == a.ns - 1) ? a.seg_tail : a.rep_seg + (int64_t)sgi * a.C;
+            s += (double)rep[c];
+        }
+        gvec[c] = n_glob > 0 ? s / (double)n_glob : 0.0;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        double gg = 0.0;
+        for (int c = lane; c < a.C; c += 64) gg += gvec[c] * gvec[c];
+        gg = wave_sum(gg);
+        if (lane == 0) gg_sh = gg;
+    }
+    __syncthreads();
+    const double gg = gg_sh;
+    for (int t = wave; t < m_f; t += kSelThreads / 64) {
+        const int fr = cand_frm[t];
+        const float *rep = a.rep_frame + (int64_t)fr * a.C;
+        double dot = 0.0, rr = 0.0;
+        for (int c = lane; c < a.C; c += 64) {
+            const double x = (double)rep[c];
+            dot += x * gvec[c];
+            rr += x * x;
+        }
+        dot = wave_sum(dot);
+        rr = wave_sum(rr);
+        if (lane == 0) {
+            const double gamma = (rr > 0.0 && gg > 0.0) ? dot / (sqrt(rr) * sqrt(gg)) : 0.0;
+            st[t] = (1.0 - a.lambda) * s_frm[fr] + a.lambda * gamma; // Eq. 8
+        }
+    }
+    __syncthreads();
+    auto st_key = [&](int i) { return desc_key(st[i]); };
+    const int m_o = block_topk(st_key, m_f, a.k_frame, order, sh);
+    for (int r = tid; r < a.k_frame; r += kSelThreads) {
+        frm_out[r] = r < m_o ? cand_frm[order[r]] : -1;
+        if (frm_sc) frm_sc[r] = r < m_o ? (float)st[order[r]] : 0.f;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Gather (Sec. 3.5): grid (x, slab = (layer, K|V, KV head), question).  Every workgroup first
+// turns the question's frame list into slot -> frame (ascending frame number for TEMPORAL,
+// list order for AS_GIVEN; -1 and out-of-range entries dropped), then moves its share of the
+// slab: slot s of the output is the dense run of kappa rows of frame slot_frame[s] in the
+// store.  Slots past the last selected frame are zero-filled.
+// ------------------------------------------------------------------------------------------
+struct GatherArgs {
+    const int32_t *frame_idx;
+    int k_frame, order;
+    const unsigned char *store_k, *store_v;
+    unsigned char *k_out, *v_out;
+    int32_t *n_tokens_out;
+    int64_t slab_b;       // bytes of one (layer, head) slab of the store
+    int64_t frame_b;      // bytes of one frame's kept rows in a slab (kappa*D*esz)
+    int units_per_frame;  // frame_b / 16
+    int L, Hkv, kappa;
+    int64_t n_frames;
+};
+
+template <int ITER>
+__global__ __launch_bounds__(256) void gather_kv_kernel(GatherArgs a) {
+    __shared__ int slot_frame[kMaxGatherK];
+    __shared__ int n_valid_sh;
+    const int tid = threadIdx.x, b = blockIdx.z, y = blockIdx.y;
+    const int32_t *idx = a.frame_idx + (int64_t)b * a.k_frame;
+    if (tid == 0) n_valid_sh = 0;
+    for (int t = tid; t < a.k_frame; t += 256) slot_frame[t] = -1;
+    __syncthreads();
+    int cnt = 0;
+    for (int t = tid; t < a.k_frame; t += 256) {
+        const int me = idx[t];
+        if (me < 0 || me >= a.n_frames) continue;
+        int pos = 0;
+        for (int u = 0; u < a.k_frame; ++u) {
+            const int o = idx[u];
+            if (o < 0 || o >= a.n_frames) continue;
+            pos += (a.order == MUKV_TEMPORAL) ? (o < me || (o == me && u < t)) : (u < t);
+        }
+        slot_frame[pos] = me;
+        ++cnt;
+    }
+    if (cnt) atomicAdd(&n_valid_sh, cnt);
+    __syncthreads();
+    const int n_valid = n_valid_sh;
+    if (a.n_tokens_out && blockIdx.x == 0 && y == 0 && tid == 0) a.n_tokens_out[b] = n_valid * a.kappa;
+
+    const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
+    const int kv = rem / a.Hkv, g = rem - kv * a.Hkv;
+    const unsigned char *src = (kv ? a.store_v : a.store_k) + ((int64_t)l * a.Hkv + g) * a.slab_b;
+    unsigned char *dst = (kv ? a.v_out : a.k_out) + (((int64_t)b * a.L + l) * a.Hkv + g) * (a.k_frame * a.frame_b);
+    const int n_units = a.k_frame * a.units_per_frame;
+    uint4 tmp[ITER];
+    const int u0 = blockIdx.x * (256 * ITER) + tid;
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        const int u = u0 + it * 256;
+        tmp[it] = make_uint4(0u, 0u, 0u, 0u);
+        if (u < n_units) {
+            const int slot = u / a.units_per_frame, part = u - slot * a.units_per_frame;
+            const int fr = slot_frame[slot];
+            if (fr >= 0) tmp[it] = *reinterpret_cast<const uint4 *>(src + (int64_t)fr * a.frame_b + (int64_t)part * 16);
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        const int u = u0 + it * 256;
+        if (u < n_units) *reinterpret_cast<uint4 *>(dst + (int64_t)u * 16) = tmp[it];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------
+hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
+    const int Hq = c.cfg.n_q_heads, Hkv = c.cfg.n_kv_heads, D = c.cfg.head_dim, G = c.group;
+    const size_t lds = (size_t)G * D * sizeof(double);
+    if (c.cfg.dtype == MUKV_BF16)
+        hipLaunchKernelGGL((pool_question_kernel<uint16_t>), dim3(a.B, Hkv), dim3(256), lds, st,
+                           reinterpret_cast<const uint16_t *>(a.q_tokens), a.q_offsets, Hq, Hkv, D, G, c.qbar, c.qq);
+    else
+        hipLaunchKernelGGL((pool_question_kernel<float>), dim3(a.B, Hkv), dim3(256), lds, st,
+                           reinterpret_cast<const float *>(a.q_tokens), a.q_offsets, Hq, Hkv, D, G, c.qbar, c.qq);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    const int F = c.cfg.frames_per_segment;
+    const int64_t seg_end = (int64_t)a.ns * F < c.n_frames ? (int64_t)a.ns * F : c.n_frames;
+    const int tail_cut = (a.ns > 0 && a.nv < seg_end) ? 1 : 0;
+    if (a.nv + a.ns > 0) {
+        ScoreArgs s;
+        s.rep_frame = c.rep_frame_k;
+        s.rep_seg = c.rep_seg_k;
+        s.fsum = c.fsum_k;
+        s.qbar = c.qbar;
+        s.qq = c.qq;
+        s.s_frm = c.s_frm;
+        s.s_seg = c.s_seg;
+        s.seg_tail = c.seg_tail;
+        s.nv = a.nv;
+        s.ns = a.ns;
+        s.B = a.B;
+        s.C = c.c_kv;
+        s.Hkv = Hkv;
+        s.G = G;
+        s.F = F;
+        s.kappa = c.kappa;
+        s.tail_cut = tail_cut;
+        s.ld_frm = c.cfg.max_frames;
+        s.ld_seg = c.max_segments;
+        hipLaunchKernelGGL(score_blocks_kernel, dim3((a.nv + a.ns + 3) / 4), dim3(256), 0, st, s);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    RerankArgs r;
+    r.s_frm = c.s_frm;
+    r.s_seg = c.s_seg;
+    r.ld_frm = c.cfg.max_frames;
+    r.ld_seg = c.max_segments;
+    r.rep_frame = c.rep_frame_k;
+    r.rep_seg = c.rep_seg_k;
+    r.seg_tail = c.seg_tail;
+    r.nv = a.nv;
+    r.ns = a.ns;
+    r.C = c.c_kv;
+    r.F = F;
+    r.tail_cut = tail_cut;
+    r.mode = a.p.mode;
+    r.k_seg = a.p.k_seg;
+    r.k_frame = a.p.k_frame;
+    r.n_global = a.p.n_global;
+    r.lambda = a.p.lambda_frame;
+    r.seg_idx = a.seg_idx;
+    r.frm_idx = a.frm_idx;
+    r.seg_score = a.seg_score;
+    r.frm_score = a.frm_score;
+    hipLaunchKernelGGL(select_rerank_kernel, dim3(a.B), dim3(kSelThreads), 0, st, r);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather(Ctx &c, const int32_t *frame_idx, int B, int k_frame, int order, void *k_out, void *v_out,
+                         int32_t *n_tokens_out, hipStream_t st) {
+    GatherArgs g;
+    const int row_b = c.cfg.head_dim * c.esz;
+    g.frame_idx = frame_idx;
+    g.k_frame = k_frame;
+    g.order = order;
+    g.store_k = reinterpret_cast<const unsigned char *>(c.store_k);
+    g.store_v = reinterpret_cast<const unsigned char *>(c.store_v);
+    g.k_out = reinterpret_cast<unsigned char *>(k_out);
+    g.v_out = reinterpret_cast<unsigned char *>(v_out);
+    g.n_tokens_out = n_tokens_out;
+    g.slab_b = c.store_cap * row_b;
+    g.frame_b = (int64_t)c.kappa * row_b;
+    g.units_per_frame = (int)(g.frame_b / 16);
+    g.L = c.cfg.n_layers;
+    g.Hkv = c.cfg.n_kv_heads;
+    g.kappa = c.kappa;
+    g.n_frames = c.n_frames;
+    constexpr int ITER = 4;
+    const int n_units = k_frame * g.units_per_frame;
+    const int gx = (n_units + 256 * ITER - 1) / (256 * ITER);
+    hipLaunchKernelGGL((gather_kv_kernel<ITER>), dim3(gx, c.cfg.n_layers * 2 * c.cfg.n_kv_heads, B), dim3(256), 0, st, g);
+    return hipGetLastError();
+}
+
+} // namespace mukv

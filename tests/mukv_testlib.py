@@ -1,0 +1,137 @@
+"""Shared helpers of the GPU parity tests: run the same seeded stream through the
+HIP library (via the C ABI binding) and through the CPU oracle, and compare."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import oracle as orc
+from paper_2605_22269_amd import binding as mk
+from paper_2605_22269_amd import synth
+
+# max-abs-error bars of the build's target: bf16 payloads 2e-2, fp32 payloads 1e-5
+TOL = {"bf16": 2e-2, "f32": 1e-5}
+
+
+def oracle_config(w: synth.Workload, **kw) -> orc.OracleConfig:
+    base = dict(n_layers=w.n_layers, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                tokens_per_frame=w.tokens_per_frame, frames_per_segment=w.frames_per_segment,
+                superpatches_per_frame=w.superpatches_per_frame, keep_ratio=w.keep_ratio, alpha=w.alpha,
+                causal=True, score_layer=-1)
+    base.update(kw)
+    return orc.OracleConfig(**base)
+
+
+def gpu_context(w: synth.Workload, max_frames=None, max_chunk_frames=None, max_questions=None, **kw) -> mk.MuKV:
+    base = dict(n_layers=w.n_layers, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                tokens_per_frame=w.tokens_per_frame, frames_per_segment=w.frames_per_segment,
+                superpatches_per_frame=w.superpatches_per_frame, dtype=w.torch_dtype, keep_ratio=w.keep_ratio,
+                alpha=w.alpha, causal=True, max_frames=max_frames or w.n_frames,
+                max_chunk_frames=max_chunk_frames or w.chunk_frames, max_questions=max_questions or w.n_questions)
+    base.update(kw)
+    return mk.MuKV(**base)
+
+
+def np_view(t):
+    return synth.as_numpy(t)
+
+
+def to_f64(a):
+    """numpy payload (uint16 bf16 bits or float32) -> float64 values"""
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+class Pair:
+    """One stream through both implementations."""
+
+    def __init__(self, w: synth.Workload, seed=0, chunk=None, with_q=True, gpu_kw=None, orc_kw=None, frames=None):
+        self.w = w
+        self.chunk = chunk or w.chunk_frames
+        self.n = frames or w.n_frames
+        self.gpu = gpu_context(w, max_frames=self.n, max_chunk_frames=self.chunk, **(gpu_kw or {}))
+        self.orc = orc.OracleMuKV(oracle_config(w, **(orc_kw or {})))
+        self.stream = synth.SynthStream(w, seed, device="cpu", with_q=with_q)
+        self.sig_gpu, self.sig_orc = [], []
+
+    def ingest(self, n_frames=None, att_from_oracle=False):
+        """Feeds the next n_frames (default: all remaining) in chunks to both sides."""
+        todo = self.n - self.orc.n_frames if n_frames is None else n_frames
+        while todo > 0:
+            n = min(self.chunk, todo)
+            k, v, q = self.stream.next_chunk(n)
+            kn, vn, qn = np_view(k), np_view(v), (np_view(q) if q is not None else None)
+            att_np = att_t = None
+            if att_from_oracle:
+                att_np = orc.att_signal(qn, kn[self.orc.ls], n, self.w.tokens_per_frame, self.orc.cfg.causal)
+                att_np = att_np.astype(np.float32)
+                att_t = torch.from_numpy(att_np).cuda()
+                self.sig_orc.append(self.orc.compress_chunk(kn, vn, att=att_np.astype(np.float64)))
+                self.sig_gpu.append(self.gpu.compress_chunk(k.cuda(), v.cuda(), att_signal=att_t, want_signals=True))
+            else:
+                self.sig_orc.append(self.orc.compress_chunk(kn, vn, q_last=qn))
+                self.sig_gpu.append(self.gpu.compress_chunk(k.cuda(), v.cuda(), q.cuda() if q is not None else None,
+                                                            want_signals=True))
+            torch.cuda.synchronize()
+            todo -= n
+
+    # ---- comparisons -----------------------------------------------------------------
+    def check_compress(self, exact_reps=True):
+        w, tol = self.w, TOL[self.w.dtype]
+        alpha = self.orc.cfg.alpha
+        for so, sg in zip(self.sig_orc, self.sig_gpu):
+            if alpha != 0.0:
+                assert np.abs(sg["att"].cpu().numpy() - so["att"]).max() <= tol
+            if alpha != 1.0:
+                assert np.abs(sg["fft"].cpu().numpy() - so["fft"]).max() <= tol
+            assert np.abs(sg["fused"].cpu().numpy() - so["fused"]).max() <= tol
+        st = self.gpu.state()
+        torch.cuda.synchronize()
+        assert st["n_frames"] == self.orc.n_frames
+        np.testing.assert_array_equal(st["kept_idx"].cpu().numpy(), self.orc.kept)       # bit-exact indices
+        n, kap = self.orc.n_frames, self.orc.kappa
+        gk, gv = self.gpu.store_rows(0, n * kap)
+        ok, ov = self.orc.store()
+        np.testing.assert_array_equal(np_view(gk), ok)                                    # byte copy
+        np.testing.assert_array_equal(np_view(gv), ov)
+        F = w.frames_per_segment
+        pairs = [("rep_frame_k", self.orc.rep_frame_k), ("rep_frame_v", self.orc.rep_frame_v),
+                 ("rep_patch_k", self.orc.rep_patch_k), ("rep_patch_v", self.orc.rep_patch_v),
+                 ("rep_seg_k", self.orc.seg_reps(which="k")), ("rep_seg_v", self.orc.seg_reps(which="v"))]
+        for name, want in pairs:
+            got = st[name].cpu().numpy()
+            assert got.shape == want.shape, name
+            assert np.abs(got - want).max() <= tol, name
+            if exact_reps:  # fp64 sums of the payload are exact, so the float32 tables agree to the bit
+                np.testing.assert_array_equal(got, want.astype(np.float32), err_msg=name)
+        np.testing.assert_array_equal(st["cnt_patch"].cpu().numpy(), self.orc.cnt_patch)
+        assert st["n_segments"] == (n + F - 1) // F
+        return st
+
+    def check_retrieve(self, questions, mode, k_seg, k_frame, lambda_frame=0.3, n_visible=-1, n_global=0):
+        """questions: list of torch tensors [Nq][Hq][D] (cpu)."""
+        tol = TOL[self.w.dtype]
+        offs = np.zeros(len(questions) + 1, np.int32)
+        offs[1:] = np.cumsum([q.shape[0] for q in questions])
+        qt = torch.cat(questions).cuda().contiguous()
+        out = self.gpu.retrieve(qt, torch.from_numpy(offs).cuda(), mode=mode, k_seg=k_seg, k_frame=k_frame,
+                                lambda_frame=lambda_frame, n_visible_frames=n_visible, n_global=n_global)
+        kg, vg, ntok = self.gpu.gather_kv(out["frame_idx"])
+        torch.cuda.synchronize()
+        res = []
+        for b, q in enumerate(questions):
+            r = self.orc.retrieve(np_view(q), orc.RetrieveParams(mode, k_seg, k_frame, lambda_frame, n_global, n_visible))
+            np.testing.assert_array_equal(out["seg_idx"][b].cpu().numpy(), r["seg_idx"])
+            np.testing.assert_array_equal(out["frame_idx"][b].cpu().numpy(), r["frame_idx"])
+            assert np.abs(out["seg_score"][b].cpu().numpy() - r["seg_score"]).max() <= min(tol, 1e-5)
+            assert np.abs(out["frame_score"][b].cpu().numpy() - r["frame_score"]).max() <= min(tol, 1e-5)
+            ko, vo, n_tok = self.orc.gather(r["frame_idx"])
+            assert int(ntok[b]) == n_tok
+            np.testing.assert_array_equal(np_view(kg[b]), ko)
+            np.testing.assert_array_equal(np_view(vg[b]), vo)
+            res.append(r)
+        return out, res
+
+    def close(self):
+        self.gpu.close()

@@ -1,0 +1,224 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the
+same seeded inputs -- kept / retrieved indices bit-exact, copied bytes exact,
+float outputs within 1e-5 (fp32 payload) / 2e-2 (bf16 payload)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2605_22269_amd import binding as mk
+from paper_2605_22269_amd import synth
+from mukv_testlib import Pair, np_view
+
+pytestmark = pytest.mark.gpu
+
+W = synth.WORKLOADS
+
+
+def questions_for(w, lengths, seed):
+    return [synth.random_question(w, n, seed + i) for i, n in enumerate(lengths)]
+
+
+# ------------------------------------------------------------------ config 1 (exactly) -----
+def test_tiny_config_end_to_end():
+    w = W["tiny"]
+    p = Pair(w, seed=11)
+    p.ingest()
+    st = p.check_compress()
+    qs = questions_for(w, [w.question_tokens], 100)
+    for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
+        p.check_retrieve(qs, mode, w.k_seg, w.k_frame, w.lambda_frame)
+    print("tiny: refined frames", int(st["refined"].sum()), "min margin", float(st["margin"].min()))
+    p.close()
+
+
+# ---------------------------------------- 7B shape, short stream (several chunks, ragged) ----
+def test_7b_shape_short_stream():
+    w = W["7b"].scaled(n_frames=21, n_questions=2)   # 8 + 8 + 5 frames; segments 16 + 5
+    p = Pair(w, seed=5)
+    p.ingest()
+    st = p.check_compress()
+    p.check_retrieve(questions_for(w, [32, 17], 200), mk.MUKV_SEMI, 2, 8, 0.3)
+    print("7b: refined frames", int(st["refined"].sum()), "min margin", float(st["margin"].min()))
+    p.close()
+
+
+def test_7b_shape_retrieval_modes():
+    w = W["7b"].scaled(n_frames=40, n_layers=2, n_questions=3)
+    p = Pair(w, seed=6)
+    p.ingest()
+    p.check_compress()
+    qs = questions_for(w, [32, 16, 64], 300)
+    for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
+        p.check_retrieve(qs, mode, 2, 6, 0.3)
+    p.check_retrieve(qs, mk.MUKV_SEMI, 2, 6, 0.0)
+    p.check_retrieve(qs, mk.MUKV_SEMI, 2, 6, 0.7, n_global=1)
+    # timestamp before the end of the stream, cutting segment 1 (frames 16..31) after frame 20
+    p.check_retrieve(qs, mk.MUKV_SEMI, 2, 6, 0.3, n_visible=21)
+    p.check_retrieve(qs, mk.MUKV_HIER, 1, 4, 0.3, n_visible=21)
+    # more blocks asked for than exist
+    p.check_retrieve(qs, mk.MUKV_SEMI, 5, 48, 0.3)
+    p.check_retrieve(qs, mk.MUKV_PARALLEL, 5, 48, 0.3, n_visible=3)
+    p.close()
+
+
+# ------------------------------------------------------ 72B shape, short stream -----------
+def test_72b_shape_short_stream():
+    w = W["72b"].scaled(n_frames=40, n_layers=3)   # kappa 8 of 64; one full 32-frame segment + 8
+    p = Pair(w, seed=7)
+    p.ingest()
+    p.check_compress()
+    qs = questions_for(w, [32], 400)
+    for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
+        p.check_retrieve(qs, mode, 2, 8, 0.3)
+    p.close()
+
+
+# ------------------------------------------------------------------------ edge cases ------
+@pytest.mark.parametrize("alpha", [0.0, 1.0, 0.5])
+@pytest.mark.parametrize("causal", [True, False])
+def test_signal_mixes_and_masks(alpha, causal):
+    w = W["tiny"].scaled(n_frames=10, alpha=alpha, n_layers=2, n_kv_heads=2)
+    p = Pair(w, seed=21, chunk=4, gpu_kw={"causal": causal}, orc_kw={"causal": causal})
+    p.ingest()
+    p.check_compress()
+    p.close()
+
+
+def test_attention_handed_over_by_the_caller():
+    w = W["tiny"].scaled(n_frames=9)
+    p = Pair(w, seed=22, chunk=4)
+    p.ingest(att_from_oracle=True)
+    p.check_compress()
+    p.close()
+
+
+def test_keep_ratio_one_is_identity():
+    w = W["tiny"].scaled(n_frames=6, keep_ratio=1.0, n_layers=2)
+    p = Pair(w, seed=23, chunk=3)
+    p.ingest()
+    st = p.check_compress()
+    P = w.tokens_per_frame
+    assert np.array_equal(st["kept_idx"].cpu().numpy(), np.tile(np.arange(P, dtype=np.int32), (6, 1)))
+    p.close()
+
+
+def test_chunking_invariance_bitwise():
+    w = W["7b"].scaled(n_frames=12, n_layers=2)
+    ref = None
+    for chunk in (12, 8, 5, 1):
+        p = Pair(w, seed=24, chunk=chunk)
+        p.ingest()
+        st = p.check_compress()
+        torch.cuda.synchronize()
+        cur = {k: st[k].cpu().numpy() for k in ("kept_idx", "rep_frame_k", "rep_seg_k", "rep_seg_v", "rep_patch_v")}
+        if ref is not None:
+            for k in cur:
+                np.testing.assert_array_equal(cur[k], ref[k], err_msg=f"{k} chunk={chunk}")
+        ref = ref or cur
+        p.close()
+
+
+def test_exact_ties_resolve_to_lowest_position():
+    # all keys zero and alpha = 0: every fused score is 0 -> the first kappa tokens
+    w = W["tiny"].scaled(n_frames=2, alpha=0.0)
+    g = Pair(w, seed=1, chunk=2).gpu
+    L, Hkv, P, D = w.n_layers, w.n_kv_heads, w.tokens_per_frame, w.head_dim
+    k = torch.zeros(L, Hkv, 2 * P, D, device="cuda")
+    v = torch.randn(L, Hkv, 2 * P, D, device="cuda")
+    g.compress_chunk(k, v)
+    st = g.state()
+    torch.cuda.synchronize()
+    assert np.array_equal(st["kept_idx"].cpu().numpy(), np.tile(np.arange(g.kappa, dtype=np.int32), (2, 1)))
+    g.close()
+    # duplicated tokens, non-causal: the copies tie exactly; oracle and GPU must agree
+    w = W["tiny"].scaled(n_frames=3, n_kv_heads=2, n_q_heads=4)
+    p = Pair(w, seed=2, chunk=3, gpu_kw={"causal": False}, orc_kw={"causal": False})
+    k, v, q = p.stream.next_chunk(3)
+    for a, b in ((3, 40), (7, 8), (20, 21), (0, 48)):
+        k[:, :, b::P] = k[:, :, a::P]
+    kn, vn, qn = np_view(k), np_view(v), np_view(q)
+    ro = p.orc.compress_chunk(kn, vn, q_last=qn)
+    p.gpu.compress_chunk(k.cuda(), v.cuda(), q.cuda())
+    st = p.gpu.state()
+    torch.cuda.synchronize()
+    assert np.array_equal(st["kept_idx"].cpu().numpy(), ro["kept"])
+    p.close()
+
+
+def test_strided_inputs_hf_layout():
+    # per-layer [1, Hkv, T_total, D] prefill tensors: a chunk is a slice along T, so the head
+    # stride exceeds n*P*D; layers sit in one big buffer here
+    w = W["tiny"].scaled(n_frames=8, n_layers=3, n_kv_heads=2)
+    p = Pair(w, seed=31, chunk=4)
+    P = w.tokens_per_frame
+    k, v, q = p.stream.next_chunk(8)
+    big_k, big_v, big_q = k.cuda(), v.cuda(), q.cuda()
+    for f0 in (0, 4):
+        sl = slice(f0 * P, (f0 + 4) * P)
+        p.sig_orc.append(p.orc.compress_chunk(np_view(k[:, :, sl]), np_view(v[:, :, sl]), q_last=np_view(q[:, sl])))
+        p.sig_gpu.append(p.gpu.compress_chunk(big_k[:, :, sl], big_v[:, :, sl], big_q[:, sl], want_signals=True))
+    p.check_compress()
+    p.close()
+
+
+def test_gather_orders_and_padding():
+    w = W["tiny"].scaled(n_frames=16, n_layers=2, n_questions=2)
+    p = Pair(w, seed=41)
+    p.ingest()
+    idx = torch.tensor([[9, 2, -1, 4, 15], [0, -1, -1, -1, -1]], dtype=torch.int32, device="cuda")
+    for order, oorder in ((mk.MUKV_TEMPORAL, orc.TEMPORAL), (mk.MUKV_AS_GIVEN, orc.AS_GIVEN)):
+        kg, vg, nt = p.gpu.gather_kv(idx, order)
+        torch.cuda.synchronize()
+        for b in range(2):
+            ko, vo, n = p.orc.gather(idx[b].cpu().numpy(), oorder)
+            assert int(nt[b]) == n
+            np.testing.assert_array_equal(np_view(kg[b]), ko)
+            np.testing.assert_array_equal(np_view(vg[b]), vo)
+    p.close()
+
+
+def test_determinism_bitwise():
+    w = W["7b"].scaled(n_frames=8, n_layers=2)
+    outs = []
+    for _ in range(2):
+        p = Pair(w, seed=51)
+        k, v, q = p.stream.next_chunk(8)
+        sg = p.gpu.compress_chunk(k.cuda(), v.cuda(), q.cuda(), want_signals=True)
+        st = p.gpu.state()
+        torch.cuda.synchronize()
+        outs.append((sg["fused"].cpu().numpy(), st["kept_idx"].cpu().numpy(), st["rep_seg_k"].cpu().numpy()))
+        p.close()
+    for a, b in zip(*outs):
+        np.testing.assert_array_equal(a, b)
+
+
+def test_capacity_and_argument_errors_on_device():
+    w = W["tiny"].scaled(n_frames=8)
+    g = Pair(w, seed=1, chunk=4).gpu
+    L, Hkv, P, D = w.n_layers, w.n_kv_heads, w.tokens_per_frame, w.head_dim
+    k = torch.zeros(L, Hkv, 5 * P, D, device="cuda")
+    q = torch.zeros(w.n_q_heads, 5 * P, D, device="cuda")
+    with pytest.raises(mk.MuKVError) as e:
+        g.compress_chunk(k, k, q)                       # 5 frames > max_chunk_frames
+    assert e.value.status == mk.MUKV_ERR_CAPACITY
+    with pytest.raises(mk.MuKVError) as e:
+        g.compress_chunk(k[:, :, : 4 * P], k[:, :, : 4 * P])  # alpha > 0 but no attention source
+    assert e.value.status == mk.MUKV_ERR_INVALID_ARG
+    k4, q4 = k[:, :, : 4 * P].contiguous(), q[:, : 4 * P].contiguous()
+    g.compress_chunk(k4, k4, q4)
+    g.compress_chunk(k4, k4, q4)
+    with pytest.raises(mk.MuKVError) as e:
+        g.compress_chunk(k4, k4, q4)                    # cache full
+    assert e.value.status == mk.MUKV_ERR_CAPACITY
+    assert g.n_frames == 8
+    qt = torch.zeros(4, w.n_q_heads, D, device="cuda")
+    offs = torch.tensor([0, 2, 4], dtype=torch.int32, device="cuda")
+    with pytest.raises(mk.MuKVError) as e:
+        g.retrieve(qt, offs, k_seg=1, k_frame=1)        # 2 questions > max_questions
+    assert e.value.status == mk.MUKV_ERR_CAPACITY
+    with pytest.raises(mk.MuKVError) as e:
+        g.retrieve(qt, offs[:2], k_seg=1, k_frame=600)
+    assert e.value.status == mk.MUKV_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    g.close()
