@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of the MuKV hot path on one MI355X.
+
+One step = one pass of the whole hot path over one synthetic stream that is
+already resident in HBM: mukv_compress_chunk for every chunk of the stream
+(attention + frequency signals, fusion, per-frame keep, all-layer KV compaction,
+block keys), then mukv_retrieve + mukv_gather_kv for the workload's questions.
+Prints ONE JSON line ("Measurement").
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload hour] [--chunk-frames 8]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="hour", choices=["tiny", "7b", "hour", "retrieval", "72b"])
+    ap.add_argument("--chunk-frames", type=int, default=0, help="frames per mukv_compress_chunk call (0: workload's)")
+    ap.add_argument("--frames", type=int, default=0, help="override the stream length (debugging)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-frames", type=int, default=64)
+    ap.add_argument("--seed", type=int, default=2605)
+    return ap.parse_args()
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU only (asked for --gpus {a.gpus}); "
+              "there is no multi-GPU path to measure.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2605_22269_amd import binding as mk
+    from paper_2605_22269_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda", 0)
+    w = synth.WORKLOADS[a.workload]
+    if a.frames:
+        w = w.scaled(n_frames=a.frames)
+    chunk = a.chunk_frames or w.chunk_frames
+    L, Hq, Hkv, D, P = w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.tokens_per_frame
+    n_frames = w.n_frames
+    n_chunks = (n_frames + chunk - 1) // chunk
+    B = w.n_questions
+    esz = w.elem_bytes
+
+    # ---- synthetic stream, resident in HBM before anything is timed ------------------------
+    t_gen = time.perf_counter()
+    stream = synth.SynthStream(w, a.seed, device=dev)
+    ks, vs, qs = [], [], []
+    K = torch.empty(n_chunks, L, Hkv, chunk * P, D, dtype=w.torch_dtype, device=dev)
+    V = torch.empty_like(K)
+    Q = torch.empty(n_chunks, Hq, chunk * P, D, dtype=w.torch_dtype, device=dev)
+    for c in range(n_chunks):
+        n = min(chunk, n_frames - c * chunk)
+        k, v, q = stream.next_chunk(n)
+        K[c, :, :, : n * P], V[c, :, :, : n * P], Q[c, :, : n * P] = k, v, q
+        ks.append(K[c, :, :, : n * P])
+        vs.append(V[c, :, :, : n * P])
+        qs.append(Q[c, :, : n * P])
+    del k, v, q
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    ctx = mk.MuKV(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, tokens_per_frame=P,
+                  frames_per_segment=w.frames_per_segment, superpatches_per_frame=w.superpatches_per_frame,
+                  dtype=w.torch_dtype, keep_ratio=w.keep_ratio, alpha=w.alpha, max_frames=n_frames,
+                  max_chunk_frames=chunk, max_questions=B)
+    kappa = ctx.kappa
+
+    # questions: random for the single-question workloads, planted targets for the batched one
+    if B == 1:
+        lens = [w.question_tokens]
+    else:
+        lens = synth.question_lengths(B, 16, w.question_tokens, a.seed + 1)
+    q_list = [synth.random_question(w, n, a.seed + 10 + i, device=dev) for i, n in enumerate(lens)]
+
+    def compress_all():
+        ctx.reset()
+        for c in range(n_chunks):
+            ctx.compress_chunk(ks[c], vs[c], qs[c])
+
+    if B > 1:  # plant 4 target frames per question, using the cache's own frame keys
+        compress_all()
+        reps = ctx.state()["rep_frame_k"]
+        g = torch.Generator().manual_seed(a.seed + 2)
+        q_list = []
+        for i, n in enumerate(lens):
+            tgt = torch.randint(0, n_frames, (4,), generator=g)
+            q_list.append(synth.planted_question(w, reps[tgt.to(dev)], n, a.seed + 10 + i, device=dev))
+    q_tokens = torch.cat(q_list).contiguous()
+    offs = torch.zeros(B + 1, dtype=torch.int32)
+    offs[1:] = torch.cumsum(torch.tensor(lens), 0)
+    offs = offs.to(dev)
+    r_out = {
+        "seg_idx": torch.empty(B, w.k_seg, dtype=torch.int32, device=dev),
+        "seg_score": torch.empty(B, w.k_seg, dtype=torch.float32, device=dev),
+        "frame_idx": torch.empty(B, w.k_frame, dtype=torch.int32, device=dev),
+        "frame_score": torch.empty(B, w.k_frame, dtype=torch.float32, device=dev),
+    }
+    g_shape = (B, L, Hkv, w.k_frame * kappa, D)
+    g_out = (torch.empty(g_shape, dtype=w.torch_dtype, device=dev), torch.empty(g_shape, dtype=w.torch_dtype, device=dev),
+             torch.empty(B, dtype=torch.int32, device=dev))
+
+    def retrieve_all():
+        ctx.retrieve(q_tokens, offs, mode=mk.MUKV_SEMI, k_seg=w.k_seg, k_frame=w.k_frame,
+                     lambda_frame=w.lambda_frame, out=r_out)
+        ctx.gather_kv(r_out["frame_idx"], out=g_out)
+
+    def step_eager():
+        compress_all()
+        retrieve_all()
+
+    # ---- launch mode: replay one HIP graph per step, or eager launches --------------------
+    step_eager()
+    torch.cuda.synchronize()
+    launch = "eager"
+    step = step_eager
+    if not a.no_graph:
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step_eager()
+            torch.cuda.synchronize()
+            step = graph.replay
+            launch = "hipgraph"
+        except Exception as e:  # capture not possible: stay eager, and say so
+            print(f"bench.py: graph capture failed ({e!r}); timing eager launches", file=sys.stderr)
+            torch.cuda.synchronize()
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
+    tokens = n_frames * P
+    value = tokens / (ms_per_step * 1e-3)
+
+    # ---- sub-phase timings with HIP events on the launch stream ---------------------------
+    def timed(fn, reps):
+        out = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            e1.synchronize()
+            out.append(e0.elapsed_time(e1))
+        return statistics.median(out)
+
+    compress_ms = timed(compress_all, 3)
+    retrieve_ms = timed(retrieve_all, 20)
+
+    # ---- per-kernel durations: the library brackets every launch with HIP events ----------
+    mk.mukv_profile_begin(ctx.h)
+    step_eager()
+    prof = mk.mukv_profile_end(ctx.h)
+    per_kernel = {n: (p["ms"] / p["launches"] * 1e3 if p["launches"] else None) for n, p in prof.items()}  # us
+
+    b_tok = 2 * Hkv * D * esz                      # K+V bytes of one token in one layer
+    compact_bytes = 2 * chunk * kappa * L * b_tok  # read + write of the kept rows of one chunk
+    compact_us = per_kernel["compact"]
+    compact_gbs = compact_bytes / (compact_us * 1e-6) / 1e9
+    gather_bytes = 2 * B * w.k_frame * kappa * L * b_tok
+    gather_us = per_kernel["gather"]
+    gather_gbs = gather_bytes / (gather_us * 1e-6) / 1e9
+    # whole-path algorithmic bytes: signals' inputs + kept rows in and out
+    path_bytes_chunk = chunk * P * D * esz * (Hq + Hkv) + compact_bytes
+    path_gbs = path_bytes_chunk * n_chunks / (compress_ms * 1e-3) / 1e9
+
+    res = {
+        "metric": "visual tokens compressed/s + retrieve latency per question (ms), % HBM peak",
+        "value": value,
+        "unit": "visual tokens/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: {n_frames} frames x {P} tokens, L={L} Hq={Hq} Hkv={Hkv} D={D} {w.dtype}, "
+                               f"chunks of {chunk} frames, F={w.frames_per_segment}, keep {kappa}/{P}, "
+                               f"{B} question(s), top-{w.k_seg} segments / top-{w.k_frame} frames",
+                   "launch": launch, "chunk_frames": chunk, "n_chunks": n_chunks},
+        "compress_ms_per_stream": compress_ms,
+        "compress_tokens_per_s": tokens / (compress_ms * 1e-3),
+        "retrieve_gather_ms_per_batch": retrieve_ms,
+        "retrieve_gather_ms_per_question": retrieve_ms / B,
+        "path_hbm": {"algorithmic_bytes_per_token": path_bytes_chunk / (chunk * P), "achieved_GBs": path_gbs,
+                     "frac_of_peak": path_gbs / HBM_PEAK_GBS},
+        "kernel_us": per_kernel,
+        "roofline": {"kernel": "compact_kernel", "bound": "hbm", "achieved": compact_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": compact_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": compact_bytes, "us_per_launch": compact_us},
+        "roofline_gather": {"kernel": "gather_kv_kernel", "bound": "hbm", "achieved": gather_gbs, "peak": HBM_PEAK_GBS,
+                            "unit": "GB/s", "frac": gather_gbs / HBM_PEAK_GBS, "traffic": None,
+                            "bytes_per_launch": gather_bytes, "us_per_launch": gather_us},
+        "setup_s": {"generate_stream": t_gen},
+    }
+
+    # ---- the oracle on the host cores, on a bounded sample of the same stream -------------
+    if not a.no_cpu_baseline:
+        from oracle import oracle as orc
+
+        n_s = min(a.cpu_sample_frames, n_frames)
+        n_sc = (n_s + chunk - 1) // chunk
+        ref = orc.OracleMuKV(orc.OracleConfig(L, Hq, Hkv, D, P, w.frames_per_segment, w.superpatches_per_frame,
+                                              w.keep_ratio, w.alpha))
+        host = [(synth.as_numpy(ks[c]), synth.as_numpy(vs[c]), synth.as_numpy(qs[c])) for c in range(n_sc)]
+        orc.lib()
+        t0 = time.perf_counter()
+        for kn, vn, qn in host:
+            ref.compress_chunk(kn, vn, q_last=qn)
+        t_cpu = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": ref.n_frames * P / t_cpu, "unit": "visual tokens/s",
+                               "cores": int(orc.lib().orc_num_threads()), "kind": "oracle",
+                               "sample": f"first {ref.n_frames} frames of the same stream through the oracle's "
+                                         f"compress_chunk ({t_cpu:.1f} s)"}
+    ctx.close()
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

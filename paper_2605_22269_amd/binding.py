@@ -60,8 +60,15 @@ class mukv_state(C.Structure):
     ]
 
 
+KERNEL_NAMES = ("att", "freq", "select", "refine", "compact", "poolq", "score", "rerank", "gather")
+
+
+class mukv_profile(C.Structure):
+    _fields_ = [("ms", C.c_double * len(KERNEL_NAMES)), ("launches", C.c_int64 * len(KERNEL_NAMES))]
+
+
 EXPORTS = ("mukv_create", "mukv_destroy", "mukv_reset", "mukv_compress_chunk", "mukv_retrieve",
-           "mukv_gather_kv", "mukv_get_state", "mukv_strerror")
+           "mukv_gather_kv", "mukv_profile_begin", "mukv_profile_end", "mukv_get_state", "mukv_strerror")
 
 _lib = None
 
@@ -84,6 +91,8 @@ def load():
     lib.mukv_retrieve.argtypes = [vp, vp, vp, i32, C.POINTER(mukv_retrieve_params), vp, vp, vp, vp, vp]
     lib.mukv_gather_kv.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.mukv_get_state.argtypes = [vp, C.POINTER(mukv_state)]
+    lib.mukv_profile_begin.argtypes = [vp]
+    lib.mukv_profile_end.argtypes = [vp, C.POINTER(mukv_profile)]
     lib.mukv_strerror.argtypes = [i32]
     lib.mukv_strerror.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -131,6 +140,16 @@ def mukv_retrieve(h, q_ptr, off_ptr, B, params, seg_idx, seg_score, frm_idx, frm
 
 def mukv_gather_kv(h, idx_ptr, B, k_frame, order, k_out, v_out, n_tok, stream):
     _check(load().mukv_gather_kv(h, idx_ptr, B, k_frame, order, k_out, v_out, n_tok, stream), "mukv_gather_kv")
+
+
+def mukv_profile_begin(h):
+    _check(load().mukv_profile_begin(h), "mukv_profile_begin")
+
+
+def mukv_profile_end(h) -> dict:
+    p = mukv_profile()
+    _check(load().mukv_profile_end(h, C.byref(p)), "mukv_profile_end")
+    return {n: {"ms": p.ms[i], "launches": p.launches[i]} for i, n in enumerate(KERNEL_NAMES)}
 
 
 def mukv_get_state(h) -> mukv_state:

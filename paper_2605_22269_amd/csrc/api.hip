@@ -107,6 +107,8 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     c.margin_thr = cfg->refine_margin < 0.0 ? kDefaultRefineMargin : cfg->refine_margin;
     c.n_frames = 0;
     c.store_cap = (int64_t)cfg->max_frames * c.kappa;
+    c.profiling = false;
+    c.prof = new (std::nothrow) std::vector<mukv::ProfEntry>();
 
     const size_t store_bytes = (size_t)cfg->n_layers * cfg->n_kv_heads * c.store_cap * cfg->head_dim * c.esz;
     const size_t MF = cfg->max_frames, C = c.c_kv, S = cfg->superpatches_per_frame, P = cfg->tokens_per_frame;
@@ -139,8 +141,9 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(dalloc(&c.s_frm, MQ * MF));
     ok(dalloc(&c.s_seg, MQ * (size_t)c.max_segments));
     ok(dalloc(&c.seg_tail, 2 * C));
-    if (e != hipSuccess) {
+    if (e != hipSuccess || !c.prof) {
         free_all(c);
+        delete c.prof;
         delete h;
         (void)hipGetLastError();
         return MUKV_ERR_HIP;
@@ -153,8 +156,40 @@ int mukv_destroy(mukv_ctx *ctx) {
     if (!ctx) return MUKV_OK;
     (void)hipSetDevice(ctx->c.cfg.device_id);
     free_all(ctx->c);
+    if (ctx->c.prof) {
+        for (auto &p : *ctx->c.prof) {
+            (void)hipEventDestroy(p.start);
+            (void)hipEventDestroy(p.stop);
+        }
+        delete ctx->c.prof;
+    }
     delete ctx;
     return MUKV_OK;
+}
+
+int mukv_profile_begin(mukv_ctx *ctx) {
+    if (!ctx) return MUKV_ERR_INVALID_ARG;
+    ctx->c.profiling = true;
+    return MUKV_OK;
+}
+
+int mukv_profile_end(mukv_ctx *ctx, mukv_profile *out) {
+    if (!ctx || !out) return MUKV_ERR_INVALID_ARG;
+    Ctx &c = ctx->c;
+    c.profiling = false;
+    std::memset(out, 0, sizeof(*out));
+    int rc = MUKV_OK;
+    for (auto &p : *c.prof) {
+        float ms = 0.f;
+        if (hipEventSynchronize(p.stop) != hipSuccess || hipEventElapsedTime(&ms, p.start, p.stop) != hipSuccess)
+            rc = MUKV_ERR_HIP;
+        out->ms[p.kid] += (double)ms;
+        out->launches[p.kid] += 1;
+        (void)hipEventDestroy(p.start);
+        (void)hipEventDestroy(p.stop);
+    }
+    c.prof->clear();
+    return rc;
 }
 
 int mukv_reset(mukv_ctx *ctx) {

@@ -555,16 +555,23 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
     const bool need_fft = c.cfg.alpha != 1.0;
     int n_part = c.cfg.n_q_heads;
     if (need_att) {
+        ProfScope ps(c, MUKV_K_ATT, st);
         if (c.use_mfma) {
             if ((e = launch_att_mfma(c, a, c.att_part, &n_part, st)) != hipSuccess) return e;
         } else {
             if ((e = launch_att_generic<T, float>(c, a, nullptr, c.att_part, st)) != hipSuccess) return e;
         }
     }
-    if (need_fft)
+    if (need_fft) {
+        ProfScope ps(c, MUKV_K_FREQ, st);
         if ((e = launch_freq<T, float>(c, a, nullptr, c.fft_sig, st)) != hipSuccess) return e;
-    if ((e = launch_select<T, float>(c, a, c.att_part, n_part, c.fft_sig, 0, st)) != hipSuccess) return e;
+    }
+    {
+        ProfScope ps(c, MUKV_K_SELECT, st);
+        if ((e = launch_select<T, float>(c, a, c.att_part, n_part, c.fft_sig, 0, st)) != hipSuccess) return e;
+    }
     if (c.margin_thr > 0.0) {
+        ProfScope ps(c, MUKV_K_REFINE, st);
         // frames with a near-tie at the keep boundary: redo Eq. 1-4 in fp64 and select again
         if (need_att)
             if ((e = launch_att_generic<T, double>(c, a, c.refined, c.att64, st)) != hipSuccess) return e;
@@ -572,6 +579,7 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
             if ((e = launch_freq<T, double>(c, a, c.refined, c.fft64, st)) != hipSuccess) return e;
         if ((e = launch_select<T, double>(c, a, c.att64, c.cfg.n_q_heads, c.fft64, 1, st)) != hipSuccess) return e;
     }
+    ProfScope ps(c, MUKV_K_COMPACT, st);
     return launch_compact(c, a, st);
 }
 

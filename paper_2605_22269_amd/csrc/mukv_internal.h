@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "mukv.h"
 
 namespace mukv {
@@ -14,8 +16,15 @@ constexpr int kMaxP = 256;        // tokens per frame the per-frame kernels are 
 constexpr int kMaxCand = 1024;    // stage-1 candidates (2*k) held in LDS by the rerank kernel
 constexpr int kMaxGatherK = 1024; // selected frames per question the gather kernel can plan
 
+struct ProfEntry {
+    int kid;
+    hipEvent_t start, stop;
+};
+
 struct Ctx {
     mukv_config cfg;
+    bool profiling;
+    std::vector<ProfEntry> *prof; // event pairs recorded since mukv_profile_begin
     int kappa, ls, c_kv, group, esz, max_segments;
     bool use_mfma;
     double margin_thr;
@@ -73,6 +82,25 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st);
 
 hipError_t launch_gather(Ctx &c, const int32_t *frame_idx, int B, int k_frame, int order, void *k_out,
                          void *v_out, int32_t *n_tokens_out, hipStream_t st);
+
+// Brackets the launches of one scope with HIP events when the context is profiling.
+struct ProfScope {
+    Ctx &c;
+    hipStream_t st;
+    ProfEntry e;
+    bool on;
+    ProfScope(Ctx &ctx, int kid, hipStream_t s) : c(ctx), st(s), on(ctx.profiling) {
+        if (!on) return;
+        e.kid = kid;
+        on = hipEventCreate(&e.start) == hipSuccess && hipEventCreate(&e.stop) == hipSuccess &&
+             hipEventRecord(e.start, st) == hipSuccess;
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(e.stop, st);
+        c.prof->push_back(e);
+    }
+};
 
 // LDS bytes the generic attention kernel needs for P tokens of D features when it accumulates
 // in a type of r_size bytes.

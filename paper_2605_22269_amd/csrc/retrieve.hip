@@ -459,13 +459,17 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(GatherArgs a) {
 hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
     const int Hq = c.cfg.n_q_heads, Hkv = c.cfg.n_kv_heads, D = c.cfg.head_dim, G = c.group;
     const size_t lds = (size_t)G * D * sizeof(double);
+    hipError_t e;
+    {
+    ProfScope ps(c, MUKV_K_POOLQ, st);
     if (c.cfg.dtype == MUKV_BF16)
         hipLaunchKernelGGL((pool_question_kernel<uint16_t>), dim3(a.B, Hkv), dim3(256), lds, st,
                            reinterpret_cast<const uint16_t *>(a.q_tokens), a.q_offsets, Hq, Hkv, D, G, c.qbar, c.qq);
     else
         hipLaunchKernelGGL((pool_question_kernel<float>), dim3(a.B, Hkv), dim3(256), lds, st,
                            reinterpret_cast<const float *>(a.q_tokens), a.q_offsets, Hq, Hkv, D, G, c.qbar, c.qq);
-    hipError_t e = hipGetLastError();
+    e = hipGetLastError();
+    }
     if (e != hipSuccess) return e;
 
     const int F = c.cfg.frames_per_segment;
@@ -492,6 +496,7 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
         s.tail_cut = tail_cut;
         s.ld_frm = c.cfg.max_frames;
         s.ld_seg = c.max_segments;
+        ProfScope ps(c, MUKV_K_SCORE, st);
         hipLaunchKernelGGL(score_blocks_kernel, dim3((a.nv + a.ns + 3) / 4), dim3(256), 0, st, s);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
@@ -517,6 +522,7 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
     r.frm_idx = a.frm_idx;
     r.seg_score = a.seg_score;
     r.frm_score = a.frm_score;
+    ProfScope ps(c, MUKV_K_RERANK, st);
     hipLaunchKernelGGL(select_rerank_kernel, dim3(a.B), dim3(kSelThreads), 0, st, r);
     return hipGetLastError();
 }
@@ -543,6 +549,7 @@ hipError_t launch_gather(Ctx &c, const int32_t *frame_idx, int B, int k_frame, i
     constexpr int ITER = 4;
     const int n_units = k_frame * g.units_per_frame;
     const int gx = (n_units + 256 * ITER - 1) / (256 * ITER);
+    ProfScope ps(c, MUKV_K_GATHER, st);
     hipLaunchKernelGGL((gather_kv_kernel<ITER>), dim3(gx, c.cfg.n_layers * 2 * c.cfg.n_kv_heads, B), dim3(256), 0, st, g);
     return hipGetLastError();
 }
