@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--frames", type=int, default=0, help="override the stream length (debugging)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-frames", type=int, default=64)
+    ap.add_argument("--cpu-sample-frames", type=int, default=1024)
     ap.add_argument("--seed", type=int, default=2605)
     return ap.parse_args()
 

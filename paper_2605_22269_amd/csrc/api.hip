@@ -53,15 +53,12 @@ int validate_config(const mukv_config *cfg) {
     return MUKV_OK;
 }
 
-bool mfma_supported(const mukv_config &c) {
-    (void)c;
-    return false;
-}
+bool mfma_supported(const mukv_config &c) { return mukv::att_mfma_supported(c); }
 
 void free_all(Ctx &c) {
     void *ptrs[] = {c.store_k,    c.store_v,    c.kept_idx,  c.rep_frame_k, c.rep_frame_v, c.rep_patch_k,
                     c.rep_patch_v, c.rep_seg_k, c.rep_seg_v, c.cnt_patch,   c.fsum_k,      c.fsum_v,
-                    c.margin,      c.refined,   c.att_part,  c.fft_sig,     c.att64,       c.fft64,
+                    c.ssum_k,      c.ssum_v,    c.margin,      c.refined,   c.att_part,  c.fft_sig,     c.att64,       c.fft64,
                     c.src_tok,     c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
@@ -129,6 +126,8 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(dalloc(&c.cnt_patch, MF * S));
     ok(dalloc(&c.fsum_k, MF * C));
     ok(dalloc(&c.fsum_v, MF * C));
+    ok(dalloc(&c.ssum_k, (size_t)c.max_segments * C));
+    ok(dalloc(&c.ssum_v, (size_t)c.max_segments * C));
     ok(dalloc(&c.margin, MF));
     ok(dalloc(&c.refined, MF));
     ok(dalloc(&c.att_part, MC * Hq * P));

@@ -195,6 +195,11 @@ __global__ __launch_bounds__(256) void att_generic_kernel(const T *__restrict__ 
 // Pooled sums are accumulated in fp64 (exact for bf16 / fp32 payloads of ordinary dynamic
 // range), divided once and rounded once to float.
 // ------------------------------------------------------------------------------------------
+template <typename T>
+struct __align__(2 * sizeof(T)) Pair2 {
+    T a, b;
+};
+
 template <typename R>
 struct SelectArgs {
     const R *att;       // [n_frames][n_part][P] partial sums, or NULL (alpha == 0)
@@ -315,35 +320,70 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
     }
     __syncthreads();
 
-    // Eq. 5 for the frame and its S super-patches, K then V
+    // Eq. 5 for the frame and its S super-patches, K and V together.  A thread owns two adjacent
+    // channels (one 4- or 8-byte load per row) and fetches the kept rows in batches of kBatch
+    // independent loads; kl is ascending, so a super-patch ends when a position reaches its end.
+    constexpr int kBatch = 12;
     const int C = a.Hkv * a.D;
     const int len = P / a.S;
-    for (int which = 0; which < 2; ++which) {
-        const T *x = reinterpret_cast<const T *>(which ? a.v : a.k);
-        float *rep_frame = which ? a.rep_frame_v : a.rep_frame_k;
-        float *rep_patch = which ? a.rep_patch_v : a.rep_patch_k;
-        double *fsum = which ? a.fsum_v : a.fsum_k;
-        for (int c = j; c < C; c += 256) {
-            const int g = c / a.D, d = c - g * a.D;
-            const T *col = x + (int64_t)g * a.sh + d;
-            int r = 0;
-            double tot = 0.0;
-            for (int s = 0; s < a.S; ++s) {
-                const int end = (s == a.S - 1) ? P : (s + 1) * len;
-                double run = 0.0;
-                int cnt = 0;
-                while (r < kappa && kl[r] < end) {
-                    run += (double)to_float(col[((int64_t)f * P + kl[r]) * a.st]);
-                    ++cnt;
-                    ++r;
-                }
-                rep_patch[(gf * a.S + s) * C + c] = cnt ? (float)(run / (double)cnt) : 0.0f;
-                if (which == 0 && c == 0) a.cnt_patch[gf * a.S + s] = cnt;
-                tot += run;
+    const T *xk = reinterpret_cast<const T *>(a.k);
+    const T *xv = reinterpret_cast<const T *>(a.v);
+    for (int cp = j; cp < C / 2; cp += 256) {
+        const int c = 2 * cp;
+        const int g = c / a.D, d = c - g * a.D;
+        const int64_t col = (int64_t)g * a.sh + d + (int64_t)f * P * a.st;
+        double run[4] = {0.0, 0.0, 0.0, 0.0}, tot[4] = {0.0, 0.0, 0.0, 0.0}; // k0 k1 v0 v1
+        int cnt = 0, s = 0;
+        int end = (a.S == 1) ? P : len;
+        auto flush = [&]() {
+            const int64_t o = (gf * a.S + s) * C + c;
+            a.rep_patch_k[o] = cnt ? (float)(run[0] / (double)cnt) : 0.0f;
+            a.rep_patch_k[o + 1] = cnt ? (float)(run[1] / (double)cnt) : 0.0f;
+            a.rep_patch_v[o] = cnt ? (float)(run[2] / (double)cnt) : 0.0f;
+            a.rep_patch_v[o + 1] = cnt ? (float)(run[3] / (double)cnt) : 0.0f;
+            if (c == 0) a.cnt_patch[gf * a.S + s] = cnt;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                tot[e] += run[e];
+                run[e] = 0.0;
             }
-            fsum[gf * C + c] = tot;
-            rep_frame[gf * C + c] = (float)(tot / (double)kappa);
+            cnt = 0;
+            ++s;
+            end = (s == a.S - 1) ? P : (s + 1) * len;
+        };
+        for (int r0 = 0; r0 < kappa; r0 += kBatch) {
+            Pair2<T> vk[kBatch], vv[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                if (r0 + u < kappa) {
+                    const int64_t off = col + (int64_t)kl[r0 + u] * a.st;
+                    vk[u] = *reinterpret_cast<const Pair2<T> *>(xk + off);
+                    vv[u] = *reinterpret_cast<const Pair2<T> *>(xv + off);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                if (r0 + u < kappa) {
+                    const int pos = kl[r0 + u];
+                    while (pos >= end) flush();
+                    run[0] += (double)to_float(vk[u].a);
+                    run[1] += (double)to_float(vk[u].b);
+                    run[2] += (double)to_float(vv[u].a);
+                    run[3] += (double)to_float(vv[u].b);
+                    ++cnt;
+                }
+            }
         }
+        while (s < a.S) flush();
+        const int64_t o = gf * C + c;
+        a.fsum_k[o] = tot[0];
+        a.fsum_k[o + 1] = tot[1];
+        a.fsum_v[o] = tot[2];
+        a.fsum_v[o + 1] = tot[3];
+        a.rep_frame_k[o] = (float)(tot[0] / (double)kappa);
+        a.rep_frame_k[o + 1] = (float)(tot[1] / (double)kappa);
+        a.rep_frame_v[o] = (float)(tot[2] / (double)kappa);
+        a.rep_frame_v[o + 1] = (float)(tot[3] / (double)kappa);
     }
 }
 
@@ -352,8 +392,10 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
 // grid.y < n_slab: slab (layer, K|V, KV head); the slab's destination is one dense run of
 // n_frames*kappa rows, so unit u of the slab goes to dst + u*VEC and comes from the row
 // src_tok[u / units_per_row] of the chunk.  Each thread moves ITER units: loads first, then
-// stores.  grid.y >= n_slab: one workgroup per segment touched by the chunk recomputes that
-// segment's keys from the exact per-frame sums (any chunking gives the same bits).
+// stores.  grid.y >= n_slab: one workgroup per segment touched by the chunk adds the chunk's
+// exact per-frame sums to the segment's running fp64 sum and refreshes the segment's keys; the
+// sums are exact for bf16 / fp32 payloads of ordinary dynamic range, so any chunking gives the
+// same bits.
 // ------------------------------------------------------------------------------------------
 struct CompactArgs {
     const unsigned char *k, *v;  // chunk base, bytes
@@ -369,6 +411,8 @@ struct CompactArgs {
     int seg_first, F, kappa, C;
     int64_t n_total;             // frames in the cache after this chunk
     const double *fsum_k, *fsum_v;
+    double *ssum_k, *ssum_v;     // running exact sums per segment
+    int64_t frame0;
     float *rep_seg_k, *rep_seg_v;
 };
 
@@ -380,15 +424,30 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
         const int s = a.seg_first + (y - a.n_slab);
         const int64_t f0 = (int64_t)s * a.F;
         const int64_t f1 = (f0 + a.F < a.n_total) ? f0 + a.F : a.n_total;
-        const double inv_n = (double)(f1 - f0) * (double)a.kappa;
+        const int64_t fa = f0 > a.frame0 ? f0 : a.frame0; // first frame of the segment in this chunk
+        const bool fresh = f0 >= a.frame0;                // the segment starts in this chunk
+        const double den = (double)(f1 - f0) * (double)a.kappa;
         for (int c = threadIdx.x; c < a.C; c += 256) {
-            double sk = 0.0, sv = 0.0;
-            for (int64_t f = f0; f < f1; ++f) {
-                sk += a.fsum_k[f * a.C + c];
-                sv += a.fsum_v[f * a.C + c];
+            double sk = fresh ? 0.0 : a.ssum_k[(int64_t)s * a.C + c];
+            double sv = fresh ? 0.0 : a.ssum_v[(int64_t)s * a.C + c];
+            for (int64_t fb = fa; fb < f1; fb += 8) {
+                double tk[8], tv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const bool in = fb + u < f1;
+                    tk[u] = in ? a.fsum_k[(fb + u) * a.C + c] : 0.0;
+                    tv[u] = in ? a.fsum_v[(fb + u) * a.C + c] : 0.0;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    sk += tk[u];
+                    sv += tv[u];
+                }
             }
-            a.rep_seg_k[(int64_t)s * a.C + c] = (float)(sk / inv_n);
-            a.rep_seg_v[(int64_t)s * a.C + c] = (float)(sv / inv_n);
+            a.ssum_k[(int64_t)s * a.C + c] = sk;
+            a.ssum_v[(int64_t)s * a.C + c] = sv;
+            a.rep_seg_k[(int64_t)s * a.C + c] = (float)(sk / den);
+            a.rep_seg_v[(int64_t)s * a.C + c] = (float)(sv / den);
         }
         return;
     }
@@ -539,6 +598,9 @@ static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, hipStream_t s
     const int seg_last = (int)((k.n_total - 1) / k.F);
     k.fsum_k = c.fsum_k;
     k.fsum_v = c.fsum_v;
+    k.ssum_k = c.ssum_k;
+    k.ssum_v = c.ssum_v;
+    k.frame0 = a.frame0;
     k.rep_seg_k = c.rep_seg_k;
     k.rep_seg_v = c.rep_seg_v;
     constexpr int ITER = 4;

@@ -36,6 +36,7 @@ struct Ctx {
     float *rep_frame_k, *rep_frame_v, *rep_patch_k, *rep_patch_v, *rep_seg_k, *rep_seg_v;
     int32_t *cnt_patch;
     double *fsum_k, *fsum_v; // [max_frames][c_kv] exact sums of the kept scoring-layer rows
+    double *ssum_k, *ssum_v; // [max_segments][c_kv] running sums of fsum over each segment
     float *margin;
     int32_t *refined;
     // per-chunk scratch (device)
@@ -101,6 +102,9 @@ struct ProfScope {
         c.prof->push_back(e);
     }
 };
+
+// True when the matrix-core attention kernel covers this configuration.
+bool att_mfma_supported(const mukv_config &c);
 
 // LDS bytes the generic attention kernel needs for P tokens of D features when it accumulates
 // in a type of r_size bytes.

@@ -22,32 +22,50 @@ constexpr int kSelThreads = 512;
 // |q|^2.
 // ------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void pool_question_kernel(const T *__restrict__ q_tokens,
-                                                            const int32_t *__restrict__ q_off, int Hq, int Hkv, int D,
-                                                            int G, double *__restrict__ qbar,
-                                                            double *__restrict__ qq) {
+__global__ __launch_bounds__(1024) void pool_question_kernel(const T *__restrict__ q_tokens,
+                                                             const int32_t *__restrict__ q_off, int Hq, int Hkv, int D,
+                                                             int G, double *__restrict__ qbar,
+                                                             double *__restrict__ qq) {
+    // threads: 256 element lanes x 4 token slices; slice t takes tokens t, t+4, ... in batches of
+    // 8 independent loads.  Token sums are exact in fp64, so the split does not change the result.
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    double *qm = reinterpret_cast<double *>(smem_raw); // [G*D]
-    __shared__ double red[4];
+    double *part = reinterpret_cast<double *>(smem_raw); // [4][G*D]
+    __shared__ double red[16];
     const int b = blockIdx.x, g = blockIdx.y, tid = threadIdx.x;
+    const int el = tid & 255, ts = tid >> 8;
     const int t0 = q_off[b], t1 = q_off[b + 1];
     const int nq = t1 - t0;
-    double sq = 0.0;
-    for (int e = tid; e < G * D; e += 256) {
+    const int GD = G * D;
+    const int64_t tstride = (int64_t)Hq * D;
+    for (int e = el; e < GD; e += 256) {
         const T *p = q_tokens + ((int64_t)t0 * Hq + (int64_t)g * G) * D + e;
         double s = 0.0;
-        for (int t = 0; t < nq; ++t) s += (double)to_float(p[(int64_t)t * Hq * D]);
-        const double m = nq > 0 ? s / (double)nq : 0.0;
-        qm[e] = m;
-        sq += m * m;
+        for (int tb = ts; tb < nq; tb += 32) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = (tb + 4 * u < nq) ? to_float(p[(int64_t)(tb + 4 * u) * tstride]) : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += (double)v[u];
+        }
+        part[ts * GD + e] = s;
+    }
+    __syncthreads();
+    double sq = 0.0;
+    if (ts == 0) {
+        for (int e = el; e < GD; e += 256) {
+            const double s = ((part[e] + part[GD + e]) + part[2 * GD + e]) + part[3 * GD + e];
+            const double m = nq > 0 ? s / (double)nq : 0.0;
+            part[e] = m;
+            sq += m * m;
+        }
     }
     sq = wave_sum(sq);
     if ((tid & 63) == 0) red[tid >> 6] = sq;
     __syncthreads();
     if (tid == 0) qq[(int64_t)b * Hkv + g] = ((red[0] + red[1]) + red[2]) + red[3];
-    for (int d = tid; d < D; d += 256) {
+    for (int d = tid; d < D; d += 1024) {
         double s = 0.0;
-        for (int hl = 0; hl < G; ++hl) s += qm[hl * D + d];
+        for (int hl = 0; hl < G; ++hl) s += part[hl * D + d];
         qbar[((int64_t)b * Hkv + g) * D + d] = s;
     }
 }
@@ -152,17 +170,38 @@ struct SelShared {
 // Chooses the m best of entries 0..n-1 (smallest key; equal keys: lowest entry number) and
 // writes their entry numbers to out[0..m_eff) in rank order.  Returns m_eff = min(m, number of
 // entries whose key is not kNoKey).  All threads of the workgroup must call it.
-// Method: 8-bit radix select of the m-th key (8 passes of LDS histograms), one pass collecting
-// everything better than it, an ordered scan handing the remaining places to the first
-// entries equal to it, then a rank-by-counting sort of the <= kMaxCand survivors.
+// The keys of the first `cap` entries are computed once (batches of independent loads) and kept
+// in the LDS array `cache`; entries past `cap` are recomputed from `key` on every pass.
+// Method: 8-bit radix select of the m-th key (8 passes of LDS histograms, the digit found by a
+// wave-parallel prefix sum), one pass collecting everything better than it, an ordered scan
+// handing the remaining places to the first entries equal to it, then a rank-by-counting sort
+// of the <= kMaxCand survivors.
 template <typename KeyFn>
-__device__ int block_topk(KeyFn key, int n, int m, int *out, SelShared &sh) {
-    const int tid = threadIdx.x;
+__device__ int block_topk(KeyFn key, int n, int m, int *out, SelShared &sh, uint64_t *cache, int cap) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     __syncthreads();
     if (tid == 0) sh.count = 0;
     __syncthreads();
     int mine = 0;
-    for (int i = tid; i < n; i += kSelThreads) mine += key(i) != kNoKey;
+    const int n_c = n < cap ? n : cap;
+    for (int i0 = tid; i0 < n_c; i0 += 8 * kSelThreads) {
+        uint64_t kk[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * kSelThreads;
+            kk[u] = i < n_c ? key(i) : kNoKey;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * kSelThreads;
+            if (i < n_c) {
+                cache[i] = kk[u];
+                mine += kk[u] != kNoKey;
+            }
+        }
+    }
+    for (int i = n_c + tid; i < n; i += kSelThreads) mine += key(i) != kNoKey;
+    auto get = [&](int i) { return i < n_c ? cache[i] : key(i); };
     if (mine) atomicAdd(&sh.count, mine);
     __syncthreads();
     const int m_eff = min(m, sh.count);
@@ -175,22 +214,43 @@ __device__ int block_topk(KeyFn key, int n, int m, int *out, SelShared &sh) {
         for (int d = tid; d < 256; d += kSelThreads) sh.hist[d] = 0;
         __syncthreads();
         for (int i = tid; i < n; i += kSelThreads) {
-            const uint64_t k = key(i);
+            const uint64_t k = get(i);
             if (k == kNoKey) continue;
             const bool match = (pb == 7) || ((k >> (8 * (pb + 1))) == prefix);
             if (match) atomicAdd(&sh.hist[(unsigned)(k >> (8 * pb)) & 255u], 1u);
         }
         __syncthreads();
-        if (tid == 0) {
-            int need = sh.need, cum = 0;
-            unsigned d = 0;
-            for (; d < 256; ++d) {
-                const int h = (int)sh.hist[d];
-                if (cum + h >= need) break;
-                cum += h;
+        if (wave == 0) {
+            // lane owns bins 4*lane..4*lane+3; find the bin where the running count reaches need
+            const int need = sh.need;
+            const int h0 = (int)sh.hist[4 * lane], h1 = (int)sh.hist[4 * lane + 1];
+            const int h2 = (int)sh.hist[4 * lane + 2], h3 = (int)sh.hist[4 * lane + 3];
+            const int loc = h0 + h1 + h2 + h3;
+            int inc = loc;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(inc, o);
+                if (lane >= o) inc += t;
             }
-            sh.digit = d;
-            sh.need = need - cum;
+            const int before = inc - loc;
+            if (before < need && need <= inc) {
+                int cum = before;
+                unsigned d = 4 * lane;
+                if (cum + h0 < need) {
+                    cum += h0;
+                    ++d;
+                    if (cum + h1 < need) {
+                        cum += h1;
+                        ++d;
+                        if (cum + h2 < need) {
+                            cum += h2;
+                            ++d;
+                        }
+                    }
+                }
+                sh.digit = d;
+                sh.need = need - cum;
+            }
         }
         __syncthreads();
         prefix = (prefix << 8) | sh.digit;
@@ -202,7 +262,7 @@ __device__ int block_topk(KeyFn key, int n, int m, int *out, SelShared &sh) {
     if (tid == 0) sh.count = 0;
     __syncthreads();
     for (int i = tid; i < n; i += kSelThreads) {
-        const uint64_t k = key(i);
+        const uint64_t k = get(i);
         if (k < thr) {
             const int pos = atomicAdd(&sh.count, 1);
             sh.sel_key[pos] = k;
@@ -211,10 +271,9 @@ __device__ int block_topk(KeyFn key, int n, int m, int *out, SelShared &sh) {
     }
     // entries equal to the threshold, in entry order
     int running = 0;
-    const int lane = tid & 63, wave = tid >> 6;
     for (int base = 0; base < n && running < n_equal; base += kSelThreads) {
         const int i = base + tid;
-        const bool flag = i < n && key(i) == thr;
+        const bool flag = i < n && get(i) == thr;
         const uint64_t bal = __ballot(flag);
         const int below = __popcll(bal & ((1ull << lane) - 1ull));
         __syncthreads();
@@ -268,6 +327,7 @@ struct RerankArgs {
     const float *rep_frame, *rep_seg, *seg_tail;
     int nv, ns, C, F, tail_cut;
     int mode, k_seg, k_frame, n_global;
+    int cache_cap; // entries of the LDS key cache (dynamic shared memory)
     double lambda;
     int32_t *seg_idx, *frm_idx;
     float *seg_score, *frm_score;
@@ -284,6 +344,9 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
     __shared__ double gvec[1024];
     __shared__ unsigned seg_ok[kMaxSegBitmapWords];
     __shared__ double gg_sh;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    uint64_t *kcache = reinterpret_cast<uint64_t *>(smem_raw); // [a.cache_cap]
+    const int cap = a.cache_cap;
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const double *s_frm = a.s_frm + (int64_t)b * a.ld_frm;
     const double *s_seg = a.s_seg + (int64_t)b * a.ld_seg;
@@ -296,7 +359,7 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
     auto frm_key = [&](int i) { return desc_key(s_frm[i]); };
 
     if (a.mode != MUKV_SEMI) {
-        const int m_s = block_topk(seg_key, a.ns, a.k_seg, cand_seg, sh);
+        const int m_s = block_topk(seg_key, a.ns, a.k_seg, cand_seg, sh, kcache, cap);
         for (int r = tid; r < a.k_seg; r += kSelThreads) {
             seg_out[r] = r < m_s ? cand_seg[r] : -1;
             if (seg_sc) seg_sc[r] = r < m_s ? (float)s_seg[cand_seg[r]] : 0.f;
@@ -311,9 +374,9 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
                 const int s = i / a.F;
                 return ((seg_ok[s >> 5] >> (s & 31)) & 1u) ? desc_key(s_frm[i]) : kNoKey;
             };
-            m_f = block_topk(hier_key, a.nv, a.k_frame, cand_frm, sh);
+            m_f = block_topk(hier_key, a.nv, a.k_frame, cand_frm, sh, kcache, cap);
         } else {
-            m_f = block_topk(frm_key, a.nv, a.k_frame, cand_frm, sh);
+            m_f = block_topk(frm_key, a.nv, a.k_frame, cand_frm, sh, kcache, cap);
         }
         for (int r = tid; r < a.k_frame; r += kSelThreads) {
             frm_out[r] = r < m_f ? cand_frm[r] : -1;
@@ -323,12 +386,12 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
     }
 
     // ---- semi-hierarchical ----
-    const int m_s = block_topk(seg_key, a.ns, 2 * a.k_seg, cand_seg, sh);
+    const int m_s = block_topk(seg_key, a.ns, 2 * a.k_seg, cand_seg, sh, kcache, cap);
     for (int r = tid; r < a.k_seg; r += kSelThreads) { // lambda = 0 for segments: stage-1 order stands
         seg_out[r] = r < m_s ? cand_seg[r] : -1;
         if (seg_sc) seg_sc[r] = r < m_s ? (float)s_seg[cand_seg[r]] : 0.f;
     }
-    const int m_f = block_topk(frm_key, a.nv, 2 * a.k_frame, order, sh);
+    const int m_f = block_topk(frm_key, a.nv, 2 * a.k_frame, order, sh, kcache, cap);
     // candidates in ascending frame order, so that equal reranked scores resolve to the lowest frame
     for (int t = tid; t < m_f; t += kSelThreads) {
         const int me = order[t];
@@ -375,7 +438,7 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
     }
     __syncthreads();
     auto st_key = [&](int i) { return desc_key(st[i]); };
-    const int m_o = block_topk(st_key, m_f, a.k_frame, order, sh);
+    const int m_o = block_topk(st_key, m_f, a.k_frame, order, sh, kcache, cap);
     for (int r = tid; r < a.k_frame; r += kSelThreads) {
         frm_out[r] = r < m_o ? cand_frm[order[r]] : -1;
         if (frm_sc) frm_sc[r] = r < m_o ? (float)st[order[r]] : 0.f;
@@ -458,15 +521,15 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(GatherArgs a) {
 // ------------------------------------------------------------------------------------------
 hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
     const int Hq = c.cfg.n_q_heads, Hkv = c.cfg.n_kv_heads, D = c.cfg.head_dim, G = c.group;
-    const size_t lds = (size_t)G * D * sizeof(double);
+    const size_t lds = (size_t)4 * G * D * sizeof(double);
     hipError_t e;
     {
     ProfScope ps(c, MUKV_K_POOLQ, st);
     if (c.cfg.dtype == MUKV_BF16)
-        hipLaunchKernelGGL((pool_question_kernel<uint16_t>), dim3(a.B, Hkv), dim3(256), lds, st,
+        hipLaunchKernelGGL((pool_question_kernel<uint16_t>), dim3(a.B, Hkv), dim3(1024), lds, st,
                            reinterpret_cast<const uint16_t *>(a.q_tokens), a.q_offsets, Hq, Hkv, D, G, c.qbar, c.qq);
     else
-        hipLaunchKernelGGL((pool_question_kernel<float>), dim3(a.B, Hkv), dim3(256), lds, st,
+        hipLaunchKernelGGL((pool_question_kernel<float>), dim3(a.B, Hkv), dim3(1024), lds, st,
                            reinterpret_cast<const float *>(a.q_tokens), a.q_offsets, Hq, Hkv, D, G, c.qbar, c.qq);
     e = hipGetLastError();
     }
@@ -522,8 +585,20 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
     r.frm_idx = a.frm_idx;
     r.seg_score = a.seg_score;
     r.frm_score = a.frm_score;
+    // key cache: as many of the frame scores as fit beside the kernel's static LDS
+    constexpr int kMaxCache = 11 * 1024; // 88 KB of 8-byte keys
+    int n_max = a.nv > a.ns ? a.nv : a.ns;
+    if (n_max < 2 * kMaxCand) n_max = 2 * kMaxCand;
+    r.cache_cap = n_max < kMaxCache ? n_max : kMaxCache;
+    static bool attr_set = false;
+    if (!attr_set) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&select_rerank_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kMaxCache * 8);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
     ProfScope ps(c, MUKV_K_RERANK, st);
-    hipLaunchKernelGGL(select_rerank_kernel, dim3(a.B), dim3(kSelThreads), 0, st, r);
+    hipLaunchKernelGGL(select_rerank_kernel, dim3(a.B), dim3(kSelThreads), (size_t)r.cache_cap * 8, st, r);
     return hipGetLastError();
 }
 

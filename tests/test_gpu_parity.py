@@ -222,3 +222,53 @@ def test_capacity_and_argument_errors_on_device():
     assert e.value.status == mk.MUKV_ERR_UNSUPPORTED
     torch.cuda.synchronize()
     g.close()
+
+
+# ----------------------------------------------------- attention kernels and fp64 re-scoring --
+@pytest.mark.parametrize("path", [mk.MUKV_ATT_GENERIC, mk.MUKV_ATT_MFMA])
+@pytest.mark.parametrize("causal", [True, False])
+def test_attention_paths_bf16(path, causal):
+    w = W["7b"].scaled(n_frames=10, n_layers=2)
+    p = Pair(w, seed=61, chunk=4, gpu_kw={"att_path": path, "causal": causal}, orc_kw={"causal": causal})
+    p.ingest()
+    p.check_compress()
+    p.close()
+
+
+@pytest.mark.parametrize("P", [50, 16, 208, 7])
+def test_mfma_ragged_token_counts(P):
+    w = W["7b"].scaled(n_frames=5, n_layers=1, tokens_per_frame=P, keep_ratio=0.3, n_q_heads=8, n_kv_heads=2)
+    p = Pair(w, seed=62 + P, chunk=3, gpu_kw={"att_path": mk.MUKV_ATT_MFMA})
+    p.ingest()
+    p.check_compress()
+    p.close()
+
+
+def test_mfma_whole_group_per_workgroup():
+    # enough frames in one call that a workgroup loops over all heads of its KV group
+    w = W["7b"].scaled(n_frames=152, n_layers=1)
+    p = Pair(w, seed=63, chunk=152, gpu_kw={"att_path": mk.MUKV_ATT_MFMA})
+    p.ingest()
+    p.check_compress()
+    p.close()
+
+
+@pytest.mark.parametrize("name", ["tiny", "7b"])
+def test_fp64_rescoring_of_every_frame(name):
+    w = W[name].scaled(n_frames=6, n_layers=2)
+    p = Pair(w, seed=64, chunk=4, gpu_kw={"refine_margin": 10.0})
+    p.ingest()
+    st = p.check_compress()
+    assert int(st["refined"].sum()) == 6
+    for so, sg in zip(p.sig_orc, p.sig_gpu):   # fp64 path: only the final float rounding differs
+        assert np.abs(sg["fused"].cpu().numpy() - so["fused"]).max() <= 2e-7
+    p.close()
+
+
+def test_no_rescoring_when_disabled():
+    w = W["tiny"].scaled(n_frames=6)
+    p = Pair(w, seed=65, chunk=6, gpu_kw={"refine_margin": 0.0})
+    p.ingest()
+    st = p.check_compress()
+    assert int(st["refined"].sum()) == 0
+    p.close()
