@@ -130,7 +130,7 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(dalloc(&c.ssum_v, (size_t)c.max_segments * C));
     ok(dalloc(&c.margin, MF));
     ok(dalloc(&c.refined, MF));
-    ok(dalloc(&c.att_part, MC * Hq * P));
+    ok(dalloc(&c.att_part, MC * Hq * 2 * P)); // up to two partial rows per head
     ok(dalloc(&c.fft_sig, MC * P));
     ok(dalloc(&c.att64, MC * Hq * P));
     ok(dalloc(&c.fft64, MC * P));

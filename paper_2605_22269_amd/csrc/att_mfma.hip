@@ -21,6 +21,7 @@ namespace mukv {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int kMaxTiles = 13;  // 13 * 16 = 208 >= P
 constexpr int kLdsRow = 136;   // bf16 elements per LDS key row: 128 + 8 of padding (272 B)
@@ -28,45 +29,75 @@ constexpr int kHeadDim = 128;
 
 __global__ __launch_bounds__(448) void att_mfma_kernel(const uint16_t *__restrict__ q, int64_t q_sh, int64_t q_st,
                                                        const uint16_t *__restrict__ k, int64_t k_sh, int64_t k_st,
-                                                       int P, int nt, int G, int hpw, int causal,
+                                                       int P, int nt, int G, int hpw, int causal, int pair, int n_split,
                                                        float scale_log2e, int n_part, float *__restrict__ out) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     uint16_t *Ks = reinterpret_cast<uint16_t *>(smem_raw);                           // [nt*16][kLdsRow]
     float *red = reinterpret_cast<float *>(smem_raw + (size_t)nt * 16 * kLdsRow * 2); // [waves][nt*16]
-    const int f = blockIdx.x, part = blockIdx.y;
+    const int f = blockIdx.x, part = blockIdx.y / n_split, sp = blockIdx.y - part * n_split;
     const int h0 = part * hpw, g = h0 / G;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n_threads = blockDim.x;
     const int lr = lane & 15, lg = lane >> 4;
 
-    // stage K of (frame, KV head) in LDS; rows past P are zero
+    // pair = 1: wave w takes strips w and nt-1-w (balanced under the causal mask, for throughput).
+    // pair = 0: one strip per wave and the strips of a (frame, part) split over n_split workgroups
+    // (shortest critical path, for calls with few frames); a workgroup then stages only the keys
+    // its strips can see.
+    const int wps = (nt + n_split - 1) / n_split; // strips per workgroup when not paired
+    const int sA = pair ? w : sp * wps + w, sB = nt - 1 - w;
+    const int n_strips = (pair && sA != sB) ? 2 : 1;
+    const bool active = sA < nt && (pair || w < wps);
+    int k_tiles = nt;
+    if (!pair && causal) k_tiles = (sp + 1) * wps < nt ? (sp + 1) * wps : nt;
+    const uint16_t *qf = q + ((int64_t)f * P) * q_st + 8 * lg;
+    // B operand of one (head, strip): 4 x 16 bytes per lane, rows past P clamped (masked later)
+    auto load_q = [&](int h, int s, bf16x8 *dst) {
+        const int qi = 16 * s + lr;
+        const uint16_t *qp = qf + (int64_t)h * q_sh + (int64_t)(qi < P ? qi : P - 1) * q_st;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) dst[kk] = *reinterpret_cast<const bf16x8 *>(qp + 32 * kk);
+    };
+    const int n_jobs = active ? hpw * n_strips : 0; // (head, strip) pairs of this wave, strip fastest
+    bf16x8 qv[4], qn[4];
+    load_q(h0, active ? sA : 0, qv); // jobs 0 and 1: in flight while K is staged
+    if (n_jobs > 1) load_q(h0 + 1 / n_strips, (1 % n_strips) ? sB : sA, qn);
+
+    // stage K of (frame, KV head) in LDS; rows past P are zero.  Loads are unconditional on a
+    // clamped row and issued in batches of 4 before the LDS stores.
     const uint16_t *kf = k + (int64_t)g * k_sh + (int64_t)f * P * k_st;
-    for (int idx = tid; idx < nt * 16 * 16; idx += n_threads) {
-        const int row = idx >> 4, u = idx & 15;
-        uint4 val = make_uint4(0u, 0u, 0u, 0u);
-        if (row < P) val = *reinterpret_cast<const uint4 *>(kf + (int64_t)row * k_st + u * 8);
-        *reinterpret_cast<uint4 *>(Ks + row * kLdsRow + u * 8) = val;
+    const int n_units = k_tiles * 16 * 16;
+    for (int i0 = tid; i0 < n_units; i0 += 8 * n_threads) {
+        u32x4 val[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            int idx = i0 + u * n_threads;
+            idx = idx < n_units ? idx : n_units - 1;
+            const int row = idx >> 4;
+            val[u] = *reinterpret_cast<const u32x4 *>(kf + (int64_t)(row < P ? row : P - 1) * k_st + (idx & 15) * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = i0 + u * n_threads;
+            if (idx < n_units) {
+                const int row = idx >> 4;
+                *reinterpret_cast<u32x4 *>(Ks + row * kLdsRow + (idx & 15) * 8) = row < P ? val[u] : u32x4{0u, 0u, 0u, 0u};
+            }
+        }
     }
     __syncthreads();
 
-    const int sA = w, sB = nt - 1 - w;
-    const int n_strips = (sA == sB) ? 1 : 2;
     f32x4 acc[kMaxTiles];
 #pragma unroll
     for (int c = 0; c < kMaxTiles; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const uint16_t *a_base = Ks + lr * kLdsRow + 8 * lg;
     const bool tail = (P & 15) != 0;
-    for (int hh = 0; hh < hpw; ++hh) {
-        const int h = h0 + hh;
-        for (int si = 0; si < n_strips; ++si) {
+    for (int job = 0; job < n_jobs; ++job) {
+        {
+            const int hh = job / n_strips, si = job - hh * n_strips;
             const int s = si ? sB : sA;
             const int qi = 16 * s + lr;
-            const int qrow = qi < P ? qi : P - 1;
-            const uint16_t *qp = q + (int64_t)h * q_sh + ((int64_t)f * P + qrow) * q_st + 8 * lg;
-            bf16x8 qv[4];
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) qv[kk] = *reinterpret_cast<const bf16x8 *>(qp + 32 * kk);
             const int cmax = causal ? s : nt - 1;
             f32x4 st[kMaxTiles];
 #pragma unroll
@@ -79,6 +110,14 @@ __global__ __launch_bounds__(448) void att_mfma_kernel(const uint16_t *__restric
                         d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qv[kk], d, 0, 0, 0);
                     }
                     st[c] = d;
+                }
+            }
+            if (job + 1 < n_jobs) { // Q of job+1 arrived long ago; fetch job+2 behind the softmax below
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) qv[kk] = qn[kk];
+                if (job + 2 < n_jobs) {
+                    const int hn = (job + 2) / n_strips, sn = (job + 2) - hn * n_strips;
+                    load_q(h0 + hn, sn ? sB : sA, qn);
                 }
             }
             // masks: keys after the query on the diagonal tile, keys past P on the last tile
@@ -100,8 +139,7 @@ __global__ __launch_bounds__(448) void att_mfma_kernel(const uint16_t *__restric
                     for (int r = 0; r < 4; ++r) m = fmaxf(m, st[c][r]);
                 }
             }
-            m = fmaxf(m, __shfl_xor(m, 16));
-            m = fmaxf(m, __shfl_xor(m, 32));
+            m = xrow_max(m);
             const float mb = m * scale_log2e;
             float z = 0.f;
 #pragma unroll
@@ -115,8 +153,7 @@ __global__ __launch_bounds__(448) void att_mfma_kernel(const uint16_t *__restric
                     }
                 }
             }
-            z += __shfl_xor(z, 16);
-            z += __shfl_xor(z, 32);
+            z = xrow_sum(z);
             const float inv = (qi < P) ? 1.0f / z : 0.0f;
 #pragma unroll
             for (int c = 0; c < kMaxTiles; ++c) {
@@ -134,11 +171,7 @@ __global__ __launch_bounds__(448) void att_mfma_kernel(const uint16_t *__restric
         if (c < nt) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                float v = acc[c][r];
-                v += __shfl_xor(v, 1);
-                v += __shfl_xor(v, 2);
-                v += __shfl_xor(v, 4);
-                v += __shfl_xor(v, 8);
+                const float v = row16_sum(acc[c][r]);
                 if (lr == 0) red[w * ld + 16 * c + 4 * lg + r] = v;
             }
         }
@@ -148,7 +181,7 @@ __global__ __launch_bounds__(448) void att_mfma_kernel(const uint16_t *__restric
     for (int j = tid; j < P; j += n_threads) {
         float s = 0.f;
         for (int ww = 0; ww < n_waves; ++ww) s += red[ww * ld + j];
-        out[((int64_t)f * n_part + part) * P + j] = s;
+        out[((int64_t)f * n_part + blockIdx.y) * P + j] = s;
     }
 }
 
@@ -159,17 +192,21 @@ bool att_mfma_supported(const mukv_config &c) {
 hipError_t launch_att_mfma(const Ctx &c, const ChunkArgs &a, float *out, int *n_part, hipStream_t st) {
     const int P = c.cfg.tokens_per_frame, Hq = c.cfg.n_q_heads, G = c.group;
     const int nt = (P + 15) / 16;
-    const int waves = (nt + 1) / 2;
-    // few frames: one head per workgroup to fill the chip; many frames: a whole KV group per
-    // workgroup so that K is staged once per group
-    const int hpw = ((int64_t)a.n_frames * Hq > 4096) ? G : 1;
-    *n_part = Hq / hpw;
+    // few frames: one head per workgroup and one strip per wave (fills the chip, shortest critical
+    // path); many frames: a whole KV group per workgroup, two strips per wave (K staged once per
+    // group, balanced waves)
+    const bool many = (int64_t)a.n_frames * Hq > 4096;
+    const int hpw = many ? G : 1;
+    const int pair = many ? 1 : 0;
+    const int n_split = (!pair && nt > 7) ? 2 : 1;
+    const int waves = pair ? (nt + 1) / 2 : (nt + n_split - 1) / n_split;
+    *n_part = (Hq / hpw) * n_split;
     const size_t lds = (size_t)nt * 16 * kLdsRow * 2 + (size_t)waves * nt * 16 * sizeof(float);
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)c.cfg.head_dim);
     const uint16_t *k = reinterpret_cast<const uint16_t *>(a.k) + (int64_t)c.ls * a.kv_sl;
     hipLaunchKernelGGL(att_mfma_kernel, dim3(a.n_frames, *n_part), dim3(waves * 64), lds, st,
                        reinterpret_cast<const uint16_t *>(a.q), a.q_sh, a.q_st, k, a.kv_sh, a.kv_st, P, nt, G, hpw,
-                       c.cfg.causal, scale_log2e, *n_part, out);
+                       c.cfg.causal, pair, n_split, scale_log2e, *n_part, out);
     return hipGetLastError();
 }
 

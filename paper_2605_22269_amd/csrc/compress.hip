@@ -255,7 +255,7 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
     __shared__ R red[8];
     __shared__ R vk[2];
     __shared__ int kl[kMaxP];
-    __shared__ unsigned char keepf[kMaxP];
+    __shared__ int wcnt[4];
     const int f = blockIdx.x, j = threadIdx.x;
     const int64_t gf = a.frame0 + f;
     const int P = a.P, kappa = a.kappa;
@@ -268,7 +268,14 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
             av = (R)a.att_in[(int64_t)f * P + j];
         } else {
             const R *pp = a.att + (int64_t)f * a.n_part * P + j;
-            for (int n = 0; n < a.n_part; ++n) av += pp[(int64_t)n * P];
+            for (int n0 = 0; n0 < a.n_part; n0 += 8) { // fixed summation order, 8 loads in flight
+                R t[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) t[u] = pp[(int64_t)(n0 + u < a.n_part ? n0 + u : a.n_part - 1) * P];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (n0 + u < a.n_part) av += t[u];
+            }
             av *= a.att_scale;
         }
     }
@@ -301,17 +308,21 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
             const R o = sc[i];
             rank += (o > fused) || (o == fused && i < j);
         }
-        keepf[j] = rank < kappa;
         if (rank == kappa - 1) vk[0] = fused;
         if (rank == kappa) vk[1] = fused;
     }
-    __syncthreads();
-    if (valid && rank < kappa) {
-        int pos = 0;
-        for (int i = 0; i < j; ++i) pos += keepf[i];
-        kl[pos] = j;
-        a.kept_idx[gf * kappa + pos] = j;
-        a.src_tok[(int64_t)f * kappa + pos] = f * P + j;
+    {   // position of a kept token among the kept ones: ballot prefix inside the wave + wave offsets
+        const bool kept = valid && rank < kappa;
+        const uint64_t bal = __ballot(kept);
+        if ((j & 63) == 0) wcnt[j >> 6] = __popcll(bal);
+        __syncthreads();
+        int pos = __popcll(bal & ((1ull << (j & 63)) - 1ull));
+        for (int w = 0; w < (j >> 6); ++w) pos += wcnt[w];
+        if (kept) {
+            kl[pos] = j;
+            a.kept_idx[gf * kappa + pos] = j;
+            a.src_tok[(int64_t)f * kappa + pos] = f * P + j;
+        }
     }
     if (j == 0) {
         const R mg = (kappa < P) ? vk[0] - vk[1] : (R)INFINITY;
@@ -355,11 +366,10 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
             Pair2<T> vk[kBatch], vv[kBatch];
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
-                if (r0 + u < kappa) {
-                    const int64_t off = col + (int64_t)kl[r0 + u] * a.st;
-                    vk[u] = *reinterpret_cast<const Pair2<T> *>(xk + off);
-                    vv[u] = *reinterpret_cast<const Pair2<T> *>(xv + off);
-                }
+                const int r = r0 + u < kappa ? r0 + u : kappa - 1; // clamped: loads stay unconditional
+                const int64_t off = col + (int64_t)kl[r] * a.st;
+                vk[u] = *reinterpret_cast<const Pair2<T> *>(xk + off);
+                vv[u] = *reinterpret_cast<const Pair2<T> *>(xv + off);
             }
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
@@ -397,6 +407,8 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
 // sums are exact for bf16 / fp32 payloads of ordinary dynamic range, so any chunking gives the
 // same bits.
 // ------------------------------------------------------------------------------------------
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 struct CompactArgs {
     const unsigned char *k, *v;  // chunk base, bytes
     int64_t sl_b, sh_b, st_b;    // byte strides layer / head / token
@@ -434,14 +446,16 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
                 double tk[8], tv[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    const bool in = fb + u < f1;
-                    tk[u] = in ? a.fsum_k[(fb + u) * a.C + c] : 0.0;
-                    tv[u] = in ? a.fsum_v[(fb + u) * a.C + c] : 0.0;
+                    const int64_t fr = fb + u < f1 ? fb + u : f1 - 1; // clamped: loads stay unconditional
+                    tk[u] = a.fsum_k[fr * a.C + c];
+                    tv[u] = a.fsum_v[fr * a.C + c];
                 }
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    sk += tk[u];
-                    sv += tv[u];
+                    if (fb + u < f1) {
+                        sk += tk[u];
+                        sv += tv[u];
+                    }
                 }
             }
             a.ssum_k[(int64_t)s * a.C + c] = sk;
@@ -456,15 +470,22 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
     const unsigned char *src = (kv ? a.v : a.k) + (int64_t)l * a.sl_b + (int64_t)g * a.sh_b;
     unsigned char *dst = (kv ? a.store_v : a.store_k) + ((int64_t)l * a.Hkv + g) * a.slab_b + a.dst_off_b;
     const int mask = (1 << a.log_upr) - 1;
+    // Loads are issued unconditionally on clamped unit numbers (first all row lookups, then all
+    // row reads) so that they overlap; only the stores are predicated.
     V tmp[ITER];
+    int row_tok[ITER];
     const int u0 = blockIdx.x * (256 * ITER) + threadIdx.x;
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
-        const int u = u0 + it * 256;
-        if (u < a.n_units) {
-            const int row = u >> a.log_upr, part = u & mask;
-            tmp[it] = *reinterpret_cast<const V *>(src + (int64_t)a.src_tok[row] * a.st_b + (int64_t)part * sizeof(V));
-        }
+        int u = u0 + it * 256;
+        u = u < a.n_units ? u : a.n_units - 1;
+        row_tok[it] = a.src_tok[u >> a.log_upr];
+    }
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        int u = u0 + it * 256;
+        u = u < a.n_units ? u : a.n_units - 1;
+        tmp[it] = *reinterpret_cast<const V *>(src + (int64_t)row_tok[it] * a.st_b + (int64_t)(u & mask) * sizeof(V));
     }
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
@@ -606,7 +627,7 @@ static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, hipStream_t s
     constexpr int ITER = 4;
     const int gx = (k.n_units + 256 * ITER - 1) / (256 * ITER);
     const int gy = k.n_slab + (seg_last - k.seg_first + 1);
-    hipLaunchKernelGGL((compact_kernel<uint4, ITER>), dim3(gx, gy), dim3(256), 0, st, k);
+    hipLaunchKernelGGL((compact_kernel<u32x4, ITER>), dim3(gx, gy), dim3(256), 0, st, k);
     return hipGetLastError();
 }
 

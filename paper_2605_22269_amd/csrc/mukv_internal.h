@@ -114,16 +114,49 @@ size_t att_generic_lds_bytes(int P, int D, size_t r_size);
 __device__ __forceinline__ float to_float(uint16_t bits) { return __uint_as_float((uint32_t)bits << 16); }
 __device__ __forceinline__ float to_float(float x) { return x; }
 
-__device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-    return x;
+// Cross-lane helpers that stay in the vector ALU (no LDS traffic).
+// dpp_lane: value of another lane of the same 16-lane row, chosen by a DPP control word.
+template <int CTRL>
+__device__ __forceinline__ float dpp_lane(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
 }
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
-    return x;
+constexpr int kDppQuadSwap1 = 0xB1;     // quad_perm [1,0,3,2]
+constexpr int kDppQuadSwap2 = 0x4E;     // quad_perm [2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;
+constexpr int kDppRowMirror = 0x140;
+
+// sum / max over the 16 lanes of a row, result in every lane of the row
+__device__ __forceinline__ float row16_sum(float v) {
+    v += dpp_lane<kDppQuadSwap1>(v);
+    v += dpp_lane<kDppQuadSwap2>(v);
+    v += dpp_lane<kDppRowHalfMirror>(v);
+    v += dpp_lane<kDppRowMirror>(v);
+    return v;
 }
+__device__ __forceinline__ float row16_max(float v) {
+    v = fmaxf(v, dpp_lane<kDppQuadSwap1>(v));
+    v = fmaxf(v, dpp_lane<kDppQuadSwap2>(v));
+    v = fmaxf(v, dpp_lane<kDppRowHalfMirror>(v));
+    v = fmaxf(v, dpp_lane<kDppRowMirror>(v));
+    return v;
+}
+// sum / max over the four lanes that share lane % 16 (one per row), result in all four:
+// v_permlane16_swap exchanges odd rows of one operand with even rows of the other,
+// v_permlane32_swap the upper half-wave of one with the lower half-wave of the other.
+__device__ __forceinline__ float xrow_sum(float v) {
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+__device__ __forceinline__ float xrow_max(float v) {
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float wave_max(float x) { return xrow_max(row16_max(x)); }
+__device__ __forceinline__ float wave_sum(float x) { return xrow_sum(row16_sum(x)); }
 __device__ __forceinline__ double wave_sum(double x) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);

@@ -43,9 +43,13 @@ __global__ __launch_bounds__(1024) void pool_question_kernel(const T *__restrict
         for (int tb = ts; tb < nq; tb += 32) {
             float v[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = (tb + 4 * u < nq) ? to_float(p[(int64_t)(tb + 4 * u) * tstride]) : 0.f;
+            for (int u = 0; u < 8; ++u) {
+                const int t = tb + 4 * u < nq ? tb + 4 * u : nq - 1; // clamped: loads stay unconditional
+                v[u] = to_float(p[(int64_t)t * tstride]);
+            }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) s += (double)v[u];
+            for (int u = 0; u < 8; ++u)
+                if (tb + 4 * u < nq) s += (double)v[u];
         }
         part[ts * GD + e] = s;
     }
@@ -116,7 +120,8 @@ __global__ __launch_bounds__(256) void score_blocks_kernel(ScoreArgs a) {
 #pragma unroll
         for (int t = 0; t < 16; ++t) {
             const int c = lane + 64 * t;
-            row[t] = (c < C) ? src[c] : 0.f;
+            const float x = src[c < C ? c : C - 1]; // clamped: loads stay unconditional
+            row[t] = (c < C) ? x : 0.f;
         }
     }
     double rr = 0.0;
@@ -129,7 +134,7 @@ __global__ __launch_bounds__(256) void score_blocks_kernel(ScoreArgs a) {
 #pragma unroll
         for (int t = 0; t < 16; ++t) {
             const int c = lane + 64 * t;
-            if (c < C) dot += (double)row[t] * qb[c];
+            dot += (double)row[t] * qb[c < C ? c : C - 1]; // row[t] is 0 past C
         }
         dot = wave_sum(dot);
         if (lane == 0) {
@@ -189,7 +194,7 @@ __device__ int block_topk(KeyFn key, int n, int m, int *out, SelShared &sh, uint
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int i = i0 + u * kSelThreads;
-            kk[u] = i < n_c ? key(i) : kNoKey;
+            kk[u] = key(i < n_c ? i : n_c - 1); // clamped: loads stay unconditional
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -497,17 +502,18 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(GatherArgs a) {
     const unsigned char *src = (kv ? a.store_v : a.store_k) + ((int64_t)l * a.Hkv + g) * a.slab_b;
     unsigned char *dst = (kv ? a.v_out : a.k_out) + (((int64_t)b * a.L + l) * a.Hkv + g) * (a.k_frame * a.frame_b);
     const int n_units = a.k_frame * a.units_per_frame;
+    // unconditional loads on clamped unit numbers / slot 0's frame, zero selected afterwards
     uint4 tmp[ITER];
     const int u0 = blockIdx.x * (256 * ITER) + tid;
+    const int fr_any = n_valid > 0 ? slot_frame[0] : 0;
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
-        const int u = u0 + it * 256;
-        tmp[it] = make_uint4(0u, 0u, 0u, 0u);
-        if (u < n_units) {
-            const int slot = u / a.units_per_frame, part = u - slot * a.units_per_frame;
-            const int fr = slot_frame[slot];
-            if (fr >= 0) tmp[it] = *reinterpret_cast<const uint4 *>(src + (int64_t)fr * a.frame_b + (int64_t)part * 16);
-        }
+        int u = u0 + it * 256;
+        u = u < n_units ? u : n_units - 1;
+        const int slot = u / a.units_per_frame, part = u - slot * a.units_per_frame;
+        const int fr = slot_frame[slot];
+        const uint4 x = *reinterpret_cast<const uint4 *>(src + (int64_t)(fr >= 0 ? fr : fr_any) * a.frame_b + (int64_t)part * 16);
+        tmp[it] = fr >= 0 ? x : make_uint4(0u, 0u, 0u, 0u);
     }
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
