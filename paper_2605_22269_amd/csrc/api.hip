@@ -15,7 +15,7 @@ struct mukv_ctx {
 
 namespace {
 
-constexpr double kDefaultRefineMargin = 1e-4;
+constexpr double kDefaultRefineMargin = 2e-5;
 
 bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 

@@ -1,0 +1,135 @@
+"""GPU parity at the full sizes of the five benchmark configurations, in the launch
+configuration bench.py times (same chunking, same kernels, same retrieval
+parameters).  The oracle is fast enough on the machine's host cores to redo every
+frame, so nothing is sampled: every kept index, every stored byte, every block
+key, and the retrieval + gather of every question is compared."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from mukv_testlib import TOL, gpu_context, np_view, oracle_config
+from oracle import oracle as orc
+from paper_2605_22269_amd import binding as mk
+from paper_2605_22269_amd import synth
+
+pytestmark = pytest.mark.gpu
+W = synth.WORKLOADS
+
+
+def run_full(w: synth.Workload, seed: int, oracle_chunk: int = 64, max_questions: int = 1):
+    """Streams the workload through the GPU library in w.chunk_frames chunks and through
+    the oracle in oracle_chunk chunks (its results do not depend on the chunking)."""
+    assert oracle_chunk % w.chunk_frames == 0
+    gpu = gpu_context(w, max_frames=w.n_frames, max_chunk_frames=w.chunk_frames, max_questions=max_questions)
+    ref = orc.OracleMuKV(oracle_config(w))
+    stream = synth.SynthStream(w, seed, device="cuda")
+    P, tol = w.tokens_per_frame, TOL[w.dtype]
+    worst = 0.0
+    t_orc = 0.0
+    done = 0
+    while done < w.n_frames:
+        n_big = min(oracle_chunk, w.n_frames - done)
+        k, v, q = stream.next_chunk(n_big)
+        fused_gpu = []
+        for f0 in range(0, n_big, w.chunk_frames):
+            n = min(w.chunk_frames, n_big - f0)
+            sl = slice(f0 * P, (f0 + n) * P)
+            fused_gpu.append(gpu.compress_chunk(k[:, :, sl], v[:, :, sl], q[:, sl], want_signals=True)["fused"])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        so = ref.compress_chunk(np_view(k), np_view(v), q_last=np_view(q))
+        t_orc += time.perf_counter() - t0
+        worst = max(worst, float(np.abs(torch.cat(fused_gpu).cpu().numpy() - so["fused"]).max()))
+        done += n_big
+        del k, v, q
+    assert worst <= tol, f"fused score error {worst}"
+    st = gpu.state()
+    torch.cuda.synchronize()
+    mism = np.nonzero((st["kept_idx"].cpu().numpy() != ref.kept).any(axis=1))[0]
+    assert mism.size == 0, f"kept indices differ in frames {mism[:10]} (margins {st['margin'].cpu().numpy()[mism[:10]]})"
+    for name, want in (("rep_frame_k", ref.rep_frame_k), ("rep_frame_v", ref.rep_frame_v),
+                       ("rep_patch_k", ref.rep_patch_k), ("rep_patch_v", ref.rep_patch_v),
+                       ("rep_seg_k", ref.seg_reps(which="k")), ("rep_seg_v", ref.seg_reps(which="v"))):
+        got = st[name].cpu().numpy()
+        assert np.abs(got - want).max() <= tol, name
+        np.testing.assert_array_equal(got, want.astype(np.float32), err_msg=name)
+    np.testing.assert_array_equal(st["cnt_patch"].cpu().numpy(), ref.cnt_patch)
+    ok, ov = ref.store()
+    kap = ref.kappa
+    step = 256 * kap                                    # compare the store in slices of 256 frames
+    for r0 in range(0, w.n_frames * kap, step):
+        r1 = min(r0 + step, w.n_frames * kap)
+        gk, gv = gpu.store_rows(r0, r1)
+        np.testing.assert_array_equal(np_view(gk), ok[:, :, r0:r1])
+        np.testing.assert_array_equal(np_view(gv), ov[:, :, r0:r1])
+    info = {"refined": int(st["refined"].sum()), "min_margin": float(st["margin"].min()), "max_fused_err": worst,
+            "oracle_s": t_orc}
+    return gpu, ref, info
+
+
+def check_questions(w, gpu, ref, questions, mode=mk.MUKV_SEMI):
+    offs = np.zeros(len(questions) + 1, np.int32)
+    offs[1:] = np.cumsum([q.shape[0] for q in questions])
+    qt = torch.cat(questions).cuda().contiguous()
+    out = gpu.retrieve(qt, torch.from_numpy(offs).cuda(), mode=mode, k_seg=w.k_seg, k_frame=w.k_frame,
+                       lambda_frame=w.lambda_frame)
+    kg, vg, nt = gpu.gather_kv(out["frame_idx"])
+    torch.cuda.synchronize()
+    hits = []
+    for b, q in enumerate(questions):
+        r = ref.retrieve(np_view(q.cpu()), orc.RetrieveParams(mode, w.k_seg, w.k_frame, w.lambda_frame))
+        np.testing.assert_array_equal(out["seg_idx"][b].cpu().numpy(), r["seg_idx"])
+        np.testing.assert_array_equal(out["frame_idx"][b].cpu().numpy(), r["frame_idx"])
+        assert np.abs(out["seg_score"][b].cpu().numpy() - r["seg_score"]).max() <= 1e-5
+        assert np.abs(out["frame_score"][b].cpu().numpy() - r["frame_score"]).max() <= 1e-5
+        ko, vo, n_tok = ref.gather(r["frame_idx"])
+        assert int(nt[b]) == n_tok
+        np.testing.assert_array_equal(np_view(kg[b]), ko)
+        np.testing.assert_array_equal(np_view(vg[b]), vo)
+        hits.append(r["frame_idx"])
+    return hits
+
+
+def test_config2_7b_256_frames():
+    w = W["7b"]
+    gpu, ref, info = run_full(w, seed=1002)
+    print("7b:", info)
+    for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
+        check_questions(w, gpu, ref, [synth.random_question(w, w.question_tokens, 77)], mode)
+    gpu.close()
+
+
+def test_config3_and_4_one_hour_stream():
+    w = W["hour"]
+    wq = W["retrieval"]
+    gpu, ref, info = run_full(w, seed=1003, max_questions=wq.n_questions)
+    print("hour:", info)
+    # config 3: one 32-token question, all three retrieval modes
+    for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
+        check_questions(w, gpu, ref, [synth.random_question(w, w.question_tokens, 78)], mode)
+    # config 4: 64 concurrent questions of 16..64 tokens with planted target frames (planted from
+    # the ORACLE's frame keys), one batched retrieve + gather
+    lens = synth.question_lengths(wq.n_questions, 16, wq.question_tokens, 79)
+    g = torch.Generator().manual_seed(80)
+    qs, targets = [], []
+    for i, n in enumerate(lens):
+        tgt = torch.randint(0, w.n_frames, (4,), generator=g)
+        targets.append(set(tgt.tolist()))
+        qs.append(synth.planted_question(wq, torch.from_numpy(ref.rep_frame_k[tgt.numpy()]), n, 81 + i))
+    hits = check_questions(wq, gpu, ref, qs)
+    found = sum(len(t & set(int(x) for x in h)) for t, h in zip(targets, hits))
+    total = sum(len(t) for t in targets)
+    print(f"retrieval-heavy: {found}/{total} planted frames retrieved")
+    assert found >= 0.9 * total
+    gpu.close()
+
+
+def test_config5_72b_shape():
+    w = W["72b"]
+    gpu, ref, info = run_full(w, seed=1005, oracle_chunk=64)
+    print("72b:", info)
+    for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
+        check_questions(w, gpu, ref, [synth.random_question(w, w.question_tokens, 82)], mode)
+    gpu.close()
