@@ -27,7 +27,75 @@ constexpr int kMaxTiles = 13;  // 13 * 16 = 208 >= P
 constexpr int kLdsRow = 136;   // bf16 elements per LDS key row: 128 + 8 of padding (272 B)
 constexpr int kHeadDim = 128;
 
-__global__ __launch_bounds__(448) void att_mfma_kernel(const uint16_t *__restrict__ q, int64_t q_sh, int64_t q_st,
+struct JobArgs {
+    const uint16_t *a_base; // this lane's key-operand address in LDS key tile 0
+    int q0;                 // first of this lane's four query positions in the frame
+    int lr;                 // lane % 16
+    int P;
+    bool diag;              // causal: the last tile holds the diagonal
+    bool tail;              // the last tile holds keys past P
+    float scale_log2e;
+};
+
+// One (head, strip) job over the first NTL key tiles, fully unrolled for that count so that no
+// arithmetic is spent on tiles above the causal diagonal.  Score tiles S = Q K^T (A operand: the
+// strip's Q, B operand: a key tile from LDS): a lane then owns one key column (lane % 16) and the
+// four query rows 4*(lane/16)..+3 of every tile.  Row statistics of the exact softmax are an
+// in-lane pass over the tiles plus a 16-lane DPP reduction; the normalised probabilities of the
+// lane's four rows are added into ONE accumulator per tile (13 registers for the whole frame).
+// `after_mfma` runs once the Q operand registers are free again.
+template <int NTL, typename F>
+__device__ __forceinline__ void strip_job(const JobArgs &ja, const bf16x8 *qv, float *acc, F after_mfma) {
+    f32x4 st[NTL];
+#pragma unroll
+    for (int c = 0; c < NTL; ++c) {
+        f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ja.a_base + c * 16 * kLdsRow + 32 * kk);
+            d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qv[kk], kf, d, 0, 0, 0);
+        }
+        st[c] = d;
+    }
+    after_mfma();
+    if (ja.diag || ja.tail) { // only the last tile can need masking
+        constexpr int c = NTL - 1;
+        const int j = 16 * c + ja.lr;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const bool ok = (j < ja.P) && (!ja.diag || j <= ja.q0 + r);
+            st[c][r] = ok ? st[c][r] : -INFINITY;
+        }
+    }
+    float m[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+    for (int c = 0; c < NTL; ++c)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) m[r] = fmaxf(m[r], st[c][r]);
+    float mb[4], z[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) mb[r] = row16_max(m[r]) * ja.scale_log2e;
+#pragma unroll
+    for (int c = 0; c < NTL; ++c)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float p = __builtin_amdgcn_exp2f(st[c][r] * ja.scale_log2e - mb[r]);
+            st[c][r] = p;
+            z[r] += p;
+        }
+    float inv[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) inv[r] = (ja.q0 + r < ja.P) ? 1.0f / row16_sum(z[r]) : 0.0f;
+#pragma unroll
+    for (int c = 0; c < NTL; ++c) {
+        float t = acc[c];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) t += st[c][r] * inv[r];
+        acc[c] = t;
+    }
+}
+
+__global__ __launch_bounds__(448) __attribute__((amdgpu_waves_per_eu(4, 4))) void att_mfma_kernel(const uint16_t *__restrict__ q, int64_t q_sh, int64_t q_st,
                                                        const uint16_t *__restrict__ k, int64_t k_sh, int64_t k_st,
                                                        int P, int nt, int G, int hpw, int causal, int pair, int n_split,
                                                        float scale_log2e, int n_part, float *__restrict__ out) {
@@ -36,7 +104,8 @@ __global__ __launch_bounds__(448) void att_mfma_kernel(const uint16_t *__restric
     float *red = reinterpret_cast<float *>(smem_raw + (size_t)nt * 16 * kLdsRow * 2); // [waves][nt*16]
     const int f = blockIdx.x, part = blockIdx.y / n_split, sp = blockIdx.y - part * n_split;
     const int h0 = part * hpw, g = h0 / G;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6); // wave-uniform: strip choices become scalar branches
     const int n_threads = blockDim.x;
     const int lr = lane & 15, lg = lane >> 4;
 
@@ -59,9 +128,8 @@ __global__ __launch_bounds__(448) void att_mfma_kernel(const uint16_t *__restric
         for (int kk = 0; kk < 4; ++kk) dst[kk] = *reinterpret_cast<const bf16x8 *>(qp + 32 * kk);
     };
     const int n_jobs = active ? hpw * n_strips : 0; // (head, strip) pairs of this wave, strip fastest
-    bf16x8 qv[4], qn[4];
-    load_q(h0, active ? sA : 0, qv); // jobs 0 and 1: in flight while K is staged
-    if (n_jobs > 1) load_q(h0 + 1 / n_strips, (1 % n_strips) ? sB : sA, qn);
+    bf16x8 qv[4];
+    load_q(h0, active ? sA : 0, qv); // job 0: in flight while K is staged
 
     // stage K of (frame, KV head) in LDS; rows past P are zero.  Loads are unconditional on a
     // clamped row and issued in batches of 4 before the LDS stores.
@@ -87,93 +155,48 @@ __global__ __launch_bounds__(448) void att_mfma_kernel(const uint16_t *__restric
     }
     __syncthreads();
 
-    f32x4 acc[kMaxTiles];
+    float acc[kMaxTiles];
 #pragma unroll
-    for (int c = 0; c < kMaxTiles; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < kMaxTiles; ++c) acc[c] = 0.f;
 
     const uint16_t *a_base = Ks + lr * kLdsRow + 8 * lg;
     const bool tail = (P & 15) != 0;
     for (int job = 0; job < n_jobs; ++job) {
-        {
-            const int hh = job / n_strips, si = job - hh * n_strips;
-            const int s = si ? sB : sA;
-            const int qi = 16 * s + lr;
-            const int cmax = causal ? s : nt - 1;
-            f32x4 st[kMaxTiles];
-#pragma unroll
-            for (int c = 0; c < kMaxTiles; ++c) {
-                if (c <= cmax) {
-                    f32x4 d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int kk = 0; kk < 4; ++kk) {
-                        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(a_base + c * 16 * kLdsRow + 32 * kk);
-                        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qv[kk], d, 0, 0, 0);
-                    }
-                    st[c] = d;
-                }
+        const int hh = job / n_strips, si = job - hh * n_strips;
+        const int s = si ? sB : sA;
+        const int ntl = __builtin_amdgcn_readfirstlane(causal ? s + 1 : nt); // key tiles this strip sees
+        JobArgs ja;
+        ja.a_base = a_base;
+        ja.q0 = 16 * s + 4 * lg;
+        ja.lr = lr;
+        ja.P = P;
+        ja.diag = causal != 0;
+        ja.tail = tail && ntl == nt;
+        ja.scale_log2e = scale_log2e;
+        // as soon as the MFMAs of this job are done its Q registers take the next job's Q; the
+        // softmax below and the other resident waves cover the load latency
+        auto next_q = [&]() {
+            if (job + 1 < n_jobs) {
+                const int hn = (job + 1) / n_strips, sn = (job + 1) - hn * n_strips;
+                load_q(h0 + hn, sn ? sB : sA, qv);
             }
-            if (job + 1 < n_jobs) { // Q of job+1 arrived long ago; fetch job+2 behind the softmax below
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) qv[kk] = qn[kk];
-                if (job + 2 < n_jobs) {
-                    const int hn = (job + 2) / n_strips, sn = (job + 2) - hn * n_strips;
-                    load_q(h0 + hn, sn ? sB : sA, qn);
-                }
-            }
-            // masks: keys after the query on the diagonal tile, keys past P on the last tile
-            float m = -INFINITY;
-#pragma unroll
-            for (int c = 0; c < kMaxTiles; ++c) {
-                if (c <= cmax) {
-                    const bool diag = causal && c == s;
-                    const bool last = tail && c == nt - 1;
-                    if (diag || last) {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const int j = 16 * c + 4 * lg + r;
-                            const bool ok = (j < P) && (!diag || j <= qi);
-                            st[c][r] = ok ? st[c][r] : -INFINITY;
-                        }
-                    }
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) m = fmaxf(m, st[c][r]);
-                }
-            }
-            m = xrow_max(m);
-            const float mb = m * scale_log2e;
-            float z = 0.f;
-#pragma unroll
-            for (int c = 0; c < kMaxTiles; ++c) {
-                if (c <= cmax) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const float p = __builtin_amdgcn_exp2f(st[c][r] * scale_log2e - mb);
-                        st[c][r] = p;
-                        z += p;
-                    }
-                }
-            }
-            z = xrow_sum(z);
-            const float inv = (qi < P) ? 1.0f / z : 0.0f;
-#pragma unroll
-            for (int c = 0; c < kMaxTiles; ++c) {
-                if (c <= cmax) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[c][r] += st[c][r] * inv;
-                }
-            }
+        };
+        switch (ntl) {
+#define MUKV_JOB_CASE(N) case N: strip_job<N>(ja, qv, acc, next_q); break;
+            MUKV_JOB_CASE(1) MUKV_JOB_CASE(2) MUKV_JOB_CASE(3) MUKV_JOB_CASE(4) MUKV_JOB_CASE(5)
+            MUKV_JOB_CASE(6) MUKV_JOB_CASE(7) MUKV_JOB_CASE(8) MUKV_JOB_CASE(9) MUKV_JOB_CASE(10)
+            MUKV_JOB_CASE(11) MUKV_JOB_CASE(12) MUKV_JOB_CASE(13)
+#undef MUKV_JOB_CASE
+        default: break;
         }
     }
-    // column sums over the 16 query lanes, then over the waves in a fixed order
+    // column sums: add the four lane groups (the other query rows), then the waves in a fixed order
     const int ld = nt * 16;
 #pragma unroll
     for (int c = 0; c < kMaxTiles; ++c) {
         if (c < nt) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float v = row16_sum(acc[c][r]);
-                if (lr == 0) red[w * ld + 16 * c + 4 * lg + r] = v;
-            }
+            const float v = xrow_sum(acc[c]);
+            if (lg == 0) red[w * ld + 16 * c + lr] = v;
         }
     }
     __syncthreads();
