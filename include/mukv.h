@@ -85,7 +85,10 @@ typedef struct mukv_config {
     int32_t max_questions;          /* largest batch of one mukv_retrieve / gather     */
     int32_t device_id;              /* HIP device ordinal                              */
     int32_t att_path;               /* mukv_att_path; AUTO picks MFMA when supported   */
-    int32_t reserved0;
+    int32_t batch_chunks;           /* 0 or 1: every mukv_compress_chunk enqueues its kernels at
+                                       once.  N > 1 (at most 32): the library gathers N chunks
+                                       and processes them with one chain of launches; see
+                                       mukv_compress_chunk for what that asks of the caller    */
     double refine_margin;           /* frames whose selection margin (gap between the
                                        last kept and first dropped fused score) is
                                        below this are re-scored in fp64 before the
@@ -124,7 +127,8 @@ typedef struct mukv_retrieve_params {
  * mukv_destroy.  Tables are valid for frames < n_frames once the stream has
  * passed the calls that produced them. */
 typedef struct mukv_state {
-    int64_t n_frames;          /* frames ingested                                     */
+    int64_t n_frames;          /* frames submitted (tables cover them once the gathered
+                                  chunks have been flushed and the stream has run)    */
     int64_t n_segments;        /* ceil(n_frames / F); the last may be partial         */
     int64_t n_kept_tokens;     /* n_frames * kappa                                    */
     int64_t store_token_capacity; /* max_frames * kappa                               */
@@ -151,8 +155,12 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out);
  * streams it used.  NULL is accepted. */
 int mukv_destroy(mukv_ctx *ctx);
 
-/* Forgets the stream (n_frames = 0) without freeing memory. */
+/* Forgets the stream (n_frames = 0, gathered chunks dropped) without freeing memory. */
 int mukv_reset(mukv_ctx *ctx);
+
+/* Enqueues the kernels of the chunks gathered so far (batch_chunks > 1); a no-op
+ * otherwise.  Does not synchronise. */
+int mukv_flush(mukv_ctx *ctx);
 
 /*
  * Offline step for n_frames new frames (Sec. 3.3).  For every frame: Eq. 1
@@ -170,6 +178,16 @@ int mukv_reset(mukv_ctx *ctx);
  *               alpha > 0 needs exactly one of q_last / att_signal;
  *               alpha == 0 ignores both
  *   sig         optional outputs, may be NULL
+ *
+ * With batch_chunks > 1 the call only records the chunk until batch_chunks
+ * chunks are gathered (or mukv_flush, mukv_retrieve or mukv_gather_kv is
+ * called); the kernels for all of them are then enqueued together on the
+ * stream the chunks were submitted with.  The caller must keep the chunk's
+ * input buffers (and `sig` outputs) alive and unchanged until the stream has
+ * passed that later call.  A chunk whose stream, strides or attention source
+ * differ from the gathered ones flushes them first.  Capacity errors are
+ * reported by the call that submits the chunk, launch errors by the call that
+ * flushes.
  *
  * Errors: INVALID_ARG (null k/v, missing or doubled attention source),
  * SHAPE (n_frames < 1), CAPACITY (n_frames > max_chunk_frames or the cache is

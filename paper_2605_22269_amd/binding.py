@@ -29,7 +29,7 @@ class mukv_config(C.Structure):
         ("tokens_per_frame", C.c_int32), ("frames_per_segment", C.c_int32), ("superpatches_per_frame", C.c_int32),
         ("dtype", C.c_int32), ("keep_ratio", C.c_double), ("alpha", C.c_double), ("causal", C.c_int32),
         ("score_layer", C.c_int32), ("max_frames", C.c_int32), ("max_chunk_frames", C.c_int32),
-        ("max_questions", C.c_int32), ("device_id", C.c_int32), ("att_path", C.c_int32), ("reserved0", C.c_int32),
+        ("max_questions", C.c_int32), ("device_id", C.c_int32), ("att_path", C.c_int32), ("batch_chunks", C.c_int32),
         ("refine_margin", C.c_double),
     ]
 
@@ -67,7 +67,7 @@ class mukv_profile(C.Structure):
     _fields_ = [("ms", C.c_double * len(KERNEL_NAMES)), ("launches", C.c_int64 * len(KERNEL_NAMES))]
 
 
-EXPORTS = ("mukv_create", "mukv_destroy", "mukv_reset", "mukv_compress_chunk", "mukv_retrieve",
+EXPORTS = ("mukv_create", "mukv_destroy", "mukv_reset", "mukv_flush", "mukv_compress_chunk", "mukv_retrieve",
            "mukv_gather_kv", "mukv_profile_begin", "mukv_profile_end", "mukv_get_state", "mukv_strerror")
 
 _lib = None
@@ -86,6 +86,7 @@ def load():
     lib.mukv_create.argtypes = [C.POINTER(mukv_config), C.POINTER(vp)]
     lib.mukv_destroy.argtypes = [vp]
     lib.mukv_reset.argtypes = [vp]
+    lib.mukv_flush.argtypes = [vp]
     lib.mukv_compress_chunk.argtypes = [vp, vp, vp, C.POINTER(mukv_strides), vp, C.POINTER(mukv_strides), vp, i32, vp,
                                         C.POINTER(mukv_signals_out)]
     lib.mukv_retrieve.argtypes = [vp, vp, vp, i32, C.POINTER(mukv_retrieve_params), vp, vp, vp, vp, vp]
@@ -125,6 +126,10 @@ def mukv_destroy(h):
 
 def mukv_reset(h):
     _check(load().mukv_reset(h), "mukv_reset")
+
+
+def mukv_flush(h):
+    _check(load().mukv_flush(h), "mukv_flush")
 
 
 def mukv_compress_chunk(h, k_ptr, v_ptr, kv_strides, q_ptr, q_strides, att_ptr, n_frames, stream, sig=None):
@@ -185,11 +190,11 @@ class MuKV:
     def __init__(self, *, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, frames_per_segment,
                  superpatches_per_frame=4, dtype=torch.bfloat16, keep_ratio=0.25, alpha=0.7, causal=True,
                  score_layer=-1, max_frames=4096, max_chunk_frames=8, max_questions=1, device_id=0,
-                 att_path=MUKV_ATT_AUTO, refine_margin=-1.0):
+                 att_path=MUKV_ATT_AUTO, refine_margin=-1.0, batch_chunks=1):
         self.cfg = mukv_config(n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, frames_per_segment,
                                superpatches_per_frame, MUKV_BF16 if dtype == torch.bfloat16 else MUKV_F32,
                                keep_ratio, alpha, int(causal), score_layer, max_frames, max_chunk_frames,
-                               max_questions, device_id, att_path, 0, refine_margin)
+                               max_questions, device_id, att_path, batch_chunks, refine_margin)
         self.dtype = dtype
         self.device = torch.device("cuda", device_id)
         self.h = mukv_create(self.cfg)
@@ -209,6 +214,9 @@ class MuKV:
 
     def reset(self):
         mukv_reset(self.h)
+
+    def flush(self):
+        mukv_flush(self.h)
 
     @property
     def n_frames(self):
@@ -280,6 +288,7 @@ class MuKV:
 
     def state(self):
         """Copies of the tables for the frames ingested so far (device tensors)."""
+        mukv_flush(self.h)
         s = mukv_get_state(self.h)
         c = self.cfg
         n, S, Ckv, kap = s.n_frames, c.superpatches_per_frame, s.c_kv, s.kappa
@@ -301,6 +310,7 @@ class MuKV:
     def store_rows(self, row0, row1):
         """Copy of store rows [row0, row1) of every (layer, head): (K, V), each
         [L][Hkv][row1-row0][D]."""
+        mukv_flush(self.h)
         s = mukv_get_state(self.h)
         c = self.cfg
         esz = 2 if self.dtype == torch.bfloat16 else 4

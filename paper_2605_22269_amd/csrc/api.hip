@@ -15,7 +15,7 @@ struct mukv_ctx {
 
 namespace {
 
-constexpr double kDefaultRefineMargin = 2e-5;
+constexpr double kDefaultRefineMargin = 1e-5;
 
 bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
@@ -39,6 +39,8 @@ int validate_config(const mukv_config *cfg) {
     if (cfg->superpatches_per_frame > cfg->tokens_per_frame) return MUKV_ERR_SHAPE;
     if (cfg->score_layer < -1 || cfg->score_layer >= cfg->n_layers) return MUKV_ERR_SHAPE;
     if (cfg->att_path < MUKV_ATT_AUTO || cfg->att_path > MUKV_ATT_MFMA) return MUKV_ERR_INVALID_ARG;
+    if (cfg->batch_chunks < 0) return MUKV_ERR_INVALID_ARG;
+    if (cfg->batch_chunks > mukv::kMaxSlots) return MUKV_ERR_UNSUPPORTED;
     const int kappa = (int)std::floor(cfg->keep_ratio * cfg->tokens_per_frame + 1e-9);
     if (kappa < 1) return MUKV_ERR_INVALID_ARG;
     if (!pow2(cfg->head_dim) || cfg->head_dim < 16 || cfg->head_dim > 128) return MUKV_ERR_UNSUPPORTED;
@@ -59,7 +61,7 @@ void free_all(Ctx &c) {
     void *ptrs[] = {c.store_k,    c.store_v,    c.kept_idx,  c.rep_frame_k, c.rep_frame_v, c.rep_patch_k,
                     c.rep_patch_v, c.rep_seg_k, c.rep_seg_v, c.cnt_patch,   c.fsum_k,      c.fsum_v,
                     c.ssum_k,      c.ssum_v,    c.margin,      c.refined,   c.att_part,  c.fft_sig,     c.att64,       c.fft64,
-                    c.src_tok,     c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail};
+                    c.src_tok,     c.flag_list,   c.flag_count, c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -103,13 +105,18 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     c.use_mfma = cfg->att_path != MUKV_ATT_GENERIC && mfma_supported(*cfg);
     c.margin_thr = cfg->refine_margin < 0.0 ? kDefaultRefineMargin : cfg->refine_margin;
     c.n_frames = 0;
+    c.n_done = 0;
+    c.batch_chunks = cfg->batch_chunks < 1 ? 1 : cfg->batch_chunks;
+    c.max_batch_frames = c.batch_chunks * cfg->max_chunk_frames;
+    c.pending = new (std::nothrow) std::vector<mukv::PendingChunk>();
+    c.p_stream = nullptr;
     c.store_cap = (int64_t)cfg->max_frames * c.kappa;
     c.profiling = false;
     c.prof = new (std::nothrow) std::vector<mukv::ProfEntry>();
 
     const size_t store_bytes = (size_t)cfg->n_layers * cfg->n_kv_heads * c.store_cap * cfg->head_dim * c.esz;
     const size_t MF = cfg->max_frames, C = c.c_kv, S = cfg->superpatches_per_frame, P = cfg->tokens_per_frame;
-    const size_t MC = cfg->max_chunk_frames, MQ = cfg->max_questions, Hq = cfg->n_q_heads;
+    const size_t MC = c.max_batch_frames, MQ = cfg->max_questions, Hq = cfg->n_q_heads;
     hipError_t e = hipSuccess;
     auto ok = [&](hipError_t r) {
         if (e == hipSuccess) e = r;
@@ -130,19 +137,24 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(dalloc(&c.ssum_v, (size_t)c.max_segments * C));
     ok(dalloc(&c.margin, MF));
     ok(dalloc(&c.refined, MF));
-    ok(dalloc(&c.att_part, MC * Hq * 2 * P)); // up to two partial rows per head
+    const size_t n_part_max = Hq * ((P + 31) / 32 > 2 ? (P + 31) / 32 : 2); // partial rows per frame
+    ok(dalloc(&c.att_part, MC * n_part_max * P));
     ok(dalloc(&c.fft_sig, MC * P));
-    ok(dalloc(&c.att64, MC * Hq * P));
+    ok(dalloc(&c.att64, MC * n_part_max * P));
     ok(dalloc(&c.fft64, MC * P));
     ok(dalloc(&c.src_tok, MC * c.kappa));
+    ok(dalloc(&c.flag_list, MC));
+    ok(dalloc(&c.flag_count, 1));
+    if (e == hipSuccess) ok(hipMemset(c.flag_count, 0, sizeof(int32_t)));
     ok(dalloc(&c.qbar, MQ * C));
     ok(dalloc(&c.qq, MQ * cfg->n_kv_heads));
     ok(dalloc(&c.s_frm, MQ * MF));
     ok(dalloc(&c.s_seg, MQ * (size_t)c.max_segments));
     ok(dalloc(&c.seg_tail, 2 * C));
-    if (e != hipSuccess || !c.prof) {
+    if (e != hipSuccess || !c.prof || !c.pending) {
         free_all(c);
         delete c.prof;
+        delete c.pending;
         delete h;
         (void)hipGetLastError();
         return MUKV_ERR_HIP;
@@ -162,6 +174,7 @@ int mukv_destroy(mukv_ctx *ctx) {
         }
         delete ctx->c.prof;
     }
+    delete ctx->c.pending;
     delete ctx;
     return MUKV_OK;
 }
@@ -194,7 +207,50 @@ int mukv_profile_end(mukv_ctx *ctx, mukv_profile *out) {
 int mukv_reset(mukv_ctx *ctx) {
     if (!ctx) return MUKV_ERR_INVALID_ARG;
     ctx->c.n_frames = 0;
+    ctx->c.n_done = 0;
+    ctx->c.pending->clear();
     return MUKV_OK;
+}
+
+// Enqueues the kernels for every chunk gathered so far (on the stream they were submitted with).
+static int flush_pending(Ctx &c) {
+    if (c.pending->empty()) return MUKV_OK;
+    mukv::ChunkArgs a;
+    std::memset(&a, 0, sizeof(a));
+    int nf = 0, s = 0;
+    for (const mukv::PendingChunk &pc : *c.pending) {
+        a.k.p[s] = pc.k;
+        a.v.p[s] = pc.v;
+        a.q.p[s] = pc.q;
+        a.att_in.p[s] = pc.att_in;
+        a.dbg_att.p[s] = pc.sig.att;
+        a.dbg_fft.p[s] = pc.sig.fft;
+        a.dbg_fused.p[s] = pc.sig.fused;
+        a.have_dbg = a.have_dbg || pc.sig.att || pc.sig.fft || pc.sig.fused;
+        a.map.fstart[s] = nf;
+        nf += pc.n_frames;
+        ++s;
+    }
+    a.map.fstart[s] = nf;
+    a.map.n_slots = s;
+    a.have_q = c.pending->front().q != nullptr;
+    a.have_att_in = c.pending->front().att_in != nullptr;
+    a.kv_sl = c.p_kv_sl;
+    a.kv_sh = c.p_kv_sh;
+    a.kv_st = c.p_kv_st;
+    a.q_sh = c.p_q_sh;
+    a.q_st = c.p_q_st;
+    a.n_frames = nf;
+    a.frame0 = c.n_done;
+    c.pending->clear();
+    c.n_done += nf;
+    if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
+    return mukv::launch_compress(c, a, c.p_stream) == hipSuccess ? MUKV_OK : MUKV_ERR_HIP;
+}
+
+int mukv_flush(mukv_ctx *ctx) {
+    if (!ctx) return MUKV_ERR_INVALID_ARG;
+    return flush_pending(ctx->c);
 }
 
 int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_strides *kv_strides,
@@ -215,29 +271,45 @@ int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_
     if (kv_strides->token % unit || kv_strides->head % unit || kv_strides->layer % unit ||
         (reinterpret_cast<uintptr_t>(k) & 15) || (reinterpret_cast<uintptr_t>(v) & 15))
         return MUKV_ERR_UNSUPPORTED;
-    mukv::ChunkArgs a;
-    std::memset(&a, 0, sizeof(a));
-    a.k = k;
-    a.v = v;
-    a.kv_sl = kv_strides->layer;
-    a.kv_sh = kv_strides->head;
-    a.kv_st = kv_strides->token;
-    if (c.cfg.alpha != 0.0 && q_last) {
+    int64_t q_sh = 0, q_st = 0;
+    const bool use_q = c.cfg.alpha != 0.0 && q_last;
+    if (use_q) {
         if (q_strides->token < D || q_strides->head < 0) return MUKV_ERR_SHAPE;
         if (q_strides->token % unit || q_strides->head % unit || (reinterpret_cast<uintptr_t>(q_last) & 15))
             return MUKV_ERR_UNSUPPORTED;
-        a.q = q_last;
-        a.q_sh = q_strides->head;
-        a.q_st = q_strides->token;
+        q_sh = q_strides->head;
+        q_st = q_strides->token;
     }
-    a.att_in = (c.cfg.alpha != 0.0) ? att_signal : nullptr;
-    a.n_frames = n_frames;
-    a.frame0 = c.n_frames;
-    if (sig) a.sig = *sig;
-    if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
-    hipError_t e = mukv::launch_compress(c, a, reinterpret_cast<hipStream_t>(stream));
-    if (e != hipSuccess) return MUKV_ERR_HIP;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const bool use_att_in = c.cfg.alpha != 0.0 && att_signal;
+    if (!c.pending->empty()) {
+        // a batch shares one stream, one set of strides and one attention source
+        const mukv::PendingChunk &p0 = c.pending->front();
+        const bool same = c.p_stream == st && c.p_kv_sl == kv_strides->layer && c.p_kv_sh == kv_strides->head &&
+                          c.p_kv_st == kv_strides->token && c.p_q_sh == q_sh && c.p_q_st == q_st &&
+                          (p0.q != nullptr) == use_q && (p0.att_in != nullptr) == use_att_in;
+        if (!same) {
+            const int rc = flush_pending(c);
+            if (rc != MUKV_OK) return rc;
+        }
+    }
+    mukv::PendingChunk pc;
+    pc.k = k;
+    pc.v = v;
+    pc.q = use_q ? q_last : nullptr;
+    pc.att_in = use_att_in ? att_signal : nullptr;
+    pc.sig = mukv_signals_out{nullptr, nullptr, nullptr};
+    if (sig) pc.sig = *sig;
+    pc.n_frames = n_frames;
+    c.p_stream = st;
+    c.p_kv_sl = kv_strides->layer;
+    c.p_kv_sh = kv_strides->head;
+    c.p_kv_st = kv_strides->token;
+    c.p_q_sh = q_sh;
+    c.p_q_st = q_st;
+    c.pending->push_back(pc);
     c.n_frames += n_frames;
+    if ((int)c.pending->size() >= c.batch_chunks) return flush_pending(c);
     return MUKV_OK;
 }
 
@@ -252,6 +324,10 @@ int mukv_retrieve(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets,
     if (params->k_seg < 1 || params->k_frame < 1 || params->n_global < 0) return MUKV_ERR_INVALID_ARG;
     if (!(params->lambda_frame >= 0.0) || params->lambda_frame > 1.0) return MUKV_ERR_INVALID_ARG;
     if (2 * params->k_seg > mukv::kMaxCand || 2 * params->k_frame > mukv::kMaxCand) return MUKV_ERR_UNSUPPORTED;
+    {
+        const int rc = flush_pending(c);
+        if (rc != MUKV_OK) return rc;
+    }
     mukv::RetrieveArgs a;
     a.q_tokens = q_tokens;
     a.q_offsets = q_offsets;
@@ -279,6 +355,10 @@ int mukv_gather_kv(mukv_ctx *ctx, const int32_t *frame_idx, int32_t B, int32_t k
     if (k_frame > mukv::kMaxGatherK) return MUKV_ERR_UNSUPPORTED;
     if ((reinterpret_cast<uintptr_t>(k_out) & 15) || (reinterpret_cast<uintptr_t>(v_out) & 15))
         return MUKV_ERR_UNSUPPORTED;
+    {
+        const int rc = flush_pending(c);
+        if (rc != MUKV_OK) return rc;
+    }
     if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
     return mukv::launch_gather(c, frame_idx, B, k_frame, order, k_out, v_out, n_tokens_out,
                                reinterpret_cast<hipStream_t>(stream)) == hipSuccess

@@ -95,8 +95,8 @@ __device__ __forceinline__ void strip_job(const JobArgs &ja, const bf16x8 *qv, f
     }
 }
 
-__global__ __launch_bounds__(448) __attribute__((amdgpu_waves_per_eu(4, 4))) void att_mfma_kernel(const uint16_t *__restrict__ q, int64_t q_sh, int64_t q_st,
-                                                       const uint16_t *__restrict__ k, int64_t k_sh, int64_t k_st,
+__global__ __launch_bounds__(448) __attribute__((amdgpu_waves_per_eu(4, 4))) void att_mfma_kernel(PtrTable qtab, PtrTable ktab, FrameMap map, int64_t k_off,
+                                                       int64_t q_sh, int64_t q_st, int64_t k_sh, int64_t k_st,
                                                        int P, int nt, int G, int hpw, int causal, int pair, int n_split,
                                                        float scale_log2e, int n_part, float *__restrict__ out) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -119,7 +119,9 @@ __global__ __launch_bounds__(448) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     const bool active = sA < nt && (pair || w < wps);
     int k_tiles = nt;
     if (!pair && causal) k_tiles = (sp + 1) * wps < nt ? (sp + 1) * wps : nt;
-    const uint16_t *qf = q + ((int64_t)f * P) * q_st + 8 * lg;
+    const int slot = find_slot(map, f);
+    const int lf = f - map.fstart[slot];
+    const uint16_t *qf = reinterpret_cast<const uint16_t *>(qtab.p[slot]) + ((int64_t)lf * P) * q_st + 8 * lg;
     // B operand of one (head, strip): 4 x 16 bytes per lane, rows past P clamped (masked later)
     auto load_q = [&](int h, int s, bf16x8 *dst) {
         const int qi = 16 * s + lr;
@@ -133,7 +135,7 @@ __global__ __launch_bounds__(448) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 
     // stage K of (frame, KV head) in LDS; rows past P are zero.  Loads are unconditional on a
     // clamped row and issued in batches of 4 before the LDS stores.
-    const uint16_t *kf = k + (int64_t)g * k_sh + (int64_t)f * P * k_st;
+    const uint16_t *kf = reinterpret_cast<const uint16_t *>(ktab.p[slot]) + k_off + (int64_t)g * k_sh + (int64_t)lf * P * k_st;
     const int n_units = k_tiles * 16 * 16;
     for (int i0 = tid; i0 < n_units; i0 += 8 * n_threads) {
         u32x4 val[8];
@@ -226,10 +228,9 @@ hipError_t launch_att_mfma(const Ctx &c, const ChunkArgs &a, float *out, int *n_
     *n_part = (Hq / hpw) * n_split;
     const size_t lds = (size_t)nt * 16 * kLdsRow * 2 + (size_t)waves * nt * 16 * sizeof(float);
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)c.cfg.head_dim);
-    const uint16_t *k = reinterpret_cast<const uint16_t *>(a.k) + (int64_t)c.ls * a.kv_sl;
-    hipLaunchKernelGGL(att_mfma_kernel, dim3(a.n_frames, *n_part), dim3(waves * 64), lds, st,
-                       reinterpret_cast<const uint16_t *>(a.q), a.q_sh, a.q_st, k, a.kv_sh, a.kv_st, P, nt, G, hpw,
-                       c.cfg.causal, pair, n_split, scale_log2e, *n_part, out);
+    hipLaunchKernelGGL(att_mfma_kernel, dim3(a.n_frames, *n_part), dim3(waves * 64), lds, st, a.q, a.k, a.map,
+                       (int64_t)c.ls * a.kv_sl, a.q_sh, a.q_st, a.kv_sh, a.kv_st, P, nt, G, hpw, c.cfg.causal, pair,
+                       n_split, scale_log2e, *n_part, out);
     return hipGetLastError();
 }
 

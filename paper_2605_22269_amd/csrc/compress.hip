@@ -39,19 +39,20 @@ __device__ __forceinline__ double sqrt_t(double x) { return sqrt(x); }
 __device__ __forceinline__ float abs_t(float x) { return fabsf(x); }
 __device__ __forceinline__ double abs_t(double x) { return fabs(x); }
 
+constexpr int kFreqBlocksPerFrame = 4;
+constexpr int kRescoreSlots = 4; // grid.x of the fp64 re-scoring kernels; they loop over the list
+
 template <typename T, typename R, int D>
-__global__ __launch_bounds__(256) void freq_signal_kernel(const T *__restrict__ k, int64_t sh, int64_t st, int Hkv,
-                                                          int P, int n_tok, int64_t frame0,
-                                                          const int32_t *__restrict__ only_flagged,
+__global__ __launch_bounds__(256) void freq_signal_kernel(PtrTable ktab, FrameMap map, int64_t k_off, int64_t sh,
+                                                          int64_t st, int Hkv, int P,
+                                                          const int32_t *__restrict__ flag_list,
+                                                          const int32_t *__restrict__ flag_count,
                                                           R *__restrict__ out) {
     constexpr int N = D / 2;
     constexpr int GROUPS = kWave / N;
     constexpr int LOG = (N == 64) ? 6 : (N == 32) ? 5 : (N == 16) ? 4 : 3;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int p = lane % N, sub = lane / N;
-    const int64_t tok = ((int64_t)blockIdx.x * 4 + wave) * GROUPS + sub;
-    bool valid = tok < n_tok;
-    if (valid && only_flagged) valid = only_flagged[frame0 + tok / P] != 0;
 
     R twr[LOG], twi[LOG];
 #pragma unroll
@@ -64,116 +65,177 @@ __global__ __launch_bounds__(256) void freq_signal_kernel(const T *__restrict__ 
     R uwr, uwi;
     sincospi_t(-(R)kb / (R)N, &uwi, &uwr);
 
-    R total = 0;
-    for (int g = 0; g < Hkv; ++g) {
-        R zr = 0, zi = 0;
-        if (valid) {
-            const T *row = k + (int64_t)g * sh + tok * st + 2 * p;
-            zr = (R)to_float(row[0]);
-            zi = (R)to_float(row[1]);
-        }
+    // frames: every batch frame (grid.x = n_frames), or the entries of the re-scoring list
+    const int n_e = flag_list ? *flag_count : (int)gridDim.x;
+    for (int e = blockIdx.x; e < n_e; e += gridDim.x) {
+    const int f = flag_list ? flag_list[e] : e;
+    const int slot = find_slot(map, f);
+    const T *k = reinterpret_cast<const T *>(ktab.p[slot]) + k_off + (int64_t)(f - map.fstart[slot]) * P * st;
+    // the workgroup's waves walk over the frame's tokens, GROUPS tokens per wave and step
+    const int stride = kFreqBlocksPerFrame * 4 * GROUPS;
+    for (int t0 = (blockIdx.y * 4 + wave) * GROUPS; t0 < P; t0 += stride) {
+        const int tok = t0 + sub;
+        const bool valid = tok < P;
+        const T *row = k + (int64_t)(valid ? tok : P - 1) * st + 2 * p;
+        R total = 0;
+        for (int g0 = 0; g0 < Hkv; g0 += 4) { // four heads' loads in flight
+            T x0[4], x1[4];
 #pragma unroll
-        for (int s = 0; s < LOG; ++s) {
-            const int h = N >> (s + 1);
-            const R pr = __shfl_xor(zr, h), pi = __shfl_xor(zi, h);
-            if (p & h) {
-                const R dr = pr - zr, di = pi - zi;
-                zr = dr * twr[s] - di * twi[s];
-                zi = dr * twi[s] + di * twr[s];
-            } else {
-                zr += pr;
-                zi += pi;
+            for (int u = 0; u < 4; ++u) {
+                const T *r = row + (int64_t)(g0 + u < Hkv ? g0 + u : Hkv - 1) * sh;
+                x0[u] = r[0];
+                x1[u] = r[1];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (g0 + u >= Hkv) break;
+                R zr = (R)to_float(x0[u]), zi = (R)to_float(x1[u]);
+#pragma unroll
+                for (int s = 0; s < LOG; ++s) {
+                    const int h = N >> (s + 1);
+                    const R pr = __shfl_xor(zr, h), pi = __shfl_xor(zi, h);
+                    if (p & h) {
+                        const R dr = pr - zr, di = pi - zi;
+                        zr = dr * twr[s] - di * twi[s];
+                        zi = dr * twi[s] + di * twr[s];
+                    } else {
+                        zr += pr;
+                        zi += pi;
+                    }
+                }
+                // lane p now holds Z[kb]; fetch Z[(N-kb) mod N]
+                const R pr = __shfl(zr, partner), pi = __shfl(zi, partner);
+                R c;
+                if (kb == 0) {
+                    c = abs_t(zr + zi) + abs_t(zr - zi); // X[0] and X[D/2]
+                } else {
+                    const R er = (R)0.5 * (zr + pr), ei = (R)0.5 * (zi - pi);
+                    const R odr = (R)0.5 * (zi + pi), odi = (R)-0.5 * (zr - pr);
+                    const R xr = er + (odr * uwr - odi * uwi);
+                    const R xi = ei + (odr * uwi + odi * uwr);
+                    c = (R)2 * sqrt_t(xr * xr + xi * xi);
+                }
+                total += c;
             }
         }
-        // lane p now holds Z[kb]; fetch Z[(N-kb) mod N]
-        const R pr = __shfl(zr, partner), pi = __shfl(zi, partner);
-        R c;
-        if (kb == 0) {
-            c = abs_t(zr + zi) + abs_t(zr - zi); // X[0] and X[D/2]
-        } else {
-            const R er = (R)0.5 * (zr + pr), ei = (R)0.5 * (zi - pi);
-            const R odr = (R)0.5 * (zi + pi), odi = (R)-0.5 * (zr - pr);
-            const R xr = er + (odr * uwr - odi * uwi);
-            const R xi = ei + (odr * uwi + odi * uwr);
-            c = (R)2 * sqrt_t(xr * xr + xi * xi);
-        }
-        total += c;
-    }
 #pragma unroll
-    for (int o = N / 2; o > 0; o >>= 1) total += __shfl_xor(total, o);
-    if (p == 0 && valid) out[tok] = total / (R)(Hkv * D);
+        for (int o = N / 2; o > 0; o >>= 1) total += __shfl_xor(total, o);
+        if (p == 0 && valid) out[(int64_t)f * P + tok] = total / (R)(Hkv * D);
+    }
+    }
 }
 
 // ------------------------------------------------------------------------------------------
-// Eq. 1, generic path (any dtype, any D, P <= 256): one workgroup per (frame, query head).
-// The frame's keys sit in LDS as float (exact for bf16 and fp32 payloads); a wave takes one
-// query row at a time, lanes own keys j = lane + 64*t, the row softmax uses wave reductions,
-// and each lane accumulates the probabilities of its keys.  Per-wave partial column sums are
-// combined in a fixed order, so results are run-to-run identical.
-// out: [frame][Hq][P] (R) partial sums over the query rows of one head, not yet divided.
+// Eq. 1, generic path (any dtype, any D, P <= 256), also the fp64 re-scoring path.
+// Grid (frame, query head, query range): a workgroup stages the frame's keys in LDS as float
+// (exact for bf16 and fp32 payloads) and handles kGenQ consecutive queries per round, four per
+// wave at once: lanes own keys j = lane + 64*t, every LDS key value read is used for four
+// queries, the row softmax uses wave reductions, and each lane accumulates the probabilities of
+// its keys.  Per-wave partial column sums are combined in a fixed order, so results are
+// run-to-run identical.
+// out: [frame][Hq * gridDim.z][P] (R) partial sums over this workgroup's query rows.
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ float exp_t(float x) { return expf(x); }
 __device__ __forceinline__ double exp_t(double x) { return exp(x); }
 
+constexpr int kGenQ = 16; // queries per round of a workgroup: 4 waves x 4
+
 template <typename T, typename R>
-__global__ __launch_bounds__(256) void att_generic_kernel(const T *__restrict__ q, int64_t q_sh, int64_t q_st,
-                                                          const T *__restrict__ k, int64_t k_sh, int64_t k_st,
-                                                          int P, int D, int G, int Hq, int causal, int64_t frame0,
-                                                          const int32_t *__restrict__ only_flagged,
+__global__ __launch_bounds__(256) void att_generic_kernel(PtrTable qtab, PtrTable ktab, FrameMap map, int64_t k_off,
+                                                          int64_t q_sh, int64_t q_st, int64_t k_sh, int64_t k_st,
+                                                          int P, int D, int G, int Hq, int causal, int q_per_block,
+                                                          const int32_t *__restrict__ flag_list,
+                                                          const int32_t *__restrict__ flag_count,
                                                           R *__restrict__ out) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    const int f = blockIdx.x, h = blockIdx.y;
-    if (only_flagged && only_flagged[frame0 + f] == 0) return;
+    const int h = blockIdx.y, z = blockIdx.z;
+    // frames: every batch frame (grid.x = n_frames), or the entries of the re-scoring list
+    const int n_e = flag_list ? *flag_count : (int)gridDim.x;
+    for (int e_idx = blockIdx.x; e_idx < n_e; e_idx += gridDim.x) {
+    const int f = flag_list ? flag_list[e_idx] : e_idx;
     const int ldk = D + 1;
     float *Ks = reinterpret_cast<float *>(smem_raw);   // [P][D+1]
-    float *qs = Ks + (size_t)P * ldk;                   // [4][D]
-    size_t n_fl = (size_t)P * ldk + 4 * D;
+    float *qs = Ks + (size_t)P * ldk;                   // [kGenQ][D]
+    size_t n_fl = (size_t)P * ldk + kGenQ * D;
     n_fl += n_fl & 1;
     R *part = reinterpret_cast<R *>(Ks + n_fl);        // [4][P], 8-byte aligned
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const T *kf = k + (int64_t)(h / G) * k_sh + (int64_t)f * P * k_st;
-    const T *qf = q + (int64_t)h * q_sh + (int64_t)f * P * q_st;
-    for (int e = tid; e < P * D; e += 256) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int slot = find_slot(map, f);
+    const int lf = f - map.fstart[slot];
+    const T *kf = reinterpret_cast<const T *>(ktab.p[slot]) + k_off + (int64_t)(h / G) * k_sh + (int64_t)lf * P * k_st;
+    const T *qf = reinterpret_cast<const T *>(qtab.p[slot]) + (int64_t)h * q_sh + (int64_t)lf * P * q_st;
+    const int i_lo = z * q_per_block;
+    const int i_hi = (i_lo + q_per_block < P) ? i_lo + q_per_block : P;
+    const int n_keys = causal ? i_hi : P; // keys any query of this workgroup can see
+    for (int e = tid; e < n_keys * D; e += 256) {
         const int j = e / D, d = e - j * D;
         Ks[j * ldk + d] = to_float(kf[(int64_t)j * k_st + d]);
     }
     const R scale = (R)1 / sqrt_t((R)D);
     R acc[4] = {0, 0, 0, 0};
-    const int n_it = (P + 3) / 4;
-    for (int it = 0; it < n_it; ++it) {
-        const int i = it * 4 + wave;
+    for (int i0 = i_lo; i0 < i_hi; i0 += kGenQ) {
         __syncthreads();
-        if (i < P)
-            for (int d = lane; d < D; d += 64) qs[wave * D + d] = to_float(qf[(int64_t)i * q_st + d]);
+        for (int e = tid; e < kGenQ * D; e += 256) {
+            const int qi = e / D, d = e - qi * D;
+            const int i = i0 + qi < i_hi ? i0 + qi : i_hi - 1;
+            qs[e] = to_float(qf[(int64_t)i * q_st + d]);
+        }
         __syncthreads();
-        if (i >= P) continue;
-        const int nj = causal ? i + 1 : P;
-        R s[4];
-        R m = -INFINITY;
+        const int iw = i0 + 4 * wave; // this wave's four queries: iw .. iw+3
+        if (iw >= i_hi) continue;
+        const int i_last = iw + 3 < i_hi ? iw + 3 : i_hi - 1;
+        const int nj_max = causal ? i_last + 1 : P;
+        R s[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) s[u][t] = 0;
+        const float *qr = qs + (4 * wave) * D;
+        int jrow[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int j = lane + 64 * t;
-            s[t] = -INFINITY;
-            if (j < nj) {
-                R dot = 0;
-                const float *kr = Ks + j * ldk;
-                const float *qr = qs + wave * D;
-                for (int d = 0; d < D; ++d) dot += (R)qr[d] * (R)kr[d];
-                s[t] = dot * scale;
+            jrow[t] = (j < nj_max ? j : nj_max - 1) * ldk;
+        }
+        const int nt_use = (nj_max + 63) >> 6; // 64-key groups that hold a visible key
+        for (int d = 0; d < D; ++d) {
+            R qq[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) qq[u] = (R)qr[u * D + d];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (t < nt_use) {
+                    const R kk = (R)Ks[jrow[t] + d];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) s[u][t] += qq[u] * kk;
+                }
             }
-            m = s[t] > m ? s[t] : m;
         }
-        m = wave_max(m);
-        R z = 0;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int j = lane + 64 * t;
-            s[t] = (j < nj) ? exp_t(s[t] - m) : (R)0;
-            z += s[t];
+        for (int u = 0; u < 4; ++u) {
+            const int i = iw + u;
+            if (i >= i_hi) break;
+            const int nj = causal ? i + 1 : P;
+            R m = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int j = lane + 64 * t;
+                s[u][t] = (j < nj) ? s[u][t] * scale : (R)-INFINITY;
+                m = s[u][t] > m ? s[u][t] : m;
+            }
+            m = wave_max(m);
+            R zsum = 0;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int j = lane + 64 * t;
+                s[u][t] = (j < nj) ? exp_t(s[u][t] - m) : (R)0;
+                zsum += s[u][t];
+            }
+            zsum = wave_sum(zsum);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[t] += s[u][t] / zsum;
         }
-        z = wave_sum(z);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) acc[t] += s[t] / z;
     }
     __syncthreads();
 #pragma unroll
@@ -182,8 +244,11 @@ __global__ __launch_bounds__(256) void att_generic_kernel(const T *__restrict__ 
         if (j < P) part[wave * P + j] = acc[t];
     }
     __syncthreads();
+    const int n_part = Hq * gridDim.z;
     for (int j = tid; j < P; j += 256)
-        out[((int64_t)f * Hq + h) * P + j] = ((part[j] + part[P + j]) + part[2 * P + j]) + part[3 * P + j];
+        out[((int64_t)f * n_part + h * gridDim.z + z) * P + j] = ((part[j] + part[P + j]) + part[2 * P + j]) + part[3 * P + j];
+    __syncthreads();
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -205,15 +270,20 @@ struct SelectArgs {
     const R *att;       // [n_frames][n_part][P] partial sums, or NULL (alpha == 0)
     int n_part;
     R att_scale;        // 1/(Hq*P) for partial sums, 1 for a caller-supplied signal
-    const float *att_in; // caller-supplied [n_frames][P], or NULL
+    PtrTable att_in;    // per slot: caller-supplied float [n][P]
+    bool have_att_in;
     const R *fft;       // [n_frames][P], or NULL (alpha == 1)
     R alpha;
     int P, kappa, S, Hkv, D;
     int64_t frame0;
-    const void *k, *v;  // scoring layer base of the chunk
+    PtrTable k, v;      // per slot: chunk base
+    FrameMap map;
+    int64_t k_off;      // element offset of the scoring layer
     int64_t sh, st;
     R margin_thr;
-    int pass2;          // 1: only frames flagged by pass 1
+    int pass2;          // 1: fp64 pass over the frames listed by pass 1
+    int32_t *flag_list; // batch frames whose fp32 margin is below the threshold (written by pass 1)
+    int32_t *flag_count;
     int32_t *kept_idx;
     int32_t *src_tok;
     float *rep_frame_k, *rep_frame_v, *rep_patch_k, *rep_patch_v;
@@ -221,7 +291,8 @@ struct SelectArgs {
     double *fsum_k, *fsum_v;
     float *margin;
     int32_t *refined;
-    float *dbg_att, *dbg_fft, *dbg_fused;
+    OutTable dbg_att, dbg_fft, dbg_fused; // per slot, float [n][P], entries may be null
+    bool have_dbg;
 };
 
 template <typename R>
@@ -256,16 +327,23 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
     __shared__ R vk[2];
     __shared__ int kl[kMaxP];
     __shared__ int wcnt[4];
-    const int f = blockIdx.x, j = threadIdx.x;
-    const int64_t gf = a.frame0 + f;
+    const int j = threadIdx.x;
     const int P = a.P, kappa = a.kappa;
-    if (a.pass2 && a.refined[gf] == 0) return;
+    const int n_e = a.pass2 ? *a.flag_count : (int)gridDim.x;
+    for (int e_idx = blockIdx.x; e_idx < n_e; e_idx += gridDim.x) {
+    const int f = a.pass2 ? a.flag_list[e_idx] : e_idx;
+    const int64_t gf = a.frame0 + f;
     const bool valid = j < P;
+    const int slot = find_slot(a.map, f);
+    const int lf = f - a.map.fstart[slot];
+    float *dbg_att = a.have_dbg ? a.dbg_att.p[slot] : nullptr;
+    float *dbg_fft = a.have_dbg ? a.dbg_fft.p[slot] : nullptr;
+    float *dbg_fused = a.have_dbg ? a.dbg_fused.p[slot] : nullptr;
 
     R av = 0, fv = 0;
     if (valid && a.alpha != (R)0) {
-        if (a.att_in) {
-            av = (R)a.att_in[(int64_t)f * P + j];
+        if (a.have_att_in) {
+            av = (R) reinterpret_cast<const float *>(a.att_in.p[slot])[(int64_t)lf * P + j];
         } else {
             const R *pp = a.att + (int64_t)f * a.n_part * P + j;
             for (int n0 = 0; n0 < a.n_part; n0 += 8) { // fixed summation order, 8 loads in flight
@@ -280,8 +358,8 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
         }
     }
     if (valid && a.alpha != (R)1) fv = a.fft[(int64_t)f * P + j];
-    if (valid && a.dbg_att) a.dbg_att[(int64_t)f * P + j] = (float)av;
-    if (valid && a.dbg_fft) a.dbg_fft[(int64_t)f * P + j] = (float)fv;
+    if (valid && dbg_att) dbg_att[(int64_t)lf * P + j] = (float)av;
+    if (valid && dbg_fft) dbg_fft[(int64_t)lf * P + j] = (float)fv;
 
     R lo, hi;
     R fused = 0;
@@ -297,7 +375,7 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
     }
     if (valid) {
         sc[j] = fused;
-        if (a.dbg_fused) a.dbg_fused[(int64_t)f * P + j] = (float)fused;
+        if (dbg_fused) dbg_fused[(int64_t)lf * P + j] = (float)fused;
     }
     if (j < 2) vk[j] = 0;
     __syncthreads();
@@ -321,13 +399,15 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
         if (kept) {
             kl[pos] = j;
             a.kept_idx[gf * kappa + pos] = j;
-            a.src_tok[(int64_t)f * kappa + pos] = f * P + j;
+            a.src_tok[(int64_t)f * kappa + pos] = lf * P + j; // token inside the slot's chunk
         }
     }
     if (j == 0) {
         const R mg = (kappa < P) ? vk[0] - vk[1] : (R)INFINITY;
         a.margin[gf] = (float)mg;
-        a.refined[gf] = a.pass2 ? 1 : ((a.margin_thr > (R)0 && mg < a.margin_thr) ? 1 : 0);
+        const bool flag = !a.pass2 && a.margin_thr > (R)0 && mg < a.margin_thr;
+        a.refined[gf] = (a.pass2 || flag) ? 1 : 0;
+        if (flag) a.flag_list[atomicAdd(a.flag_count, 1)] = f; // order is irrelevant: frames are independent
     }
     __syncthreads();
 
@@ -337,12 +417,12 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
     constexpr int kBatch = 12;
     const int C = a.Hkv * a.D;
     const int len = P / a.S;
-    const T *xk = reinterpret_cast<const T *>(a.k);
-    const T *xv = reinterpret_cast<const T *>(a.v);
+    const T *xk = reinterpret_cast<const T *>(a.k.p[slot]) + a.k_off;
+    const T *xv = reinterpret_cast<const T *>(a.v.p[slot]) + a.k_off;
     for (int cp = j; cp < C / 2; cp += 256) {
         const int c = 2 * cp;
         const int g = c / a.D, d = c - g * a.D;
-        const int64_t col = (int64_t)g * a.sh + d + (int64_t)f * P * a.st;
+        const int64_t col = (int64_t)g * a.sh + d + (int64_t)lf * P * a.st;
         double run[4] = {0.0, 0.0, 0.0, 0.0}, tot[4] = {0.0, 0.0, 0.0, 0.0}; // k0 k1 v0 v1
         int cnt = 0, s = 0;
         int end = (a.S == 1) ? P : len;
@@ -395,13 +475,15 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
         a.rep_frame_v[o] = (float)(tot[2] / (double)kappa);
         a.rep_frame_v[o + 1] = (float)(tot[3] / (double)kappa);
     }
+    __syncthreads();
+    }
 }
 
 // ------------------------------------------------------------------------------------------
 // Storage of the kept KV rows of every layer (Sec. 3.3, last paragraph) and segment keys.
-// grid.y < n_slab: slab (layer, K|V, KV head); the slab's destination is one dense run of
-// n_frames*kappa rows, so unit u of the slab goes to dst + u*VEC and comes from the row
-// src_tok[u / units_per_row] of the chunk.  Each thread moves ITER units: loads first, then
+// grid.y < n_slab: slab (layer, K|V, KV head); grid.x = (slot of the batch, part of the slot).
+// A slot's destination inside the slab is one dense run of its frames' kappa rows, so unit u of
+// the slot goes to dst + u*VEC and comes from row src_tok[u / units_per_row] of the slot's chunk.  Each thread moves ITER units: loads first, then
 // stores.  grid.y >= n_slab: one workgroup per segment touched by the chunk adds the chunk's
 // exact per-frame sums to the segment's running fp64 sum and refreshes the segment's keys; the
 // sums are exact for bf16 / fp32 payloads of ordinary dynamic range, so any chunking gives the
@@ -410,13 +492,15 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 struct CompactArgs {
-    const unsigned char *k, *v;  // chunk base, bytes
+    PtrTable k, v;               // per slot: chunk base
+    FrameMap map;
+    int bps;                     // workgroups per slot along grid.x
     int64_t sl_b, sh_b, st_b;    // byte strides layer / head / token
     unsigned char *store_k, *store_v;
     int64_t slab_b;              // bytes of one (layer, head) slab of the store
     int64_t dst_off_b;           // byte offset of frame0's first row inside a slab
     const int32_t *src_tok;
-    int n_units;                 // units per slab = n_frames*kappa*units_per_row
+    int units_per_frame;         // kappa * units per row
     int log_upr;                 // log2(units per row)
     int Hkv, n_slab;
     // segment update
@@ -426,11 +510,13 @@ struct CompactArgs {
     double *ssum_k, *ssum_v;     // running exact sums per segment
     int64_t frame0;
     float *rep_seg_k, *rep_seg_v;
+    int32_t *flag_count;         // re-scoring list length, cleared here for the next batch
 };
 
 template <typename V, int ITER>
 __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
     const int y = blockIdx.y;
+    if (y == 0 && blockIdx.x == 0 && threadIdx.x == 0) *a.flag_count = 0;
     if (y >= a.n_slab) {
         if (blockIdx.x != 0) return;
         const int s = a.seg_first + (y - a.n_slab);
@@ -467,30 +553,37 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
     }
     const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
     const int kv = rem / a.Hkv, g = rem - kv * a.Hkv;
-    const unsigned char *src = (kv ? a.v : a.k) + (int64_t)l * a.sl_b + (int64_t)g * a.sh_b;
-    unsigned char *dst = (kv ? a.store_v : a.store_k) + ((int64_t)l * a.Hkv + g) * a.slab_b + a.dst_off_b;
+    const int slot = blockIdx.x / a.bps, bx = blockIdx.x - slot * a.bps;
+    const int f_lo = a.map.fstart[slot];
+    const int n_units = (a.map.fstart[slot + 1] - f_lo) * a.units_per_frame;
+    if (bx * (256 * ITER) >= n_units) return;
+    const unsigned char *src = reinterpret_cast<const unsigned char *>(kv ? a.v.p[slot] : a.k.p[slot]) +
+                               (int64_t)l * a.sl_b + (int64_t)g * a.sh_b;
+    unsigned char *dst = (kv ? a.store_v : a.store_k) + ((int64_t)l * a.Hkv + g) * a.slab_b + a.dst_off_b +
+                         (int64_t)f_lo * a.units_per_frame * sizeof(V);
+    const int32_t *src_tok = a.src_tok + (int64_t)f_lo * (a.units_per_frame >> a.log_upr);
     const int mask = (1 << a.log_upr) - 1;
     // Loads are issued unconditionally on clamped unit numbers (first all row lookups, then all
     // row reads) so that they overlap; only the stores are predicated.
     V tmp[ITER];
     int row_tok[ITER];
-    const int u0 = blockIdx.x * (256 * ITER) + threadIdx.x;
+    const int u0 = bx * (256 * ITER) + threadIdx.x;
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
         int u = u0 + it * 256;
-        u = u < a.n_units ? u : a.n_units - 1;
-        row_tok[it] = a.src_tok[u >> a.log_upr];
+        u = u < n_units ? u : n_units - 1;
+        row_tok[it] = src_tok[u >> a.log_upr];
     }
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
         int u = u0 + it * 256;
-        u = u < a.n_units ? u : a.n_units - 1;
+        u = u < n_units ? u : n_units - 1;
         tmp[it] = *reinterpret_cast<const V *>(src + (int64_t)row_tok[it] * a.st_b + (int64_t)(u & mask) * sizeof(V));
     }
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
         const int u = u0 + it * 256;
-        if (u < a.n_units) *reinterpret_cast<V *>(dst + (int64_t)u * sizeof(V)) = tmp[it];
+        if (u < n_units) *reinterpret_cast<V *>(dst + (int64_t)u * sizeof(V)) = tmp[it];
     }
 }
 
@@ -498,15 +591,14 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
 // host side
 // ------------------------------------------------------------------------------------------
 template <typename T, typename R>
-static hipError_t launch_freq(const Ctx &c, const ChunkArgs &a, const int32_t *flags, R *out, hipStream_t st) {
-    const T *k = reinterpret_cast<const T *>(a.k) + (int64_t)c.ls * a.kv_sl;
+static hipError_t launch_freq(const Ctx &c, const ChunkArgs &a, bool listed, R *out, hipStream_t st) {
     const int P = c.cfg.tokens_per_frame, D = c.cfg.head_dim, Hkv = c.cfg.n_kv_heads;
-    const int n_tok = a.n_frames * P;
-    const int groups = kWave / (D / 2);
-    const int n_blk = (n_tok + 4 * groups - 1) / (4 * groups);
-#define MUKV_FREQ(DD)                                                                                        \
-    hipLaunchKernelGGL((freq_signal_kernel<T, R, DD>), dim3(n_blk), dim3(256), 0, st, k, a.kv_sh, a.kv_st, \
-                       Hkv, P, n_tok, a.frame0, flags, out)
+    const int64_t k_off = (int64_t)c.ls * a.kv_sl;
+    const dim3 grid(listed ? kRescoreSlots : a.n_frames, kFreqBlocksPerFrame);
+    const int32_t *fl = listed ? c.flag_list : nullptr, *fc = listed ? c.flag_count : nullptr;
+#define MUKV_FREQ(DD)                                                                                         \
+    hipLaunchKernelGGL((freq_signal_kernel<T, R, DD>), grid, dim3(256), 0, st, a.k, a.map, k_off, a.kv_sh, \
+                       a.kv_st, Hkv, P, fl, fc, out)
     switch (D) {
     case 128: MUKV_FREQ(128); break;
     case 64: MUKV_FREQ(64); break;
@@ -519,16 +611,18 @@ static hipError_t launch_freq(const Ctx &c, const ChunkArgs &a, const int32_t *f
 }
 
 size_t att_generic_lds_bytes(int P, int D, size_t r_size) {
-    size_t floats = (size_t)P * (D + 1) + 4 * D;
+    size_t floats = (size_t)P * (D + 1) + kGenQ * D;
     floats += floats & 1;
     return floats * 4 + (size_t)4 * P * r_size;
 }
 
 template <typename T, typename R>
-static hipError_t launch_att_generic(const Ctx &c, const ChunkArgs &a, const int32_t *flags, R *out, hipStream_t st) {
+static hipError_t launch_att_generic(const Ctx &c, const ChunkArgs &a, bool listed, R *out, int *n_part,
+                                     hipStream_t st) {
     const int P = c.cfg.tokens_per_frame, D = c.cfg.head_dim;
-    const T *k = reinterpret_cast<const T *>(a.k) + (int64_t)c.ls * a.kv_sl;
-    const T *q = reinterpret_cast<const T *>(a.q);
+    const int q_per_block = 2 * kGenQ; // two rounds per workgroup
+    const int qsplit = (P + q_per_block - 1) / q_per_block;
+    *n_part = c.cfg.n_q_heads * qsplit;
     const size_t lds = att_generic_lds_bytes(P, D, sizeof(R));
     static bool attr_set = false; // per instantiation
     if (!attr_set) {
@@ -537,9 +631,10 @@ static hipError_t launch_att_generic(const Ctx &c, const ChunkArgs &a, const int
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((att_generic_kernel<T, R>), dim3(a.n_frames, c.cfg.n_q_heads), dim3(256), lds, st, q, a.q_sh,
-                       a.q_st, k, a.kv_sh, a.kv_st, P, D, c.group, c.cfg.n_q_heads, c.cfg.causal, a.frame0, flags,
-                       out);
+    hipLaunchKernelGGL((att_generic_kernel<T, R>), dim3(listed ? kRescoreSlots : a.n_frames, c.cfg.n_q_heads, qsplit),
+                       dim3(256), lds, st, a.q, a.k, a.map, (int64_t)c.ls * a.kv_sl, a.q_sh, a.q_st, a.kv_sh, a.kv_st, P,
+                       D, c.group, c.cfg.n_q_heads, c.cfg.causal, q_per_block, listed ? c.flag_list : nullptr,
+                       listed ? c.flag_count : nullptr, out);
     return hipGetLastError();
 }
 
@@ -550,10 +645,11 @@ static hipError_t launch_select(const Ctx &c, const ChunkArgs &a, const R *att, 
                                 hipStream_t st) {
     SelectArgs<R> s;
     const bool need_att = c.cfg.alpha != 0.0;
-    s.att = (need_att && !a.att_in) ? att : nullptr;
+    s.att = (need_att && !a.have_att_in) ? att : nullptr;
     s.n_part = n_part;
     s.att_scale = (R)(1.0 / ((double)c.cfg.n_q_heads * (double)c.cfg.tokens_per_frame));
-    s.att_in = need_att ? a.att_in : nullptr;
+    s.att_in = a.att_in;
+    s.have_att_in = need_att && a.have_att_in;
     s.fft = (c.cfg.alpha != 1.0) ? fft : nullptr;
     s.alpha = (R)c.cfg.alpha;
     s.P = c.cfg.tokens_per_frame;
@@ -562,12 +658,16 @@ static hipError_t launch_select(const Ctx &c, const ChunkArgs &a, const R *att, 
     s.Hkv = c.cfg.n_kv_heads;
     s.D = c.cfg.head_dim;
     s.frame0 = a.frame0;
-    s.k = reinterpret_cast<const T *>(a.k) + (int64_t)c.ls * a.kv_sl;
-    s.v = reinterpret_cast<const T *>(a.v) + (int64_t)c.ls * a.kv_sl;
+    s.k = a.k;
+    s.v = a.v;
+    s.map = a.map;
+    s.k_off = (int64_t)c.ls * a.kv_sl;
     s.sh = a.kv_sh;
     s.st = a.kv_st;
     s.margin_thr = (R)c.margin_thr;
     s.pass2 = pass2;
+    s.flag_list = c.flag_list;
+    s.flag_count = c.flag_count;
     s.kept_idx = c.kept_idx;
     s.src_tok = c.src_tok;
     s.rep_frame_k = c.rep_frame_k;
@@ -579,10 +679,11 @@ static hipError_t launch_select(const Ctx &c, const ChunkArgs &a, const R *att, 
     s.fsum_v = c.fsum_v;
     s.margin = c.margin;
     s.refined = c.refined;
-    s.dbg_att = a.sig.att;
-    s.dbg_fft = a.sig.fft;
-    s.dbg_fused = a.sig.fused;
-    hipLaunchKernelGGL((select_pool_kernel<T, R>), dim3(a.n_frames), dim3(256), 0, st, s);
+    s.dbg_att = a.dbg_att;
+    s.dbg_fft = a.dbg_fft;
+    s.dbg_fused = a.dbg_fused;
+    s.have_dbg = a.have_dbg;
+    hipLaunchKernelGGL((select_pool_kernel<T, R>), dim3(pass2 ? kRescoreSlots : a.n_frames), dim3(256), 0, st, s);
     return hipGetLastError();
 }
 
@@ -596,8 +697,9 @@ static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, hipStream_t s
     CompactArgs k;
     const int esz = c.esz, D = c.cfg.head_dim;
     const int row_b = D * esz;
-    k.k = reinterpret_cast<const unsigned char *>(a.k);
-    k.v = reinterpret_cast<const unsigned char *>(a.v);
+    k.k = a.k;
+    k.v = a.v;
+    k.map = a.map;
     k.sl_b = a.kv_sl * esz;
     k.sh_b = a.kv_sh * esz;
     k.st_b = a.kv_st * esz;
@@ -608,7 +710,7 @@ static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, hipStream_t s
     k.src_tok = c.src_tok;
     const int upr = row_b / 16; // rows are whole 16-byte units (validated at create)
     k.log_upr = ilog2(upr);
-    k.n_units = a.n_frames * c.kappa * upr;
+    k.units_per_frame = c.kappa * upr;
     k.Hkv = c.cfg.n_kv_heads;
     k.n_slab = c.cfg.n_layers * 2 * c.cfg.n_kv_heads;
     k.F = c.cfg.frames_per_segment;
@@ -624,8 +726,15 @@ static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, hipStream_t s
     k.frame0 = a.frame0;
     k.rep_seg_k = c.rep_seg_k;
     k.rep_seg_v = c.rep_seg_v;
+    k.flag_count = c.flag_count;
     constexpr int ITER = 4;
-    const int gx = (k.n_units + 256 * ITER - 1) / (256 * ITER);
+    int max_slot_frames = 0;
+    for (int s = 0; s < a.map.n_slots; ++s) {
+        const int n = a.map.fstart[s + 1] - a.map.fstart[s];
+        max_slot_frames = n > max_slot_frames ? n : max_slot_frames;
+    }
+    k.bps = (max_slot_frames * k.units_per_frame + 256 * ITER - 1) / (256 * ITER);
+    const int gx = k.bps * a.map.n_slots;
     const int gy = k.n_slab + (seg_last - k.seg_first + 1);
     hipLaunchKernelGGL((compact_kernel<u32x4, ITER>), dim3(gx, gy), dim3(256), 0, st, k);
     return hipGetLastError();
@@ -634,7 +743,7 @@ static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, hipStream_t s
 template <typename T>
 static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
     hipError_t e;
-    const bool need_att = c.cfg.alpha != 0.0 && !a.att_in;
+    const bool need_att = c.cfg.alpha != 0.0 && !a.have_att_in;
     const bool need_fft = c.cfg.alpha != 1.0;
     int n_part = c.cfg.n_q_heads;
     if (need_att) {
@@ -642,12 +751,12 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
         if (c.use_mfma) {
             if ((e = launch_att_mfma(c, a, c.att_part, &n_part, st)) != hipSuccess) return e;
         } else {
-            if ((e = launch_att_generic<T, float>(c, a, nullptr, c.att_part, st)) != hipSuccess) return e;
+            if ((e = launch_att_generic<T, float>(c, a, false, c.att_part, &n_part, st)) != hipSuccess) return e;
         }
     }
     if (need_fft) {
         ProfScope ps(c, MUKV_K_FREQ, st);
-        if ((e = launch_freq<T, float>(c, a, nullptr, c.fft_sig, st)) != hipSuccess) return e;
+        if ((e = launch_freq<T, float>(c, a, false, c.fft_sig, st)) != hipSuccess) return e;
     }
     {
         ProfScope ps(c, MUKV_K_SELECT, st);
@@ -656,11 +765,12 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
     if (c.margin_thr > 0.0) {
         ProfScope ps(c, MUKV_K_REFINE, st);
         // frames with a near-tie at the keep boundary: redo Eq. 1-4 in fp64 and select again
+        int n_part64 = c.cfg.n_q_heads;
         if (need_att)
-            if ((e = launch_att_generic<T, double>(c, a, c.refined, c.att64, st)) != hipSuccess) return e;
+            if ((e = launch_att_generic<T, double>(c, a, true, c.att64, &n_part64, st)) != hipSuccess) return e;
         if (need_fft)
-            if ((e = launch_freq<T, double>(c, a, c.refined, c.fft64, st)) != hipSuccess) return e;
-        if ((e = launch_select<T, double>(c, a, c.att64, c.cfg.n_q_heads, c.fft64, 1, st)) != hipSuccess) return e;
+            if ((e = launch_freq<T, double>(c, a, true, c.fft64, st)) != hipSuccess) return e;
+        if ((e = launch_select<T, double>(c, a, c.att64, n_part64, c.fft64, 1, st)) != hipSuccess) return e;
     }
     ProfScope ps(c, MUKV_K_COMPACT, st);
     return launch_compact(c, a, st);

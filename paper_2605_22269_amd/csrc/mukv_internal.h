@@ -16,6 +16,14 @@ constexpr int kMaxP = 256;        // tokens per frame the per-frame kernels are 
 constexpr int kMaxCand = 1024;    // stage-1 candidates (2*k) held in LDS by the rerank kernel
 constexpr int kMaxGatherK = 1024; // selected frames per question the gather kernel can plan
 
+// one chunk handed to mukv_compress_chunk and not yet launched
+struct PendingChunk {
+    const void *k, *v, *q;
+    const float *att_in;
+    mukv_signals_out sig;
+    int n_frames;
+};
+
 struct ProfEntry {
     int kid;
     hipEvent_t start, stop;
@@ -28,7 +36,13 @@ struct Ctx {
     int kappa, ls, c_kv, group, esz, max_segments;
     bool use_mfma;
     double margin_thr;
-    int64_t n_frames;  // host-side append position
+    int64_t n_frames;  // frames submitted so far (host-side append position)
+    int64_t n_done;    // frames whose kernels have been enqueued
+    int batch_chunks;  // chunks gathered before a chain of launches goes out
+    int max_batch_frames;
+    std::vector<PendingChunk> *pending;
+    int64_t p_kv_sl, p_kv_sh, p_kv_st, p_q_sh, p_q_st; // strides shared by the pending chunks
+    hipStream_t p_stream;
     int64_t store_cap; // tokens per (layer, head) slab of the store
     // cache (device)
     void *store_k, *store_v;
@@ -44,7 +58,8 @@ struct Ctx {
     float *fft_sig;   // [max_chunk_frames][P]
     double *att64;    // [max_chunk_frames][Hq][P] partial fp64 attention of re-scored frames
     double *fft64;    // [max_chunk_frames][P]
-    int32_t *src_tok; // [max_chunk_frames*kappa] chunk-local token of every kept row
+    int32_t *src_tok; // [max_batch_frames*kappa] chunk-local token of every kept row
+    int32_t *flag_list, *flag_count; // batch frames to re-score in fp64, and how many
     // retrieval scratch (device)
     double *qbar;    // [max_questions][c_kv]  group-summed mean query
     double *qq;      // [max_questions][Hkv]   partial squared norms of the mean query
@@ -53,16 +68,39 @@ struct Ctx {
     float *seg_tail; // [2][c_kv] key (K, V) of a segment cut by the question's timestamp
 };
 
-// ---- launchers (defined in the .hip files; all enqueue on `st`, never sync) ----
-struct ChunkArgs {
-    const void *k, *v, *q;
-    const float *att_in;
-    int64_t kv_sl, kv_sh, kv_st; // element strides layer / head / token
-    int64_t q_sh, q_st;
-    int n_frames;
-    int64_t frame0;
-    mukv_signals_out sig;
+// ---- a batch of chunks processed by one chain of launches ----
+// Every chunk handed to mukv_compress_chunk occupies one slot; the kernels see the batch as
+// frames 0..n_frames-1 and resolve a frame to (slot, frame inside the chunk) with FrameMap.
+// The tables travel by value in the kernel arguments, so a captured HIP graph replays them as is.
+constexpr int kMaxSlots = 32;
+struct PtrTable {
+    const void *p[kMaxSlots];
 };
+struct OutTable {
+    float *p[kMaxSlots];
+};
+struct FrameMap {
+    int fstart[kMaxSlots + 1]; // first batch frame of every slot; fstart[n_slots] = n_frames
+    int n_slots;
+};
+// slot of batch frame f (f is uniform over the workgroup at every call site, so this is scalar code)
+__device__ __forceinline__ int find_slot(const FrameMap &m, int f) {
+    int s = 0;
+    while (s + 1 < m.n_slots && f >= m.fstart[s + 1]) ++s;
+    return s;
+}
+
+struct ChunkArgs {
+    PtrTable k, v, q, att_in;      // per slot: chunk base pointers (att_in: float [n][P] or null)
+    OutTable dbg_att, dbg_fft, dbg_fused;
+    FrameMap map;
+    bool have_q, have_att_in, have_dbg;
+    int64_t kv_sl, kv_sh, kv_st; // element strides layer / head / token (same for every slot)
+    int64_t q_sh, q_st;
+    int n_frames;                // frames in the batch
+    int64_t frame0;              // cache position of batch frame 0
+};
+
 
 hipError_t launch_compress(Ctx &c, const ChunkArgs &a, hipStream_t st);
 

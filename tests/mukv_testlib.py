@@ -54,6 +54,7 @@ class Pair:
         self.orc = orc.OracleMuKV(oracle_config(w, **(orc_kw or {})))
         self.stream = synth.SynthStream(w, seed, device="cpu", with_q=with_q)
         self.sig_gpu, self.sig_orc = [], []
+        self.keep_alive = []  # device inputs must outlive a gathered batch
 
     def ingest(self, n_frames=None, att_from_oracle=False):
         """Feeds the next n_frames (default: all remaining) in chunks to both sides."""
@@ -67,12 +68,15 @@ class Pair:
                 att_np = orc.att_signal(qn, kn[self.orc.ls], n, self.w.tokens_per_frame, self.orc.cfg.causal)
                 att_np = att_np.astype(np.float32)
                 att_t = torch.from_numpy(att_np).cuda()
+                kd, vd = k.cuda(), v.cuda()
+                self.keep_alive += [kd, vd, att_t]
                 self.sig_orc.append(self.orc.compress_chunk(kn, vn, att=att_np.astype(np.float64)))
-                self.sig_gpu.append(self.gpu.compress_chunk(k.cuda(), v.cuda(), att_signal=att_t, want_signals=True))
+                self.sig_gpu.append(self.gpu.compress_chunk(kd, vd, att_signal=att_t, want_signals=True))
             else:
+                kd, vd, qd = k.cuda(), v.cuda(), (q.cuda() if q is not None else None)
+                self.keep_alive += [kd, vd, qd]
                 self.sig_orc.append(self.orc.compress_chunk(kn, vn, q_last=qn))
-                self.sig_gpu.append(self.gpu.compress_chunk(k.cuda(), v.cuda(), q.cuda() if q is not None else None,
-                                                            want_signals=True))
+                self.sig_gpu.append(self.gpu.compress_chunk(kd, vd, qd, want_signals=True))
             torch.cuda.synchronize()
             todo -= n
 
@@ -80,6 +84,8 @@ class Pair:
     def check_compress(self, exact_reps=True):
         w, tol = self.w, TOL[self.w.dtype]
         alpha = self.orc.cfg.alpha
+        self.gpu.flush()
+        torch.cuda.synchronize()
         for so, sg in zip(self.sig_orc, self.sig_gpu):
             if alpha != 0.0:
                 assert np.abs(sg["att"].cpu().numpy() - so["att"]).max() <= tol

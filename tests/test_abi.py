@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def good_cfg(**kw):
     base = dict(n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=64, tokens_per_frame=49, frames_per_segment=8,
                 superpatches_per_frame=4, dtype=mk.MUKV_F32, keep_ratio=0.25, alpha=0.7, causal=1, score_layer=-1,
-                max_frames=64, max_chunk_frames=8, max_questions=2, device_id=0, att_path=0, reserved0=0,
+                max_frames=64, max_chunk_frames=8, max_questions=2, device_id=0, att_path=0, batch_chunks=0,
                 refine_margin=-1.0)
     base.update(kw)
     return mk.mukv_config(**base)
@@ -51,6 +51,8 @@ def test_strerror_covers_every_status():
     ("head_dim", 256, mk.MUKV_ERR_UNSUPPORTED),
     ("tokens_per_frame", 300, mk.MUKV_ERR_UNSUPPORTED),
     ("max_frames", 0, mk.MUKV_ERR_INVALID_ARG),
+    ("batch_chunks", -1, mk.MUKV_ERR_INVALID_ARG),
+    ("batch_chunks", 33, mk.MUKV_ERR_UNSUPPORTED),
 ])
 def test_create_rejects_bad_config_on_the_host(field, value, status):
     lib = mk.load()
@@ -67,6 +69,7 @@ def test_null_arguments():
     assert lib.mukv_create(C.byref(cfg), None) == mk.MUKV_ERR_INVALID_ARG
     assert lib.mukv_destroy(None) == mk.MUKV_OK
     assert lib.mukv_reset(None) == mk.MUKV_ERR_INVALID_ARG
+    assert lib.mukv_flush(None) == mk.MUKV_ERR_INVALID_ARG
     st = mk.mukv_strides(1, 1, 1)
     assert lib.mukv_compress_chunk(None, None, None, C.byref(st), None, None, None, 1, None, None) == mk.MUKV_ERR_INVALID_ARG
     prm = mk.mukv_retrieve_params(0, 1, 1, 0, -1, 0, 0.3)

@@ -272,3 +272,47 @@ def test_no_rescoring_when_disabled():
     st = p.check_compress()
     assert int(st["refined"].sum()) == 0
     p.close()
+
+
+# ------------------------------------------------------------------ gathered (batched) chunks --
+@pytest.mark.parametrize("name,frames,chunk,batch", [("7b", 21, 4, 3), ("tiny", 30, 4, 32), ("72b", 19, 8, 2)])
+def test_batched_chunks_match_oracle(name, frames, chunk, batch):
+    w = W[name].scaled(n_frames=frames, n_layers=2, n_questions=2)
+    p = Pair(w, seed=71, chunk=chunk, gpu_kw={"batch_chunks": batch})
+    p.ingest()
+    p.check_compress()
+    p.check_retrieve(questions_for(w, [16, 24], 500), mk.MUKV_SEMI, 2, 5, 0.3)
+    p.close()
+
+
+def test_batching_does_not_change_a_bit():
+    w = W["7b"].scaled(n_frames=26, n_layers=2)
+    ref = None
+    for batch in (1, 2, 5):
+        p = Pair(w, seed=72, chunk=4, gpu_kw={"batch_chunks": batch})
+        p.ingest()
+        st = p.check_compress()
+        cur = {k: st[k].cpu().numpy() for k in ("kept_idx", "rep_frame_k", "rep_seg_k", "rep_patch_v", "margin")}
+        cur["fused"] = torch.cat([sg["fused"] for sg in p.sig_gpu]).cpu().numpy()
+        if ref is not None:
+            for k in cur:
+                np.testing.assert_array_equal(cur[k], ref[k], err_msg=f"{k} batch={batch}")
+        ref = ref or cur
+        p.close()
+
+
+def test_batch_is_flushed_when_the_layout_changes():
+    # the second chunk comes with other strides (a slice of a larger buffer): the gathered chunk
+    # must be launched with its own strides first
+    w = W["tiny"].scaled(n_frames=8, n_layers=2, n_kv_heads=2)
+    p = Pair(w, seed=73, chunk=4, gpu_kw={"batch_chunks": 4})
+    P = w.tokens_per_frame
+    k, v, q = p.stream.next_chunk(8)
+    kd, vd, qd = k.cuda(), v.cuda(), q.cuda()
+    k0, v0, q0 = kd[:, :, : 4 * P].contiguous(), vd[:, :, : 4 * P].contiguous(), qd[:, : 4 * P].contiguous()
+    p.sig_orc.append(p.orc.compress_chunk(np_view(k[:, :, : 4 * P]), np_view(v[:, :, : 4 * P]), q_last=np_view(q[:, : 4 * P])))
+    p.sig_gpu.append(p.gpu.compress_chunk(k0, v0, q0, want_signals=True))
+    p.sig_orc.append(p.orc.compress_chunk(np_view(k[:, :, 4 * P:]), np_view(v[:, :, 4 * P:]), q_last=np_view(q[:, 4 * P:])))
+    p.sig_gpu.append(p.gpu.compress_chunk(kd[:, :, 4 * P:], vd[:, :, 4 * P:], qd[:, 4 * P:], want_signals=True))
+    p.check_compress()
+    p.close()
