@@ -39,7 +39,7 @@ __device__ __forceinline__ double sqrt_t(double x) { return sqrt(x); }
 __device__ __forceinline__ float abs_t(float x) { return fabsf(x); }
 __device__ __forceinline__ double abs_t(double x) { return fabs(x); }
 
-constexpr int kFreqBlocksPerFrame = 4;
+constexpr int kFreqBlocksPerFrame = 7;
 constexpr int kRescoreSlots = 4; // grid.x of the fp64 re-scoring kernels; they loop over the list
 
 template <typename T, typename R, int D>
@@ -54,11 +54,17 @@ __global__ __launch_bounds__(256) void freq_signal_kernel(PtrTable ktab, FrameMa
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int p = lane % N, sub = lane / N;
 
-    R twr[LOG], twi[LOG];
+    // Per stage and lane: the butterfly is written branch-free as (partner + sg*own) * w, with
+    // sg = +1, w = 1 on the lanes that take the sum and sg = -1, w = twiddle on the others.
+    R twr[LOG], twi[LOG], sg[LOG];
 #pragma unroll
     for (int s = 0; s < LOG; ++s) {
         const int h = N >> (s + 1);
         sincospi_t(-(R)(p & (h - 1)) / (R)h, &twi[s], &twr[s]);
+        const bool lower = (p & h) != 0;
+        sg[s] = lower ? (R)-1 : (R)1;
+        twr[s] = lower ? twr[s] : (R)1;
+        twi[s] = lower ? twi[s] : (R)0;
     }
     const int kb = bitrev<N>(p);
     const int partner = bitrev<N>((N - kb) & (N - 1)) + sub * N;
@@ -73,49 +79,47 @@ __global__ __launch_bounds__(256) void freq_signal_kernel(PtrTable ktab, FrameMa
     const T *k = reinterpret_cast<const T *>(ktab.p[slot]) + k_off + (int64_t)(f - map.fstart[slot]) * P * st;
     // the workgroup's waves walk over the frame's tokens, GROUPS tokens per wave and step
     const int stride = kFreqBlocksPerFrame * 4 * GROUPS;
-    for (int t0 = (blockIdx.y * 4 + wave) * GROUPS; t0 < P; t0 += stride) {
+    // The (token, head) transforms of this wave form one sequence; the two key elements of step
+    // n+1 are loaded before step n is computed, so the load latency hides behind the butterflies.
+    const int t_first = (blockIdx.y * 4 + wave) * GROUPS;
+    auto load_pair = [&](int t0, int g, T &a0, T &a1) {
+        const int tok = t0 + sub < P ? t0 + sub : P - 1;
+        const T *r = k + (int64_t)tok * st + (int64_t)g * sh + 2 * p;
+        a0 = r[0];
+        a1 = r[1];
+    };
+    T n0, n1;
+    if (t_first < P) load_pair(t_first, 0, n0, n1);
+    for (int t0 = t_first; t0 < P; t0 += stride) {
         const int tok = t0 + sub;
         const bool valid = tok < P;
-        const T *row = k + (int64_t)(valid ? tok : P - 1) * st + 2 * p;
         R total = 0;
-        for (int g0 = 0; g0 < Hkv; g0 += 4) { // four heads' loads in flight
-            T x0[4], x1[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const T *r = row + (int64_t)(g0 + u < Hkv ? g0 + u : Hkv - 1) * sh;
-                x0[u] = r[0];
-                x1[u] = r[1];
+        for (int g = 0; g < Hkv; ++g) {
+            const T x0 = n0, x1 = n1;
+            {   // next step: next head of this token, else head 0 of the wave's next token
+                const bool wrap = g + 1 == Hkv;
+                const int tn = wrap ? t0 + stride : t0;
+                load_pair(tn < P ? tn : t0, wrap ? 0 : g + 1, n0, n1);
             }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (g0 + u >= Hkv) break;
-                R zr = (R)to_float(x0[u]), zi = (R)to_float(x1[u]);
+            {
+                R zr = (R)to_float(x0), zi = (R)to_float(x1);
 #pragma unroll
                 for (int s = 0; s < LOG; ++s) {
                     const int h = N >> (s + 1);
                     const R pr = __shfl_xor(zr, h), pi = __shfl_xor(zi, h);
-                    if (p & h) {
-                        const R dr = pr - zr, di = pi - zi;
-                        zr = dr * twr[s] - di * twi[s];
-                        zi = dr * twi[s] + di * twr[s];
-                    } else {
-                        zr += pr;
-                        zi += pi;
-                    }
+                    const R tr = pr + sg[s] * zr, ti = pi + sg[s] * zi;
+                    zr = tr * twr[s] - ti * twi[s];
+                    zi = tr * twi[s] + ti * twr[s];
                 }
                 // lane p now holds Z[kb]; fetch Z[(N-kb) mod N]
                 const R pr = __shfl(zr, partner), pi = __shfl(zi, partner);
-                R c;
-                if (kb == 0) {
-                    c = abs_t(zr + zi) + abs_t(zr - zi); // X[0] and X[D/2]
-                } else {
-                    const R er = (R)0.5 * (zr + pr), ei = (R)0.5 * (zi - pi);
-                    const R odr = (R)0.5 * (zi + pi), odi = (R)-0.5 * (zr - pr);
-                    const R xr = er + (odr * uwr - odi * uwi);
-                    const R xi = ei + (odr * uwi + odi * uwr);
-                    c = (R)2 * sqrt_t(xr * xr + xi * xi);
-                }
-                total += c;
+                const R er = (R)0.5 * (zr + pr), ei = (R)0.5 * (zi - pi);
+                const R odr = (R)0.5 * (zi + pi), odi = (R)-0.5 * (zr - pr);
+                const R xr = er + (odr * uwr - odi * uwi);
+                const R xi = ei + (odr * uwi + odi * uwr);
+                const R c_mid = (R)2 * sqrt_t(xr * xr + xi * xi);
+                const R c_end = abs_t(zr + zi) + abs_t(zr - zi); // bins 0 and D/2 (held by the lane with kb = 0)
+                total += (kb == 0) ? c_end : c_mid;
             }
         }
 #pragma unroll
@@ -135,6 +139,25 @@ __global__ __launch_bounds__(256) void freq_signal_kernel(PtrTable ktab, FrameMa
 // run-to-run identical.
 // out: [frame][Hq * gridDim.z][P] (R) partial sums over this workgroup's query rows.
 // ------------------------------------------------------------------------------------------
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// 16 bytes of payload -> floats in LDS (8 bf16 or 4 fp32 values)
+template <typename T>
+__device__ __forceinline__ void unpack_to_float(u32x4 raw, float *dst);
+template <>
+__device__ __forceinline__ void unpack_to_float<uint16_t>(u32x4 raw, float *dst) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        dst[2 * i] = __uint_as_float(raw[i] << 16);
+        dst[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
+    }
+}
+template <>
+__device__ __forceinline__ void unpack_to_float<float>(u32x4 raw, float *dst) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dst[i] = __uint_as_float(raw[i]);
+}
+
 __device__ __forceinline__ float exp_t(float x) { return expf(x); }
 __device__ __forceinline__ double exp_t(double x) { return exp(x); }
 
@@ -168,18 +191,36 @@ __global__ __launch_bounds__(256) void att_generic_kernel(PtrTable qtab, PtrTabl
     const int i_lo = z * q_per_block;
     const int i_hi = (i_lo + q_per_block < P) ? i_lo + q_per_block : P;
     const int n_keys = causal ? i_hi : P; // keys any query of this workgroup can see
-    for (int e = tid; e < n_keys * D; e += 256) {
-        const int j = e / D, d = e - j * D;
-        Ks[j * ldk + d] = to_float(kf[(int64_t)j * k_st + d]);
+    // stage keys: 16-byte units, eight loads in flight per thread
+    constexpr int EPU = 16 / sizeof(T);          // elements per unit
+    const int upr = D / EPU;                      // units per row (D*sizeof(T) is a multiple of 16)
+    const int n_ku = n_keys * upr;
+    for (int u0 = tid; u0 < n_ku; u0 += 8 * 256) {
+        u32x4 raw[8];
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const int u = u0 + b * 256 < n_ku ? u0 + b * 256 : n_ku - 1;
+            const int j = u / upr, c = u - j * upr;
+            raw[b] = *reinterpret_cast<const u32x4 *>(kf + (int64_t)j * k_st + c * EPU);
+        }
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const int u = u0 + b * 256;
+            if (u < n_ku) {
+                const int j = u / upr, c = u - j * upr;
+                unpack_to_float<T>(raw[b], Ks + j * ldk + c * EPU);
+            }
+        }
     }
     const R scale = (R)1 / sqrt_t((R)D);
     R acc[4] = {0, 0, 0, 0};
     for (int i0 = i_lo; i0 < i_hi; i0 += kGenQ) {
         __syncthreads();
-        for (int e = tid; e < kGenQ * D; e += 256) {
-            const int qi = e / D, d = e - qi * D;
+        for (int u = tid; u < kGenQ * upr; u += 256) {
+            const int qi = u / upr, c = u - qi * upr;
             const int i = i0 + qi < i_hi ? i0 + qi : i_hi - 1;
-            qs[e] = to_float(qf[(int64_t)i * q_st + d]);
+            const u32x4 raw = *reinterpret_cast<const u32x4 *>(qf + (int64_t)i * q_st + c * EPU);
+            unpack_to_float<T>(raw, qs + qi * D + c * EPU);
         }
         __syncthreads();
         const int iw = i0 + 4 * wave; // this wave's four queries: iw .. iw+3
@@ -489,8 +530,6 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
 // sums are exact for bf16 / fp32 payloads of ordinary dynamic range, so any chunking gives the
 // same bits.
 // ------------------------------------------------------------------------------------------
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
 struct CompactArgs {
     PtrTable k, v;               // per slot: chunk base
     FrameMap map;
