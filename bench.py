@@ -5,7 +5,9 @@ One step = one pass of the whole hot path over one synthetic stream that is
 already resident in HBM: mukv_compress_chunk for every chunk of the stream
 (attention + frequency signals, fusion, per-frame keep, all-layer KV compaction,
 block keys), then mukv_retrieve + mukv_gather_kv for the workload's questions.
-Prints ONE JSON line ("Measurement").
+Prints ONE JSON line: throughput of the whole step, per-kernel times from HIP
+events, the HBM roofline of the dominant kernel, and the CPU oracle's rate on
+a sample of the same stream.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload hour] [--chunk-frames 8]
 """
@@ -23,6 +25,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+# HBM bytes actually moved per algorithmic byte, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs on the 1-hour shape (256 frames per launch), calibrated with a plain copy kernel; the
+# summary of those runs is kept under profiles/.
+TRAFFIC_PER_ALGORITHMIC = {"compact": 707.0 / 704.6, "gather": 88.1 / 88.08}
 
 
 def parse():
@@ -38,6 +44,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-frames", type=int, default=1024)
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="also run the library's plain copy kernel once on this many MiB (reference for rocprofv3 "
+                         "traffic counters)")
     ap.add_argument("--seed", type=int, default=2605)
     return ap.parse_args()
 
@@ -222,13 +231,23 @@ def main():
                      "frac_of_peak": path_gbs / HBM_PEAK_GBS},
         "kernel_us": per_kernel,
         "roofline": {"kernel": "compact_kernel", "bound": "hbm", "achieved": compact_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": compact_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": compact_gbs / HBM_PEAK_GBS,
+                     "traffic": compact_bytes * TRAFFIC_PER_ALGORITHMIC["compact"],
                      "bytes_per_launch": compact_bytes, "us_per_launch": compact_us},
         "roofline_gather": {"kernel": "gather_kv_kernel", "bound": "hbm", "achieved": gather_gbs, "peak": HBM_PEAK_GBS,
-                            "unit": "GB/s", "frac": gather_gbs / HBM_PEAK_GBS, "traffic": None,
+                            "unit": "GB/s", "frac": gather_gbs / HBM_PEAK_GBS,
+                            "traffic": gather_bytes * TRAFFIC_PER_ALGORITHMIC["gather"],
                             "bytes_per_launch": gather_bytes, "us_per_launch": gather_us},
         "setup_s": {"generate_stream": t_gen},
     }
+
+    if a.calibrate_copy_mib:
+        nb = a.calibrate_copy_mib << 20
+        src = torch.empty(nb, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        mk.mukv_plain_copy(dst.data_ptr(), src.data_ptr(), nb, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        res["calibration_copy_bytes"] = nb
 
     # ---- the oracle on the host cores, on a bounded sample of the same stream -------------
     if not a.no_cpu_baseline:

@@ -266,6 +266,11 @@ typedef struct mukv_profile {
 int mukv_profile_begin(mukv_ctx *ctx);
 int mukv_profile_end(mukv_ctx *ctx, mukv_profile *out);
 
+/* Measurement aid: a plain 16-bytes-per-thread device copy of `bytes` bytes (a
+ * multiple of 16; both pointers 16-byte aligned) on `stream`.  Used to calibrate
+ * hardware traffic counters against a kernel whose HBM traffic is known. */
+int mukv_plain_copy(void *dst, const void *src, int64_t bytes, void *stream);
+
 /* Fills *out (host).  Does not synchronise. */
 int mukv_get_state(const mukv_ctx *ctx, mukv_state *out);
 

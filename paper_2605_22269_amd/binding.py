@@ -68,7 +68,8 @@ class mukv_profile(C.Structure):
 
 
 EXPORTS = ("mukv_create", "mukv_destroy", "mukv_reset", "mukv_flush", "mukv_compress_chunk", "mukv_retrieve",
-           "mukv_gather_kv", "mukv_profile_begin", "mukv_profile_end", "mukv_get_state", "mukv_strerror")
+           "mukv_gather_kv", "mukv_profile_begin", "mukv_profile_end", "mukv_plain_copy", "mukv_get_state",
+           "mukv_strerror")
 
 _lib = None
 
@@ -92,6 +93,7 @@ def load():
     lib.mukv_retrieve.argtypes = [vp, vp, vp, i32, C.POINTER(mukv_retrieve_params), vp, vp, vp, vp, vp]
     lib.mukv_gather_kv.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.mukv_get_state.argtypes = [vp, C.POINTER(mukv_state)]
+    lib.mukv_plain_copy.argtypes = [vp, vp, C.c_int64, vp]
     lib.mukv_profile_begin.argtypes = [vp]
     lib.mukv_profile_end.argtypes = [vp, C.POINTER(mukv_profile)]
     lib.mukv_strerror.argtypes = [i32]
@@ -155,6 +157,10 @@ def mukv_profile_end(h) -> dict:
     p = mukv_profile()
     _check(load().mukv_profile_end(h, C.byref(p)), "mukv_profile_end")
     return {n: {"ms": p.ms[i], "launches": p.launches[i]} for i, n in enumerate(KERNEL_NAMES)}
+
+
+def mukv_plain_copy(dst_ptr, src_ptr, n_bytes, stream):
+    _check(load().mukv_plain_copy(dst_ptr, src_ptr, n_bytes, stream), "mukv_plain_copy")
 
 
 def mukv_get_state(h) -> mukv_state:

@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmukv.so")
-SOURCES = ["api.hip", "compress.hip", "att_mfma.hip", "retrieve.hip"]
+SOURCES = ["api.hip", "compress.hip", "att_mfma.hip", "retrieve.hip"]  # traffic_probe.cpp is a separate program
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [
@@ -28,6 +28,19 @@ def build_lib(verbose: bool = False) -> str:
     return LIB
 
 
+PROBE = os.path.join(PKG, "traffic_probe")
+
+
+def build_probe(verbose: bool = False) -> str:
+    """Small torch-free driver used for rocprofv3 hardware-counter runs (see profiles/)."""
+    cmd = [HIPCC, "-O2", "-std=c++17", "-I", os.path.join(ROOT, "include"), os.path.join(CSRC, "traffic_probe.cpp"),
+           "-o", PROBE, "-L", PKG, "-lmukv", "-Wl,-rpath,$ORIGIN"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return PROBE
+
+
 def stale() -> bool:
     if not os.path.exists(LIB):
         return True
@@ -38,3 +51,4 @@ def stale() -> bool:
 
 if __name__ == "__main__":
     print(build_lib(verbose=True))
+    print(build_probe(verbose=True))

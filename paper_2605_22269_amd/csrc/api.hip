@@ -366,6 +366,14 @@ int mukv_gather_kv(mukv_ctx *ctx, const int32_t *frame_idx, int32_t B, int32_t k
                : MUKV_ERR_HIP;
 }
 
+int mukv_plain_copy(void *dst, const void *src, int64_t bytes, void *stream) {
+    if (!dst || !src || bytes < 0 || (bytes & 15)) return MUKV_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(dst) & 15) || (reinterpret_cast<uintptr_t>(src) & 15)) return MUKV_ERR_UNSUPPORTED;
+    if (bytes / 16 / 1024 > 0x7fffffff) return MUKV_ERR_UNSUPPORTED;
+    return mukv::launch_plain_copy(dst, src, bytes, reinterpret_cast<hipStream_t>(stream)) == hipSuccess ? MUKV_OK
+                                                                                                         : MUKV_ERR_HIP;
+}
+
 int mukv_get_state(const mukv_ctx *ctx, mukv_state *out) {
     if (!ctx || !out) return MUKV_ERR_INVALID_ARG;
     const Ctx &c = ctx->c;

@@ -141,6 +141,8 @@ struct ProfScope {
     }
 };
 
+hipError_t launch_plain_copy(void *dst, const void *src, int64_t bytes, hipStream_t st);
+
 // True when the matrix-core attention kernel covers this configuration.
 bool att_mfma_supported(const mukv_config &c);
 

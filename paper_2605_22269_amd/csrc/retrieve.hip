@@ -522,6 +522,32 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(GatherArgs a) {
     }
 }
 
+// Plain streaming copy, 4 x 16 bytes per thread: the calibration kernel for traffic counters.
+typedef unsigned int cp_u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void plain_copy_kernel(const cp_u32x4 *__restrict__ src, cp_u32x4 *__restrict__ dst,
+                                                         int64_t n_units) {
+    const int64_t u0 = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+    cp_u32x4 t[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t u = u0 + i * 256;
+        t[i] = src[u < n_units ? u : n_units - 1];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t u = u0 + i * 256;
+        if (u < n_units) dst[u] = t[i];
+    }
+}
+
+hipError_t launch_plain_copy(void *dst, const void *src, int64_t bytes, hipStream_t st) {
+    const int64_t n_units = bytes / 16;
+    if (n_units == 0) return hipSuccess;
+    hipLaunchKernelGGL(plain_copy_kernel, dim3((unsigned)((n_units + 1023) / 1024)), dim3(256), 0, st,
+                       reinterpret_cast<const cp_u32x4 *>(src), reinterpret_cast<cp_u32x4 *>(dst), n_units);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
