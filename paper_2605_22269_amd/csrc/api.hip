@@ -61,9 +61,12 @@ void free_all(Ctx &c) {
     void *ptrs[] = {c.store_k,    c.store_v,    c.kept_idx,  c.rep_frame_k, c.rep_frame_v, c.rep_patch_k,
                     c.rep_patch_v, c.rep_seg_k, c.rep_seg_v, c.cnt_patch,   c.fsum_k,      c.fsum_v,
                     c.ssum_k,      c.ssum_v,    c.margin,      c.refined,   c.att_part,  c.fft_sig,     c.att64,       c.fft64,
-                    c.src_tok,     c.flag_list,   c.flag_count, c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail};
+                    c.src_tok,     c.src_tok2,    c.flag_list[0], c.flag_list[1], c.flag_count, c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
+    if (c.side) (void)hipStreamDestroy(c.side);
+    if (c.ev_fork) (void)hipEventDestroy(c.ev_fork);
+    if (c.ev_join) (void)hipEventDestroy(c.ev_join);
 }
 
 } // namespace
@@ -143,9 +146,14 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(dalloc(&c.att64, MC * n_part_max * P));
     ok(dalloc(&c.fft64, MC * P));
     ok(dalloc(&c.src_tok, MC * c.kappa));
-    ok(dalloc(&c.flag_list, MC));
-    ok(dalloc(&c.flag_count, 1));
-    if (e == hipSuccess) ok(hipMemset(c.flag_count, 0, sizeof(int32_t)));
+    ok(dalloc(&c.src_tok2, MC * c.kappa));
+    ok(dalloc(&c.flag_list[0], MC));
+    ok(dalloc(&c.flag_list[1], MC));
+    ok(dalloc(&c.flag_count, 2));
+    if (e == hipSuccess) ok(hipMemset(c.flag_count, 0, 2 * sizeof(int32_t)));
+    ok(hipStreamCreateWithFlags(&c.side, hipStreamNonBlocking));
+    ok(hipEventCreateWithFlags(&c.ev_fork, hipEventDisableTiming));
+    ok(hipEventCreateWithFlags(&c.ev_join, hipEventDisableTiming));
     ok(dalloc(&c.qbar, MQ * C));
     ok(dalloc(&c.qq, MQ * cfg->n_kv_heads));
     ok(dalloc(&c.s_frm, MQ * MF));
@@ -242,6 +250,7 @@ static int flush_pending(Ctx &c) {
     a.q_st = c.p_q_st;
     a.n_frames = nf;
     a.frame0 = c.n_done;
+    a.parity = 0;
     c.pending->clear();
     c.n_done += nf;
     if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;

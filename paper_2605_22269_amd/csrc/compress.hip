@@ -21,6 +21,11 @@ namespace mukv {
 // 2*sum_{0<m<D/2} |X[m]|.  One wave handles 64/N tokens at a time and loops over the KV heads.
 // R is the arithmetic type (float for the main path, double for re-scored frames).
 // ------------------------------------------------------------------------------------------
+template <typename T>
+struct __align__(2 * sizeof(T)) Pair2 {
+    T a, b;
+};
+
 template <int N>
 __device__ __forceinline__ int bitrev(int x) {
     int r = 0;
@@ -40,7 +45,40 @@ __device__ __forceinline__ float abs_t(float x) { return fabsf(x); }
 __device__ __forceinline__ double abs_t(double x) { return fabs(x); }
 
 constexpr int kFreqBlocksPerFrame = 7;
-constexpr int kRescoreSlots = 4; // grid.x of the fp64 re-scoring kernels; they loop over the list
+
+// sum over the N consecutive lanes of a transform (N a power of two <= 64), result in every lane
+template <int N, typename R>
+__device__ __forceinline__ R group_sum(R v) {
+    if constexpr (N > 1) {
+        v += lane_xor<N / 2>(v);
+        return group_sum<N / 2>(v);
+    } else {
+        return v;
+    }
+}
+
+// Radix-2 decimation-in-frequency stages S..LOG-1 of the N-point transform held one point per
+// lane, for GH independent transforms at once.  Stage S pairs lanes N >> (S+1) apart.
+template <int N, int S, int LOG, typename R, int GH>
+__device__ __forceinline__ void fft_stages(R (&zr)[GH], R (&zi)[GH], const R *sg, const R *twr, const R *twi) {
+    if constexpr (S < LOG) {
+        constexpr int h = N >> (S + 1);
+        R pr[GH], pi[GH];
+#pragma unroll
+        for (int u = 0; u < GH; ++u) {
+            pr[u] = lane_xor<h>(zr[u]);
+            pi[u] = lane_xor<h>(zi[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < GH; ++u) {
+            const R tr = pr[u] + sg[S] * zr[u], ti = pi[u] + sg[S] * zi[u];
+            zr[u] = tr * twr[S] - ti * twi[S];
+            zi[u] = tr * twi[S] + ti * twr[S];
+        }
+        fft_stages<N, S + 1, LOG, R, GH>(zr, zi, sg, twr, twi);
+    }
+}
+constexpr int kRescoreSlots = 1; // grid.x of the fp64 re-scoring kernels; they loop over the list
 
 template <typename T, typename R, int D>
 __global__ __launch_bounds__(256) void freq_signal_kernel(PtrTable ktab, FrameMap map, int64_t k_off, int64_t sh,
@@ -79,51 +117,60 @@ __global__ __launch_bounds__(256) void freq_signal_kernel(PtrTable ktab, FrameMa
     const T *k = reinterpret_cast<const T *>(ktab.p[slot]) + k_off + (int64_t)(f - map.fstart[slot]) * P * st;
     // the workgroup's waves walk over the frame's tokens, GROUPS tokens per wave and step
     const int stride = kFreqBlocksPerFrame * 4 * GROUPS;
-    // The (token, head) transforms of this wave form one sequence; the two key elements of step
-    // n+1 are loaded before step n is computed, so the load latency hides behind the butterflies.
+    // Up to four heads of a token are transformed together (independent butterflies hide the
+    // lane-exchange latency), and the key elements of the next group are loaded before the
+    // current group is computed.
+    constexpr int GH = 4;
     const int t_first = (blockIdx.y * 4 + wave) * GROUPS;
-    auto load_pair = [&](int t0, int g, T &a0, T &a1) {
+    auto load_group = [&](int t0, int g0, T *a0, T *a1) {
         const int tok = t0 + sub < P ? t0 + sub : P - 1;
-        const T *r = k + (int64_t)tok * st + (int64_t)g * sh + 2 * p;
-        a0 = r[0];
-        a1 = r[1];
+        const T *r = k + (int64_t)tok * st + 2 * p;
+#pragma unroll
+        for (int u = 0; u < GH; ++u) { // both elements of the lane in one load
+            const Pair2<T> pr = *reinterpret_cast<const Pair2<T> *>(r + (int64_t)(g0 + u < Hkv ? g0 + u : Hkv - 1) * sh);
+            a0[u] = pr.a;
+            a1[u] = pr.b;
+        }
     };
-    T n0, n1;
-    if (t_first < P) load_pair(t_first, 0, n0, n1);
+    T n0[GH], n1[GH];
+    if (t_first < P) load_group(t_first, 0, n0, n1);
     for (int t0 = t_first; t0 < P; t0 += stride) {
         const int tok = t0 + sub;
         const bool valid = tok < P;
         R total = 0;
-        for (int g = 0; g < Hkv; ++g) {
-            const T x0 = n0, x1 = n1;
-            {   // next step: next head of this token, else head 0 of the wave's next token
-                const bool wrap = g + 1 == Hkv;
-                const int tn = wrap ? t0 + stride : t0;
-                load_pair(tn < P ? tn : t0, wrap ? 0 : g + 1, n0, n1);
-            }
-            {
-                R zr = (R)to_float(x0), zi = (R)to_float(x1);
+        for (int g0 = 0; g0 < Hkv; g0 += GH) {
+            R zr[GH], zi[GH];
 #pragma unroll
-                for (int s = 0; s < LOG; ++s) {
-                    const int h = N >> (s + 1);
-                    const R pr = __shfl_xor(zr, h), pi = __shfl_xor(zi, h);
-                    const R tr = pr + sg[s] * zr, ti = pi + sg[s] * zi;
-                    zr = tr * twr[s] - ti * twi[s];
-                    zi = tr * twi[s] + ti * twr[s];
-                }
-                // lane p now holds Z[kb]; fetch Z[(N-kb) mod N]
-                const R pr = __shfl(zr, partner), pi = __shfl(zi, partner);
-                const R er = (R)0.5 * (zr + pr), ei = (R)0.5 * (zi - pi);
-                const R odr = (R)0.5 * (zi + pi), odi = (R)-0.5 * (zr - pr);
+            for (int u = 0; u < GH; ++u) {
+                zr[u] = (R)to_float(n0[u]);
+                zi[u] = (R)to_float(n1[u]);
+            }
+            {   // next group: further heads of this token, else the first heads of the wave's next token
+                const bool wrap = g0 + GH >= Hkv;
+                const int tn = wrap ? t0 + stride : t0;
+                load_group(tn < P ? tn : t0, wrap ? 0 : g0 + GH, n0, n1);
+            }
+            fft_stages<N, 0, LOG, R, GH>(zr, zi, sg, twr, twi);
+            // lane p now holds Z[kb]; fetch Z[(N-kb) mod N]
+            R pr[GH], pi[GH];
+#pragma unroll
+            for (int u = 0; u < GH; ++u) {
+                pr[u] = __shfl(zr[u], partner);
+                pi[u] = __shfl(zi[u], partner);
+            }
+#pragma unroll
+            for (int u = 0; u < GH; ++u) {
+                const R er = (R)0.5 * (zr[u] + pr[u]), ei = (R)0.5 * (zi[u] - pi[u]);
+                const R odr = (R)0.5 * (zi[u] + pi[u]), odi = (R)-0.5 * (zr[u] - pr[u]);
                 const R xr = er + (odr * uwr - odi * uwi);
                 const R xi = ei + (odr * uwi + odi * uwr);
                 const R c_mid = (R)2 * sqrt_t(xr * xr + xi * xi);
-                const R c_end = abs_t(zr + zi) + abs_t(zr - zi); // bins 0 and D/2 (held by the lane with kb = 0)
-                total += (kb == 0) ? c_end : c_mid;
+                const R c_end = abs_t(zr[u] + zi[u]) + abs_t(zr[u] - zi[u]); // bins 0 and D/2 (lane with kb = 0)
+                const R c = (kb == 0) ? c_end : c_mid;
+                total += (g0 + u < Hkv) ? c : (R)0;
             }
         }
-#pragma unroll
-        for (int o = N / 2; o > 0; o >>= 1) total += __shfl_xor(total, o);
+        total = group_sum<N>(total);
         if (p == 0 && valid) out[(int64_t)f * P + tok] = total / (R)(Hkv * D);
     }
     }
@@ -176,8 +223,8 @@ __global__ __launch_bounds__(256) void att_generic_kernel(PtrTable qtab, PtrTabl
     const int n_e = flag_list ? *flag_count : (int)gridDim.x;
     for (int e_idx = blockIdx.x; e_idx < n_e; e_idx += gridDim.x) {
     const int f = flag_list ? flag_list[e_idx] : e_idx;
-    const int ldk = D + 1;
-    float *Ks = reinterpret_cast<float *>(smem_raw);   // [P][D+1]
+    const int ldk = D + 4; // 16-byte aligned rows; 4-word lane stride keeps 16 lanes on distinct banks
+    float *Ks = reinterpret_cast<float *>(smem_raw);   // [P][D+4]
     float *qs = Ks + (size_t)P * ldk;                   // [kGenQ][D]
     size_t n_fl = (size_t)P * ldk + kGenQ * D;
     n_fl += n_fl & 1;
@@ -239,19 +286,23 @@ __global__ __launch_bounds__(256) void att_generic_kernel(PtrTable qtab, PtrTabl
             const int j = lane + 64 * t;
             jrow[t] = (j < nj_max ? j : nj_max - 1) * ldk;
         }
-        const int nt_use = (nj_max + 63) >> 6; // 64-key groups that hold a visible key
-        for (int d = 0; d < D; ++d) {
-            R qq[4];
+        for (int d = 0; d < D; d += 4) { // 8 x 16-byte LDS reads feed 64 multiply-adds
+            float4 qv[4], kv[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) qq[u] = (R)qr[u * D + d];
+            for (int u = 0; u < 4; ++u) qv[u] = *reinterpret_cast<const float4 *>(qr + u * D + d);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                if (t < nt_use) {
-                    const R kk = (R)Ks[jrow[t] + d];
+            for (int t = 0; t < 4; ++t) kv[t] = *reinterpret_cast<const float4 *>(Ks + jrow[t] + d);
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) s[u][t] += qq[u] * kk;
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    R a = s[u][t];
+                    a += (R)qv[u].x * (R)kv[t].x;
+                    a += (R)qv[u].y * (R)kv[t].y;
+                    a += (R)qv[u].z * (R)kv[t].z;
+                    a += (R)qv[u].w * (R)kv[t].w;
+                    s[u][t] = a;
                 }
-            }
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -301,11 +352,6 @@ __global__ __launch_bounds__(256) void att_generic_kernel(PtrTable qtab, PtrTabl
 // Pooled sums are accumulated in fp64 (exact for bf16 / fp32 payloads of ordinary dynamic
 // range), divided once and rounded once to float.
 // ------------------------------------------------------------------------------------------
-template <typename T>
-struct __align__(2 * sizeof(T)) Pair2 {
-    T a, b;
-};
-
 template <typename R>
 struct SelectArgs {
     const R *att;       // [n_frames][n_part][P] partial sums, or NULL (alpha == 0)
@@ -387,12 +433,13 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
             av = (R) reinterpret_cast<const float *>(a.att_in.p[slot])[(int64_t)lf * P + j];
         } else {
             const R *pp = a.att + (int64_t)f * a.n_part * P + j;
-            for (int n0 = 0; n0 < a.n_part; n0 += 8) { // fixed summation order, 8 loads in flight
-                R t[8];
+            constexpr int kPB = 16;
+            for (int n0 = 0; n0 < a.n_part; n0 += kPB) { // fixed summation order, kPB loads in flight
+                R t[kPB];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) t[u] = pp[(int64_t)(n0 + u < a.n_part ? n0 + u : a.n_part - 1) * P];
+                for (int u = 0; u < kPB; ++u) t[u] = pp[(int64_t)(n0 + u < a.n_part ? n0 + u : a.n_part - 1) * P];
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
+                for (int u = 0; u < kPB; ++u)
                     if (n0 + u < a.n_part) av += t[u];
             }
             av *= a.att_scale;
@@ -437,18 +484,21 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
         __syncthreads();
         int pos = __popcll(bal & ((1ull << (j & 63)) - 1ull));
         for (int w = 0; w < (j >> 6); ++w) pos += wcnt[w];
+        // selection margin: gap between the last kept and the first dropped fused score.  A pass-1
+        // frame whose margin is below the threshold goes on the re-scoring list; its rows are
+        // marked -1 so that the main copy leaves them to the fp64 pass.
+        const R mg = (kappa < P) ? vk[0] - vk[1] : (R)INFINITY;
+        const bool flag = !a.pass2 && a.margin_thr > (R)0 && mg < a.margin_thr;
         if (kept) {
             kl[pos] = j;
             a.kept_idx[gf * kappa + pos] = j;
-            a.src_tok[(int64_t)f * kappa + pos] = lf * P + j; // token inside the slot's chunk
+            a.src_tok[(int64_t)f * kappa + pos] = flag ? -1 : lf * P + j; // token inside the slot's chunk
         }
-    }
-    if (j == 0) {
-        const R mg = (kappa < P) ? vk[0] - vk[1] : (R)INFINITY;
-        a.margin[gf] = (float)mg;
-        const bool flag = !a.pass2 && a.margin_thr > (R)0 && mg < a.margin_thr;
-        a.refined[gf] = (a.pass2 || flag) ? 1 : 0;
-        if (flag) a.flag_list[atomicAdd(a.flag_count, 1)] = f; // order is irrelevant: frames are independent
+        if (j == 0) {
+            a.margin[gf] = (float)mg;
+            a.refined[gf] = (a.pass2 || flag) ? 1 : 0;
+            if (flag) a.flag_list[atomicAdd(a.flag_count, 1)] = f; // order is irrelevant: frames are independent
+        }
     }
     __syncthreads();
 
@@ -549,45 +599,46 @@ struct CompactArgs {
     double *ssum_k, *ssum_v;     // running exact sums per segment
     int64_t frame0;
     float *rep_seg_k, *rep_seg_v;
-    int32_t *flag_count;         // re-scoring list length, cleared here for the next batch
 };
+
+// Adds the batch's exact per-frame sums to segment s's running fp64 sums and refreshes its keys.
+__device__ __forceinline__ void segment_update(const CompactArgs &a, int s) {
+    const int64_t f0 = (int64_t)s * a.F;
+    const int64_t f1 = (f0 + a.F < a.n_total) ? f0 + a.F : a.n_total;
+    const int64_t fa = f0 > a.frame0 ? f0 : a.frame0; // first frame of the segment in this batch
+    const bool fresh = f0 >= a.frame0;                // the segment starts in this batch
+    const double den = (double)(f1 - f0) * (double)a.kappa;
+    for (int c = threadIdx.x; c < a.C; c += 256) {
+        double sk = fresh ? 0.0 : a.ssum_k[(int64_t)s * a.C + c];
+        double sv = fresh ? 0.0 : a.ssum_v[(int64_t)s * a.C + c];
+        for (int64_t fb = fa; fb < f1; fb += 8) {
+            double tk[8], tv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t fr = fb + u < f1 ? fb + u : f1 - 1; // clamped: loads stay unconditional
+                tk[u] = a.fsum_k[fr * a.C + c];
+                tv[u] = a.fsum_v[fr * a.C + c];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (fb + u < f1) {
+                    sk += tk[u];
+                    sv += tv[u];
+                }
+            }
+        }
+        a.ssum_k[(int64_t)s * a.C + c] = sk;
+        a.ssum_v[(int64_t)s * a.C + c] = sv;
+        a.rep_seg_k[(int64_t)s * a.C + c] = (float)(sk / den);
+        a.rep_seg_v[(int64_t)s * a.C + c] = (float)(sv / den);
+    }
+}
 
 template <typename V, int ITER>
 __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
     const int y = blockIdx.y;
-    if (y == 0 && blockIdx.x == 0 && threadIdx.x == 0) *a.flag_count = 0;
     if (y >= a.n_slab) {
-        if (blockIdx.x != 0) return;
-        const int s = a.seg_first + (y - a.n_slab);
-        const int64_t f0 = (int64_t)s * a.F;
-        const int64_t f1 = (f0 + a.F < a.n_total) ? f0 + a.F : a.n_total;
-        const int64_t fa = f0 > a.frame0 ? f0 : a.frame0; // first frame of the segment in this chunk
-        const bool fresh = f0 >= a.frame0;                // the segment starts in this chunk
-        const double den = (double)(f1 - f0) * (double)a.kappa;
-        for (int c = threadIdx.x; c < a.C; c += 256) {
-            double sk = fresh ? 0.0 : a.ssum_k[(int64_t)s * a.C + c];
-            double sv = fresh ? 0.0 : a.ssum_v[(int64_t)s * a.C + c];
-            for (int64_t fb = fa; fb < f1; fb += 8) {
-                double tk[8], tv[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int64_t fr = fb + u < f1 ? fb + u : f1 - 1; // clamped: loads stay unconditional
-                    tk[u] = a.fsum_k[fr * a.C + c];
-                    tv[u] = a.fsum_v[fr * a.C + c];
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    if (fb + u < f1) {
-                        sk += tk[u];
-                        sv += tv[u];
-                    }
-                }
-            }
-            a.ssum_k[(int64_t)s * a.C + c] = sk;
-            a.ssum_v[(int64_t)s * a.C + c] = sv;
-            a.rep_seg_k[(int64_t)s * a.C + c] = (float)(sk / den);
-            a.rep_seg_v[(int64_t)s * a.C + c] = (float)(sv / den);
-        }
+        if (blockIdx.x == 0) segment_update(a, a.seg_first + (y - a.n_slab));
         return;
     }
     const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
@@ -617,14 +668,62 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
     for (int it = 0; it < ITER; ++it) {
         int u = u0 + it * 256;
         u = u < n_units ? u : n_units - 1;
-        tmp[it] = *reinterpret_cast<const V *>(src + (int64_t)row_tok[it] * a.st_b + (int64_t)(u & mask) * sizeof(V));
+        const int tok = row_tok[it] < 0 ? 0 : row_tok[it]; // -1: a frame left to the fp64 pass
+        tmp[it] = *reinterpret_cast<const V *>(src + (int64_t)tok * a.st_b + (int64_t)(u & mask) * sizeof(V));
     }
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
         const int u = u0 + it * 256;
-        if (u < n_units) *reinterpret_cast<V *>(dst + (int64_t)u * sizeof(V)) = tmp[it];
+        if (u < n_units && row_tok[it] >= 0) *reinterpret_cast<V *>(dst + (int64_t)u * sizeof(V)) = tmp[it];
     }
 }
+
+// Copy of the kept rows of the re-scored frames (rows chosen by the fp64 pass), list driven like
+// the other re-scoring kernels; the extra workgroups in grid.y update the batch's segments, which
+// need the final per-frame sums of every frame.
+template <typename V>
+__global__ __launch_bounds__(256) void compact_listed_kernel(CompactArgs a, const int32_t *__restrict__ flag_list,
+                                                             const int32_t *__restrict__ flag_count) {
+    const int y = blockIdx.y;
+    if (y >= a.n_slab) {
+        if (blockIdx.x == 0) segment_update(a, a.seg_first + (y - a.n_slab));
+        return;
+    }
+    const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
+    const int kv = rem / a.Hkv, g = rem - kv * a.Hkv;
+    const int mask = (1 << a.log_upr) - 1;
+    const int n_e = *flag_count;
+    for (int e = blockIdx.x; e < n_e; e += gridDim.x) {
+        const int f = flag_list[e];
+        const int slot = find_slot(a.map, f);
+        const unsigned char *src = reinterpret_cast<const unsigned char *>(kv ? a.v.p[slot] : a.k.p[slot]) +
+                                   (int64_t)l * a.sl_b + (int64_t)g * a.sh_b;
+        unsigned char *dst = (kv ? a.store_v : a.store_k) + ((int64_t)l * a.Hkv + g) * a.slab_b + a.dst_off_b +
+                             (int64_t)f * a.units_per_frame * sizeof(V);
+        const int32_t *src_tok = a.src_tok + (int64_t)f * (a.units_per_frame >> a.log_upr);
+        for (int u0 = threadIdx.x; u0 < a.units_per_frame; u0 += 2 * 256) {
+            V tmp[2];
+            int row_tok[2];
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int u = u0 + it * 256 < a.units_per_frame ? u0 + it * 256 : a.units_per_frame - 1;
+                row_tok[it] = src_tok[u >> a.log_upr];
+            }
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int u = u0 + it * 256 < a.units_per_frame ? u0 + it * 256 : a.units_per_frame - 1;
+                tmp[it] = *reinterpret_cast<const V *>(src + (int64_t)row_tok[it] * a.st_b + (int64_t)(u & mask) * sizeof(V));
+            }
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int u = u0 + it * 256;
+                if (u < a.units_per_frame) *reinterpret_cast<V *>(dst + (int64_t)u * sizeof(V)) = tmp[it];
+            }
+        }
+    }
+}
+
+__global__ void clear_count_kernel(int32_t *count) { *count = 0; }
 
 // ------------------------------------------------------------------------------------------
 // host side
@@ -634,7 +733,7 @@ static hipError_t launch_freq(const Ctx &c, const ChunkArgs &a, bool listed, R *
     const int P = c.cfg.tokens_per_frame, D = c.cfg.head_dim, Hkv = c.cfg.n_kv_heads;
     const int64_t k_off = (int64_t)c.ls * a.kv_sl;
     const dim3 grid(listed ? kRescoreSlots : a.n_frames, kFreqBlocksPerFrame);
-    const int32_t *fl = listed ? c.flag_list : nullptr, *fc = listed ? c.flag_count : nullptr;
+    const int32_t *fl = listed ? c.flag_list[a.parity] : nullptr, *fc = listed ? c.flag_count + a.parity : nullptr;
 #define MUKV_FREQ(DD)                                                                                         \
     hipLaunchKernelGGL((freq_signal_kernel<T, R, DD>), grid, dim3(256), 0, st, a.k, a.map, k_off, a.kv_sh, \
                        a.kv_st, Hkv, P, fl, fc, out)
@@ -650,7 +749,7 @@ static hipError_t launch_freq(const Ctx &c, const ChunkArgs &a, bool listed, R *
 }
 
 size_t att_generic_lds_bytes(int P, int D, size_t r_size) {
-    size_t floats = (size_t)P * (D + 1) + kGenQ * D;
+    size_t floats = (size_t)P * (D + 4) + kGenQ * D;
     floats += floats & 1;
     return floats * 4 + (size_t)4 * P * r_size;
 }
@@ -672,8 +771,8 @@ static hipError_t launch_att_generic(const Ctx &c, const ChunkArgs &a, bool list
     }
     hipLaunchKernelGGL((att_generic_kernel<T, R>), dim3(listed ? kRescoreSlots : a.n_frames, c.cfg.n_q_heads, qsplit),
                        dim3(256), lds, st, a.q, a.k, a.map, (int64_t)c.ls * a.kv_sl, a.q_sh, a.q_st, a.kv_sh, a.kv_st, P,
-                       D, c.group, c.cfg.n_q_heads, c.cfg.causal, q_per_block, listed ? c.flag_list : nullptr,
-                       listed ? c.flag_count : nullptr, out);
+                       D, c.group, c.cfg.n_q_heads, c.cfg.causal, q_per_block, listed ? c.flag_list[a.parity] : nullptr,
+                       listed ? c.flag_count + a.parity : nullptr, out);
     return hipGetLastError();
 }
 
@@ -705,10 +804,10 @@ static hipError_t launch_select(const Ctx &c, const ChunkArgs &a, const R *att, 
     s.st = a.kv_st;
     s.margin_thr = (R)c.margin_thr;
     s.pass2 = pass2;
-    s.flag_list = c.flag_list;
-    s.flag_count = c.flag_count;
+    s.flag_list = c.flag_list[a.parity];
+    s.flag_count = c.flag_count + a.parity;
     s.kept_idx = c.kept_idx;
-    s.src_tok = c.src_tok;
+    s.src_tok = pass2 ? c.src_tok2 : c.src_tok;
     s.rep_frame_k = c.rep_frame_k;
     s.rep_frame_v = c.rep_frame_v;
     s.rep_patch_k = c.rep_patch_k;
@@ -732,7 +831,9 @@ static int ilog2(int x) {
     return l;
 }
 
-static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, hipStream_t st) {
+// mode 0: every frame + segment update (no re-scoring); 1: main copy, frames on the re-scoring
+// list skipped, no segment update; 2: listed frames only (rows from the fp64 pass) + segment update
+static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, int mode, hipStream_t st) {
     CompactArgs k;
     const int esz = c.esz, D = c.cfg.head_dim;
     const int row_b = D * esz;
@@ -746,7 +847,7 @@ static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, hipStream_t s
     k.store_v = reinterpret_cast<unsigned char *>(c.store_v);
     k.slab_b = c.store_cap * row_b;
     k.dst_off_b = a.frame0 * c.kappa * (int64_t)row_b;
-    k.src_tok = c.src_tok;
+    k.src_tok = mode == 2 ? c.src_tok2 : c.src_tok;
     const int upr = row_b / 16; // rows are whole 16-byte units (validated at create)
     k.log_upr = ilog2(upr);
     k.units_per_frame = c.kappa * upr;
@@ -765,7 +866,13 @@ static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, hipStream_t s
     k.frame0 = a.frame0;
     k.rep_seg_k = c.rep_seg_k;
     k.rep_seg_v = c.rep_seg_v;
-    k.flag_count = c.flag_count;
+    const int n_seg = seg_last - k.seg_first + 1;
+    if (mode == 2) {
+        k.bps = 0;
+        hipLaunchKernelGGL((compact_listed_kernel<u32x4>), dim3(kRescoreSlots, k.n_slab + n_seg), dim3(256), 0, st, k,
+                           c.flag_list[a.parity], c.flag_count + a.parity);
+        return hipGetLastError();
+    }
     constexpr int ITER = 4;
     int max_slot_frames = 0;
     for (int s = 0; s < a.map.n_slots; ++s) {
@@ -774,7 +881,7 @@ static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, hipStream_t s
     }
     k.bps = (max_slot_frames * k.units_per_frame + 256 * ITER - 1) / (256 * ITER);
     const int gx = k.bps * a.map.n_slots;
-    const int gy = k.n_slab + (seg_last - k.seg_first + 1);
+    const int gy = k.n_slab + (mode == 0 ? n_seg : 0);
     hipLaunchKernelGGL((compact_kernel<u32x4, ITER>), dim3(gx, gy), dim3(256), 0, st, k);
     return hipGetLastError();
 }
@@ -801,18 +908,35 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
         ProfScope ps(c, MUKV_K_SELECT, st);
         if ((e = launch_select<T, float>(c, a, c.att_part, n_part, c.fft_sig, 0, st)) != hipSuccess) return e;
     }
-    if (c.margin_thr > 0.0) {
-        ProfScope ps(c, MUKV_K_REFINE, st);
-        // frames with a near-tie at the keep boundary: redo Eq. 1-4 in fp64 and select again
+    if (c.margin_thr <= 0.0) {
+        ProfScope ps(c, MUKV_K_COMPACT, st);
+        return launch_compact(c, a, 0, st);
+    }
+    // Frames with a near-tie at the keep boundary are on the re-scoring list: Eq. 1-4 are redone
+    // for them in fp64, the keep repeated and their rows copied, all on the context's side stream,
+    // while the main copy of every other frame runs on the caller's stream; the two meet again
+    // before this call returns control of the stream to the caller's next work.
+    if (hipEventRecord(c.ev_fork, st) != hipSuccess) return hipErrorUnknown;
+    if (hipStreamWaitEvent(c.side, c.ev_fork, 0) != hipSuccess) return hipErrorUnknown;
+    {
+        ProfScope ps(c, MUKV_K_REFINE, c.side);
         int n_part64 = c.cfg.n_q_heads;
         if (need_att)
-            if ((e = launch_att_generic<T, double>(c, a, true, c.att64, &n_part64, st)) != hipSuccess) return e;
+            if ((e = launch_att_generic<T, double>(c, a, true, c.att64, &n_part64, c.side)) != hipSuccess) return e;
         if (need_fft)
-            if ((e = launch_freq<T, double>(c, a, true, c.fft64, st)) != hipSuccess) return e;
-        if ((e = launch_select<T, double>(c, a, c.att64, n_part64, c.fft64, 1, st)) != hipSuccess) return e;
+            if ((e = launch_freq<T, double>(c, a, true, c.fft64, c.side)) != hipSuccess) return e;
+        if ((e = launch_select<T, double>(c, a, c.att64, n_part64, c.fft64, 1, c.side)) != hipSuccess) return e;
+        if ((e = launch_compact(c, a, 2, c.side)) != hipSuccess) return e;
     }
-    ProfScope ps(c, MUKV_K_COMPACT, st);
-    return launch_compact(c, a, st);
+    if (hipEventRecord(c.ev_join, c.side) != hipSuccess) return hipErrorUnknown;
+    {
+        ProfScope ps(c, MUKV_K_COMPACT, st);
+        if ((e = launch_compact(c, a, 1, st)) != hipSuccess) return e;
+    }
+    if (hipStreamWaitEvent(st, c.ev_join, 0) != hipSuccess) return hipErrorUnknown;
+    // empty the list for the next batch (a one-thread kernel: memset nodes are avoided in graphs)
+    hipLaunchKernelGGL(clear_count_kernel, dim3(1), dim3(1), 0, st, c.flag_count + a.parity);
+    return hipGetLastError();
 }
 
 hipError_t launch_compress(Ctx &c, const ChunkArgs &a, hipStream_t st) {

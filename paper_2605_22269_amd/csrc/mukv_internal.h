@@ -43,6 +43,7 @@ struct Ctx {
     std::vector<PendingChunk> *pending;
     int64_t p_kv_sl, p_kv_sh, p_kv_st, p_q_sh, p_q_st; // strides shared by the pending chunks
     hipStream_t p_stream;
+    int batch_parity;
     int64_t store_cap; // tokens per (layer, head) slab of the store
     // cache (device)
     void *store_k, *store_v;
@@ -59,7 +60,10 @@ struct Ctx {
     double *att64;    // [max_chunk_frames][Hq][P] partial fp64 attention of re-scored frames
     double *fft64;    // [max_chunk_frames][P]
     int32_t *src_tok; // [max_batch_frames*kappa] chunk-local token of every kept row
-    int32_t *flag_list, *flag_count; // batch frames to re-score in fp64, and how many
+    int32_t *src_tok2;                // the same for the frames re-scored in fp64
+    int32_t *flag_list[2], *flag_count; // batch frames to re-score in fp64 and how many, by batch parity
+    hipStream_t side;                 // re-scoring chain runs here, beside the main copy
+    hipEvent_t ev_fork, ev_join;
     // retrieval scratch (device)
     double *qbar;    // [max_questions][c_kv]  group-summed mean query
     double *qq;      // [max_questions][Hkv]   partial squared norms of the mean query
@@ -99,6 +103,7 @@ struct ChunkArgs {
     int64_t q_sh, q_st;
     int n_frames;                // frames in the batch
     int64_t frame0;              // cache position of batch frame 0
+    int parity;                  // which re-scoring list this batch uses (always 0 at present)
 };
 
 
@@ -195,6 +200,37 @@ __device__ __forceinline__ float xrow_max(float v) {
     auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
     return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
+// value of lane (lane ^ H), H a power of two below 64, without going through LDS:
+// quad permutes for 1 and 2, mirror pairs for 4 (i^7 then i^3) and 8 (i^15 then i^7), row /
+// half-wave swaps for 16 and 32.
+constexpr int kDppQuadReverse = 0x1B; // quad_perm [3,2,1,0]
+template <int H>
+__device__ __forceinline__ float lane_xor(float v) {
+    static_assert(H == 1 || H == 2 || H == 4 || H == 8 || H == 16 || H == 32, "lane distance");
+    if constexpr (H == 1) {
+        return dpp_lane<kDppQuadSwap1>(v);
+    } else if constexpr (H == 2) {
+        return dpp_lane<kDppQuadSwap2>(v);
+    } else if constexpr (H == 4) {
+        return dpp_lane<kDppQuadReverse>(dpp_lane<kDppRowHalfMirror>(v));
+    } else if constexpr (H == 8) {
+        return dpp_lane<kDppRowHalfMirror>(dpp_lane<kDppRowMirror>(v));
+    } else if constexpr (H == 16) {
+        auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+        const bool odd_row = (__lane_id() >> 4) & 1;
+        return __uint_as_float(odd_row ? a[0] : a[1]);
+    } else {
+        auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+        return __uint_as_float(__lane_id() < 32 ? b[1] : b[0]);
+    }
+}
+template <int H>
+__device__ __forceinline__ double lane_xor(double v) {
+    const float lo = lane_xor<H>(__int_as_float(__double2loint(v)));
+    const float hi = lane_xor<H>(__int_as_float(__double2hiint(v)));
+    return __hiloint2double(__float_as_int(hi), __float_as_int(lo));
+}
+
 __device__ __forceinline__ float wave_max(float x) { return xrow_max(row16_max(x)); }
 __device__ __forceinline__ float wave_sum(float x) { return xrow_sum(row16_sum(x)); }
 __device__ __forceinline__ double wave_sum(double x) {
