@@ -97,7 +97,7 @@ def main():
     ctx = mk.MuKV(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, tokens_per_frame=P,
                   frames_per_segment=w.frames_per_segment, superpatches_per_frame=w.superpatches_per_frame,
                   dtype=w.torch_dtype, keep_ratio=w.keep_ratio, alpha=w.alpha, max_frames=n_frames,
-                  max_chunk_frames=chunk, max_questions=B, batch_chunks=a.batch_chunks)
+                  max_chunk_frames=chunk, max_questions=max(B, 64), batch_chunks=a.batch_chunks)
     kappa = ctx.kappa
 
     # questions: random for the single-question workloads, planted targets for the batched one
@@ -240,6 +240,34 @@ def main():
                             "bytes_per_launch": gather_bytes, "us_per_launch": gather_us},
         "setup_s": {"generate_stream": t_gen},
     }
+
+    # ---- the same cache under 64 concurrent questions of 16..64 tokens (one batched call each) --
+    if B == 1:
+        Bq = 64
+        lens_q = synth.question_lengths(Bq, 16, 64, a.seed + 3)
+        qt64 = torch.cat([synth.random_question(w, n, a.seed + 100 + i, device=dev) for i, n in enumerate(lens_q)]).contiguous()
+        offs64 = torch.zeros(Bq + 1, dtype=torch.int32)
+        offs64[1:] = torch.cumsum(torch.tensor(lens_q), 0)
+        offs64 = offs64.to(dev)
+        r64 = {"seg_idx": torch.empty(Bq, w.k_seg, dtype=torch.int32, device=dev),
+               "seg_score": torch.empty(Bq, w.k_seg, dtype=torch.float32, device=dev),
+               "frame_idx": torch.empty(Bq, w.k_frame, dtype=torch.int32, device=dev),
+               "frame_score": torch.empty(Bq, w.k_frame, dtype=torch.float32, device=dev)}
+        shape64 = (Bq, L, Hkv, w.k_frame * kappa, D)
+        g64 = (torch.empty(shape64, dtype=w.torch_dtype, device=dev), torch.empty(shape64, dtype=w.torch_dtype, device=dev),
+               torch.empty(Bq, dtype=torch.int32, device=dev))
+
+        def retrieve_64():
+            ctx.retrieve(qt64, offs64, mode=mk.MUKV_SEMI, k_seg=w.k_seg, k_frame=w.k_frame,
+                         lambda_frame=w.lambda_frame, out=r64)
+            ctx.gather_kv(r64["frame_idx"], out=g64)
+
+        retrieve_64()
+        ms64 = timed(retrieve_64, 10)
+        res["retrieve_gather_64_questions"] = {
+            "ms_per_batch": ms64, "ms_per_question": ms64 / Bq,
+            "gather_bytes": Bq * gather_bytes, "path_GBs": Bq * gather_bytes / (ms64 * 1e-3) / 1e9}
+        del g64
 
     if a.calibrate_copy_mib:
         nb = a.calibrate_copy_mib << 20

@@ -231,8 +231,26 @@ __device__ __forceinline__ double lane_xor(double v) {
     return __hiloint2double(__float_as_int(hi), __float_as_int(lo));
 }
 
+__device__ __forceinline__ double row16_sum(double v) {
+    v += lane_xor<1>(v);
+    v += lane_xor<2>(v);
+    v += lane_xor<4>(v);
+    v += lane_xor<8>(v);
+    return v;
+}
+
 __device__ __forceinline__ float wave_max(float x) { return xrow_max(row16_max(x)); }
 __device__ __forceinline__ float wave_sum(float x) { return xrow_sum(row16_sum(x)); }
+__device__ __forceinline__ int wave_sum(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, kDppQuadSwap1, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, kDppQuadSwap2, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, kDppRowHalfMirror, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, kDppRowMirror, 0xF, 0xF, true);
+    auto a = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
+    v = (int)(a[0] + a[1]);
+    auto b = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+    return (int)(b[0] + b[1]);
+}
 __device__ __forceinline__ double wave_sum(double x) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);

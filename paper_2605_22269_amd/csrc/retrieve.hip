@@ -13,6 +13,8 @@
 
 namespace mukv {
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int cp_u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kSelThreads = 512;
 
 // ------------------------------------------------------------------------------------------
@@ -166,28 +168,83 @@ struct SelShared {
     unsigned hist[256];
     uint64_t sel_key[kMaxCand];
     int sel_idx[kMaxCand];
+    uint64_t loc_key[kSelThreads];
     int wtot[kSelThreads / 64];
     int count;
     int need;
     unsigned digit;
+    int n_cand;
+    uint64_t thr;
 };
+
+constexpr int kDirectN = 512; // up to this many entries are ranked against each other directly
+
+// Rank by counting: for every entry t < n of keys[] (ties broken by ids[], or by the entry
+// number when ids is null) the number of entries ahead of it.  The n*n comparisons are spread
+// over the workgroup: `per` adjacent lanes share one entry, each counting over a stride of the
+// entries, and add their counts with lane exchanges.  fn(t, rank) runs in one lane per entry.
+// All threads of the workgroup must call it; keys / ids are LDS arrays complete before the call.
+template <typename Fn>
+__device__ __forceinline__ void block_rank(const uint64_t *keys, const int *ids, int n, Fn fn) {
+    int p2 = 1;
+    while (p2 < n) p2 <<= 1;
+    int per = kSelThreads / p2;
+    per = per < 1 ? 1 : (per > 64 ? 64 : per);
+    const int tid = threadIdx.x, part = tid & (per - 1);
+    for (int t0 = 0; t0 < n; t0 += kSelThreads / per) {
+        const int t = t0 + tid / per;
+        const bool live = t < n;
+        const uint64_t kt = keys[live ? t : 0];
+        const int it = ids ? ids[live ? t : 0] : t;
+        int cnt = 0;
+        for (int u0 = part; u0 < n; u0 += 8 * per) { // 8 independent LDS reads, then branch-free compares
+            uint64_t ku[8];
+            int iu[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int u = u0 + j * per;
+                const int uc = u < n ? u : n - 1;
+                ku[j] = keys[uc];
+                iu[j] = ids ? ids[uc] : uc;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int ahead = (int)(ku[j] < kt) | ((int)(ku[j] == kt) & (int)(iu[j] < it));
+                cnt += (u0 + j * per < n) ? ahead : 0;
+            }
+        }
+        for (int o = 1; o < per; o <<= 1) cnt += __shfl_xor(cnt, o);
+        if (live && part == 0) fn(t, cnt);
+    }
+}
 
 // Chooses the m best of entries 0..n-1 (smallest key; equal keys: lowest entry number) and
 // writes their entry numbers to out[0..m_eff) in rank order.  Returns m_eff = min(m, number of
 // entries whose key is not kNoKey).  All threads of the workgroup must call it.
 // The keys of the first `cap` entries are computed once (batches of independent loads) and kept
 // in the LDS array `cache`; entries past `cap` are recomputed from `key` on every pass.
-// Method: 8-bit radix select of the m-th key (8 passes of LDS histograms, the digit found by a
-// wave-parallel prefix sum), one pass collecting everything better than it, an ordered scan
-// handing the remaining places to the first entries equal to it, then a rank-by-counting sort
-// of the <= kMaxCand survivors.
+// Three routes, all giving the same (key, entry)-ordered result:
+//  * n <= kDirectN: every entry counts the entries ahead of it (rank by counting);
+//  * otherwise a pre-filter: the entries are dealt to at least 2*m_eff groups of threads, each
+//    group keeps its best key, the m_eff-th best of the group keys bounds the m_eff-th best
+//    key overall from above, and the (usually few) entries at or below that bound are ranked
+//    by counting;
+//  * when the pre-filter leaves more than kMaxCand entries (many equal keys, or m_eff larger
+//    than the thread count): 8-bit radix select of the m_eff-th key (LDS histograms, the digit
+//    found by a wave-parallel prefix sum), one pass collecting everything better than it, an
+//    ordered scan handing the remaining places to the first entries equal to it, then a
+//    rank-by-counting sort of the survivors.
 template <typename KeyFn>
 __device__ int block_topk(KeyFn key, int n, int m, int *out, SelShared &sh, uint64_t *cache, int cap) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     __syncthreads();
-    if (tid == 0) sh.count = 0;
+    if (tid == 0) {
+        sh.count = 0;
+        sh.n_cand = 0;
+    }
     __syncthreads();
     int mine = 0;
+    uint64_t best = kNoKey;
     const int n_c = n < cap ? n : cap;
     for (int i0 = tid; i0 < n_c; i0 += 8 * kSelThreads) {
         uint64_t kk[8];
@@ -202,16 +259,66 @@ __device__ int block_topk(KeyFn key, int n, int m, int *out, SelShared &sh, uint
             if (i < n_c) {
                 cache[i] = kk[u];
                 mine += kk[u] != kNoKey;
+                best = kk[u] < best ? kk[u] : best;
             }
         }
     }
-    for (int i = n_c + tid; i < n; i += kSelThreads) mine += key(i) != kNoKey;
+    for (int i = n_c + tid; i < n; i += kSelThreads) {
+        const uint64_t k = key(i);
+        mine += k != kNoKey;
+        best = k < best ? k : best;
+    }
     auto get = [&](int i) { return i < n_c ? cache[i] : key(i); };
-    if (mine) atomicAdd(&sh.count, mine);
+    mine = wave_sum(mine);
+    if (lane == 0 && mine) atomicAdd(&sh.count, mine);
     __syncthreads();
     const int m_eff = min(m, sh.count);
-    __syncthreads();
     if (m_eff == 0) return 0;
+
+    if (n <= kDirectN && n <= n_c) {
+        // entries without a key rank behind every entry that has one, so they never reach out[]
+        block_rank(cache, nullptr, n, [&](int t, int rank) {
+            if (rank < m_eff) out[rank] = t;
+        });
+        __syncthreads();
+        return m_eff;
+    }
+    if (m_eff <= kSelThreads) {
+        int n_grp = 8;
+        while (n_grp < 2 * m_eff && n_grp < kSelThreads) n_grp <<= 1;
+        const int grp = kSelThreads / n_grp; // adjacent lanes per group, a power of two <= 64
+        for (int o = 1; o < grp; o <<= 1) {
+            const uint64_t other = (uint64_t)__shfl_xor((unsigned long long)best, o);
+            best = other < best ? other : best;
+        }
+        if ((tid & (grp - 1)) == 0) sh.loc_key[tid / grp] = best;
+        __syncthreads();
+        block_rank(sh.loc_key, nullptr, n_grp, [&](int t, int rank) {
+            if (rank == m_eff - 1) sh.thr = sh.loc_key[t];
+        });
+        __syncthreads();
+        const uint64_t bound = sh.thr;
+        for (int i = tid; i < n; i += kSelThreads) {
+            const uint64_t k = get(i);
+            if (k <= bound && k != kNoKey) {
+                const int pos = atomicAdd(&sh.n_cand, 1);
+                if (pos < kMaxCand) {
+                    sh.sel_key[pos] = k;
+                    sh.sel_idx[pos] = i;
+                }
+            }
+        }
+        __syncthreads();
+        const int n_cand = sh.n_cand;
+        if (n_cand <= kMaxCand) {
+            block_rank(sh.sel_key, sh.sel_idx, n_cand, [&](int t, int rank) {
+                if (rank < m_eff) out[rank] = sh.sel_idx[t];
+            });
+            __syncthreads();
+            return m_eff;
+        }
+    }
+    __syncthreads();
 
     uint64_t prefix = 0;
     if (tid == 0) sh.need = m_eff;
@@ -409,10 +516,17 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
     n_glob = min(n_glob, m_s);
     for (int c = tid; c < a.C; c += kSelThreads) {
         double s = 0.0;
-        for (int r = 0; r < n_glob; ++r) {
-            const int sgi = cand_seg[r];
-            const float *rep = (a.tail_cut && sgi == a.ns - 1) ? a.seg_tail : a.rep_seg + (int64_t)sgi * a.C;
-            s += (double)rep[c];
+        for (int r0 = 0; r0 < n_glob; r0 += 8) { // batches of 8 independent loads, summed in list order
+            float x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int sgi = cand_seg[r0 + u < n_glob ? r0 + u : n_glob - 1];
+                const float *rep = (a.tail_cut && sgi == a.ns - 1) ? a.seg_tail : a.rep_seg + (int64_t)sgi * a.C;
+                x[u] = rep[c];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (r0 + u < n_glob) s += (double)x[u];
         }
         gvec[c] = n_glob > 0 ? s / (double)n_glob : 0.0;
     }
@@ -425,20 +539,54 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
     }
     __syncthreads();
     const double gg = gg_sh;
-    for (int t = wave; t < m_f; t += kSelThreads / 64) {
-        const int fr = cand_frm[t];
-        const float *rep = a.rep_frame + (int64_t)fr * a.C;
-        double dot = 0.0, rr = 0.0;
-        for (int c = lane; c < a.C; c += 64) {
-            const double x = (double)rep[c];
-            dot += x * gvec[c];
-            rr += x * x;
+    // Eq. 8: a 16-lane row per candidate, 4 candidates per wave and round, two rounds' key loads
+    // (16-byte pieces, lane r of the row takes pieces r, r+16, ...) in flight before any use
+    constexpr int kWaves = kSelThreads / 64;
+    const int row = lane >> 4, rl = lane & 15;
+    const int n_piece = a.C >> 2; // C is a multiple of 16
+    for (int t0 = 0; t0 < m_f; t0 += 8 * kWaves) {
+        double dot[2] = {0.0, 0.0}, rr[2] = {0.0, 0.0};
+        int tc[2];
+        const f32x4 *rep[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            tc[u] = t0 + (2 * wave + u) * 4 + row;
+            rep[u] = reinterpret_cast<const f32x4 *>(a.rep_frame + (int64_t)cand_frm[tc[u] < m_f ? tc[u] : m_f - 1] * a.C);
         }
-        dot = wave_sum(dot);
-        rr = wave_sum(rr);
-        if (lane == 0) {
-            const double gamma = (rr > 0.0 && gg > 0.0) ? dot / (sqrt(rr) * sqrt(gg)) : 0.0;
-            st[t] = (1.0 - a.lambda) * s_frm[fr] + a.lambda * gamma; // Eq. 8
+        for (int p0 = 0; p0 < n_piece; p0 += 64) {
+            f32x4 x[2][4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int pc = p0 + rl + 16 * j;
+                const int pcc = pc < n_piece ? pc : n_piece - 1;
+#pragma unroll
+                for (int u = 0; u < 2; ++u) x[u][j] = rep[u][pcc];
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int pc = p0 + rl + 16 * j;
+                if (pc < n_piece) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const double g = gvec[4 * pc + e];
+#pragma unroll
+                        for (int u = 0; u < 2; ++u) {
+                            const double xv = (double)x[u][j][e];
+                            dot[u] += xv * g;
+                            rr[u] += xv * xv;
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            dot[u] = row16_sum(dot[u]);
+            rr[u] = row16_sum(rr[u]);
+            if (rl == 0 && tc[u] < m_f) {
+                const double gamma = (rr[u] > 0.0 && gg > 0.0) ? dot[u] / (sqrt(rr[u]) * sqrt(gg)) : 0.0;
+                st[tc[u]] = (1.0 - a.lambda) * s_frm[cand_frm[tc[u]]] + a.lambda * gamma;
+            }
         }
     }
     __syncthreads();
@@ -476,18 +624,28 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(GatherArgs a) {
     __shared__ int n_valid_sh;
     const int tid = threadIdx.x, b = blockIdx.z, y = blockIdx.y;
     const int32_t *idx = a.frame_idx + (int64_t)b * a.k_frame;
+    __shared__ int raw[kMaxGatherK];
     if (tid == 0) n_valid_sh = 0;
-    for (int t = tid; t < a.k_frame; t += 256) slot_frame[t] = -1;
+    for (int t = tid; t < a.k_frame; t += 256) {
+        slot_frame[t] = -1;
+        const int me = idx[t];
+        raw[t] = (me < 0 || me >= a.n_frames) ? -1 : me;
+    }
     __syncthreads();
     int cnt = 0;
     for (int t = tid; t < a.k_frame; t += 256) {
-        const int me = idx[t];
-        if (me < 0 || me >= a.n_frames) continue;
+        const int me = raw[t];
+        if (me < 0) continue;
         int pos = 0;
-        for (int u = 0; u < a.k_frame; ++u) {
-            const int o = idx[u];
-            if (o < 0 || o >= a.n_frames) continue;
-            pos += (a.order == MUKV_TEMPORAL) ? (o < me || (o == me && u < t)) : (u < t);
+        if (a.order == MUKV_TEMPORAL) {
+#pragma unroll 4
+            for (int u = 0; u < a.k_frame; ++u) {
+                const int o = raw[u];
+                pos += (o >= 0) && (o < me || (o == me && u < t));
+            }
+        } else {
+#pragma unroll 4
+            for (int u = 0; u < t; ++u) pos += raw[u] >= 0;
         }
         slot_frame[pos] = me;
         ++cnt;
@@ -503,7 +661,7 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(GatherArgs a) {
     unsigned char *dst = (kv ? a.v_out : a.k_out) + (((int64_t)b * a.L + l) * a.Hkv + g) * (a.k_frame * a.frame_b);
     const int n_units = a.k_frame * a.units_per_frame;
     // unconditional loads on clamped unit numbers / slot 0's frame, zero selected afterwards
-    uint4 tmp[ITER];
+    cp_u32x4 tmp[ITER];
     const int u0 = blockIdx.x * (256 * ITER) + tid;
     const int fr_any = n_valid > 0 ? slot_frame[0] : 0;
 #pragma unroll
@@ -512,18 +670,17 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(GatherArgs a) {
         u = u < n_units ? u : n_units - 1;
         const int slot = u / a.units_per_frame, part = u - slot * a.units_per_frame;
         const int fr = slot_frame[slot];
-        const uint4 x = *reinterpret_cast<const uint4 *>(src + (int64_t)(fr >= 0 ? fr : fr_any) * a.frame_b + (int64_t)part * 16);
-        tmp[it] = fr >= 0 ? x : make_uint4(0u, 0u, 0u, 0u);
+        const cp_u32x4 x = *reinterpret_cast<const cp_u32x4 *>(src + (int64_t)(fr >= 0 ? fr : fr_any) * a.frame_b + (int64_t)part * 16);
+        tmp[it] = fr >= 0 ? x : cp_u32x4{0u, 0u, 0u, 0u};
     }
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
         const int u = u0 + it * 256;
-        if (u < n_units) *reinterpret_cast<uint4 *>(dst + (int64_t)u * 16) = tmp[it];
+        if (u < n_units) *reinterpret_cast<cp_u32x4 *>(dst + (int64_t)u * 16) = tmp[it];
     }
 }
 
 // Plain streaming copy, 4 x 16 bytes per thread: the calibration kernel for traffic counters.
-typedef unsigned int cp_u32x4 __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void plain_copy_kernel(const cp_u32x4 *__restrict__ src, cp_u32x4 *__restrict__ dst,
                                                          int64_t n_units) {
     const int64_t u0 = (int64_t)blockIdx.x * 1024 + threadIdx.x;
@@ -653,8 +810,8 @@ hipError_t launch_gather(Ctx &c, const int32_t *frame_idx, int B, int k_frame, i
     g.Hkv = c.cfg.n_kv_heads;
     g.kappa = c.kappa;
     g.n_frames = c.n_frames;
-    constexpr int ITER = 4;
     const int n_units = k_frame * g.units_per_frame;
+    constexpr int ITER = 8; // 16-byte pieces per thread: fewer, longer workgroups amortise the slot plan
     const int gx = (n_units + 256 * ITER - 1) / (256 * ITER);
     ProfScope ps(c, MUKV_K_GATHER, st);
     hipLaunchKernelGGL((gather_kv_kernel<ITER>), dim3(gx, c.cfg.n_layers * 2 * c.cfg.n_kv_heads, B), dim3(256), 0, st, g);

@@ -62,6 +62,32 @@ def test_7b_shape_retrieval_modes():
     p.close()
 
 
+@pytest.mark.parametrize("distinct", [1, 3, 40])
+def test_retrieval_with_many_equal_scores(distinct):
+    # 1300 frames cycling through `distinct` different ones: whole classes of frame and segment
+    # scores tie exactly, and the selections must still be the oracle's (lowest index first).
+    # One class of 1300 overflows the candidate list of the selection kernel's short route,
+    # classes of 433 stay inside it, 40 classes put ties across the cut; k_frame = 300 asks for
+    # more candidates than the kernel has threads.
+    w = W["tiny"].scaled(n_frames=1300, n_questions=2)
+    p = Pair(w, seed=90 + distinct, chunk=100)
+    P = w.tokens_per_frame
+    k0, v0, q0 = p.stream.next_chunk(distinct)
+    for c0 in range(0, 1300, 100):
+        fr = (torch.arange(c0, c0 + 100) % distinct)
+        tok = (fr[:, None] * P + torch.arange(P)[None, :]).reshape(-1)
+        k, v, q = k0[:, :, tok].contiguous(), v0[:, :, tok].contiguous(), q0[:, tok].contiguous()
+        p.orc.compress_chunk(np_view(k), np_view(v), q_last=np_view(q))
+        p.gpu.compress_chunk(k.cuda(), v.cuda(), q.cuda())
+        torch.cuda.synchronize()
+    qs = questions_for(w, [16, 9], 600)
+    for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
+        p.check_retrieve(qs, mode, 4, 8, 0.3)
+    p.check_retrieve(qs, mk.MUKV_SEMI, 40, 300, 0.3)
+    p.check_retrieve(qs, mk.MUKV_PARALLEL, 3, 512, 0.3)
+    p.close()
+
+
 # ------------------------------------------------------ 72B shape, short stream -----------
 def test_72b_shape_short_stream():
     w = W["72b"].scaled(n_frames=40, n_layers=3)   # kappa 8 of 64; one full 32-frame segment + 8
