@@ -42,6 +42,9 @@ def parse():
                     help="chunks the library gathers before it launches their kernels together (1: launch per chunk)")
     ap.add_argument("--frames", type=int, default=0, help="override the stream length (debugging)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--overlap-copy", type=int, default=1, choices=(0, 1),
+                    help="1: the copy of a batch's kept rows overlaps the next batch's scoring kernels "
+                         "(mukv_config.overlap_copy; the whole stream is resident, so inputs outlive the copies)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-frames", type=int, default=1024)
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
@@ -97,7 +100,7 @@ def main():
     ctx = mk.MuKV(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, tokens_per_frame=P,
                   frames_per_segment=w.frames_per_segment, superpatches_per_frame=w.superpatches_per_frame,
                   dtype=w.torch_dtype, keep_ratio=w.keep_ratio, alpha=w.alpha, max_frames=n_frames,
-                  max_chunk_frames=chunk, max_questions=max(B, 64), batch_chunks=a.batch_chunks)
+                  max_chunk_frames=chunk, max_questions=max(B, 64), batch_chunks=a.batch_chunks, overlap_copy=a.overlap_copy)
     kappa = ctx.kappa
 
     # questions: random for the single-question workloads, planted targets for the batched one
@@ -222,7 +225,7 @@ def main():
                                f"chunks of {chunk} frames, F={w.frames_per_segment}, keep {kappa}/{P}, "
                                f"{B} question(s), top-{w.k_seg} segments / top-{w.k_frame} frames",
                    "launch": launch, "chunk_frames": chunk, "n_chunks": n_chunks,
-                   "batch_chunks": a.batch_chunks},
+                   "batch_chunks": a.batch_chunks, "overlap_copy": a.overlap_copy},
         "compress_ms_per_stream": compress_ms,
         "compress_tokens_per_s": tokens / (compress_ms * 1e-3),
         "retrieve_gather_ms_per_batch": retrieve_ms,

@@ -93,6 +93,12 @@ typedef struct mukv_config {
                                        last kept and first dropped fused score) is
                                        below this are re-scored in fp64 before the
                                        keep; < 0 = library default, 0 = never          */
+    int32_t overlap_copy;           /* 0: a call that enqueues kernels leaves the caller's
+                                       stream ordered after all of them.  1: the copy of the
+                                       kept rows (and the fp64 re-scoring) of one batch runs on
+                                       the library's own streams while the caller's stream goes
+                                       on to the scoring kernels of the next batch; see
+                                       mukv_compress_chunk for what that asks of the caller    */
 } mukv_config;
 
 /* Element strides (not bytes) of a [layer][head][token][dim] tensor; dim is
@@ -158,8 +164,10 @@ int mukv_destroy(mukv_ctx *ctx);
 /* Forgets the stream (n_frames = 0, gathered chunks dropped) without freeing memory. */
 int mukv_reset(mukv_ctx *ctx);
 
-/* Enqueues the kernels of the chunks gathered so far (batch_chunks > 1); a no-op
- * otherwise.  Does not synchronise. */
+/* Enqueues the kernels of the chunks gathered so far (batch_chunks > 1) and, with
+ * overlap_copy, orders the stream of the last compress call after the work still
+ * running on the library's own streams.  A no-op when there is neither.  Does not
+ * synchronise the host. */
 int mukv_flush(mukv_ctx *ctx);
 
 /*
@@ -188,6 +196,13 @@ int mukv_flush(mukv_ctx *ctx);
  * differ from the gathered ones flushes them first.  Capacity errors are
  * reported by the call that submits the chunk, launch errors by the call that
  * flushes.
+ *
+ * With overlap_copy = 1 the rows of a batch are still being copied out of the
+ * input buffers while the stream already runs what the caller enqueues next.
+ * The inputs (and `sig` outputs) of a batch must then stay alive and unchanged
+ * until the stream has passed the NEXT call that enqueues compress kernels, or
+ * a mukv_flush, mukv_retrieve or mukv_gather_kv call: each of these orders its
+ * stream after the outstanding copies.  Results are the same bit for bit.
  *
  * Errors: INVALID_ARG (null k/v, missing or doubled attention source),
  * SHAPE (n_frames < 1), CAPACITY (n_frames > max_chunk_frames or the cache is

@@ -40,6 +40,7 @@ int validate_config(const mukv_config *cfg) {
     if (cfg->score_layer < -1 || cfg->score_layer >= cfg->n_layers) return MUKV_ERR_SHAPE;
     if (cfg->att_path < MUKV_ATT_AUTO || cfg->att_path > MUKV_ATT_MFMA) return MUKV_ERR_INVALID_ARG;
     if (cfg->batch_chunks < 0) return MUKV_ERR_INVALID_ARG;
+    if (cfg->overlap_copy != 0 && cfg->overlap_copy != 1) return MUKV_ERR_INVALID_ARG;
     if (cfg->batch_chunks > mukv::kMaxSlots) return MUKV_ERR_UNSUPPORTED;
     const int kappa = (int)std::floor(cfg->keep_ratio * cfg->tokens_per_frame + 1e-9);
     if (kappa < 1) return MUKV_ERR_INVALID_ARG;
@@ -62,11 +63,16 @@ void free_all(Ctx &c) {
                     c.rep_patch_v, c.rep_seg_k, c.rep_seg_v, c.cnt_patch,   c.fsum_k,      c.fsum_v,
                     c.ssum_k,      c.ssum_v,    c.margin,      c.refined,   c.att_part,  c.fft_sig,     c.att64,       c.fft64,
                     c.src_tok,     c.src_tok2,    c.flag_list[0], c.flag_list[1], c.flag_count, c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail};
+    // nothing of the library's own may still be running on what is freed below
+    if (c.side) (void)hipStreamSynchronize(c.side);
+    if (c.copy) (void)hipStreamSynchronize(c.copy);
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (c.side) (void)hipStreamDestroy(c.side);
     if (c.ev_fork) (void)hipEventDestroy(c.ev_fork);
     if (c.ev_join) (void)hipEventDestroy(c.ev_join);
+    if (c.copy) (void)hipStreamDestroy(c.copy);
+    if (c.ev_copy) (void)hipEventDestroy(c.ev_copy);
 }
 
 } // namespace
@@ -154,6 +160,8 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(hipStreamCreateWithFlags(&c.side, hipStreamNonBlocking));
     ok(hipEventCreateWithFlags(&c.ev_fork, hipEventDisableTiming));
     ok(hipEventCreateWithFlags(&c.ev_join, hipEventDisableTiming));
+    ok(hipStreamCreateWithFlags(&c.copy, hipStreamNonBlocking));
+    ok(hipEventCreateWithFlags(&c.ev_copy, hipEventDisableTiming));
     ok(dalloc(&c.qbar, MQ * C));
     ok(dalloc(&c.qq, MQ * cfg->n_kv_heads));
     ok(dalloc(&c.s_frm, MQ * MF));
@@ -221,8 +229,13 @@ int mukv_reset(mukv_ctx *ctx) {
 }
 
 // Enqueues the kernels for every chunk gathered so far (on the stream they were submitted with).
-static int flush_pending(Ctx &c) {
-    if (c.pending->empty()) return MUKV_OK;
+// join: also order `join_stream` after the work outstanding on the library's own streams.
+static int flush_pending(Ctx &c, bool join, hipStream_t join_stream) {
+    if (c.pending->empty()) {
+        if (!join) return MUKV_OK;
+        if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
+        return mukv::join_streams(c, join_stream) == hipSuccess ? MUKV_OK : MUKV_ERR_HIP;
+    }
     mukv::ChunkArgs a;
     std::memset(&a, 0, sizeof(a));
     int nf = 0, s = 0;
@@ -254,12 +267,14 @@ static int flush_pending(Ctx &c) {
     c.pending->clear();
     c.n_done += nf;
     if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
-    return mukv::launch_compress(c, a, c.p_stream) == hipSuccess ? MUKV_OK : MUKV_ERR_HIP;
+    if (mukv::launch_compress(c, a, c.p_stream) != hipSuccess) return MUKV_ERR_HIP;
+    if (join && mukv::join_streams(c, join_stream) != hipSuccess) return MUKV_ERR_HIP;
+    return MUKV_OK;
 }
 
 int mukv_flush(mukv_ctx *ctx) {
     if (!ctx) return MUKV_ERR_INVALID_ARG;
-    return flush_pending(ctx->c);
+    return flush_pending(ctx->c, true, ctx->c.p_stream);
 }
 
 int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_strides *kv_strides,
@@ -298,7 +313,7 @@ int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_
                           c.p_kv_st == kv_strides->token && c.p_q_sh == q_sh && c.p_q_st == q_st &&
                           (p0.q != nullptr) == use_q && (p0.att_in != nullptr) == use_att_in;
         if (!same) {
-            const int rc = flush_pending(c);
+            const int rc = flush_pending(c, true, c.p_stream);
             if (rc != MUKV_OK) return rc;
         }
     }
@@ -318,7 +333,7 @@ int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_
     c.p_q_st = q_st;
     c.pending->push_back(pc);
     c.n_frames += n_frames;
-    if ((int)c.pending->size() >= c.batch_chunks) return flush_pending(c);
+    if ((int)c.pending->size() >= c.batch_chunks) return flush_pending(c, false, nullptr);
     return MUKV_OK;
 }
 
@@ -334,7 +349,7 @@ int mukv_retrieve(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets,
     if (!(params->lambda_frame >= 0.0) || params->lambda_frame > 1.0) return MUKV_ERR_INVALID_ARG;
     if (2 * params->k_seg > mukv::kMaxCand || 2 * params->k_frame > mukv::kMaxCand) return MUKV_ERR_UNSUPPORTED;
     {
-        const int rc = flush_pending(c);
+        const int rc = flush_pending(c, true, reinterpret_cast<hipStream_t>(stream));
         if (rc != MUKV_OK) return rc;
     }
     mukv::RetrieveArgs a;
@@ -365,7 +380,7 @@ int mukv_gather_kv(mukv_ctx *ctx, const int32_t *frame_idx, int32_t B, int32_t k
     if ((reinterpret_cast<uintptr_t>(k_out) & 15) || (reinterpret_cast<uintptr_t>(v_out) & 15))
         return MUKV_ERR_UNSUPPORTED;
     {
-        const int rc = flush_pending(c);
+        const int rc = flush_pending(c, true, reinterpret_cast<hipStream_t>(stream));
         if (rc != MUKV_OK) return rc;
     }
     if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;

@@ -601,32 +601,46 @@ struct CompactArgs {
     float *rep_seg_k, *rep_seg_v;
 };
 
-// Adds the batch's exact per-frame sums to segment s's running fp64 sums and refreshes its keys.
-__device__ __forceinline__ void segment_update(const CompactArgs &a, int s) {
+// Adds the batch's exact per-frame sums to a segment's running fp64 sums and refreshes its keys.
+// Job j = (segment, group of 64 channels): 64 channel lanes x 4 frame slices per workgroup, each
+// slice one batch of independent loads, the four partial sums joined through LDS (the sums are
+// exact, so their order does not matter).
+constexpr int kSegChan = 64;
+__device__ __forceinline__ void segment_update(const CompactArgs &a, int job) {
+    __shared__ double part_k[4][kSegChan], part_v[4][kSegChan];
+    const int n_cg = (a.C + kSegChan - 1) / kSegChan;
+    const int s = a.seg_first + job / n_cg;
+    const int c = (job % n_cg) * kSegChan + (threadIdx.x & (kSegChan - 1));
+    const int slice = threadIdx.x / kSegChan;
     const int64_t f0 = (int64_t)s * a.F;
     const int64_t f1 = (f0 + a.F < a.n_total) ? f0 + a.F : a.n_total;
     const int64_t fa = f0 > a.frame0 ? f0 : a.frame0; // first frame of the segment in this batch
     const bool fresh = f0 >= a.frame0;                // the segment starts in this batch
     const double den = (double)(f1 - f0) * (double)a.kappa;
-    for (int c = threadIdx.x; c < a.C; c += 256) {
-        double sk = fresh ? 0.0 : a.ssum_k[(int64_t)s * a.C + c];
-        double sv = fresh ? 0.0 : a.ssum_v[(int64_t)s * a.C + c];
-        for (int64_t fb = fa; fb < f1; fb += 8) {
-            double tk[8], tv[8];
+    const int cc = c < a.C ? c : a.C - 1;
+    double sk = 0.0, sv = 0.0;
+    for (int64_t fb = fa + slice; fb < f1; fb += 32) {
+        double tk[8], tv[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int64_t fr = fb + u < f1 ? fb + u : f1 - 1; // clamped: loads stay unconditional
-                tk[u] = a.fsum_k[fr * a.C + c];
-                tv[u] = a.fsum_v[fr * a.C + c];
-            }
+        for (int u = 0; u < 8; ++u) {
+            const int64_t fr = fb + 4 * u < f1 ? fb + 4 * u : f1 - 1; // clamped: loads stay unconditional
+            tk[u] = a.fsum_k[fr * a.C + cc];
+            tv[u] = a.fsum_v[fr * a.C + cc];
+        }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                if (fb + u < f1) {
-                    sk += tk[u];
-                    sv += tv[u];
-                }
+        for (int u = 0; u < 8; ++u) {
+            if (fb + 4 * u < f1) {
+                sk += tk[u];
+                sv += tv[u];
             }
         }
+    }
+    part_k[slice][threadIdx.x & (kSegChan - 1)] = sk;
+    part_v[slice][threadIdx.x & (kSegChan - 1)] = sv;
+    __syncthreads();
+    if (slice == 0 && c < a.C) {
+        sk = (fresh ? 0.0 : a.ssum_k[(int64_t)s * a.C + c]) + ((part_k[0][threadIdx.x] + part_k[1][threadIdx.x]) + (part_k[2][threadIdx.x] + part_k[3][threadIdx.x]));
+        sv = (fresh ? 0.0 : a.ssum_v[(int64_t)s * a.C + c]) + ((part_v[0][threadIdx.x] + part_v[1][threadIdx.x]) + (part_v[2][threadIdx.x] + part_v[3][threadIdx.x]));
         a.ssum_k[(int64_t)s * a.C + c] = sk;
         a.ssum_v[(int64_t)s * a.C + c] = sv;
         a.rep_seg_k[(int64_t)s * a.C + c] = (float)(sk / den);
@@ -638,7 +652,7 @@ template <typename V, int ITER>
 __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
     const int y = blockIdx.y;
     if (y >= a.n_slab) {
-        if (blockIdx.x == 0) segment_update(a, a.seg_first + (y - a.n_slab));
+        if (blockIdx.x == 0) segment_update(a, y - a.n_slab);
         return;
     }
     const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
@@ -686,7 +700,7 @@ __global__ __launch_bounds__(256) void compact_listed_kernel(CompactArgs a, cons
                                                              const int32_t *__restrict__ flag_count) {
     const int y = blockIdx.y;
     if (y >= a.n_slab) {
-        if (blockIdx.x == 0) segment_update(a, a.seg_first + (y - a.n_slab));
+        if (blockIdx.x == 0) segment_update(a, y - a.n_slab);
         return;
     }
     const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
@@ -866,10 +880,10 @@ static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, int mode, hip
     k.frame0 = a.frame0;
     k.rep_seg_k = c.rep_seg_k;
     k.rep_seg_v = c.rep_seg_v;
-    const int n_seg = seg_last - k.seg_first + 1;
+    const int n_seg_jobs = (seg_last - k.seg_first + 1) * ((k.C + kSegChan - 1) / kSegChan);
     if (mode == 2) {
         k.bps = 0;
-        hipLaunchKernelGGL((compact_listed_kernel<u32x4>), dim3(kRescoreSlots, k.n_slab + n_seg), dim3(256), 0, st, k,
+        hipLaunchKernelGGL((compact_listed_kernel<u32x4>), dim3(kRescoreSlots, k.n_slab + n_seg_jobs), dim3(256), 0, st, k,
                            c.flag_list[a.parity], c.flag_count + a.parity);
         return hipGetLastError();
     }
@@ -881,10 +895,12 @@ static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, int mode, hip
     }
     k.bps = (max_slot_frames * k.units_per_frame + 256 * ITER - 1) / (256 * ITER);
     const int gx = k.bps * a.map.n_slots;
-    const int gy = k.n_slab + (mode == 0 ? n_seg : 0);
+    const int gy = k.n_slab + (mode == 0 ? n_seg_jobs : 0);
     hipLaunchKernelGGL((compact_kernel<u32x4, ITER>), dim3(gx, gy), dim3(256), 0, st, k);
     return hipGetLastError();
 }
+
+static hipError_t join_copy(Ctx &c, hipStream_t st);
 
 template <typename T>
 static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
@@ -892,6 +908,16 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
     const bool need_att = c.cfg.alpha != 0.0 && !a.have_att_in;
     const bool need_fft = c.cfg.alpha != 1.0;
     int n_part = c.cfg.n_q_heads;
+    // Order on the caller's stream: the frequency kernel (arithmetic bound, little traffic) first,
+    // so that with overlap_copy it runs beside the previous batch's copy (HBM bound); the
+    // attention kernel streams all the queries and gains nothing beside the copy, so it waits
+    // for it; the keep overwrites the list the previous re-scoring chain works from, so it waits
+    // for that chain, which has had the attention kernel's time to finish.
+    if (need_fft) {
+        ProfScope ps(c, MUKV_K_FREQ, st);
+        if ((e = launch_freq<T, float>(c, a, false, c.fft_sig, st)) != hipSuccess) return e;
+    }
+    if ((e = join_copy(c, st)) != hipSuccess) return e;
     if (need_att) {
         ProfScope ps(c, MUKV_K_ATT, st);
         if (c.use_mfma) {
@@ -900,43 +926,75 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
             if ((e = launch_att_generic<T, float>(c, a, false, c.att_part, &n_part, st)) != hipSuccess) return e;
         }
     }
-    if (need_fft) {
-        ProfScope ps(c, MUKV_K_FREQ, st);
-        if ((e = launch_freq<T, float>(c, a, false, c.fft_sig, st)) != hipSuccess) return e;
-    }
+    if ((e = join_streams(c, st)) != hipSuccess) return e;
     {
         ProfScope ps(c, MUKV_K_SELECT, st);
         if ((e = launch_select<T, float>(c, a, c.att_part, n_part, c.fft_sig, 0, st)) != hipSuccess) return e;
     }
-    if (c.margin_thr <= 0.0) {
+    const bool overlap = c.cfg.overlap_copy != 0;
+    const bool rescoring = c.margin_thr > 0.0;
+    if (!overlap && !rescoring) {
         ProfScope ps(c, MUKV_K_COMPACT, st);
         return launch_compact(c, a, 0, st);
     }
-    // Frames with a near-tie at the keep boundary are on the re-scoring list: Eq. 1-4 are redone
-    // for them in fp64, the keep repeated and their rows copied, all on the context's side stream,
-    // while the main copy of every other frame runs on the caller's stream; the two meet again
-    // before this call returns control of the stream to the caller's next work.
-    if (hipEventRecord(c.ev_fork, st) != hipSuccess) return hipErrorUnknown;
-    if (hipStreamWaitEvent(c.side, c.ev_fork, 0) != hipSuccess) return hipErrorUnknown;
-    {
-        ProfScope ps(c, MUKV_K_REFINE, c.side);
-        int n_part64 = c.cfg.n_q_heads;
-        if (need_att)
-            if ((e = launch_att_generic<T, double>(c, a, true, c.att64, &n_part64, c.side)) != hipSuccess) return e;
-        if (need_fft)
-            if ((e = launch_freq<T, double>(c, a, true, c.fft64, c.side)) != hipSuccess) return e;
-        if ((e = launch_select<T, double>(c, a, c.att64, n_part64, c.fft64, 1, c.side)) != hipSuccess) return e;
-        if ((e = launch_compact(c, a, 2, c.side)) != hipSuccess) return e;
+    if ((e = hipEventRecord(c.ev_fork, st)) != hipSuccess) return e;
+    if (rescoring) {
+        // Frames with a near-tie at the keep boundary are on the re-scoring list: Eq. 1-4 are
+        // redone for them in fp64, the keep repeated and their rows copied, all on the context's
+        // side stream, beside the main copy of every other frame.
+        if ((e = hipStreamWaitEvent(c.side, c.ev_fork, 0)) != hipSuccess) return e;
+        {
+            ProfScope ps(c, MUKV_K_REFINE, c.side);
+            int n_part64 = c.cfg.n_q_heads;
+            if (need_att)
+                if ((e = launch_att_generic<T, double>(c, a, true, c.att64, &n_part64, c.side)) != hipSuccess) return e;
+            if (need_fft)
+                if ((e = launch_freq<T, double>(c, a, true, c.fft64, c.side)) != hipSuccess) return e;
+            if ((e = launch_select<T, double>(c, a, c.att64, n_part64, c.fft64, 1, c.side)) != hipSuccess) return e;
+            if ((e = launch_compact(c, a, 2, c.side)) != hipSuccess) return e;
+            // empty the list for the next batch (a one-thread kernel: memset nodes are avoided in graphs)
+            hipLaunchKernelGGL(clear_count_kernel, dim3(1), dim3(1), 0, c.side, c.flag_count + a.parity);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
+        if ((e = hipEventRecord(c.ev_join, c.side)) != hipSuccess) return e;
+        c.side_pending = true;
     }
-    if (hipEventRecord(c.ev_join, c.side) != hipSuccess) return hipErrorUnknown;
-    {
-        ProfScope ps(c, MUKV_K_COMPACT, st);
-        if ((e = launch_compact(c, a, 1, st)) != hipSuccess) return e;
+    // The main copy: on the caller's stream, or (overlap_copy) on the context's copy stream so
+    // that the caller's stream is free for the next batch's scoring kernels meanwhile.
+    hipStream_t cs = st;
+    if (overlap) {
+        cs = c.copy;
+        if ((e = hipStreamWaitEvent(cs, c.ev_fork, 0)) != hipSuccess) return e;
     }
-    if (hipStreamWaitEvent(st, c.ev_join, 0) != hipSuccess) return hipErrorUnknown;
-    // empty the list for the next batch (a one-thread kernel: memset nodes are avoided in graphs)
-    hipLaunchKernelGGL(clear_count_kernel, dim3(1), dim3(1), 0, st, c.flag_count + a.parity);
-    return hipGetLastError();
+    {
+        ProfScope ps(c, MUKV_K_COMPACT, cs);
+        if ((e = launch_compact(c, a, rescoring ? 1 : 0, cs)) != hipSuccess) return e;
+    }
+    if (overlap) {
+        if ((e = hipEventRecord(c.ev_copy, cs)) != hipSuccess) return e;
+        c.copy_pending = true;
+        return hipSuccess;
+    }
+    return join_streams(c, st);
+}
+
+static hipError_t join_copy(Ctx &c, hipStream_t st) {
+    if (c.copy_pending) {
+        hipError_t e = hipStreamWaitEvent(st, c.ev_copy, 0);
+        if (e != hipSuccess) return e;
+        c.copy_pending = false;
+    }
+    return hipSuccess;
+}
+
+hipError_t join_streams(Ctx &c, hipStream_t st) {
+    hipError_t e;
+    if ((e = join_copy(c, st)) != hipSuccess) return e;
+    if (c.side_pending) {
+        if ((e = hipStreamWaitEvent(st, c.ev_join, 0)) != hipSuccess) return e;
+        c.side_pending = false;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_compress(Ctx &c, const ChunkArgs &a, hipStream_t st) {

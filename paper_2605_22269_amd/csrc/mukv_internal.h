@@ -63,7 +63,10 @@ struct Ctx {
     int32_t *src_tok2;                // the same for the frames re-scored in fp64
     int32_t *flag_list[2], *flag_count; // batch frames to re-score in fp64 and how many, by batch parity
     hipStream_t side;                 // re-scoring chain runs here, beside the main copy
-    hipEvent_t ev_fork, ev_join;
+    hipStream_t copy;                 // overlap_copy: the main copy runs here, beside the next batch's scoring
+    hipEvent_t ev_fork;               // scoring and keep of the batch are enqueued
+    hipEvent_t ev_join, ev_copy;      // re-scoring chain / main copy of the batch are enqueued
+    bool side_pending, copy_pending;  // recorded and not yet waited for by the caller's stream
     // retrieval scratch (device)
     double *qbar;    // [max_questions][c_kv]  group-summed mean query
     double *qq;      // [max_questions][Hkv]   partial squared norms of the mean query
@@ -108,6 +111,8 @@ struct ChunkArgs {
 
 
 hipError_t launch_compress(Ctx &c, const ChunkArgs &a, hipStream_t st);
+// orders `st` after the copies and re-scoring chains still outstanding on the library's streams
+hipError_t join_streams(Ctx &c, hipStream_t st);
 
 struct RetrieveArgs {
     const void *q_tokens;

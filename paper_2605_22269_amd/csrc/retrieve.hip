@@ -130,24 +130,35 @@ __global__ __launch_bounds__(256) void score_blocks_kernel(ScoreArgs a) {
 #pragma unroll
     for (int t = 0; t < 16; ++t) rr += (double)row[t] * (double)row[t];
     rr = wave_sum(rr);
-    for (int b = 0; b < a.B; ++b) {
-        const double *qb = a.qbar + (int64_t)b * C;
-        double dot = 0.0;
+    // four questions per round: their pooled queries are loaded together (independent loads),
+    // the four dot products reduced side by side, and lanes 0..3 finish one question each
+    for (int b0 = 0; b0 < a.B; b0 += 4) {
+        double dot[4] = {0.0, 0.0, 0.0, 0.0};
+        const double *qb[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) qb[j] = a.qbar + (int64_t)(b0 + j < a.B ? b0 + j : a.B - 1) * C;
 #pragma unroll
         for (int t = 0; t < 16; ++t) {
-            const int c = lane + 64 * t;
-            dot += (double)row[t] * qb[c < C ? c : C - 1]; // row[t] is 0 past C
+            if (64 * t < C) { // uniform
+                const int c = lane + 64 * t;
+                const int cc = c < C ? c : C - 1; // row[t] is 0 past C
+#pragma unroll
+                for (int j = 0; j < 4; ++j) dot[j] += (double)row[t] * qb[j][cc];
+            }
         }
-        dot = wave_sum(dot);
-        if (lane == 0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dot[j] = wave_sum(dot[j]);
+        const int b = b0 + lane;
+        if (lane < 4 && b < a.B) {
+            const double d = lane == 0 ? dot[0] : (lane == 1 ? dot[1] : (lane == 2 ? dot[2] : dot[3]));
             double qn = 0.0;
             for (int g = 0; g < a.Hkv; ++g) qn += a.qq[(int64_t)b * a.Hkv + g];
-            double s = 0.0;
-            if (rr > 0.0 && qn > 0.0) s = dot / (sqrt(qn) * sqrt((double)a.G * rr));
+            double sc = 0.0;
+            if (rr > 0.0 && qn > 0.0) sc = d / (sqrt(qn) * sqrt((double)a.G * rr));
             if (is_seg)
-                a.s_seg[(int64_t)b * a.ld_seg + idx] = s;
+                a.s_seg[(int64_t)b * a.ld_seg + idx] = sc;
             else
-                a.s_frm[(int64_t)b * a.ld_frm + idx] = s;
+                a.s_frm[(int64_t)b * a.ld_frm + idx] = sc;
         }
     }
 }

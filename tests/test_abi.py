@@ -3,6 +3,7 @@ every symbol the header declares, and rejects bad arguments before touching
 the device."""
 import ctypes as C
 import os
+import subprocess
 import re
 
 import pytest
@@ -16,7 +17,7 @@ def good_cfg(**kw):
     base = dict(n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=64, tokens_per_frame=49, frames_per_segment=8,
                 superpatches_per_frame=4, dtype=mk.MUKV_F32, keep_ratio=0.25, alpha=0.7, causal=1, score_layer=-1,
                 max_frames=64, max_chunk_frames=8, max_questions=2, device_id=0, att_path=0, batch_chunks=0,
-                refine_margin=-1.0)
+                refine_margin=-1.0, overlap_copy=0)
     base.update(kw)
     return mk.mukv_config(**base)
 
@@ -53,6 +54,7 @@ def test_strerror_covers_every_status():
     ("max_frames", 0, mk.MUKV_ERR_INVALID_ARG),
     ("batch_chunks", -1, mk.MUKV_ERR_INVALID_ARG),
     ("batch_chunks", 33, mk.MUKV_ERR_UNSUPPORTED),
+    ("overlap_copy", 2, mk.MUKV_ERR_INVALID_ARG),
 ])
 def test_create_rejects_bad_config_on_the_host(field, value, status):
     lib = mk.load()
@@ -78,9 +80,28 @@ def test_null_arguments():
     assert lib.mukv_get_state(None, None) == mk.MUKV_ERR_INVALID_ARG
 
 
-def test_binding_struct_sizes_match_header_layout():
-    # 8 int32 | 2 double | 8 int32 | double
-    assert C.sizeof(mk.mukv_config) == 8 * 4 + 2 * 8 + 8 * 4 + 8
+def test_binding_struct_sizes_match_header_layout(tmp_path):
+    # 8 int32 | 2 double | 8 int32 | double | int32 (+ tail padding)
+    assert C.sizeof(mk.mukv_config) == 8 * 4 + 2 * 8 + 8 * 4 + 8 + 8
     assert C.sizeof(mk.mukv_retrieve_params) == 6 * 4 + 8
     assert C.sizeof(mk.mukv_strides) == 24
     assert C.sizeof(mk.mukv_state) == 4 * 8 + 2 * 4 + 12 * 8
+    # and against the header itself, through the C compiler: sizes and every field offset
+    structs = {"mukv_config": mk.mukv_config, "mukv_retrieve_params": mk.mukv_retrieve_params,
+               "mukv_strides": mk.mukv_strides, "mukv_state": mk.mukv_state,
+               "mukv_signals_out": mk.mukv_signals_out, "mukv_profile": mk.mukv_profile}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "mukv.h"', 'int main(void) {']
+    for name, st in structs.items():
+        lines.append(f'printf("{name} %zu\\n", sizeof({name}));')
+        for fname, _ in st._fields_:
+            lines.append(f'printf("{name}.{fname} %zu\\n", offsetof({name}, {fname}));')
+    lines += ['return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = dict(l.split() for l in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for name, st in structs.items():
+        assert int(out[name]) == C.sizeof(st), name
+        for fname, _ in st._fields_:
+            assert int(out[f"{name}.{fname}"]) == getattr(st, fname).offset, f"{name}.{fname}"

@@ -342,3 +342,51 @@ def test_batch_is_flushed_when_the_layout_changes():
     p.sig_gpu.append(p.gpu.compress_chunk(kd[:, :, 4 * P:], vd[:, :, 4 * P:], qd[:, 4 * P:], want_signals=True))
     p.check_compress()
     p.close()
+
+
+# ----------------------------------------- copies overlapped with the next batch's scoring ----
+@pytest.mark.parametrize("name,frames,chunk,batch,margin", [("7b", 37, 4, 3, -1.0), ("tiny", 50, 4, 4, 10.0),
+                                                            ("72b", 19, 8, 1, -1.0), ("tiny", 21, 4, 2, 0.0)])
+def test_overlapped_copy_matches_oracle(name, frames, chunk, batch, margin):
+    # every input stays alive in Pair.keep_alive, as the overlapped mode asks
+    w = W[name].scaled(n_frames=frames, n_layers=2, n_questions=2)
+    p = Pair(w, seed=74, chunk=chunk, gpu_kw={"batch_chunks": batch, "overlap_copy": 1, "refine_margin": margin})
+    p.ingest()
+    p.check_compress()
+    p.check_retrieve(questions_for(w, [16, 24], 510), mk.MUKV_SEMI, 2, 5, 0.3)
+    p.close()
+
+
+def test_overlapped_copy_does_not_change_a_bit():
+    w = W["7b"].scaled(n_frames=40, n_layers=3)
+    ref = None
+    for overlap in (0, 1):
+        p = Pair(w, seed=75, chunk=4, gpu_kw={"batch_chunks": 2, "overlap_copy": overlap})
+        p.ingest()
+        st = p.check_compress()
+        n = w.n_frames * p.gpu.kappa
+        gk, gv = p.gpu.store_rows(0, n)
+        cur = {k: st[k].cpu().numpy() for k in ("kept_idx", "rep_frame_k", "rep_seg_k", "rep_seg_v", "rep_patch_v", "margin")}
+        cur["store_k"], cur["store_v"] = np_view(gk).copy(), np_view(gv).copy()
+        if ref is not None:
+            for k in cur:
+                np.testing.assert_array_equal(cur[k], ref[k], err_msg=k)
+        ref = ref or cur
+        p.close()
+
+
+def test_overlapped_copy_retrieve_without_flush_or_sync():
+    # retrieve + gather right behind the last compress call, on the same stream, no host sync
+    # in between: the library itself must order them after the copies still in flight
+    w = W["7b"].scaled(n_frames=24, n_layers=2, n_questions=1)
+    p = Pair(w, seed=76, chunk=8, gpu_kw={"batch_chunks": 1, "overlap_copy": 1})
+    ks, vs, qs = [], [], []
+    for _ in range(3):
+        k, v, q = p.stream.next_chunk(8)
+        p.orc.compress_chunk(np_view(k), np_view(v), q_last=np_view(q))
+        ks.append(k.cuda()); vs.append(v.cuda()); qs.append(q.cuda())
+    torch.cuda.synchronize()
+    for k, v, q in zip(ks, vs, qs):
+        p.gpu.compress_chunk(k, v, q)
+    p.check_retrieve(questions_for(w, [32], 520), mk.MUKV_SEMI, 1, 6, 0.3)
+    p.close()
