@@ -38,13 +38,13 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="hour", choices=["tiny", "7b", "hour", "retrieval", "72b"])
     ap.add_argument("--chunk-frames", type=int, default=0, help="frames per mukv_compress_chunk call (0: workload's)")
-    ap.add_argument("--batch-chunks", type=int, default=32,
+    ap.add_argument("--batch-chunks", type=int, default=64,
                     help="chunks the library gathers before it launches their kernels together (1: launch per chunk)")
     ap.add_argument("--frames", type=int, default=0, help="override the stream length (debugging)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--overlap-copy", type=int, default=1, choices=(0, 1),
-                    help="1: the copy of a batch's kept rows overlaps the next batch's scoring kernels "
-                         "(mukv_config.overlap_copy; the whole stream is resident, so inputs outlive the copies)")
+                    help="1: the copy of a batch's kept rows shares a launch with the next batch's frequency "
+                         "kernel (mukv_config.overlap_copy; the whole stream is resident, so inputs outlive the copies)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-frames", type=int, default=1024)
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,

@@ -86,19 +86,19 @@ typedef struct mukv_config {
     int32_t device_id;              /* HIP device ordinal                              */
     int32_t att_path;               /* mukv_att_path; AUTO picks MFMA when supported   */
     int32_t batch_chunks;           /* 0 or 1: every mukv_compress_chunk enqueues its kernels at
-                                       once.  N > 1 (at most 32): the library gathers N chunks
+                                       once.  N > 1 (at most 64): the library gathers N chunks
                                        and processes them with one chain of launches; see
                                        mukv_compress_chunk for what that asks of the caller    */
     double refine_margin;           /* frames whose selection margin (gap between the
                                        last kept and first dropped fused score) is
                                        below this are re-scored in fp64 before the
                                        keep; < 0 = library default, 0 = never          */
-    int32_t overlap_copy;           /* 0: a call that enqueues kernels leaves the caller's
-                                       stream ordered after all of them.  1: the copy of the
-                                       kept rows (and the fp64 re-scoring) of one batch runs on
-                                       the library's own streams while the caller's stream goes
-                                       on to the scoring kernels of the next batch; see
-                                       mukv_compress_chunk for what that asks of the caller    */
+    int32_t overlap_copy;           /* 0: a call that enqueues kernels enqueues all of them.
+                                       1: the copy of a batch's kept rows is put off until the
+                                       next batch arrives and then shares one launch with that
+                                       batch's frequency kernel (HBM-bound and arithmetic-bound
+                                       work side by side); see mukv_compress_chunk for what that
+                                       asks of the caller                                       */
 } mukv_config;
 
 /* Element strides (not bytes) of a [layer][head][token][dim] tensor; dim is
@@ -161,13 +161,15 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out);
  * streams it used.  NULL is accepted. */
 int mukv_destroy(mukv_ctx *ctx);
 
-/* Forgets the stream (n_frames = 0, gathered chunks dropped) without freeing memory. */
+/* Forgets the stream (n_frames = 0, gathered chunks and a copy that was put off
+ * are dropped) without freeing memory.  Kernels of earlier calls may still be
+ * running: later calls on the same stream are ordered after them as usual. */
 int mukv_reset(mukv_ctx *ctx);
 
 /* Enqueues the kernels of the chunks gathered so far (batch_chunks > 1) and, with
- * overlap_copy, orders the stream of the last compress call after the work still
- * running on the library's own streams.  A no-op when there is neither.  Does not
- * synchronise the host. */
+ * overlap_copy, the copy that was put off; the stream of the last compress call is
+ * then ordered after everything the library has enqueued.  A no-op when there is
+ * neither.  Does not synchronise the host. */
 int mukv_flush(mukv_ctx *ctx);
 
 /*
@@ -197,12 +199,11 @@ int mukv_flush(mukv_ctx *ctx);
  * reported by the call that submits the chunk, launch errors by the call that
  * flushes.
  *
- * With overlap_copy = 1 the rows of a batch are still being copied out of the
- * input buffers while the stream already runs what the caller enqueues next.
- * The inputs (and `sig` outputs) of a batch must then stay alive and unchanged
- * until the stream has passed the NEXT call that enqueues compress kernels, or
- * a mukv_flush, mukv_retrieve or mukv_gather_kv call: each of these orders its
- * stream after the outstanding copies.  Results are the same bit for bit.
+ * With overlap_copy = 1 the rows of a batch are copied out of the input buffers
+ * only by the NEXT call that enqueues compress kernels, or by a mukv_flush,
+ * mukv_retrieve or mukv_gather_kv call.  The inputs (and `sig` outputs) of a
+ * batch must then stay alive and unchanged until the stream has passed that
+ * call.  Results are the same bit for bit.
  *
  * Errors: INVALID_ARG (null k/v, missing or doubled attention source),
  * SHAPE (n_frames < 1), CAPACITY (n_frames > max_chunk_frames or the cache is
@@ -262,7 +263,9 @@ typedef enum mukv_kernel_id {
     MUKV_K_SCORE = 6,   /* Eq. 7                                               */
     MUKV_K_RERANK = 7,  /* top-k selections and Eq. 8                          */
     MUKV_K_GATHER = 8,  /* Sec. 3.5 gather                                     */
-    MUKV_K_COUNT = 9
+    MUKV_K_COPY_FREQ = 9, /* overlap_copy: copy of the previous batch's kept rows and
+                             Eq. 2-3 of the new batch in one launch                */
+    MUKV_K_COUNT = 10
 } mukv_kernel_id;
 
 typedef struct mukv_profile {

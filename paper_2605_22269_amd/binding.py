@@ -8,6 +8,7 @@ has not been built, loading raises.
 """
 from __future__ import annotations
 
+import collections
 import ctypes as C
 import os
 
@@ -60,7 +61,7 @@ class mukv_state(C.Structure):
     ]
 
 
-KERNEL_NAMES = ("att", "freq", "select", "refine", "compact", "poolq", "score", "rerank", "gather")
+KERNEL_NAMES = ("att", "freq", "select", "refine", "compact", "poolq", "score", "rerank", "gather", "copy_freq")
 
 
 class mukv_profile(C.Structure):
@@ -206,6 +207,9 @@ class MuKV:
         self.h = mukv_create(self.cfg)
         st = mukv_get_state(self.h)
         self.kappa, self.c_kv = st.kappa, st.c_kv
+        # references to the buffers of the chunks the library may still read: the batch being
+        # gathered, the one before it (overlap_copy) and one spare
+        self._held = collections.deque(maxlen=2 * max(1, batch_chunks) + 1)
 
     def close(self):
         if self.h is not None:
@@ -220,9 +224,11 @@ class MuKV:
 
     def reset(self):
         mukv_reset(self.h)
+        self._held.clear()
 
     def flush(self):
         mukv_flush(self.h)
+        self._held.clear()   # everything that reads them is enqueued on the stream
 
     @property
     def n_frames(self):
@@ -248,6 +254,9 @@ class MuKV:
         if att_signal is not None:
             assert att_signal.dtype == torch.float32 and att_signal.is_contiguous() and att_signal.shape == (n, P)
         mukv_compress_chunk(self.h, _ptr(k), _ptr(v), kvs, _ptr(q_last), qs, _ptr(att_signal), n, _stream(), sig)
+        # The library reads these buffers (and writes the signal outputs) when the gathered batch is
+        # launched, with overlap_copy one batch later still: hold references that long.
+        self._held.append((k, v, q_last, att_signal, outs))
         return outs
 
     def retrieve(self, q_tokens, q_offsets, *, mode=MUKV_SEMI, k_seg=8, k_frame=32, lambda_frame=0.3, n_global=0,
@@ -267,6 +276,7 @@ class MuKV:
             }
         mukv_retrieve(self.h, _ptr(q_tokens), _ptr(q_offsets), B, prm, _ptr(out["seg_idx"]), _ptr(out["seg_score"]),
                       _ptr(out["frame_idx"]), _ptr(out["frame_score"]), _stream())
+        self._held.clear()   # the call has enqueued everything that reads them
         return out
 
     def gather_kv(self, frame_idx, order=MUKV_TEMPORAL, out=None):
@@ -281,6 +291,7 @@ class MuKV:
                    torch.empty(shape, dtype=self.dtype, device=frame_idx.device),
                    torch.empty(B, dtype=torch.int32, device=frame_idx.device))
         mukv_gather_kv(self.h, _ptr(frame_idx), B, kf, order, _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _stream())
+        self._held.clear()
         return out
 
     # -- read-only copies of the context's tables (tests, inspection) ----------------------

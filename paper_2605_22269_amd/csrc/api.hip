@@ -65,13 +65,12 @@ void free_all(Ctx &c) {
                     c.src_tok,     c.src_tok2,    c.flag_list[0], c.flag_list[1], c.flag_count, c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail};
     // nothing of the library's own may still be running on what is freed below
     if (c.side) (void)hipStreamSynchronize(c.side);
-    if (c.copy) (void)hipStreamSynchronize(c.copy);
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (c.side) (void)hipStreamDestroy(c.side);
     if (c.ev_fork) (void)hipEventDestroy(c.ev_fork);
     if (c.ev_join) (void)hipEventDestroy(c.ev_join);
-    if (c.copy) (void)hipStreamDestroy(c.copy);
+    delete c.deferred;
     if (c.ev_copy) (void)hipEventDestroy(c.ev_copy);
 }
 
@@ -160,14 +159,14 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(hipStreamCreateWithFlags(&c.side, hipStreamNonBlocking));
     ok(hipEventCreateWithFlags(&c.ev_fork, hipEventDisableTiming));
     ok(hipEventCreateWithFlags(&c.ev_join, hipEventDisableTiming));
-    ok(hipStreamCreateWithFlags(&c.copy, hipStreamNonBlocking));
+    c.deferred = new (std::nothrow) mukv::ChunkArgs();
     ok(hipEventCreateWithFlags(&c.ev_copy, hipEventDisableTiming));
     ok(dalloc(&c.qbar, MQ * C));
     ok(dalloc(&c.qq, MQ * cfg->n_kv_heads));
     ok(dalloc(&c.s_frm, MQ * MF));
     ok(dalloc(&c.s_seg, MQ * (size_t)c.max_segments));
     ok(dalloc(&c.seg_tail, 2 * C));
-    if (e != hipSuccess || !c.prof || !c.pending) {
+    if (e != hipSuccess || !c.prof || !c.pending || !c.deferred) {
         free_all(c);
         delete c.prof;
         delete c.pending;
@@ -225,6 +224,10 @@ int mukv_reset(mukv_ctx *ctx) {
     ctx->c.n_frames = 0;
     ctx->c.n_done = 0;
     ctx->c.pending->clear();
+    if (ctx->c.deferred_pending) { // the rows it would have copied are forgotten with the rest
+        if (hipSetDevice(ctx->c.cfg.device_id) != hipSuccess || mukv::drop_deferred(ctx->c) != hipSuccess)
+            return MUKV_ERR_HIP;
+    }
     return MUKV_OK;
 }
 

@@ -80,12 +80,12 @@ __device__ __forceinline__ void fft_stages(R (&zr)[GH], R (&zi)[GH], const R *sg
 }
 constexpr int kRescoreSlots = 1; // grid.x of the fp64 re-scoring kernels; they loop over the list
 
+// Work of workgroup (bx, by) of a (gx, kFreqBlocksPerFrame) grid.
 template <typename T, typename R, int D>
-__global__ __launch_bounds__(256) void freq_signal_kernel(PtrTable ktab, FrameMap map, int64_t k_off, int64_t sh,
-                                                          int64_t st, int Hkv, int P,
-                                                          const int32_t *__restrict__ flag_list,
-                                                          const int32_t *__restrict__ flag_count,
-                                                          R *__restrict__ out) {
+__device__ __forceinline__ void freq_body(const PtrTable &ktab, const FrameMap &map, int64_t k_off, int64_t sh,
+                                          int64_t st, int Hkv, int P, const int32_t *__restrict__ flag_list,
+                                          const int32_t *__restrict__ flag_count, R *__restrict__ out, int bx, int by,
+                                          int gx) {
     constexpr int N = D / 2;
     constexpr int GROUPS = kWave / N;
     constexpr int LOG = (N == 64) ? 6 : (N == 32) ? 5 : (N == 16) ? 4 : 3;
@@ -110,8 +110,8 @@ __global__ __launch_bounds__(256) void freq_signal_kernel(PtrTable ktab, FrameMa
     sincospi_t(-(R)kb / (R)N, &uwi, &uwr);
 
     // frames: every batch frame (grid.x = n_frames), or the entries of the re-scoring list
-    const int n_e = flag_list ? *flag_count : (int)gridDim.x;
-    for (int e = blockIdx.x; e < n_e; e += gridDim.x) {
+    const int n_e = flag_list ? *flag_count : gx;
+    for (int e = bx; e < n_e; e += gx) {
     const int f = flag_list ? flag_list[e] : e;
     const int slot = find_slot(map, f);
     const T *k = reinterpret_cast<const T *>(ktab.p[slot]) + k_off + (int64_t)(f - map.fstart[slot]) * P * st;
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(256) void freq_signal_kernel(PtrTable ktab, FrameMa
     // lane-exchange latency), and the key elements of the next group are loaded before the
     // current group is computed.
     constexpr int GH = 4;
-    const int t_first = (blockIdx.y * 4 + wave) * GROUPS;
+    const int t_first = (by * 4 + wave) * GROUPS;
     auto load_group = [&](int t0, int g0, T *a0, T *a1) {
         const int tok = t0 + sub < P ? t0 + sub : P - 1;
         const T *r = k + (int64_t)tok * st + 2 * p;
@@ -174,6 +174,15 @@ __global__ __launch_bounds__(256) void freq_signal_kernel(PtrTable ktab, FrameMa
         if (p == 0 && valid) out[(int64_t)f * P + tok] = total / (R)(Hkv * D);
     }
     }
+}
+
+template <typename T, typename R, int D>
+__global__ __launch_bounds__(256) void freq_signal_kernel(PtrTable ktab, FrameMap map, int64_t k_off, int64_t sh,
+                                                          int64_t st, int Hkv, int P,
+                                                          const int32_t *__restrict__ flag_list,
+                                                          const int32_t *__restrict__ flag_count,
+                                                          R *__restrict__ out) {
+    freq_body<T, R, D>(ktab, map, k_off, sh, st, Hkv, P, flag_list, flag_count, out, blockIdx.x, blockIdx.y, gridDim.x);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -648,16 +657,16 @@ __device__ __forceinline__ void segment_update(const CompactArgs &a, int job) {
     }
 }
 
+// Work of workgroup (gx_i, y) of compact_kernel's grid.
 template <typename V, int ITER>
-__global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
-    const int y = blockIdx.y;
+__device__ __forceinline__ void compact_body(const CompactArgs &a, int gx_i, int y) {
     if (y >= a.n_slab) {
-        if (blockIdx.x == 0) segment_update(a, y - a.n_slab);
+        if (gx_i == 0) segment_update(a, y - a.n_slab);
         return;
     }
     const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
     const int kv = rem / a.Hkv, g = rem - kv * a.Hkv;
-    const int slot = blockIdx.x / a.bps, bx = blockIdx.x - slot * a.bps;
+    const int slot = gx_i / a.bps, bx = gx_i - slot * a.bps;
     const int f_lo = a.map.fstart[slot];
     const int n_units = (a.map.fstart[slot + 1] - f_lo) * a.units_per_frame;
     if (bx * (256 * ITER) >= n_units) return;
@@ -689,6 +698,40 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
     for (int it = 0; it < ITER; ++it) {
         const int u = u0 + it * 256;
         if (u < n_units && row_tok[it] >= 0) *reinterpret_cast<V *>(dst + (int64_t)u * sizeof(V)) = tmp[it];
+    }
+}
+
+template <typename V, int ITER>
+__global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
+    compact_body<V, ITER>(a, blockIdx.x, blockIdx.y);
+}
+
+// overlap_copy: the copy of the previous batch's kept rows (HBM bound) and the frequency signal of
+// the new batch (arithmetic bound) in one launch, so that both kinds of work are resident on every
+// compute unit together.  1-D grid of n_copy + n_freq workgroups; every `period`-th one is a
+// frequency workgroup, the others walk compact_kernel's (copy_gx, y) grid in its own order.
+constexpr int kFusedCopyIter = 4; // 16-byte loads in flight per lane of a copy workgroup
+struct FreqPart {
+    PtrTable k;
+    FrameMap map;
+    int64_t k_off, sh, st;
+    int Hkv, P;
+    float *out;
+    int n_frames; // grid.x of the stand-alone frequency kernel
+    int n_wg;     // n_frames * kFreqBlocksPerFrame
+};
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void copy_freq_kernel(CompactArgs ca, int copy_gx, FreqPart fp, int period) {
+    const int b = blockIdx.x;
+    const int q = b / period, r = b - q * period;
+    if (r == 0 && q < fp.n_wg) {
+        freq_body<T, float, D>(fp.k, fp.map, fp.k_off, fp.sh, fp.st, fp.Hkv, fp.P, nullptr, nullptr, fp.out,
+                               q % fp.n_frames, q / fp.n_frames, fp.n_frames);
+    } else {
+        const int before = q + (r > 0) < fp.n_wg ? q + (r > 0) : fp.n_wg; // frequency workgroups with a lower number
+        const int cid = b - before;
+        compact_body<u32x4, kFusedCopyIter>(ca, cid % copy_gx, cid / copy_gx);
     }
 }
 
@@ -847,8 +890,8 @@ static int ilog2(int x) {
 
 // mode 0: every frame + segment update (no re-scoring); 1: main copy, frames on the re-scoring
 // list skipped, no segment update; 2: listed frames only (rows from the fp64 pass) + segment update
-static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, int mode, hipStream_t st) {
-    CompactArgs k;
+constexpr int kCompactIter = 4;
+static void compact_args(const Ctx &c, const ChunkArgs &a, int mode, int iter, CompactArgs &k, int &gx, int &gy) {
     const int esz = c.esz, D = c.cfg.head_dim;
     const int row_b = D * esz;
     k.k = a.k;
@@ -883,41 +926,170 @@ static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, int mode, hip
     const int n_seg_jobs = (seg_last - k.seg_first + 1) * ((k.C + kSegChan - 1) / kSegChan);
     if (mode == 2) {
         k.bps = 0;
-        hipLaunchKernelGGL((compact_listed_kernel<u32x4>), dim3(kRescoreSlots, k.n_slab + n_seg_jobs), dim3(256), 0, st, k,
-                           c.flag_list[a.parity], c.flag_count + a.parity);
-        return hipGetLastError();
+        gx = kRescoreSlots;
+        gy = k.n_slab + n_seg_jobs;
+        return;
     }
-    constexpr int ITER = 4;
     int max_slot_frames = 0;
     for (int s = 0; s < a.map.n_slots; ++s) {
         const int n = a.map.fstart[s + 1] - a.map.fstart[s];
         max_slot_frames = n > max_slot_frames ? n : max_slot_frames;
     }
-    k.bps = (max_slot_frames * k.units_per_frame + 256 * ITER - 1) / (256 * ITER);
-    const int gx = k.bps * a.map.n_slots;
-    const int gy = k.n_slab + (mode == 0 ? n_seg_jobs : 0);
-    hipLaunchKernelGGL((compact_kernel<u32x4, ITER>), dim3(gx, gy), dim3(256), 0, st, k);
+    k.bps = (max_slot_frames * k.units_per_frame + 256 * iter - 1) / (256 * iter);
+    gx = k.bps * a.map.n_slots;
+    gy = k.n_slab + (mode == 0 ? n_seg_jobs : 0);
+}
+
+static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, int mode, hipStream_t st) {
+    CompactArgs k;
+    int gx, gy;
+    compact_args(c, a, mode, kCompactIter, k, gx, gy);
+    if (mode == 2)
+        hipLaunchKernelGGL((compact_listed_kernel<u32x4>), dim3(gx, gy), dim3(256), 0, st, k, c.flag_list[a.parity],
+                           c.flag_count + a.parity);
+    else
+        hipLaunchKernelGGL((compact_kernel<u32x4, kCompactIter>), dim3(gx, gy), dim3(256), 0, st, k);
     return hipGetLastError();
 }
 
-static hipError_t join_copy(Ctx &c, hipStream_t st);
+// One launch for the copy of batch `prev` (mode as for launch_compact) and Eq. 2-3 of batch `a`.
+template <typename T>
+static hipError_t launch_copy_freq(const Ctx &c, const ChunkArgs &prev, int mode, const ChunkArgs &a, hipStream_t st) {
+    CompactArgs k;
+    int gx, gy;
+    compact_args(c, prev, mode, kFusedCopyIter, k, gx, gy);
+    FreqPart fp;
+    fp.k = a.k;
+    fp.map = a.map;
+    fp.k_off = (int64_t)c.ls * a.kv_sl;
+    fp.sh = a.kv_sh;
+    fp.st = a.kv_st;
+    fp.Hkv = c.cfg.n_kv_heads;
+    fp.P = c.cfg.tokens_per_frame;
+    fp.out = c.fft_sig;
+    fp.n_frames = a.n_frames;
+    fp.n_wg = a.n_frames * kFreqBlocksPerFrame;
+    const int64_t n_copy = (int64_t)gx * gy;
+    const int64_t total = n_copy + fp.n_wg;
+    if (total > 0x7fffffff) return hipErrorInvalidValue;
+    const int period = (int)(total / fp.n_wg); // >= 1; frequency workgroups at 0, period, 2*period, ...
+#define MUKV_COPY_FREQ(DD) \
+    hipLaunchKernelGGL((copy_freq_kernel<T, DD>), dim3((unsigned)total), dim3(256), 0, st, k, gx, fp, period)
+    switch (c.cfg.head_dim) {
+    case 128: MUKV_COPY_FREQ(128); break;
+    case 64: MUKV_COPY_FREQ(64); break;
+    case 32: MUKV_COPY_FREQ(32); break;
+    case 16: MUKV_COPY_FREQ(16); break;
+    default: return hipErrorInvalidValue;
+    }
+#undef MUKV_COPY_FREQ
+    return hipGetLastError();
+}
+
+static hipError_t wait_side(Ctx &c, hipStream_t st) {
+    if (c.side_pending) {
+        hipError_t e = hipStreamWaitEvent(st, c.ev_join, 0);
+        if (e != hipSuccess) return e;
+        c.side_pending = false;
+    }
+    return hipSuccess;
+}
+
+// Frames with a near-tie at the keep boundary are on the re-scoring list: Eq. 1-4 are redone for
+// them in fp64, the keep repeated and their rows copied, all on the context's side stream (behind
+// ev_fork, recorded after the batch's keep), beside whatever the caller's stream does meanwhile.
+template <typename T>
+static hipError_t launch_rescoring(Ctx &c, const ChunkArgs &a) {
+    hipError_t e;
+    const bool need_att = c.cfg.alpha != 0.0 && !a.have_att_in;
+    const bool need_fft = c.cfg.alpha != 1.0;
+    if ((e = hipStreamWaitEvent(c.side, c.ev_fork, 0)) != hipSuccess) return e;
+    {
+        ProfScope ps(c, MUKV_K_REFINE, c.side);
+        int n_part64 = c.cfg.n_q_heads;
+        if (need_att)
+            if ((e = launch_att_generic<T, double>(c, a, true, c.att64, &n_part64, c.side)) != hipSuccess) return e;
+        if (need_fft)
+            if ((e = launch_freq<T, double>(c, a, true, c.fft64, c.side)) != hipSuccess) return e;
+        if ((e = launch_select<T, double>(c, a, c.att64, n_part64, c.fft64, 1, c.side)) != hipSuccess) return e;
+        if ((e = launch_compact(c, a, 2, c.side)) != hipSuccess) return e;
+        // empty the list for the next batch (a one-thread kernel: memset nodes are avoided in graphs)
+        hipLaunchKernelGGL(clear_count_kernel, dim3(1), dim3(1), 0, c.side, c.flag_count + a.parity);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if ((e = hipEventRecord(c.ev_join, c.side)) != hipSuccess) return e;
+    c.side_pending = true;
+    return hipSuccess;
+}
+
+static hipError_t launch_deferred_rescoring(Ctx &c) {
+    if (c.margin_thr <= 0.0) return hipSuccess;
+    return c.cfg.dtype == MUKV_BF16 ? launch_rescoring<uint16_t>(c, *c.deferred) : launch_rescoring<float>(c, *c.deferred);
+}
+
+// The copy (and re-scoring) that was put off, launched on its own: no new batch to share with.
+static hipError_t launch_deferred(Ctx &c) {
+    if (!c.deferred_pending) return hipSuccess;
+    c.deferred_pending = false;
+    hipError_t e;
+    {
+        ProfScope ps(c, MUKV_K_COMPACT, c.deferred_stream);
+        if ((e = launch_compact(c, *c.deferred, c.margin_thr > 0.0 ? 1 : 0, c.deferred_stream)) != hipSuccess) return e;
+    }
+    return launch_deferred_rescoring(c);
+}
+
+hipError_t drop_deferred(Ctx &c) {
+    if (!c.deferred_pending) return hipSuccess;
+    c.deferred_pending = false;
+    if (c.margin_thr <= 0.0) return hipSuccess;
+    // the dropped batch's keep may have left frames on the re-scoring list
+    hipLaunchKernelGGL(clear_count_kernel, dim3(1), dim3(1), 0, c.deferred_stream, c.flag_count + c.deferred->parity);
+    return hipGetLastError();
+}
+
+hipError_t join_streams(Ctx &c, hipStream_t st) {
+    hipError_t e;
+    if (c.deferred_pending) {
+        hipStream_t ds = c.deferred_stream;
+        if ((e = launch_deferred(c)) != hipSuccess) return e;
+        if (ds != st) {
+            if ((e = hipEventRecord(c.ev_copy, ds)) != hipSuccess) return e;
+            if ((e = hipStreamWaitEvent(st, c.ev_copy, 0)) != hipSuccess) return e;
+        }
+    }
+    return wait_side(c, st);
+}
 
 template <typename T>
 static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
     hipError_t e;
     const bool need_att = c.cfg.alpha != 0.0 && !a.have_att_in;
     const bool need_fft = c.cfg.alpha != 1.0;
+    const bool overlap = c.cfg.overlap_copy != 0;
+    const bool rescoring = c.margin_thr > 0.0;
     int n_part = c.cfg.n_q_heads;
-    // Order on the caller's stream: the frequency kernel (arithmetic bound, little traffic) first,
-    // so that with overlap_copy it runs beside the previous batch's copy (HBM bound); the
-    // attention kernel streams all the queries and gains nothing beside the copy, so it waits
-    // for it; the keep overwrites the list the previous re-scoring chain works from, so it waits
-    // for that chain, which has had the attention kernel's time to finish.
-    if (need_fft) {
-        ProfScope ps(c, MUKV_K_FREQ, st);
-        if ((e = launch_freq<T, float>(c, a, false, c.fft_sig, st)) != hipSuccess) return e;
+    // a copy put off on another stream cannot share a launch with this batch
+    if (c.deferred_pending && c.deferred_stream != st)
+        if ((e = join_streams(c, st)) != hipSuccess) return e;
+    // Frequency signal first: with overlap_copy it shares its launch with the previous batch's
+    // row copy (arithmetic-bound beside HBM-bound work; the attention kernel streams all the
+    // queries and gains nothing beside a copy).  The previous batch's re-scoring chain goes out
+    // right behind it, so that the caller's stream continues with this launch.
+    if (need_fft && c.deferred_pending) {
+        c.deferred_pending = false;
+        {
+            ProfScope ps(c, MUKV_K_COPY_FREQ, st);
+            if ((e = launch_copy_freq<T>(c, *c.deferred, rescoring ? 1 : 0, a, st)) != hipSuccess) return e;
+        }
+        if ((e = launch_deferred_rescoring(c)) != hipSuccess) return e;
+    } else {
+        if ((e = launch_deferred(c)) != hipSuccess) return e;
+        if (need_fft) {
+            ProfScope ps(c, MUKV_K_FREQ, st);
+            if ((e = launch_freq<T, float>(c, a, false, c.fft_sig, st)) != hipSuccess) return e;
+        }
     }
-    if ((e = join_copy(c, st)) != hipSuccess) return e;
     if (need_att) {
         ProfScope ps(c, MUKV_K_ATT, st);
         if (c.use_mfma) {
@@ -926,75 +1098,28 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
             if ((e = launch_att_generic<T, float>(c, a, false, c.att_part, &n_part, st)) != hipSuccess) return e;
         }
     }
-    if ((e = join_streams(c, st)) != hipSuccess) return e;
+    // The keep overwrites the list the previous batch's re-scoring chain works from: that chain
+    // must have finished (it has had the kernels above to do so).
+    if ((e = wait_side(c, st)) != hipSuccess) return e;
     {
         ProfScope ps(c, MUKV_K_SELECT, st);
         if ((e = launch_select<T, float>(c, a, c.att_part, n_part, c.fft_sig, 0, st)) != hipSuccess) return e;
     }
-    const bool overlap = c.cfg.overlap_copy != 0;
-    const bool rescoring = c.margin_thr > 0.0;
-    if (!overlap && !rescoring) {
-        ProfScope ps(c, MUKV_K_COMPACT, st);
-        return launch_compact(c, a, 0, st);
-    }
-    if ((e = hipEventRecord(c.ev_fork, st)) != hipSuccess) return e;
-    if (rescoring) {
-        // Frames with a near-tie at the keep boundary are on the re-scoring list: Eq. 1-4 are
-        // redone for them in fp64, the keep repeated and their rows copied, all on the context's
-        // side stream, beside the main copy of every other frame.
-        if ((e = hipStreamWaitEvent(c.side, c.ev_fork, 0)) != hipSuccess) return e;
-        {
-            ProfScope ps(c, MUKV_K_REFINE, c.side);
-            int n_part64 = c.cfg.n_q_heads;
-            if (need_att)
-                if ((e = launch_att_generic<T, double>(c, a, true, c.att64, &n_part64, c.side)) != hipSuccess) return e;
-            if (need_fft)
-                if ((e = launch_freq<T, double>(c, a, true, c.fft64, c.side)) != hipSuccess) return e;
-            if ((e = launch_select<T, double>(c, a, c.att64, n_part64, c.fft64, 1, c.side)) != hipSuccess) return e;
-            if ((e = launch_compact(c, a, 2, c.side)) != hipSuccess) return e;
-            // empty the list for the next batch (a one-thread kernel: memset nodes are avoided in graphs)
-            hipLaunchKernelGGL(clear_count_kernel, dim3(1), dim3(1), 0, c.side, c.flag_count + a.parity);
-            if ((e = hipGetLastError()) != hipSuccess) return e;
-        }
-        if ((e = hipEventRecord(c.ev_join, c.side)) != hipSuccess) return e;
-        c.side_pending = true;
-    }
-    // The main copy: on the caller's stream, or (overlap_copy) on the context's copy stream so
-    // that the caller's stream is free for the next batch's scoring kernels meanwhile.
-    hipStream_t cs = st;
-    if (overlap) {
-        cs = c.copy;
-        if ((e = hipStreamWaitEvent(cs, c.ev_fork, 0)) != hipSuccess) return e;
-    }
-    {
-        ProfScope ps(c, MUKV_K_COMPACT, cs);
-        if ((e = launch_compact(c, a, rescoring ? 1 : 0, cs)) != hipSuccess) return e;
-    }
-    if (overlap) {
-        if ((e = hipEventRecord(c.ev_copy, cs)) != hipSuccess) return e;
-        c.copy_pending = true;
+    if (rescoring)
+        if ((e = hipEventRecord(c.ev_fork, st)) != hipSuccess) return e;
+    if (overlap) { // copy and re-scoring wait for the next batch (or a flush / retrieve / gather call)
+        *c.deferred = a;
+        c.deferred_pending = true;
+        c.deferred_stream = st;
         return hipSuccess;
     }
-    return join_streams(c, st);
-}
-
-static hipError_t join_copy(Ctx &c, hipStream_t st) {
-    if (c.copy_pending) {
-        hipError_t e = hipStreamWaitEvent(st, c.ev_copy, 0);
-        if (e != hipSuccess) return e;
-        c.copy_pending = false;
+    if (rescoring)
+        if ((e = launch_rescoring<T>(c, a)) != hipSuccess) return e;
+    {
+        ProfScope ps(c, MUKV_K_COMPACT, st);
+        if ((e = launch_compact(c, a, rescoring ? 1 : 0, st)) != hipSuccess) return e;
     }
-    return hipSuccess;
-}
-
-hipError_t join_streams(Ctx &c, hipStream_t st) {
-    hipError_t e;
-    if ((e = join_copy(c, st)) != hipSuccess) return e;
-    if (c.side_pending) {
-        if ((e = hipStreamWaitEvent(st, c.ev_join, 0)) != hipSuccess) return e;
-        c.side_pending = false;
-    }
-    return hipSuccess;
+    return wait_side(c, st);
 }
 
 hipError_t launch_compress(Ctx &c, const ChunkArgs &a, hipStream_t st) {

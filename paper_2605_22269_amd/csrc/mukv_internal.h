@@ -29,6 +29,8 @@ struct ProfEntry {
     hipEvent_t start, stop;
 };
 
+struct ChunkArgs;
+
 struct Ctx {
     mukv_config cfg;
     bool profiling;
@@ -63,10 +65,13 @@ struct Ctx {
     int32_t *src_tok2;                // the same for the frames re-scored in fp64
     int32_t *flag_list[2], *flag_count; // batch frames to re-score in fp64 and how many, by batch parity
     hipStream_t side;                 // re-scoring chain runs here, beside the main copy
-    hipStream_t copy;                 // overlap_copy: the main copy runs here, beside the next batch's scoring
     hipEvent_t ev_fork;               // scoring and keep of the batch are enqueued
-    hipEvent_t ev_join, ev_copy;      // re-scoring chain / main copy of the batch are enqueued
-    bool side_pending, copy_pending;  // recorded and not yet waited for by the caller's stream
+    hipEvent_t ev_join;               // re-scoring chain of the batch is enqueued
+    hipEvent_t ev_copy;               // the copy that was put off is enqueued (orders another stream after it)
+    bool side_pending;                // ev_join recorded and not yet waited for by the caller's stream
+    ChunkArgs *deferred;              // overlap_copy: the batch whose row copy is still to be launched
+    bool deferred_pending;
+    hipStream_t deferred_stream;      // stream that batch was submitted on
     // retrieval scratch (device)
     double *qbar;    // [max_questions][c_kv]  group-summed mean query
     double *qq;      // [max_questions][Hkv]   partial squared norms of the mean query
@@ -79,7 +84,7 @@ struct Ctx {
 // Every chunk handed to mukv_compress_chunk occupies one slot; the kernels see the batch as
 // frames 0..n_frames-1 and resolve a frame to (slot, frame inside the chunk) with FrameMap.
 // The tables travel by value in the kernel arguments, so a captured HIP graph replays them as is.
-constexpr int kMaxSlots = 32;
+constexpr int kMaxSlots = 64;
 struct PtrTable {
     const void *p[kMaxSlots];
 };
@@ -111,8 +116,11 @@ struct ChunkArgs {
 
 
 hipError_t launch_compress(Ctx &c, const ChunkArgs &a, hipStream_t st);
-// orders `st` after the copies and re-scoring chains still outstanding on the library's streams
+// launches the copy that was put off (overlap_copy) and orders `st` after it and after the
+// re-scoring chain still outstanding on the side stream
 hipError_t join_streams(Ctx &c, hipStream_t st);
+// forgets the copy that was put off (mukv_reset) and leaves the re-scoring list empty
+hipError_t drop_deferred(Ctx &c);
 
 struct RetrieveArgs {
     const void *q_tokens;

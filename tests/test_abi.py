@@ -53,7 +53,7 @@ def test_strerror_covers_every_status():
     ("tokens_per_frame", 300, mk.MUKV_ERR_UNSUPPORTED),
     ("max_frames", 0, mk.MUKV_ERR_INVALID_ARG),
     ("batch_chunks", -1, mk.MUKV_ERR_INVALID_ARG),
-    ("batch_chunks", 33, mk.MUKV_ERR_UNSUPPORTED),
+    ("batch_chunks", 65, mk.MUKV_ERR_UNSUPPORTED),
     ("overlap_copy", 2, mk.MUKV_ERR_INVALID_ARG),
 ])
 def test_create_rejects_bad_config_on_the_host(field, value, status):

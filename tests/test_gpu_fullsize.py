@@ -18,11 +18,19 @@ pytestmark = pytest.mark.gpu
 W = synth.WORKLOADS
 
 
+BENCH_LAUNCH = dict(batch_chunks=64, overlap_copy=1)   # bench.py's defaults
+
+
 def run_full(w: synth.Workload, seed: int, oracle_chunk: int = 64, max_questions: int = 1):
-    """Streams the workload through the GPU library in w.chunk_frames chunks and through
-    the oracle in oracle_chunk chunks (its results do not depend on the chunking)."""
+    """Streams the workload through the GPU library in w.chunk_frames chunks, gathered and
+    overlapped as bench.py does, and through the oracle in oracle_chunk chunks (its results
+    do not depend on the chunking).  Inputs of the last two batches are kept alive, as the
+    overlapped mode asks."""
     assert oracle_chunk % w.chunk_frames == 0
-    gpu = gpu_context(w, max_frames=w.n_frames, max_chunk_frames=w.chunk_frames, max_questions=max_questions)
+    gpu = gpu_context(w, max_frames=w.n_frames, max_chunk_frames=w.chunk_frames, max_questions=max_questions,
+                      **BENCH_LAUNCH)
+    alive = []
+    keep_big = 2 * (BENCH_LAUNCH["batch_chunks"] * w.chunk_frames + oracle_chunk - 1) // oracle_chunk + 1
     ref = orc.OracleMuKV(oracle_config(w))
     stream = synth.SynthStream(w, seed, device="cuda")
     P, tol = w.tokens_per_frame, TOL[w.dtype]
@@ -36,14 +44,23 @@ def run_full(w: synth.Workload, seed: int, oracle_chunk: int = 64, max_questions
         for f0 in range(0, n_big, w.chunk_frames):
             n = min(w.chunk_frames, n_big - f0)
             sl = slice(f0 * P, (f0 + n) * P)
-            fused_gpu.append(gpu.compress_chunk(k[:, :, sl], v[:, :, sl], q[:, sl], want_signals=True)["fused"])
-        torch.cuda.synchronize()
+            # the whole dict is kept: all three signal buffers are written when the batch is launched
+            fused_gpu.append(gpu.compress_chunk(k[:, :, sl], v[:, :, sl], q[:, sl], want_signals=True))
         t0 = time.perf_counter()
         so = ref.compress_chunk(np_view(k), np_view(v), q_last=np_view(q))
         t_orc += time.perf_counter() - t0
-        worst = max(worst, float(np.abs(torch.cat(fused_gpu).cpu().numpy() - so["fused"]).max()))
+        alive.append((k, v, q, fused_gpu, so["fused"]))
         done += n_big
         del k, v, q
+        if len(alive) > keep_big:       # its batch was flushed at least one batch ago
+            _, _, _, fg, fo = alive.pop(0)
+            torch.cuda.synchronize()
+            worst = max(worst, float(np.abs(torch.cat([x["fused"] for x in fg]).cpu().numpy() - fo).max()))
+    gpu.flush()
+    torch.cuda.synchronize()
+    for _, _, _, fg, fo in alive:
+        worst = max(worst, float(np.abs(torch.cat([x["fused"] for x in fg]).cpu().numpy() - fo).max()))
+    alive.clear()
     assert worst <= tol, f"fused score error {worst}"
     st = gpu.state()
     torch.cuda.synchronize()
