@@ -26,9 +26,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # HBM bytes actually moved per algorithmic byte, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs on the 1-hour shape (256 frames per launch), calibrated with a plain copy kernel; the
+# runs on the 1-hour shape (512 frames per launch), calibrated with a plain copy kernel; the
 # summary of those runs is kept under profiles/.
-TRAFFIC_PER_ALGORITHMIC = {"compact": 707.0 / 704.6, "gather": 88.1 / 88.08}
+TRAFFIC_PER_ALGORITHMIC = {"compact": 1409.5 / 1409.2, "copy_freq": 1513.7 / 1512.4, "gather": 88.2 / 88.08}
 
 
 def parse():
@@ -197,10 +197,20 @@ def main():
     per_kernel = {n: (p["ms"] / p["launches"] * 1e3 if p["launches"] else None) for n, p in prof.items()}  # us
 
     b_tok = 2 * Hkv * D * esz                      # K+V bytes of one token in one layer
-    n_launch = prof["compact"]["launches"]
-    compact_bytes = 2 * n_frames * kappa * L * b_tok / n_launch  # read + write of the kept rows, per launch
-    compact_us = per_kernel["compact"]
-    compact_gbs = compact_bytes / (compact_us * 1e-6) / 1e9
+    copy_frame = 2 * kappa * L * b_tok             # kept rows of one frame, read + written
+    freq_frame = P * Hkv * D * esz                 # scoring-layer keys of one frame, read once
+    per_batch = a.batch_chunks * chunk
+    batches = [min(per_batch, n_frames - f0) for f0 in range(0, n_frames, per_batch)]
+    if a.overlap_copy and prof["copy_freq"]["launches"]:
+        # the launch that copies batch i-1's rows and computes batch i's frequency signal
+        dom, dom_kernel = "copy_freq", "copy_freq_kernel"
+        assert prof[dom]["launches"] == len(batches) - 1
+        dom_bytes = sum(copy_frame * batches[i - 1] + freq_frame * batches[i] for i in range(1, len(batches))) / (len(batches) - 1)
+    else:
+        dom, dom_kernel = "compact", "compact_kernel"
+        dom_bytes = copy_frame * n_frames / prof[dom]["launches"]
+    dom_us = per_kernel[dom]
+    dom_gbs = dom_bytes / (dom_us * 1e-6) / 1e9
     gather_bytes = 2 * B * w.k_frame * kappa * L * b_tok
     gather_us = per_kernel["gather"]
     gather_gbs = gather_bytes / (gather_us * 1e-6) / 1e9
@@ -233,10 +243,10 @@ def main():
         "path_hbm": {"algorithmic_bytes_per_token": path_bytes_frame / P, "achieved_GBs": path_gbs,
                      "frac_of_peak": path_gbs / HBM_PEAK_GBS},
         "kernel_us": per_kernel,
-        "roofline": {"kernel": "compact_kernel", "bound": "hbm", "achieved": compact_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": compact_gbs / HBM_PEAK_GBS,
-                     "traffic": compact_bytes * TRAFFIC_PER_ALGORITHMIC["compact"],
-                     "bytes_per_launch": compact_bytes, "us_per_launch": compact_us},
+        "roofline": {"kernel": dom_kernel, "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS,
+                     "traffic": dom_bytes * TRAFFIC_PER_ALGORITHMIC[dom],
+                     "bytes_per_launch": dom_bytes, "us_per_launch": dom_us},
         "roofline_gather": {"kernel": "gather_kv_kernel", "bound": "hbm", "achieved": gather_gbs, "peak": HBM_PEAK_GBS,
                             "unit": "GB/s", "frac": gather_gbs / HBM_PEAK_GBS,
                             "traffic": gather_bytes * TRAFFIC_PER_ALGORITHMIC["gather"],

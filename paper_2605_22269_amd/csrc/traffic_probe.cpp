@@ -2,12 +2,13 @@
 //
 // rocprofv3 --pmc is run on this small program instead of bench.py: it streams pseudo-random
 // bf16 chunks of the 1-hour shape (L=28, Hq=28, Hkv=4, D=128, P=196, keep 24/196) through
-// mukv_compress_chunk in 8-frame chunks gathered 32 at a time, asks one question
+// mukv_compress_chunk in 8-frame chunks gathered 64 at a time with overlap_copy (the launch
+// configuration bench.py times; every chunk has its own resident buffers), asks one question
 // (mukv_retrieve + mukv_gather_kv), and runs the library's plain copy kernel on 1 GiB as the
 // reference whose HBM traffic is known (1 GiB read, 1 GiB written).  Counter values do not
 // depend on the data, only on the access pattern, so the filler is a cheap LCG.
 //
-//   traffic_probe [n_frames=1024]
+//   traffic_probe [n_frames=2048]
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -36,8 +37,8 @@
     } while (0)
 
 int main(int argc, char **argv) {
-    const int L = 28, Hq = 28, Hkv = 4, D = 128, P = 196, chunk = 8, batch = 32;
-    const int n_frames = argc > 1 ? std::atoi(argv[1]) : 1024;
+    const int L = 28, Hq = 28, Hkv = 4, D = 128, P = 196, chunk = 8, batch = 64;
+    const int n_frames = argc > 1 ? std::atoi(argv[1]) : 2048;
     const int n_chunks = n_frames / chunk;
     mukv_config cfg;
     std::memset(&cfg, 0, sizeof cfg);
@@ -58,6 +59,7 @@ int main(int argc, char **argv) {
     cfg.max_questions = 1;
     cfg.batch_chunks = batch;
     cfg.refine_margin = -1.0;
+    cfg.overlap_copy = 1;
     mukv_ctx *ctx = nullptr;
     MK(mukv_create(&cfg, &ctx));
 
