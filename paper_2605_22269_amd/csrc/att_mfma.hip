@@ -2,15 +2,17 @@
 // P <= 208 tokens per frame.
 //
 // One workgroup per (frame, part) where a part is `hpw` consecutive query heads of one KV
-// group.  The frame's keys are staged once in LDS (row stride 272 B, so the 16-byte operand
-// reads of 8 consecutive rows fall into different banks).  The score tile is computed
-// transposed, S^T = K Q^T, with v_mfma_f32_16x16x32_bf16: the A operand is a 16-key x 32-dim
-// slice of K from LDS, the B operand a 32-dim x 16-query slice of Q read straight from global
-// memory (every Q element is used exactly once).  In the accumulator layout a lane owns one
-// query column (lane % 16) and the four key rows 4*(lane/16)..+3 of each 16-key tile, so the
-// softmax statistics of a query are an in-lane reduction over its tiles plus two cross-lane
-// steps, and the per-key column sums can stay in registers across queries, strips and heads;
-// they are reduced over the 16 query lanes once at the end.
+// group.  The frame's keys are staged once in LDS: rows of 256 B whose 16-byte pieces are
+// stored at piece ^ (row % 16), so the 16-byte operand reads of 16 consecutive rows fall into
+// different banks without padding.  The score tile S = Q K^T is computed with
+// v_mfma_f32_16x16x32_bf16: the A operand is a 16-query x 32-dim slice of Q, the B operand a
+// 32-dim x 16-key slice of K from LDS.  Every Q element is used exactly once; a wave's next
+// 16-query strip is fetched by the global-to-LDS load (no registers held while it is in flight)
+// into the wave's own 4 KB buffer, in the same swizzled layout, while the current strip -- already
+// in registers -- is processed.  In the accumulator layout a lane owns one key column
+// (lane % 16) and the four query rows 4*(lane/16)..+3 of each tile, so the softmax statistics of
+// a query row are an in-lane pass over its tiles plus a 16-lane reduction, and the per-key
+// column sums stay in registers (one per tile) across queries, strips and heads.
 //
 // A query strip is 16 queries.  With the causal mask strip s needs key tiles 0..s only, so
 // wave w takes strips w and nt-1-w (nt = ceil(P/16)) to balance the work.
@@ -24,11 +26,15 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int kMaxTiles = 13;  // 13 * 16 = 208 >= P
-constexpr int kLdsRow = 136;   // bf16 elements per LDS key row: 128 + 8 of padding (272 B)
 constexpr int kHeadDim = 128;
+constexpr int kRowB = kHeadDim * 2;   // bytes of one key / query row in LDS
+constexpr int kTileB = 16 * kRowB;    // one 16-row tile: 4 KB
+#define MUKV_GLOBAL_PTR(p) ((const void __attribute__((address_space(1))) *)(p))
+#define MUKV_LDS_PTR(p) ((void __attribute__((address_space(3))) *)(p))
 
 struct JobArgs {
-    const uint16_t *a_base; // this lane's key-operand address in LDS key tile 0
+    const unsigned char *k_lds; // LDS key tile 0
+    int off[4];                 // this lane's byte offset inside a tile for feature slices 0..3
     int q0;                 // first of this lane's four query positions in the frame
     int lr;                 // lane % 16
     int P;
@@ -43,21 +49,19 @@ struct JobArgs {
 // four query rows 4*(lane/16)..+3 of every tile.  Row statistics of the exact softmax are an
 // in-lane pass over the tiles plus a 16-lane DPP reduction; the normalised probabilities of the
 // lane's four rows are added into ONE accumulator per tile (13 registers for the whole frame).
-// `after_mfma` runs once the Q operand registers are free again.
-template <int NTL, typename F>
-__device__ __forceinline__ void strip_job(const JobArgs &ja, const bf16x8 *qv, float *acc, F after_mfma) {
+template <int NTL>
+__device__ __forceinline__ void strip_job(const JobArgs &ja, const bf16x8 *qv, float *acc) {
     f32x4 st[NTL];
 #pragma unroll
     for (int c = 0; c < NTL; ++c) {
         f32x4 d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ja.a_base + c * 16 * kLdsRow + 32 * kk);
+            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ja.k_lds + c * kTileB + ja.off[kk]);
             d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qv[kk], kf, d, 0, 0, 0);
         }
         st[c] = d;
     }
-    after_mfma();
     if (ja.diag || ja.tail) { // only the last tile can need masking
         constexpr int c = NTL - 1;
         const int j = 16 * c + ja.lr;
@@ -99,15 +103,17 @@ __global__ __launch_bounds__(448) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                                                        int64_t q_sh, int64_t q_st, int64_t k_sh, int64_t k_st,
                                                        int P, int nt, int G, int hpw, int causal, int pair, int n_split,
                                                        float scale_log2e, int n_part, float *__restrict__ out) {
+    // LDS: key tiles [nt][16 rows][256 B], then one 4 KB query buffer per wave.  After the last
+    // job the key region is reused for the per-wave column sums.
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    uint16_t *Ks = reinterpret_cast<uint16_t *>(smem_raw);                           // [nt*16][kLdsRow]
-    float *red = reinterpret_cast<float *>(smem_raw + (size_t)nt * 16 * kLdsRow * 2); // [waves][nt*16]
+    unsigned char *Ks = smem_raw;
     const int f = blockIdx.x, part = blockIdx.y / n_split, sp = blockIdx.y - part * n_split;
     const int h0 = part * hpw, g = h0 / G;
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6); // wave-uniform: strip choices become scalar branches
     const int n_threads = blockDim.x;
     const int lr = lane & 15, lg = lane >> 4;
+    unsigned char *Qs = smem_raw + (size_t)nt * kTileB + (size_t)w * kTileB;
 
     // pair = 1: wave w takes strips w and nt-1-w (balanced under the causal mask, for throughput).
     // pair = 0: one strip per wave and the strips of a (frame, part) split over n_split workgroups
@@ -121,20 +127,27 @@ __global__ __launch_bounds__(448) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     if (!pair && causal) k_tiles = (sp + 1) * wps < nt ? (sp + 1) * wps : nt;
     const int slot = find_slot(map, f);
     const int lf = f - map.fstart[slot];
-    const uint16_t *qf = reinterpret_cast<const uint16_t *>(qtab.p[slot]) + ((int64_t)lf * P) * q_st + 8 * lg;
-    // B operand of one (head, strip): 4 x 16 bytes per lane, rows past P clamped (masked later)
-    auto load_q = [&](int h, int s, bf16x8 *dst) {
-        const int qi = 16 * s + lr;
-        const uint16_t *qp = qf + (int64_t)h * q_sh + (int64_t)(qi < P ? qi : P - 1) * q_st;
+    const uint16_t *qf = reinterpret_cast<const uint16_t *>(qtab.p[slot]) + ((int64_t)lf * P) * q_st;
+    // Request of one (head, strip) into the wave's query buffer: four 1 KB instructions, lane i of
+    // instruction j fills 16-byte slot 64*j + i = (row 4*j + i/16, position i%16), which holds
+    // piece position ^ row of that row.  Rows past P are clamped (masked later).
+    auto request_q = [&](int h, int s) {
+        // wave-uniform 64-bit base + a 32-bit per-lane byte offset (a frame's queries of one head
+        // span far less than 4 GB)
+        const unsigned char *base = reinterpret_cast<const unsigned char *>(qf + (int64_t)h * q_sh);
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) dst[kk] = *reinterpret_cast<const bf16x8 *>(qp + 32 * kk);
+        for (int j = 0; j < 4; ++j) {
+            const int row = 4 * j + lg;
+            const int qi = 16 * s + row;
+            const unsigned off = ((unsigned)((qi < P ? qi : P - 1) * (int)q_st) + (unsigned)((lr ^ row) << 3)) * 2u;
+            __builtin_amdgcn_global_load_lds(MUKV_GLOBAL_PTR(base + off), MUKV_LDS_PTR(Qs + 1024 * j), 16, 0, 0);
+        }
     };
     const int n_jobs = active ? hpw * n_strips : 0; // (head, strip) pairs of this wave, strip fastest
-    bf16x8 qv[4];
-    load_q(h0, active ? sA : 0, qv); // job 0: in flight while K is staged
+    if (n_jobs > 0) request_q(h0, sA);              // job 0: in flight while K is staged
 
     // stage K of (frame, KV head) in LDS; rows past P are zero.  Loads are unconditional on a
-    // clamped row and issued in batches of 4 before the LDS stores.
+    // clamped row and issued in batches of 8 before the LDS stores.
     const uint16_t *kf = reinterpret_cast<const uint16_t *>(ktab.p[slot]) + k_off + (int64_t)g * k_sh + (int64_t)lf * P * k_st;
     const int n_units = k_tiles * 16 * 16;
     for (int i0 = tid; i0 < n_units; i0 += 8 * n_threads) {
@@ -150,8 +163,9 @@ __global__ __launch_bounds__(448) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         for (int u = 0; u < 8; ++u) {
             const int idx = i0 + u * n_threads;
             if (idx < n_units) {
-                const int row = idx >> 4;
-                *reinterpret_cast<u32x4 *>(Ks + row * kLdsRow + (idx & 15) * 8) = row < P ? val[u] : u32x4{0u, 0u, 0u, 0u};
+                const int row = idx >> 4, piece = idx & 15;
+                *reinterpret_cast<u32x4 *>(Ks + row * kRowB + ((piece ^ (row & 15)) << 4)) =
+                    row < P ? val[u] : u32x4{0u, 0u, 0u, 0u};
             }
         }
     }
@@ -161,30 +175,35 @@ __global__ __launch_bounds__(448) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 #pragma unroll
     for (int c = 0; c < kMaxTiles; ++c) acc[c] = 0.f;
 
-    const uint16_t *a_base = Ks + lr * kLdsRow + 8 * lg;
+    JobArgs ja;
+    ja.k_lds = Ks;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) ja.off[kk] = lr * kRowB + (((4 * kk + lg) ^ lr) << 4);
+    ja.lr = lr;
+    ja.P = P;
+    ja.diag = causal != 0;
+    ja.scale_log2e = scale_log2e;
     const bool tail = (P & 15) != 0;
     for (int job = 0; job < n_jobs; ++job) {
         const int hh = job / n_strips, si = job - hh * n_strips;
         const int s = si ? sB : sA;
         const int ntl = __builtin_amdgcn_readfirstlane(causal ? s + 1 : nt); // key tiles this strip sees
-        JobArgs ja;
-        ja.a_base = a_base;
         ja.q0 = 16 * s + 4 * lg;
-        ja.lr = lr;
-        ja.P = P;
-        ja.diag = causal != 0;
         ja.tail = tail && ntl == nt;
-        ja.scale_log2e = scale_log2e;
-        // as soon as the MFMAs of this job are done its Q registers take the next job's Q; the
-        // softmax below and the other resident waves cover the load latency
-        auto next_q = [&]() {
-            if (job + 1 < n_jobs) {
-                const int hn = (job + 1) / n_strips, sn = (job + 1) - hn * n_strips;
-                load_q(h0 + hn, sn ? sB : sA, qv);
-            }
-        };
+        // this job's queries have arrived in the wave's buffer: move them to registers, and once
+        // they are there let the buffer take the next job's queries, which then have this whole
+        // job (and the other resident waves) to arrive
+        bf16x8 qv[4];
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) qv[kk] = *reinterpret_cast<const bf16x8 *>(Qs + ja.off[kk]);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (job + 1 < n_jobs) {
+            const int hn = (job + 1) / n_strips, sn = (job + 1) - hn * n_strips;
+            request_q(h0 + hn, sn ? sB : sA);
+        }
         switch (ntl) {
-#define MUKV_JOB_CASE(N) case N: strip_job<N>(ja, qv, acc, next_q); break;
+#define MUKV_JOB_CASE(N) case N: strip_job<N>(ja, qv, acc); break;
             MUKV_JOB_CASE(1) MUKV_JOB_CASE(2) MUKV_JOB_CASE(3) MUKV_JOB_CASE(4) MUKV_JOB_CASE(5)
             MUKV_JOB_CASE(6) MUKV_JOB_CASE(7) MUKV_JOB_CASE(8) MUKV_JOB_CASE(9) MUKV_JOB_CASE(10)
             MUKV_JOB_CASE(11) MUKV_JOB_CASE(12) MUKV_JOB_CASE(13)
@@ -192,7 +211,10 @@ __global__ __launch_bounds__(448) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         default: break;
         }
     }
-    // column sums: add the four lane groups (the other query rows), then the waves in a fixed order
+    // column sums: add the four lane groups (the other query rows), then the waves in a fixed
+    // order; the key tiles are no longer needed and give room for the per-wave sums
+    __syncthreads();
+    float *red = reinterpret_cast<float *>(smem_raw); // [waves][nt*16]
     const int ld = nt * 16;
 #pragma unroll
     for (int c = 0; c < kMaxTiles; ++c) {
@@ -226,8 +248,16 @@ hipError_t launch_att_mfma(const Ctx &c, const ChunkArgs &a, float *out, int *n_
     const int n_split = (!pair && nt > 7) ? 2 : 1;
     const int waves = pair ? (nt + 1) / 2 : (nt + n_split - 1) / n_split;
     *n_part = (Hq / hpw) * n_split;
-    const size_t lds = (size_t)nt * 16 * kLdsRow * 2 + (size_t)waves * nt * 16 * sizeof(float);
+    const size_t lds = (size_t)(nt + waves) * kTileB; // key tiles + one query buffer per wave (>= the per-wave sums)
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)c.cfg.head_dim);
+    static bool attr_set = false; // more than 64 KB of dynamic LDS has to be asked for once
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&att_mfma_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 (kMaxTiles + (kMaxTiles + 1) / 2) * kTileB);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
     hipLaunchKernelGGL(att_mfma_kernel, dim3(a.n_frames, *n_part), dim3(waves * 64), lds, st, a.q, a.k, a.map,
                        (int64_t)c.ls * a.kv_sl, a.q_sh, a.q_st, a.kv_sh, a.kv_st, P, nt, G, hpw, c.cfg.causal, pair,
                        n_split, scale_log2e, *n_part, out);
