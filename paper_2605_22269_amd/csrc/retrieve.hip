@@ -143,7 +143,8 @@ __global__ __launch_bounds__(256) void score_blocks_kernel(ScoreArgs a) {
                 const int c = lane + 64 * t;
                 const int cc = c < C ? c : C - 1; // row[t] is 0 past C
 #pragma unroll
-                for (int j = 0; j < 4; ++j) dot[j] += (double)row[t] * qb[j][cc];
+                for (int j = 0; j < 4; ++j)
+                    if (b0 + j < a.B) dot[j] += (double)row[t] * qb[j][cc]; // uniform
             }
         }
 #pragma unroll
@@ -159,6 +160,84 @@ __global__ __launch_bounds__(256) void score_blocks_kernel(ScoreArgs a) {
                 a.s_seg[(int64_t)b * a.ld_seg + idx] = sc;
             else
                 a.s_frm[(int64_t)b * a.ld_frm + idx] = sc;
+        }
+    }
+}
+
+// Eq. 7 when many questions are asked at once: the scores are a [keys x C] x [C x questions]
+// product, done on the fp64 matrix cores.  A wave owns a tile of 16 keys x 16 questions and
+// walks the channels 16 at a time: lane l holds channels c0 + 4*(l/16) .. +3 of key l%16 (one
+// 16-byte load) and of question l%16 (two 16-byte loads)
+// and issues four v_mfma_f64_16x16x4_f64, element e of the lane's four channels being reduction
+// index l/16 of the e-th.  Operand / result layout (checked on the device): A[row = l%16][k = l/16],
+// B[k = l/16][col = l%16], D register r of lane l = D[row = 4*r + l/16][col = l%16].
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+typedef double f64x2 __attribute__((ext_vector_type(2)));
+// Key of a segment cut by the question's timestamp, from the exact per-frame sums of its visible
+// frames (the wave-per-key kernel does this inline; the matrix-core kernel reads the result).
+__global__ __launch_bounds__(256) void seg_tail_kernel(ScoreArgs a) {
+    const int f0 = (a.ns - 1) * a.F;
+    const double den = (double)(a.nv - f0) * (double)a.kappa;
+    for (int c = blockIdx.x * 256 + threadIdx.x; c < a.C; c += gridDim.x * 256) {
+        double s = 0.0;
+        for (int f = f0; f < a.nv; ++f) s += a.fsum[(int64_t)f * a.C + c];
+        a.seg_tail[c] = (float)(s / den);
+    }
+}
+
+// grid.x: the frame tiles, then the segment tiles (16 keys each)
+__global__ __launch_bounds__(256) void score_blocks_mfma_kernel(ScoreArgs a) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lr = lane & 15, kq = lane >> 4;
+    const int C = a.C;
+    const int n_ft = (a.nv + 15) / 16;
+    const bool is_seg = (int)blockIdx.x >= n_ft;
+    const int row0 = (is_seg ? (int)blockIdx.x - n_ft : (int)blockIdx.x) * 16;
+    const int n_rows = is_seg ? a.ns : a.nv;
+    const int rw_in = row0 + lr < n_rows ? row0 + lr : n_rows - 1;
+    const float *kp = (is_seg ? ((a.tail_cut && rw_in == a.ns - 1) ? a.seg_tail : a.rep_seg + (int64_t)rw_in * C)
+                              : a.rep_frame + (int64_t)rw_in * C) + 4 * kq;
+    double *s_out = is_seg ? a.s_seg : a.s_frm;
+    const int64_t ld_out = is_seg ? a.ld_seg : a.ld_frm;
+    for (int q0 = 16 * wave; q0 < a.B; q0 += 64) {
+        const int bq = q0 + lr < a.B ? q0 + lr : a.B - 1;
+        const double *qp = a.qbar + (int64_t)bq * C + 4 * kq;
+        f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+        double rr = 0.0;
+        for (int c0 = 0; c0 < C; c0 += 64) { // four steps of 16 channels, their loads issued together
+            f32x4 kv[4];
+            f64x2 qlo[4], qhi[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + 16 * u < C ? c0 + 16 * u : C - 16;
+                kv[u] = *reinterpret_cast<const f32x4 *>(kp + c);
+                qlo[u] = *reinterpret_cast<const f64x2 *>(qp + c);
+                qhi[u] = *reinterpret_cast<const f64x2 *>(qp + c + 2);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (c0 + 16 * u < C) { // uniform
+                    const double k0 = (double)kv[u][0], k1 = (double)kv[u][1], k2 = (double)kv[u][2], k3 = (double)kv[u][3];
+                    rr += (k0 * k0 + k1 * k1) + (k2 * k2 + k3 * k3);
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(k0, qlo[u][0], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(k1, qlo[u][1], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(k2, qhi[u][0], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(k3, qhi[u][1], acc, 0, 0, 0);
+                }
+            }
+        }
+        // |r|^2 of key lr: add the four lanes that hold its channels
+        rr += lane_xor<16>(rr);
+        rr += lane_xor<32>(rr);
+        double qn = 0.0;
+        for (int g = 0; g < a.Hkv; ++g) qn += a.qq[(int64_t)bq * a.Hkv + g];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int rw = 4 * r + kq; // tile row of result register r
+            const double rr_row = __shfl(rr, rw);
+            double sc = 0.0;
+            if (rr_row > 0.0 && qn > 0.0) sc = acc[r] / (sqrt(qn) * sqrt((double)a.G * rr_row));
+            if (row0 + rw < n_rows && q0 + lr < a.B) s_out[(int64_t)(q0 + lr) * ld_out + row0 + rw] = sc;
         }
     }
 }
@@ -760,7 +839,13 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
         s.ld_frm = c.cfg.max_frames;
         s.ld_seg = c.max_segments;
         ProfScope ps(c, MUKV_K_SCORE, st);
-        hipLaunchKernelGGL(score_blocks_kernel, dim3((a.nv + a.ns + 3) / 4), dim3(256), 0, st, s);
+        // many questions: the scores are a small matrix product for the fp64 matrix cores
+        if (a.B >= 16) {
+            if (tail_cut) hipLaunchKernelGGL(seg_tail_kernel, dim3((s.C + 255) / 256), dim3(256), 0, st, s);
+            hipLaunchKernelGGL(score_blocks_mfma_kernel, dim3((a.nv + 15) / 16 + (a.ns + 15) / 16), dim3(256), 0, st, s);
+        } else {
+            hipLaunchKernelGGL(score_blocks_kernel, dim3((a.nv + a.ns + 3) / 4), dim3(256), 0, st, s);
+        }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     RerankArgs r;

@@ -88,6 +88,22 @@ def test_retrieval_with_many_equal_scores(distinct):
     p.close()
 
 
+@pytest.mark.parametrize("name,frames", [("7b", 41), ("tiny", 100), ("72b", 21)])
+def test_batches_of_sixteen_or_more_questions(name, frames):
+    # from 16 questions on, the frame scores come from the fp64 matrix-core kernel: ragged
+    # frame and question counts, a timestamp that cuts a segment, every retrieval mode
+    w = W[name].scaled(n_frames=frames, n_layers=2, n_questions=37)
+    p = Pair(w, seed=95, chunk=8)
+    p.ingest()
+    p.check_compress()
+    for nq in (16, 37):
+        qs = questions_for(w, [5 + (7 * i) % 40 for i in range(nq)], 700)
+        p.check_retrieve(qs, mk.MUKV_SEMI, 2, 6, 0.3)
+        p.check_retrieve(qs, mk.MUKV_HIER, 2, 6, 0.3, n_visible=frames - 3)
+        p.check_retrieve(qs, mk.MUKV_PARALLEL, 2, 6, 0.3, n_visible=9)
+    p.close()
+
+
 # ------------------------------------------------------ 72B shape, short stream -----------
 def test_72b_shape_short_stream():
     w = W["72b"].scaled(n_frames=40, n_layers=3)   # kappa 8 of 64; one full 32-frame segment + 8
