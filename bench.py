@@ -31,6 +31,16 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 TRAFFIC_PER_ALGORITHMIC = {"compact": 1409.5 / 1409.2, "copy_freq": 1513.7 / 1512.4, "gather": 88.2 / 88.08}
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown CPU"
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,8 +58,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-frames", type=int, default=1024)
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
-                    help="also run the library's plain copy kernel once on this many MiB (reference for rocprofv3 "
-                         "traffic counters)")
+                    help="size in MiB of the plain-copy reference run (default 1024)")
     ap.add_argument("--seed", type=int, default=2605)
     return ap.parse_args()
 
@@ -282,13 +291,40 @@ def main():
             "gather_bytes": Bq * gather_bytes, "path_GBs": Bq * gather_bytes / (ms64 * 1e-3) / 1e9}
         del g64
 
-    if a.calibrate_copy_mib:
-        nb = a.calibrate_copy_mib << 20
-        src = torch.empty(nb, dtype=torch.uint8, device=dev).random_(0, 255)
-        dst = torch.empty_like(src)
-        mk.mukv_plain_copy(dst.data_ptr(), src.data_ptr(), nb, torch.cuda.current_stream().cuda_stream)
-        torch.cuda.synchronize()
-        res["calibration_copy_bytes"] = nb
+    # ---- what a plain copy reaches on this machine: the library's 16-byte streaming copy on 1 GiB ----
+    nb = (a.calibrate_copy_mib or 1024) << 20
+    src = torch.empty(nb, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    cur = torch.cuda.current_stream().cuda_stream
+    mk.mukv_plain_copy(dst.data_ptr(), src.data_ptr(), nb, cur)
+    copy_ms = timed(lambda: mk.mukv_plain_copy(dst.data_ptr(), src.data_ptr(), nb, cur), 10)
+    res["plain_copy"] = {"bytes_read_plus_written": 2 * nb, "ms": copy_ms, "GBs": 2 * nb / (copy_ms * 1e-3) / 1e9,
+                         "frac_of_peak": 2 * nb / (copy_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    del src, dst
+
+    # ---- the same kernels fed by single calls of 512 frames (no gathering of small chunks) -----
+    if a.workload == "hour" and not a.frames:
+        nbig = 512
+        kb = torch.cat([ks[c] for c in range(nbig // chunk)], dim=2)
+        vb = torch.cat([vs[c] for c in range(nbig // chunk)], dim=2)
+        qb = torch.cat([qs[c] for c in range(nbig // chunk)], dim=1)
+        big = mk.MuKV(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, tokens_per_frame=P,
+                      frames_per_segment=w.frames_per_segment, superpatches_per_frame=w.superpatches_per_frame,
+                      dtype=w.torch_dtype, keep_ratio=w.keep_ratio, alpha=w.alpha, max_frames=7 * nbig,
+                      max_chunk_frames=nbig, max_questions=1, batch_chunks=1, overlap_copy=a.overlap_copy)
+
+        def big_calls():
+            big.reset()
+            for _ in range(7):
+                big.compress_chunk(kb, vb, qb)
+            big.flush()
+
+        big_calls()
+        big_ms = timed(big_calls, 3)
+        res["compress_single_calls_of_512_frames"] = {"calls": 7, "ms": big_ms,
+                                                      "tokens_per_s": 7 * nbig * P / (big_ms * 1e-3)}
+        big.close()
+        del kb, vb, qb
 
     # ---- the oracle on the host cores, on a bounded sample of the same stream -------------
     if not a.no_cpu_baseline:
@@ -307,7 +343,7 @@ def main():
         res["cpu_baseline"] = {"value": ref.n_frames * P / t_cpu, "unit": "visual tokens/s",
                                "cores": int(orc.lib().orc_num_threads()), "kind": "oracle",
                                "sample": f"first {ref.n_frames} frames of the same stream through the oracle's "
-                                         f"compress_chunk ({t_cpu:.1f} s)"}
+                                         f"compress_chunk ({t_cpu:.1f} s) on {cpu_model()}"}
     ctx.close()
     print(json.dumps(res))
 
