@@ -78,7 +78,11 @@ __device__ __forceinline__ void fft_stages(R (&zr)[GH], R (&zi)[GH], const R *sg
         fft_stages<N, S + 1, LOG, R, GH>(zr, zi, sg, twr, twi);
     }
 }
-constexpr int kRescoreSlots = 1; // grid.x of the fp64 re-scoring kernels; they loop over the list
+// grid.x of the fp64 re-scoring kernels: listed frames handled side by side (the kernels loop
+// over the list from their slot).  The attention kernel's workgroups hold ~100 KB of LDS each,
+// so it gets fewer slots: its idle ones still have to be placed before they can leave.
+constexpr int kRescoreSlots = 4;
+constexpr int kRescoreSlotsAtt = 2;
 
 // Work of workgroup (bx, by) of a (gx, kFreqBlocksPerFrame) grid.
 template <typename T, typename R, int D>
@@ -826,7 +830,7 @@ static hipError_t launch_att_generic(const Ctx &c, const ChunkArgs &a, bool list
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((att_generic_kernel<T, R>), dim3(listed ? kRescoreSlots : a.n_frames, c.cfg.n_q_heads, qsplit),
+    hipLaunchKernelGGL((att_generic_kernel<T, R>), dim3(listed ? kRescoreSlotsAtt : a.n_frames, c.cfg.n_q_heads, qsplit),
                        dim3(256), lds, st, a.q, a.k, a.map, (int64_t)c.ls * a.kv_sl, a.q_sh, a.q_st, a.kv_sh, a.kv_st, P,
                        D, c.group, c.cfg.n_q_heads, c.cfg.causal, q_per_block, listed ? c.flag_list[a.parity] : nullptr,
                        listed ? c.flag_count + a.parity : nullptr, out);
