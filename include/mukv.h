@@ -21,12 +21,16 @@
  *  - "device" pointers are HIP device pointers valid on the context's device;
  *    "host" pointers are ordinary process memory.  The caller owns every buffer
  *    it passes in; the context owns the cache.  Inputs may be reused as soon as
- *    the stream has passed the call.
+ *    the stream has passed the call (batch_chunks and overlap_copy lengthen
+ *    that for mukv_compress_chunk: see there).
  *  - Work is enqueued on the hipStream_t passed as `stream` (void*, NULL = the
  *    default stream) and is never synchronised by the library.  Calls on one
  *    context must be issued in stream order; the context is not thread-safe.
  *  - After mukv_create no device memory is allocated or freed until
  *    mukv_destroy.
+ *  - MUKV_ERR_HIP from a call that launches kernels leaves the cache in an
+ *    unspecified state: destroy the context.  Every other error leaves it as
+ *    it was.
  *  - Inputs must be finite.  Non-finite values give unspecified selections.
  */
 #ifndef MUKV_H

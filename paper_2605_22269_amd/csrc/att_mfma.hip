@@ -250,14 +250,10 @@ hipError_t launch_att_mfma(const Ctx &c, const ChunkArgs &a, float *out, int *n_
     *n_part = (Hq / hpw) * n_split;
     const size_t lds = (size_t)(nt + waves) * kTileB; // key tiles + one query buffer per wave (>= the per-wave sums)
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)c.cfg.head_dim);
-    static bool attr_set = false; // more than 64 KB of dynamic LDS has to be asked for once
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&att_mfma_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                 (kMaxTiles + (kMaxTiles + 1) / 2) * kTileB);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static bool lds_ok[kMaxDevices];
+    const hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(&att_mfma_kernel),
+                                            (size_t)(kMaxTiles + (kMaxTiles + 1) / 2) * kTileB, c.cfg.device_id, lds_ok);
+    if (ea != hipSuccess) return ea;
     hipLaunchKernelGGL(att_mfma_kernel, dim3(a.n_frames, *n_part), dim3(waves * 64), lds, st, a.q, a.k, a.map,
                        (int64_t)c.ls * a.kv_sl, a.q_sh, a.q_st, a.kv_sh, a.kv_st, P, nt, G, hpw, c.cfg.causal, pair,
                        n_split, scale_log2e, *n_part, out);

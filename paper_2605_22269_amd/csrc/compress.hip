@@ -823,13 +823,10 @@ static hipError_t launch_att_generic(const Ctx &c, const ChunkArgs &a, bool list
     const int qsplit = (P + q_per_block - 1) / q_per_block;
     *n_part = c.cfg.n_q_heads * qsplit;
     const size_t lds = att_generic_lds_bytes(P, D, sizeof(R));
-    static bool attr_set = false; // per instantiation
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&att_generic_kernel<T, R>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static bool lds_ok[kMaxDevices]; // per instantiation
+    const hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(&att_generic_kernel<T, R>), 160 * 1024,
+                                            c.cfg.device_id, lds_ok);
+    if (ea != hipSuccess) return ea;
     hipLaunchKernelGGL((att_generic_kernel<T, R>), dim3(listed ? kRescoreSlotsAtt : a.n_frames, c.cfg.n_q_heads, qsplit),
                        dim3(256), lds, st, a.q, a.k, a.map, (int64_t)c.ls * a.kv_sl, a.q_sh, a.q_st, a.kv_sh, a.kv_st, P,
                        D, c.group, c.cfg.n_q_heads, c.cfg.causal, q_per_block, listed ? c.flag_list[a.parity] : nullptr,

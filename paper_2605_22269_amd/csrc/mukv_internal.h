@@ -161,6 +161,17 @@ struct ProfScope {
 
 hipError_t launch_plain_copy(void *dst, const void *src, int64_t bytes, hipStream_t st);
 
+// Kernels that use more than 64 KB of dynamic LDS have to ask for it once per device; `done` is
+// the caller's per-kernel table of devices already served.
+constexpr int kMaxDevices = 64;
+inline hipError_t allow_dynamic_lds(const void *kernel, size_t bytes, int device, bool (&done)[kMaxDevices]) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    if (done[device]) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) done[device] = true;
+    return e;
+}
+
 // True when the matrix-core attention kernel covers this configuration.
 bool att_mfma_supported(const mukv_config &c);
 

@@ -875,13 +875,10 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
     int n_max = a.nv > a.ns ? a.nv : a.ns;
     if (n_max < 2 * kMaxCand) n_max = 2 * kMaxCand;
     r.cache_cap = n_max < kMaxCache ? n_max : kMaxCache;
-    static bool attr_set = false;
-    if (!attr_set) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&select_rerank_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kMaxCache * 8);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static bool lds_ok[kMaxDevices];
+    if ((e = allow_dynamic_lds(reinterpret_cast<const void *>(&select_rerank_kernel), (size_t)kMaxCache * 8,
+                               c.cfg.device_id, lds_ok)) != hipSuccess)
+        return e;
     ProfScope ps(c, MUKV_K_RERANK, st);
     hipLaunchKernelGGL(select_rerank_kernel, dim3(a.B), dim3(kSelThreads), (size_t)r.cache_cap * 8, st, r);
     return hipGetLastError();
