@@ -56,7 +56,7 @@ def parse():
                     help="1: the copy of a batch's kept rows shares a launch with the next batch's frequency "
                          "kernel (mukv_config.overlap_copy; the whole stream is resident, so inputs outlive the copies)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-frames", type=int, default=1024)
+    ap.add_argument("--cpu-sample-frames", type=int, default=2048)
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="size in MiB of the plain-copy reference run (default 1024)")
     ap.add_argument("--seed", type=int, default=2605)

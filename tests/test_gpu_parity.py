@@ -406,3 +406,84 @@ def test_overlapped_copy_retrieve_without_flush_or_sync():
         p.gpu.compress_chunk(k, v, q)
     p.check_retrieve(questions_for(w, [32], 520), mk.MUKV_SEMI, 1, 6, 0.3)
     p.close()
+
+
+# ------------------------------------------------------------- HIP graph replay, reset --------
+@pytest.mark.parametrize("overlap,margin", [(1, 10.0), (1, -1.0), (0, 10.0)])
+def test_graph_replay_matches_the_oracle_every_time(overlap, margin):
+    # the whole path (gathered chunks, re-scoring chain on the side stream, put-off copy,
+    # retrieve, gather) captured once and replayed: every replay, with eager work and host
+    # synchronisation between them, must leave the oracle's results
+    w = W["7b"].scaled(n_frames=28, n_layers=2, n_questions=1)
+    p = Pair(w, seed=97, chunk=4, gpu_kw={"batch_chunks": 3, "overlap_copy": overlap, "refine_margin": margin})
+    chunks = []
+    for _ in range(7):
+        k, v, q = p.stream.next_chunk(4)
+        p.orc.compress_chunk(np_view(k), np_view(v), q_last=np_view(q))
+        chunks.append((k.cuda(), v.cuda(), q.cuda()))
+    qt = synth.random_question(w, 24, 530)
+    qd = qt.cuda()
+    offs = torch.tensor([0, 24], dtype=torch.int32, device="cuda")
+    r_out = {"seg_idx": torch.empty(1, 2, dtype=torch.int32, device="cuda"),
+             "seg_score": torch.empty(1, 2, dtype=torch.float32, device="cuda"),
+             "frame_idx": torch.empty(1, 6, dtype=torch.int32, device="cuda"),
+             "frame_score": torch.empty(1, 6, dtype=torch.float32, device="cuda")}
+    shape = (1, w.n_layers, w.n_kv_heads, 6 * p.gpu.kappa, w.head_dim)
+    g_out = (torch.empty(shape, dtype=w.torch_dtype, device="cuda"), torch.empty(shape, dtype=w.torch_dtype, device="cuda"),
+             torch.empty(1, dtype=torch.int32, device="cuda"))
+
+    def step(chs):
+        p.gpu.reset()
+        for k, v, q in chs:
+            p.gpu.compress_chunk(k, v, q)
+        p.gpu.retrieve(qd, offs, mode=mk.MUKV_SEMI, k_seg=2, k_frame=6, lambda_frame=0.3, out=r_out)
+        p.gpu.gather_kv(r_out["frame_idx"], out=g_out)
+
+    junk_stream = synth.SynthStream(w, 197, device="cuda")
+    junk = [junk_stream.next_chunk(4) for _ in range(7)]
+    step(chunks)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(chunks)
+    torch.cuda.synchronize()
+    want = p.orc.retrieve(np_view(qt), orc.RetrieveParams(orc.SEMI, 2, 6, 0.3))
+    ko, vo, n_tok = p.orc.gather(want["frame_idx"])
+    for replay in range(3):
+        step(junk)                           # eager work between the replays: another stream through
+        for t in r_out.values():             # the same context, so cache and outputs hold other values
+            t.fill_(-7)
+        g_out[0].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        st = p.gpu.state()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(st["kept_idx"].cpu().numpy(), p.orc.kept, err_msg=f"replay {replay}")
+        np.testing.assert_array_equal(st["rep_seg_k"].cpu().numpy(), p.orc.seg_reps(which="k").astype(np.float32))
+        np.testing.assert_array_equal(r_out["frame_idx"][0].cpu().numpy(), want["frame_idx"])
+        np.testing.assert_array_equal(r_out["seg_idx"][0].cpu().numpy(), want["seg_idx"])
+        assert int(g_out[2][0]) == n_tok
+        np.testing.assert_array_equal(np_view(g_out[0][0]), ko)
+        np.testing.assert_array_equal(np_view(g_out[1][0]), vo)
+        if margin > 1.0:
+            assert int(st["refined"].sum()) == 28
+    p.close()
+
+
+def test_reset_drops_a_copy_that_was_put_off():
+    # a stream is abandoned with its last batch's copy (and re-scoring) still put off; the next
+    # stream through the same context must come out as if the context were new
+    w = W["7b"].scaled(n_frames=12, n_layers=2)
+    p = Pair(w, seed=98, chunk=4, gpu_kw={"batch_chunks": 1, "overlap_copy": 1, "refine_margin": 10.0})
+    junk = synth.SynthStream(w, 99, device="cpu")
+    for _ in range(2):
+        k, v, q = junk.next_chunk(4)
+        kd, vd, qd = k.cuda(), v.cuda(), q.cuda()
+        p.keep_alive += [kd, vd, qd]
+        p.gpu.compress_chunk(kd, vd, qd)
+    p.gpu.reset()
+    p.ingest()
+    st = p.check_compress()
+    assert int(st["refined"].sum()) == 12
+    p.close()
