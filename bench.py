@@ -261,6 +261,14 @@ def main():
                             "traffic": gather_bytes * TRAFFIC_PER_ALGORITHMIC["gather"],
                             "bytes_per_launch": gather_bytes, "us_per_launch": gather_us},
         "setup_s": {"generate_stream": t_gen},
+        # context only, not comparable: end to end including the LLM's answer decoding
+        "paper_context": {"source": "real-deployment table of the paper (Sec. 4)", "hardware": "1x NVIDIA A5000 24 GB",
+                          "seconds_per_question_incl_llm_decode": {"ReKV": 0.92, "MuKV uncompressed": 0.72,
+                                                                   "MuKV compress 2/3 (default)": 0.65,
+                                                                   "MuKV compress 3/4": 0.59},
+                          "cache_GB_per_hour_of_video": {"ReKV": 4.00, "MuKV compress 2/3": 1.23},
+                          "note": "the paper reports no compression throughput and no retrieval or KV-loading "
+                                  "latency in isolation, hence vs_baseline is null"},
     }
 
     # ---- the same cache under 64 concurrent questions of 16..64 tokens (one batched call each) --
