@@ -487,3 +487,42 @@ def test_reset_drops_a_copy_that_was_put_off():
     st = p.check_compress()
     assert int(st["refined"].sum()) == 12
     p.close()
+
+
+# ----------------------------------------------------------- seeded sweep of small shapes ------
+def _random_case(i):
+    rng = np.random.default_rng(4000 + i)
+    hkv = int(rng.choice([1, 2, 4, 8]))
+    group = int(rng.choice([1, 2, 7]))
+    d = int(rng.choice([16, 32, 64, 128]))
+    while hkv * d > 1024:
+        hkv //= 2
+    dtype = str(rng.choice(["bf16", "f32"]))
+    p_tok = int(rng.integers(3, 257)) if i % 3 else int(rng.choice([16, 64, 196, 208, 256]))
+    s_pat = int(rng.integers(1, min(p_tok, 6) + 1))
+    rho = float(rng.choice([0.1, 0.25, 0.5, 0.9, 1.0]))
+    if int(np.floor(rho * p_tok + 1e-9)) < 1:
+        rho = 1.0
+    w = synth.Workload(f"case{i}", int(rng.integers(1, 4)), hkv * group, hkv, d, dtype, int(rng.integers(3, 30)), p_tok,
+                       int(rng.choice([1, 3, 8])), superpatches_per_frame=s_pat, chunk_frames=int(rng.integers(1, 7)),
+                       spike_prob=float(rng.choice([0.0, 0.1])), keep_ratio=rho, alpha=float(rng.choice([0.0, 0.3, 0.7, 1.0])),
+                       lambda_frame=float(rng.choice([0.0, 0.3, 0.8])), k_seg=int(rng.integers(1, 5)),
+                       k_frame=int(rng.integers(1, 9)), question_tokens=int(rng.integers(1, 40)), n_questions=3)
+    kw = {"causal": bool(rng.integers(0, 2)), "batch_chunks": int(rng.choice([1, 3])), "overlap_copy": int(rng.integers(0, 2)),
+          "refine_margin": float(rng.choice([-1.0, 0.0, 10.0]))}
+    return w, kw
+
+
+@pytest.mark.parametrize("i", range(48))
+def test_seeded_sweep_of_small_shapes(i):
+    # shapes nobody picked by hand: head counts and groups, every head size, odd token counts,
+    # super-patch counts, keep ratios, signal mixes, masks, chunkings, launch modes
+    w, kw = _random_case(i)
+    p = Pair(w, seed=5000 + i, chunk=w.chunk_frames, gpu_kw=dict(kw), orc_kw={"causal": kw["causal"]})
+    p.ingest()
+    p.check_compress()
+    qs = questions_for(w, [w.question_tokens, 1, 7], 800 + i)
+    for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
+        p.check_retrieve(qs, mode, w.k_seg, w.k_frame, w.lambda_frame)
+    p.check_retrieve(qs, mk.MUKV_SEMI, w.k_seg, w.k_frame, w.lambda_frame, n_visible=max(1, w.n_frames - 2))
+    p.close()
