@@ -156,6 +156,8 @@ typedef struct mukv_state {
     const float *rep_seg_v;
     const float *margin;       /* [max_frames] selection margin of each frame         */
     const int32_t *refined;    /* [max_frames] 1 where the fp64 re-scoring ran        */
+    int32_t patch_cap;         /* most kept tokens a super-patch can hold:
+                                  min(kappa, longest super-patch)                     */
 } mukv_state;
 
 /* Allocates the cache on cfg->device_id.  *out is set only on success. */
@@ -239,6 +241,41 @@ int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_
 int mukv_retrieve(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, int32_t B,
                   const mukv_retrieve_params *params, int32_t *seg_idx_out, float *seg_score_out,
                   int32_t *frame_idx_out, float *frame_score_out, void *stream);
+
+/*
+ * The same search with the super-patch as the fine level (the patch granularity
+ * of Sec. 3.2 / 3.4): Eq. 7 against every visible super-patch key, stage-1
+ * top-2k, Eq. 8 against the global query of the top-N segments, final top-k.
+ * params->k_frame and params->lambda_frame are read as k_g and lambda_g of the
+ * patch level; k_seg, n_global, mode and n_visible_frames keep their meaning
+ * (HIER: super-patches inside the k_seg chosen segments).  A patch is named
+ * frame * S + s.  Super-patches without a kept token are never returned.
+ *
+ *   patch_idx_out    device int32 [B][k_frame], rank order, padded with -1
+ *   patch_score_out  device float [B][k_frame] or NULL
+ *
+ * Errors as for mukv_retrieve.
+ */
+int mukv_retrieve_patches(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, int32_t B,
+                          const mukv_retrieve_params *params, int32_t *patch_idx_out, float *patch_score_out,
+                          void *stream);
+
+/*
+ * Packs the stored K,V of the selected super-patches of each question into a
+ * dense decode context: for every patch the kept rows whose position lies in it
+ * (a dense run inside its frame's rows), patches in ascending id (MUKV_TEMPORAL)
+ * or list order, rows back to back.
+ *
+ *   patch_idx     device int32 [B][k_patch]; -1 and ids >= n_frames*S are skipped
+ *   k_out, v_out  device [B][L][H_kv][k_patch*patch_cap][D] (patch_cap from
+ *                 mukv_get_state), payload dtype; rows past the last copied one
+ *                 are zero-filled
+ *   n_tokens_out  device int32 [B] = rows copied per (layer, head), may be NULL
+ *
+ * Errors: INVALID_ARG, CAPACITY (B > max_questions), UNSUPPORTED (k_patch > 1024).
+ */
+int mukv_gather_patches(mukv_ctx *ctx, const int32_t *patch_idx, int32_t B, int32_t k_patch, int32_t order,
+                        void *k_out, void *v_out, int32_t *n_tokens_out, void *stream);
 
 /*
  * Packs the stored K,V of the selected frames of each question into a dense

@@ -298,14 +298,32 @@ class OracleMuKV:
         return out
 
     # -- online -------------------------------------------------------------
-    def retrieve(self, q_tokens, prm: RetrieveParams):
-        """q_tokens: [Nq][Hq][D] scoring-layer query states of one question."""
+    def retrieve(self, q_tokens, prm: RetrieveParams, level="frame"):
+        """q_tokens: [Nq][Hq][D] scoring-layer query states of one question.
+
+        level="frame": Sec. 3.4 with frames as the fine level.  level="patch": the
+        same with the super-patches as the fine level (block f*S + s; k_frame and
+        lambda_frame are then k_g and lambda_g of the patch level; super-patches
+        without a kept token cannot be chosen; the results come back under the
+        "frame_*" names)."""
         c = self.cfg
         Hq, Hkv, D = c.n_q_heads, c.n_kv_heads, c.head_dim
         nv = self.n_frames if prm.n_visible_frames < 0 else min(prm.n_visible_frames, self.n_frames)
         F = c.frames_per_segment
-        # the cache stores block keys as float32
-        frm32 = self.rep_frame_k[:nv].astype(np.float32)
+        if level == "patch":
+            return self._retrieve_fine(q_tokens, prm, nv, self.rep_patch_k[:nv * c.superpatches_per_frame].astype(np.float32),
+                                       F * c.superpatches_per_frame,
+                                       (self.cnt_patch[:nv * c.superpatches_per_frame] > 0).astype(np.uint8))
+        return self._retrieve_fine(q_tokens, prm, nv, self.rep_frame_k[:nv].astype(np.float32), F, None)
+
+    def _retrieve_fine(self, q_tokens, prm, nv, frm32, F, allowed):
+        """Sec. 3.4 over the segment keys and one table of finer block keys: frm32
+        [n_fine][C] float32, F fine blocks per segment, allowed = optional 0/1 mask
+        of the fine blocks that may be chosen."""
+        c = self.cfg
+        Hq, Hkv, D = c.n_q_heads, c.n_kv_heads, c.head_dim
+        nf = frm32.shape[0]
+        base = np.ones(nf, np.uint8) if allowed is None else allowed
         seg32 = self.seg_reps(nv).astype(np.float32) if nv > 0 else np.empty((0, Hkv * D), np.float32)
         q = pool_question(q_tokens)                               # Eq. 6
         s_seg = score_blocks(q, seg32, Hq, Hkv, D)                # Eq. 7
@@ -314,35 +332,59 @@ class OracleMuKV:
         res = {"s_seg": s_seg, "s_frm": s_frm}
         if prm.mode == PARALLEL:
             seg_idx, ns = topk(s_seg, ks)
-            frm_idx, nf = topk(s_frm, kf)
+            frm_idx, nfound = topk(s_frm, kf, base)
             frm_score = s_frm
         elif prm.mode == HIER:
             seg_idx, ns = topk(s_seg, ks)
-            mask = np.zeros(nv, np.uint8)
+            mask = np.zeros(nf, np.uint8)
             for s in seg_idx[:ns]:
-                mask[s * F:min((s + 1) * F, nv)] = 1
-            frm_idx, nf = topk(s_frm, kf, mask)
+                mask[s * F:min((s + 1) * F, nf)] = 1
+            frm_idx, nfound = topk(s_frm, kf, mask & base)
             frm_score = s_frm
         else:
             cand_seg, ncs = topk(s_seg, 2 * ks)                   # stage 1
-            cand_frm, ncf = topk(s_frm, 2 * kf)
+            cand_frm, ncf = topk(s_frm, 2 * kf, base)
             n_glob = min(prm.n_global if prm.n_global > 0 else ks, ncs)
             g_vec = seg32[cand_seg[:n_glob]].astype(np.float64).mean(axis=0) if n_glob else np.zeros(Hkv * D)
             gamma = consistency(g_vec, frm32, cand_frm[:ncf])     # stage 2
-            s_tilde = np.full(nv, -np.inf)
+            s_tilde = np.full(nf, -np.inf)
             s_tilde[cand_frm[:ncf]] = (1.0 - prm.lambda_frame) * s_frm[cand_frm[:ncf]] + prm.lambda_frame * gamma  # Eq. 8
-            mask = np.zeros(nv, np.uint8)
+            mask = np.zeros(nf, np.uint8)
             mask[cand_frm[:ncf]] = 1
-            frm_idx, nf = topk(s_tilde, kf, mask)
+            frm_idx, nfound = topk(s_tilde, kf, mask)
             seg_idx, ns = cand_seg[:ks].copy(), min(ks, ncs)      # lambda = 0 for segments
             frm_score = s_tilde
             res.update({"cand_seg": cand_seg, "cand_frm": cand_frm, "g": g_vec, "gamma": gamma})
         seg_score = np.zeros(ks)
         seg_score[:ns] = s_seg[seg_idx[:ns]]
         frame_score = np.zeros(kf)
-        frame_score[:nf] = frm_score[frm_idx[:nf]]
+        frame_score[:nfound] = frm_score[frm_idx[:nfound]]
         res.update({"seg_idx": seg_idx, "seg_score": seg_score, "frame_idx": frm_idx, "frame_score": frame_score})
         return res
+
+    def gather_patches(self, patch_idx, order=TEMPORAL):
+        """Concatenate the stored K,V of the selected super-patches: for patch
+        f*S + s the kept rows of frame f whose position lies in super-patch s.
+        Returns (K, V, n_tokens), K and V [L][Hkv][len(patch_idx)*patch_cap][D]
+        with the unused tail zero.  Entries equal to -1 are skipped."""
+        sk, sv = self.store()
+        kap, S, P = self.kappa, self.cfg.superpatches_per_frame, self.cfg.tokens_per_frame
+        cap = min(kap, P - (S - 1) * (P // S))
+        sel = [int(x) for x in patch_idx if 0 <= x < self.n_frames * S]
+        if order == TEMPORAL:
+            sel = sorted(sel)
+        L, Hkv, _, D = sk.shape
+        ko = np.zeros((L, Hkv, len(patch_idx) * cap, D), sk.dtype)
+        vo = np.zeros_like(ko)
+        n = 0
+        for pid in sel:
+            f, sp = divmod(pid, S)
+            lo, hi = superpatch_bounds(P, S)[sp]
+            rows = [f * kap + r for r in range(kap) if lo <= self.kept[f, r] < hi]
+            ko[:, :, n:n + len(rows)] = sk[:, :, rows]
+            vo[:, :, n:n + len(rows)] = sv[:, :, rows]
+            n += len(rows)
+        return ko, vo, n
 
     def gather(self, frame_idx, order=TEMPORAL):
         """Concatenate the stored K,V of the selected frames (Sec. 3.5): returns

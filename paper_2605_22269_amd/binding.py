@@ -57,7 +57,7 @@ class mukv_state(C.Structure):
         ("store_k", C.c_void_p), ("store_v", C.c_void_p), ("kept_idx", C.c_void_p),
         ("rep_frame_k", C.c_void_p), ("rep_frame_v", C.c_void_p), ("rep_patch_k", C.c_void_p),
         ("rep_patch_v", C.c_void_p), ("cnt_patch", C.c_void_p), ("rep_seg_k", C.c_void_p),
-        ("rep_seg_v", C.c_void_p), ("margin", C.c_void_p), ("refined", C.c_void_p),
+        ("rep_seg_v", C.c_void_p), ("margin", C.c_void_p), ("refined", C.c_void_p), ("patch_cap", C.c_int32),
     ]
 
 
@@ -69,8 +69,8 @@ class mukv_profile(C.Structure):
 
 
 EXPORTS = ("mukv_create", "mukv_destroy", "mukv_reset", "mukv_flush", "mukv_compress_chunk", "mukv_retrieve",
-           "mukv_gather_kv", "mukv_profile_begin", "mukv_profile_end", "mukv_plain_copy", "mukv_get_state",
-           "mukv_strerror")
+           "mukv_retrieve_patches", "mukv_gather_kv", "mukv_gather_patches", "mukv_profile_begin", "mukv_profile_end",
+           "mukv_plain_copy", "mukv_get_state", "mukv_strerror")
 
 _lib = None
 
@@ -93,6 +93,8 @@ def load():
                                         C.POINTER(mukv_signals_out)]
     lib.mukv_retrieve.argtypes = [vp, vp, vp, i32, C.POINTER(mukv_retrieve_params), vp, vp, vp, vp, vp]
     lib.mukv_gather_kv.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
+    lib.mukv_retrieve_patches.argtypes = [vp, vp, vp, i32, C.POINTER(mukv_retrieve_params), vp, vp, vp]
+    lib.mukv_gather_patches.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.mukv_get_state.argtypes = [vp, C.POINTER(mukv_state)]
     lib.mukv_plain_copy.argtypes = [vp, vp, C.c_int64, vp]
     lib.mukv_profile_begin.argtypes = [vp]
@@ -148,6 +150,15 @@ def mukv_retrieve(h, q_ptr, off_ptr, B, params, seg_idx, seg_score, frm_idx, frm
 
 def mukv_gather_kv(h, idx_ptr, B, k_frame, order, k_out, v_out, n_tok, stream):
     _check(load().mukv_gather_kv(h, idx_ptr, B, k_frame, order, k_out, v_out, n_tok, stream), "mukv_gather_kv")
+
+
+def mukv_retrieve_patches(h, q_ptr, off_ptr, B, params, patch_idx, patch_score, stream):
+    _check(load().mukv_retrieve_patches(h, q_ptr, off_ptr, B, C.byref(params), patch_idx, patch_score, stream),
+           "mukv_retrieve_patches")
+
+
+def mukv_gather_patches(h, idx_ptr, B, k_patch, order, k_out, v_out, n_tok, stream):
+    _check(load().mukv_gather_patches(h, idx_ptr, B, k_patch, order, k_out, v_out, n_tok, stream), "mukv_gather_patches")
 
 
 def mukv_profile_begin(h):
@@ -206,7 +217,7 @@ class MuKV:
         self.device = torch.device("cuda", device_id)
         self.h = mukv_create(self.cfg)
         st = mukv_get_state(self.h)
-        self.kappa, self.c_kv = st.kappa, st.c_kv
+        self.kappa, self.c_kv, self.patch_cap = st.kappa, st.c_kv, st.patch_cap
         # references to the buffers of the chunks the library may still read: the batch being
         # gathered, the one before it (overlap_copy) and one spare
         self._held = collections.deque(maxlen=2 * max(1, batch_chunks) + 1)
@@ -277,6 +288,37 @@ class MuKV:
         mukv_retrieve(self.h, _ptr(q_tokens), _ptr(q_offsets), B, prm, _ptr(out["seg_idx"]), _ptr(out["seg_score"]),
                       _ptr(out["frame_idx"]), _ptr(out["frame_score"]), _stream())
         self._held.clear()   # the call has enqueued everything that reads them
+        return out
+
+    def retrieve_patches(self, q_tokens, q_offsets, *, mode=MUKV_SEMI, k_seg=8, k_patch=20, lambda_patch=0.3, n_global=0,
+                         n_visible_frames=-1, out=None):
+        """The search of retrieve() with super-patches as the fine level; a patch is frame * S + s."""
+        assert q_tokens.is_contiguous() and q_tokens.dtype == self.dtype
+        assert q_offsets.dtype == torch.int32 and q_offsets.is_cuda
+        B = q_offsets.numel() - 1
+        prm = mukv_retrieve_params(mode, k_seg, k_patch, n_global, n_visible_frames, 0, lambda_patch)
+        if out is None:
+            dev = q_tokens.device
+            out = {"patch_idx": torch.empty(B, k_patch, dtype=torch.int32, device=dev),
+                   "patch_score": torch.empty(B, k_patch, dtype=torch.float32, device=dev)}
+        mukv_retrieve_patches(self.h, _ptr(q_tokens), _ptr(q_offsets), B, prm, _ptr(out["patch_idx"]),
+                              _ptr(out["patch_score"]), _stream())
+        self._held.clear()
+        return out
+
+    def gather_patches(self, patch_idx, order=MUKV_TEMPORAL, out=None):
+        """patch_idx: int32 [B][k_patch] on the device.  Returns (k_out, v_out, n_tokens) with
+        k_out, v_out [B][L][Hkv][k_patch*patch_cap][D]."""
+        assert patch_idx.dtype == torch.int32 and patch_idx.is_contiguous() and patch_idx.dim() == 2
+        B, kp = patch_idx.shape
+        c = self.cfg
+        if out is None:
+            shape = (B, c.n_layers, c.n_kv_heads, kp * self.patch_cap, c.head_dim)
+            out = (torch.empty(shape, dtype=self.dtype, device=patch_idx.device),
+                   torch.empty(shape, dtype=self.dtype, device=patch_idx.device),
+                   torch.empty(B, dtype=torch.int32, device=patch_idx.device))
+        mukv_gather_patches(self.h, _ptr(patch_idx), B, kp, order, _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _stream())
+        self._held.clear()
         return out
 
     def gather_kv(self, frame_idx, order=MUKV_TEMPORAL, out=None):

@@ -58,6 +58,13 @@ int validate_config(const mukv_config *cfg) {
 
 bool mfma_supported(const mukv_config &c) { return mukv::att_mfma_supported(c); }
 
+// most kept tokens one super-patch can hold: the last super-patch is the longest
+int patch_cap(const Ctx &c) {
+    const int P = c.cfg.tokens_per_frame, S = c.cfg.superpatches_per_frame;
+    const int longest = P - (S - 1) * (P / S);
+    return longest < c.kappa ? longest : c.kappa;
+}
+
 void free_all(Ctx &c) {
     void *ptrs[] = {c.store_k,    c.store_v,    c.kept_idx,  c.rep_frame_k, c.rep_frame_v, c.rep_patch_k,
                     c.rep_patch_v, c.rep_seg_k, c.rep_seg_v, c.cnt_patch,   c.fsum_k,      c.fsum_v,
@@ -163,7 +170,7 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(hipEventCreateWithFlags(&c.ev_copy, hipEventDisableTiming));
     ok(dalloc(&c.qbar, MQ * C));
     ok(dalloc(&c.qq, MQ * cfg->n_kv_heads));
-    ok(dalloc(&c.s_frm, MQ * MF));
+    ok(dalloc(&c.s_frm, MQ * MF * S)); // room for the super-patch level
     ok(dalloc(&c.s_seg, MQ * (size_t)c.max_segments));
     ok(dalloc(&c.seg_tail, 2 * C));
     if (e != hipSuccess || !c.prof || !c.pending || !c.deferred) {
@@ -340,10 +347,10 @@ int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_
     return MUKV_OK;
 }
 
-int mukv_retrieve(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, int32_t B,
-                  const mukv_retrieve_params *params, int32_t *seg_idx_out, float *seg_score_out,
-                  int32_t *frame_idx_out, float *frame_score_out, void *stream) {
-    if (!ctx || !q_tokens || !q_offsets || !params || !seg_idx_out || !frame_idx_out) return MUKV_ERR_INVALID_ARG;
+static int retrieve_any(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, int32_t B,
+                        const mukv_retrieve_params *params, bool patches, int32_t *seg_idx_out, float *seg_score_out,
+                        int32_t *fine_idx_out, float *fine_score_out, void *stream) {
+    if (!ctx || !q_tokens || !q_offsets || !params || !fine_idx_out) return MUKV_ERR_INVALID_ARG;
     Ctx &c = ctx->c;
     if (B < 1) return MUKV_ERR_INVALID_ARG;
     if (B > c.cfg.max_questions) return MUKV_ERR_CAPACITY;
@@ -364,12 +371,49 @@ int mukv_retrieve(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets,
     if (nv > c.n_frames) nv = c.n_frames;
     a.nv = (int)nv;
     a.ns = (int)((nv + c.cfg.frames_per_segment - 1) / c.cfg.frames_per_segment);
+    a.patches = patches;
     a.seg_idx = seg_idx_out;
     a.seg_score = seg_score_out;
-    a.frm_idx = frame_idx_out;
-    a.frm_score = frame_score_out;
+    a.frm_idx = fine_idx_out;
+    a.frm_score = fine_score_out;
     if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
     return mukv::launch_retrieve(c, a, reinterpret_cast<hipStream_t>(stream)) == hipSuccess ? MUKV_OK : MUKV_ERR_HIP;
+}
+
+int mukv_retrieve(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, int32_t B,
+                  const mukv_retrieve_params *params, int32_t *seg_idx_out, float *seg_score_out,
+                  int32_t *frame_idx_out, float *frame_score_out, void *stream) {
+    if (!seg_idx_out) return MUKV_ERR_INVALID_ARG;
+    return retrieve_any(ctx, q_tokens, q_offsets, B, params, false, seg_idx_out, seg_score_out, frame_idx_out,
+                        frame_score_out, stream);
+}
+
+int mukv_retrieve_patches(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, int32_t B,
+                          const mukv_retrieve_params *params, int32_t *patch_idx_out, float *patch_score_out,
+                          void *stream) {
+    return retrieve_any(ctx, q_tokens, q_offsets, B, params, true, nullptr, nullptr, patch_idx_out, patch_score_out,
+                        stream);
+}
+
+int mukv_gather_patches(mukv_ctx *ctx, const int32_t *patch_idx, int32_t B, int32_t k_patch, int32_t order,
+                        void *k_out, void *v_out, int32_t *n_tokens_out, void *stream) {
+    if (!ctx || !patch_idx || !k_out || !v_out) return MUKV_ERR_INVALID_ARG;
+    Ctx &c = ctx->c;
+    if (B < 1 || k_patch < 1) return MUKV_ERR_INVALID_ARG;
+    if (order != MUKV_TEMPORAL && order != MUKV_AS_GIVEN) return MUKV_ERR_INVALID_ARG;
+    if (B > c.cfg.max_questions) return MUKV_ERR_CAPACITY;
+    if (k_patch > mukv::kMaxGatherK) return MUKV_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(k_out) & 15) || (reinterpret_cast<uintptr_t>(v_out) & 15))
+        return MUKV_ERR_UNSUPPORTED;
+    {
+        const int rc = flush_pending(c, true, reinterpret_cast<hipStream_t>(stream));
+        if (rc != MUKV_OK) return rc;
+    }
+    if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
+    return mukv::launch_gather_patches(c, patch_idx, B, k_patch, order, k_patch * patch_cap(c), k_out, v_out,
+                                       n_tokens_out, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
+               ? MUKV_OK
+               : MUKV_ERR_HIP;
 }
 
 int mukv_gather_kv(mukv_ctx *ctx, const int32_t *frame_idx, int32_t B, int32_t k_frame, int32_t order,
@@ -423,6 +467,7 @@ int mukv_get_state(const mukv_ctx *ctx, mukv_state *out) {
     out->rep_seg_v = c.rep_seg_v;
     out->margin = c.margin;
     out->refined = c.refined;
+    out->patch_cap = patch_cap(c);
     return MUKV_OK;
 }
 

@@ -129,6 +129,7 @@ struct RetrieveArgs {
     mukv_retrieve_params p;
     int nv;      // visible frames
     int ns;      // visible segments
+    bool patches; // fine level of the search: super-patches instead of frames (k_frame, lambda_frame apply to it)
     int32_t *seg_idx;
     float *seg_score;
     int32_t *frm_idx;
@@ -139,6 +140,9 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st);
 
 hipError_t launch_gather(Ctx &c, const int32_t *frame_idx, int B, int k_frame, int order, void *k_out,
                          void *v_out, int32_t *n_tokens_out, hipStream_t st);
+
+hipError_t launch_gather_patches(Ctx &c, const int32_t *patch_idx, int B, int k_patch, int order, int rows_cap,
+                                 void *k_out, void *v_out, int32_t *n_tokens_out, hipStream_t st);
 
 // Brackets the launches of one scope with HIP events when the context is profiling.
 struct ProfScope {

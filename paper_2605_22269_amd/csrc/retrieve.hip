@@ -91,6 +91,7 @@ struct ScoreArgs {
     double *s_frm, *s_seg;
     float *seg_tail;
     int nv, ns, B, C, Hkv, G, F, kappa;
+    int nf; // keys of the fine level in rep_frame / s_frm: the visible frames, or their super-patches
     int tail_cut; // 1: segment ns-1 must be rebuilt from frames [ (ns-1)*F, nv )
     int64_t ld_frm, ld_seg;
 };
@@ -98,9 +99,9 @@ struct ScoreArgs {
 __global__ __launch_bounds__(256) void score_blocks_kernel(ScoreArgs a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = blockIdx.x * 4 + wave;
-    if (r >= a.nv + a.ns) return;
-    const bool is_seg = r >= a.nv;
-    const int idx = is_seg ? r - a.nv : r;
+    if (r >= a.nf + a.ns) return;
+    const bool is_seg = r >= a.nf;
+    const int idx = is_seg ? r - a.nf : r;
     const int C = a.C;
     float row[16];
     if (is_seg && a.tail_cut && idx == a.ns - 1) {
@@ -190,10 +191,10 @@ __global__ __launch_bounds__(256) void score_blocks_mfma_kernel(ScoreArgs a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lr = lane & 15, kq = lane >> 4;
     const int C = a.C;
-    const int n_ft = (a.nv + 15) / 16;
+    const int n_ft = (a.nf + 15) / 16;
     const bool is_seg = (int)blockIdx.x >= n_ft;
     const int row0 = (is_seg ? (int)blockIdx.x - n_ft : (int)blockIdx.x) * 16;
-    const int n_rows = is_seg ? a.ns : a.nv;
+    const int n_rows = is_seg ? a.ns : a.nf;
     const int rw_in = row0 + lr < n_rows ? row0 + lr : n_rows - 1;
     const float *kp = (is_seg ? ((a.tail_cut && rw_in == a.ns - 1) ? a.seg_tail : a.rep_seg + (int64_t)rw_in * C)
                               : a.rep_frame + (int64_t)rw_in * C) + 4 * kq;
@@ -529,6 +530,7 @@ struct RerankArgs {
     const float *rep_frame, *rep_seg, *seg_tail;
     int nv, ns, C, F, tail_cut;
     int mode, k_seg, k_frame, n_global;
+    const int32_t *cnt; // fine level = super-patches: kept tokens per super-patch (empty ones are never chosen); else null
     int cache_cap; // entries of the LDS key cache (dynamic shared memory)
     double lambda;
     int32_t *seg_idx, *frm_idx;
@@ -558,11 +560,11 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
     float *frm_sc = a.frm_score ? a.frm_score + (int64_t)b * a.k_frame : nullptr;
 
     auto seg_key = [&](int i) { return desc_key(s_seg[i]); };
-    auto frm_key = [&](int i) { return desc_key(s_frm[i]); };
+    auto frm_key = [&](int i) { return (a.cnt && a.cnt[i] == 0) ? kNoKey : desc_key(s_frm[i]); };
 
     if (a.mode != MUKV_SEMI) {
         const int m_s = block_topk(seg_key, a.ns, a.k_seg, cand_seg, sh, kcache, cap);
-        for (int r = tid; r < a.k_seg; r += kSelThreads) {
+        for (int r = tid; r < a.k_seg && a.seg_idx; r += kSelThreads) {
             seg_out[r] = r < m_s ? cand_seg[r] : -1;
             if (seg_sc) seg_sc[r] = r < m_s ? (float)s_seg[cand_seg[r]] : 0.f;
         }
@@ -574,7 +576,7 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
             __syncthreads();
             auto hier_key = [&](int i) {
                 const int s = i / a.F;
-                return ((seg_ok[s >> 5] >> (s & 31)) & 1u) ? desc_key(s_frm[i]) : kNoKey;
+                return ((seg_ok[s >> 5] >> (s & 31)) & 1u) ? frm_key(i) : kNoKey;
             };
             m_f = block_topk(hier_key, a.nv, a.k_frame, cand_frm, sh, kcache, cap);
         } else {
@@ -589,7 +591,7 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
 
     // ---- semi-hierarchical ----
     const int m_s = block_topk(seg_key, a.ns, 2 * a.k_seg, cand_seg, sh, kcache, cap);
-    for (int r = tid; r < a.k_seg; r += kSelThreads) { // lambda = 0 for segments: stage-1 order stands
+    for (int r = tid; r < a.k_seg && a.seg_idx; r += kSelThreads) { // lambda = 0 for segments: stage-1 order stands
         seg_out[r] = r < m_s ? cand_seg[r] : -1;
         if (seg_sc) seg_sc[r] = r < m_s ? (float)s_seg[cand_seg[r]] : 0.f;
     }
@@ -770,6 +772,86 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(GatherArgs a) {
     }
 }
 
+// Gather at super-patch granularity.  Patch id = frame * S + s; its kept rows are the dense run
+// [offset, offset + count) inside the frame's kappa rows, offset = the counts of the frame's
+// earlier super-patches (kept positions are ascending, super-patches index-contiguous).  Grid as
+// for gather_kv.  Every workgroup plans the question's list in LDS: valid patches in ascending id
+// (TEMPORAL) or list order, their source row and the running output row; rows are then copied
+// 16 bytes per lane, the slot of an output row found by bisection of the running offsets.  The
+// output holds rows_cap rows per (layer, head); rows past the last copied one are zero-filled.
+struct GatherPatchArgs {
+    const int32_t *patch_idx;
+    int k_patch, order, S;
+    const int32_t *cnt_patch;
+    const unsigned char *store_k, *store_v;
+    unsigned char *k_out, *v_out;
+    int32_t *n_tokens_out;
+    int64_t slab_b;
+    int row_b, upr_log; // bytes per row, log2(16-byte units per row)
+    int rows_cap;       // output rows per (layer, head)
+    int L, Hkv, kappa;
+    int64_t n_patches;  // n_frames * S
+};
+
+__global__ __launch_bounds__(256) void gather_patches_kernel(GatherPatchArgs a) {
+    __shared__ int raw[kMaxGatherK], s_src[kMaxGatherK], s_cnt[kMaxGatherK], s_off[kMaxGatherK + 1];
+    const int tid = threadIdx.x, b = blockIdx.z, y = blockIdx.y;
+    const int32_t *idx = a.patch_idx + (int64_t)b * a.k_patch;
+    for (int t = tid; t < a.k_patch; t += 256) {
+        const int me = idx[t];
+        raw[t] = (me < 0 || me >= a.n_patches) ? -1 : me;
+        s_cnt[t] = 0;
+        s_src[t] = 0;
+    }
+    __syncthreads();
+    for (int t = tid; t < a.k_patch; t += 256) {
+        const int me = raw[t];
+        if (me < 0) continue;
+        int pos = 0;
+        for (int u = 0; u < a.k_patch; ++u) {
+            const int o = raw[u];
+            pos += (o >= 0) && ((a.order == MUKV_TEMPORAL) ? (o < me || (o == me && u < t)) : (u < t));
+        }
+        const int f = me / a.S, sp = me - f * a.S;
+        int before = 0;
+        for (int q = 0; q < sp; ++q) before += a.cnt_patch[(int64_t)f * a.S + q];
+        s_src[pos] = f * a.kappa + before;
+        s_cnt[pos] = a.cnt_patch[me];
+    }
+    __syncthreads();
+    if (tid == 0) { // running output rows (k_patch <= 1024: a short serial scan)
+        int run = 0;
+        for (int t = 0; t < a.k_patch; ++t) {
+            s_off[t] = run;
+            run += s_cnt[t];
+        }
+        s_off[a.k_patch] = run;
+    }
+    __syncthreads();
+    const int n_rows = s_off[a.k_patch];
+    if (a.n_tokens_out && blockIdx.x == 0 && y == 0 && tid == 0) a.n_tokens_out[b] = n_rows;
+    const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
+    const int kv = rem / a.Hkv, g = rem - kv * a.Hkv;
+    const unsigned char *src = (kv ? a.store_v : a.store_k) + ((int64_t)l * a.Hkv + g) * a.slab_b;
+    unsigned char *dst = (kv ? a.v_out : a.k_out) + (((int64_t)b * a.L + l) * a.Hkv + g) * ((int64_t)a.rows_cap * a.row_b);
+    const int n_units = a.rows_cap << a.upr_log;
+    const int mask = (1 << a.upr_log) - 1;
+    for (int u = blockIdx.x * 256 + tid; u < n_units; u += gridDim.x * 256) {
+        const int row = u >> a.upr_log;
+        cp_u32x4 val = {0u, 0u, 0u, 0u};
+        if (row < n_rows) {
+            int lo = 0, hi = a.k_patch - 1; // last slot whose first output row is <= row
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (s_off[mid] <= row) lo = mid; else hi = mid - 1;
+            }
+            const int64_t srow = (int64_t)s_src[lo] + (row - s_off[lo]);
+            val = *reinterpret_cast<const cp_u32x4 *>(src + srow * a.row_b + (int64_t)(u & mask) * 16);
+        }
+        *reinterpret_cast<cp_u32x4 *>(dst + (int64_t)u * 16) = val;
+    }
+}
+
 // Plain streaming copy, 4 x 16 bytes per thread: the calibration kernel for traffic counters.
 __global__ __launch_bounds__(256) void plain_copy_kernel(const cp_u32x4 *__restrict__ src, cp_u32x4 *__restrict__ dst,
                                                          int64_t n_units) {
@@ -817,9 +899,16 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
     const int F = c.cfg.frames_per_segment;
     const int64_t seg_end = (int64_t)a.ns * F < c.n_frames ? (int64_t)a.ns * F : c.n_frames;
     const int tail_cut = (a.ns > 0 && a.nv < seg_end) ? 1 : 0;
+    // fine level: the frames, or (a.patches) their super-patches -- the same kernels on the other
+    // key table, S keys per frame
+    const int kpf = a.patches ? c.cfg.superpatches_per_frame : 1;
+    const int nf = a.nv * kpf;
+    const float *rep_fine = a.patches ? c.rep_patch_k : c.rep_frame_k;
+    const int64_t ld_fine = (int64_t)c.cfg.max_frames * kpf;
     if (a.nv + a.ns > 0) {
         ScoreArgs s;
-        s.rep_frame = c.rep_frame_k;
+        s.rep_frame = rep_fine;
+        s.nf = nf;
         s.rep_seg = c.rep_seg_k;
         s.fsum = c.fsum_k;
         s.qbar = c.qbar;
@@ -836,30 +925,31 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
         s.F = F;
         s.kappa = c.kappa;
         s.tail_cut = tail_cut;
-        s.ld_frm = c.cfg.max_frames;
+        s.ld_frm = ld_fine;
         s.ld_seg = c.max_segments;
         ProfScope ps(c, MUKV_K_SCORE, st);
         // many questions: the scores are a small matrix product for the fp64 matrix cores
         if (a.B >= 16) {
             if (tail_cut) hipLaunchKernelGGL(seg_tail_kernel, dim3((s.C + 255) / 256), dim3(256), 0, st, s);
-            hipLaunchKernelGGL(score_blocks_mfma_kernel, dim3((a.nv + 15) / 16 + (a.ns + 15) / 16), dim3(256), 0, st, s);
+            hipLaunchKernelGGL(score_blocks_mfma_kernel, dim3((nf + 15) / 16 + (a.ns + 15) / 16), dim3(256), 0, st, s);
         } else {
-            hipLaunchKernelGGL(score_blocks_kernel, dim3((a.nv + a.ns + 3) / 4), dim3(256), 0, st, s);
+            hipLaunchKernelGGL(score_blocks_kernel, dim3((nf + a.ns + 3) / 4), dim3(256), 0, st, s);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     RerankArgs r;
     r.s_frm = c.s_frm;
     r.s_seg = c.s_seg;
-    r.ld_frm = c.cfg.max_frames;
+    r.ld_frm = ld_fine;
     r.ld_seg = c.max_segments;
-    r.rep_frame = c.rep_frame_k;
+    r.rep_frame = rep_fine;
     r.rep_seg = c.rep_seg_k;
     r.seg_tail = c.seg_tail;
-    r.nv = a.nv;
+    r.nv = nf;
     r.ns = a.ns;
     r.C = c.c_kv;
-    r.F = F;
+    r.F = F * kpf; // fine keys per segment
+    r.cnt = a.patches ? c.cnt_patch : nullptr;
     r.tail_cut = tail_cut;
     r.mode = a.p.mode;
     r.k_seg = a.p.k_seg;
@@ -872,7 +962,7 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
     r.frm_score = a.frm_score;
     // key cache: as many of the frame scores as fit beside the kernel's static LDS
     constexpr int kMaxCache = 11 * 1024; // 88 KB of 8-byte keys
-    int n_max = a.nv > a.ns ? a.nv : a.ns;
+    int n_max = nf > a.ns ? nf : a.ns;
     if (n_max < 2 * kMaxCand) n_max = 2 * kMaxCand;
     r.cache_cap = n_max < kMaxCache ? n_max : kMaxCache;
     static bool lds_ok[kMaxDevices];
@@ -908,6 +998,37 @@ hipError_t launch_gather(Ctx &c, const int32_t *frame_idx, int B, int k_frame, i
     const int gx = (n_units + 256 * ITER - 1) / (256 * ITER);
     ProfScope ps(c, MUKV_K_GATHER, st);
     hipLaunchKernelGGL((gather_kv_kernel<ITER>), dim3(gx, c.cfg.n_layers * 2 * c.cfg.n_kv_heads, B), dim3(256), 0, st, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_patches(Ctx &c, const int32_t *patch_idx, int B, int k_patch, int order, int rows_cap,
+                                 void *k_out, void *v_out, int32_t *n_tokens_out, hipStream_t st) {
+    GatherPatchArgs g;
+    g.patch_idx = patch_idx;
+    g.k_patch = k_patch;
+    g.order = order;
+    g.S = c.cfg.superpatches_per_frame;
+    g.cnt_patch = c.cnt_patch;
+    g.store_k = reinterpret_cast<const unsigned char *>(c.store_k);
+    g.store_v = reinterpret_cast<const unsigned char *>(c.store_v);
+    g.k_out = reinterpret_cast<unsigned char *>(k_out);
+    g.v_out = reinterpret_cast<unsigned char *>(v_out);
+    g.n_tokens_out = n_tokens_out;
+    g.row_b = c.cfg.head_dim * c.esz;
+    g.slab_b = c.store_cap * g.row_b;
+    int upr = g.row_b / 16, lg = 0;
+    while ((1 << lg) < upr) ++lg;
+    g.upr_log = lg;
+    g.rows_cap = rows_cap;
+    g.L = c.cfg.n_layers;
+    g.Hkv = c.cfg.n_kv_heads;
+    g.kappa = c.kappa;
+    g.n_patches = c.n_frames * g.S;
+    const int n_units = rows_cap * upr;
+    int gx = (n_units + 256 * 8 - 1) / (256 * 8);
+    gx = gx < 1 ? 1 : gx;
+    ProfScope ps(c, MUKV_K_GATHER, st);
+    hipLaunchKernelGGL(gather_patches_kernel, dim3(gx, c.cfg.n_layers * 2 * c.cfg.n_kv_heads, B), dim3(256), 0, st, g);
     return hipGetLastError();
 }
 

@@ -139,5 +139,29 @@ class Pair:
             res.append(r)
         return out, res
 
+    def check_retrieve_patches(self, questions, mode, k_seg, k_patch, lambda_patch=0.3, n_visible=-1, n_global=0):
+        """The super-patch level: indices and gathered bytes exact, scores within tolerance."""
+        tol = TOL[self.w.dtype]
+        offs = np.zeros(len(questions) + 1, np.int32)
+        offs[1:] = np.cumsum([q.shape[0] for q in questions])
+        qt = torch.cat(questions).cuda().contiguous()
+        out = self.gpu.retrieve_patches(qt, torch.from_numpy(offs).cuda(), mode=mode, k_seg=k_seg, k_patch=k_patch,
+                                        lambda_patch=lambda_patch, n_visible_frames=n_visible, n_global=n_global)
+        res = []
+        for order, oorder in ((mk.MUKV_TEMPORAL, orc.TEMPORAL), (mk.MUKV_AS_GIVEN, orc.AS_GIVEN)):
+            kg, vg, ntok = self.gpu.gather_patches(out["patch_idx"], order)
+            torch.cuda.synchronize()
+            for b, q in enumerate(questions):
+                r = self.orc.retrieve(np_view(q), orc.RetrieveParams(mode, k_seg, k_patch, lambda_patch, n_global, n_visible),
+                                      level="patch")
+                np.testing.assert_array_equal(out["patch_idx"][b].cpu().numpy(), r["frame_idx"])
+                assert np.abs(out["patch_score"][b].cpu().numpy() - r["frame_score"]).max() <= min(tol, 1e-5)
+                ko, vo, n_tok = self.orc.gather_patches(r["frame_idx"], oorder)
+                assert int(ntok[b]) == n_tok
+                np.testing.assert_array_equal(np_view(kg[b]), ko)
+                np.testing.assert_array_equal(np_view(vg[b]), vo)
+                res.append(r)
+        return out, res
+
     def close(self):
         self.gpu.close()

@@ -85,7 +85,7 @@ def test_binding_struct_sizes_match_header_layout(tmp_path):
     assert C.sizeof(mk.mukv_config) == 8 * 4 + 2 * 8 + 8 * 4 + 8 + 8
     assert C.sizeof(mk.mukv_retrieve_params) == 6 * 4 + 8
     assert C.sizeof(mk.mukv_strides) == 24
-    assert C.sizeof(mk.mukv_state) == 4 * 8 + 2 * 4 + 12 * 8
+    assert C.sizeof(mk.mukv_state) == 4 * 8 + 2 * 4 + 12 * 8 + 8
     # and against the header itself, through the C compiler: sizes and every field offset
     structs = {"mukv_config": mk.mukv_config, "mukv_retrieve_params": mk.mukv_retrieve_params,
                "mukv_strides": mk.mukv_strides, "mukv_state": mk.mukv_state,

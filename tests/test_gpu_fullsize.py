@@ -109,6 +109,25 @@ def check_questions(w, gpu, ref, questions, mode=mk.MUKV_SEMI):
     return hits
 
 
+def check_patch_questions(w, gpu, ref, questions, mode, k_patch=20):
+    """Super-patch level of the search (k_g = 20 as the paper's patch level) and its gather."""
+    offs = np.zeros(len(questions) + 1, np.int32)
+    offs[1:] = np.cumsum([q.shape[0] for q in questions])
+    qt = torch.cat(questions).cuda().contiguous()
+    out = gpu.retrieve_patches(qt, torch.from_numpy(offs).cuda(), mode=mode, k_seg=w.k_seg, k_patch=k_patch,
+                               lambda_patch=w.lambda_frame)
+    kg, vg, nt = gpu.gather_patches(out["patch_idx"])
+    torch.cuda.synchronize()
+    for b, q in enumerate(questions):
+        r = ref.retrieve(np_view(q.cpu()), orc.RetrieveParams(mode, w.k_seg, k_patch, w.lambda_frame), level="patch")
+        np.testing.assert_array_equal(out["patch_idx"][b].cpu().numpy(), r["frame_idx"])
+        assert np.abs(out["patch_score"][b].cpu().numpy() - r["frame_score"]).max() <= 1e-5
+        ko, vo, n_tok = ref.gather_patches(r["frame_idx"])
+        assert int(nt[b]) == n_tok
+        np.testing.assert_array_equal(np_view(kg[b]), ko)
+        np.testing.assert_array_equal(np_view(vg[b]), vo)
+
+
 def test_config2_7b_256_frames():
     w = W["7b"]
     gpu, ref, info = run_full(w, seed=1002)
@@ -126,6 +145,7 @@ def test_config3_and_4_one_hour_stream():
     # config 3: one 32-token question, all three retrieval modes
     for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
         check_questions(w, gpu, ref, [synth.random_question(w, w.question_tokens, 78)], mode)
+        check_patch_questions(w, gpu, ref, [synth.random_question(w, w.question_tokens, 78)], mode)   # 14 400 keys
     # config 4: 64 concurrent questions of 16..64 tokens with planted target frames (planted from
     # the ORACLE's frame keys), one batched retrieve + gather
     lens = synth.question_lengths(wq.n_questions, 16, wq.question_tokens, 79)
@@ -136,6 +156,7 @@ def test_config3_and_4_one_hour_stream():
         targets.append(set(tgt.tolist()))
         qs.append(synth.planted_question(wq, torch.from_numpy(ref.rep_frame_k[tgt.numpy()]), n, 81 + i))
     hits = check_questions(wq, gpu, ref, qs)
+    check_patch_questions(wq, gpu, ref, qs[:20], mk.MUKV_SEMI)
     found = sum(len(t & set(int(x) for x in h)) for t, h in zip(targets, hits))
     total = sum(len(t) for t in targets)
     print(f"retrieval-heavy: {found}/{total} planted frames retrieved")
@@ -149,4 +170,5 @@ def test_config5_72b_shape():
     print("72b:", info)
     for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
         check_questions(w, gpu, ref, [synth.random_question(w, w.question_tokens, 82)], mode)
+        check_patch_questions(w, gpu, ref, [synth.random_question(w, w.question_tokens, 82)], mode)
     gpu.close()

@@ -525,4 +525,34 @@ def test_seeded_sweep_of_small_shapes(i):
     for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
         p.check_retrieve(qs, mode, w.k_seg, w.k_frame, w.lambda_frame)
     p.check_retrieve(qs, mk.MUKV_SEMI, w.k_seg, w.k_frame, w.lambda_frame, n_visible=max(1, w.n_frames - 2))
+    p.check_retrieve_patches(qs, (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL)[i % 3], w.k_seg, w.k_frame + 3, w.lambda_frame)
+    p.close()
+
+
+# -------------------------------------------------------- super-patch level of the search -----
+@pytest.mark.parametrize("name,frames,kw", [("tiny", 32, {}), ("7b", 21, {"n_layers": 2}),
+                                            ("72b", 19, {"n_layers": 2}),               # kappa 8 of 64: empty super-patches
+                                            ("tiny", 40, {"superpatches_per_frame": 7, "keep_ratio": 0.1})])
+def test_super_patch_retrieval_and_gather(name, frames, kw):
+    w = W[name].scaled(n_frames=frames, n_questions=3, **kw)
+    p = Pair(w, seed=120, chunk=8)
+    p.ingest()
+    p.check_compress()
+    qs = questions_for(w, [w.question_tokens, 3, 20], 900)
+    for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
+        p.check_retrieve_patches(qs, mode, 2, 9, 0.3)
+    p.check_retrieve_patches(qs, mk.MUKV_SEMI, 2, 9, 0.0)
+    p.check_retrieve_patches(qs, mk.MUKV_SEMI, 3, 200, 0.5, n_visible=frames - 5)   # more asked for than exist
+    p.check_retrieve(qs, mk.MUKV_SEMI, 2, 5, 0.3)                                    # the frame level is untouched
+    p.close()
+
+
+def test_super_patch_level_with_many_questions():
+    # 16 and more questions: the fp64 matrix-core scoring over the super-patch table
+    w = W["7b"].scaled(n_frames=37, n_layers=2, n_questions=20)
+    p = Pair(w, seed=121, chunk=8)
+    p.ingest()
+    qs = questions_for(w, [4 + (5 * i) % 30 for i in range(20)], 950)
+    p.check_retrieve_patches(qs, mk.MUKV_SEMI, 2, 12, 0.3)
+    p.check_retrieve_patches(qs, mk.MUKV_HIER, 2, 12, 0.3, n_visible=30)
     p.close()

@@ -473,3 +473,94 @@ class TestRetrieval:
         ko2, _, _ = o.gather(np.array([9, 2, -1, 4], np.int32), order=orc.AS_GIVEN)
         rows2 = np.concatenate([np.arange(f * kap, (f + 1) * kap) for f in (9, 2, 4)])
         np.testing.assert_array_equal(ko2[:, :, :n], sk[:, :, rows2])
+
+
+class TestPatchLevel:
+    """Super-patches as the fine level of the search and of the gather (Sec. 3.2, 3.4)."""
+
+    def _state(self, n_frames=24, **kw):
+        cfg = tiny_cfg(frames_per_segment=4, **kw)
+        k, v, q = tiny_stream(cfg, n_frames, seed=5)
+        return cfg, run_stream(cfg, k, v, q, 8), (k, v)
+
+    @pytest.mark.parametrize("mode", [orc.SEMI, orc.HIER, orc.PARALLEL])
+    def test_one_super_patch_per_frame_is_the_frame_level(self, mode):
+        cfg, o, _ = self._state(superpatches_per_frame=1)
+        qt = rng.standard_normal((5, 4, 16)).astype(np.float32)
+        prm = orc.RetrieveParams(mode, 2, 5, lambda_frame=0.4)
+        a, b = o.retrieve(qt, prm), o.retrieve(qt, prm, level="patch")
+        np.testing.assert_array_equal(a["frame_idx"], b["frame_idx"])
+        np.testing.assert_array_equal(a["frame_score"], b["frame_score"])
+        ka, va, na = o.gather(a["frame_idx"])
+        kb, vb, nb = o.gather_patches(b["frame_idx"])
+        assert na == nb
+        np.testing.assert_array_equal(ka, kb)
+        np.testing.assert_array_equal(va, vb)
+
+    def test_parallel_mode_is_a_masked_argsort_of_literal_cosines(self):
+        cfg, o, _ = self._state(keep_ratio=0.2)            # kappa = 2 of 13: at least two empty super-patches per frame
+        assert (o.cnt_patch == 0).any()
+        qt = rng.standard_normal((7, 4, 16)).astype(np.float32)
+        r = o.retrieve(qt, orc.RetrieveParams(orc.PARALLEL, 2, 9), level="patch")
+        q = qt.astype(np.float64).mean(axis=0).reshape(-1)                       # Eq. 6, heads concatenated
+        reps = o.rep_patch_k.astype(np.float32).astype(np.float64)
+        G = cfg.n_q_heads // cfg.n_kv_heads
+        full = np.repeat(reps.reshape(len(reps), cfg.n_kv_heads, 1, cfg.head_dim), G, axis=2).reshape(len(reps), -1)
+        with np.errstate(invalid="ignore", divide="ignore"):
+            cos = full @ q / (np.linalg.norm(full, axis=1) * np.linalg.norm(q))
+        cos[o.cnt_patch.reshape(-1) == 0] = -np.inf
+        want = np.argsort(-cos, kind="stable")[:9]
+        np.testing.assert_array_equal(r["frame_idx"], want)
+        assert all(o.cnt_patch.reshape(-1)[p] > 0 for p in r["frame_idx"])
+
+    def test_lambda_zero_semi_equals_parallel_and_hier_stays_inside(self):
+        cfg, o, _ = self._state()
+        qt = rng.standard_normal((6, 4, 16)).astype(np.float32)
+        a = o.retrieve(qt, orc.RetrieveParams(orc.SEMI, 2, 7, lambda_frame=0.0), level="patch")
+        b = o.retrieve(qt, orc.RetrieveParams(orc.PARALLEL, 2, 7), level="patch")
+        np.testing.assert_array_equal(a["frame_idx"], b["frame_idx"])
+        h = o.retrieve(qt, orc.RetrieveParams(orc.HIER, 2, 7), level="patch")
+        per_seg = cfg.frames_per_segment * cfg.superpatches_per_frame
+        assert all(p // per_seg in set(int(s) for s in h["seg_idx"]) for p in h["frame_idx"] if p >= 0)
+
+    def test_planted_super_patches_are_retrieved(self):
+        cfg, o, _ = self._state(n_frames=40)
+        w = synth.Workload("t", 2, 4, 2, 16, "f32", 40, 13, 4)
+        full = [p for p in range(160) if o.cnt_patch.reshape(-1)[p] > 0]
+        for i, target in enumerate((full[3], full[40], full[77])):       # one target per question: keys of 32
+            key = torch.from_numpy(o.rep_patch_k.reshape(-1, 32)[[target]])  # channels are too noisy for a mean of several
+            qt = synth.as_numpy(synth.planted_question(w, key, 12, seed=9 + i, cosine=0.95))
+            for mode in (orc.PARALLEL, orc.SEMI):
+                r = o.retrieve(qt, orc.RetrieveParams(mode, 3, 2, lambda_frame=0.2), level="patch")
+                assert int(r["frame_idx"][0]) == target
+
+    def test_gather_is_the_kept_rows_inside_each_super_patch(self):
+        cfg, o, (k, v) = self._state()
+        P, S, kap = cfg.tokens_per_frame, cfg.superpatches_per_frame, o.kappa
+        cap = min(kap, P - (S - 1) * (P // S))
+        sel = np.array([4 * 7 + 3, -1, 4 * 2 + 1, 4 * 7 + 0, 4 * 20 + 2], np.int32)
+        ko, vo, n = o.gather_patches(sel)
+        tok = []
+        for pid in sorted(int(x) for x in sel if x >= 0):                       # straight from the inputs
+            f, sp = divmod(pid, S)
+            lo, hi = orc.superpatch_bounds(P, S)[sp]
+            tok += [f * P + j for j in o.kept[f] if lo <= j < hi]
+        assert n == len(tok) and ko.shape[2] == len(sel) * cap
+        np.testing.assert_array_equal(ko[:, :, :n], k[:, :, tok])
+        np.testing.assert_array_equal(vo[:, :, :n], v[:, :, tok])
+        assert not ko[:, :, n:].any() and not vo[:, :, n:].any()
+        # all S super-patches of a frame, in order, are the frame
+        kf, vf, nf = o.gather(np.array([7], np.int32))
+        kp, vp, npat = o.gather_patches(np.arange(4 * 7, 4 * 8, dtype=np.int32))
+        assert nf == npat == kap
+        np.testing.assert_array_equal(kf[:, :, :kap], kp[:, :, :kap])
+        np.testing.assert_array_equal(vf[:, :, :kap], vp[:, :, :kap])
+        # list order
+        k2, _, n2 = o.gather_patches(sel, order=orc.AS_GIVEN)
+        tok2 = []
+        for pid in (int(x) for x in sel if x >= 0):
+            f, sp = divmod(pid, S)
+            lo, hi = orc.superpatch_bounds(P, S)[sp]
+            tok2 += [f * P + j for j in o.kept[f] if lo <= j < hi]
+        assert n2 == n
+        np.testing.assert_array_equal(k2[:, :, :n], k[:, :, tok2])
