@@ -299,6 +299,25 @@ def main():
             "gather_bytes": Bq * gather_bytes, "path_GBs": Bq * gather_bytes / (ms64 * 1e-3) / 1e9}
         del g64
 
+    # ---- the super-patch level of the search on the same cache: one question, k_g = 20 --------
+    p_out = {"patch_idx": torch.empty(B, 20, dtype=torch.int32, device=dev),
+             "patch_score": torch.empty(B, 20, dtype=torch.float32, device=dev)}
+    pshape = (B, L, Hkv, 20 * ctx.patch_cap, D)
+    pg_out = (torch.empty(pshape, dtype=w.torch_dtype, device=dev), torch.empty(pshape, dtype=w.torch_dtype, device=dev),
+              torch.empty(B, dtype=torch.int32, device=dev))
+
+    def retrieve_patches():
+        ctx.retrieve_patches(q_tokens, offs, mode=mk.MUKV_SEMI, k_seg=w.k_seg, k_patch=20, lambda_patch=w.lambda_frame,
+                             out=p_out)
+        ctx.gather_patches(p_out["patch_idx"], out=pg_out)
+
+    retrieve_patches()
+    pms = timed(retrieve_patches, 20)
+    torch.cuda.synchronize()
+    res["retrieve_gather_super_patches"] = {"k_patch": 20, "keys_scored": n_frames * w.superpatches_per_frame,
+                                            "ms_per_batch": pms, "ms_per_question": pms / B,
+                                            "tokens_gathered_q0": int(pg_out[2][0])}
+
     # ---- what a plain copy reaches on this machine: the library's 16-byte streaming copy on 1 GiB ----
     nb = (a.calibrate_copy_mib or 1024) << 20
     src = torch.empty(nb, dtype=torch.uint8, device=dev).random_(0, 255)
