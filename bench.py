@@ -314,6 +314,31 @@ def main():
     retrieve_patches()
     pms = timed(retrieve_patches, 20)
     torch.cuda.synchronize()
+    # ---- combined gather over the three levels with the paper's k_g = 12 / 32 / 20 ------------
+    u_seg = {"seg_idx": torch.empty(B, 12, dtype=torch.int32, device=dev), "seg_score": None,
+             "frame_idx": torch.empty(B, w.k_frame, dtype=torch.int32, device=dev), "frame_score": None}
+    u_cap = (12 * w.frames_per_segment + w.k_frame) * kappa + 20 * ctx.patch_cap
+    ushape = (B, L, Hkv, u_cap, D)
+    ug_out = (torch.empty(ushape, dtype=w.torch_dtype, device=dev), torch.empty(ushape, dtype=w.torch_dtype, device=dev),
+              torch.empty(B, dtype=torch.int32, device=dev))
+
+    def retrieve_union():
+        mk.mukv_retrieve(ctx.h, q_tokens.data_ptr(), offs.data_ptr(), B,
+                         mk.mukv_retrieve_params(mk.MUKV_SEMI, 12, w.k_frame, 0, -1, 0, w.lambda_frame),
+                         u_seg["seg_idx"].data_ptr(), None, u_seg["frame_idx"].data_ptr(), None,
+                         torch.cuda.current_stream().cuda_stream)
+        ctx.retrieve_patches(q_tokens, offs, mode=mk.MUKV_SEMI, k_seg=12, k_patch=20, lambda_patch=w.lambda_frame, out=p_out)
+        ctx.gather_union(u_seg["seg_idx"], u_seg["frame_idx"], p_out["patch_idx"], rows_cap=u_cap, out=ug_out)
+
+    retrieve_union()
+    ums = timed(retrieve_union, 20)
+    torch.cuda.synchronize()
+    u_tok = int(ug_out[2][0])
+    res["retrieve_gather_three_levels"] = {"k_seg": 12, "k_frame": w.k_frame, "k_patch": 20, "ms_per_batch": ums,
+                                           "tokens_gathered_q0": u_tok,
+                                           "gather_bytes_q0": 2 * u_tok * L * b_tok}
+    del ug_out
+
     res["retrieve_gather_super_patches"] = {"k_patch": 20, "keys_scored": n_frames * w.superpatches_per_frame,
                                             "ms_per_batch": pms, "ms_per_question": pms / B,
                                             "tokens_gathered_q0": int(pg_out[2][0])}

@@ -278,6 +278,28 @@ int mukv_gather_patches(mukv_ctx *ctx, const int32_t *patch_idx, int32_t B, int3
                         void *k_out, void *v_out, int32_t *n_tokens_out, void *stream);
 
 /*
+ * Combined gather over the three granularities of Sec. 3.4: the kept rows of
+ * every frame of the selected segments, of the selected frames and of the
+ * selected super-patches, every row once, in temporal order (ascending frame,
+ * ascending position), packed into one dense decode context per question.
+ *
+ *   seg_idx, frame_idx, patch_idx  device int32 [B][k_*]; a list may be NULL
+ *                 with its k 0; -1 and out-of-range entries are skipped
+ *   rows_cap      rows per (layer, head) the outputs have room for
+ *   k_out, v_out  device [B][L][H_kv][rows_cap][D], payload dtype; rows past the
+ *                 last copied one are zero-filled
+ *   n_tokens_out  device int32 [B]: rows the union holds; when it exceeds
+ *                 rows_cap only the first rows_cap rows were copied.  May be NULL.
+ *
+ * Needs superpatches_per_frame <= 32.  Calls on one context must not overlap
+ * (the plan of the union lives in the context).
+ * Errors: INVALID_ARG, CAPACITY (B > max_questions), UNSUPPORTED.
+ */
+int mukv_gather_union(mukv_ctx *ctx, const int32_t *seg_idx, int32_t k_seg, const int32_t *frame_idx, int32_t k_frame,
+                      const int32_t *patch_idx, int32_t k_patch, int32_t B, int32_t rows_cap, void *k_out, void *v_out,
+                      int32_t *n_tokens_out, void *stream);
+
+/*
  * Packs the stored K,V of the selected frames of each question into a dense
  * decode context (the retrieved part of R_k, R_v in Eq. 9).
  *

@@ -362,6 +362,40 @@ class OracleMuKV:
         res.update({"seg_idx": seg_idx, "seg_score": seg_score, "frame_idx": frm_idx, "frame_score": frame_score})
         return res
 
+    def gather_union(self, seg_idx=(), frame_idx=(), patch_idx=(), rows_cap=None):
+        """Combined gather over the three granularities (Sec. 3.4): the kept rows
+        of every frame of the chosen segments, of the chosen frames and of the
+        chosen super-patches, each row once, ascending (frame, position).
+        Returns (K, V, n_rows); K, V [L][Hkv][rows_cap][D], tail zero; when the
+        union holds more than rows_cap rows only the first rows_cap are copied."""
+        sk, sv = self.store()
+        c = self.cfg
+        kap, S, P, F = self.kappa, c.superpatches_per_frame, c.tokens_per_frame, c.frames_per_segment
+        rows = set()
+        for s in seg_idx:
+            if s >= 0:
+                for f in range(int(s) * F, min((int(s) + 1) * F, self.n_frames)):
+                    rows.update(range(f * kap, (f + 1) * kap))
+        for f in frame_idx:
+            if 0 <= f < self.n_frames:
+                rows.update(range(int(f) * kap, (int(f) + 1) * kap))
+        bounds = superpatch_bounds(P, S)
+        for pid in patch_idx:
+            if 0 <= pid < self.n_frames * S:
+                f, sp = divmod(int(pid), S)
+                lo, hi = bounds[sp]
+                rows.update(f * kap + r for r in range(kap) if lo <= self.kept[f, r] < hi)
+        rows = sorted(rows)
+        if rows_cap is None:
+            rows_cap = max(len(rows), 1)
+        L, Hkv, _, D = sk.shape
+        ko = np.zeros((L, Hkv, rows_cap, D), sk.dtype)
+        vo = np.zeros_like(ko)
+        n = min(len(rows), rows_cap)
+        ko[:, :, :n] = sk[:, :, rows[:n]]
+        vo[:, :, :n] = sv[:, :, rows[:n]]
+        return ko, vo, len(rows)
+
     def gather_patches(self, patch_idx, order=TEMPORAL):
         """Concatenate the stored K,V of the selected super-patches: for patch
         f*S + s the kept rows of frame f whose position lies in super-patch s.

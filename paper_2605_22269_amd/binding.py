@@ -69,7 +69,7 @@ class mukv_profile(C.Structure):
 
 
 EXPORTS = ("mukv_create", "mukv_destroy", "mukv_reset", "mukv_flush", "mukv_compress_chunk", "mukv_retrieve",
-           "mukv_retrieve_patches", "mukv_gather_kv", "mukv_gather_patches", "mukv_profile_begin", "mukv_profile_end",
+           "mukv_retrieve_patches", "mukv_gather_kv", "mukv_gather_patches", "mukv_gather_union", "mukv_profile_begin", "mukv_profile_end",
            "mukv_plain_copy", "mukv_get_state", "mukv_strerror")
 
 _lib = None
@@ -95,6 +95,7 @@ def load():
     lib.mukv_gather_kv.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.mukv_retrieve_patches.argtypes = [vp, vp, vp, i32, C.POINTER(mukv_retrieve_params), vp, vp, vp]
     lib.mukv_gather_patches.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
+    lib.mukv_gather_union.argtypes = [vp, vp, i32, vp, i32, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.mukv_get_state.argtypes = [vp, C.POINTER(mukv_state)]
     lib.mukv_plain_copy.argtypes = [vp, vp, C.c_int64, vp]
     lib.mukv_profile_begin.argtypes = [vp]
@@ -159,6 +160,11 @@ def mukv_retrieve_patches(h, q_ptr, off_ptr, B, params, patch_idx, patch_score, 
 
 def mukv_gather_patches(h, idx_ptr, B, k_patch, order, k_out, v_out, n_tok, stream):
     _check(load().mukv_gather_patches(h, idx_ptr, B, k_patch, order, k_out, v_out, n_tok, stream), "mukv_gather_patches")
+
+
+def mukv_gather_union(h, seg_ptr, k_seg, frm_ptr, k_frame, pat_ptr, k_patch, B, rows_cap, k_out, v_out, n_tok, stream):
+    _check(load().mukv_gather_union(h, seg_ptr, k_seg, frm_ptr, k_frame, pat_ptr, k_patch, B, rows_cap, k_out, v_out, n_tok,
+                                    stream), "mukv_gather_union")
 
 
 def mukv_profile_begin(h):
@@ -318,6 +324,29 @@ class MuKV:
                    torch.empty(shape, dtype=self.dtype, device=patch_idx.device),
                    torch.empty(B, dtype=torch.int32, device=patch_idx.device))
         mukv_gather_patches(self.h, _ptr(patch_idx), B, kp, order, _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _stream())
+        self._held.clear()
+        return out
+
+    def gather_union(self, seg_idx=None, frame_idx=None, patch_idx=None, rows_cap=None, out=None):
+        """Kept rows of the chosen segments' frames, the chosen frames and the chosen super-patches,
+        each once, in temporal order.  Index tensors int32 [B][k] on the device (or None).  Returns
+        (k_out, v_out, n_tokens) with k_out, v_out [B][L][Hkv][rows_cap][D]."""
+        lists = [t for t in (seg_idx, frame_idx, patch_idx) if t is not None]
+        assert lists and all(t.dtype == torch.int32 and t.is_contiguous() and t.dim() == 2 for t in lists)
+        B = lists[0].shape[0]
+        c = self.cfg
+        ks = 0 if seg_idx is None else seg_idx.shape[1]
+        kf = 0 if frame_idx is None else frame_idx.shape[1]
+        kp = 0 if patch_idx is None else patch_idx.shape[1]
+        if rows_cap is None:  # room for everything that could be chosen
+            rows_cap = (ks * c.frames_per_segment + kf) * self.kappa + kp * self.patch_cap
+        if out is None:
+            shape = (B, c.n_layers, c.n_kv_heads, rows_cap, c.head_dim)
+            dev = lists[0].device
+            out = (torch.empty(shape, dtype=self.dtype, device=dev), torch.empty(shape, dtype=self.dtype, device=dev),
+                   torch.empty(B, dtype=torch.int32, device=dev))
+        mukv_gather_union(self.h, _ptr(seg_idx), ks, _ptr(frame_idx), kf, _ptr(patch_idx), kp, B, rows_cap,
+                          _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _stream())
         self._held.clear()
         return out
 

@@ -69,7 +69,8 @@ void free_all(Ctx &c) {
     void *ptrs[] = {c.store_k,    c.store_v,    c.kept_idx,  c.rep_frame_k, c.rep_frame_v, c.rep_patch_k,
                     c.rep_patch_v, c.rep_seg_k, c.rep_seg_v, c.cnt_patch,   c.fsum_k,      c.fsum_v,
                     c.ssum_k,      c.ssum_v,    c.margin,      c.refined,   c.att_part,  c.fft_sig,     c.att64,       c.fft64,
-                    c.src_tok,     c.src_tok2,    c.flag_list[0], c.flag_list[1], c.flag_count, c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail};
+                    c.src_tok,     c.src_tok2,    c.flag_list[0], c.flag_list[1], c.flag_count, c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail,
+                    c.u_mask,      c.u_entry,     c.u_count};
     // nothing of the library's own may still be running on what is freed below
     if (c.side) (void)hipStreamSynchronize(c.side);
     for (void *p : ptrs)
@@ -173,6 +174,9 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(dalloc(&c.s_frm, MQ * MF * S)); // room for the super-patch level
     ok(dalloc(&c.s_seg, MQ * (size_t)c.max_segments));
     ok(dalloc(&c.seg_tail, 2 * C));
+    ok(dalloc(&c.u_mask, MQ * MF));
+    ok(dalloc(&c.u_entry, MQ * MF * 3));
+    ok(dalloc(&c.u_count, MQ * 2));
     if (e != hipSuccess || !c.prof || !c.pending || !c.deferred) {
         free_all(c);
         delete c.prof;
@@ -435,6 +439,37 @@ int mukv_gather_kv(mukv_ctx *ctx, const int32_t *frame_idx, int32_t B, int32_t k
                                reinterpret_cast<hipStream_t>(stream)) == hipSuccess
                ? MUKV_OK
                : MUKV_ERR_HIP;
+}
+
+int mukv_gather_union(mukv_ctx *ctx, const int32_t *seg_idx, int32_t k_seg, const int32_t *frame_idx, int32_t k_frame,
+                      const int32_t *patch_idx, int32_t k_patch, int32_t B, int32_t rows_cap, void *k_out, void *v_out,
+                      int32_t *n_tokens_out, void *stream) {
+    if (!ctx || !k_out || !v_out) return MUKV_ERR_INVALID_ARG;
+    Ctx &c = ctx->c;
+    if (B < 1 || rows_cap < 1 || k_seg < 0 || k_frame < 0 || k_patch < 0) return MUKV_ERR_INVALID_ARG;
+    if ((k_seg > 0 && !seg_idx) || (k_frame > 0 && !frame_idx) || (k_patch > 0 && !patch_idx)) return MUKV_ERR_INVALID_ARG;
+    if (B > c.cfg.max_questions) return MUKV_ERR_CAPACITY;
+    if (c.cfg.superpatches_per_frame > 32) return MUKV_ERR_UNSUPPORTED; // one mask bit per super-patch
+    if ((reinterpret_cast<uintptr_t>(k_out) & 15) || (reinterpret_cast<uintptr_t>(v_out) & 15))
+        return MUKV_ERR_UNSUPPORTED;
+    {
+        const int rc = flush_pending(c, true, reinterpret_cast<hipStream_t>(stream));
+        if (rc != MUKV_OK) return rc;
+    }
+    mukv::UnionArgs a;
+    a.seg_idx = k_seg > 0 ? seg_idx : nullptr;
+    a.frame_idx = k_frame > 0 ? frame_idx : nullptr;
+    a.patch_idx = k_patch > 0 ? patch_idx : nullptr;
+    a.k_seg = k_seg;
+    a.k_frame = k_frame;
+    a.k_patch = k_patch;
+    a.B = B;
+    a.rows_cap = rows_cap;
+    a.k_out = k_out;
+    a.v_out = v_out;
+    a.n_tokens_out = n_tokens_out;
+    if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
+    return mukv::launch_gather_union(c, a, reinterpret_cast<hipStream_t>(stream)) == hipSuccess ? MUKV_OK : MUKV_ERR_HIP;
 }
 
 int mukv_plain_copy(void *dst, const void *src, int64_t bytes, void *stream) {

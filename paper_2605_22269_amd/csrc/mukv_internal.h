@@ -78,6 +78,10 @@ struct Ctx {
     double *s_frm;   // [max_questions][max_frames]
     double *s_seg;   // [max_questions][max_segments]
     float *seg_tail; // [2][c_kv] key (K, V) of a segment cut by the question's timestamp
+    // combined gather scratch (device)
+    uint32_t *u_mask;  // [max_questions][max_frames] super-patches of a frame chosen at any level
+    int32_t *u_entry;  // [max_questions][max_frames][3] chosen frames in time order: frame, mask, first output row
+    int32_t *u_count;  // [max_questions][2] entries, rows
 };
 
 // ---- a batch of chunks processed by one chain of launches ----
@@ -143,6 +147,15 @@ hipError_t launch_gather(Ctx &c, const int32_t *frame_idx, int B, int k_frame, i
 
 hipError_t launch_gather_patches(Ctx &c, const int32_t *patch_idx, int B, int k_patch, int order, int rows_cap,
                                  void *k_out, void *v_out, int32_t *n_tokens_out, hipStream_t st);
+
+struct UnionArgs {
+    const int32_t *seg_idx, *frame_idx, *patch_idx; // [B][k] each, any may be null
+    int k_seg, k_frame, k_patch;
+    int B, rows_cap;
+    void *k_out, *v_out;
+    int32_t *n_tokens_out;
+};
+hipError_t launch_gather_union(Ctx &c, const UnionArgs &a, hipStream_t st);
 
 // Brackets the launches of one scope with HIP events when the context is profiling.
 struct ProfScope {

@@ -852,6 +852,145 @@ __global__ __launch_bounds__(256) void gather_patches_kernel(GatherPatchArgs a) 
     }
 }
 
+// Combined gather over the three granularities (Sec. 3.4): the union of the kept rows of every
+// frame of the chosen segments, of the chosen frames and of the chosen super-patches, each row
+// once, in temporal order.  Two kernels.  union_plan: one workgroup per question marks, per
+// frame, the super-patches chosen at any level (a 32-bit mask in the context's scratch; a whole
+// frame sets all S bits), counts the rows behind every mask from the per-super-patch counts,
+// and scans the frames in time order into a list of entries (frame, mask, first output row).
+// gather_union: workgroups walk the entries; inside a frame the rows of a chosen super-patch are
+// a dense run (kept positions ascend, super-patches are index-contiguous).
+struct UnionPlanArgs {
+    const int32_t *seg_idx, *frame_idx, *patch_idx;
+    int k_seg, k_frame, k_patch;
+    int S, F, kappa;
+    int n_frames;
+    int64_t ld; // max_frames
+    const int32_t *cnt_patch;
+    uint32_t *mask;
+    int32_t *entry, *count;
+};
+
+constexpr int kPlanThreads = 512;
+__global__ __launch_bounds__(kPlanThreads) void union_plan_kernel(UnionPlanArgs a) {
+    __shared__ int sh_sel[kPlanThreads], sh_rows[kPlanThreads];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    uint32_t *mask = a.mask + (int64_t)b * a.ld;
+    int32_t *entry = a.entry + (int64_t)b * a.ld * 3;
+    const uint32_t full = a.S >= 32 ? 0xffffffffu : ((1u << a.S) - 1u);
+    for (int f = tid; f < a.n_frames; f += kPlanThreads) mask[f] = 0u;
+    __syncthreads();
+    for (int i = tid; i < a.k_seg * a.F; i += kPlanThreads) {
+        const int sg = a.seg_idx[(int64_t)b * a.k_seg + i / a.F];
+        const int64_t f = (int64_t)sg * a.F + i % a.F;
+        if (sg >= 0 && f < a.n_frames) atomicOr(&mask[f], full);
+    }
+    for (int i = tid; i < a.k_frame; i += kPlanThreads) {
+        const int f = a.frame_idx[(int64_t)b * a.k_frame + i];
+        if (f >= 0 && f < a.n_frames) atomicOr(&mask[f], full);
+    }
+    for (int i = tid; i < a.k_patch; i += kPlanThreads) {
+        const int p = a.patch_idx[(int64_t)b * a.k_patch + i];
+        if (p >= 0 && p / a.S < a.n_frames) atomicOr(&mask[p / a.S], 1u << (p % a.S));
+    }
+    __syncthreads();
+    // every thread owns a contiguous range of frames; rows behind a mask from the super-patch counts
+    const int per = (a.n_frames + kPlanThreads - 1) / kPlanThreads;
+    const int f_lo = tid * per < a.n_frames ? tid * per : a.n_frames;
+    const int f_hi = f_lo + per < a.n_frames ? f_lo + per : a.n_frames;
+    auto rows_of = [&](int f, uint32_t m) {
+        if (m == full) return a.kappa;
+        int r = 0;
+        for (int sp = 0; sp < a.S; ++sp)
+            if ((m >> sp) & 1u) r += a.cnt_patch[(int64_t)f * a.S + sp];
+        return r;
+    };
+    int n_sel = 0, n_rows = 0;
+    for (int f = f_lo; f < f_hi; ++f) {
+        const uint32_t m = mask[f];
+        if (m) {
+            ++n_sel;
+            n_rows += rows_of(f, m);
+        }
+    }
+    sh_sel[tid] = n_sel;
+    sh_rows[tid] = n_rows;
+    __syncthreads();
+    if (tid == 0) { // exclusive scan over the threads' ranges (512 short steps)
+        int rs = 0, rr = 0;
+        for (int t = 0; t < kPlanThreads; ++t) {
+            const int s0 = sh_sel[t], r0 = sh_rows[t];
+            sh_sel[t] = rs;
+            sh_rows[t] = rr;
+            rs += s0;
+            rr += r0;
+        }
+        a.count[2 * b] = rs;
+        a.count[2 * b + 1] = rr;
+    }
+    __syncthreads();
+    int e = sh_sel[tid], row = sh_rows[tid];
+    for (int f = f_lo; f < f_hi; ++f) {
+        const uint32_t m = mask[f];
+        if (m) {
+            entry[3 * e] = f;
+            entry[3 * e + 1] = (int32_t)m;
+            entry[3 * e + 2] = row;
+            row += rows_of(f, m);
+            ++e;
+        }
+    }
+}
+
+struct UnionGatherArgs {
+    const int32_t *entry, *count;
+    int64_t ld;
+    const int32_t *cnt_patch;
+    int S, kappa;
+    const unsigned char *store_k, *store_v;
+    unsigned char *k_out, *v_out;
+    int32_t *n_tokens_out;
+    int64_t slab_b;
+    int row_b, upr_log, rows_cap;
+    int L, Hkv;
+};
+
+__global__ __launch_bounds__(256) void gather_union_kernel(UnionGatherArgs a) {
+    const int tid = threadIdx.x, b = blockIdx.z, y = blockIdx.y;
+    const int n_ent = a.count[2 * b], n_rows = a.count[2 * b + 1];
+    if (a.n_tokens_out && blockIdx.x == 0 && y == 0 && tid == 0) a.n_tokens_out[b] = n_rows;
+    const int32_t *entry = a.entry + (int64_t)b * a.ld * 3;
+    const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
+    const int kv = rem / a.Hkv, g = rem - kv * a.Hkv;
+    const unsigned char *src = (kv ? a.store_v : a.store_k) + ((int64_t)l * a.Hkv + g) * a.slab_b;
+    unsigned char *dst = (kv ? a.v_out : a.k_out) + (((int64_t)b * a.L + l) * a.Hkv + g) * ((int64_t)a.rows_cap * a.row_b);
+    const int upr = 1 << a.upr_log;
+    for (int e = blockIdx.x; e < n_ent; e += gridDim.x) {
+        const int f = entry[3 * e];
+        const uint32_t m = (uint32_t)entry[3 * e + 1];
+        int out_row = entry[3 * e + 2];
+        int before = 0; // kept rows of the frame in earlier super-patches
+        for (int sp = 0; sp < a.S; ++sp) {
+            const int c = a.cnt_patch[(int64_t)f * a.S + sp];
+            if ((m >> sp) & 1u) {
+                const int c_fit = out_row + c <= a.rows_cap ? c : (a.rows_cap > out_row ? a.rows_cap - out_row : 0);
+                const unsigned char *s0 = src + ((int64_t)f * a.kappa + before) * a.row_b;
+                unsigned char *d0 = dst + (int64_t)out_row * a.row_b;
+                for (int u = tid; u < c_fit * upr; u += 256)
+                    *reinterpret_cast<cp_u32x4 *>(d0 + (int64_t)u * 16) = *reinterpret_cast<const cp_u32x4 *>(s0 + (int64_t)u * 16);
+                out_row += c;
+            }
+            before += c;
+        }
+    }
+    // rows past the union are zero
+    const int first = n_rows < a.rows_cap ? n_rows : a.rows_cap;
+    const int64_t n_zero = (int64_t)(a.rows_cap - first) * upr;
+    unsigned char *z0 = dst + (int64_t)first * a.row_b;
+    for (int64_t u = (int64_t)blockIdx.x * 256 + tid; u < n_zero; u += (int64_t)gridDim.x * 256)
+        *reinterpret_cast<cp_u32x4 *>(z0 + u * 16) = cp_u32x4{0u, 0u, 0u, 0u};
+}
+
 // Plain streaming copy, 4 x 16 bytes per thread: the calibration kernel for traffic counters.
 __global__ __launch_bounds__(256) void plain_copy_kernel(const cp_u32x4 *__restrict__ src, cp_u32x4 *__restrict__ dst,
                                                          int64_t n_units) {
@@ -1029,6 +1168,51 @@ hipError_t launch_gather_patches(Ctx &c, const int32_t *patch_idx, int B, int k_
     gx = gx < 1 ? 1 : gx;
     ProfScope ps(c, MUKV_K_GATHER, st);
     hipLaunchKernelGGL(gather_patches_kernel, dim3(gx, c.cfg.n_layers * 2 * c.cfg.n_kv_heads, B), dim3(256), 0, st, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_union(Ctx &c, const UnionArgs &a, hipStream_t st) {
+    UnionPlanArgs p;
+    p.seg_idx = a.seg_idx;
+    p.frame_idx = a.frame_idx;
+    p.patch_idx = a.patch_idx;
+    p.k_seg = a.seg_idx ? a.k_seg : 0;
+    p.k_frame = a.frame_idx ? a.k_frame : 0;
+    p.k_patch = a.patch_idx ? a.k_patch : 0;
+    p.S = c.cfg.superpatches_per_frame;
+    p.F = c.cfg.frames_per_segment;
+    p.kappa = c.kappa;
+    p.n_frames = (int)c.n_frames;
+    p.ld = c.cfg.max_frames;
+    p.cnt_patch = c.cnt_patch;
+    p.mask = c.u_mask;
+    p.entry = c.u_entry;
+    p.count = c.u_count;
+    ProfScope ps(c, MUKV_K_GATHER, st);
+    hipLaunchKernelGGL(union_plan_kernel, dim3(a.B), dim3(kPlanThreads), 0, st, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    UnionGatherArgs g;
+    g.entry = c.u_entry;
+    g.count = c.u_count;
+    g.ld = c.cfg.max_frames;
+    g.cnt_patch = c.cnt_patch;
+    g.S = p.S;
+    g.kappa = c.kappa;
+    g.store_k = reinterpret_cast<const unsigned char *>(c.store_k);
+    g.store_v = reinterpret_cast<const unsigned char *>(c.store_v);
+    g.k_out = reinterpret_cast<unsigned char *>(a.k_out);
+    g.v_out = reinterpret_cast<unsigned char *>(a.v_out);
+    g.n_tokens_out = a.n_tokens_out;
+    g.row_b = c.cfg.head_dim * c.esz;
+    g.slab_b = c.store_cap * g.row_b;
+    int upr = g.row_b / 16, lg = 0;
+    while ((1 << lg) < upr) ++lg;
+    g.upr_log = lg;
+    g.rows_cap = a.rows_cap;
+    g.L = c.cfg.n_layers;
+    g.Hkv = c.cfg.n_kv_heads;
+    hipLaunchKernelGGL(gather_union_kernel, dim3(64, c.cfg.n_layers * 2 * c.cfg.n_kv_heads, a.B), dim3(256), 0, st, g);
     return hipGetLastError();
 }
 

@@ -163,5 +163,19 @@ class Pair:
                 res.append(r)
         return out, res
 
+    def check_gather_union(self, seg_idx, frame_idx, patch_idx, rows_cap=None):
+        """Lists of per-question index lists (or None).  Bytes and counts exact."""
+        def dev(x):
+            return None if x is None else torch.tensor(x, dtype=torch.int32, device="cuda")
+        kg, vg, nt = self.gpu.gather_union(dev(seg_idx), dev(frame_idx), dev(patch_idx), rows_cap)
+        torch.cuda.synchronize()
+        B = kg.shape[0]
+        for b in range(B):
+            ko, vo, n = self.orc.gather_union(() if seg_idx is None else seg_idx[b], () if frame_idx is None else frame_idx[b],
+                                              () if patch_idx is None else patch_idx[b], rows_cap=kg.shape[3])
+            assert int(nt[b]) == n
+            np.testing.assert_array_equal(np_view(kg[b]), ko)
+            np.testing.assert_array_equal(np_view(vg[b]), vo)
+
     def close(self):
         self.gpu.close()

@@ -128,6 +128,22 @@ def check_patch_questions(w, gpu, ref, questions, mode, k_patch=20):
         np.testing.assert_array_equal(np_view(vg[b]), vo)
 
 
+def check_union(w, gpu, ref, question):
+    """Combined gather fed by the two searches: the paper's k_g = 12 segments, 32 frames, 20 super-patches."""
+    offs = torch.tensor([0, question.shape[0]], dtype=torch.int32, device="cuda")
+    qt = question.cuda().contiguous()
+    o1 = gpu.retrieve(qt, offs, mode=mk.MUKV_SEMI, k_seg=12, k_frame=32, lambda_frame=w.lambda_frame)
+    o2 = gpu.retrieve_patches(qt, offs, mode=mk.MUKV_SEMI, k_seg=12, k_patch=20, lambda_patch=w.lambda_frame)
+    kg, vg, nt = gpu.gather_union(o1["seg_idx"], o1["frame_idx"], o2["patch_idx"])
+    torch.cuda.synchronize()
+    ko, vo, n = ref.gather_union(o1["seg_idx"][0].cpu().numpy(), o1["frame_idx"][0].cpu().numpy(),
+                                 o2["patch_idx"][0].cpu().numpy(), rows_cap=kg.shape[3])
+    assert int(nt[0]) == n
+    np.testing.assert_array_equal(np_view(kg[0]), ko)
+    np.testing.assert_array_equal(np_view(vg[0]), vo)
+    return n
+
+
 def test_config2_7b_256_frames():
     w = W["7b"]
     gpu, ref, info = run_full(w, seed=1002)
@@ -146,6 +162,8 @@ def test_config3_and_4_one_hour_stream():
     for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
         check_questions(w, gpu, ref, [synth.random_question(w, w.question_tokens, 78)], mode)
         check_patch_questions(w, gpu, ref, [synth.random_question(w, w.question_tokens, 78)], mode)   # 14 400 keys
+    print("hour: combined gather of 12 segments + 32 frames + 20 super-patches:",
+          check_union(w, gpu, ref, synth.random_question(w, w.question_tokens, 78)), "tokens")
     # config 4: 64 concurrent questions of 16..64 tokens with planted target frames (planted from
     # the ORACLE's frame keys), one batched retrieve + gather
     lens = synth.question_lengths(wq.n_questions, 16, wq.question_tokens, 79)

@@ -556,3 +556,26 @@ def test_super_patch_level_with_many_questions():
     p.check_retrieve_patches(qs, mk.MUKV_SEMI, 2, 12, 0.3)
     p.check_retrieve_patches(qs, mk.MUKV_HIER, 2, 12, 0.3, n_visible=30)
     p.close()
+
+
+@pytest.mark.parametrize("name,frames,kw", [("tiny", 32, {}), ("7b", 40, {"n_layers": 2}), ("72b", 70, {"n_layers": 2})])
+def test_combined_gather_over_the_three_levels(name, frames, kw):
+    w = W[name].scaled(n_frames=frames, n_questions=2, **kw)
+    p = Pair(w, seed=130, chunk=8)
+    p.ingest()
+    S, F = w.superpatches_per_frame, w.frames_per_segment
+    # overlapping choices at all levels, invalid entries, one question with almost nothing
+    segs = [[1, -1, 0], [-1, -1, 99]]
+    frms = [[F + 1, frames - 1, 3, -1], [2, 2, -1, frames + 5]]
+    pats = [[S * 3 + 1, S * (frames - 2) + S - 1, S * (F + 1), -1, S * 5 + 0], [S * 2 + 1, -1, S * frames + 3, 7 * S, 7 * S + 1]]
+    p.check_gather_union(segs, frms, pats)
+    p.check_gather_union(None, frms, None)
+    p.check_gather_union(segs, None, None)
+    p.check_gather_union(None, None, pats)
+    p.check_gather_union(segs, frms, pats, rows_cap=3 * p.gpu.kappa + 1)       # too small: first rows only, full count
+    # fed by the searches themselves
+    qs = questions_for(w, [w.question_tokens, 5], 970)
+    out, _ = p.check_retrieve(qs, mk.MUKV_SEMI, 2, 4, 0.3)
+    pout, _ = p.check_retrieve_patches(qs, mk.MUKV_SEMI, 2, 6, 0.3)
+    p.check_gather_union(out["seg_idx"].cpu().tolist(), out["frame_idx"].cpu().tolist(), pout["patch_idx"].cpu().tolist())
+    p.close()

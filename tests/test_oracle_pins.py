@@ -564,3 +564,37 @@ class TestPatchLevel:
             tok2 += [f * P + j for j in o.kept[f] if lo <= j < hi]
         assert n2 == n
         np.testing.assert_array_equal(k2[:, :, :n], k[:, :, tok2])
+
+    def test_combined_gather_is_the_union_of_the_three_levels(self):
+        cfg, o, (k, v) = self._state()
+        P, S, kap, F = cfg.tokens_per_frame, cfg.superpatches_per_frame, o.kappa, cfg.frames_per_segment
+        # one level at a time it is that level's gather (temporal order, distinct entries)
+        frames = np.array([9, 2, 4], np.int32)
+        ka, va, na = o.gather(frames)
+        kb, vb, nb = o.gather_union(frame_idx=frames, rows_cap=ka.shape[2])
+        assert na == nb
+        np.testing.assert_array_equal(ka, kb)
+        np.testing.assert_array_equal(va, vb)
+        pats = np.array([4 * 7 + 3, 4 * 2 + 1, 4 * 7 + 0], np.int32)
+        ka, va, na = o.gather_patches(pats)
+        kb, vb, nb = o.gather_union(patch_idx=pats, rows_cap=ka.shape[2])
+        assert na == nb
+        np.testing.assert_array_equal(ka, kb)
+        ka, _, na = o.gather(np.arange(2 * F, 3 * F, dtype=np.int32))          # a segment is its frames
+        kb, _, nb = o.gather_union(seg_idx=[2], rows_cap=ka.shape[2])
+        assert na == nb == F * kap
+        np.testing.assert_array_equal(ka, kb)
+        # together: every row once, straight from the inputs, in (frame, position) order
+        ku, vu, n = o.gather_union(seg_idx=[1, -1], frame_idx=[5, 17, 99], patch_idx=[4 * 5 + 1, 4 * 20 + 2, 4 * 17 + 3, -1])
+        want = set()
+        for f in list(range(F, 2 * F)) + [5, 17]:
+            want.update(f * P + int(j) for j in o.kept[f])
+        lo, hi = orc.superpatch_bounds(P, S)[2]
+        want.update(20 * P + int(j) for j in o.kept[20] if lo <= j < hi)
+        tok = sorted(want)
+        assert n == len(tok) == ku.shape[2]
+        np.testing.assert_array_equal(ku, k[:, :, tok])
+        np.testing.assert_array_equal(vu, v[:, :, tok])
+        # a smaller output holds the first rows only, the count still reports the union
+        k3, _, n3 = o.gather_union(seg_idx=[1], frame_idx=[5, 17], rows_cap=7)
+        assert n3 == (F + 1) * kap and k3.shape[2] == 7                    # frame 5 lies inside segment 1: counted once
