@@ -539,6 +539,8 @@ struct RerankArgs {
 
 constexpr int kMaxSegBitmapWords = 2048; // HIER mode: segments 0..65535
 
+// kPatches: the fine level is the super-patch table (empty super-patches get no key).
+template <bool kPatches>
 __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a) {
     __shared__ SelShared sh;
     __shared__ int cand_seg[kMaxCand];
@@ -560,7 +562,15 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
     float *frm_sc = a.frm_score ? a.frm_score + (int64_t)b * a.k_frame : nullptr;
 
     auto seg_key = [&](int i) { return desc_key(s_seg[i]); };
-    auto frm_key = [&](int i) { return (a.cnt && a.cnt[i] == 0) ? kNoKey : desc_key(s_frm[i]); };
+    auto frm_key = [&](int i) { // both loads unconditional, the choice afterwards
+        const uint64_t k = desc_key(s_frm[i]);
+        if constexpr (kPatches) {
+            const int n_kept = a.cnt[i];
+            return n_kept == 0 ? kNoKey : k;
+        } else {
+            return k;
+        }
+    };
 
     if (a.mode != MUKV_SEMI) {
         const int m_s = block_topk(seg_key, a.ns, a.k_seg, cand_seg, sh, kcache, cap);
@@ -1105,11 +1115,17 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
     if (n_max < 2 * kMaxCand) n_max = 2 * kMaxCand;
     r.cache_cap = n_max < kMaxCache ? n_max : kMaxCache;
     static bool lds_ok[kMaxDevices];
-    if ((e = allow_dynamic_lds(reinterpret_cast<const void *>(&select_rerank_kernel), (size_t)kMaxCache * 8,
-                               c.cfg.device_id, lds_ok)) != hipSuccess)
+    static bool lds_ok_p[kMaxDevices];
+    if ((e = a.patches ? allow_dynamic_lds(reinterpret_cast<const void *>(&select_rerank_kernel<true>),
+                                           (size_t)kMaxCache * 8, c.cfg.device_id, lds_ok_p)
+                       : allow_dynamic_lds(reinterpret_cast<const void *>(&select_rerank_kernel<false>),
+                                           (size_t)kMaxCache * 8, c.cfg.device_id, lds_ok)) != hipSuccess)
         return e;
     ProfScope ps(c, MUKV_K_RERANK, st);
-    hipLaunchKernelGGL(select_rerank_kernel, dim3(a.B), dim3(kSelThreads), (size_t)r.cache_cap * 8, st, r);
+    if (a.patches)
+        hipLaunchKernelGGL(select_rerank_kernel<true>, dim3(a.B), dim3(kSelThreads), (size_t)r.cache_cap * 8, st, r);
+    else
+        hipLaunchKernelGGL(select_rerank_kernel<false>, dim3(a.B), dim3(kSelThreads), (size_t)r.cache_cap * 8, st, r);
     return hipGetLastError();
 }
 
