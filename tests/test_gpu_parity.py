@@ -579,3 +579,23 @@ def test_combined_gather_over_the_three_levels(name, frames, kw):
     pout, _ = p.check_retrieve_patches(qs, mk.MUKV_SEMI, 2, 6, 0.3)
     p.check_gather_union(out["seg_idx"].cpu().tolist(), out["frame_idx"].cpu().tolist(), pout["patch_idx"].cpu().tolist())
     p.close()
+
+
+@pytest.mark.parametrize("scale", [1e-3, 30.0, 300.0])
+@pytest.mark.parametrize("name", ["7b", "tiny"])
+def test_extreme_input_magnitudes(name, scale):
+    # logits far outside the comfortable range: near-uniform and near-one-hot softmax rows
+    w = W[name].scaled(n_frames=12, n_layers=2, n_questions=2)
+    p = Pair(w, seed=140, chunk=4, gpu_kw={"batch_chunks": 2})
+    for _ in range(3):
+        k, v, q = p.stream.next_chunk(4)
+        k, v, q = (k.float() * scale).to(k.dtype), (v.float() * scale).to(v.dtype), (q.float() * scale).to(q.dtype)
+        kd, vd, qd = k.cuda(), v.cuda(), q.cuda()
+        p.keep_alive += [kd, vd, qd]
+        p.sig_orc.append(p.orc.compress_chunk(np_view(k), np_view(v), q_last=np_view(q)))
+        p.sig_gpu.append(p.gpu.compress_chunk(kd, vd, qd, want_signals=True))
+    p.check_compress(exact_reps=True, raw_signals=False)   # the fused, normalised scores keep the absolute bar
+    qs = [synth.random_question(w, 9, 990) * scale, synth.random_question(w, 20, 991)]
+    qs = [x.to(w.torch_dtype) for x in qs]
+    p.check_retrieve(qs, mk.MUKV_SEMI, 2, 4, 0.3)
+    p.close()
