@@ -27,7 +27,8 @@
  *    default stream) and is never synchronised by the library.  Calls on one
  *    context must be issued in stream order; the context is not thread-safe.
  *  - After mukv_create no device memory is allocated or freed until
- *    mukv_destroy.
+ *    mukv_destroy.  A call makes the context's device current while it runs
+ *    and gives the caller's current device back.
  *  - MUKV_ERR_HIP from a call that launches kernels leaves the cache in an
  *    unspecified state: destroy the context.  Every other error leaves it as
  *    it was.

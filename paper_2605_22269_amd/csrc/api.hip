@@ -19,6 +19,19 @@ constexpr double kDefaultRefineMargin = 1e-5;
 
 bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
+// Makes the context's device current for the duration of a call and gives the caller's back.
+struct DeviceScope {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceScope(int device) {
+        if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+        ok = hipSetDevice(device) == hipSuccess;
+    }
+    ~DeviceScope() {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
 template <typename T>
 hipError_t dalloc(T **p, size_t count) {
     *p = nullptr;
@@ -52,6 +65,10 @@ int validate_config(const mukv_config *cfg) {
         return MUKV_ERR_UNSUPPORTED;
     if ((cfg->head_dim * esz) % 16) return MUKV_ERR_UNSUPPORTED;
     if (((int64_t)cfg->max_frames + cfg->frames_per_segment - 1) / cfg->frames_per_segment > 65536)
+        return MUKV_ERR_UNSUPPORTED;
+    // block numbers (frame * S + s) and batch token offsets are 32-bit in the kernels
+    if ((int64_t)cfg->max_frames * cfg->superpatches_per_frame > 0x7fffffff ||
+        (int64_t)cfg->max_frames * cfg->tokens_per_frame > 0x7fffffff)
         return MUKV_ERR_UNSUPPORTED;
     return MUKV_OK;
 }
@@ -105,7 +122,8 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     if (cfg->att_path == MUKV_ATT_MFMA && !mfma_supported(*cfg)) return MUKV_ERR_UNSUPPORTED;
     int n_dev = 0;
     if (hipGetDeviceCount(&n_dev) != hipSuccess || cfg->device_id >= n_dev) return MUKV_ERR_HIP;
-    if (hipSetDevice(cfg->device_id) != hipSuccess) return MUKV_ERR_HIP;
+    DeviceScope dev(cfg->device_id);
+    if (!dev.ok) return MUKV_ERR_HIP;
 
     mukv_ctx *h = new (std::nothrow) mukv_ctx();
     if (!h) return MUKV_ERR_HIP;
@@ -191,7 +209,7 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
 
 int mukv_destroy(mukv_ctx *ctx) {
     if (!ctx) return MUKV_OK;
-    (void)hipSetDevice(ctx->c.cfg.device_id);
+    DeviceScope dev(ctx->c.cfg.device_id);
     free_all(ctx->c);
     if (ctx->c.prof) {
         for (auto &p : *ctx->c.prof) {
@@ -236,8 +254,8 @@ int mukv_reset(mukv_ctx *ctx) {
     ctx->c.n_done = 0;
     ctx->c.pending->clear();
     if (ctx->c.deferred_pending) { // the rows it would have copied are forgotten with the rest
-        if (hipSetDevice(ctx->c.cfg.device_id) != hipSuccess || mukv::drop_deferred(ctx->c) != hipSuccess)
-            return MUKV_ERR_HIP;
+        DeviceScope dev(ctx->c.cfg.device_id);
+        if (!dev.ok || mukv::drop_deferred(ctx->c) != hipSuccess) return MUKV_ERR_HIP;
     }
     return MUKV_OK;
 }
@@ -247,7 +265,8 @@ int mukv_reset(mukv_ctx *ctx) {
 static int flush_pending(Ctx &c, bool join, hipStream_t join_stream) {
     if (c.pending->empty()) {
         if (!join) return MUKV_OK;
-        if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
+        DeviceScope dev(c.cfg.device_id);
+    if (!dev.ok) return MUKV_ERR_HIP;
         return mukv::join_streams(c, join_stream) == hipSuccess ? MUKV_OK : MUKV_ERR_HIP;
     }
     mukv::ChunkArgs a;
@@ -280,7 +299,8 @@ static int flush_pending(Ctx &c, bool join, hipStream_t join_stream) {
     a.parity = 0;
     c.pending->clear();
     c.n_done += nf;
-    if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
+    DeviceScope dev(c.cfg.device_id);
+    if (!dev.ok) return MUKV_ERR_HIP;
     if (mukv::launch_compress(c, a, c.p_stream) != hipSuccess) return MUKV_ERR_HIP;
     if (join && mukv::join_streams(c, join_stream) != hipSuccess) return MUKV_ERR_HIP;
     return MUKV_OK;
@@ -380,7 +400,8 @@ static int retrieve_any(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_of
     a.seg_score = seg_score_out;
     a.frm_idx = fine_idx_out;
     a.frm_score = fine_score_out;
-    if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
+    DeviceScope dev(c.cfg.device_id);
+    if (!dev.ok) return MUKV_ERR_HIP;
     return mukv::launch_retrieve(c, a, reinterpret_cast<hipStream_t>(stream)) == hipSuccess ? MUKV_OK : MUKV_ERR_HIP;
 }
 
@@ -413,7 +434,8 @@ int mukv_gather_patches(mukv_ctx *ctx, const int32_t *patch_idx, int32_t B, int3
         const int rc = flush_pending(c, true, reinterpret_cast<hipStream_t>(stream));
         if (rc != MUKV_OK) return rc;
     }
-    if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
+    DeviceScope dev(c.cfg.device_id);
+    if (!dev.ok) return MUKV_ERR_HIP;
     return mukv::launch_gather_patches(c, patch_idx, B, k_patch, order, k_patch * patch_cap(c), k_out, v_out,
                                        n_tokens_out, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
                ? MUKV_OK
@@ -434,7 +456,8 @@ int mukv_gather_kv(mukv_ctx *ctx, const int32_t *frame_idx, int32_t B, int32_t k
         const int rc = flush_pending(c, true, reinterpret_cast<hipStream_t>(stream));
         if (rc != MUKV_OK) return rc;
     }
-    if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
+    DeviceScope dev(c.cfg.device_id);
+    if (!dev.ok) return MUKV_ERR_HIP;
     return mukv::launch_gather(c, frame_idx, B, k_frame, order, k_out, v_out, n_tokens_out,
                                reinterpret_cast<hipStream_t>(stream)) == hipSuccess
                ? MUKV_OK
@@ -447,6 +470,7 @@ int mukv_gather_union(mukv_ctx *ctx, const int32_t *seg_idx, int32_t k_seg, cons
     if (!ctx || !k_out || !v_out) return MUKV_ERR_INVALID_ARG;
     Ctx &c = ctx->c;
     if (B < 1 || rows_cap < 1 || k_seg < 0 || k_frame < 0 || k_patch < 0) return MUKV_ERR_INVALID_ARG;
+    if (k_seg > 65536 || k_frame > (1 << 24) || k_patch > (1 << 24)) return MUKV_ERR_UNSUPPORTED;
     if ((k_seg > 0 && !seg_idx) || (k_frame > 0 && !frame_idx) || (k_patch > 0 && !patch_idx)) return MUKV_ERR_INVALID_ARG;
     if (B > c.cfg.max_questions) return MUKV_ERR_CAPACITY;
     if (c.cfg.superpatches_per_frame > 32) return MUKV_ERR_UNSUPPORTED; // one mask bit per super-patch
@@ -468,7 +492,8 @@ int mukv_gather_union(mukv_ctx *ctx, const int32_t *seg_idx, int32_t k_seg, cons
     a.k_out = k_out;
     a.v_out = v_out;
     a.n_tokens_out = n_tokens_out;
-    if (hipSetDevice(c.cfg.device_id) != hipSuccess) return MUKV_ERR_HIP;
+    DeviceScope dev(c.cfg.device_id);
+    if (!dev.ok) return MUKV_ERR_HIP;
     return mukv::launch_gather_union(c, a, reinterpret_cast<hipStream_t>(stream)) == hipSuccess ? MUKV_OK : MUKV_ERR_HIP;
 }
 
