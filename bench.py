@@ -392,6 +392,18 @@ def main():
         for kn, vn, qn in host:
             ref.compress_chunk(kn, vn, q_last=qn)
         t_cpu = time.perf_counter() - t0
+        # the same on one host thread, on a sample an order of magnitude smaller
+        n_all = int(orc.lib().orc_num_threads())
+        orc.lib().orc_set_num_threads(1)
+        ref1 = orc.OracleMuKV(orc.OracleConfig(L, Hq, Hkv, D, P, w.frames_per_segment, w.superpatches_per_frame,
+                                               w.keep_ratio, w.alpha))
+        t0 = time.perf_counter()
+        for kn, vn, qn in host[: max(1, 128 // chunk)]:
+            ref1.compress_chunk(kn, vn, q_last=qn)
+        t_one = time.perf_counter() - t0
+        orc.lib().orc_set_num_threads(n_all)
+        res["cpu_baseline_one_thread"] = {"value": ref1.n_frames * P / t_one, "unit": "visual tokens/s", "cores": 1,
+                                          "kind": "oracle", "sample": f"first {ref1.n_frames} frames ({t_one:.1f} s)"}
         res["cpu_baseline"] = {"value": ref.n_frames * P / t_cpu, "unit": "visual tokens/s",
                                "cores": int(orc.lib().orc_num_threads()), "kind": "oracle",
                                "sample": f"first {ref.n_frames} frames of the same stream through the oracle's "

@@ -43,6 +43,16 @@ static double widen(const void *base, int dtype, int64_t i)
     return (double)((const float *)base)[i];
 }
 
+/* Sets the number of host threads the loops over frames / blocks may use (n >= 1). */
+void orc_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int orc_num_threads(void)
 {
     int n = 1;
