@@ -262,6 +262,20 @@ int mukv_retrieve_patches(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_
                           void *stream);
 
 /*
+ * The search for questions asked at different times (the streaming setting of
+ * Sec. 3.1: a question is answered from the content before its timestamp).
+ * Question b sees frames < n_visible[b] (device int32 [B]; a negative value or
+ * one past the ingested frames means all of them); params->n_visible_frames
+ * is ignored.  A segment cut by a question's timestamp is re-pooled from its
+ * visible frames for that question.  level 0: frames are the fine level
+ * (mukv_retrieve), 1: super-patches (mukv_retrieve_patches).  seg_idx_out /
+ * seg_score_out may be NULL.  Everything else as in mukv_retrieve.
+ */
+int mukv_retrieve_at(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, const int32_t *n_visible, int32_t B,
+                     const mukv_retrieve_params *params, int32_t level, int32_t *seg_idx_out, float *seg_score_out,
+                     int32_t *fine_idx_out, float *fine_score_out, void *stream);
+
+/*
  * Packs the stored K,V of the selected super-patches of each question into a
  * dense decode context: for every patch the kept rows whose position lies in it
  * (a dense run inside its frame's rows), patches in ascending id (MUKV_TEMPORAL)

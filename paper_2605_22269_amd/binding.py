@@ -69,7 +69,7 @@ class mukv_profile(C.Structure):
 
 
 EXPORTS = ("mukv_create", "mukv_destroy", "mukv_reset", "mukv_flush", "mukv_compress_chunk", "mukv_retrieve",
-           "mukv_retrieve_patches", "mukv_gather_kv", "mukv_gather_patches", "mukv_gather_union", "mukv_profile_begin", "mukv_profile_end",
+           "mukv_retrieve_patches", "mukv_retrieve_at", "mukv_gather_kv", "mukv_gather_patches", "mukv_gather_union", "mukv_profile_begin", "mukv_profile_end",
            "mukv_plain_copy", "mukv_get_state", "mukv_strerror")
 
 _lib = None
@@ -95,6 +95,7 @@ def load():
     lib.mukv_gather_kv.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.mukv_retrieve_patches.argtypes = [vp, vp, vp, i32, C.POINTER(mukv_retrieve_params), vp, vp, vp]
     lib.mukv_gather_patches.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
+    lib.mukv_retrieve_at.argtypes = [vp, vp, vp, vp, i32, C.POINTER(mukv_retrieve_params), i32, vp, vp, vp, vp, vp]
     lib.mukv_gather_union.argtypes = [vp, vp, i32, vp, i32, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.mukv_get_state.argtypes = [vp, C.POINTER(mukv_state)]
     lib.mukv_plain_copy.argtypes = [vp, vp, C.c_int64, vp]
@@ -156,6 +157,11 @@ def mukv_gather_kv(h, idx_ptr, B, k_frame, order, k_out, v_out, n_tok, stream):
 def mukv_retrieve_patches(h, q_ptr, off_ptr, B, params, patch_idx, patch_score, stream):
     _check(load().mukv_retrieve_patches(h, q_ptr, off_ptr, B, C.byref(params), patch_idx, patch_score, stream),
            "mukv_retrieve_patches")
+
+
+def mukv_retrieve_at(h, q_ptr, off_ptr, nv_ptr, B, params, level, seg_idx, seg_score, fine_idx, fine_score, stream):
+    _check(load().mukv_retrieve_at(h, q_ptr, off_ptr, nv_ptr, B, C.byref(params), level, seg_idx, seg_score, fine_idx,
+                                   fine_score, stream), "mukv_retrieve_at")
 
 
 def mukv_gather_patches(h, idx_ptr, B, k_patch, order, k_out, v_out, n_tok, stream):
@@ -309,6 +315,27 @@ class MuKV:
                    "patch_score": torch.empty(B, k_patch, dtype=torch.float32, device=dev)}
         mukv_retrieve_patches(self.h, _ptr(q_tokens), _ptr(q_offsets), B, prm, _ptr(out["patch_idx"]),
                               _ptr(out["patch_score"]), _stream())
+        self._held.clear()
+        return out
+
+    def retrieve_at(self, q_tokens, q_offsets, n_visible, *, level="frame", mode=MUKV_SEMI, k_seg=8, k_fine=32,
+                    lambda_fine=0.3, n_global=0):
+        """retrieve() / retrieve_patches() for questions asked at different times: n_visible is an
+        int32 tensor [B] on the device, question b sees frames < n_visible[b]."""
+        assert q_tokens.is_contiguous() and q_tokens.dtype == self.dtype
+        assert q_offsets.dtype == torch.int32 and q_offsets.is_cuda
+        assert n_visible.dtype == torch.int32 and n_visible.is_cuda and n_visible.is_contiguous()
+        B = q_offsets.numel() - 1
+        assert n_visible.numel() == B
+        prm = mukv_retrieve_params(mode, k_seg, k_fine, n_global, -1, 0, lambda_fine)
+        dev = q_tokens.device
+        out = {"seg_idx": torch.empty(B, k_seg, dtype=torch.int32, device=dev),
+               "seg_score": torch.empty(B, k_seg, dtype=torch.float32, device=dev),
+               "fine_idx": torch.empty(B, k_fine, dtype=torch.int32, device=dev),
+               "fine_score": torch.empty(B, k_fine, dtype=torch.float32, device=dev)}
+        mukv_retrieve_at(self.h, _ptr(q_tokens), _ptr(q_offsets), _ptr(n_visible), B, prm, 1 if level == "patch" else 0,
+                         _ptr(out["seg_idx"]), _ptr(out["seg_score"]), _ptr(out["fine_idx"]), _ptr(out["fine_score"]),
+                         _stream())
         self._held.clear()
         return out
 

@@ -191,7 +191,7 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(dalloc(&c.qq, MQ * cfg->n_kv_heads));
     ok(dalloc(&c.s_frm, MQ * MF * S)); // room for the super-patch level
     ok(dalloc(&c.s_seg, MQ * (size_t)c.max_segments));
-    ok(dalloc(&c.seg_tail, 2 * C));
+    ok(dalloc(&c.seg_tail, MQ * C));
     ok(dalloc(&c.u_mask, MQ * MF));
     ok(dalloc(&c.u_entry, MQ * MF * 3));
     ok(dalloc(&c.u_count, MQ * 2));
@@ -371,7 +371,7 @@ int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_
     return MUKV_OK;
 }
 
-static int retrieve_any(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, int32_t B,
+static int retrieve_any(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, const int32_t *n_visible, int32_t B,
                         const mukv_retrieve_params *params, bool patches, int32_t *seg_idx_out, float *seg_score_out,
                         int32_t *fine_idx_out, float *fine_score_out, void *stream) {
     if (!ctx || !q_tokens || !q_offsets || !params || !fine_idx_out) return MUKV_ERR_INVALID_ARG;
@@ -392,7 +392,8 @@ static int retrieve_any(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_of
     a.B = B;
     a.p = *params;
     int64_t nv = params->n_visible_frames < 0 ? c.n_frames : params->n_visible_frames;
-    if (nv > c.n_frames) nv = c.n_frames;
+    if (nv > c.n_frames || n_visible) nv = c.n_frames; // per-question timestamps: every ingested frame is scored
+    a.nv_q = n_visible;
     a.nv = (int)nv;
     a.ns = (int)((nv + c.cfg.frames_per_segment - 1) / c.cfg.frames_per_segment);
     a.patches = patches;
@@ -409,15 +410,23 @@ int mukv_retrieve(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets,
                   const mukv_retrieve_params *params, int32_t *seg_idx_out, float *seg_score_out,
                   int32_t *frame_idx_out, float *frame_score_out, void *stream) {
     if (!seg_idx_out) return MUKV_ERR_INVALID_ARG;
-    return retrieve_any(ctx, q_tokens, q_offsets, B, params, false, seg_idx_out, seg_score_out, frame_idx_out,
+    return retrieve_any(ctx, q_tokens, q_offsets, nullptr, B, params, false, seg_idx_out, seg_score_out, frame_idx_out,
                         frame_score_out, stream);
 }
 
 int mukv_retrieve_patches(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, int32_t B,
                           const mukv_retrieve_params *params, int32_t *patch_idx_out, float *patch_score_out,
                           void *stream) {
-    return retrieve_any(ctx, q_tokens, q_offsets, B, params, true, nullptr, nullptr, patch_idx_out, patch_score_out,
-                        stream);
+    return retrieve_any(ctx, q_tokens, q_offsets, nullptr, B, params, true, nullptr, nullptr, patch_idx_out,
+                        patch_score_out, stream);
+}
+
+int mukv_retrieve_at(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, const int32_t *n_visible, int32_t B,
+                     const mukv_retrieve_params *params, int32_t level, int32_t *seg_idx_out, float *seg_score_out,
+                     int32_t *fine_idx_out, float *fine_score_out, void *stream) {
+    if (!n_visible || (level != 0 && level != 1)) return MUKV_ERR_INVALID_ARG;
+    return retrieve_any(ctx, q_tokens, q_offsets, n_visible, B, params, level == 1, seg_idx_out, seg_score_out, fine_idx_out,
+                        fine_score_out, stream);
 }
 
 int mukv_gather_patches(mukv_ctx *ctx, const int32_t *patch_idx, int32_t B, int32_t k_patch, int32_t order,

@@ -77,7 +77,7 @@ struct Ctx {
     double *qq;      // [max_questions][Hkv]   partial squared norms of the mean query
     double *s_frm;   // [max_questions][max_frames]
     double *s_seg;   // [max_questions][max_segments]
-    float *seg_tail; // [2][c_kv] key (K, V) of a segment cut by the question's timestamp
+    float *seg_tail; // [max_questions][c_kv] key of the segment cut by a question's timestamp
     // combined gather scratch (device)
     uint32_t *u_mask;  // [max_questions][max_frames] super-patches of a frame chosen at any level
     int32_t *u_entry;  // [max_questions][max_frames][3] chosen frames in time order: frame, mask, first output row
@@ -134,6 +134,7 @@ struct RetrieveArgs {
     int nv;      // visible frames
     int ns;      // visible segments
     bool patches; // fine level of the search: super-patches instead of frames (k_frame, lambda_frame apply to it)
+    const int32_t *nv_q; // device [B] per-question timestamps, or null (then nv / ns hold for every question)
     int32_t *seg_idx;
     float *seg_score;
     int32_t *frm_idx;

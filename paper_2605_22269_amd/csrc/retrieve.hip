@@ -186,6 +186,56 @@ __global__ __launch_bounds__(256) void seg_tail_kernel(ScoreArgs a) {
     }
 }
 
+// Per-question timestamps: the scoring kernels have scored every ingested block with its full
+// key; question b, which sees frames < nv_q[b], may cut one segment.  One workgroup per question
+// rebuilds that segment's key from the exact per-frame sums of its visible frames (kept for the
+// rerank kernel in seg_tail[b]) and replaces its score.
+struct TailArgs {
+    const int32_t *nv_q;
+    int n_all, F, kappa, C, Hkv, G;
+    const double *fsum, *qbar, *qq;
+    double *s_seg;
+    int64_t ld_seg;
+    float *seg_tail;
+};
+
+__global__ __launch_bounds__(256) void tail_fix_kernel(TailArgs a) {
+    __shared__ double red[8];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    int nvb = a.nv_q[b];
+    nvb = (nvb < 0 || nvb > a.n_all) ? a.n_all : nvb;
+    const int ns = (nvb + a.F - 1) / a.F;
+    const int seg_end = ns * a.F < a.n_all ? ns * a.F : a.n_all;
+    if (ns == 0 || nvb >= seg_end) return; // uniform over the workgroup
+    const int f0 = (ns - 1) * a.F;
+    const double den = (double)(nvb - f0) * (double)a.kappa;
+    double dot = 0.0, rr = 0.0;
+    for (int c = tid; c < a.C; c += 256) {
+        double s = 0.0;
+        for (int f = f0; f < nvb; ++f) s += a.fsum[(int64_t)f * a.C + c];
+        const float key = (float)(s / den);
+        a.seg_tail[(int64_t)b * a.C + c] = key;
+        dot += (double)key * a.qbar[(int64_t)b * a.C + c];
+        rr += (double)key * (double)key;
+    }
+    dot = wave_sum(dot);
+    rr = wave_sum(rr);
+    if ((tid & 63) == 0) {
+        red[tid >> 6] = dot;
+        red[4 + (tid >> 6)] = rr;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        dot = (red[0] + red[1]) + (red[2] + red[3]);
+        rr = (red[4] + red[5]) + (red[6] + red[7]);
+        double qn = 0.0;
+        for (int g = 0; g < a.Hkv; ++g) qn += a.qq[(int64_t)b * a.Hkv + g];
+        double sc = 0.0;
+        if (rr > 0.0 && qn > 0.0) sc = dot / (sqrt(qn) * sqrt((double)a.G * rr));
+        a.s_seg[(int64_t)b * a.ld_seg + ns - 1] = sc;
+    }
+}
+
 // grid.x: the frame tiles, then the segment tiles (16 keys each)
 __global__ __launch_bounds__(256) void score_blocks_mfma_kernel(ScoreArgs a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -531,6 +581,8 @@ struct RerankArgs {
     int nv, ns, C, F, tail_cut;
     int mode, k_seg, k_frame, n_global;
     const int32_t *cnt; // fine level = super-patches: kept tokens per super-patch (empty ones are never chosen); else null
+    const int32_t *nv_q; // per-question timestamps (visible frames), or null: nv / ns / tail_cut above hold for all
+    int n_all, kpf, Ff;  // ingested frames, fine keys per frame, frames per segment (used with nv_q)
     int cache_cap; // entries of the LDS key cache (dynamic shared memory)
     double lambda;
     int32_t *seg_idx, *frm_idx;
@@ -554,6 +606,15 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
     uint64_t *kcache = reinterpret_cast<uint64_t *>(smem_raw); // [a.cache_cap]
     const int cap = a.cache_cap;
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (a.nv_q) { // this question's own timestamp: what it sees, and whether it cuts a segment
+        int nvb = a.nv_q[b];
+        nvb = (nvb < 0 || nvb > a.n_all) ? a.n_all : nvb;
+        a.nv = nvb * a.kpf;
+        a.ns = (nvb + a.Ff - 1) / a.Ff;
+        const int seg_end = a.ns * a.Ff < a.n_all ? a.ns * a.Ff : a.n_all;
+        a.tail_cut = (a.ns > 0 && nvb < seg_end) ? 1 : 0;
+        a.seg_tail += (int64_t)b * a.C;
+    }
     const double *s_frm = a.s_frm + (int64_t)b * a.ld_frm;
     const double *s_seg = a.s_seg + (int64_t)b * a.ld_seg;
     int32_t *seg_out = a.seg_idx + (int64_t)b * a.k_seg;
@@ -1047,7 +1108,9 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
 
     const int F = c.cfg.frames_per_segment;
     const int64_t seg_end = (int64_t)a.ns * F < c.n_frames ? (int64_t)a.ns * F : c.n_frames;
-    const int tail_cut = (a.ns > 0 && a.nv < seg_end) ? 1 : 0;
+    // per-question timestamps (a.nv_q): a.nv / a.ns cover every ingested frame, all keys are scored
+    // in full and tail_fix_kernel repairs the one segment each question may cut
+    const int tail_cut = (!a.nv_q && a.ns > 0 && a.nv < seg_end) ? 1 : 0;
     // fine level: the frames, or (a.patches) their super-patches -- the same kernels on the other
     // key table, S keys per frame
     const int kpf = a.patches ? c.cfg.superpatches_per_frame : 1;
@@ -1085,6 +1148,24 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
             hipLaunchKernelGGL(score_blocks_kernel, dim3((nf + a.ns + 3) / 4), dim3(256), 0, st, s);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
+        if (a.nv_q) {
+            TailArgs t;
+            t.nv_q = a.nv_q;
+            t.n_all = (int)c.n_frames;
+            t.F = F;
+            t.kappa = c.kappa;
+            t.C = c.c_kv;
+            t.Hkv = Hkv;
+            t.G = G;
+            t.fsum = c.fsum_k;
+            t.qbar = c.qbar;
+            t.qq = c.qq;
+            t.s_seg = c.s_seg;
+            t.ld_seg = c.max_segments;
+            t.seg_tail = c.seg_tail;
+            hipLaunchKernelGGL(tail_fix_kernel, dim3(a.B), dim3(256), 0, st, t);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
     }
     RerankArgs r;
     r.s_frm = c.s_frm;
@@ -1099,6 +1180,10 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
     r.C = c.c_kv;
     r.F = F * kpf; // fine keys per segment
     r.cnt = a.patches ? c.cnt_patch : nullptr;
+    r.nv_q = a.nv_q;
+    r.n_all = (int)c.n_frames;
+    r.kpf = kpf;
+    r.Ff = F;
     r.tail_cut = tail_cut;
     r.mode = a.p.mode;
     r.k_seg = a.p.k_seg;

@@ -163,6 +163,24 @@ class Pair:
                 res.append(r)
         return out, res
 
+    def check_retrieve_at(self, questions, n_visible, level, mode, k_seg, k_fine, lambda_fine=0.3):
+        """Questions with their own timestamps in one call against one oracle call per question."""
+        tol = TOL[self.w.dtype]
+        offs = np.zeros(len(questions) + 1, np.int32)
+        offs[1:] = np.cumsum([q.shape[0] for q in questions])
+        qt = torch.cat(questions).cuda().contiguous()
+        nv = torch.tensor(n_visible, dtype=torch.int32, device="cuda")
+        out = self.gpu.retrieve_at(qt, torch.from_numpy(offs).cuda(), nv, level=level, mode=mode, k_seg=k_seg, k_fine=k_fine,
+                                   lambda_fine=lambda_fine)
+        torch.cuda.synchronize()
+        for b, q in enumerate(questions):
+            r = self.orc.retrieve(np_view(q), orc.RetrieveParams(mode, k_seg, k_fine, lambda_fine, 0, n_visible[b]), level=level)
+            np.testing.assert_array_equal(out["seg_idx"][b].cpu().numpy(), r["seg_idx"], err_msg=f"question {b}")
+            np.testing.assert_array_equal(out["fine_idx"][b].cpu().numpy(), r["frame_idx"], err_msg=f"question {b}")
+            assert np.abs(out["seg_score"][b].cpu().numpy() - r["seg_score"]).max() <= min(tol, 1e-5)
+            assert np.abs(out["fine_score"][b].cpu().numpy() - r["frame_score"]).max() <= min(tol, 1e-5)
+        return out
+
     def check_gather_union(self, seg_idx, frame_idx, patch_idx, rows_cap=None):
         """Lists of per-question index lists (or None).  Bytes and counts exact."""
         def dev(x):

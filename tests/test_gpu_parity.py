@@ -599,3 +599,20 @@ def test_extreme_input_magnitudes(name, scale):
     qs = [x.to(w.torch_dtype) for x in qs]
     p.check_retrieve(qs, mk.MUKV_SEMI, 2, 4, 0.3)
     p.close()
+
+
+@pytest.mark.parametrize("name,frames,nq", [("7b", 45, 5), ("tiny", 61, 20), ("72b", 40, 17)])
+def test_questions_with_their_own_timestamps(name, frames, nq):
+    # one call, every question at another time: before the first segment ends, on a segment
+    # boundary, inside a segment, at the end, "everything" (-1); fewer than 16 and 16+ questions
+    w = W[name].scaled(n_frames=frames, n_layers=2, n_questions=nq)
+    p = Pair(w, seed=150, chunk=8)
+    p.ingest()
+    F = w.frames_per_segment
+    base = [3, F, F + 1, 2 * F, frames - 1, frames, -1, 1, 2 * F + F // 2]
+    nvs = [base[i % len(base)] if base[i % len(base)] <= frames else frames for i in range(nq)]
+    qs = questions_for(w, [4 + (3 * i) % 25 for i in range(nq)], 1000)
+    for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
+        p.check_retrieve_at(qs, nvs, "frame", mode, 2, 5)
+        p.check_retrieve_at(qs, nvs, "patch", mode, 2, 7)
+    p.close()
