@@ -261,6 +261,9 @@ def main():
                             "traffic": gather_bytes * TRAFFIC_PER_ALGORITHMIC["gather"],
                             "bytes_per_launch": gather_bytes, "us_per_launch": gather_us},
         "setup_s": {"generate_stream": t_gen},
+        # the paper's device-independent proxies (Sec. 4.1): tokens held in the cache, tokens handed to the LLM
+        "memory_tokens": n_frames * kappa,
+        "inference_tokens_per_question": w.k_frame * kappa,
         # context only, not comparable: end to end including the LLM's answer decoding
         "paper_context": {"source": "real-deployment table of the paper (Sec. 4)", "hardware": "1x NVIDIA A5000 24 GB",
                           "seconds_per_question_incl_llm_decode": {"ReKV": 0.92, "MuKV uncompressed": 0.72,

@@ -616,3 +616,51 @@ def test_questions_with_their_own_timestamps(name, frames, nq):
         p.check_retrieve_at(qs, nvs, "frame", mode, 2, 5)
         p.check_retrieve_at(qs, nvs, "patch", mode, 2, 7)
     p.close()
+
+
+def test_outputs_stay_inside_their_buffers():
+    # every output sits between guard words; the calls may not touch them
+    w = W["7b"].scaled(n_frames=24, n_layers=2, n_questions=3)
+    p = Pair(w, seed=160, chunk=8)
+    p.ingest()
+    g = p.gpu
+    qs = questions_for(w, [8, 3, 20], 1100)
+    offs = torch.tensor([0, 8, 11, 31], dtype=torch.int32, device="cuda")
+    qt = torch.cat(qs).cuda().contiguous()
+    GUARD = 64
+
+    def guarded(n, dtype):
+        buf = torch.full((n + 2 * GUARD,), -77, dtype=dtype, device="cuda")
+        return buf, buf[GUARD:GUARD + n]
+
+    def intact(buf):
+        assert bool((buf[:GUARD] == -77).all()) and bool((buf[-GUARD:] == -77).all())
+
+    bufs = {}
+    out = {}
+    for name, n, dt in (("seg_idx", 3 * 2, torch.int32), ("seg_score", 3 * 2, torch.float32),
+                        ("frame_idx", 3 * 5, torch.int32), ("frame_score", 3 * 5, torch.float32)):
+        bufs[name], view = guarded(n, dt)
+        out[name] = view.view(3, -1)
+    g.retrieve(qt, offs, mode=mk.MUKV_SEMI, k_seg=2, k_frame=5, out=out)
+    pout = {}
+    for name, n, dt in (("patch_idx", 3 * 7, torch.int32), ("patch_score", 3 * 7, torch.float32)):
+        bufs[name], view = guarded(n, dt)
+        pout[name] = view.view(3, -1)
+    g.retrieve_patches(qt, offs, mode=mk.MUKV_SEMI, k_seg=2, k_patch=7, out=pout)
+    L, Hkv, D, kap = w.n_layers, w.n_kv_heads, w.head_dim, g.kappa
+
+    def kv_out(rows, tag):
+        n = 3 * L * Hkv * rows * D
+        bufs[tag + "k"], kview = guarded(n, w.torch_dtype)
+        bufs[tag + "v"], vview = guarded(n, w.torch_dtype)
+        bufs[tag + "n"], nview = guarded(3, torch.int32)
+        return kview.view(3, L, Hkv, rows, D), vview.view(3, L, Hkv, rows, D), nview
+
+    g.gather_kv(out["frame_idx"], out=kv_out(5 * kap, "g"))
+    g.gather_patches(pout["patch_idx"], out=kv_out(7 * g.patch_cap, "p"))
+    g.gather_union(out["seg_idx"], out["frame_idx"], pout["patch_idx"], rows_cap=3 * kap + 5, out=kv_out(3 * kap + 5, "u"))
+    torch.cuda.synchronize()
+    for b in bufs.values():
+        intact(b)
+    p.close()
