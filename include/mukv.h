@@ -293,6 +293,30 @@ int mukv_gather_patches(mukv_ctx *ctx, const int32_t *patch_idx, int32_t B, int3
                         void *k_out, void *v_out, int32_t *n_tokens_out, void *stream);
 
 /*
+ * Snapshot of the cache (the offline memory of Sec. 3.3 is persistent state):
+ * the kept K/V rows, kept positions, block keys and running segment sums of
+ * the frames ingested so far, in one host buffer, so that a stream can be
+ * resumed in another context of the same configuration.  These three calls
+ * are for set-up and tear-down, not for the hot path: save and load copy
+ * between device and host on `stream` and SYNCHRONISE it before returning.
+ *
+ *   mukv_snapshot_size  bytes a snapshot of the current content needs
+ *   mukv_snapshot_save  host_dst: host buffer of at least that size.  Gathered
+ *                       chunks are launched first.  CAPACITY if too small.
+ *   mukv_snapshot_load  host_src: a buffer written by mukv_snapshot_save.  The
+ *                       context's content is replaced (after a wait for all
+ *                       work on the device); afterwards the stream
+ *                       continues at the snapshot's frame count.  SHAPE if
+ *                       the configurations differ (layers, heads, D, P, F, S,
+ *                       dtype, kappa, scoring layer), CAPACITY if the
+ *                       snapshot holds more than max_frames frames,
+ *                       INVALID_ARG if the buffer is not a snapshot.
+ */
+int mukv_snapshot_size(const mukv_ctx *ctx, int64_t *bytes_out);
+int mukv_snapshot_save(mukv_ctx *ctx, void *host_dst, int64_t bytes, void *stream);
+int mukv_snapshot_load(mukv_ctx *ctx, const void *host_src, int64_t bytes, void *stream);
+
+/*
  * Combined gather over the three granularities of Sec. 3.4: the kept rows of
  * every frame of the selected segments, of the selected frames and of the
  * selected super-patches, every row once, in temporal order (ascending frame,

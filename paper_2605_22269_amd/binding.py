@@ -69,7 +69,8 @@ class mukv_profile(C.Structure):
 
 
 EXPORTS = ("mukv_create", "mukv_destroy", "mukv_reset", "mukv_flush", "mukv_compress_chunk", "mukv_retrieve",
-           "mukv_retrieve_patches", "mukv_retrieve_at", "mukv_gather_kv", "mukv_gather_patches", "mukv_gather_union", "mukv_profile_begin", "mukv_profile_end",
+           "mukv_retrieve_patches", "mukv_retrieve_at", "mukv_gather_kv", "mukv_gather_patches", "mukv_gather_union",
+           "mukv_snapshot_size", "mukv_snapshot_save", "mukv_snapshot_load", "mukv_profile_begin", "mukv_profile_end",
            "mukv_plain_copy", "mukv_get_state", "mukv_strerror")
 
 _lib = None
@@ -97,6 +98,9 @@ def load():
     lib.mukv_gather_patches.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.mukv_retrieve_at.argtypes = [vp, vp, vp, vp, i32, C.POINTER(mukv_retrieve_params), i32, vp, vp, vp, vp, vp]
     lib.mukv_gather_union.argtypes = [vp, vp, i32, vp, i32, vp, i32, i32, i32, vp, vp, vp, vp]
+    lib.mukv_snapshot_size.argtypes = [vp, C.POINTER(C.c_int64)]
+    lib.mukv_snapshot_save.argtypes = [vp, vp, C.c_int64, vp]
+    lib.mukv_snapshot_load.argtypes = [vp, vp, C.c_int64, vp]
     lib.mukv_get_state.argtypes = [vp, C.POINTER(mukv_state)]
     lib.mukv_plain_copy.argtypes = [vp, vp, C.c_int64, vp]
     lib.mukv_profile_begin.argtypes = [vp]
@@ -171,6 +175,20 @@ def mukv_gather_patches(h, idx_ptr, B, k_patch, order, k_out, v_out, n_tok, stre
 def mukv_gather_union(h, seg_ptr, k_seg, frm_ptr, k_frame, pat_ptr, k_patch, B, rows_cap, k_out, v_out, n_tok, stream):
     _check(load().mukv_gather_union(h, seg_ptr, k_seg, frm_ptr, k_frame, pat_ptr, k_patch, B, rows_cap, k_out, v_out, n_tok,
                                     stream), "mukv_gather_union")
+
+
+def mukv_snapshot_size(h) -> int:
+    n = C.c_int64()
+    _check(load().mukv_snapshot_size(h, C.byref(n)), "mukv_snapshot_size")
+    return n.value
+
+
+def mukv_snapshot_save(h, host_ptr, n_bytes, stream):
+    _check(load().mukv_snapshot_save(h, host_ptr, n_bytes, stream), "mukv_snapshot_save")
+
+
+def mukv_snapshot_load(h, host_ptr, n_bytes, stream):
+    _check(load().mukv_snapshot_load(h, host_ptr, n_bytes, stream), "mukv_snapshot_load")
 
 
 def mukv_profile_begin(h):
@@ -256,6 +274,19 @@ class MuKV:
     @property
     def n_frames(self):
         return mukv_get_state(self.h).n_frames
+
+    def snapshot(self):
+        """The cache's content as a host uint8 tensor (mukv_snapshot_save)."""
+        buf = torch.empty(mukv_snapshot_size(self.h), dtype=torch.uint8)
+        mukv_snapshot_save(self.h, C.c_void_p(buf.data_ptr()), buf.numel(), _stream())
+        self._held.clear()
+        return buf
+
+    def restore(self, buf):
+        """Replaces the content by a snapshot taken from a context of the same configuration."""
+        assert buf.device.type == "cpu" and buf.dtype == torch.uint8 and buf.is_contiguous()
+        mukv_snapshot_load(self.h, C.c_void_p(buf.data_ptr()), buf.numel(), _stream())
+        self._held.clear()
 
     def compress_chunk(self, k, v, q_last=None, att_signal=None, want_signals=False):
         """k, v: [L][Hkv][n*P][D] (any layer/head/token strides, D contiguous);

@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "mukv_internal.h"
 
@@ -99,6 +100,73 @@ void free_all(Ctx &c) {
     if (c.ev_copy) (void)hipEventDestroy(c.ev_copy);
 }
 
+} // namespace
+
+// ---- snapshot of the cache: header, then every table trimmed to the frames it holds ----
+namespace {
+struct SnapHeader {
+    char magic[8]; // "MUKVSNP1"
+    int32_t n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, frames_per_segment, superpatches_per_frame, dtype;
+    int32_t kappa, score_layer;
+    int64_t n_frames;
+};
+
+// the pieces of the cache in file order: device pointer, bytes used by n frames, stride between
+// `count` such pieces on the device (the store is one piece per (layer, head) slab)
+struct SnapPiece {
+    void *dev;
+    size_t bytes, stride;
+    int count;
+};
+
+std::vector<SnapPiece> snap_pieces(const Ctx &c, int64_t n) {
+    const size_t C = c.c_kv, S = c.cfg.superpatches_per_frame, row_b = (size_t)c.cfg.head_dim * c.esz;
+    const size_t ns = (size_t)((n + c.cfg.frames_per_segment - 1) / c.cfg.frames_per_segment);
+    const int slabs = c.cfg.n_layers * c.cfg.n_kv_heads;
+    const size_t un = (size_t)n;
+    return {
+        {c.store_k, un * c.kappa * row_b, (size_t)c.store_cap * row_b, slabs},
+        {c.store_v, un * c.kappa * row_b, (size_t)c.store_cap * row_b, slabs},
+        {c.kept_idx, un * c.kappa * 4, 0, 1},
+        {c.rep_frame_k, un * C * 4, 0, 1},
+        {c.rep_frame_v, un * C * 4, 0, 1},
+        {c.rep_patch_k, un * S * C * 4, 0, 1},
+        {c.rep_patch_v, un * S * C * 4, 0, 1},
+        {c.cnt_patch, un * S * 4, 0, 1},
+        {c.rep_seg_k, ns * C * 4, 0, 1},
+        {c.rep_seg_v, ns * C * 4, 0, 1},
+        {c.fsum_k, un * C * 8, 0, 1},
+        {c.fsum_v, un * C * 8, 0, 1},
+        {c.ssum_k, ns * C * 8, 0, 1},
+        {c.ssum_v, ns * C * 8, 0, 1},
+        {c.margin, un * 4, 0, 1},
+        {c.refined, un * 4, 0, 1},
+    };
+}
+
+int64_t snap_bytes(const Ctx &c, int64_t n) {
+    int64_t total = (int64_t)sizeof(SnapHeader);
+    for (const SnapPiece &p : snap_pieces(c, n)) total += (int64_t)p.bytes * p.count;
+    return total;
+}
+
+SnapHeader snap_header(const Ctx &c) {
+    SnapHeader h;
+    std::memset(&h, 0, sizeof h);
+    std::memcpy(h.magic, "MUKVSNP1", 8);
+    h.n_layers = c.cfg.n_layers;
+    h.n_q_heads = c.cfg.n_q_heads;
+    h.n_kv_heads = c.cfg.n_kv_heads;
+    h.head_dim = c.cfg.head_dim;
+    h.tokens_per_frame = c.cfg.tokens_per_frame;
+    h.frames_per_segment = c.cfg.frames_per_segment;
+    h.superpatches_per_frame = c.cfg.superpatches_per_frame;
+    h.dtype = c.cfg.dtype;
+    h.kappa = c.kappa;
+    h.score_layer = c.ls;
+    h.n_frames = c.n_frames;
+    return h;
+}
 } // namespace
 
 extern "C" {
@@ -266,7 +334,7 @@ static int flush_pending(Ctx &c, bool join, hipStream_t join_stream) {
     if (c.pending->empty()) {
         if (!join) return MUKV_OK;
         DeviceScope dev(c.cfg.device_id);
-    if (!dev.ok) return MUKV_ERR_HIP;
+        if (!dev.ok) return MUKV_ERR_HIP;
         return mukv::join_streams(c, join_stream) == hipSuccess ? MUKV_OK : MUKV_ERR_HIP;
     }
     mukv::ChunkArgs a;
@@ -504,6 +572,76 @@ int mukv_gather_union(mukv_ctx *ctx, const int32_t *seg_idx, int32_t k_seg, cons
     DeviceScope dev(c.cfg.device_id);
     if (!dev.ok) return MUKV_ERR_HIP;
     return mukv::launch_gather_union(c, a, reinterpret_cast<hipStream_t>(stream)) == hipSuccess ? MUKV_OK : MUKV_ERR_HIP;
+}
+
+int mukv_snapshot_size(const mukv_ctx *ctx, int64_t *bytes_out) {
+    if (!ctx || !bytes_out) return MUKV_ERR_INVALID_ARG;
+    *bytes_out = snap_bytes(ctx->c, ctx->c.n_frames);
+    return MUKV_OK;
+}
+
+int mukv_snapshot_save(mukv_ctx *ctx, void *host_dst, int64_t bytes, void *stream) {
+    if (!ctx || !host_dst) return MUKV_ERR_INVALID_ARG;
+    Ctx &c = ctx->c;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    {
+        const int rc = flush_pending(c, true, st);
+        if (rc != MUKV_OK) return rc;
+    }
+    if (bytes < snap_bytes(c, c.n_frames)) return MUKV_ERR_CAPACITY;
+    DeviceScope dev(c.cfg.device_id);
+    if (!dev.ok) return MUKV_ERR_HIP;
+    unsigned char *out = static_cast<unsigned char *>(host_dst);
+    const SnapHeader h = snap_header(c);
+    std::memcpy(out, &h, sizeof h);
+    out += sizeof h;
+    for (const SnapPiece &p : snap_pieces(c, c.n_frames))
+        for (int i = 0; i < p.count; ++i) {
+            if (p.bytes &&
+                hipMemcpyAsync(out, static_cast<unsigned char *>(p.dev) + (size_t)i * p.stride, p.bytes,
+                               hipMemcpyDeviceToHost, st) != hipSuccess)
+                return MUKV_ERR_HIP;
+            out += p.bytes;
+        }
+    return hipStreamSynchronize(st) == hipSuccess ? MUKV_OK : MUKV_ERR_HIP;
+}
+
+int mukv_snapshot_load(mukv_ctx *ctx, const void *host_src, int64_t bytes, void *stream) {
+    if (!ctx || !host_src || bytes < (int64_t)sizeof(SnapHeader)) return MUKV_ERR_INVALID_ARG;
+    Ctx &c = ctx->c;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    SnapHeader h;
+    std::memcpy(&h, host_src, sizeof h);
+    const SnapHeader mine = snap_header(c);
+    if (std::memcmp(h.magic, mine.magic, 8) != 0) return MUKV_ERR_INVALID_ARG;
+    if (h.n_layers != mine.n_layers || h.n_q_heads != mine.n_q_heads || h.n_kv_heads != mine.n_kv_heads ||
+        h.head_dim != mine.head_dim || h.tokens_per_frame != mine.tokens_per_frame ||
+        h.frames_per_segment != mine.frames_per_segment || h.superpatches_per_frame != mine.superpatches_per_frame ||
+        h.dtype != mine.dtype || h.kappa != mine.kappa || h.score_layer != mine.score_layer)
+        return MUKV_ERR_SHAPE;
+    if (h.n_frames < 0 || h.n_frames > c.cfg.max_frames) return MUKV_ERR_CAPACITY;
+    if (bytes < snap_bytes(c, h.n_frames)) return MUKV_ERR_INVALID_ARG;
+    {
+        const int rc = mukv_reset(ctx); // drops gathered chunks and a copy that was put off
+        if (rc != MUKV_OK) return rc;
+    }
+    DeviceScope dev(c.cfg.device_id);
+    if (!dev.ok) return MUKV_ERR_HIP;
+    // earlier kernels of this context, on whichever stream, may still write the tables
+    if (mukv::join_streams(c, st) != hipSuccess || hipDeviceSynchronize() != hipSuccess) return MUKV_ERR_HIP;
+    const unsigned char *in = static_cast<const unsigned char *>(host_src) + sizeof h;
+    for (const SnapPiece &p : snap_pieces(c, h.n_frames))
+        for (int i = 0; i < p.count; ++i) {
+            if (p.bytes &&
+                hipMemcpyAsync(static_cast<unsigned char *>(p.dev) + (size_t)i * p.stride, in, p.bytes,
+                               hipMemcpyHostToDevice, st) != hipSuccess)
+                return MUKV_ERR_HIP;
+            in += p.bytes;
+        }
+    if (hipStreamSynchronize(st) != hipSuccess) return MUKV_ERR_HIP;
+    c.n_frames = h.n_frames;
+    c.n_done = h.n_frames;
+    return MUKV_OK;
 }
 
 int mukv_plain_copy(void *dst, const void *src, int64_t bytes, void *stream) {

@@ -8,7 +8,7 @@ import torch
 from oracle import oracle as orc
 from paper_2605_22269_amd import binding as mk
 from paper_2605_22269_amd import synth
-from mukv_testlib import Pair, np_view
+from mukv_testlib import Pair, gpu_context, np_view
 
 pytestmark = pytest.mark.gpu
 
@@ -663,4 +663,69 @@ def test_outputs_stay_inside_their_buffers():
     torch.cuda.synchronize()
     for b in bufs.values():
         intact(b)
+    p.close()
+
+
+# ------------------------------------------------------------------ snapshot of the cache ------
+@pytest.mark.parametrize("name,first,rest,kw", [
+    ("7b", 21, 19, {}),                                               # cut inside a segment
+    ("tiny", 32, 13, {"batch_chunks": 4, "overlap_copy": 1}),          # cut on a segment boundary, copy put off
+    ("72b", 7, 9, {"refine_margin": 10.0}),                            # every frame re-scored in fp64
+])
+def test_snapshot_resumes_a_stream_in_another_context(name, first, rest, kw):
+    # ingest the first part, save, load into a fresh context that held something else, ingest
+    # the rest there: tables, retrieval and gathers must equal the oracle's over the whole stream
+    w = W[name].scaled(n_frames=first + rest, n_layers=2, n_questions=3)
+    p = Pair(w, seed=170, chunk=4, gpu_kw=kw)
+    p.ingest(first)
+    snap = p.gpu.snapshot()
+    assert snap.numel() == mk.mukv_snapshot_size(p.gpu.h)
+    other = gpu_context(w, max_frames=first + rest, max_chunk_frames=4, **kw)
+    junk = synth.SynthStream(w, 171, device="cpu")
+    k, v, q = junk.next_chunk(4)
+    held = [k.cuda(), v.cuda(), q.cuda()]
+    other.compress_chunk(*held)
+    other.restore(snap)
+    assert other.n_frames == first
+    # the same bytes come back out of the second context
+    assert torch.equal(other.snapshot(), snap)
+    p.gpu.close()
+    p.gpu = other
+    p.ingest(rest)
+    p.check_compress()
+    qs = questions_for(w, [6, 17, 3], 1200)
+    p.check_retrieve(qs, mk.MUKV_SEMI, 2, 5, 0.3)
+    p.check_retrieve_patches(qs, mk.MUKV_HIER, 2, 6)
+    p.close()
+
+
+def test_snapshot_argument_errors():
+    w = W["tiny"].scaled(n_frames=8, n_layers=2)
+    p = Pair(w, seed=172, chunk=4)
+    p.ingest()
+    snap = p.gpu.snapshot()
+    small = torch.empty(snap.numel() - 1, dtype=torch.uint8)
+    with pytest.raises(mk.MuKVError) as e:
+        mk.mukv_snapshot_save(p.gpu.h, small.data_ptr(), small.numel(), None)
+    assert e.value.status == mk.MUKV_ERR_CAPACITY
+    with pytest.raises(mk.MuKVError) as e:      # truncated
+        mk.mukv_snapshot_load(p.gpu.h, snap.data_ptr(), snap.numel() - 1, None)
+    assert e.value.status == mk.MUKV_ERR_INVALID_ARG
+    bad = snap.clone()
+    bad[0] ^= 0xFF
+    with pytest.raises(mk.MuKVError) as e:      # not a snapshot
+        p.gpu.restore(bad)
+    assert e.value.status == mk.MUKV_ERR_INVALID_ARG
+    other = gpu_context(w.scaled(n_layers=3), max_frames=8, max_chunk_frames=4)
+    with pytest.raises(mk.MuKVError) as e:      # another configuration
+        other.restore(snap)
+    assert e.value.status == mk.MUKV_ERR_SHAPE
+    tight = gpu_context(w, max_frames=4, max_chunk_frames=4)
+    with pytest.raises(mk.MuKVError) as e:      # more frames than the context can hold
+        tight.restore(snap)
+    assert e.value.status == mk.MUKV_ERR_CAPACITY
+    # failed loads left the first context as it was
+    p.check_compress()
+    other.close()
+    tight.close()
     p.close()
