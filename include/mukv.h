@@ -214,7 +214,8 @@ int mukv_flush(mukv_ctx *ctx);
  *
  * Errors: INVALID_ARG (null k/v, missing or doubled attention source),
  * SHAPE (n_frames < 1), CAPACITY (n_frames > max_chunk_frames or the cache is
- * full), UNSUPPORTED (strides or pointers not 16-byte aligned).
+ * full), UNSUPPORTED (strides or pointers not 16-byte aligned, or a query
+ * token stride of 16 MiB or more).
  */
 int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_strides *kv_strides,
                         const void *q_last, const mukv_strides *q_strides, const float *att_signal,

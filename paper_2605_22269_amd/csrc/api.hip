@@ -403,6 +403,7 @@ int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_
         if (q_strides->token < D || q_strides->head < 0) return MUKV_ERR_SHAPE;
         if (q_strides->token % unit || q_strides->head % unit || (reinterpret_cast<uintptr_t>(q_last) & 15))
             return MUKV_ERR_UNSUPPORTED;
+        if (q_strides->token * c.esz >= (int64_t)1 << 24) return MUKV_ERR_UNSUPPORTED; // 24-bit offset arithmetic
         q_sh = q_strides->head;
         q_st = q_strides->token;
     }

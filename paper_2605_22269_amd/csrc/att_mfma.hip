@@ -35,50 +35,71 @@ constexpr int kTileB = 16 * kRowB;    // one 16-row tile: 4 KB
 struct JobArgs {
     const unsigned char *k_lds; // LDS key tile 0
     int off[4];                 // this lane's byte offset inside a tile for feature slices 0..3
-    int q0;                 // first of this lane's four query positions in the frame
-    int lr;                 // lane % 16
-    int P;
-    bool diag;              // causal: the last tile holds the diagonal
-    bool tail;              // the last tile holds keys past P
+    int t;                      // last tile: query row r of this lane sees the lane's key iff t <= r
+    int rows;                   // query rows r < rows of this lane exist (position < P)
+    bool mask;                  // the last tile holds the causal diagonal or keys past P
     float scale_log2e;
 };
+
+// Maximum over the 16 lanes of a row for four values at once.  The four chains are interleaved so
+// that a value is read (through the lane permute) three instructions after it was written, which
+// covers the two wait states the permute needs; the leading s_nop covers the instruction before
+// the block.  All lanes are active and every permutation stays inside the row.
+__device__ __forceinline__ void row16_max4(float &a, float &b, float &c, float &d) {
+#define MUKV_MAX4(CTRL)                                                  \
+    "v_max_f32_dpp %0, %0, %0 " CTRL " row_mask:0xf bank_mask:0xf\n\t" \
+    "v_max_f32_dpp %1, %1, %1 " CTRL " row_mask:0xf bank_mask:0xf\n\t" \
+    "v_max_f32_dpp %2, %2, %2 " CTRL " row_mask:0xf bank_mask:0xf\n\t" \
+    "v_max_f32_dpp %3, %3, %3 " CTRL " row_mask:0xf bank_mask:0xf\n\t"
+    asm("s_nop 1\n\t" MUKV_MAX4("quad_perm:[1,0,3,2]") MUKV_MAX4("quad_perm:[2,3,0,1]") MUKV_MAX4("row_half_mirror")
+            MUKV_MAX4("row_mirror")
+        : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+#undef MUKV_MAX4
+}
 
 // One (head, strip) job over the first NTL key tiles, fully unrolled for that count so that no
 // arithmetic is spent on tiles above the causal diagonal.  Score tiles S = Q K^T (A operand: the
 // strip's Q, B operand: a key tile from LDS): a lane then owns one key column (lane % 16) and the
-// four query rows 4*(lane/16)..+3 of every tile.  Row statistics of the exact softmax are an
-// in-lane pass over the tiles plus a 16-lane DPP reduction; the normalised probabilities of the
-// lane's four rows are added into ONE accumulator per tile (13 registers for the whole frame).
+// four query rows 4*(lane/16)..+3 of every tile.  The key operands of tile c+1 are requested from
+// LDS before the matrix instructions of tile c are issued.  Row statistics of the exact softmax
+// are an in-lane pass over the tiles plus a 16-lane reduction; the normalised probabilities of
+// the lane's four rows are added into ONE accumulator per tile (13 registers for the whole frame).
 template <int NTL>
 __device__ __forceinline__ void strip_job(const JobArgs &ja, const bf16x8 *qv, float *acc) {
     f32x4 st[NTL];
+    bf16x8 kf[2][4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) kf[0][kk] = *reinterpret_cast<const bf16x8 *>(ja.k_lds + ja.off[kk]);
 #pragma unroll
     for (int c = 0; c < NTL; ++c) {
+        if (c + 1 < NTL) {
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                kf[(c + 1) & 1][kk] = *reinterpret_cast<const bf16x8 *>(ja.k_lds + (c + 1) * kTileB + ja.off[kk]);
+        }
+        __builtin_amdgcn_sched_barrier(0); // keeps the requests of tile c+1 ahead of the matrix instructions of tile c
         f32x4 d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ja.k_lds + c * kTileB + ja.off[kk]);
-            d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qv[kk], kf, d, 0, 0, 0);
-        }
+        for (int kk = 0; kk < 4; ++kk) d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qv[kk], kf[c & 1][kk], d, 0, 0, 0);
         st[c] = d;
+        __builtin_amdgcn_sched_barrier(0);
     }
-    if (ja.diag || ja.tail) { // only the last tile can need masking
+    if (ja.mask) { // only the last tile can need masking
         constexpr int c = NTL - 1;
-        const int j = 16 * c + ja.lr;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const bool ok = (j < ja.P) && (!ja.diag || j <= ja.q0 + r);
-            st[c][r] = ok ? st[c][r] : -INFINITY;
-        }
+        for (int r = 0; r < 4; ++r) st[c][r] = (ja.t <= r) ? st[c][r] : -INFINITY;
     }
-    float m[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    float m[4];
 #pragma unroll
-    for (int c = 0; c < NTL; ++c)
+    for (int r = 0; r < 4; ++r) m[r] = st[0][r];
+#pragma unroll
+    for (int c = 1; c < NTL; ++c)
 #pragma unroll
         for (int r = 0; r < 4; ++r) m[r] = fmaxf(m[r], st[c][r]);
+    row16_max4(m[0], m[1], m[2], m[3]); // every query row sees at least its own key: finite
     float mb[4], z[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int r = 0; r < 4; ++r) mb[r] = row16_max(m[r]) * ja.scale_log2e;
+    for (int r = 0; r < 4; ++r) mb[r] = m[r] * ja.scale_log2e;
 #pragma unroll
     for (int c = 0; c < NTL; ++c)
 #pragma unroll
@@ -89,7 +110,13 @@ __device__ __forceinline__ void strip_job(const JobArgs &ja, const bf16x8 *qv, f
         }
     float inv[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) inv[r] = (ja.q0 + r < ja.P) ? 1.0f / row16_sum(z[r]) : 0.0f;
+    for (int r = 0; r < 4; ++r) {
+        // 1 <= z <= P (the largest term is 1): reciprocal estimate + one Newton step
+        const float zr = row16_sum(z[r]);
+        float rc = __builtin_amdgcn_rcpf(zr);
+        rc = fmaf(fmaf(-zr, rc, 1.0f), rc, rc);
+        inv[r] = (r < ja.rows) ? rc : 0.0f;
+    }
 #pragma unroll
     for (int c = 0; c < NTL; ++c) {
         float t = acc[c];
@@ -131,15 +158,16 @@ __global__ __launch_bounds__(448) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     // Request of one (head, strip) into the wave's query buffer: four 1 KB instructions, lane i of
     // instruction j fills 16-byte slot 64*j + i = (row 4*j + i/16, position i%16), which holds
     // piece position ^ row of that row.  Rows past P are clamped (masked later).
+    const unsigned q_st2 = (unsigned)q_st * 2u; // token stride in bytes
     auto request_q = [&](int h, int s) {
-        // wave-uniform 64-bit base + a 32-bit per-lane byte offset (a frame's queries of one head
-        // span far less than 4 GB)
+        // wave-uniform 64-bit base + a 32-bit per-lane byte offset: the token stride is below
+        // 2^24 bytes (checked on the host), so position * stride is one 24-bit multiply-add
         const unsigned char *base = reinterpret_cast<const unsigned char *>(qf + (int64_t)h * q_sh);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int row = 4 * j + lg;
             const int qi = 16 * s + row;
-            const unsigned off = ((unsigned)((qi < P ? qi : P - 1) * (int)q_st) + (unsigned)((lr ^ row) << 3)) * 2u;
+            const unsigned off = __umul24((unsigned)(qi < P ? qi : P - 1), q_st2) + (unsigned)((lr ^ row) << 4);
             __builtin_amdgcn_global_load_lds(MUKV_GLOBAL_PTR(base + off), MUKV_LDS_PTR(Qs + 1024 * j), 16, 0, 0);
         }
     };
@@ -179,17 +207,17 @@ __global__ __launch_bounds__(448) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     ja.k_lds = Ks;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) ja.off[kk] = lr * kRowB + (((4 * kk + lg) ^ lr) << 4);
-    ja.lr = lr;
-    ja.P = P;
-    ja.diag = causal != 0;
     ja.scale_log2e = scale_log2e;
     const bool tail = (P & 15) != 0;
     for (int job = 0; job < n_jobs; ++job) {
         const int hh = job / n_strips, si = job - hh * n_strips;
         const int s = si ? sB : sA;
         const int ntl = __builtin_amdgcn_readfirstlane(causal ? s + 1 : nt); // key tiles this strip sees
-        ja.q0 = 16 * s + 4 * lg;
-        ja.tail = tail && ntl == nt;
+        const int q0 = 16 * s + 4 * lg;   // first of this lane's four query positions
+        const int j = 16 * (ntl - 1) + lr; // this lane's key in the last tile
+        ja.t = j < P ? (causal ? j - q0 : -1) : 4;
+        ja.rows = P - q0;
+        ja.mask = causal || (tail && ntl == nt);
         // this job's queries have arrived in the wave's buffer: move them to registers, and once
         // they are there let the buffer take the next job's queries, which then have this whole
         // job (and the other resident waves) to arrive
