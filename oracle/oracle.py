@@ -9,7 +9,9 @@ method in the order the paper gives them:
   block keys of Eq. 5 at super-patch, frame and segment level;
 * online, per question (Sec. 3.4): Eq. 6 question pooling, Eq. 7 cosine
   scoring, stage-1 candidates, the global query and Eq. 8 rerank, final
-  selection, and the concatenation of the selected blocks' KV (Sec. 3.5).
+  selection, and the concatenation of the selected blocks' KV (Sec. 3.5);
+* the attention of new tokens over that context (Sec. 3.5, Eq. 9), one layer
+  at a time.
 
 Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 ``bench.py`` may import this module.  It imports nothing from the HIP package.
@@ -68,6 +70,13 @@ def _dtype_code(a: np.ndarray) -> int:
 
 def _c(a: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(a)
+
+
+def values_f64(a: np.ndarray) -> np.ndarray:
+    """Payload (bf16 bit patterns or float32) as float64 values."""
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
 
 
 def kappa_of(keep_ratio: float, unit: int) -> int:
@@ -419,6 +428,47 @@ class OracleMuKV:
             vo[:, :, n:n + len(rows)] = sv[:, :, rows]
             n += len(rows)
         return ko, vo, n
+
+    def attend(self, layer, q, frame_idx, k_local=None, v_local=None, causal_local=True):
+        """Attention of new tokens over the retrieved context at one layer
+        (Sec. 3.5, Eq. 9): query token i, head h attends to the keys
+        [R_k, W_K X] = kept rows of the listed frames (entries -1 skipped)
+        followed by the caller's own ("local") rows, with values [R_v, W_V X];
+        scores q.k / sqrt(D), softmax over all visible keys, KV head h // G.
+        The query tokens are the last n_q local rows: with causal_local, token
+        i sees local row j only if j <= n_l - n_q + i.  Every retrieved row is
+        visible.  q [n_q][Hq][D]; k_local, v_local [n_l][Hkv][D] or None.
+        Returns float64 [n_q][Hq][D]; all zero for a token that sees no key."""
+        c = self.cfg
+        sk, sv = self.store() if self.n_frames else (None, None)
+        kap, G, D = self.kappa, c.n_q_heads // c.n_kv_heads, c.head_dim
+        qf = values_f64(np.asarray(q))
+        n_q = qf.shape[0]
+        n_l = 0 if k_local is None else k_local.shape[0]
+        rows = [r for f in frame_idx if f >= 0 for r in range(int(f) * kap, (int(f) + 1) * kap)]
+        out = np.zeros((n_q, c.n_q_heads, D))
+        for h in range(c.n_q_heads):
+            g = h // G
+            parts_k, parts_v = [], []
+            if rows:
+                parts_k.append(values_f64(sk[layer, g][rows]))
+                parts_v.append(values_f64(sv[layer, g][rows]))
+            if n_l:
+                parts_k.append(values_f64(np.asarray(k_local)[:, g]))
+                parts_v.append(values_f64(np.asarray(v_local)[:, g]))
+            if not parts_k:
+                continue
+            kk, vv = np.concatenate(parts_k), np.concatenate(parts_v)
+            for i in range(n_q):
+                s = kk @ qf[i, h] / math.sqrt(D)
+                if causal_local and n_l:
+                    j = np.arange(n_l)
+                    s[len(rows):][j > n_l - n_q + i] = -np.inf
+                if not np.isfinite(s).any():
+                    continue
+                w = np.exp(s - s[np.isfinite(s)].max())
+                out[i, h] = (w / w.sum()) @ vv
+        return out
 
     def gather(self, frame_idx, order=TEMPORAL):
         """Concatenate the stored K,V of the selected frames (Sec. 3.5): returns

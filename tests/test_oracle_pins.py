@@ -598,3 +598,118 @@ class TestPatchLevel:
         # a smaller output holds the first rows only, the count still reports the union
         k3, _, n3 = o.gather_union(seg_idx=[1], frame_idx=[5, 17], rows_cap=7)
         assert n3 == (F + 1) * kap and k3.shape[2] == 7                    # frame 5 lies inside segment 1: counted once
+
+
+# ------------------------------------------------------------ Sec. 3.5, Eq. 9 ----
+class TestAttend:
+    """Attention of new tokens over [retrieved rows, local rows] at one layer."""
+
+    def _state(self, n_frames=12, const_values=False, dtype="f32"):
+        cfg = tiny_cfg(frames_per_segment=4)
+        k, v, q = tiny_stream(cfg, n_frames, dtype=dtype, seed=6)
+        if const_values:   # every value vector of (layer l, KV head g) is the constant 10 (l + 1) + g + 1
+            for l in range(cfg.n_layers):
+                for g in range(cfg.n_kv_heads):
+                    v[l, g] = 10.0 * (l + 1) + g + 1
+        return cfg, run_stream(cfg, k, v, q, 4)
+
+    def test_a_single_visible_key_returns_its_value(self):
+        cfg, o = self._state()
+        q = rng.standard_normal((1, 4, 16)).astype(np.float32)
+        kl = rng.standard_normal((1, 2, 16)).astype(np.float32)
+        vl = rng.standard_normal((1, 2, 16)).astype(np.float32)
+        out = o.attend(0, q, [-1, -1], kl, vl)
+        for h in range(4):
+            np.testing.assert_allclose(out[0, h], vl[0, h // 2].astype(np.float64), rtol=0, atol=1e-15)
+
+    def test_no_visible_key_gives_zero(self):
+        cfg, o = self._state()
+        q = rng.standard_normal((2, 4, 16)).astype(np.float32)
+        assert not o.attend(1, q, [-1]).any()
+
+    def test_equal_keys_average_the_values(self):
+        cfg, o = self._state()
+        q = rng.standard_normal((1, 4, 16)).astype(np.float32)
+        kl = np.repeat(rng.standard_normal((1, 2, 16)).astype(np.float32), 5, axis=0)
+        vl = rng.standard_normal((5, 2, 16)).astype(np.float32)
+        out = o.attend(0, q, [], kl, vl, causal_local=False)
+        for h in range(4):
+            np.testing.assert_allclose(out[0, h], vl[:, h // 2].astype(np.float64).mean(axis=0), atol=1e-14)
+
+    def test_two_keys_mix_with_the_logistic_of_the_scaled_score_gap(self):
+        cfg, o = self._state()
+        D = 16
+        q = np.zeros((1, 4, D), np.float32)
+        q[0, :, 3] = 2.0
+        kl = np.zeros((2, 2, D), np.float32)
+        kl[0, :, 3], kl[1, :, 3] = 1.5, -0.5           # scores 3/sqrt(D) and -1/sqrt(D)
+        vl = np.zeros((2, 2, D), np.float32)
+        vl[0, :, 0], vl[1, :, 0] = 1.0, 0.0
+        out = o.attend(0, q, [], kl, vl, causal_local=False)
+        want = 1.0 / (1.0 + math.exp(-(3.0 - (-1.0)) / math.sqrt(D)))    # 1/sqrt(D) scale: gap 4/4 = 1
+        np.testing.assert_allclose(out[0, :, 0], want, atol=1e-15)
+
+    def test_layer_and_grouped_head_of_the_retrieved_rows(self):
+        # constant values per (layer, KV head): whatever the weights, the output names the slab read
+        cfg, o = self._state(const_values=True)
+        q = rng.standard_normal((3, 4, 16)).astype(np.float32)
+        for layer in (0, 1):
+            out = o.attend(layer, q, [7, 2, -1, 9])
+            for h in range(4):
+                np.testing.assert_allclose(out[:, h], 10.0 * (layer + 1) + h // 2 + 1, rtol=1e-14)
+
+    def test_matches_library_softmax_over_the_gathered_rows(self):
+        import scipy.special
+        cfg, o = self._state(dtype="bf16")
+        sel = [5, 0, 11, -1, 3]
+        ko, vo, n = o.gather(sel, orc.AS_GIVEN)                  # gather is pinned on its own
+        q = bf16_bits(rng.standard_normal((2, 4, 16)))
+        kl, vl = bf16_bits(rng.standard_normal((3, 2, 16))), bf16_bits(rng.standard_normal((3, 2, 16)))
+        out = o.attend(1, q, sel, kl, vl, causal_local=False)
+        for h in range(4):
+            K = np.concatenate([bf16_value(ko[1, h // 2, :n]), bf16_value(kl[:, h // 2])])
+            V = np.concatenate([bf16_value(vo[1, h // 2, :n]), bf16_value(vl[:, h // 2])])
+            w = scipy.special.softmax(bf16_value(q[:, h]) @ K.T / 4.0, axis=1)
+            np.testing.assert_allclose(out[:, h], w @ V, atol=1e-13)
+
+    def test_order_of_the_retrieved_frames_does_not_matter(self):
+        cfg, o = self._state()
+        q = rng.standard_normal((2, 4, 16)).astype(np.float32)
+        a = o.attend(0, q, [1, 8, 4, -1])
+        b = o.attend(0, q, [-1, 4, 1, 8])
+        np.testing.assert_allclose(a, b, atol=1e-13)
+
+    def test_causal_mask_over_the_local_rows(self):
+        cfg, o = self._state()
+        n = 5
+        q = rng.standard_normal((n, 4, 16)).astype(np.float32)
+        kl = rng.standard_normal((n, 2, 16)).astype(np.float32)
+        vl = rng.standard_normal((n, 2, 16)).astype(np.float32)
+        out = o.attend(0, q, [], kl, vl)                      # pure self-attention of the local rows
+        for h in range(4):                                     # token 0 sees only row 0
+            np.testing.assert_allclose(out[0, h], vl[0, h // 2].astype(np.float64), atol=1e-15)
+        kl2, vl2 = kl.copy(), vl.copy()
+        kl2[3:], vl2[3:] = 7.0, -3.0                           # rows 3, 4 changed: tokens 0..2 must not notice
+        out2 = o.attend(0, q, [], kl2, vl2)
+        np.testing.assert_array_equal(out[:3], out2[:3])
+        assert np.abs(out[3:] - out2[3:]).max() > 1e-3
+        free = o.attend(0, q, [], kl2, vl2, causal_local=False)
+        assert np.abs(free[:3] - out2[:3]).max() > 1e-3
+        # fewer query tokens than local rows: the queries are the LAST rows
+        tail = o.attend(0, q[3:], [], kl, vl)
+        np.testing.assert_allclose(tail, out[3:], atol=1e-14)
+
+    def test_retrieved_rows_are_visible_to_every_token_and_scores_shift_freely(self):
+        cfg, o = self._state()
+        q = rng.standard_normal((1, 4, 16)).astype(np.float32)
+        kl = rng.standard_normal((1, 2, 16)).astype(np.float32)
+        vl = rng.standard_normal((1, 2, 16)).astype(np.float32)
+        with_ctx = o.attend(1, q, [2, 6], kl, vl)
+        ctx_only = o.attend(1, q, [2, 6])
+        # a local key far below every other score drops out: the retrieved part alone remains
+        far = kl.copy()
+        for g in range(2):
+            far[0, g] = -1e4 * q[0, 2 * g] / np.linalg.norm(q[0, 2 * g])
+        drop = o.attend(1, q[:, [0, 0, 2, 2]], [2, 6], far, vl)
+        np.testing.assert_allclose(drop, o.attend(1, q[:, [0, 0, 2, 2]], [2, 6]), atol=1e-12)
+        assert np.abs(with_ctx - ctx_only).max() > 1e-6
