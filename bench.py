@@ -302,6 +302,30 @@ def main():
             "gather_bytes": Bq * gather_bytes, "path_GBs": Bq * gather_bytes / (ms64 * 1e-3) / 1e9}
         del g64
 
+        # ---- the step after the path (Eq. 9): one new token per question attends to the kept rows of
+        # its retrieved frames, read in place, plus 32 local rows; one call per layer, all L layers ----
+        n_loc = 32
+        gen = torch.Generator(device=dev).manual_seed(a.seed + 7)
+        q_dec = torch.randn(Bq, 1, Hq, D, generator=gen, device=dev).to(w.torch_dtype)
+        kl = torch.randn(Bq * n_loc, Hkv, D, generator=gen, device=dev).to(w.torch_dtype)
+        vl = torch.randn(Bq * n_loc, Hkv, D, generator=gen, device=dev).to(w.torch_dtype)
+        lo = (torch.arange(Bq + 1, dtype=torch.int32) * n_loc).to(dev)
+        o_dec = torch.empty_like(q_dec)
+        rows_q = w.k_frame * kappa + n_loc
+        res["decode_attention"] = {"new_tokens_per_question": 1, "retrieved_rows": w.k_frame * kappa, "local_rows": n_loc,
+                                   "layers": L}
+        for nb in (Bq, 1):
+            def decode_layers(nb=nb):
+                for layer in range(L):
+                    ctx.attend(layer, q_dec[:nb], r64["frame_idx"][:nb], kl[:nb * n_loc], vl[:nb * n_loc], lo[:nb + 1],
+                               True, out=o_dec[:nb])
+            decode_layers()
+            dms = timed(decode_layers, 10)
+            kv_bytes = nb * rows_q * b_tok                      # K and V rows of one layer, read once
+            res["decode_attention"][f"{nb}_questions"] = {
+                "ms_all_layers": dms, "us_per_layer_call": dms / L * 1e3, "kv_bytes_per_layer_call": kv_bytes,
+                "GBs": kv_bytes * L / (dms * 1e-3) / 1e9}
+
     # ---- the super-patch level of the search on the same cache: one question, k_g = 20 --------
     p_out = {"patch_idx": torch.empty(B, 20, dtype=torch.int32, device=dev),
              "patch_score": torch.empty(B, 20, dtype=torch.float32, device=dev)}

@@ -294,6 +294,42 @@ int mukv_gather_patches(mukv_ctx *ctx, const int32_t *patch_idx, int32_t B, int3
                         void *k_out, void *v_out, int32_t *n_tokens_out, void *stream);
 
 /*
+ * Attention of new tokens over the retrieved context at one layer (Sec. 3.5,
+ * Eq. 9): the step after the retrieval.  For question b, query token i and
+ * head h the keys are [R_k, W_K X]: the kept rows of the frames listed in
+ * frame_idx[b] (entries -1 or out of range are skipped; the rows are read in
+ * place from the cache, no gathered copy is needed) followed by the
+ * question's own "local" rows (question tokens, tokens generated so far, the
+ * current token), and the values [R_v, W_V X] likewise.  Scores are
+ * q.k / sqrt(D), the softmax runs over all visible keys, head h uses KV head
+ * h / (Hq / Hkv).  Every retrieved row is visible to every token.  The n_q
+ * query tokens are the LAST n_q local rows: with causal_local = 1 token i sees
+ * local row j only if j <= n_local_b - n_q + i; with 0 it sees all of them.
+ * A token that sees no key at all gets zeros.
+ *
+ *   layer          0 .. n_layers-1: which layer's kept rows are read
+ *   q              device, payload dtype, [B][n_q][Hq][D] contiguous
+ *   n_q            query tokens per question, 1 .. 16 (1 = decode)
+ *   frame_idx      device int32 [B][k_frame] (e.g. mukv_retrieve's output), or
+ *                  null with k_frame = 0
+ *   k_local,       device, payload dtype, [n_local_total][Hkv][D]: the local
+ *   v_local        rows of all questions back to back
+ *   local_offsets  device int32 [B+1]: question b owns local rows
+ *                  local_offsets[b] .. local_offsets[b+1]-1.  k_local,
+ *                  v_local and local_offsets are given together or all null.
+ *   out            device, payload dtype, [B][n_q][Hq][D]
+ *
+ * Arithmetic in fp32 (dot products, exp2, sums in a fixed order); the output
+ * is rounded to the payload dtype.  Uses scratch owned by the context: calls
+ * on one context must not overlap.
+ * Errors: INVALID_ARG, CAPACITY (B > max_questions), UNSUPPORTED (n_q > 16,
+ * k_frame > 1024, pointers not 16-byte aligned).
+ */
+int mukv_attend(mukv_ctx *ctx, int32_t layer, const void *q, int32_t n_q, const int32_t *frame_idx, int32_t k_frame,
+                const void *k_local, const void *v_local, const int32_t *local_offsets, int32_t B, int32_t causal_local,
+                void *out, void *stream);
+
+/*
  * Snapshot of the cache (the offline memory of Sec. 3.3 is persistent state):
  * the kept K/V rows, kept positions, block keys and running segment sums of
  * the frames ingested so far, in one host buffer, so that a stream can be

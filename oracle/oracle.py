@@ -432,7 +432,8 @@ class OracleMuKV:
     def attend(self, layer, q, frame_idx, k_local=None, v_local=None, causal_local=True):
         """Attention of new tokens over the retrieved context at one layer
         (Sec. 3.5, Eq. 9): query token i, head h attends to the keys
-        [R_k, W_K X] = kept rows of the listed frames (entries -1 skipped)
+        [R_k, W_K X] = kept rows of the listed frames (entries that name no
+        frame of the cache, such as the -1 padding, are skipped)
         followed by the caller's own ("local") rows, with values [R_v, W_V X];
         scores q.k / sqrt(D), softmax over all visible keys, KV head h // G.
         The query tokens are the last n_q local rows: with causal_local, token
@@ -445,7 +446,7 @@ class OracleMuKV:
         qf = values_f64(np.asarray(q))
         n_q = qf.shape[0]
         n_l = 0 if k_local is None else k_local.shape[0]
-        rows = [r for f in frame_idx if f >= 0 for r in range(int(f) * kap, (int(f) + 1) * kap)]
+        rows = [r for f in frame_idx if 0 <= f < self.n_frames for r in range(int(f) * kap, (int(f) + 1) * kap)]
         out = np.zeros((n_q, c.n_q_heads, D))
         for h in range(c.n_q_heads):
             g = h // G

@@ -70,7 +70,7 @@ class mukv_profile(C.Structure):
 
 EXPORTS = ("mukv_create", "mukv_destroy", "mukv_reset", "mukv_flush", "mukv_compress_chunk", "mukv_retrieve",
            "mukv_retrieve_patches", "mukv_retrieve_at", "mukv_gather_kv", "mukv_gather_patches", "mukv_gather_union",
-           "mukv_snapshot_size", "mukv_snapshot_save", "mukv_snapshot_load", "mukv_profile_begin", "mukv_profile_end",
+           "mukv_attend", "mukv_snapshot_size", "mukv_snapshot_save", "mukv_snapshot_load", "mukv_profile_begin", "mukv_profile_end",
            "mukv_plain_copy", "mukv_get_state", "mukv_strerror")
 
 _lib = None
@@ -98,6 +98,7 @@ def load():
     lib.mukv_gather_patches.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.mukv_retrieve_at.argtypes = [vp, vp, vp, vp, i32, C.POINTER(mukv_retrieve_params), i32, vp, vp, vp, vp, vp]
     lib.mukv_gather_union.argtypes = [vp, vp, i32, vp, i32, vp, i32, i32, i32, vp, vp, vp, vp]
+    lib.mukv_attend.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp, vp, i32, i32, vp, vp]
     lib.mukv_snapshot_size.argtypes = [vp, C.POINTER(C.c_int64)]
     lib.mukv_snapshot_save.argtypes = [vp, vp, C.c_int64, vp]
     lib.mukv_snapshot_load.argtypes = [vp, vp, C.c_int64, vp]
@@ -175,6 +176,11 @@ def mukv_gather_patches(h, idx_ptr, B, k_patch, order, k_out, v_out, n_tok, stre
 def mukv_gather_union(h, seg_ptr, k_seg, frm_ptr, k_frame, pat_ptr, k_patch, B, rows_cap, k_out, v_out, n_tok, stream):
     _check(load().mukv_gather_union(h, seg_ptr, k_seg, frm_ptr, k_frame, pat_ptr, k_patch, B, rows_cap, k_out, v_out, n_tok,
                                     stream), "mukv_gather_union")
+
+
+def mukv_attend(h, layer, q_ptr, n_q, idx_ptr, k_frame, kl_ptr, vl_ptr, loff_ptr, B, causal_local, out_ptr, stream):
+    _check(load().mukv_attend(h, layer, q_ptr, n_q, idx_ptr, k_frame, kl_ptr, vl_ptr, loff_ptr, B, causal_local, out_ptr,
+                              stream), "mukv_attend")
 
 
 def mukv_snapshot_size(h) -> int:
@@ -405,6 +411,18 @@ class MuKV:
                    torch.empty(B, dtype=torch.int32, device=dev))
         mukv_gather_union(self.h, _ptr(seg_idx), ks, _ptr(frame_idx), kf, _ptr(patch_idx), kp, B, rows_cap,
                           _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _stream())
+        self._held.clear()
+        return out
+
+    def attend(self, layer, q, frame_idx=None, k_local=None, v_local=None, local_offsets=None, causal_local=True,
+               out=None):
+        """q [B][n_q][Hq][D]; frame_idx [B][k] int32 or None; local rows [n][Hkv][D] with offsets [B+1]."""
+        B, n_q = q.shape[0], q.shape[1]
+        k_frame = 0 if frame_idx is None else frame_idx.shape[1]
+        if out is None:
+            out = torch.empty_like(q)
+        mukv_attend(self.h, layer, _ptr(q), n_q, _ptr(frame_idx), k_frame, _ptr(k_local), _ptr(v_local),
+                    _ptr(local_offsets), B, int(causal_local), _ptr(out), _stream())
         self._held.clear()
         return out
 

@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmukv.so")
-SOURCES = ["api.hip", "compress.hip", "att_mfma.hip", "retrieve.hip"]  # traffic_probe.cpp is a separate program
+SOURCES = ["api.hip", "compress.hip", "att_mfma.hip", "retrieve.hip", "attend.hip"]  # traffic_probe.cpp is a separate program
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [

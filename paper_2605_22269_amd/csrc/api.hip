@@ -88,7 +88,7 @@ void free_all(Ctx &c) {
                     c.rep_patch_v, c.rep_seg_k, c.rep_seg_v, c.cnt_patch,   c.fsum_k,      c.fsum_v,
                     c.ssum_k,      c.ssum_v,    c.margin,      c.refined,   c.att_part,  c.fft_sig,     c.att64,       c.fft64,
                     c.src_tok,     c.src_tok2,    c.flag_list[0], c.flag_list[1], c.flag_count, c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail,
-                    c.u_mask,      c.u_entry,     c.u_count};
+                    c.u_mask,      c.u_entry,     c.u_count,   c.attend_part};
     // nothing of the library's own may still be running on what is freed below
     if (c.side) (void)hipStreamSynchronize(c.side);
     for (void *p : ptrs)
@@ -263,6 +263,7 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(dalloc(&c.u_mask, MQ * MF));
     ok(dalloc(&c.u_entry, MQ * MF * 3));
     ok(dalloc(&c.u_count, MQ * 2));
+    ok(dalloc(&c.attend_part, MQ * mukv::kAttendMaxTokens * cfg->n_q_heads * mukv::kAttendMaxSplit * (size_t)(cfg->head_dim + 2)));
     if (e != hipSuccess || !c.prof || !c.pending || !c.deferred) {
         free_all(c);
         delete c.prof;
@@ -537,6 +538,33 @@ int mukv_gather_kv(mukv_ctx *ctx, const int32_t *frame_idx, int32_t B, int32_t k
     DeviceScope dev(c.cfg.device_id);
     if (!dev.ok) return MUKV_ERR_HIP;
     return mukv::launch_gather(c, frame_idx, B, k_frame, order, k_out, v_out, n_tokens_out,
+                               reinterpret_cast<hipStream_t>(stream)) == hipSuccess
+               ? MUKV_OK
+               : MUKV_ERR_HIP;
+}
+
+int mukv_attend(mukv_ctx *ctx, int32_t layer, const void *q, int32_t n_q, const int32_t *frame_idx, int32_t k_frame,
+                const void *k_local, const void *v_local, const int32_t *local_offsets, int32_t B, int32_t causal_local,
+                void *out, void *stream) {
+    if (!ctx || !q || !out) return MUKV_ERR_INVALID_ARG;
+    Ctx &c = ctx->c;
+    if (B < 1 || n_q < 1 || k_frame < 0 || layer < 0 || layer >= c.cfg.n_layers) return MUKV_ERR_INVALID_ARG;
+    if (causal_local != 0 && causal_local != 1) return MUKV_ERR_INVALID_ARG;
+    if (k_frame > 0 && !frame_idx) return MUKV_ERR_INVALID_ARG;
+    const int n_local_args = (k_local != nullptr) + (v_local != nullptr) + (local_offsets != nullptr);
+    if (n_local_args != 0 && n_local_args != 3) return MUKV_ERR_INVALID_ARG;
+    if (B > c.cfg.max_questions) return MUKV_ERR_CAPACITY;
+    if (n_q > mukv::kAttendMaxTokens || k_frame > mukv::kMaxGatherK) return MUKV_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(q) & 15) || (reinterpret_cast<uintptr_t>(out) & 15) ||
+        (reinterpret_cast<uintptr_t>(k_local) & 15) || (reinterpret_cast<uintptr_t>(v_local) & 15))
+        return MUKV_ERR_UNSUPPORTED;
+    {
+        const int rc = flush_pending(c, true, reinterpret_cast<hipStream_t>(stream));
+        if (rc != MUKV_OK) return rc;
+    }
+    DeviceScope dev(c.cfg.device_id);
+    if (!dev.ok) return MUKV_ERR_HIP;
+    return mukv::launch_attend(c, layer, q, n_q, frame_idx, k_frame, k_local, v_local, local_offsets, B, causal_local, out,
                                reinterpret_cast<hipStream_t>(stream)) == hipSuccess
                ? MUKV_OK
                : MUKV_ERR_HIP;

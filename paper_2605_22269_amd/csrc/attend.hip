@@ -1,0 +1,456 @@
+// Attention of new tokens over the retrieved context at one layer (Sec. 3.5, Eq. 9): queries
+// W_Q X against keys [R_k, W_K X] and values [R_v, W_V X], where R are the kept rows of the
+// frames chosen by the retrieval -- read in place from the store, no gathered copy -- and X the
+// caller's own ("local") rows.
+//
+// attend_partial_kernel: one workgroup per (question, KV head, tile of up to 8 queries, split of
+// the frame list).  A query of the tile is a (token, head of the KV group) pair, so a key / value
+// row is read once for all the heads that share it.  Rows are taken in chunks of up to 512:
+//   1. a table of where each row of the chunk lives (store row or local row) and which token is
+//      the first to see it;
+//   2. the scores of the chunk, kept in LDS, and their maximum per query.  bf16 rows of 32, 64 or
+//      128 features: S^T = K Q^T with v_mfma_f32_16x16x32_bf16, 16 key rows per wave and step,
+//      the A operand loaded straight from the row (lane % 16 = row, 8 features from
+//      8 * (lane / 16) of every 32).  Otherwise: a row spread over D/E lanes (E = elements in 16
+//      bytes), dot products reduced over those lanes;
+//   3. with that maximum fixed, exp2 and the value accumulation (a value row spread over D/E
+//      lanes, 256*E/D rows in flight per pass, four passes of loads issued together) -- so the
+//      running sums are rescaled once per chunk, not once per row.
+// The split's (maximum, normaliser, unnormalised output) per query go to a scratch table;
+// attend_combine_kernel merges the splits and writes the output in the payload type.
+// Everything is summed in a fixed order: the result does not depend on timing.
+#include <climits>
+
+#include "mukv_internal.h"
+
+namespace mukv {
+
+namespace {
+
+constexpr int kTileQ = 8;    // queries per workgroup
+constexpr int kChunk = 512;  // rows whose scores are held in LDS at a time
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;   // rows a lane has in flight
+
+struct AttendArgs {
+    const void *q;            // [B][n_q][Hq][D]
+    const int32_t *frame_idx; // [B][k_frame] or null
+    const void *k_local, *v_local; // [n_local_total][Hkv][D] or null
+    const int32_t *local_offsets;  // [B+1] or null
+    const void *store_k, *store_v; // the layer's slabs: [Hkv][store_cap][D]
+    float *part;                   // [B][n_q*Hq][n_split][D+2]
+    int64_t store_cap;
+    int n_q, Hq, Hkv, G, k_frame, kappa, n_frames, n_split, frames_per_split, n_qtiles, causal;
+    float scale_log2e;
+};
+
+template <typename T>
+struct Row16;
+typedef __attribute__((ext_vector_type(4))) unsigned int raw16; // 16 bytes as they come from memory
+template <>
+struct Row16<uint16_t> { // eight bf16
+    static constexpr int E = 8;
+    __device__ static void expand(raw16 u, float *x) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[2 * i] = __uint_as_float(u[i] << 16);
+            x[2 * i + 1] = __uint_as_float(u[i] & 0xFFFF0000u);
+        }
+    }
+};
+template <>
+struct Row16<float> {
+    static constexpr int E = 4;
+    __device__ static void expand(raw16 u, float *x) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = __uint_as_float(u[i]);
+    }
+};
+template <typename T>
+__device__ __forceinline__ raw16 load16(const T *p) {
+    return *reinterpret_cast<const raw16 *>(p);
+}
+
+// sum over the LPR consecutive lanes that hold one row; result in all of them
+template <int LPR>
+__device__ __forceinline__ float row_lanes_sum(float v) {
+    if constexpr (LPR >= 2) v += lane_xor<1>(v);
+    if constexpr (LPR >= 4) v += lane_xor<2>(v);
+    if constexpr (LPR >= 8) v += lane_xor<4>(v);
+    if constexpr (LPR >= 16) v += lane_xor<8>(v);
+    if constexpr (LPR >= 32) v += lane_xor<16>(v);
+    return v;
+}
+// sum over the lanes of a wave that hold the same piece of different rows; result in all of them
+template <int LPR>
+__device__ __forceinline__ float same_piece_sum(float v) {
+    if constexpr (LPR <= 1) v += lane_xor<1>(v);
+    if constexpr (LPR <= 2) v += lane_xor<2>(v);
+    if constexpr (LPR <= 4) v += lane_xor<4>(v);
+    if constexpr (LPR <= 8) v += lane_xor<8>(v);
+    if constexpr (LPR <= 16) v += lane_xor<16>(v);
+    if constexpr (LPR <= 32) v += lane_xor<32>(v);
+    return v;
+}
+
+__device__ __forceinline__ uint16_t bf16_round(float x) { // round to nearest even; inputs are finite
+    const uint32_t u = __float_as_uint(x);
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+__device__ __forceinline__ void store_out(uint16_t *p, float x) { *p = bf16_round(x); }
+__device__ __forceinline__ void store_out(float *p, float x) { *p = x; }
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) {
+    constexpr int E = Row16<T>::E, LPR = D / E, RPP = kThreads / LPR; // lanes per row, rows per pass
+    // bf16 rows whose length is a multiple of 32: the scores come from the matrix cores
+    constexpr bool kMfma = sizeof(T) == 2 && D % 32 == 0;
+    constexpr int kWaves = kThreads / 64;
+    static_assert(LPR >= 1 && LPR <= 32, "a row fits in half a wave");
+    __shared__ float s_sc[kTileQ][kChunk];  // scores of the chunk, log2 units
+    __shared__ int s_row[kChunk]; // where row i of the chunk lives: >= 0 store row, <= -2 local row -2 - code, -1 nowhere
+    __shared__ int s_ft[kChunk];  // first token that sees the row (INT_MAX: nobody does)
+    __shared__ float s_red[kWaves][kTileQ][D > 64 ? D : 64]; // per-wave maxima, later per-wave outputs
+    __shared__ float s_max[kTileQ];
+    __shared__ float s_z[kWaves][kTileQ];
+    __shared__ int s_frame[kMaxGatherK]; // this split's frames; -1: names no frame of the cache
+    const int sp = blockIdx.x, g = blockIdx.y % a.Hkv, qt = blockIdx.y / a.Hkv, b = blockIdx.z;
+    const int tid = threadIdx.x, li = tid % LPR, rg = tid / LPR, wave = tid >> 6, lane = tid & 63;
+    const int lr = lane & 15, lg = lane >> 4;
+    const int n_queries = a.n_q * a.G; // of this KV head: (token, head in group), token-major
+    const T *q = static_cast<const T *>(a.q);
+    auto query_row = [&](int n, bool *ok) { // element offset of query n of the tile
+        const int qq = qt * kTileQ + n;
+        *ok = n < kTileQ && qq < n_queries;
+        const int i = *ok ? qq / a.G : 0, h = g * a.G + (*ok ? qq % a.G : 0);
+        return (((int64_t)b * a.n_q + i) * a.Hq + h) * D;
+    };
+    auto token_of = [&](int n) { // INT_MIN: no such query, sees nothing
+        const int qq = qt * kTileQ + n;
+        return (n < kTileQ && qq < n_queries) ? qq / a.G : INT_MIN;
+    };
+
+    // VALU path: this lane's piece of every query of the tile, scaled so that scores come out in
+    // log2 units.  Matrix path: the queries as the B operand (column lane % 16 = query, 8 features
+    // from 8 * (lane / 16) of every 32), unscaled.
+    float qr[kMfma ? 1 : kTileQ][E];
+    bf16x8 qb[kMfma ? D / 32 : 1];
+    if constexpr (kMfma) {
+        bool ok;
+        const int64_t off = query_row(lr, &ok);
+#pragma unroll
+        for (int kk = 0; kk < D / 32; ++kk) {
+            raw16 u = load16(q + off + kk * 32 + lg * 8);
+            if (!ok) u = raw16{0u, 0u, 0u, 0u};
+            qb[kk] = __builtin_bit_cast(bf16x8, u);
+        }
+    } else {
+#pragma unroll
+        for (int n = 0; n < kTileQ; ++n) {
+            bool ok;
+            const int64_t off = query_row(n, &ok);
+            float x[E];
+            Row16<T>::expand(load16(q + off + li * E), x);
+#pragma unroll
+            for (int e = 0; e < E; ++e) qr[n][e] = ok ? x[e] * a.scale_log2e : 0.f;
+        }
+    }
+
+    // rows of this split: kept rows of its frames, then (last split only) the local rows
+    const int f_lo = sp * a.frames_per_split;
+    const int f_hi = f_lo + a.frames_per_split < a.k_frame ? f_lo + a.frames_per_split : a.k_frame;
+    const int n_ret = f_hi > f_lo ? (f_hi - f_lo) * a.kappa : 0;
+    int l0 = 0, n_loc = 0;
+    if (a.local_offsets && sp == a.n_split - 1) {
+        l0 = a.local_offsets[b];
+        n_loc = a.local_offsets[b + 1] - l0;
+        if (n_loc < 0) n_loc = 0;
+    }
+    const int total = n_ret + n_loc;
+    for (int i = tid; i < f_hi - f_lo; i += kThreads) {
+        const int f = a.frame_idx[(int64_t)b * a.k_frame + f_lo + i];
+        s_frame[i] = (f >= 0 && f < a.n_frames) ? f : -1;
+    }
+    __syncthreads();
+    const T *sk = static_cast<const T *>(a.store_k) + (int64_t)g * a.store_cap * D;
+    const T *sv = static_cast<const T *>(a.store_v) + (int64_t)g * a.store_cap * D;
+    const T *lk = static_cast<const T *>(a.k_local), *lv = static_cast<const T *>(a.v_local);
+    // address of a row from its code; a row that lives nowhere reads the slab's first row (valid
+    // memory, the result is masked)
+    auto row_ptr = [&](const T *store, const T *local, int code) -> const T * {
+        if (code >= 0) return store + (int64_t)code * D;
+        if (code <= -2) return local + ((int64_t)(-2 - code) * a.Hkv + g) * D;
+        return store;
+    };
+
+    float m_run[kTileQ], z[kTileQ], o[kTileQ][E];
+#pragma unroll
+    for (int n = 0; n < kTileQ; ++n) {
+        m_run[n] = -INFINITY;
+        z[n] = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[n][e] = 0.f;
+    }
+
+    for (int c0 = 0; c0 < total; c0 += kChunk) {
+        const int n_rows = (c0 + kChunk < total ? c0 + kChunk : total) - c0;
+        // ---- where the rows of the chunk live and who sees them ----
+        for (int i = tid; i < n_rows; i += kThreads) {
+            const int r = c0 + i;
+            int code, ft = 0;
+            if (r < n_ret) {
+                const int slot = r / a.kappa;
+                const int f = s_frame[slot];
+                code = f < 0 ? -1 : f * a.kappa + (r - slot * a.kappa);
+            } else {
+                const int j = r - n_ret;
+                code = -2 - (l0 + j);
+                if (a.causal) ft = j - (n_loc - a.n_q); // token i sees local row j iff j <= n_loc - n_q + i
+            }
+            s_row[i] = code;
+            s_ft[i] = code == -1 ? INT_MAX : ft;
+        }
+        __syncthreads();
+        // ---- scores of the chunk and their maxima ----
+        if constexpr (kMfma) {
+            // 16 rows per wave and step: S^T = K Q^T, so a lane ends up with one query (lane % 16)
+            // and the four rows 4 * (lane / 16) .. +3 of the step
+            const int my_tok = token_of(lr);
+            float m_q = -INFINITY;
+            for (int R = 16 * wave; R < n_rows; R += 16 * kWaves) {
+                const int i = R + lr < n_rows ? R + lr : n_rows - 1;
+                const T *kp = row_ptr(sk, lk, s_row[i]) + lg * 8;
+                raw16 ka[D / 32];
+#pragma unroll
+                for (int kk = 0; kk < D / 32; ++kk) ka[kk] = load16(kp + kk * 32);
+                f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < D / 32; ++kk)
+                    d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kk]), qb[kk], d, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int i2 = R + 4 * lg + r;
+                    if (i2 < n_rows && lr < kTileQ) {
+                        const float sc = my_tok >= s_ft[i2] ? d[r] * a.scale_log2e : -INFINITY;
+                        s_sc[lr][i2] = sc;
+                        m_q = fmaxf(m_q, sc);
+                    }
+                }
+            }
+            m_q = xrow_max(m_q);
+            if (lg == 0 && lr < kTileQ) s_red[wave][lr][0] = m_q;
+        } else {
+            int tok[kTileQ];
+            float m_loc[kTileQ];
+#pragma unroll
+            for (int n = 0; n < kTileQ; ++n) {
+                tok[n] = token_of(n);
+                m_loc[n] = -INFINITY;
+            }
+            for (int i0 = rg; i0 < n_rows; i0 += kUnroll * RPP) {
+                // all loads of the batch first, each from an address that is valid whatever the row is
+                raw16 kr[kUnroll];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    const int i = i0 + u * RPP;
+                    kr[u] = load16(row_ptr(sk, lk, s_row[i < n_rows ? i : n_rows - 1]) + li * E);
+                }
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    const int i = i0 + u * RPP;
+                    if (i >= n_rows) break;
+                    const int ft = s_ft[i];
+                    float kx[E];
+                    Row16<T>::expand(kr[u], kx);
+#pragma unroll
+                    for (int n = 0; n < kTileQ; ++n) {
+                        float sc = 0.f;
+#pragma unroll
+                        for (int e = 0; e < E; ++e) sc = fmaf(qr[n][e], kx[e], sc);
+                        sc = row_lanes_sum<LPR>(sc);
+                        if (tok[n] < ft) sc = -INFINITY;
+                        if (li == 0) s_sc[n][i] = sc;
+                        m_loc[n] = fmaxf(m_loc[n], sc);
+                    }
+                }
+            }
+#pragma unroll
+            for (int n = 0; n < kTileQ; ++n) {
+                const float m = wave_max(m_loc[n]);
+                if (lane == 0) s_red[wave][n][0] = m;
+            }
+        }
+        __syncthreads();
+        if (tid < kTileQ) {
+            float m = s_red[0][tid][0];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) m = fmaxf(m, s_red[w][tid][0]);
+            s_max[tid] = m;
+        }
+        __syncthreads();
+        // ---- new running maximum: rescale what has been summed so far (once per chunk) ----
+        float m_ref[kTileQ]; // what the exponent subtracts: the running maximum, or 0 while nothing was seen
+#pragma unroll
+        for (int n = 0; n < kTileQ; ++n) {
+            const float m_new = fmaxf(m_run[n], s_max[n]);
+            const float corr = m_run[n] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run[n] - m_new);
+            z[n] *= corr;
+#pragma unroll
+            for (int e = 0; e < E; ++e) o[n][e] *= corr;
+            m_run[n] = m_new;
+            m_ref[n] = m_new == -INFINITY ? 0.f : m_new;
+        }
+        // ---- weights and value accumulation ----
+        for (int i0 = rg; i0 < n_rows; i0 += kUnroll * RPP) {
+            bool seen[kUnroll];
+            raw16 vr[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int i = i0 + u * RPP;
+                const int code = s_row[i < n_rows ? i : n_rows - 1];
+                seen[u] = i < n_rows && code != -1;
+                vr[u] = load16(row_ptr(sv, lv, code) + li * E);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                if (!seen[u]) continue; // what was loaded instead of a row that lives nowhere is not a value
+                const int i = i0 + u * RPP;
+                float vx[E];
+                Row16<T>::expand(vr[u], vx);
+#pragma unroll
+                for (int n = 0; n < kTileQ; ++n) {
+                    const float p = __builtin_amdgcn_exp2f(s_sc[n][i] - m_ref[n]); // exp2(-inf) = 0 for a masked row
+                    z[n] += p;
+#pragma unroll
+                    for (int e = 0; e < E; ++e) o[n][e] = fmaf(p, vx[e], o[n][e]);
+                }
+            }
+        }
+        __syncthreads(); // the tables are rewritten by the next chunk
+    }
+
+    // ---- add the rows held by different lanes: inside a wave, then across the waves ----
+#pragma unroll
+    for (int n = 0; n < kTileQ; ++n) {
+        z[n] = same_piece_sum<LPR>(z[n]);
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[n][e] = same_piece_sum<LPR>(o[n][e]);
+    }
+    if (lane < LPR) {
+#pragma unroll
+        for (int n = 0; n < kTileQ; ++n)
+#pragma unroll
+            for (int e = 0; e < E; ++e) s_red[wave][n][li * E + e] = o[n][e];
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int n = 0; n < kTileQ; ++n) s_z[wave][n] = z[n];
+    }
+    __syncthreads();
+    // the split's record of a query: [0] running maximum, [1] normaliser, [2..] unnormalised output
+    for (int idx = tid; idx < kTileQ * (D + 1); idx += kThreads) {
+        const int n = idx / (D + 1), d = idx - n * (D + 1);
+        const int qq = qt * kTileQ + n;
+        if (qq >= n_queries) continue;
+        float val = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) val += d == 0 ? s_z[w][n] : s_red[w][n][d - 1];
+        const int i = qq / a.G, h = g * a.G + qq % a.G;
+        a.part[((((int64_t)b * a.n_q + i) * a.Hq + h) * a.n_split + sp) * (D + 2) + 1 + d] = val;
+    }
+    if (tid == 0) { // the running maximum is the same in every lane
+#pragma unroll
+        for (int n = 0; n < kTileQ; ++n) {
+            const int qq = qt * kTileQ + n;
+            if (qq < n_queries) {
+                const int i = qq / a.G, h = g * a.G + qq % a.G;
+                a.part[((((int64_t)b * a.n_q + i) * a.Hq + h) * a.n_split + sp) * (D + 2)] = m_run[n];
+            }
+        }
+    }
+}
+
+// out[b][i][h][:] = sum_s o_s 2^(m_s - m) / sum_s z_s 2^(m_s - m), m = max_s m_s; zero if no split saw a key
+template <typename T, int D>
+__global__ void attend_combine_kernel(const float *__restrict__ part, int n_split, T *__restrict__ out) {
+    const int64_t row = blockIdx.x;
+    const float *p = part + row * n_split * (D + 2);
+    float m = -INFINITY;
+    for (int s = 0; s < n_split; ++s) m = fmaxf(m, p[s * (D + 2)]);
+    for (int d = threadIdx.x; d < D; d += blockDim.x) {
+        float zs = 0.f, os = 0.f;
+        if (m > -INFINITY) {
+            for (int s = 0; s < n_split; ++s) {
+                const float ms = p[s * (D + 2)];
+                const float w = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - m);
+                zs = fmaf(p[s * (D + 2) + 1], w, zs);
+                os = fmaf(p[s * (D + 2) + 2 + d], w, os);
+            }
+        }
+        store_out(out + row * D + d, zs > 0.f ? os / zs : 0.f);
+    }
+}
+
+template <typename T, int D>
+hipError_t launch_typed(const AttendArgs &a, int B, void *out, hipStream_t st) {
+    hipLaunchKernelGGL((attend_partial_kernel<T, D>), dim3(a.n_split, a.Hkv * a.n_qtiles, B), dim3(kThreads), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((attend_combine_kernel<T, D>), dim3((unsigned)(B * a.n_q * a.Hq)), dim3(D < 64 ? 64 : D), 0, st,
+                       a.part, a.n_split, static_cast<T *>(out));
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_by_dim(const AttendArgs &a, int D, int B, void *out, hipStream_t st) {
+    switch (D) {
+    case 16: return launch_typed<T, 16>(a, B, out, st);
+    case 32: return launch_typed<T, 32>(a, B, out, st);
+    case 64: return launch_typed<T, 64>(a, B, out, st);
+    case 128: return launch_typed<T, 128>(a, B, out, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+} // namespace
+
+hipError_t launch_attend(const Ctx &c, int layer, const void *q, int n_q, const int32_t *frame_idx, int k_frame,
+                         const void *k_local, const void *v_local, const int32_t *local_offsets, int B, int causal,
+                         void *out, hipStream_t st) {
+    AttendArgs a;
+    a.q = q;
+    a.frame_idx = k_frame > 0 ? frame_idx : nullptr;
+    a.k_local = k_local;
+    a.v_local = v_local;
+    a.local_offsets = local_offsets;
+    const int64_t slab = (int64_t)c.store_cap * c.cfg.head_dim * c.esz; // bytes of one (layer, head) slab
+    a.store_k = static_cast<const unsigned char *>(c.store_k) + (int64_t)layer * c.cfg.n_kv_heads * slab;
+    a.store_v = static_cast<const unsigned char *>(c.store_v) + (int64_t)layer * c.cfg.n_kv_heads * slab;
+    a.part = c.attend_part;
+    a.store_cap = c.store_cap;
+    a.n_q = n_q;
+    a.Hq = c.cfg.n_q_heads;
+    a.Hkv = c.cfg.n_kv_heads;
+    a.G = c.group;
+    a.k_frame = k_frame > 0 ? k_frame : 0;
+    a.kappa = c.kappa;
+    a.n_frames = (int)c.n_frames;
+    a.n_qtiles = (n_q * c.group + kTileQ - 1) / kTileQ;
+    a.causal = causal;
+    a.scale_log2e = 1.4426950408889634f / sqrtf((float)c.cfg.head_dim);
+    // enough workgroups to fill the chip, at most kAttendMaxSplit splits, at least one frame each
+    int n_split = (2 * 256 + B * a.Hkv * a.n_qtiles - 1) / (B * a.Hkv * a.n_qtiles);
+    if (n_split > kAttendMaxSplit) n_split = kAttendMaxSplit;
+    if (n_split > a.k_frame) n_split = a.k_frame;
+    if (n_split < 1) n_split = 1;
+    a.frames_per_split = a.k_frame > 0 ? (a.k_frame + n_split - 1) / n_split : 0;
+    if (a.k_frame > 0) n_split = (a.k_frame + a.frames_per_split - 1) / a.frames_per_split;
+    a.n_split = n_split;
+    return c.cfg.dtype == MUKV_BF16 ? launch_by_dim<uint16_t>(a, c.cfg.head_dim, B, out, st)
+                                    : launch_by_dim<float>(a, c.cfg.head_dim, B, out, st);
+}
+
+} // namespace mukv

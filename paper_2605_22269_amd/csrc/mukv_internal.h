@@ -31,6 +31,9 @@ struct ProfEntry {
 
 struct ChunkArgs;
 
+constexpr int kAttendMaxTokens = 16; // query tokens per question in one mukv_attend call
+constexpr int kAttendMaxSplit = 8;   // workgroups sharing the frame list of one (question, KV head)
+
 struct Ctx {
     mukv_config cfg;
     bool profiling;
@@ -82,6 +85,8 @@ struct Ctx {
     uint32_t *u_mask;  // [max_questions][max_frames] super-patches of a frame chosen at any level
     int32_t *u_entry;  // [max_questions][max_frames][3] chosen frames in time order: frame, mask, first output row
     int32_t *u_count;  // [max_questions][2] entries, rows
+    // attention over the retrieved context: per (question, token, head, split) maximum, normaliser, output
+    float *attend_part; // [max_questions][kAttendMaxTokens][Hq][kAttendMaxSplit][D+2]
 };
 
 // ---- a batch of chunks processed by one chain of launches ----
@@ -192,6 +197,9 @@ inline hipError_t allow_dynamic_lds(const void *kernel, size_t bytes, int device
 
 // True when the matrix-core attention kernel covers this configuration.
 bool att_mfma_supported(const mukv_config &c);
+hipError_t launch_attend(const Ctx &c, int layer, const void *q, int n_q, const int32_t *frame_idx, int k_frame,
+                         const void *k_local, const void *v_local, const int32_t *local_offsets, int B, int causal,
+                         void *out, hipStream_t st);
 
 // LDS bytes the generic attention kernel needs for P tokens of D features when it accumulates
 // in a type of r_size bytes.

@@ -195,5 +195,38 @@ class Pair:
             np.testing.assert_array_equal(np_view(kg[b]), ko)
             np.testing.assert_array_equal(np_view(vg[b]), vo)
 
+    def check_attend(self, layer, n_q, frame_idx, local_lens=None, causal=True, seed=0):
+        """Attention of n_q new tokens per question over [kept rows of frame_idx[b], local rows of b]
+        (Eq. 9) against the oracle, question by question.  frame_idx: list of lists (or None);
+        local_lens: local rows per question (or None).  Returns the largest error (absolute, or
+        relative to the largest output where that exceeds one)."""
+        w, tol = self.w, TOL[self.w.dtype]
+        B = len(frame_idx) if frame_idx is not None else len(local_lens)
+        g = torch.Generator().manual_seed(seed)
+        q = torch.randn(B, n_q, w.n_q_heads, w.head_dim, generator=g).to(w.torch_dtype)
+        fi = None if frame_idx is None else torch.tensor(frame_idx, dtype=torch.int32, device="cuda")
+        kl = vl = lo = None
+        if local_lens is not None:
+            offs = np.zeros(B + 1, np.int32)
+            offs[1:] = np.cumsum(local_lens)
+            kl = torch.randn(int(offs[-1]), w.n_kv_heads, w.head_dim, generator=g).to(w.torch_dtype)
+            vl = torch.randn(int(offs[-1]), w.n_kv_heads, w.head_dim, generator=g).to(w.torch_dtype)
+            lo = torch.from_numpy(offs).cuda()
+        out = self.gpu.attend(layer, q.cuda(), fi, None if kl is None else kl.cuda(), None if vl is None else vl.cuda(),
+                              lo, causal)
+        torch.cuda.synchronize()
+        got = to_f64(np_view(out.cpu()))
+        worst = 0.0
+        for b in range(B):
+            kb = vb = None
+            if local_lens is not None:
+                kb, vb = np_view(kl[offs[b]:offs[b + 1]]), np_view(vl[offs[b]:offs[b + 1]])
+            want = self.orc.attend(layer, np_view(q[b]), [] if frame_idx is None else frame_idx[b], kb, vb, causal)
+            # the output is rounded to the payload type: the bar scales with the values, as for the key tables
+            err = float(np.abs(got[b] - want).max()) / max(1.0, float(np.abs(want).max()))
+            assert err <= tol, (b, err)
+            worst = max(worst, err)
+        return worst
+
     def close(self):
         self.gpu.close()

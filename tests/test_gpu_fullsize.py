@@ -144,12 +144,38 @@ def check_union(w, gpu, ref, question):
     return n
 
 
+def check_decode(w, gpu, ref, hits, layers, n_q=1, n_local=32, seed=0):
+    """The step after the path (Eq. 9) at full size: new tokens of every question attend to the kept
+    rows of the frames retrieved for it (hits: per-question index lists) plus local rows."""
+    B = len(hits)
+    g = torch.Generator().manual_seed(seed)
+    q = torch.randn(B, n_q, w.n_q_heads, w.head_dim, generator=g).to(w.torch_dtype)
+    kl = torch.randn(B * n_local, w.n_kv_heads, w.head_dim, generator=g).to(w.torch_dtype)
+    vl = torch.randn(B * n_local, w.n_kv_heads, w.head_dim, generator=g).to(w.torch_dtype)
+    lo = (torch.arange(B + 1, dtype=torch.int32) * n_local).cuda()
+    idx = torch.tensor(np.asarray(hits), dtype=torch.int32, device="cuda")
+    worst = 0.0
+    for layer in layers:
+        out = gpu.attend(layer, q.cuda(), idx, kl.cuda(), vl.cuda(), lo, True)
+        torch.cuda.synchronize()
+        got = np_view(out.cpu())
+        got = (got.astype(np.uint32) << 16).view(np.float32).astype(np.float64) if got.dtype == np.uint16 else got.astype(np.float64)
+        for b in range(B):
+            want = ref.attend(layer, np_view(q[b]), hits[b], np_view(kl[b * n_local:(b + 1) * n_local]),
+                              np_view(vl[b * n_local:(b + 1) * n_local]), True)
+            err = float(np.abs(got[b] - want).max()) / max(1.0, float(np.abs(want).max()))
+            assert err <= (2e-2 if w.dtype == "bf16" else 1e-5), (layer, b, err)
+            worst = max(worst, err)
+    return worst
+
+
 def test_config2_7b_256_frames():
     w = W["7b"]
     gpu, ref, info = run_full(w, seed=1002)
     print("7b:", info)
     for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
-        check_questions(w, gpu, ref, [synth.random_question(w, w.question_tokens, 77)], mode)
+        hits = check_questions(w, gpu, ref, [synth.random_question(w, w.question_tokens, 77)], mode)
+    print("7b: decode attention over the retrieved rows, worst error", check_decode(w, gpu, ref, hits, (0, w.n_layers - 1), seed=5))
     gpu.close()
 
 
@@ -174,6 +200,9 @@ def test_config3_and_4_one_hour_stream():
         targets.append(set(tgt.tolist()))
         qs.append(synth.planted_question(wq, torch.from_numpy(ref.rep_frame_k[tgt.numpy()]), n, 81 + i))
     hits = check_questions(wq, gpu, ref, qs)
+    print("retrieval-heavy: decode attention of 64 questions, worst error",
+          check_decode(wq, gpu, ref, hits, (w.n_layers - 1,), seed=6),
+          "; 3 new tokens of 8 questions:", check_decode(wq, gpu, ref, hits[:8], (0,), n_q=3, seed=7))
     check_patch_questions(wq, gpu, ref, qs[:20], mk.MUKV_SEMI)
     found = sum(len(t & set(int(x) for x in h)) for t, h in zip(targets, hits))
     total = sum(len(t) for t in targets)

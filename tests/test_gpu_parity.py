@@ -8,7 +8,7 @@ import torch
 from oracle import oracle as orc
 from paper_2605_22269_amd import binding as mk
 from paper_2605_22269_amd import synth
-from mukv_testlib import Pair, gpu_context, np_view
+from mukv_testlib import Pair, gpu_context, np_view, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -526,6 +526,9 @@ def test_seeded_sweep_of_small_shapes(i):
         p.check_retrieve(qs, mode, w.k_seg, w.k_frame, w.lambda_frame)
     p.check_retrieve(qs, mk.MUKV_SEMI, w.k_seg, w.k_frame, w.lambda_frame, n_visible=max(1, w.n_frames - 2))
     p.check_retrieve_patches(qs, (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL)[i % 3], w.k_seg, w.k_frame + 3, w.lambda_frame)
+    out, _ = p.check_retrieve(qs, mk.MUKV_SEMI, w.k_seg, w.k_frame, w.lambda_frame)
+    idx = [[int(x) for x in row] for row in out["frame_idx"].cpu().numpy()]
+    p.check_attend(i % w.n_layers, 1 + i % 5, idx, [1 + i % 5 + (3 * i + b) % 9 for b in range(3)], causal=bool(i % 2), seed=i)
     p.close()
 
 
@@ -728,4 +731,80 @@ def test_snapshot_argument_errors():
     p.check_compress()
     other.close()
     tight.close()
+    p.close()
+
+
+# ------------------------------------------- attention over the retrieved context (Eq. 9) ------
+@pytest.mark.parametrize("name,frames,kw", [("tiny", 20, {}), ("7b", 24, {"n_layers": 2}), ("72b", 16, {"n_layers": 2})])
+def test_attention_over_retrieved_and_local_rows(name, frames, kw):
+    w = W[name].scaled(n_frames=frames, n_questions=4, **kw)
+    p = Pair(w, seed=180, chunk=4)
+    p.ingest()
+    idx = [[3, frames - 1, -1, 0, 7], [-1, -1, -1, -1, -1], [5, 5, 2, frames + 3, 9], [1, 2, 3, 4, 6]]  # skipped, doubled, out of range
+    last = w.n_layers - 1
+    p.check_attend(last, 1, idx, [1, 4, 9, 30], causal=True, seed=1)        # decode: one token, ragged local rows
+    p.check_attend(0, 3, idx, [3, 5, 3, 17], causal=True, seed=2)           # layer 0, three tokens, causal among them
+    p.check_attend(last, 3, idx, [3, 5, 3, 17], causal=False, seed=3)
+    p.check_attend(last, 16, idx, [16, 20, 16, 40], causal=True, seed=4)    # the most tokens a call takes
+    p.check_attend(last, 2, idx, None, seed=5)                              # no local rows; question 1 sees nothing: zeros
+    p.check_attend(last, 5, None, [5, 8, 5, 6], causal=True, seed=6)        # no retrieved rows: plain causal self-attention
+    p.check_attend(last, 4, idx, [2, 1, 0, 3], causal=True, seed=7)         # fewer local rows than tokens
+    p.close()
+
+
+def test_attention_over_long_contexts_and_many_questions():
+    # 64 questions (one split per workgroup, rows taken in several chunks of 512) and one
+    # question (the frame list split over workgroups); local rows longer than a chunk
+    w = W["7b"].scaled(n_frames=40, n_layers=2, n_questions=64)
+    p = Pair(w, seed=181, chunk=8)
+    p.ingest()
+    rs = np.random.default_rng(5)
+    idx = [[int(x) for x in rs.permutation(40)[:32]] for _ in range(64)]
+    assert 32 * p.gpu.kappa > 512
+    p.check_attend(1, 2, idx, [int(x) for x in rs.integers(2, 40, 64)], causal=True, seed=8)
+    p.check_attend(1, 1, idx[:1], [700], causal=True, seed=9)
+    p.check_attend(0, 1, [idx[0][:1]], [3], causal=True, seed=10)
+    p.close()
+
+
+def test_attention_follows_the_retrieval_without_a_gather():
+    # the indices stay on the device between the two calls; extreme scores (near one-hot rows)
+    w = W["7b"].scaled(n_frames=48, n_layers=2, n_questions=3)
+    p = Pair(w, seed=182, chunk=8)
+    p.ingest()
+    qs = questions_for(w, [6, 11, 4], 1300)
+    out, res = p.check_retrieve(qs, mk.MUKV_SEMI, 2, 6, 0.3)
+    g = torch.Generator().manual_seed(3)
+    q = (torch.randn(3, 1, w.n_q_heads, w.head_dim, generator=g) * 6).to(w.torch_dtype)
+    got = p.gpu.attend(1, q.cuda(), out["frame_idx"])
+    torch.cuda.synchronize()
+    for b in range(3):
+        want = p.orc.attend(1, np_view(q[b]), res[b]["frame_idx"])
+        assert np.abs(to_f64(np_view(got[b].cpu())) - want).max() <= 2e-2 * max(1.0, np.abs(want).max())
+    p.close()
+
+
+def test_attention_argument_errors():
+    w = W["tiny"].scaled(n_frames=8, n_layers=2, n_questions=2)
+    p = Pair(w, seed=183, chunk=4)
+    p.ingest()
+    g = p.gpu
+    q = torch.zeros(2, 1, w.n_q_heads, w.head_dim, dtype=w.torch_dtype, device="cuda")
+    idx = torch.zeros(2, 3, dtype=torch.int32, device="cuda")
+    kl = torch.zeros(4, w.n_kv_heads, w.head_dim, dtype=w.torch_dtype, device="cuda")
+    lo = torch.tensor([0, 2, 4], dtype=torch.int32, device="cuda")
+
+    def status(fn):
+        with pytest.raises(mk.MuKVError) as e:
+            fn()
+        return e.value.status
+
+    assert status(lambda: g.attend(w.n_layers, q, idx)) == mk.MUKV_ERR_INVALID_ARG          # no such layer
+    assert status(lambda: g.attend(0, q, idx, kl, None, lo)) == mk.MUKV_ERR_INVALID_ARG     # local rows given in part
+    big = torch.zeros(2, 17, w.n_q_heads, w.head_dim, dtype=w.torch_dtype, device="cuda")
+    assert status(lambda: g.attend(0, big, idx)) == mk.MUKV_ERR_UNSUPPORTED                 # more than 16 tokens
+    three = torch.zeros(3, 1, w.n_q_heads, w.head_dim, dtype=w.torch_dtype, device="cuda")
+    assert status(lambda: g.attend(0, three, None, kl, kl, lo)) == mk.MUKV_ERR_CAPACITY     # more questions than the context holds
+    assert status(lambda: mk.mukv_attend(g.h, 0, q.data_ptr(), 1, None, 3, None, None, None, 2, 1, q.data_ptr(),
+                                         None)) == mk.MUKV_ERR_INVALID_ARG                   # k_frame without a list
     p.close()
