@@ -320,11 +320,23 @@ def main():
                     ctx.attend(layer, q_dec[:nb], r64["frame_idx"][:nb], kl[:nb * n_loc], vl[:nb * n_loc], lo[:nb + 1],
                                True, out=o_dec[:nb])
             decode_layers()
-            dms = timed(decode_layers, 10)
+            dms_eager = timed(decode_layers, 10)
+            dms, how = dms_eager, "eager"
+            if not a.no_graph:      # a serving loop would replay the decode step as one graph
+                try:
+                    torch.cuda.synchronize()
+                    dgraph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(dgraph):
+                        decode_layers()
+                    torch.cuda.synchronize()
+                    dgraph.replay()
+                    dms, how = timed(dgraph.replay, 10), "hipgraph"
+                except Exception as e:
+                    print(f"bench.py: decode graph capture failed ({e}); eager timing kept", file=sys.stderr)
             kv_bytes = nb * rows_q * b_tok                      # K and V rows of one layer, read once
             res["decode_attention"][f"{nb}_questions"] = {
-                "ms_all_layers": dms, "us_per_layer_call": dms / L * 1e3, "kv_bytes_per_layer_call": kv_bytes,
-                "GBs": kv_bytes * L / (dms * 1e-3) / 1e9}
+                "launch": how, "ms_all_layers": dms, "us_per_layer_call": dms / L * 1e3, "ms_all_layers_eager": dms_eager,
+                "kv_bytes_per_layer_call": kv_bytes, "GBs": kv_bytes * L / (dms * 1e-3) / 1e9}
 
     # ---- the super-patch level of the search on the same cache: one question, k_g = 20 --------
     p_out = {"patch_idx": torch.empty(B, 20, dtype=torch.int32, device=dev),

@@ -31,6 +31,7 @@ constexpr int kTileQ = 8;    // queries per workgroup
 constexpr int kChunk = 512;  // rows whose scores are held in LDS at a time
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;   // rows a lane has in flight
+constexpr int kStepsA = 2;   // matrix path: 16-row steps of a wave whose loads are issued together
 
 struct AttendArgs {
     const void *q;            // [B][n_q][Hq][D]
@@ -88,8 +89,10 @@ __device__ __forceinline__ float same_piece_sum(float v) {
     if constexpr (LPR <= 2) v += lane_xor<2>(v);
     if constexpr (LPR <= 4) v += lane_xor<4>(v);
     if constexpr (LPR <= 8) v += lane_xor<8>(v);
-    if constexpr (LPR <= 16) v += lane_xor<16>(v);
-    if constexpr (LPR <= 32) v += lane_xor<32>(v);
+    // across rows of 16 lanes: the LDS crossbar shuffle (the register-swap instructions, used 72
+    // times in a row at the end of the kernel, cost it ~70 registers)
+    if constexpr (LPR <= 16) v += __shfl_xor(v, 16);
+    if constexpr (LPR <= 32) v += __shfl_xor(v, 32);
     return v;
 }
 
@@ -110,11 +113,15 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
     constexpr bool kMfma = sizeof(T) == 2 && D % 32 == 0;
     constexpr int kWaves = kThreads / 64;
     static_assert(LPR >= 1 && LPR <= 32, "a row fits in half a wave");
-    __shared__ float s_sc[kTileQ][kChunk];  // scores of the chunk, log2 units
+    // scores of the chunk, log2 units; after the last chunk the same memory takes the per-wave outputs
+    __shared__ float s_sc[kTileQ][kChunk];
+    static_assert(kWaves * (D > 64 ? D : 64) <= kChunk, "the per-wave outputs fit where the scores were");
     __shared__ int s_row[kChunk]; // where row i of the chunk lives: >= 0 store row, <= -2 local row -2 - code, -1 nowhere
     __shared__ int s_ft[kChunk];  // first token that sees the row (INT_MAX: nobody does)
-    __shared__ float s_red[kWaves][kTileQ][D > 64 ? D : 64]; // per-wave maxima, later per-wave outputs
-    __shared__ float s_max[kTileQ];
+    __shared__ float s_wmax[kWaves][kTileQ]; // per-wave maxima of the chunk
+    __shared__ float s_run[kTileQ];  // running maximum of every query over the chunks so far
+    __shared__ float s_corr[kTileQ]; // factor that brings the sums so far to the new maximum
+    __shared__ float s_ref[kTileQ];  // what the exponent subtracts: the running maximum, or 0 while nothing was seen
     __shared__ float s_z[kWaves][kTileQ];
     __shared__ int s_frame[kMaxGatherK]; // this split's frames; -1: names no frame of the cache
     const int sp = blockIdx.x, g = blockIdx.y % a.Hkv, qt = blockIdx.y / a.Hkv, b = blockIdx.z;
@@ -137,17 +144,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
     // log2 units.  Matrix path: the queries as the B operand (column lane % 16 = query, 8 features
     // from 8 * (lane / 16) of every 32), unscaled.
     float qr[kMfma ? 1 : kTileQ][E];
-    bf16x8 qb[kMfma ? D / 32 : 1];
-    if constexpr (kMfma) {
-        bool ok;
-        const int64_t off = query_row(lr, &ok);
-#pragma unroll
-        for (int kk = 0; kk < D / 32; ++kk) {
-            raw16 u = load16(q + off + kk * 32 + lg * 8);
-            if (!ok) u = raw16{0u, 0u, 0u, 0u};
-            qb[kk] = __builtin_bit_cast(bf16x8, u);
-        }
-    } else {
+    if constexpr (!kMfma) {
 #pragma unroll
         for (int n = 0; n < kTileQ; ++n) {
             bool ok;
@@ -186,10 +183,10 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
         return store;
     };
 
-    float m_run[kTileQ], z[kTileQ], o[kTileQ][E];
+    float z[kTileQ], o[kTileQ][E];
+    if (tid < kTileQ) s_run[tid] = -INFINITY; // read again only after the barriers of the first chunk
 #pragma unroll
     for (int n = 0; n < kTileQ; ++n) {
-        m_run[n] = -INFINITY;
         z[n] = 0.f;
 #pragma unroll
         for (int e = 0; e < E; ++e) o[n][e] = 0.f;
@@ -218,30 +215,51 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
         if constexpr (kMfma) {
             // 16 rows per wave and step: S^T = K Q^T, so a lane ends up with one query (lane % 16)
             // and the four rows 4 * (lane / 16) .. +3 of the step
+            // (the operand is fetched per chunk so that it is not held through the value pass)
+            bf16x8 qb[D / 32];
+            {
+                bool ok;
+                const int64_t off = query_row(lr, &ok);
+#pragma unroll
+                for (int kk = 0; kk < D / 32; ++kk) {
+                    raw16 u = load16(q + off + kk * 32 + lg * 8);
+                    if (!ok) u = raw16{0u, 0u, 0u, 0u};
+                    qb[kk] = __builtin_bit_cast(bf16x8, u);
+                }
+            }
             const int my_tok = token_of(lr);
             float m_q = -INFINITY;
-            for (int R = 16 * wave; R < n_rows; R += 16 * kWaves) {
-                const int i = R + lr < n_rows ? R + lr : n_rows - 1;
-                const T *kp = row_ptr(sk, lk, s_row[i]) + lg * 8;
-                raw16 ka[D / 32];
+            for (int R0 = 16 * wave; R0 < n_rows; R0 += kStepsA * 16 * kWaves) {
+                // the key rows of kStepsA steps are requested together
+                raw16 ka[kStepsA][D / 32];
 #pragma unroll
-                for (int kk = 0; kk < D / 32; ++kk) ka[kk] = load16(kp + kk * 32);
-                f32x4 d = {0.f, 0.f, 0.f, 0.f};
+                for (int t = 0; t < kStepsA; ++t) {
+                    const int i = R0 + t * 16 * kWaves + lr;
+                    const T *kp = row_ptr(sk, lk, s_row[i < n_rows ? i : n_rows - 1]) + lg * 8;
 #pragma unroll
-                for (int kk = 0; kk < D / 32; ++kk)
-                    d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kk]), qb[kk], d, 0, 0, 0);
+                    for (int kk = 0; kk < D / 32; ++kk) ka[t][kk] = load16(kp + kk * 32);
+                }
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int i2 = R + 4 * lg + r;
-                    if (i2 < n_rows && lr < kTileQ) {
-                        const float sc = my_tok >= s_ft[i2] ? d[r] * a.scale_log2e : -INFINITY;
-                        s_sc[lr][i2] = sc;
-                        m_q = fmaxf(m_q, sc);
+                for (int t = 0; t < kStepsA; ++t) {
+                    const int R = R0 + t * 16 * kWaves;
+                    if (R >= n_rows) break;
+                    f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int kk = 0; kk < D / 32; ++kk)
+                        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[t][kk]), qb[kk], d, 0, 0, 0);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int i2 = R + 4 * lg + r;
+                        if (i2 < n_rows && lr < kTileQ) {
+                            const float sc = my_tok >= s_ft[i2] ? d[r] * a.scale_log2e : -INFINITY;
+                            s_sc[lr][i2] = sc;
+                            m_q = fmaxf(m_q, sc);
+                        }
                     }
                 }
             }
             m_q = xrow_max(m_q);
-            if (lg == 0 && lr < kTileQ) s_red[wave][lr][0] = m_q;
+            if (lg == 0 && lr < kTileQ) s_wmax[wave][lr] = m_q;
         } else {
             int tok[kTileQ];
             float m_loc[kTileQ];
@@ -280,28 +298,29 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
 #pragma unroll
             for (int n = 0; n < kTileQ; ++n) {
                 const float m = wave_max(m_loc[n]);
-                if (lane == 0) s_red[wave][n][0] = m;
+                if (lane == 0) s_wmax[wave][n] = m;
             }
         }
         __syncthreads();
+        // ---- new running maximum: rescale what has been summed so far (once per chunk) ----
         if (tid < kTileQ) {
-            float m = s_red[0][tid][0];
+            float m = s_wmax[0][tid];
 #pragma unroll
-            for (int w = 1; w < kWaves; ++w) m = fmaxf(m, s_red[w][tid][0]);
-            s_max[tid] = m;
+            for (int w = 1; w < kWaves; ++w) m = fmaxf(m, s_wmax[w][tid]);
+            const float m_old = s_run[tid], m_new = fmaxf(m_old, m);
+            s_corr[tid] = m_old == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_old - m_new);
+            s_run[tid] = m_new;
+            s_ref[tid] = m_new == -INFINITY ? 0.f : m_new;
         }
         __syncthreads();
-        // ---- new running maximum: rescale what has been summed so far (once per chunk) ----
-        float m_ref[kTileQ]; // what the exponent subtracts: the running maximum, or 0 while nothing was seen
+        if (c0 > 0) {
 #pragma unroll
-        for (int n = 0; n < kTileQ; ++n) {
-            const float m_new = fmaxf(m_run[n], s_max[n]);
-            const float corr = m_run[n] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run[n] - m_new);
-            z[n] *= corr;
+            for (int n = 0; n < kTileQ; ++n) {
+                const float corr = s_corr[n];
+                z[n] *= corr;
 #pragma unroll
-            for (int e = 0; e < E; ++e) o[n][e] *= corr;
-            m_run[n] = m_new;
-            m_ref[n] = m_new == -INFINITY ? 0.f : m_new;
+                for (int e = 0; e < E; ++e) o[n][e] *= corr;
+            }
         }
         // ---- weights and value accumulation ----
         for (int i0 = rg; i0 < n_rows; i0 += kUnroll * RPP) {
@@ -322,7 +341,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
                 Row16<T>::expand(vr[u], vx);
 #pragma unroll
                 for (int n = 0; n < kTileQ; ++n) {
-                    const float p = __builtin_amdgcn_exp2f(s_sc[n][i] - m_ref[n]); // exp2(-inf) = 0 for a masked row
+                    const float p = __builtin_amdgcn_exp2f(s_sc[n][i] - s_ref[n]); // exp2(-inf) = 0 for a masked row
                     z[n] += p;
 #pragma unroll
                     for (int e = 0; e < E; ++e) o[n][e] = fmaf(p, vx[e], o[n][e]);
@@ -343,7 +362,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
 #pragma unroll
         for (int n = 0; n < kTileQ; ++n)
 #pragma unroll
-            for (int e = 0; e < E; ++e) s_red[wave][n][li * E + e] = o[n][e];
+            for (int e = 0; e < E; ++e) s_sc[n][wave * (D > 64 ? D : 64) + li * E + e] = o[n][e];
     }
     if (lane == 0) {
 #pragma unroll
@@ -357,18 +376,15 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
         if (qq >= n_queries) continue;
         float val = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) val += d == 0 ? s_z[w][n] : s_red[w][n][d - 1];
+        for (int w = 0; w < kWaves; ++w) val += d == 0 ? s_z[w][n] : s_sc[n][w * (D > 64 ? D : 64) + d - 1];
         const int i = qq / a.G, h = g * a.G + qq % a.G;
         a.part[((((int64_t)b * a.n_q + i) * a.Hq + h) * a.n_split + sp) * (D + 2) + 1 + d] = val;
     }
-    if (tid == 0) { // the running maximum is the same in every lane
-#pragma unroll
-        for (int n = 0; n < kTileQ; ++n) {
-            const int qq = qt * kTileQ + n;
-            if (qq < n_queries) {
-                const int i = qq / a.G, h = g * a.G + qq % a.G;
-                a.part[((((int64_t)b * a.n_q + i) * a.Hq + h) * a.n_split + sp) * (D + 2)] = m_run[n];
-            }
+    if (tid < kTileQ) {
+        const int qq = qt * kTileQ + tid;
+        if (qq < n_queries) {
+            const int i = qq / a.G, h = g * a.G + qq % a.G;
+            a.part[((((int64_t)b * a.n_q + i) * a.Hq + h) * a.n_split + sp) * (D + 2)] = s_run[tid];
         }
     }
 }
@@ -441,8 +457,10 @@ hipError_t launch_attend(const Ctx &c, int layer, const void *q, int n_q, const 
     a.n_qtiles = (n_q * c.group + kTileQ - 1) / kTileQ;
     a.causal = causal;
     a.scale_log2e = 1.4426950408889634f / sqrtf((float)c.cfg.head_dim);
-    // enough workgroups to fill the chip, at most kAttendMaxSplit splits, at least one frame each
-    int n_split = (2 * 256 + B * a.Hkv * a.n_qtiles - 1) / (B * a.Hkv * a.n_qtiles);
+    // about three workgroups per compute unit (what fits at once): a workgroup walks its rows in
+    // dependent batches of loads, so shorter lists finish sooner; at most kAttendMaxSplit splits,
+    // at least one frame each
+    int n_split = (3 * 256 + B * a.Hkv * a.n_qtiles - 1) / (B * a.Hkv * a.n_qtiles);
     if (n_split > kAttendMaxSplit) n_split = kAttendMaxSplit;
     if (n_split > a.k_frame) n_split = a.k_frame;
     if (n_split < 1) n_split = 1;
