@@ -159,6 +159,53 @@ int orc_fft_signal(const void *k, int dtype, int n_frames, int Hkv, int P,
 }
 
 /*
+ * Eq. 2-3, the other reading of the transform's axis: along the TOKEN axis of
+ * the frame, separately for every feature of every KV head:
+ *   Z_g[m][d] = sum_j K_g[j][d] * exp(-2*pi*i*m*j/P),  m = 0..P-1
+ *   I_fft[m]  = 1/(Hkv*D) * sum_g sum_d |Z_g[m][d]|
+ * (row m of Z is then a frequency of the frame, not a token; the result still
+ * has one value per row, as Eq. 3 states).  Direct O(P^2) evaluation.  The keys
+ * are real, so |Z[P-m]| = |Z[m]| exactly: rows 0..P/2 are evaluated and rows
+ * above P/2 take the value of their mirror row, which makes the tie between
+ * the two exact (it then resolves to the lower row like any other tie).
+ * out: [n_frames][P].
+ */
+int orc_fft_signal_token(const void *k, int dtype, int n_frames, int Hkv, int P,
+                         int D, double *out)
+{
+    const int64_t T = (int64_t)n_frames * P;
+    double *cs = (double *)malloc(sizeof(double) * (size_t)P * 2);
+    for (int r = 0; r < P; ++r) {
+        cs[2 * r] = cos(2.0 * M_PI * (double)r / (double)P);
+        cs[2 * r + 1] = sin(2.0 * M_PI * (double)r / (double)P);
+    }
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (int f = 0; f < n_frames; ++f) {
+        for (int m = 0; m <= P / 2; ++m) {
+            double total = 0.0;
+            for (int g = 0; g < Hkv; ++g) {
+                for (int d = 0; d < D; ++d) {
+                    double re = 0.0, im = 0.0;
+                    for (int j = 0; j < P; ++j) {
+                        const int r = (int)(((int64_t)m * j) % P);
+                        const double x = widen(k, dtype, ((int64_t)g * T + (int64_t)f * P + j) * D + d);
+                        re += x * cs[2 * r];
+                        im -= x * cs[2 * r + 1];
+                    }
+                    total += sqrt(re * re + im * im);
+                }
+            }
+            out[(int64_t)f * P + m] = total / ((double)Hkv * (double)D);
+        }
+        for (int m = P / 2 + 1; m < P; ++m) out[(int64_t)f * P + m] = out[(int64_t)f * P + (P - m)];
+    }
+    free(cs);
+    return 0;
+}
+
+/*
  * Eq. 4 (Sec. 3.3, dual signal fusion).  Per frame, each signal is min-max
  * normalised to [0,1] over the frame's P values (a constant signal maps to all
  * zeros), then I = alpha*att_hat + (1-alpha)*fft_hat.  Either input may be NULL

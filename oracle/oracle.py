@@ -105,12 +105,18 @@ def att_signal(q, k, n_frames, P, causal=True):
     return out
 
 
-def fft_signal(k, n_frames, P):
+FEATURE_AXIS, TOKEN_AXIS = 0, 1
+
+
+def fft_signal(k, n_frames, P, axis=FEATURE_AXIS):
+    """Eq. 2-3.  axis: the transform runs along each token's features (the reading
+    taken by default) or along the frame's tokens, feature by feature."""
     k = _c(k)
     Hkv, T, D = k.shape
     assert T == n_frames * P
     out = np.empty((n_frames, P), np.float64)
-    rc = lib().orc_fft_signal(_p(k), _dtype_code(k), n_frames, Hkv, P, D, _p(out))
+    fn = lib().orc_fft_signal if axis == FEATURE_AXIS else lib().orc_fft_signal_token
+    rc = fn(_p(k), _dtype_code(k), n_frames, Hkv, P, D, _p(out))
     assert rc == 0
     return out
 
@@ -212,6 +218,7 @@ class OracleConfig:
     alpha: float = 0.7
     causal: bool = True
     score_layer: int = -1
+    freq_axis: int = FEATURE_AXIS
 
 
 @dataclass
@@ -255,7 +262,7 @@ class OracleMuKV:
         a = None
         if c.alpha != 0.0:
             a = att if att is not None else att_signal(q_last, k_s, n, P, c.causal)
-        fq = fft_signal(k_s, n, P) if c.alpha != 1.0 else None
+        fq = fft_signal(k_s, n, P, c.freq_axis) if c.alpha != 1.0 else None
         fused = fuse(a, fq, c.alpha)
         kept = keep(fused, self.kappa)
         self._store_k.append(compact(k, n, P, kept))

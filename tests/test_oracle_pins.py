@@ -82,6 +82,67 @@ class TestFrequencySignal:
         assert orc.fft_signal(k, 1, 1)[0, 0] == pytest.approx(2.5, abs=1e-12)
 
 
+class TestFrequencySignalAlongTokens:
+    """The other reading of Eq. 2: the transform runs over the frame's tokens, feature by feature."""
+
+    def _frame(self, cols):
+        """cols: [P][D] values of one KV head of one frame."""
+        k = np.asarray(cols, np.float32)[None]
+        return orc.fft_signal(k, 1, k.shape[1], orc.TOKEN_AXIS)[0]
+
+    def test_static_frame_has_only_dc(self):
+        # every token the same vector c: Z[0][d] = P c_d, all other rows 0
+        P, D = 12, 8
+        c = rng.standard_normal(D).astype(np.float32)
+        got = self._frame(np.tile(c, (P, 1)))
+        assert got[0] == pytest.approx(P * np.abs(c.astype(np.float64)).mean(), abs=1e-12)
+        assert np.abs(got[1:]).max() < 1e-12
+
+    def test_one_token_lights_every_frequency_equally(self):
+        P, D = 9, 4
+        x = np.zeros((P, D), np.float32)
+        x[5] = [1.0, -2.0, 0.5, 4.0]
+        np.testing.assert_allclose(self._frame(x), np.full(P, 7.5 / 4), atol=1e-12)
+
+    def test_cosine_over_the_tokens_has_two_rows(self):
+        P, D = 14, 3
+        j = np.arange(P)[:, None]
+        amp = np.array([1.0, 2.0, 0.25])
+        x = (amp * np.cos(2 * np.pi * 3 * j / P)).astype(np.float32)
+        got = self._frame(x)
+        want = np.zeros(P)
+        want[3] = want[P - 3] = P / 2 * amp.mean()
+        np.testing.assert_allclose(got, want, atol=1e-5)
+
+    @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+    def test_matches_numpy_fft_along_token_axis(self, dtype):
+        Hkv, n, P, D = 3, 2, 7, 16                      # P not a power of two
+        x = rng.standard_normal((Hkv, n * P, D)).astype(np.float32)
+        if dtype == "bf16":
+            bits = bf16_bits(x)
+            val = bf16_value(bits)
+            got = orc.fft_signal(bits, n, P, orc.TOKEN_AXIS)
+        else:
+            val = x.astype(np.float64)
+            got = orc.fft_signal(x, n, P, orc.TOKEN_AXIS)
+        want = np.abs(np.fft.fft(val.reshape(Hkv, n, P, D), axis=2)).mean(axis=(0, 3))
+        np.testing.assert_allclose(got, want, rtol=0, atol=1e-12)
+        # rows m and P - m of a real signal carry the same magnitude: the oracle makes the tie exact
+        np.testing.assert_array_equal(got[:, 1:], got[:, 1:][:, ::-1])
+        # and it is not the feature-axis signal
+        assert np.abs(got - orc.fft_signal(bits if dtype == "bf16" else x, n, P)).max() > 1e-2
+
+    def test_the_stream_keeps_what_this_signal_ranks_first(self):
+        # alpha = 0: the keep is the top-kappa of the token-axis signal alone
+        cfg = tiny_cfg(alpha=0.0, freq_axis=orc.TOKEN_AXIS)
+        k, v, q = tiny_stream(cfg, 6, seed=12)
+        o = run_stream(cfg, k, v, q, 3)
+        sig = orc.fft_signal(k[-1], 6, cfg.tokens_per_frame, orc.TOKEN_AXIS)
+        for f in range(6):
+            want = np.sort(np.argsort(-sig[f], kind="stable")[:o.kappa])
+            np.testing.assert_array_equal(o.kept[f], want)
+
+
 # ------------------------------------------------------------------ Eq. 1 ----
 def numpy_att(q, k, n, P, causal):
     Hq, T, D = q.shape
