@@ -55,6 +55,9 @@ def parse():
     ap.add_argument("--overlap-copy", type=int, default=1, choices=(0, 1),
                     help="1: the copy of a batch's kept rows shares a launch with the next batch's frequency "
                          "kernel (mukv_config.overlap_copy; the whole stream is resident, so inputs outlive the copies)")
+    ap.add_argument("--freq-axis", default="feature", choices=["feature", "token"],
+                    help="axis of the transform in the frequency indicator (mukv_config.freq_axis); "
+                         "the default is the reading the build takes, 'token' the other one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-frames", type=int, default=2048)
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
@@ -109,7 +112,8 @@ def main():
     ctx = mk.MuKV(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, tokens_per_frame=P,
                   frames_per_segment=w.frames_per_segment, superpatches_per_frame=w.superpatches_per_frame,
                   dtype=w.torch_dtype, keep_ratio=w.keep_ratio, alpha=w.alpha, max_frames=n_frames,
-                  max_chunk_frames=chunk, max_questions=max(B, 64), batch_chunks=a.batch_chunks, overlap_copy=a.overlap_copy)
+                  max_chunk_frames=chunk, max_questions=max(B, 64), batch_chunks=a.batch_chunks, overlap_copy=a.overlap_copy,
+                  freq_axis=mk.MUKV_FREQ_TOKEN if a.freq_axis == "token" else mk.MUKV_FREQ_FEATURE)
     kappa = ctx.kappa
 
     # questions: random for the single-question workloads, planted targets for the batched one
@@ -244,7 +248,7 @@ def main():
                                f"chunks of {chunk} frames, F={w.frames_per_segment}, keep {kappa}/{P}, "
                                f"{B} question(s), top-{w.k_seg} segments / top-{w.k_frame} frames",
                    "launch": launch, "chunk_frames": chunk, "n_chunks": n_chunks,
-                   "batch_chunks": a.batch_chunks, "overlap_copy": a.overlap_copy},
+                   "batch_chunks": a.batch_chunks, "overlap_copy": a.overlap_copy, "freq_axis": a.freq_axis},
         "compress_ms_per_stream": compress_ms,
         "compress_tokens_per_s": tokens / (compress_ms * 1e-3),
         "retrieve_gather_ms_per_batch": retrieve_ms,
@@ -423,8 +427,9 @@ def main():
 
         n_s = min(a.cpu_sample_frames, n_frames)
         n_sc = (n_s + chunk - 1) // chunk
+        axis = orc.TOKEN_AXIS if a.freq_axis == "token" else orc.FEATURE_AXIS
         ref = orc.OracleMuKV(orc.OracleConfig(L, Hq, Hkv, D, P, w.frames_per_segment, w.superpatches_per_frame,
-                                              w.keep_ratio, w.alpha))
+                                              w.keep_ratio, w.alpha, freq_axis=axis))
         host = [(synth.as_numpy(ks[c]), synth.as_numpy(vs[c]), synth.as_numpy(qs[c])) for c in range(n_sc)]
         orc.lib()
         t0 = time.perf_counter()
@@ -435,7 +440,7 @@ def main():
         n_all = int(orc.lib().orc_num_threads())
         orc.lib().orc_set_num_threads(1)
         ref1 = orc.OracleMuKV(orc.OracleConfig(L, Hq, Hkv, D, P, w.frames_per_segment, w.superpatches_per_frame,
-                                               w.keep_ratio, w.alpha))
+                                               w.keep_ratio, w.alpha, freq_axis=axis))
         t0 = time.perf_counter()
         for kn, vn, qn in host[: max(1, 128 // chunk)]:
             ref1.compress_chunk(kn, vn, q_last=qn)

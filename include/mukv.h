@@ -71,6 +71,8 @@ typedef enum mukv_att_path { MUKV_ATT_AUTO = 0, MUKV_ATT_GENERIC = 1, MUKV_ATT_M
  * L layers, P tokens per frame, F frames per segment, S super-patches per
  * frame, rho keep ratio, alpha signal mix).
  */
+enum { MUKV_FREQ_FEATURE = 0, MUKV_FREQ_TOKEN = 1 };
+
 typedef struct mukv_config {
     int32_t n_layers;               /* L                                               */
     int32_t n_q_heads;              /* H_q, a multiple of n_kv_heads                   */
@@ -104,6 +106,11 @@ typedef struct mukv_config {
                                        batch's frequency kernel (HBM-bound and arithmetic-bound
                                        work side by side); see mukv_compress_chunk for what that
                                        asks of the caller                                       */
+    int32_t freq_axis;              /* axis of the transform in Eq. 2, which the text leaves open:
+                                       MUKV_FREQ_FEATURE (0, default) along the D features of each
+                                       token's key; MUKV_FREQ_TOKEN (1) along the P tokens of the
+                                       frame, feature by feature (row m of the signal is then the
+                                       m-th frequency of the frame; rows m and P-m are equal) */
 } mukv_config;
 
 /* Element strides (not bytes) of a [layer][head][token][dim] tensor; dim is

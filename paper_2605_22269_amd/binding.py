@@ -22,6 +22,7 @@ MUKV_BF16, MUKV_F32 = 0, 1
 MUKV_SEMI, MUKV_HIER, MUKV_PARALLEL = 0, 1, 2
 MUKV_TEMPORAL, MUKV_AS_GIVEN = 0, 1
 MUKV_ATT_AUTO, MUKV_ATT_GENERIC, MUKV_ATT_MFMA = 0, 1, 2
+MUKV_FREQ_FEATURE, MUKV_FREQ_TOKEN = 0, 1
 
 
 class mukv_config(C.Structure):
@@ -31,7 +32,7 @@ class mukv_config(C.Structure):
         ("dtype", C.c_int32), ("keep_ratio", C.c_double), ("alpha", C.c_double), ("causal", C.c_int32),
         ("score_layer", C.c_int32), ("max_frames", C.c_int32), ("max_chunk_frames", C.c_int32),
         ("max_questions", C.c_int32), ("device_id", C.c_int32), ("att_path", C.c_int32), ("batch_chunks", C.c_int32),
-        ("refine_margin", C.c_double), ("overlap_copy", C.c_int32),
+        ("refine_margin", C.c_double), ("overlap_copy", C.c_int32), ("freq_axis", C.c_int32),
     ]
 
 
@@ -244,11 +245,12 @@ class MuKV:
     def __init__(self, *, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, frames_per_segment,
                  superpatches_per_frame=4, dtype=torch.bfloat16, keep_ratio=0.25, alpha=0.7, causal=True,
                  score_layer=-1, max_frames=4096, max_chunk_frames=8, max_questions=1, device_id=0,
-                 att_path=MUKV_ATT_AUTO, refine_margin=-1.0, batch_chunks=1, overlap_copy=0):
+                 att_path=MUKV_ATT_AUTO, refine_margin=-1.0, batch_chunks=1, overlap_copy=0,
+                 freq_axis=MUKV_FREQ_FEATURE):
         self.cfg = mukv_config(n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, frames_per_segment,
                                superpatches_per_frame, MUKV_BF16 if dtype == torch.bfloat16 else MUKV_F32,
                                keep_ratio, alpha, int(causal), score_layer, max_frames, max_chunk_frames,
-                               max_questions, device_id, att_path, batch_chunks, refine_margin, overlap_copy)
+                               max_questions, device_id, att_path, batch_chunks, refine_margin, overlap_copy, freq_axis)
         self.dtype = dtype
         self.device = torch.device("cuda", device_id)
         self.h = mukv_create(self.cfg)

@@ -55,6 +55,7 @@ int validate_config(const mukv_config *cfg) {
     if (cfg->att_path < MUKV_ATT_AUTO || cfg->att_path > MUKV_ATT_MFMA) return MUKV_ERR_INVALID_ARG;
     if (cfg->batch_chunks < 0) return MUKV_ERR_INVALID_ARG;
     if (cfg->overlap_copy != 0 && cfg->overlap_copy != 1) return MUKV_ERR_INVALID_ARG;
+    if (cfg->freq_axis != MUKV_FREQ_FEATURE && cfg->freq_axis != MUKV_FREQ_TOKEN) return MUKV_ERR_INVALID_ARG;
     if (cfg->batch_chunks > mukv::kMaxSlots) return MUKV_ERR_UNSUPPORTED;
     const int kappa = (int)std::floor(cfg->keep_ratio * cfg->tokens_per_frame + 1e-9);
     if (kappa < 1) return MUKV_ERR_INVALID_ARG;
@@ -88,7 +89,7 @@ void free_all(Ctx &c) {
                     c.rep_patch_v, c.rep_seg_k, c.rep_seg_v, c.cnt_patch,   c.fsum_k,      c.fsum_v,
                     c.ssum_k,      c.ssum_v,    c.margin,      c.refined,   c.att_part,  c.fft_sig,     c.att64,       c.fft64,
                     c.src_tok,     c.src_tok2,    c.flag_list[0], c.flag_list[1], c.flag_count, c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail,
-                    c.u_mask,      c.u_entry,     c.u_count,   c.attend_part};
+                    c.u_mask,      c.u_entry,     c.u_count,   c.attend_part, c.tw32, c.tw64, c.tok_part};
     // nothing of the library's own may still be running on what is freed below
     if (c.side) (void)hipStreamSynchronize(c.side);
     for (void *p : ptrs)
@@ -264,6 +265,30 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(dalloc(&c.u_entry, MQ * MF * 3));
     ok(dalloc(&c.u_count, MQ * 2));
     ok(dalloc(&c.attend_part, MQ * mukv::kAttendMaxTokens * cfg->n_q_heads * mukv::kAttendMaxSplit * (size_t)(cfg->head_dim + 2)));
+    if (cfg->freq_axis == MUKV_FREQ_TOKEN) {
+        // rows 0..P/2 of the DFT matrix over the frame's tokens, columns 0..P/2 (the others mirror
+        // them), as (cos, -sin) pairs, rounded once from double for the fp32 pass.  The sine of
+        // column 0 and, for even P, of column P/2 is exactly zero.
+        const int P = cfg->tokens_per_frame, hc = P / 2 + 1;
+        std::vector<double> t64((size_t)hc * hc * 2);
+        std::vector<float> t32(t64.size());
+        for (int m = 0; m < hc; ++m)
+            for (int j = 0; j < hc; ++j) {
+                const int r = (int)(((int64_t)m * j) % P);
+                const double ang = 2.0 * 3.14159265358979323846 * (double)r / (double)P;
+                t64[((size_t)m * hc + j) * 2] = std::cos(ang);
+                t64[((size_t)m * hc + j) * 2 + 1] = (j == 0 || 2 * j == P) ? 0.0 : -std::sin(ang);
+            }
+        for (size_t i = 0; i < t64.size(); ++i) t32[i] = (float)t64[i];
+        ok(dalloc(&c.tw32, t32.size()));
+        ok(dalloc(&c.tw64, t64.size()));
+        if (e == hipSuccess) ok(hipMemcpy(c.tw32, t32.data(), t32.size() * sizeof(float), hipMemcpyHostToDevice));
+        if (e == hipSuccess) ok(hipMemcpy(c.tw64, t64.data(), t64.size() * sizeof(double), hipMemcpyHostToDevice));
+        const size_t n_groups = ((size_t)cfg->n_kv_heads * cfg->head_dim + 63) / 64;
+        c.tok_part_half = (size_t)c.max_batch_frames * n_groups * hc * sizeof(float);
+        c.tok_part_half = (c.tok_part_half + 255) & ~(size_t)255;
+        ok(dalloc(&c.tok_part, c.tok_part_half + (size_t)c.max_batch_frames * n_groups * hc * sizeof(double)));
+    }
     if (e != hipSuccess || !c.prof || !c.pending || !c.deferred) {
         free_all(c);
         delete c.prof;

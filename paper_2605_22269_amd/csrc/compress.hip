@@ -41,6 +41,8 @@ __device__ __forceinline__ void sincospi_t(float x, float *s, float *c) { sincos
 __device__ __forceinline__ void sincospi_t(double x, double *s, double *c) { sincospi(x, s, c); }
 __device__ __forceinline__ float sqrt_t(float x) { return sqrtf(x); }
 __device__ __forceinline__ double sqrt_t(double x) { return sqrt(x); }
+__device__ __forceinline__ float fma_t(float a, float b, float c) { return fmaf(a, b, c); }
+__device__ __forceinline__ double fma_t(double a, double b, double c) { return fma(a, b, c); }
 __device__ __forceinline__ float abs_t(float x) { return fabsf(x); }
 __device__ __forceinline__ double abs_t(double x) { return fabs(x); }
 
@@ -187,6 +189,128 @@ __global__ __launch_bounds__(256) void freq_signal_kernel(PtrTable ktab, FrameMa
                                                           const int32_t *__restrict__ flag_count,
                                                           R *__restrict__ out) {
     freq_body<T, R, D>(ktab, map, k_off, sh, st, Hkv, P, flag_list, flag_count, out, blockIdx.x, blockIdx.y, gridDim.x);
+}
+
+// ------------------------------------------------------------------------------------------
+// Eq. 2-3 with the transform along the TOKEN axis of the frame (the other reading of Eq. 2):
+//   Z[m][c] = sum_j K[j][c] exp(-2 pi i m j / P),  I[m] = mean_c |Z[m][c]|,  c over Hkv*D features.
+// A direct DFT: P is any number up to 256 (196 = 4*7*7 in the paper's setting).  The keys are real,
+// so rows m and P-m have the same magnitude: rows 0..P/2 are evaluated and the rows above copy
+// their mirror row, which keeps that tie exact.  For the same reason tokens j and P-j share their
+// factors up to a sign: with e_j = k_j + k_{P-j}, o_j = k_j - k_{P-j} (1 <= j < P/2)
+//   Re Z[m] = k_0 + sum_j e_j cos(2 pi m j/P) (+ k_{P/2} cos(pi m)),  Im Z[m] = -sum_j o_j sin(2 pi m j/P),
+// half the multiply-adds of the plain sum.
+// freq_token_kernel: one workgroup per (frame, group of 64 features).  The frame's [P][64] slice is
+// staged in LDS (as R) and folded in place (slot j: e_j, slot P-j: o_j, slot P: zero); lane =
+// feature, wave w owns rows m = w, w+4, ..., kTokBins of them at a time, so a staged value is read
+// once per kTokBins rows; the (cos, -sin) factors of a (row, token) pair are the same for the whole
+// wave and come from a table through scalar loads.  |Z| is summed over the lanes.
+// freq_token_finish_kernel adds the feature groups in order and writes both mirror rows.
+// ------------------------------------------------------------------------------------------
+constexpr int kTokBins = 4;
+constexpr int kTokStep = 8; // tokens per batch of loads
+template <typename T, typename R>
+__global__ __launch_bounds__(256) void freq_token_kernel(PtrTable ktab, FrameMap map, int64_t k_off, int64_t sh,
+                                                         int64_t st, int Hkv, int D, int P,
+                                                         const R *__restrict__ tw, // [P/2+1][P/2+1][2]
+                                                         const int32_t *__restrict__ flag_list,
+                                                         const int32_t *__restrict__ flag_count,
+                                                         R *__restrict__ part, // [frame][group][P/2+1]
+                                                         int n_frames) {
+    extern __shared__ __align__(16) unsigned char smem_tok[];
+    R *X = reinterpret_cast<R *>(smem_tok); // [P+1][64]
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int C = Hkv * D, hc = P / 2 + 1, n_groups = gridDim.y, grp = blockIdx.y;
+    const int c = grp * 64 + lane;
+    const bool live = c < C;
+    const int cc = live ? c : C - 1; // loads stay unconditional
+    const int n_e = flag_list ? *flag_count : n_frames;
+    for (int e = blockIdx.x; e < n_e; e += gridDim.x) {
+        const int f = flag_list ? flag_list[e] : e;
+        const int slot = find_slot(map, f);
+        const T *col = reinterpret_cast<const T *>(ktab.p[slot]) + k_off + (int64_t)(f - map.fstart[slot]) * P * st +
+                       (int64_t)(cc / D) * sh + (cc % D);
+        for (int j0 = w; j0 < P; j0 += 4 * 8) { // 8 independent loads per lane
+            T v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = col[(int64_t)(j0 + 4 * u < P ? j0 + 4 * u : P - 1) * st];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (j0 + 4 * u < P) X[(j0 + 4 * u) * 64 + lane] = live ? (R)to_float(v[u]) : (R)0;
+        }
+        if (w == 0) X[P * 64 + lane] = (R)0;
+        __syncthreads();
+        for (int j = 1 + w; 2 * j < P; j += 4) { // fold: a pair of slots belongs to one wave
+            const R a = X[j * 64 + lane], b = X[(P - j) * 64 + lane];
+            X[j * 64 + lane] = a + b;
+            X[(P - j) * 64 + lane] = a - b;
+        }
+        __syncthreads();
+        for (int m0 = w; m0 < hc; m0 += 4 * kTokBins) {
+            R re[kTokBins], im[kTokBins];
+            const R *row[kTokBins];
+#pragma unroll
+            for (int b = 0; b < kTokBins; ++b) {
+                re[b] = im[b] = (R)0;
+                const int m = m0 + 4 * b < hc ? m0 + 4 * b : hc - 1; // a row past the end repeats the last one
+                row[b] = tw + (size_t)m * hc * 2;
+            }
+            // token pairs in batches of kTokStep: their staged values and the factors (scalar
+            // loads of consecutive table entries) are requested together; then the remaining ones
+            int j0 = 0;
+            for (; j0 + kTokStep <= hc; j0 += kTokStep) {
+                R xe[kTokStep], xo[kTokStep];
+#pragma unroll
+                for (int u = 0; u < kTokStep; ++u) {
+                    xe[u] = X[(j0 + u) * 64 + lane];
+                    xo[u] = X[(P - j0 - u) * 64 + lane];
+                }
+#pragma unroll
+                for (int b = 0; b < kTokBins; ++b) {
+                    const R *t = row[b] + 2 * j0;
+#pragma unroll
+                    for (int u = 0; u < kTokStep; ++u) {
+                        re[b] = fma_t(xe[u], t[2 * u], re[b]);
+                        im[b] = fma_t(xo[u], t[2 * u + 1], im[b]);
+                    }
+                }
+            }
+            for (int j = j0; j < hc; ++j) {
+                const R xe = X[j * 64 + lane], xo = X[(P - j) * 64 + lane];
+#pragma unroll
+                for (int b = 0; b < kTokBins; ++b) {
+                    re[b] = fma_t(xe, row[b][2 * j], re[b]);
+                    im[b] = fma_t(xo, row[b][2 * j + 1], im[b]);
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < kTokBins; ++b) {
+                const R mag = wave_sum(sqrt_t(re[b] * re[b] + im[b] * im[b])); // dead lanes hold zeros
+                if (lane == 0 && m0 + 4 * b < hc) part[((int64_t)f * n_groups + grp) * hc + m0 + 4 * b] = mag;
+            }
+        }
+        __syncthreads(); // the slice is restaged for the next listed frame
+    }
+}
+
+template <typename R>
+__global__ __launch_bounds__(256) void freq_token_finish_kernel(const R *__restrict__ part, int n_groups, int P, int C,
+                                                                const int32_t *__restrict__ flag_list,
+                                                                const int32_t *__restrict__ flag_count,
+                                                                R *__restrict__ out, int n_frames) {
+    const int hc = P / 2 + 1;
+    const int n_e = flag_list ? *flag_count : n_frames;
+    for (int e = blockIdx.x; e < n_e; e += gridDim.x) {
+        const int f = flag_list ? flag_list[e] : e;
+        for (int m = threadIdx.x; m < hc; m += 256) {
+            R s = (R)0;
+            for (int g = 0; g < n_groups; ++g) s += part[((int64_t)f * n_groups + g) * hc + m];
+            const R val = s / (R)C;
+            out[(int64_t)f * P + m] = val;
+            if (m > 0 && P - m > m) out[(int64_t)f * P + P - m] = val;
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -789,8 +913,35 @@ __global__ void clear_count_kernel(int32_t *count) { *count = 0; }
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
+static const float *token_table(const Ctx &c, float) { return c.tw32; }
+static const double *token_table(const Ctx &c, double) { return c.tw64; }
+
+template <typename T, typename R>
+static hipError_t launch_freq_token(const Ctx &c, const ChunkArgs &a, bool listed, R *out, hipStream_t st) {
+    const int P = c.cfg.tokens_per_frame, C = c.cfg.n_kv_heads * c.cfg.head_dim;
+    const int n_groups = (C + 63) / 64;
+    const size_t lds = (size_t)(P + 1) * 64 * sizeof(R);
+    static bool lds_ok[kMaxDevices];
+    const hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(&freq_token_kernel<T, R>),
+                                            (size_t)(kMaxP + 1) * 64 * sizeof(R), c.cfg.device_id, lds_ok);
+    if (ea != hipSuccess) return ea;
+    const int32_t *fl = listed ? c.flag_list[a.parity] : nullptr, *fc = listed ? c.flag_count + a.parity : nullptr;
+    // the two passes (fp32 on the caller's stream, fp64 on the side stream) may run at the same
+    // time: each has its own half of the partial-sum scratch
+    R *part = reinterpret_cast<R *>(c.tok_part + (sizeof(R) == 8 ? c.tok_part_half : 0));
+    hipLaunchKernelGGL((freq_token_kernel<T, R>), dim3(listed ? kRescoreSlots : a.n_frames, n_groups), dim3(256), lds, st,
+                       a.k, a.map, (int64_t)c.ls * a.kv_sl, a.kv_sh, a.kv_st, c.cfg.n_kv_heads, c.cfg.head_dim, P,
+                       token_table(c, R()), fl, fc, part, a.n_frames);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((freq_token_finish_kernel<R>), dim3(listed ? kRescoreSlots : a.n_frames), dim3(256), 0, st, part,
+                       n_groups, P, C, fl, fc, out, a.n_frames);
+    return hipGetLastError();
+}
+
 template <typename T, typename R>
 static hipError_t launch_freq(const Ctx &c, const ChunkArgs &a, bool listed, R *out, hipStream_t st) {
+    if (c.cfg.freq_axis == MUKV_FREQ_TOKEN) return launch_freq_token<T, R>(c, a, listed, out, st);
     const int P = c.cfg.tokens_per_frame, D = c.cfg.head_dim, Hkv = c.cfg.n_kv_heads;
     const int64_t k_off = (int64_t)c.ls * a.kv_sl;
     const dim3 grid(listed ? kRescoreSlots : a.n_frames, kFreqBlocksPerFrame);
@@ -1077,7 +1228,7 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
     // row copy (arithmetic-bound beside HBM-bound work; the attention kernel streams all the
     // queries and gains nothing beside a copy).  The previous batch's re-scoring chain goes out
     // right behind it, so that the caller's stream continues with this launch.
-    if (need_fft && c.deferred_pending) {
+    if (need_fft && c.deferred_pending && c.cfg.freq_axis == MUKV_FREQ_FEATURE) {
         c.deferred_pending = false;
         {
             ProfScope ps(c, MUKV_K_COPY_FREQ, st);

@@ -85,6 +85,13 @@ struct Ctx {
     uint32_t *u_mask;  // [max_questions][max_frames] super-patches of a frame chosen at any level
     int32_t *u_entry;  // [max_questions][max_frames][3] chosen frames in time order: frame, mask, first output row
     int32_t *u_count;  // [max_questions][2] entries, rows
+    // token-axis frequency signal: cos and -sin of 2*pi*m*j/P for rows and token pairs 0..P/2,
+    // [P/2+1][P/2+1][2]; per (batch frame, group of 64 features, row) sums of |Z|: the fp32 pass
+    // uses the first tok_part_half bytes, the fp64 pass the rest
+    float *tw32;
+    double *tw64;
+    unsigned char *tok_part;
+    size_t tok_part_half;
     // attention over the retrieved context: per (question, token, head, split) maximum, normaliser, output
     float *attend_part; // [max_questions][kAttendMaxTokens][Hq][kAttendMaxSplit][D+2]
 };

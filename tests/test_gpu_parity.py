@@ -15,6 +15,10 @@ pytestmark = pytest.mark.gpu
 W = synth.WORKLOADS
 
 
+def mk_tol(w):
+    return 2e-2 if w.dtype == "bf16" else 1e-5
+
+
 def questions_for(w, lengths, seed):
     return [synth.random_question(w, n, seed + i) for i, n in enumerate(lengths)]
 
@@ -808,3 +812,40 @@ def test_attention_argument_errors():
     assert status(lambda: mk.mukv_attend(g.h, 0, q.data_ptr(), 1, None, 3, None, None, None, 2, 1, q.data_ptr(),
                                          None)) == mk.MUKV_ERR_INVALID_ARG                   # k_frame without a list
     p.close()
+
+
+# --------------------------------- the token-axis reading of the frequency indicator (Eq. 2) ------
+@pytest.mark.parametrize("name,frames,alpha,kw", [
+    ("tiny", 24, 0.7, {}),
+    ("tiny", 24, 0.0, {}),                                            # the signal alone: every mirror pair is an exact tie
+    ("7b", 21, 0.7, {"batch_chunks": 2, "overlap_copy": 1}),          # P = 196 = 4 * 7 * 7
+    ("7b", 12, 0.3, {"refine_margin": 10.0}),                         # every frame through the fp64 pass
+    ("72b", 16, 0.5, {"batch_chunks": 4}),
+])
+def test_frequency_signal_along_the_token_axis(name, frames, alpha, kw):
+    w = W[name].scaled(n_frames=frames, n_layers=2, n_questions=2, alpha=alpha)
+    gkw = dict(kw, freq_axis=mk.MUKV_FREQ_TOKEN)
+    p = Pair(w, seed=190, chunk=4, gpu_kw=gkw, orc_kw={"freq_axis": orc.TOKEN_AXIS})
+    p.ingest()
+    st = p.check_compress(raw_signals=False)      # the raw signal grows with P: its bar is relative, below
+    for so, sg in zip(p.sig_orc, p.sig_gpu):
+        got, want = sg["fft"].cpu().numpy(), so["fft"]
+        assert np.abs(got - want).max() <= mk_tol(w) * max(1.0, float(np.abs(want).max()))
+        np.testing.assert_array_equal(got[:, 1:], got[:, 1:][:, ::-1])      # mirror rows: the same bits
+    if kw.get("refine_margin", 0) >= 10.0:
+        assert int(st["refined"].sum()) == frames
+    qs = questions_for(w, [7, 3], 1400)
+    p.check_retrieve(qs, mk.MUKV_SEMI, 2, 4, 0.3)
+    p.close()
+
+
+def test_token_axis_signal_with_odd_token_counts():
+    # P odd, P prime, P below one load batch: no row is its own mirror except row 0
+    for i, P in enumerate((3, 7, 13, 97, 255)):
+        w = synth.Workload(f"tok{P}", 1, 4, 2, 32, "f32" if i % 2 else "bf16", 6, P, 3, superpatches_per_frame=1 + i % 3,
+                           keep_ratio=0.5, alpha=0.4, chunk_frames=3,
+                           k_seg=1, k_frame=2, question_tokens=5, n_questions=1)
+        p = Pair(w, seed=191 + i, chunk=3, gpu_kw={"freq_axis": mk.MUKV_FREQ_TOKEN}, orc_kw={"freq_axis": orc.TOKEN_AXIS})
+        p.ingest()
+        p.check_compress(raw_signals=False)
+        p.close()
