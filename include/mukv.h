@@ -101,11 +101,12 @@ typedef struct mukv_config {
                                        below this are re-scored in fp64 before the
                                        keep; < 0 = library default, 0 = never          */
     int32_t overlap_copy;           /* 0: a call that enqueues kernels enqueues all of them.
-                                       1: the copy of a batch's kept rows is put off until the
-                                       next batch arrives and then shares one launch with that
-                                       batch's frequency kernel (HBM-bound and arithmetic-bound
-                                       work side by side); see mukv_compress_chunk for what that
-                                       asks of the caller                                       */
+                                       1: the keep of a batch runs on a stream of the library's
+                                       own beside the next batch's kernels, and the copy of its
+                                       kept rows is put off until the batch after next arrives
+                                       and then shares one launch with that batch's frequency
+                                       kernel (HBM-bound and arithmetic-bound work side by side);
+                                       see mukv_compress_chunk for what that asks of the caller */
     int32_t freq_axis;              /* axis of the transform in Eq. 2, which the text leaves open:
                                        MUKV_FREQ_FEATURE (0, default) along the D features of each
                                        token's key; MUKV_FREQ_TOKEN (1) along the P tokens of the
@@ -214,10 +215,10 @@ int mukv_flush(mukv_ctx *ctx);
  * flushes.
  *
  * With overlap_copy = 1 the rows of a batch are copied out of the input buffers
- * only by the NEXT call that enqueues compress kernels, or by a mukv_flush,
- * mukv_retrieve or mukv_gather_kv call.  The inputs (and `sig` outputs) of a
- * batch must then stay alive and unchanged until the stream has passed that
- * call.  Results are the same bit for bit.
+ * only by the SECOND call after it that enqueues compress kernels, or by a
+ * mukv_flush, retrieve, gather, attend or snapshot call.  The inputs (and `sig`
+ * outputs) of a batch must then stay alive and unchanged until the stream has
+ * passed that call.  Results are the same bit for bit.
  *
  * Errors: INVALID_ARG (null k/v, missing or doubled attention source),
  * SHAPE (n_frames < 1), CAPACITY (n_frames > max_chunk_frames or the cache is

@@ -257,8 +257,8 @@ class MuKV:
         st = mukv_get_state(self.h)
         self.kappa, self.c_kv, self.patch_cap = st.kappa, st.c_kv, st.patch_cap
         # references to the buffers of the chunks the library may still read: the batch being
-        # gathered, the one before it (overlap_copy) and one spare
-        self._held = collections.deque(maxlen=2 * max(1, batch_chunks) + 1)
+        # gathered, the two before it (overlap_copy) and one spare
+        self._held = collections.deque(maxlen=4 * max(1, batch_chunks) + 1)
 
     def close(self):
         if self.h is not None:

@@ -87,8 +87,8 @@ int patch_cap(const Ctx &c) {
 void free_all(Ctx &c) {
     void *ptrs[] = {c.store_k,    c.store_v,    c.kept_idx,  c.rep_frame_k, c.rep_frame_v, c.rep_patch_k,
                     c.rep_patch_v, c.rep_seg_k, c.rep_seg_v, c.cnt_patch,   c.fsum_k,      c.fsum_v,
-                    c.ssum_k,      c.ssum_v,    c.margin,      c.refined,   c.att_part,  c.fft_sig,     c.att64,       c.fft64,
-                    c.src_tok,     c.src_tok2,    c.flag_list[0], c.flag_list[1], c.flag_count, c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail,
+                    c.ssum_k,      c.ssum_v,    c.margin,      c.refined,   c.att_part[0], c.att_part[1], c.fft_sig[0], c.fft_sig[1],     c.att64,       c.fft64,
+                    c.src_tok[0],  c.src_tok[1],   c.src_tok2,    c.flag_list[0], c.flag_list[1], c.flag_count, c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail,
                     c.u_mask,      c.u_entry,     c.u_count,   c.attend_part, c.tw32, c.tw64, c.tok_part};
     // nothing of the library's own may still be running on what is freed below
     if (c.side) (void)hipStreamSynchronize(c.side);
@@ -96,8 +96,9 @@ void free_all(Ctx &c) {
         if (p) (void)hipFree(p);
     if (c.side) (void)hipStreamDestroy(c.side);
     if (c.ev_fork) (void)hipEventDestroy(c.ev_fork);
-    if (c.ev_join) (void)hipEventDestroy(c.ev_join);
-    delete c.deferred;
+    for (hipEvent_t ev : c.ev_join)
+        if (ev) (void)hipEventDestroy(ev);
+    delete[] c.deferred;
     if (c.ev_copy) (void)hipEventDestroy(c.ev_copy);
 }
 
@@ -241,11 +242,14 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(dalloc(&c.margin, MF));
     ok(dalloc(&c.refined, MF));
     const size_t n_part_max = Hq * ((P + 31) / 32 > 2 ? (P + 31) / 32 : 2); // partial rows per frame
-    ok(dalloc(&c.att_part, MC * n_part_max * P));
-    ok(dalloc(&c.fft_sig, MC * P));
+    for (int par = 0; par < 2; ++par) {
+        ok(dalloc(&c.att_part[par], MC * n_part_max * P));
+        ok(dalloc(&c.fft_sig[par], MC * P));
+        ok(dalloc(&c.src_tok[par], MC * c.kappa));
+        ok(hipEventCreateWithFlags(&c.ev_join[par], hipEventDisableTiming));
+    }
     ok(dalloc(&c.att64, MC * n_part_max * P));
     ok(dalloc(&c.fft64, MC * P));
-    ok(dalloc(&c.src_tok, MC * c.kappa));
     ok(dalloc(&c.src_tok2, MC * c.kappa));
     ok(dalloc(&c.flag_list[0], MC));
     ok(dalloc(&c.flag_list[1], MC));
@@ -253,8 +257,7 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     if (e == hipSuccess) ok(hipMemset(c.flag_count, 0, 2 * sizeof(int32_t)));
     ok(hipStreamCreateWithFlags(&c.side, hipStreamNonBlocking));
     ok(hipEventCreateWithFlags(&c.ev_fork, hipEventDisableTiming));
-    ok(hipEventCreateWithFlags(&c.ev_join, hipEventDisableTiming));
-    c.deferred = new (std::nothrow) mukv::ChunkArgs();
+    c.deferred = new (std::nothrow) mukv::ChunkArgs[2];
     ok(hipEventCreateWithFlags(&c.ev_copy, hipEventDisableTiming));
     ok(dalloc(&c.qbar, MQ * C));
     ok(dalloc(&c.qq, MQ * cfg->n_kv_heads));
@@ -347,7 +350,7 @@ int mukv_reset(mukv_ctx *ctx) {
     ctx->c.n_frames = 0;
     ctx->c.n_done = 0;
     ctx->c.pending->clear();
-    if (ctx->c.deferred_pending) { // the rows it would have copied are forgotten with the rest
+    if (ctx->c.n_deferred) { // the rows they would have copied are forgotten with the rest
         DeviceScope dev(ctx->c.cfg.device_id);
         if (!dev.ok || mukv::drop_deferred(ctx->c) != hipSuccess) return MUKV_ERR_HIP;
     }
@@ -390,7 +393,8 @@ static int flush_pending(Ctx &c, bool join, hipStream_t join_stream) {
     a.q_st = c.p_q_st;
     a.n_frames = nf;
     a.frame0 = c.n_done;
-    a.parity = 0;
+    a.parity = c.batch_parity;
+    c.batch_parity ^= 1;
     c.pending->clear();
     c.n_done += nf;
     DeviceScope dev(c.cfg.device_id);

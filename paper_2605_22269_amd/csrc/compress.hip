@@ -1016,7 +1016,7 @@ static hipError_t launch_select(const Ctx &c, const ChunkArgs &a, const R *att, 
     s.flag_list = c.flag_list[a.parity];
     s.flag_count = c.flag_count + a.parity;
     s.kept_idx = c.kept_idx;
-    s.src_tok = pass2 ? c.src_tok2 : c.src_tok;
+    s.src_tok = pass2 ? c.src_tok2 : c.src_tok[a.parity];
     s.rep_frame_k = c.rep_frame_k;
     s.rep_frame_v = c.rep_frame_v;
     s.rep_patch_k = c.rep_patch_k;
@@ -1056,7 +1056,7 @@ static void compact_args(const Ctx &c, const ChunkArgs &a, int mode, int iter, C
     k.store_v = reinterpret_cast<unsigned char *>(c.store_v);
     k.slab_b = c.store_cap * row_b;
     k.dst_off_b = a.frame0 * c.kappa * (int64_t)row_b;
-    k.src_tok = mode == 2 ? c.src_tok2 : c.src_tok;
+    k.src_tok = mode == 2 ? c.src_tok2 : c.src_tok[a.parity];
     const int upr = row_b / 16; // rows are whole 16-byte units (validated at create)
     k.log_upr = ilog2(upr);
     k.units_per_frame = c.kappa * upr;
@@ -1118,7 +1118,7 @@ static hipError_t launch_copy_freq(const Ctx &c, const ChunkArgs &prev, int mode
     fp.st = a.kv_st;
     fp.Hkv = c.cfg.n_kv_heads;
     fp.P = c.cfg.tokens_per_frame;
-    fp.out = c.fft_sig;
+    fp.out = c.fft_sig[a.parity];
     fp.n_frames = a.n_frames;
     fp.n_wg = a.n_frames * kFreqBlocksPerFrame;
     const int64_t n_copy = (int64_t)gx * gy;
@@ -1138,25 +1138,39 @@ static hipError_t launch_copy_freq(const Ctx &c, const ChunkArgs &prev, int mode
     return hipGetLastError();
 }
 
-static hipError_t wait_side(Ctx &c, hipStream_t st) {
-    if (c.side_pending) {
-        hipError_t e = hipStreamWaitEvent(st, c.ev_join, 0);
+static hipError_t wait_side(Ctx &c, int parity, hipStream_t st) {
+    if (c.side_pending[parity]) {
+        hipError_t e = hipStreamWaitEvent(st, c.ev_join[parity], 0);
         if (e != hipSuccess) return e;
-        c.side_pending = false;
+        c.side_pending[parity] = false;
     }
     return hipSuccess;
 }
 
-// Frames with a near-tie at the keep boundary are on the re-scoring list: Eq. 1-4 are redone for
-// them in fp64, the keep repeated and their rows copied, all on the context's side stream (behind
-// ev_fork, recorded after the batch's keep), beside whatever the caller's stream does meanwhile.
+static hipError_t wait_side_all(Ctx &c, hipStream_t st) {
+    const hipError_t e = wait_side(c, 0, st);
+    return e != hipSuccess ? e : wait_side(c, 1, st);
+}
+
+// The side stream's share of a batch, behind ev_fork (recorded on the caller's stream once the
+// batch's signals are enqueued):
+//  - with overlap_copy the keep itself (Eq. 4, top-kappa, block keys), so that the caller's stream
+//    goes straight on to the next batch;
+//  - with re-scoring on, the fp64 chain: frames with a near-tie at the keep boundary are on the
+//    re-scoring list; Eq. 1-4 are redone for them in fp64, the keep repeated and their rows copied.
+// ev_join[parity] marks its end.
 template <typename T>
-static hipError_t launch_rescoring(Ctx &c, const ChunkArgs &a) {
+static hipError_t launch_side(Ctx &c, const ChunkArgs &a, bool with_keep, int n_part) {
     hipError_t e;
     const bool need_att = c.cfg.alpha != 0.0 && !a.have_att_in;
     const bool need_fft = c.cfg.alpha != 1.0;
     if ((e = hipStreamWaitEvent(c.side, c.ev_fork, 0)) != hipSuccess) return e;
-    {
+    if (with_keep) {
+        ProfScope ps(c, MUKV_K_SELECT, c.side);
+        if ((e = launch_select<T, float>(c, a, c.att_part[a.parity], n_part, c.fft_sig[a.parity], 0, c.side)) != hipSuccess)
+            return e;
+    }
+    if (c.margin_thr > 0.0) {
         ProfScope ps(c, MUKV_K_REFINE, c.side);
         int n_part64 = c.cfg.n_q_heads;
         if (need_att)
@@ -1169,50 +1183,48 @@ static hipError_t launch_rescoring(Ctx &c, const ChunkArgs &a) {
         hipLaunchKernelGGL(clear_count_kernel, dim3(1), dim3(1), 0, c.side, c.flag_count + a.parity);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    if ((e = hipEventRecord(c.ev_join, c.side)) != hipSuccess) return e;
-    c.side_pending = true;
+    if ((e = hipEventRecord(c.ev_join[a.parity], c.side)) != hipSuccess) return e;
+    c.side_pending[a.parity] = true;
     return hipSuccess;
 }
 
-static hipError_t launch_deferred_rescoring(Ctx &c) {
-    if (c.margin_thr <= 0.0) return hipSuccess;
-    return c.cfg.dtype == MUKV_BF16 ? launch_rescoring<uint16_t>(c, *c.deferred) : launch_rescoring<float>(c, *c.deferred);
-}
-
-// The copy (and re-scoring) that was put off, launched on its own: no new batch to share with.
-static hipError_t launch_deferred(Ctx &c) {
-    if (!c.deferred_pending) return hipSuccess;
-    c.deferred_pending = false;
+// The copy of a batch that was put off, launched on its own (no new batch to share a launch with):
+// its keep, on the side stream, must have finished.
+static hipError_t launch_deferred_copy(Ctx &c, const ChunkArgs &d, hipStream_t st) {
     hipError_t e;
-    {
-        ProfScope ps(c, MUKV_K_COMPACT, c.deferred_stream);
-        if ((e = launch_compact(c, *c.deferred, c.margin_thr > 0.0 ? 1 : 0, c.deferred_stream)) != hipSuccess) return e;
-    }
-    return launch_deferred_rescoring(c);
+    if ((e = wait_side(c, d.parity, st)) != hipSuccess) return e;
+    ProfScope ps(c, MUKV_K_COMPACT, st);
+    return launch_compact(c, d, c.margin_thr > 0.0 ? 1 : 0, st);
 }
 
+// mukv_reset: the copies that were put off are forgotten.  What the side stream still does for
+// those batches is harmless (the cache is empty again) and is waited for, by parity, before its
+// scratch is used again.
 hipError_t drop_deferred(Ctx &c) {
-    if (!c.deferred_pending) return hipSuccess;
-    c.deferred_pending = false;
-    if (c.margin_thr <= 0.0) return hipSuccess;
-    // the dropped batch's keep may have left frames on the re-scoring list
-    hipLaunchKernelGGL(clear_count_kernel, dim3(1), dim3(1), 0, c.deferred_stream, c.flag_count + c.deferred->parity);
-    return hipGetLastError();
+    c.n_deferred = 0;
+    return hipSuccess;
 }
 
 hipError_t join_streams(Ctx &c, hipStream_t st) {
     hipError_t e;
-    if (c.deferred_pending) {
+    if (c.n_deferred) {
         hipStream_t ds = c.deferred_stream;
-        if ((e = launch_deferred(c)) != hipSuccess) return e;
+        for (int i = 0; i < c.n_deferred; ++i)
+            if ((e = launch_deferred_copy(c, c.deferred[i], ds)) != hipSuccess) return e;
+        c.n_deferred = 0;
         if (ds != st) {
             if ((e = hipEventRecord(c.ev_copy, ds)) != hipSuccess) return e;
             if ((e = hipStreamWaitEvent(st, c.ev_copy, 0)) != hipSuccess) return e;
         }
     }
-    return wait_side(c, st);
+    return wait_side_all(c, st);
 }
 
+// One batch.  Without overlap_copy, on the caller's stream: signals, keep, copy, with the fp64
+// chain beside the copy.  With overlap_copy the caller's stream carries only
+//     [copy of batch n-2 + frequency signal of batch n] (one launch), attention signal of batch n
+// and the side stream the keep of batch n (and its fp64 chain) meanwhile: the keep of a batch has
+// the next batch's launches to finish in, the copy of its rows follows two batches later.
 template <typename T>
 static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
     hipError_t e;
@@ -1221,57 +1233,60 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
     const bool overlap = c.cfg.overlap_copy != 0;
     const bool rescoring = c.margin_thr > 0.0;
     int n_part = c.cfg.n_q_heads;
-    // a copy put off on another stream cannot share a launch with this batch
-    if (c.deferred_pending && c.deferred_stream != st)
+    // copies put off on another stream cannot share a launch with this batch
+    if (c.n_deferred && c.deferred_stream != st)
         if ((e = join_streams(c, st)) != hipSuccess) return e;
-    // Frequency signal first: with overlap_copy it shares its launch with the previous batch's
-    // row copy (arithmetic-bound beside HBM-bound work; the attention kernel streams all the
-    // queries and gains nothing beside a copy).  The previous batch's re-scoring chain goes out
-    // right behind it, so that the caller's stream continues with this launch.
-    if (need_fft && c.deferred_pending && c.cfg.freq_axis == MUKV_FREQ_FEATURE) {
-        c.deferred_pending = false;
-        {
-            ProfScope ps(c, MUKV_K_COPY_FREQ, st);
-            if ((e = launch_copy_freq<T>(c, *c.deferred, rescoring ? 1 : 0, a, st)) != hipSuccess) return e;
-        }
-        if ((e = launch_deferred_rescoring(c)) != hipSuccess) return e;
+    // This batch's parity was last used two batches ago: that batch's keep and fp64 chain must be
+    // through with the scratch (they have had a whole batch of launches to do so), and its rows
+    // may now be copied.
+    if ((e = wait_side(c, a.parity, st)) != hipSuccess) return e;
+    const bool have_old = c.n_deferred == 2;
+    if (have_old && need_fft && c.cfg.freq_axis == MUKV_FREQ_FEATURE) {
+        // the copy shares its launch with this batch's frequency kernel: HBM-bound beside
+        // arithmetic-bound work (the attention kernel streams all the queries and gains nothing
+        // beside a copy)
+        ProfScope ps(c, MUKV_K_COPY_FREQ, st);
+        if ((e = launch_copy_freq<T>(c, c.deferred[0], rescoring ? 1 : 0, a, st)) != hipSuccess) return e;
     } else {
-        if ((e = launch_deferred(c)) != hipSuccess) return e;
+        if (have_old)
+            if ((e = launch_deferred_copy(c, c.deferred[0], st)) != hipSuccess) return e;
         if (need_fft) {
             ProfScope ps(c, MUKV_K_FREQ, st);
-            if ((e = launch_freq<T, float>(c, a, false, c.fft_sig, st)) != hipSuccess) return e;
+            if ((e = launch_freq<T, float>(c, a, false, c.fft_sig[a.parity], st)) != hipSuccess) return e;
         }
+    }
+    if (have_old) {
+        c.deferred[0] = c.deferred[1];
+        c.n_deferred = 1;
     }
     if (need_att) {
         ProfScope ps(c, MUKV_K_ATT, st);
         if (c.use_mfma) {
-            if ((e = launch_att_mfma(c, a, c.att_part, &n_part, st)) != hipSuccess) return e;
+            if ((e = launch_att_mfma(c, a, c.att_part[a.parity], &n_part, st)) != hipSuccess) return e;
         } else {
-            if ((e = launch_att_generic<T, float>(c, a, false, c.att_part, &n_part, st)) != hipSuccess) return e;
+            if ((e = launch_att_generic<T, float>(c, a, false, c.att_part[a.parity], &n_part, st)) != hipSuccess) return e;
         }
     }
-    // The keep overwrites the list the previous batch's re-scoring chain works from: that chain
-    // must have finished (it has had the kernels above to do so).
-    if ((e = wait_side(c, st)) != hipSuccess) return e;
-    {
-        ProfScope ps(c, MUKV_K_SELECT, st);
-        if ((e = launch_select<T, float>(c, a, c.att_part, n_part, c.fft_sig, 0, st)) != hipSuccess) return e;
-    }
-    if (rescoring)
+    if (overlap) { // keep on the side stream; the copy waits for the batch after next (or a flush / retrieve / gather call)
         if ((e = hipEventRecord(c.ev_fork, st)) != hipSuccess) return e;
-    if (overlap) { // copy and re-scoring wait for the next batch (or a flush / retrieve / gather call)
-        *c.deferred = a;
-        c.deferred_pending = true;
+        if ((e = launch_side<T>(c, a, true, n_part)) != hipSuccess) return e;
+        c.deferred[c.n_deferred++] = a;
         c.deferred_stream = st;
         return hipSuccess;
     }
-    if (rescoring)
-        if ((e = launch_rescoring<T>(c, a)) != hipSuccess) return e;
+    {
+        ProfScope ps(c, MUKV_K_SELECT, st);
+        if ((e = launch_select<T, float>(c, a, c.att_part[a.parity], n_part, c.fft_sig[a.parity], 0, st)) != hipSuccess) return e;
+    }
+    if (rescoring) {
+        if ((e = hipEventRecord(c.ev_fork, st)) != hipSuccess) return e;
+        if ((e = launch_side<T>(c, a, false, n_part)) != hipSuccess) return e;
+    }
     {
         ProfScope ps(c, MUKV_K_COMPACT, st);
         if ((e = launch_compact(c, a, rescoring ? 1 : 0, st)) != hipSuccess) return e;
     }
-    return wait_side(c, st);
+    return wait_side(c, a.parity, st);
 }
 
 hipError_t launch_compress(Ctx &c, const ChunkArgs &a, hipStream_t st) {

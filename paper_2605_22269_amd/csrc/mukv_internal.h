@@ -60,21 +60,23 @@ struct Ctx {
     float *margin;
     int32_t *refined;
     // per-chunk scratch (device)
-    float *att_part;  // [max_chunk_frames][n_part][P]
-    float *fft_sig;   // [max_chunk_frames][P]
+    // (two of each, by batch parity: with overlap_copy the keep of a batch runs beside the next
+    // batch's kernels)
+    float *att_part[2]; // [max_batch_frames][n_part][P]
+    float *fft_sig[2];  // [max_batch_frames][P]
     double *att64;    // [max_chunk_frames][Hq][P] partial fp64 attention of re-scored frames
     double *fft64;    // [max_chunk_frames][P]
-    int32_t *src_tok; // [max_batch_frames*kappa] chunk-local token of every kept row
+    int32_t *src_tok[2]; // [max_batch_frames*kappa] chunk-local token of every kept row
     int32_t *src_tok2;                // the same for the frames re-scored in fp64
     int32_t *flag_list[2], *flag_count; // batch frames to re-score in fp64 and how many, by batch parity
-    hipStream_t side;                 // re-scoring chain runs here, beside the main copy
-    hipEvent_t ev_fork;               // scoring and keep of the batch are enqueued
-    hipEvent_t ev_join;               // re-scoring chain of the batch is enqueued
-    hipEvent_t ev_copy;               // the copy that was put off is enqueued (orders another stream after it)
-    bool side_pending;                // ev_join recorded and not yet waited for by the caller's stream
-    ChunkArgs *deferred;              // overlap_copy: the batch whose row copy is still to be launched
-    bool deferred_pending;
-    hipStream_t deferred_stream;      // stream that batch was submitted on
+    hipStream_t side;                 // re-scoring chain (with overlap_copy also the keep) runs here
+    hipEvent_t ev_fork;               // the batch's signals are enqueued on the caller's stream
+    hipEvent_t ev_join[2];            // the side stream's work for the batch of that parity is enqueued
+    hipEvent_t ev_copy;               // the copies that were put off are enqueued (orders another stream after them)
+    bool side_pending[2];             // ev_join recorded and not yet waited for by the caller's stream
+    ChunkArgs *deferred;              // overlap_copy: the (at most two) batches whose row copy is still to be
+    int n_deferred;                   // launched, the older one first
+    hipStream_t deferred_stream;      // stream those batches were submitted on
     // retrieval scratch (device)
     double *qbar;    // [max_questions][c_kv]  group-summed mean query
     double *qq;      // [max_questions][Hkv]   partial squared norms of the mean query
@@ -127,7 +129,7 @@ struct ChunkArgs {
     int64_t q_sh, q_st;
     int n_frames;                // frames in the batch
     int64_t frame0;              // cache position of batch frame 0
-    int parity;                  // which re-scoring list this batch uses (always 0 at present)
+    int parity;                  // which set of per-batch scratch (signals, row list, re-scoring list) this batch uses
 };
 
 
