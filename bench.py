@@ -229,7 +229,9 @@ def main():
     gather_gbs = gather_bytes / (gather_us * 1e-6) / 1e9
     # whole-path algorithmic bytes: signals' inputs + kept rows in and out
     path_bytes_frame = P * D * esz * (Hq + Hkv) + 2 * kappa * L * b_tok
-    path_gbs = path_bytes_frame * n_frames / (compress_ms * 1e-3) / 1e9
+    # over the timed step (which also holds the retrieval and the gather): the eager pass issues its
+    # calls one by one from Python and is bound by the host, not by the device
+    path_gbs = path_bytes_frame * n_frames / (ms_per_step * 1e-3) / 1e9
 
     res = {
         "metric": "visual tokens compressed/s + retrieve latency per question (ms), % HBM peak",
@@ -249,12 +251,12 @@ def main():
                                f"{B} question(s), top-{w.k_seg} segments / top-{w.k_frame} frames",
                    "launch": launch, "chunk_frames": chunk, "n_chunks": n_chunks,
                    "batch_chunks": a.batch_chunks, "overlap_copy": a.overlap_copy, "freq_axis": a.freq_axis},
-        "compress_ms_per_stream": compress_ms,
-        "compress_tokens_per_s": tokens / (compress_ms * 1e-3),
+        "compress_ms_per_stream_eager_calls": compress_ms,
+        "compress_tokens_per_s_eager_calls": tokens / (compress_ms * 1e-3),
         "retrieve_gather_ms_per_batch": retrieve_ms,
         "retrieve_gather_ms_per_question": retrieve_ms / B,
         "path_hbm": {"algorithmic_bytes_per_token": path_bytes_frame / P, "achieved_GBs": path_gbs,
-                     "frac_of_peak": path_gbs / HBM_PEAK_GBS},
+                     "frac_of_peak": path_gbs / HBM_PEAK_GBS, "over": "ms_per_step"},
         "kernel_us": per_kernel,
         "roofline": {"kernel": dom_kernel, "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS,
