@@ -436,12 +436,21 @@ def test_graph_replay_matches_the_oracle_every_time(overlap, margin):
     g_out = (torch.empty(shape, dtype=w.torch_dtype, device="cuda"), torch.empty(shape, dtype=w.torch_dtype, device="cuda"),
              torch.empty(1, dtype=torch.int32, device="cuda"))
 
+    gen = torch.Generator().manual_seed(531)   # two new tokens attend to the retrieved rows and five local rows (Eq. 9)
+    q_new = torch.randn(1, 2, w.n_q_heads, w.head_dim, generator=gen).to(w.torch_dtype)
+    k_loc = torch.randn(5, w.n_kv_heads, w.head_dim, generator=gen).to(w.torch_dtype)
+    v_loc = torch.randn(5, w.n_kv_heads, w.head_dim, generator=gen).to(w.torch_dtype)
+    q_new_d, k_loc_d, v_loc_d = q_new.cuda(), k_loc.cuda(), v_loc.cuda()
+    l_off = torch.tensor([0, 5], dtype=torch.int32, device="cuda")
+    a_out = torch.empty_like(q_new_d)
+
     def step(chs):
         p.gpu.reset()
         for k, v, q in chs:
             p.gpu.compress_chunk(k, v, q)
         p.gpu.retrieve(qd, offs, mode=mk.MUKV_SEMI, k_seg=2, k_frame=6, lambda_frame=0.3, out=r_out)
         p.gpu.gather_kv(r_out["frame_idx"], out=g_out)
+        p.gpu.attend(1, q_new_d, r_out["frame_idx"], k_loc_d, v_loc_d, l_off, True, out=a_out)
 
     junk_stream = synth.SynthStream(w, 197, device="cuda")
     junk = [junk_stream.next_chunk(4) for _ in range(7)]
@@ -453,11 +462,13 @@ def test_graph_replay_matches_the_oracle_every_time(overlap, margin):
     torch.cuda.synchronize()
     want = p.orc.retrieve(np_view(qt), orc.RetrieveParams(orc.SEMI, 2, 6, 0.3))
     ko, vo, n_tok = p.orc.gather(want["frame_idx"])
+    a_want = p.orc.attend(1, np_view(q_new[0]), want["frame_idx"], np_view(k_loc), np_view(v_loc), True)
     for replay in range(3):
         step(junk)                           # eager work between the replays: another stream through
         for t in r_out.values():             # the same context, so cache and outputs hold other values
             t.fill_(-7)
         g_out[0].zero_()
+        a_out.zero_()
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
@@ -470,6 +481,7 @@ def test_graph_replay_matches_the_oracle_every_time(overlap, margin):
         assert int(g_out[2][0]) == n_tok
         np.testing.assert_array_equal(np_view(g_out[0][0]), ko)
         np.testing.assert_array_equal(np_view(g_out[1][0]), vo)
+        assert np.abs(to_f64(np_view(a_out[0].cpu())) - a_want).max() <= 2e-2 * max(1.0, np.abs(a_want).max())
         if margin > 1.0:
             assert int(st["refined"].sum()) == 28
     p.close()
