@@ -526,6 +526,8 @@ def _random_case(i):
                        k_frame=int(rng.integers(1, 9)), question_tokens=int(rng.integers(1, 40)), n_questions=3)
     kw = {"causal": bool(rng.integers(0, 2)), "batch_chunks": int(rng.choice([1, 3])), "overlap_copy": int(rng.integers(0, 2)),
           "refine_margin": float(rng.choice([-1.0, 0.0, 10.0]))}
+    if i % 6 == 5:   # the other reading of the transform's axis
+        kw["freq_axis"] = mk.MUKV_FREQ_TOKEN
     return w, kw
 
 
@@ -534,9 +536,11 @@ def test_seeded_sweep_of_small_shapes(i):
     # shapes nobody picked by hand: head counts and groups, every head size, odd token counts,
     # super-patch counts, keep ratios, signal mixes, masks, chunkings, launch modes
     w, kw = _random_case(i)
-    p = Pair(w, seed=5000 + i, chunk=w.chunk_frames, gpu_kw=dict(kw), orc_kw={"causal": kw["causal"]})
+    token_axis = kw.get("freq_axis", mk.MUKV_FREQ_FEATURE) == mk.MUKV_FREQ_TOKEN
+    p = Pair(w, seed=5000 + i, chunk=w.chunk_frames, gpu_kw=dict(kw),
+             orc_kw={"causal": kw["causal"], "freq_axis": orc.TOKEN_AXIS if token_axis else orc.FEATURE_AXIS})
     p.ingest()
-    p.check_compress()
+    p.check_compress(raw_signals=not token_axis)   # the token-axis signal grows with P: only its fused form has an absolute bar
     qs = questions_for(w, [w.question_tokens, 1, 7], 800 + i)
     for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
         p.check_retrieve(qs, mode, w.k_seg, w.k_frame, w.lambda_frame)
