@@ -411,6 +411,69 @@ class TestCompactionAndPooling:
         assert o.kappa == 1 and list(r["kept"][:, 0]) == [4, 9]
 
 
+class TestSegmentAsUnit:
+    """Sec. 3.3 with a whole segment as the unit of Eq. 4 (the coarsest granularity keeps a
+    fraction of the segment's tokens, wherever they lie): the unit is F_u frames of p tokens,
+    its attention signal is handed over, its super-patches are its frames."""
+
+    def cfg(self, **kw):
+        base = dict(tokens_per_frame=6 * 49, superpatches_per_frame=6, frames_per_segment=1, keep_ratio=0.8, alpha=0.8)
+        base.update(kw)
+        return tiny_cfg(**base)
+
+    def test_ramp_of_attention_over_equal_keys_keeps_the_top_of_the_ramp(self):
+        cfg = self.cfg()
+        P, kap = cfg.tokens_per_frame, int(0.8 * 6 * 49 + 1e-9)
+        k = np.ones((2, 2, 2 * P, 16), np.float32)  # equal keys: the frequency indicator is flat and drops out
+        v = rng.standard_normal(k.shape).astype(np.float32)
+        ramp = np.stack([np.arange(P, dtype=np.float64), np.arange(P, 0, -1, dtype=np.float64)])
+        o = orc.OracleMuKV(cfg)
+        r = o.compress_chunk(k, v, att=ramp)
+        assert o.kappa == kap == 235
+        np.testing.assert_array_equal(r["kept"][0], np.arange(P - kap, P))  # rising ramp: the last kappa tokens
+        np.testing.assert_array_equal(r["kept"][1], np.arange(kap))         # falling ramp: the first kappa
+        # the unit's frames are its super-patches: 59 tokens go, the first frame and 10 of the second
+        assert list(o.cnt_patch.reshape(2, 6)[0]) == [0, 39, 49, 49, 49, 49]
+        assert list(o.cnt_patch.reshape(2, 6)[1]) == [49, 49, 49, 49, 39, 0]
+
+    def test_tokens_are_ranked_over_the_unit_not_per_frame(self):
+        # all of the attention mass in one frame of the unit: that frame is kept whole and the
+        # other frames share what is left, which a per-frame ratio could not do
+        cfg = self.cfg(alpha=1.0, keep_ratio=0.25)
+        P = cfg.tokens_per_frame
+        k, v, _ = tiny_stream(cfg, 1)
+        att = np.zeros((1, P))
+        att[0, 3 * 49:4 * 49] = 1.0 + rng.random(49)
+        o = orc.OracleMuKV(cfg)
+        r = o.compress_chunk(k, v, att=att)
+        kap = o.kappa
+        assert kap == 73
+        kept = r["kept"][0]
+        assert set(range(3 * 49, 4 * 49)) <= set(kept)
+        # the remaining 24 slots go to equal (zero) scores: the earliest positions
+        np.testing.assert_array_equal(kept[:kap - 49], np.arange(kap - 49))
+        assert list(o.cnt_patch.reshape(1, 6)[0]) == [kap - 49, 0, 0, 49, 0, 0]
+
+    def test_block_keys_of_the_unit_are_means_of_its_kept_rows(self):
+        cfg = self.cfg()
+        P = cfg.tokens_per_frame
+        k, v, _ = tiny_stream(cfg, 3, "bf16")
+        att = rng.random((3, P))
+        o = orc.OracleMuKV(cfg)
+        r = o.compress_chunk(k, v, att=att)
+        kv = bf16_value(k[-1])  # scoring layer, [Hkv][3P][D]
+        for u in range(3):
+            kept = r["kept"][u]
+            rows = kv[:, u * P + kept]                                  # [Hkv][kappa][D]
+            np.testing.assert_allclose(o.rep_frame_k[u], rows.mean(axis=1).reshape(-1), atol=1e-14)
+            for s in range(6):
+                inside = kept[(kept >= s * 49) & (kept < (s + 1) * 49)]
+                want = kv[:, u * P + inside].mean(axis=1).reshape(-1) if len(inside) else np.zeros(32)
+                np.testing.assert_allclose(o.rep_patch_k[u * 6 + s], want, atol=1e-14)
+        # a segment of one unit has the unit's key
+        np.testing.assert_allclose(o.seg_reps(), o.rep_frame_k, atol=1e-14)
+
+
 # ------------------------------------------------------------- Eq. 6, 7, 8 ---
 class TestRetrieval:
     def test_question_pooling_is_token_mean(self):
