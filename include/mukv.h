@@ -78,7 +78,11 @@ typedef struct mukv_config {
     int32_t n_q_heads;              /* H_q, a multiple of n_kv_heads                   */
     int32_t n_kv_heads;             /* H_kv                                            */
     int32_t head_dim;               /* D: a power of two in 16..128                    */
-    int32_t tokens_per_frame;       /* P, 1..256                                       */
+    int32_t tokens_per_frame;       /* P, 1..256: the unit of Eq. 4.  257..8192 declares
+                                       a unit of several frames (up to a segment, Sec. 3.3
+                                       at the coarsest granularity) that is ranked as one:
+                                       S can then count its frames; alpha > 0 needs  
+                                       att_signal and freq_axis must be FEATURE           */
     int32_t frames_per_segment;     /* F >= 1                                          */
     int32_t superpatches_per_frame; /* S, 1..P: index-contiguous groups of floor(P/S)
                                        tokens, the last one takes the remainder        */
@@ -222,8 +226,8 @@ int mukv_flush(mukv_ctx *ctx);
  *
  * Errors: INVALID_ARG (null k/v, missing or doubled attention source),
  * SHAPE (n_frames < 1), CAPACITY (n_frames > max_chunk_frames or the cache is
- * full), UNSUPPORTED (strides or pointers not 16-byte aligned, or a query
- * token stride of 16 MiB or more).
+ * full), UNSUPPORTED (strides or pointers not 16-byte aligned, a query
+ * token stride of 16 MiB or more, or q_last for units of more than 256 tokens).
  */
 int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_strides *kv_strides,
                         const void *q_last, const mukv_strides *q_strides, const float *att_signal,

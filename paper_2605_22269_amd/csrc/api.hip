@@ -60,10 +60,14 @@ int validate_config(const mukv_config *cfg) {
     const int kappa = (int)std::floor(cfg->keep_ratio * cfg->tokens_per_frame + 1e-9);
     if (kappa < 1) return MUKV_ERR_INVALID_ARG;
     if (!pow2(cfg->head_dim) || cfg->head_dim < 16 || cfg->head_dim > 128) return MUKV_ERR_UNSUPPORTED;
-    if (cfg->tokens_per_frame > mukv::kMaxP) return MUKV_ERR_UNSUPPORTED;
+    if (cfg->tokens_per_frame > mukv::kMaxUnit) return MUKV_ERR_UNSUPPORTED;
+    // a unit of several frames: ranked as one, attention signal from the caller, feature-axis indicator
+    const bool large_unit = cfg->tokens_per_frame > mukv::kMaxP;
+    if (large_unit && cfg->freq_axis != MUKV_FREQ_FEATURE) return MUKV_ERR_UNSUPPORTED;
     if ((int64_t)cfg->n_kv_heads * cfg->head_dim > 1024) return MUKV_ERR_UNSUPPORTED;
     const int esz = cfg->dtype == MUKV_BF16 ? 2 : 4;
-    if (mukv::att_generic_lds_bytes(cfg->tokens_per_frame, cfg->head_dim, sizeof(double)) > 160 * 1024)
+    if (!large_unit &&
+        mukv::att_generic_lds_bytes(cfg->tokens_per_frame, cfg->head_dim, sizeof(double)) > 160 * 1024)
         return MUKV_ERR_UNSUPPORTED;
     if ((cfg->head_dim * esz) % 16) return MUKV_ERR_UNSUPPORTED;
     if (((int64_t)cfg->max_frames + cfg->frames_per_segment - 1) / cfg->frames_per_segment > 65536)
@@ -241,7 +245,8 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(dalloc(&c.ssum_v, (size_t)c.max_segments * C));
     ok(dalloc(&c.margin, MF));
     ok(dalloc(&c.refined, MF));
-    const size_t n_part_max = Hq * ((P + 31) / 32 > 2 ? (P + 31) / 32 : 2); // partial rows per frame
+    // partial rows per frame; none for a unit of several frames, whose attention signal is the caller's
+    const size_t n_part_max = P > (size_t)mukv::kMaxP ? 0 : Hq * ((P + 31) / 32 > 2 ? (P + 31) / 32 : 2);
     for (int par = 0; par < 2; ++par) {
         ok(dalloc(&c.att_part[par], MC * n_part_max * P));
         ok(dalloc(&c.fft_sig[par], MC * P));
@@ -418,6 +423,7 @@ int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_
         if ((q_last != nullptr) == (att_signal != nullptr)) return MUKV_ERR_INVALID_ARG;
         if (q_last && !q_strides) return MUKV_ERR_INVALID_ARG;
     }
+    if (c.cfg.tokens_per_frame > mukv::kMaxP && c.cfg.alpha != 0.0 && !att_signal) return MUKV_ERR_UNSUPPORTED;
     if (n_frames < 1) return MUKV_ERR_SHAPE;
     if (n_frames > c.cfg.max_chunk_frames) return MUKV_ERR_CAPACITY;
     if (c.n_frames + n_frames > c.cfg.max_frames) return MUKV_ERR_CAPACITY;

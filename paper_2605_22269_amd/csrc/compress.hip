@@ -708,6 +708,345 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Units of more than kMaxP tokens: several frames, up to a segment, ranked as ONE unit of Eq. 4
+// (Sec. 3.3 at the coarsest granularity keeps a fraction of the segment's tokens wherever they
+// lie).  P <= kMaxUnit.  The attention signal of such a unit is the caller's: the prefill that
+// produced the keys has it.  Two kernels take the place of select_pool_kernel.
+//
+// select_large_kernel: one workgroup of 1024 threads per unit, thread t owns the kUnitTok
+// consecutive tokens from kUnitTok * t.  Fused scores become order-preserving unsigned keys
+// (a padding token gets key 0, below every real one).  The kappa-th largest key is built bit by
+// bit from the top: the largest value x with #{key >= x} >= kappa.  Tokens above it are kept;
+// of those equal to it the lowest positions, by a prefix count; a second prefix count gives each
+// kept token its row.  Same outputs as select_pool_kernel up to the kept list.
+//
+// pool_large_kernel: Eq. 5 for the unit and its S super-patches.  Grid (unit, group of 64 channel
+// pairs); the unit's kept list sits in LDS; the kept rows of a super-patch are a run of that list
+// (positions ascend), found by bisection; the 4 waves take every 4th row of the run, a batch of
+// independent loads at a time, and their fp64 sums are joined in wave order.
+// ------------------------------------------------------------------------------------------
+constexpr int kUnitThreads = 1024;
+constexpr int kUnitTok = kMaxUnit / kUnitThreads;
+constexpr int kUnitWaves = kUnitThreads / kWave;
+
+template <typename R>
+struct OrdKey;
+template <>
+struct OrdKey<float> {
+    using U = uint32_t;
+    static constexpr int kBits = 32;
+    static __device__ __forceinline__ U of(float x) {
+        const uint32_t b = __float_as_uint(x);
+        return (b >> 31) ? ~b : (b | 0x80000000u);
+    }
+    static __device__ __forceinline__ float back(U k) { return __uint_as_float((k >> 31) ? (k & 0x7fffffffu) : ~k); }
+};
+template <>
+struct OrdKey<double> {
+    using U = uint64_t;
+    static constexpr int kBits = 64;
+    static __device__ __forceinline__ U of(double x) {
+        const uint64_t b = (uint64_t)__double_as_longlong(x);
+        return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+    }
+    static __device__ __forceinline__ double back(U k) {
+        return __longlong_as_double((long long)((k >> 63) ? (k & 0x7fffffffffffffffull) : ~k));
+    }
+};
+
+// Sum of v over the 16 waves.  buf: kUnitWaves ints; two calls in a row use different buffers.
+__device__ __forceinline__ int unit_sum(int v, int *buf) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    if ((threadIdx.x & 63) == 0) buf[threadIdx.x >> 6] = v;
+    __syncthreads();
+    int s = 0;
+#pragma unroll
+    for (int w = 0; w < kUnitWaves; ++w) s += buf[w];
+    return s;
+}
+
+// Exclusive prefix of v in thread order and the total; buf as for unit_sum.
+__device__ __forceinline__ int unit_scan(int v, int *buf, int &total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o);
+        inc += lane >= o ? t : 0;
+    }
+    if (lane == 63) buf[wave] = inc;
+    __syncthreads();
+    int base = 0;
+    total = 0;
+#pragma unroll
+    for (int w = 0; w < kUnitWaves; ++w) {
+        const int c = buf[w];
+        base += w < wave ? c : 0;
+        total += c;
+    }
+    return base + inc - v;
+}
+
+template <typename R>
+__device__ __forceinline__ void unit_minmax(R mn, R mx, R *red, R &lo, R &hi) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const R a = __shfl_xor(mn, o), b = __shfl_xor(mx, o);
+        mn = a < mn ? a : mn;
+        mx = b > mx ? b : mx;
+    }
+    __syncthreads(); // the previous use of red is over
+    if ((threadIdx.x & 63) == 0) {
+        red[threadIdx.x >> 6] = mn;
+        red[kUnitWaves + (threadIdx.x >> 6)] = mx;
+    }
+    __syncthreads();
+    lo = red[0];
+    hi = red[kUnitWaves];
+#pragma unroll
+    for (int w = 1; w < kUnitWaves; ++w) {
+        lo = red[w] < lo ? red[w] : lo;
+        hi = red[kUnitWaves + w] > hi ? red[kUnitWaves + w] : hi;
+    }
+}
+
+template <typename R>
+__global__ __launch_bounds__(kUnitThreads) void select_large_kernel(SelectArgs<R> a) {
+    using K = OrdKey<R>;
+    using U = typename K::U;
+    __shared__ R red[2 * kUnitWaves];
+    __shared__ U kred[kUnitWaves];
+    __shared__ int cnt[2][kUnitWaves];
+    const int tid = threadIdx.x;
+    const int P = a.P, kappa = a.kappa;
+    const int j0 = tid * kUnitTok;
+    const int n_e = a.pass2 ? *a.flag_count : (int)gridDim.x;
+    for (int e_idx = blockIdx.x; e_idx < n_e; e_idx += gridDim.x) {
+        const int f = a.pass2 ? a.flag_list[e_idx] : e_idx;
+        const int64_t gf = a.frame0 + f;
+        const int slot = find_slot(a.map, f);
+        const int lf = f - a.map.fstart[slot];
+        float *dbg_att = a.have_dbg ? a.dbg_att.p[slot] : nullptr;
+        float *dbg_fft = a.have_dbg ? a.dbg_fft.p[slot] : nullptr;
+        float *dbg_fused = a.have_dbg ? a.dbg_fused.p[slot] : nullptr;
+        const float *att_in = a.have_att_in ? reinterpret_cast<const float *>(a.att_in.p[slot]) + (int64_t)lf * P : nullptr;
+        const R *fft = a.fft ? a.fft + (int64_t)f * P : nullptr;
+
+        R av[kUnitTok], fv[kUnitTok];
+#pragma unroll
+        for (int u = 0; u < kUnitTok; ++u) {
+            const int j = j0 + u < P ? j0 + u : P - 1;
+            av[u] = att_in ? (R)att_in[j] : (R)0;
+            fv[u] = fft ? fft[j] : (R)0;
+        }
+#pragma unroll
+        for (int u = 0; u < kUnitTok; ++u) {
+            if (j0 + u < P) {
+                if (dbg_att) dbg_att[(int64_t)lf * P + j0 + u] = (float)av[u];
+                if (dbg_fft) dbg_fft[(int64_t)lf * P + j0 + u] = (float)fv[u];
+            }
+        }
+        R fused[kUnitTok];
+#pragma unroll
+        for (int u = 0; u < kUnitTok; ++u) fused[u] = 0;
+        if (a.alpha != (R)0) { // clamped tokens repeat token P-1: they change neither bound
+            R mn = av[0], mx = av[0], lo, hi;
+#pragma unroll
+            for (int u = 1; u < kUnitTok; ++u) {
+                mn = av[u] < mn ? av[u] : mn;
+                mx = av[u] > mx ? av[u] : mx;
+            }
+            unit_minmax(mn, mx, red, lo, hi);
+#pragma unroll
+            for (int u = 0; u < kUnitTok; ++u) fused[u] = a.alpha * ((hi > lo) ? (av[u] - lo) / (hi - lo) : (R)0);
+        }
+        if (a.alpha != (R)1) {
+            R mn = fv[0], mx = fv[0], lo, hi;
+#pragma unroll
+            for (int u = 1; u < kUnitTok; ++u) {
+                mn = fv[u] < mn ? fv[u] : mn;
+                mx = fv[u] > mx ? fv[u] : mx;
+            }
+            unit_minmax(mn, mx, red, lo, hi);
+#pragma unroll
+            for (int u = 0; u < kUnitTok; ++u)
+                fused[u] += ((R)1 - a.alpha) * ((hi > lo) ? (fv[u] - lo) / (hi - lo) : (R)0);
+        }
+        U key[kUnitTok];
+#pragma unroll
+        for (int u = 0; u < kUnitTok; ++u) {
+            const bool valid = j0 + u < P;
+            key[u] = valid ? K::of(fused[u]) : (U)0;
+            if (valid && dbg_fused) dbg_fused[(int64_t)lf * P + j0 + u] = (float)fused[u];
+        }
+
+        // the kappa-th largest key
+        U kth = 0;
+        for (int b = K::kBits - 1; b >= 0; --b) {
+            const U cand = kth | ((U)1 << b);
+            int n = 0;
+#pragma unroll
+            for (int u = 0; u < kUnitTok; ++u) n += key[u] >= cand;
+            if (unit_sum(n, cnt[b & 1]) >= kappa) kth = cand;
+        }
+        // ties at the threshold go to the lowest positions
+        int n_gt = 0, n_eq = 0;
+#pragma unroll
+        for (int u = 0; u < kUnitTok; ++u) {
+            n_gt += key[u] > kth;
+            n_eq += key[u] == kth;
+        }
+        const int tot_gt = unit_sum(n_gt, cnt[1]); // the loop's last call used cnt[0]
+        const int need = kappa - tot_gt;
+        int tot_eq;
+        int eq_rank = unit_scan(n_eq, cnt[0], tot_eq);
+        unsigned kept_mask = 0;
+        int n_kept = 0;
+#pragma unroll
+        for (int u = 0; u < kUnitTok; ++u) {
+            const bool eq = key[u] == kth;
+            const bool kept = key[u] > kth || (eq && eq_rank < need);
+            eq_rank += eq;
+            kept_mask |= (unsigned)kept << u;
+            n_kept += kept;
+        }
+        int tot_kept;
+        int pos = unit_scan(n_kept, cnt[1], tot_kept); // tot_kept == kappa
+
+        // selection margin: the kappa-th largest score minus the next one in rank order
+        R mg = (R)INFINITY;
+        if (kappa < P) {
+            U below = 0;
+            if (tot_gt + tot_eq > kappa) {
+                below = kth; // a token equal to the threshold was dropped
+            } else {
+#pragma unroll
+                for (int u = 0; u < kUnitTok; ++u) below = (key[u] < kth && key[u] > below) ? key[u] : below;
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) {
+                    const U t = __shfl_xor(below, o);
+                    below = t > below ? t : below;
+                }
+                if ((tid & 63) == 0) kred[tid >> 6] = below;
+                __syncthreads();
+                below = kred[0];
+#pragma unroll
+                for (int w = 1; w < kUnitWaves; ++w) below = kred[w] > below ? kred[w] : below;
+            }
+            mg = K::back(kth) - K::back(below);
+        }
+        const bool flag = !a.pass2 && a.margin_thr > (R)0 && mg < a.margin_thr;
+#pragma unroll
+        for (int u = 0; u < kUnitTok; ++u) {
+            if ((kept_mask >> u) & 1u) {
+                a.kept_idx[gf * kappa + pos] = j0 + u;
+                a.src_tok[(int64_t)f * kappa + pos] = flag ? -1 : lf * P + j0 + u;
+                ++pos;
+            }
+        }
+        if (tid == 0) {
+            a.margin[gf] = (float)mg;
+            a.refined[gf] = (a.pass2 || flag) ? 1 : 0;
+            if (flag) a.flag_list[atomicAdd(a.flag_count, 1)] = f;
+        }
+        __syncthreads(); // kred and cnt are reused by the next unit
+    }
+}
+
+constexpr int kPoolBatch = 8;
+template <typename T, typename R>
+__global__ __launch_bounds__(256) void pool_large_kernel(SelectArgs<R> a) {
+    __shared__ int kl[kMaxUnit];
+    __shared__ double part[4][64][4];
+    const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int P = a.P, kappa = a.kappa, S = a.S;
+    const int C = a.Hkv * a.D;
+    const int cp = blockIdx.y * 64 + lane;
+    const bool live = cp < C / 2;
+    const int c = live ? 2 * cp : 0;
+    const int g = c / a.D, d = c - g * a.D;
+    const int len = P / S;
+    const int n_e = a.pass2 ? *a.flag_count : (int)gridDim.x;
+    for (int e_idx = blockIdx.x; e_idx < n_e; e_idx += gridDim.x) {
+        const int f = a.pass2 ? a.flag_list[e_idx] : e_idx;
+        const int64_t gf = a.frame0 + f;
+        const int slot = find_slot(a.map, f);
+        const int lf = f - a.map.fstart[slot];
+        for (int r = threadIdx.x; r < kappa; r += 256) kl[r] = a.kept_idx[gf * kappa + r];
+        __syncthreads();
+        const T *xk = reinterpret_cast<const T *>(a.k.p[slot]) + a.k_off;
+        const T *xv = reinterpret_cast<const T *>(a.v.p[slot]) + a.k_off;
+        const int64_t col = (int64_t)g * a.sh + d + (int64_t)lf * P * a.st;
+        double tot[4] = {0.0, 0.0, 0.0, 0.0}; // k0 k1 v0 v1, used by wave 0
+        int b = 0;
+        for (int s = 0; s < S; ++s) {
+            int e = kappa;
+            if (s < S - 1) { // first kept row at or beyond the next super-patch
+                const int bound = (s + 1) * len;
+                int lo = b, hi = kappa;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (kl[mid] < bound) lo = mid + 1; else hi = mid;
+                }
+                e = lo;
+            }
+            double run[4] = {0.0, 0.0, 0.0, 0.0};
+            for (int r0 = b + slice; r0 < e; r0 += 4 * kPoolBatch) {
+                Pair2<T> yk[kPoolBatch], yv[kPoolBatch];
+#pragma unroll
+                for (int u = 0; u < kPoolBatch; ++u) {
+                    const int r = r0 + 4 * u < e ? r0 + 4 * u : e - 1; // clamped: loads stay unconditional
+                    const int64_t off = col + (int64_t)kl[r] * a.st;
+                    yk[u] = *reinterpret_cast<const Pair2<T> *>(xk + off);
+                    yv[u] = *reinterpret_cast<const Pair2<T> *>(xv + off);
+                }
+#pragma unroll
+                for (int u = 0; u < kPoolBatch; ++u) {
+                    if (r0 + 4 * u < e) {
+                        run[0] += (double)to_float(yk[u].a);
+                        run[1] += (double)to_float(yk[u].b);
+                        run[2] += (double)to_float(yv[u].a);
+                        run[3] += (double)to_float(yv[u].b);
+                    }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) part[slice][lane][q] = run[q];
+            __syncthreads();
+            if (slice == 0 && live) {
+                const int n = e - b;
+                double sum[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    sum[q] = (part[0][lane][q] + part[1][lane][q]) + (part[2][lane][q] + part[3][lane][q]);
+                    tot[q] += sum[q];
+                }
+                const int64_t o = (gf * S + s) * C + c;
+                a.rep_patch_k[o] = n ? (float)(sum[0] / (double)n) : 0.0f;
+                a.rep_patch_k[o + 1] = n ? (float)(sum[1] / (double)n) : 0.0f;
+                a.rep_patch_v[o] = n ? (float)(sum[2] / (double)n) : 0.0f;
+                a.rep_patch_v[o + 1] = n ? (float)(sum[3] / (double)n) : 0.0f;
+                if (c == 0) a.cnt_patch[gf * S + s] = n;
+            }
+            __syncthreads();
+            b = e;
+        }
+        if (slice == 0 && live) {
+            const int64_t o = gf * C + c;
+            a.fsum_k[o] = tot[0];
+            a.fsum_k[o + 1] = tot[1];
+            a.fsum_v[o] = tot[2];
+            a.fsum_v[o + 1] = tot[3];
+            a.rep_frame_k[o] = (float)(tot[0] / (double)kappa);
+            a.rep_frame_k[o + 1] = (float)(tot[1] / (double)kappa);
+            a.rep_frame_v[o] = (float)(tot[2] / (double)kappa);
+            a.rep_frame_v[o + 1] = (float)(tot[3] / (double)kappa);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Storage of the kept KV rows of every layer (Sec. 3.3, last paragraph) and segment keys.
 // grid.y < n_slab: slab (layer, K|V, KV head); grid.x = (slot of the batch, part of the slot).
 // A slot's destination inside the slab is one dense run of its frames' kappa rows, so unit u of
@@ -1030,7 +1369,14 @@ static hipError_t launch_select(const Ctx &c, const ChunkArgs &a, const R *att, 
     s.dbg_fft = a.dbg_fft;
     s.dbg_fused = a.dbg_fused;
     s.have_dbg = a.have_dbg;
-    hipLaunchKernelGGL((select_pool_kernel<T, R>), dim3(pass2 ? kRescoreSlots : a.n_frames), dim3(256), 0, st, s);
+    const int gx = pass2 ? kRescoreSlots : a.n_frames;
+    if (s.P > kMaxP) { // a unit of several frames: the keep and the block keys in two launches
+        const int n_cg = (s.Hkv * s.D / 2 + 63) / 64;
+        hipLaunchKernelGGL((select_large_kernel<R>), dim3(gx), dim3(kUnitThreads), 0, st, s);
+        hipLaunchKernelGGL((pool_large_kernel<T, R>), dim3(gx, n_cg), dim3(256), 0, st, s);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL((select_pool_kernel<T, R>), dim3(gx), dim3(256), 0, st, s);
     return hipGetLastError();
 }
 

@@ -13,6 +13,7 @@ namespace mukv {
 
 constexpr int kWave = 64;
 constexpr int kMaxP = 256;        // tokens per frame the per-frame kernels are built for
+constexpr int kMaxUnit = 8192;    // tokens of a unit of several frames ranked as one (attention signal handed over)
 constexpr int kMaxCand = 1024;    // stage-1 candidates (2*k) held in LDS by the rerank kernel
 constexpr int kMaxGatherK = 1024; // selected frames per question the gather kernel can plan
 

@@ -166,6 +166,21 @@ def planted_question(w: Workload, target_keys: torch.Tensor, n_tokens: int, seed
     return (q_bar.unsqueeze(0) + eps).view(n_tokens, Hq, D).to(w.torch_dtype)
 
 
+def handed_over_attention(n_units: int, tokens_per_unit: int, seed: int, tie_fraction: float = 0.3):
+    """Stand-in for the attention-received signal (Eq. 1) that a prefill hands over for units it
+    has just processed: float32 [n_units][tokens_per_unit], positive, heavy-tailed, a sink at the
+    first token of every unit, and a fraction of the values snapped to a coarse grid so that exact
+    ties occur.  No arithmetic of the method is in here: just numbers with that shape."""
+    g = torch.Generator().manual_seed(seed)
+    a = torch.rand(n_units, tokens_per_unit, generator=g, dtype=torch.float64)
+    a = (a * a * a) / tokens_per_unit
+    a[:, 0] += 20.0 / tokens_per_unit
+    snap = torch.rand(n_units, tokens_per_unit, generator=g) < tie_fraction
+    grid = 2.0 ** -14
+    a = torch.where(snap, torch.round(a / grid) * grid, a)
+    return a.to(torch.float32)
+
+
 def question_lengths(n_questions: int, lo: int, hi: int, seed: int):
     """Uniform integer lengths in [lo, hi] for a batch of questions."""
     g = torch.Generator()

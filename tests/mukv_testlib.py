@@ -56,17 +56,22 @@ class Pair:
         self.sig_gpu, self.sig_orc = [], []
         self.keep_alive = []  # device inputs must outlive a gathered batch
 
-    def ingest(self, n_frames=None, att_from_oracle=False):
-        """Feeds the next n_frames (default: all remaining) in chunks to both sides."""
+    def ingest(self, n_frames=None, att_from_oracle=False, att_seed=None):
+        """Feeds the next n_frames (default: all remaining) in chunks to both sides.  The attention
+        signal is computed by each side from the queries, or handed to both: the oracle's own
+        (att_from_oracle) or a seeded stand-in (att_seed)."""
         todo = self.n - self.orc.n_frames if n_frames is None else n_frames
         while todo > 0:
             n = min(self.chunk, todo)
             k, v, q = self.stream.next_chunk(n)
             kn, vn, qn = np_view(k), np_view(v), (np_view(q) if q is not None else None)
             att_np = att_t = None
-            if att_from_oracle:
-                att_np = orc.att_signal(qn, kn[self.orc.ls], n, self.w.tokens_per_frame, self.orc.cfg.causal)
-                att_np = att_np.astype(np.float32)
+            if att_from_oracle or att_seed is not None:
+                if att_seed is not None:
+                    att_np = synth.handed_over_attention(n, self.w.tokens_per_frame, att_seed + self.orc.n_frames).numpy()
+                else:
+                    att_np = orc.att_signal(qn, kn[self.orc.ls], n, self.w.tokens_per_frame, self.orc.cfg.causal)
+                    att_np = att_np.astype(np.float32)
                 att_t = torch.from_numpy(att_np).cuda()
                 kd, vd = k.cuda(), v.cuda()
                 self.keep_alive += [kd, vd, att_t]

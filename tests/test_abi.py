@@ -50,7 +50,7 @@ def test_strerror_covers_every_status():
     ("score_layer", 2, mk.MUKV_ERR_SHAPE),
     ("head_dim", 48, mk.MUKV_ERR_UNSUPPORTED),
     ("head_dim", 256, mk.MUKV_ERR_UNSUPPORTED),
-    ("tokens_per_frame", 300, mk.MUKV_ERR_UNSUPPORTED),
+    ("tokens_per_frame", 8193, mk.MUKV_ERR_UNSUPPORTED),
     ("max_frames", 0, mk.MUKV_ERR_INVALID_ARG),
     ("batch_chunks", -1, mk.MUKV_ERR_INVALID_ARG),
     ("batch_chunks", 65, mk.MUKV_ERR_UNSUPPORTED),

@@ -865,3 +865,74 @@ def test_token_axis_signal_with_odd_token_counts():
         p.ingest()
         p.check_compress(raw_signals=False)
         p.close()
+
+
+# ------------------------------------- a unit of several frames ranked as one (Sec. 3.3) -----
+def _unit_workload(dtype, P, S, rho, alpha, units, **kw):
+    base = dict(dtype=dtype, tokens_per_frame=P, superpatches_per_frame=S, keep_ratio=rho, alpha=alpha,
+                n_frames=units, frames_per_segment=2, n_layers=2, n_kv_heads=2, n_q_heads=4, head_dim=32,
+                spike_prob=0.05, k_seg=1, k_frame=2, n_questions=2)
+    base.update(kw)
+    return W["tiny"].scaled(**base)
+
+
+@pytest.mark.parametrize("dtype,P,S,rho,alpha,units,chunk", [
+    ("bf16", 6 * 49, 6, 0.8, 0.8, 7, 3),     # just above what the per-frame kernels take
+    ("f32", 1000, 1, 0.5, 0.5, 4, 4),
+    ("bf16", 2049, 7, 0.1, 1.0, 3, 2),       # the last thread's tokens are ragged
+    ("f32", 3000, 32, 0.8, 0.0, 3, 1),       # frequency indicator alone
+    ("bf16", 8192, 32, 0.8, 0.8, 2, 1),      # the largest unit
+    ("bf16", 257, 257, 1.0, 0.5, 3, 3),      # everything kept, every token its own super-patch
+])
+def test_segment_ranked_as_one_unit(dtype, P, S, rho, alpha, units, chunk):
+    w = _unit_workload(dtype, P, S, rho, alpha, units)
+    p = Pair(w, seed=300 + P, chunk=chunk, with_q=False)
+    p.ingest(att_seed=7000 + P)
+    st = p.check_compress()
+    print(f"unit of {P} tokens: kappa {p.orc.kappa}, re-scored {int(st['refined'].sum())} of {units}")
+    # the cache behaves like any other downstream: retrieval over units, gather, attention
+    qs = questions_for(w, [5, 9], 310)
+    p.check_retrieve(qs, mk.MUKV_SEMI, 1, 2, 0.3)
+    p.check_retrieve_patches(qs, mk.MUKV_PARALLEL, 1, min(3, S * units), 0.3)
+    p.check_attend(1, 3, [[0, units - 1], [units - 1, -1]], [4, 0], True, seed=311)
+    p.close()
+
+
+def test_segment_of_the_paper_as_one_unit():
+    # 32 frames of 196 tokens, 80 % kept, frames as super-patches, 7B head layout
+    w = _unit_workload("bf16", 32 * 196, 32, 0.8, 0.8, 3, n_kv_heads=4, n_q_heads=28, head_dim=128, frames_per_segment=1)
+    p = Pair(w, seed=320, chunk=2, with_q=False)
+    p.ingest(att_seed=7320)
+    st = p.check_compress()
+    assert p.orc.kappa == 5017
+    p.check_attend(0, 2, [[2, 0]], [3], True, seed=321)
+    p.close()
+
+
+@pytest.mark.parametrize("kw", [{"refine_margin": 10.0}, {"batch_chunks": 2, "overlap_copy": 1},
+                                {"batch_chunks": 3, "refine_margin": 10.0, "overlap_copy": 1}])
+def test_large_units_with_rescoring_batching_and_overlapped_copy(kw):
+    w = _unit_workload("bf16", 700, 4, 0.3, 0.6, 9)
+    p = Pair(w, seed=330, chunk=2, with_q=False, gpu_kw=kw)
+    p.ingest(att_seed=7330)
+    st = p.check_compress()
+    if kw.get("refine_margin", 0) > 1:
+        assert int(st["refined"].sum()) == 9
+    p.close()
+
+
+def test_large_unit_argument_errors():
+    w = _unit_workload("bf16", 512, 2, 0.5, 0.5, 2)
+    with pytest.raises(mk.MuKVError) as e:                   # the token-axis indicator is per frame
+        gpu_context(w, freq_axis=mk.MUKV_FREQ_TOKEN)
+    assert e.value.status == mk.MUKV_ERR_UNSUPPORTED
+    with pytest.raises(mk.MuKVError) as e:
+        gpu_context(_unit_workload("bf16", 8193, 1, 0.5, 0.5, 2))
+    assert e.value.status == mk.MUKV_ERR_UNSUPPORTED
+    g = gpu_context(w)
+    k, v, q = synth.SynthStream(w, 1).next_chunk(1)
+    with pytest.raises(mk.MuKVError) as e:                   # the attention signal has to be handed over
+        g.compress_chunk(k.cuda(), v.cuda(), q.cuda())
+    assert e.value.status == mk.MUKV_ERR_UNSUPPORTED
+    assert g.state()["n_frames"] == 0
+    g.close()
