@@ -421,7 +421,39 @@ def main():
         res["compress_single_calls_of_512_frames"] = {"calls": 7, "ms": big_ms,
                                                       "tokens_per_s": 7 * nbig * P / (big_ms * 1e-3)}
         big.close()
-        del kb, vb, qb
+
+        # ---- the coarsest granularity of Sec. 3.3: a segment of 32 frames ranked as ONE unit of Eq. 4,
+        # 80 % of its tokens kept, alpha = 0.8, its frames as super-patches, the attention signal handed
+        # over; the same 512 frames as 16 units per call, 7 calls ----
+        seg_P, seg_units = 32 * P, nbig // 32
+        seg = mk.MuKV(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, tokens_per_frame=seg_P,
+                      frames_per_segment=1, superpatches_per_frame=32, dtype=w.torch_dtype, keep_ratio=0.8, alpha=0.8,
+                      max_frames=7 * seg_units, max_chunk_frames=seg_units, max_questions=1, batch_chunks=1,
+                      overlap_copy=a.overlap_copy)
+        att_u = synth.handed_over_attention(seg_units, seg_P, a.seed + 5, tie_fraction=0.0).to(dev)
+
+        def seg_calls():
+            seg.reset()
+            for _ in range(7):
+                seg.compress_chunk(kb, vb, None, att_signal=att_u)
+            seg.flush()
+
+        seg_calls()
+        seg_ms = timed(seg_calls, 3)
+        mk.mukv_profile_begin(seg.h)
+        seg_calls()
+        seg_prof = mk.mukv_profile_end(seg.h)
+        seg_tok = 7 * nbig * P
+        seg_bytes = 2 * seg.kappa * L * b_tok / seg_P + Hkv * D * esz + 4   # per token: kept rows in and out, keys, the signal
+        res["compress_segments_as_units"] = {
+            "unit_tokens": seg_P, "kept_per_unit": seg.kappa, "units_per_call": seg_units, "calls": 7, "ms": seg_ms,
+            "tokens_per_s": seg_tok / (seg_ms * 1e-3), "algorithmic_bytes_per_token": seg_bytes,
+            "achieved_GBs": seg_bytes * seg_tok / (seg_ms * 1e-3) / 1e9,
+            "frac_of_peak": seg_bytes * seg_tok / (seg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "refined_units": int(seg.state()["refined"].sum()),
+            "kernel_us": {n: p["ms"] / p["launches"] * 1e3 for n, p in seg_prof.items() if p["launches"]}}
+        seg.close()
+        del kb, vb, qb, att_u
 
     # ---- the attention signal handed over by the caller (the paper takes it from the prefill that
     # produced the KV, "without additional computation"): the same stream, Eq. 1 skipped, Q not read --

@@ -46,7 +46,9 @@ __device__ __forceinline__ double fma_t(double a, double b, double c) { return f
 __device__ __forceinline__ float abs_t(float x) { return fabsf(x); }
 __device__ __forceinline__ double abs_t(double x) { return fabs(x); }
 
-constexpr int kFreqBlocksPerFrame = 7;
+// Workgroups that share the tokens of one frame (grid.y of the frequency kernel): 7 for a frame of
+// up to kMaxP tokens, and as many per 196 tokens for a unit of several frames.
+static inline int freq_blocks_per_frame(int P) { return P <= kMaxP ? 7 : 7 * ((P + 195) / 196); }
 
 // sum over the N consecutive lanes of a transform (N a power of two <= 64), result in every lane
 template <int N, typename R>
@@ -85,13 +87,15 @@ __device__ __forceinline__ void fft_stages(R (&zr)[GH], R (&zi)[GH], const R *sg
 // so it gets fewer slots: its idle ones still have to be placed before they can leave.
 constexpr int kRescoreSlots = 4;
 constexpr int kRescoreSlotsAtt = 2;
+// A unit of several frames is tens of frames' worth of work and a batch holds few of them: one slot each.
+static inline int rescore_slots(int P, int n_frames) { return P > kMaxP ? n_frames : kRescoreSlots; }
 
-// Work of workgroup (bx, by) of a (gx, kFreqBlocksPerFrame) grid.
+// Work of workgroup (bx, by) of a (gx, bpf) grid.
 template <typename T, typename R, int D>
 __device__ __forceinline__ void freq_body(const PtrTable &ktab, const FrameMap &map, int64_t k_off, int64_t sh,
                                           int64_t st, int Hkv, int P, const int32_t *__restrict__ flag_list,
                                           const int32_t *__restrict__ flag_count, R *__restrict__ out, int bx, int by,
-                                          int gx) {
+                                          int gx, int bpf) {
     constexpr int N = D / 2;
     constexpr int GROUPS = kWave / N;
     constexpr int LOG = (N == 64) ? 6 : (N == 32) ? 5 : (N == 16) ? 4 : 3;
@@ -122,7 +126,7 @@ __device__ __forceinline__ void freq_body(const PtrTable &ktab, const FrameMap &
     const int slot = find_slot(map, f);
     const T *k = reinterpret_cast<const T *>(ktab.p[slot]) + k_off + (int64_t)(f - map.fstart[slot]) * P * st;
     // the workgroup's waves walk over the frame's tokens, GROUPS tokens per wave and step
-    const int stride = kFreqBlocksPerFrame * 4 * GROUPS;
+    const int stride = bpf * 4 * GROUPS;
     // Up to four heads of a token are transformed together (independent butterflies hide the
     // lane-exchange latency), and the key elements of the next group are loaded before the
     // current group is computed.
@@ -188,7 +192,8 @@ __global__ __launch_bounds__(256) void freq_signal_kernel(PtrTable ktab, FrameMa
                                                           const int32_t *__restrict__ flag_list,
                                                           const int32_t *__restrict__ flag_count,
                                                           R *__restrict__ out) {
-    freq_body<T, R, D>(ktab, map, k_off, sh, st, Hkv, P, flag_list, flag_count, out, blockIdx.x, blockIdx.y, gridDim.x);
+    freq_body<T, R, D>(ktab, map, k_off, sh, st, Hkv, P, flag_list, flag_count, out, blockIdx.x, blockIdx.y, gridDim.x,
+                       gridDim.y);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -722,7 +727,7 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
 //
 // pool_large_kernel: Eq. 5 for the unit and its S super-patches.  Grid (unit, group of 64 channel
 // pairs); the unit's kept list sits in LDS; the kept rows of a super-patch are a run of that list
-// (positions ascend), found by bisection; the 4 waves take every 4th row of the run, a batch of
+// (positions ascend), found by bisection; the 16 waves take every 16th row of the run, a batch of
 // independent loads at a time, and their fp64 sums are joined in wave order.
 // ------------------------------------------------------------------------------------------
 constexpr int kUnitThreads = 1024;
@@ -955,10 +960,11 @@ __global__ __launch_bounds__(kUnitThreads) void select_large_kernel(SelectArgs<R
 }
 
 constexpr int kPoolBatch = 8;
+constexpr int kPoolSlices = kUnitWaves;
 template <typename T, typename R>
-__global__ __launch_bounds__(256) void pool_large_kernel(SelectArgs<R> a) {
+__global__ __launch_bounds__(kUnitThreads) void pool_large_kernel(SelectArgs<R> a) {
     __shared__ int kl[kMaxUnit];
-    __shared__ double part[4][64][4];
+    __shared__ double part[kPoolSlices][64][4];
     const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
     const int P = a.P, kappa = a.kappa, S = a.S;
     const int C = a.Hkv * a.D;
@@ -971,9 +977,10 @@ __global__ __launch_bounds__(256) void pool_large_kernel(SelectArgs<R> a) {
     for (int e_idx = blockIdx.x; e_idx < n_e; e_idx += gridDim.x) {
         const int f = a.pass2 ? a.flag_list[e_idx] : e_idx;
         const int64_t gf = a.frame0 + f;
+        if (!a.pass2 && a.refined[gf]) continue; // on the re-scoring list: its keys come from the fp64 pass
         const int slot = find_slot(a.map, f);
         const int lf = f - a.map.fstart[slot];
-        for (int r = threadIdx.x; r < kappa; r += 256) kl[r] = a.kept_idx[gf * kappa + r];
+        for (int r = threadIdx.x; r < kappa; r += kUnitThreads) kl[r] = a.kept_idx[gf * kappa + r];
         __syncthreads();
         const T *xk = reinterpret_cast<const T *>(a.k.p[slot]) + a.k_off;
         const T *xv = reinterpret_cast<const T *>(a.v.p[slot]) + a.k_off;
@@ -992,18 +999,18 @@ __global__ __launch_bounds__(256) void pool_large_kernel(SelectArgs<R> a) {
                 e = lo;
             }
             double run[4] = {0.0, 0.0, 0.0, 0.0};
-            for (int r0 = b + slice; r0 < e; r0 += 4 * kPoolBatch) {
+            for (int r0 = b + slice; r0 < e; r0 += kPoolSlices * kPoolBatch) {
                 Pair2<T> yk[kPoolBatch], yv[kPoolBatch];
 #pragma unroll
                 for (int u = 0; u < kPoolBatch; ++u) {
-                    const int r = r0 + 4 * u < e ? r0 + 4 * u : e - 1; // clamped: loads stay unconditional
+                    const int r = r0 + kPoolSlices * u < e ? r0 + kPoolSlices * u : e - 1; // clamped: loads stay unconditional
                     const int64_t off = col + (int64_t)kl[r] * a.st;
                     yk[u] = *reinterpret_cast<const Pair2<T> *>(xk + off);
                     yv[u] = *reinterpret_cast<const Pair2<T> *>(xv + off);
                 }
 #pragma unroll
                 for (int u = 0; u < kPoolBatch; ++u) {
-                    if (r0 + 4 * u < e) {
+                    if (r0 + kPoolSlices * u < e) {
                         run[0] += (double)to_float(yk[u].a);
                         run[1] += (double)to_float(yk[u].b);
                         run[2] += (double)to_float(yv[u].a);
@@ -1019,7 +1026,9 @@ __global__ __launch_bounds__(256) void pool_large_kernel(SelectArgs<R> a) {
                 double sum[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    sum[q] = (part[0][lane][q] + part[1][lane][q]) + (part[2][lane][q] + part[3][lane][q]);
+                    sum[q] = part[0][lane][q];
+#pragma unroll
+                    for (int w = 1; w < kPoolSlices; ++w) sum[q] += part[w][lane][q];
                     tot[q] += sum[q];
                 }
                 const int64_t o = (gf * S + s) * C + c;
@@ -1185,7 +1194,8 @@ struct FreqPart {
     int Hkv, P;
     float *out;
     int n_frames; // grid.x of the stand-alone frequency kernel
-    int n_wg;     // n_frames * kFreqBlocksPerFrame
+    int bpf;      // grid.y of the stand-alone frequency kernel
+    int n_wg;     // n_frames * bpf
 };
 
 template <typename T, int D>
@@ -1194,11 +1204,15 @@ __global__ __launch_bounds__(256) void copy_freq_kernel(CompactArgs ca, int copy
     const int q = b / period, r = b - q * period;
     if (r == 0 && q < fp.n_wg) {
         freq_body<T, float, D>(fp.k, fp.map, fp.k_off, fp.sh, fp.st, fp.Hkv, fp.P, nullptr, nullptr, fp.out,
-                               q % fp.n_frames, q / fp.n_frames, fp.n_frames);
+                               q % fp.n_frames, q / fp.n_frames, fp.n_frames, fp.bpf);
     } else {
         const int before = q + (r > 0) < fp.n_wg ? q + (r > 0) : fp.n_wg; // frequency workgroups with a lower number
         const int cid = b - before;
-        compact_body<u32x4, kFusedCopyIter>(ca, cid % copy_gx, cid / copy_gx);
+        const int n_rows = copy_gx * ca.n_slab; // then one workgroup per segment job
+        if (cid < n_rows)
+            compact_body<u32x4, kFusedCopyIter>(ca, cid % copy_gx, cid / copy_gx);
+        else
+            segment_update(ca, cid - n_rows);
     }
 }
 
@@ -1210,7 +1224,7 @@ __global__ __launch_bounds__(256) void compact_listed_kernel(CompactArgs a, cons
                                                              const int32_t *__restrict__ flag_count) {
     const int y = blockIdx.y;
     if (y >= a.n_slab) {
-        if (blockIdx.x == 0) segment_update(a, y - a.n_slab);
+        if (blockIdx.x == 0 && blockIdx.z == 0) segment_update(a, y - a.n_slab);
         return;
     }
     const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
@@ -1225,7 +1239,7 @@ __global__ __launch_bounds__(256) void compact_listed_kernel(CompactArgs a, cons
         unsigned char *dst = (kv ? a.store_v : a.store_k) + ((int64_t)l * a.Hkv + g) * a.slab_b + a.dst_off_b +
                              (int64_t)f * a.units_per_frame * sizeof(V);
         const int32_t *src_tok = a.src_tok + (int64_t)f * (a.units_per_frame >> a.log_upr);
-        for (int u0 = threadIdx.x; u0 < a.units_per_frame; u0 += 2 * 256) {
+        for (int u0 = blockIdx.z * (2 * 256) + threadIdx.x; u0 < a.units_per_frame; u0 += gridDim.z * (2 * 256)) {
             V tmp[2];
             int row_tok[2];
 #pragma unroll
@@ -1283,7 +1297,7 @@ static hipError_t launch_freq(const Ctx &c, const ChunkArgs &a, bool listed, R *
     if (c.cfg.freq_axis == MUKV_FREQ_TOKEN) return launch_freq_token<T, R>(c, a, listed, out, st);
     const int P = c.cfg.tokens_per_frame, D = c.cfg.head_dim, Hkv = c.cfg.n_kv_heads;
     const int64_t k_off = (int64_t)c.ls * a.kv_sl;
-    const dim3 grid(listed ? kRescoreSlots : a.n_frames, kFreqBlocksPerFrame);
+    const dim3 grid(listed ? rescore_slots(P, a.n_frames) : a.n_frames, freq_blocks_per_frame(P));
     const int32_t *fl = listed ? c.flag_list[a.parity] : nullptr, *fc = listed ? c.flag_count + a.parity : nullptr;
 #define MUKV_FREQ(DD)                                                                                         \
     hipLaunchKernelGGL((freq_signal_kernel<T, R, DD>), grid, dim3(256), 0, st, a.k, a.map, k_off, a.kv_sh, \
@@ -1355,7 +1369,9 @@ static hipError_t launch_select(const Ctx &c, const ChunkArgs &a, const R *att, 
     s.flag_list = c.flag_list[a.parity];
     s.flag_count = c.flag_count + a.parity;
     s.kept_idx = c.kept_idx;
-    s.src_tok = pass2 ? c.src_tok2 : c.src_tok[a.parity];
+    // with overlap_copy the rows chosen by the fp64 pass replace the marks of the first pass: the
+    // copy, which comes later, then takes every frame in one go
+    s.src_tok = (pass2 && !c.cfg.overlap_copy) ? c.src_tok2 : c.src_tok[a.parity];
     s.rep_frame_k = c.rep_frame_k;
     s.rep_frame_v = c.rep_frame_v;
     s.rep_patch_k = c.rep_patch_k;
@@ -1369,11 +1385,11 @@ static hipError_t launch_select(const Ctx &c, const ChunkArgs &a, const R *att, 
     s.dbg_fft = a.dbg_fft;
     s.dbg_fused = a.dbg_fused;
     s.have_dbg = a.have_dbg;
-    const int gx = pass2 ? kRescoreSlots : a.n_frames;
+    const int gx = pass2 ? rescore_slots(s.P, a.n_frames) : a.n_frames;
     if (s.P > kMaxP) { // a unit of several frames: the keep and the block keys in two launches
         const int n_cg = (s.Hkv * s.D / 2 + 63) / 64;
         hipLaunchKernelGGL((select_large_kernel<R>), dim3(gx), dim3(kUnitThreads), 0, st, s);
-        hipLaunchKernelGGL((pool_large_kernel<T, R>), dim3(gx, n_cg), dim3(256), 0, st, s);
+        hipLaunchKernelGGL((pool_large_kernel<T, R>), dim3(gx, n_cg), dim3(kUnitThreads), 0, st, s);
         return hipGetLastError();
     }
     hipLaunchKernelGGL((select_pool_kernel<T, R>), dim3(gx), dim3(256), 0, st, s);
@@ -1386,7 +1402,7 @@ static int ilog2(int x) {
     return l;
 }
 
-// mode 0: every frame + segment update (no re-scoring); 1: main copy, frames on the re-scoring
+// mode 0: every frame + segment update (no re-scoring, or a copy that comes after it); 1: main copy, frames on the re-scoring
 // list skipped, no segment update; 2: listed frames only (rows from the fp64 pass) + segment update
 constexpr int kCompactIter = 4;
 static void compact_args(const Ctx &c, const ChunkArgs &a, int mode, int iter, CompactArgs &k, int &gx, int &gy) {
@@ -1424,7 +1440,7 @@ static void compact_args(const Ctx &c, const ChunkArgs &a, int mode, int iter, C
     const int n_seg_jobs = (seg_last - k.seg_first + 1) * ((k.C + kSegChan - 1) / kSegChan);
     if (mode == 2) {
         k.bps = 0;
-        gx = kRescoreSlots;
+        gx = rescore_slots(c.cfg.tokens_per_frame, a.n_frames);
         gy = k.n_slab + n_seg_jobs;
         return;
     }
@@ -1442,9 +1458,11 @@ static hipError_t launch_compact(const Ctx &c, const ChunkArgs &a, int mode, hip
     CompactArgs k;
     int gx, gy;
     compact_args(c, a, mode, kCompactIter, k, gx, gy);
-    if (mode == 2)
-        hipLaunchKernelGGL((compact_listed_kernel<u32x4>), dim3(gx, gy), dim3(256), 0, st, k, c.flag_list[a.parity],
-                           c.flag_count + a.parity);
+    if (mode == 2) { // grid.z: a listed frame's rows are shared so that a workgroup makes at most 8 rounds
+        const int gz = (k.units_per_frame + 8 * 512 - 1) / (8 * 512);
+        hipLaunchKernelGGL((compact_listed_kernel<u32x4>), dim3(gx, gy, gz < 64 ? gz : 64), dim3(256), 0, st, k,
+                           c.flag_list[a.parity], c.flag_count + a.parity);
+    }
     else
         hipLaunchKernelGGL((compact_kernel<u32x4, kCompactIter>), dim3(gx, gy), dim3(256), 0, st, k);
     return hipGetLastError();
@@ -1466,8 +1484,9 @@ static hipError_t launch_copy_freq(const Ctx &c, const ChunkArgs &prev, int mode
     fp.P = c.cfg.tokens_per_frame;
     fp.out = c.fft_sig[a.parity];
     fp.n_frames = a.n_frames;
-    fp.n_wg = a.n_frames * kFreqBlocksPerFrame;
-    const int64_t n_copy = (int64_t)gx * gy;
+    fp.bpf = freq_blocks_per_frame(fp.P);
+    fp.n_wg = a.n_frames * fp.bpf;
+    const int64_t n_copy = (int64_t)gx * k.n_slab + (gy - k.n_slab); // row copies, then the segment jobs
     const int64_t total = n_copy + fp.n_wg;
     if (total > 0x7fffffff) return hipErrorInvalidValue;
     const int period = (int)(total / fp.n_wg); // >= 1; frequency workgroups at 0, period, 2*period, ...
@@ -1503,7 +1522,9 @@ static hipError_t wait_side_all(Ctx &c, hipStream_t st) {
 //  - with overlap_copy the keep itself (Eq. 4, top-kappa, block keys), so that the caller's stream
 //    goes straight on to the next batch;
 //  - with re-scoring on, the fp64 chain: frames with a near-tie at the keep boundary are on the
-//    re-scoring list; Eq. 1-4 are redone for them in fp64, the keep repeated and their rows copied.
+//    re-scoring list; Eq. 1-4 are redone for them in fp64 and the keep repeated.  Without
+//    overlap_copy their rows are copied here, beside the main copy that skips them; with it the
+//    copy has not been launched yet and will find the final rows of every frame.
 // ev_join[parity] marks its end.
 template <typename T>
 static hipError_t launch_side(Ctx &c, const ChunkArgs &a, bool with_keep, int n_part) {
@@ -1524,7 +1545,8 @@ static hipError_t launch_side(Ctx &c, const ChunkArgs &a, bool with_keep, int n_
         if (need_fft)
             if ((e = launch_freq<T, double>(c, a, true, c.fft64, c.side)) != hipSuccess) return e;
         if ((e = launch_select<T, double>(c, a, c.att64, n_part64, c.fft64, 1, c.side)) != hipSuccess) return e;
-        if ((e = launch_compact(c, a, 2, c.side)) != hipSuccess) return e;
+        if (!with_keep)
+            if ((e = launch_compact(c, a, 2, c.side)) != hipSuccess) return e;
         // empty the list for the next batch (a one-thread kernel: memset nodes are avoided in graphs)
         hipLaunchKernelGGL(clear_count_kernel, dim3(1), dim3(1), 0, c.side, c.flag_count + a.parity);
         if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -1540,7 +1562,7 @@ static hipError_t launch_deferred_copy(Ctx &c, const ChunkArgs &d, hipStream_t s
     hipError_t e;
     if ((e = wait_side(c, d.parity, st)) != hipSuccess) return e;
     ProfScope ps(c, MUKV_K_COMPACT, st);
-    return launch_compact(c, d, c.margin_thr > 0.0 ? 1 : 0, st);
+    return launch_compact(c, d, 0, st);
 }
 
 // mukv_reset: the copies that were put off are forgotten.  What the side stream still does for
@@ -1592,7 +1614,7 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
         // arithmetic-bound work (the attention kernel streams all the queries and gains nothing
         // beside a copy)
         ProfScope ps(c, MUKV_K_COPY_FREQ, st);
-        if ((e = launch_copy_freq<T>(c, c.deferred[0], rescoring ? 1 : 0, a, st)) != hipSuccess) return e;
+        if ((e = launch_copy_freq<T>(c, c.deferred[0], 0, a, st)) != hipSuccess) return e;
     } else {
         if (have_old)
             if ((e = launch_deferred_copy(c, c.deferred[0], st)) != hipSuccess) return e;
