@@ -447,6 +447,23 @@ class OracleMuKV:
         i sees local row j only if j <= n_l - n_q + i.  Every retrieved row is
         visible.  q [n_q][Hq][D]; k_local, v_local [n_l][Hkv][D] or None.
         Returns float64 [n_q][Hq][D]; all zero for a token that sees no key."""
+        return self._attend(layer, q, frame_idx, k_local, v_local, causal_local)[0]
+
+    def prefill_attend(self, layer, q, frame_idx, k_local, v_local, causal_local=True):
+        """The prefill of new tokens at one layer (Sec. 3.2: the new tokens attend
+        to the past cache and to themselves), which also yields the attention
+        each new token RECEIVES (Sec. 3.3, Eq. 1) with no second pass: the same
+        attention as attend(); the signal of new token j (local row n_l - n_q + j)
+        is the mean over the heads and over the n_q query rows of the softmax
+        weight put on it, the softmax being normalised over everything the query
+        sees, past rows included.  Returns (out [n_q][Hq][D], signal [n_q])."""
+        out, w_local = self._attend(layer, q, frame_idx, k_local, v_local, causal_local)
+        n_q = out.shape[0]
+        return out, w_local[w_local.shape[0] - n_q:] / (self.cfg.n_q_heads * n_q)
+
+    def _attend(self, layer, q, frame_idx, k_local, v_local, causal_local):
+        """Eq. 9 as described in attend(); also returns, per local row, the softmax
+        weight it receives summed over heads and query tokens."""
         c = self.cfg
         sk, sv = self.store() if self.n_frames else (None, None)
         kap, G, D = self.kappa, c.n_q_heads // c.n_kv_heads, c.head_dim
@@ -455,6 +472,7 @@ class OracleMuKV:
         n_l = 0 if k_local is None else k_local.shape[0]
         rows = [r for f in frame_idx if 0 <= f < self.n_frames for r in range(int(f) * kap, (int(f) + 1) * kap)]
         out = np.zeros((n_q, c.n_q_heads, D))
+        received = np.zeros(n_l)
         for h in range(c.n_q_heads):
             g = h // G
             parts_k, parts_v = [], []
@@ -475,8 +493,10 @@ class OracleMuKV:
                 if not np.isfinite(s).any():
                     continue
                 w = np.exp(s - s[np.isfinite(s)].max())
-                out[i, h] = (w / w.sum()) @ vv
-        return out
+                w = w / w.sum()
+                out[i, h] = w @ vv
+                received += w[len(rows):]
+        return out, received
 
     def gather(self, frame_idx, order=TEMPORAL):
         """Concatenate the stored K,V of the selected frames (Sec. 3.5): returns

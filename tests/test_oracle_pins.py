@@ -837,3 +837,70 @@ class TestAttend:
         drop = o.attend(1, q[:, [0, 0, 2, 2]], [2, 6], far, vl)
         np.testing.assert_allclose(drop, o.attend(1, q[:, [0, 0, 2, 2]], [2, 6]), atol=1e-12)
         assert np.abs(with_ctx - ctx_only).max() > 1e-6
+
+
+class TestPrefillAttend:
+    """The prefill of new tokens over [past cache, themselves] that also yields Eq. 1."""
+
+    def _state(self, n_frames=8):
+        cfg = tiny_cfg(frames_per_segment=4)
+        k, v, q = tiny_stream(cfg, n_frames, seed=9)
+        return cfg, run_stream(cfg, k, v, q, 4)
+
+    def test_without_a_past_it_is_the_attention_signal_of_the_frame(self):
+        # no retrieved rows, the local rows are exactly the new tokens: Eq. 1 of one frame, which has its own pins
+        cfg, o = self._state()
+        P = cfg.tokens_per_frame
+        k, v, q = tiny_stream(cfg, 1, seed=31)
+        ql = np.ascontiguousarray(q.transpose(1, 0, 2))                 # [P][Hq][D]
+        kl = np.ascontiguousarray(k[-1].transpose(1, 0, 2))             # [P][Hkv][D]
+        vl = np.ascontiguousarray(v[-1].transpose(1, 0, 2))
+        for causal in (True, False):
+            out, sig = o.prefill_attend(1, ql, [], kl, vl, causal)
+            np.testing.assert_allclose(sig, orc.att_signal(q, k[-1], 1, P, causal)[0], rtol=0, atol=1e-14)
+            np.testing.assert_array_equal(out, o.attend(1, ql, [], kl, vl, causal))
+
+    def test_equal_keys_closed_form_with_a_past(self):
+        # every key the same (retrieved rows replaced by copies would need the store; use older local rows as the
+        # past): query i sees n_old + i + 1 equal keys, so new token j receives sum_{i >= j} 1 / (n_old + i + 1)
+        cfg, o = self._state()
+        n_old, n_q = 5, 4
+        q = rng.standard_normal((n_q, 4, 16)).astype(np.float32)
+        kl = np.repeat(rng.standard_normal((1, 2, 16)).astype(np.float32), n_old + n_q, axis=0)
+        vl = rng.standard_normal((n_old + n_q, 2, 16)).astype(np.float32)
+        _, sig = o.prefill_attend(0, q, [], kl, vl, True)
+        want = [sum(1.0 / (n_old + i + 1) for i in range(j, n_q)) / n_q for j in range(n_q)]
+        np.testing.assert_allclose(sig, want, rtol=0, atol=1e-14)
+
+    def test_what_the_past_absorbs_is_missing_from_the_signal(self):
+        cfg, o = self._state()
+        n_q = 6
+        q = rng.standard_normal((n_q, 4, 16)).astype(np.float32)
+        kl = rng.standard_normal((n_q, 2, 16)).astype(np.float32)
+        vl = rng.standard_normal((n_q, 2, 16)).astype(np.float32)
+        _, alone = o.prefill_attend(1, q, [], kl, vl, True)
+        assert alone.sum() == pytest.approx(1.0, abs=1e-14)            # all of every query's mass lies on new tokens
+        _, with_past = o.prefill_attend(1, q, [2, 5], kl, vl, True)
+        assert 0.0 < with_past.sum() < 1.0 and np.all(with_past <= alone + 1e-15)
+        # the mass on the retrieved rows, recomputed with scipy over the gathered rows
+        from scipy.special import softmax
+        sk, _ = o.store()
+        kap = o.kappa
+        rows = np.r_[2 * kap:3 * kap, 5 * kap:6 * kap]
+        on_new = 0.0
+        for h in range(4):
+            kk = np.concatenate([sk[1, h // 2][rows].astype(np.float64), kl[:, h // 2].astype(np.float64)])
+            for i in range(n_q):
+                s = kk[:len(rows) + i + 1] @ q[i, h].astype(np.float64) / 4.0
+                on_new += softmax(s)[len(rows):].sum()
+        assert with_past.sum() == pytest.approx(on_new / (4 * n_q), abs=1e-13)
+
+    def test_a_new_token_nobody_can_see_receives_nothing_but_its_own_glance(self):
+        # causal: the last new token is seen only by itself
+        cfg, o = self._state()
+        n_q = 3
+        q = np.zeros((n_q, 4, 16), np.float32)                         # zero queries: uniform weights
+        kl = rng.standard_normal((n_q, 2, 16)).astype(np.float32)
+        vl = rng.standard_normal((n_q, 2, 16)).astype(np.float32)
+        _, sig = o.prefill_attend(0, q, [], kl, vl, True)
+        np.testing.assert_allclose(sig, [(1 + 1 / 2 + 1 / 3) / 3, (1 / 2 + 1 / 3) / 3, (1 / 3) / 3], atol=1e-15)
