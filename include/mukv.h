@@ -342,6 +342,37 @@ int mukv_attend(mukv_ctx *ctx, int32_t layer, const void *q, int32_t n_q, const 
                 void *out, void *stream);
 
 /*
+ * The prefill of new tokens at one layer, which also yields the attention the
+ * new tokens receive (Sec. 3.2: each step's tokens attend to the past cache of
+ * their granularity and to themselves; Sec. 3.3, Eq. 1: the compression takes
+ * its attention signal from that prefill at no extra cost).  The attention is
+ * that of mukv_attend -- same arguments, same visibility rules -- for up to
+ * 8192 query tokens per question; the new tokens are the LAST n_q local rows
+ * of the question (local rows before them, if any, are older context).
+ *
+ *   att_signal_out  device float [B][n_q]: for new token j of question b the
+ *                   mean over the Hq heads and the n_q query tokens of the
+ *                   softmax weight put on it, the softmax being normalised over
+ *                   everything the query sees (retrieved rows, older local rows,
+ *                   new tokens).  With B = 1 and n_q = n_frames * P it is the
+ *                   att_signal argument of mukv_compress_chunk (Eq. 4 min-max
+ *                   normalises it per unit, so the common factor is immaterial).
+ *   workspace       device scratch of at least mukv_prefill_workspace_size()
+ *                   bytes, 16-byte aligned, owned by the caller; contents are
+ *                   undefined afterwards.  The call allocates nothing.
+ *
+ * Arithmetic in fp32, sums in a fixed order; `out` is rounded to the payload
+ * dtype.  Errors: INVALID_ARG (null pointers: here the local rows and both
+ * outputs are required), CAPACITY (B > max_questions, workspace too small),
+ * UNSUPPORTED (n_q > 8192, k_frame > 1024, n_q * Hq > 524 280, alignment).
+ */
+int mukv_prefill_workspace_size(const mukv_ctx *ctx, int32_t n_q, int32_t k_frame, int32_t B, int64_t *bytes_out);
+int mukv_prefill_attend(mukv_ctx *ctx, int32_t layer, const void *q, int32_t n_q, const int32_t *frame_idx,
+                        int32_t k_frame, const void *k_local, const void *v_local, const int32_t *local_offsets,
+                        int32_t B, int32_t causal_local, void *out, float *att_signal_out, void *workspace,
+                        int64_t workspace_bytes, void *stream);
+
+/*
  * Snapshot of the cache (the offline memory of Sec. 3.3 is persistent state):
  * the kept K/V rows, kept positions, block keys and running segment sums of
  * the frames ingested so far, in one host buffer, so that a stream can be

@@ -71,7 +71,7 @@ class mukv_profile(C.Structure):
 
 EXPORTS = ("mukv_create", "mukv_destroy", "mukv_reset", "mukv_flush", "mukv_compress_chunk", "mukv_retrieve",
            "mukv_retrieve_patches", "mukv_retrieve_at", "mukv_gather_kv", "mukv_gather_patches", "mukv_gather_union",
-           "mukv_attend", "mukv_snapshot_size", "mukv_snapshot_save", "mukv_snapshot_load", "mukv_profile_begin", "mukv_profile_end",
+           "mukv_attend", "mukv_prefill_workspace_size", "mukv_prefill_attend", "mukv_snapshot_size", "mukv_snapshot_save", "mukv_snapshot_load", "mukv_profile_begin", "mukv_profile_end",
            "mukv_plain_copy", "mukv_get_state", "mukv_strerror")
 
 _lib = None
@@ -100,6 +100,8 @@ def load():
     lib.mukv_retrieve_at.argtypes = [vp, vp, vp, vp, i32, C.POINTER(mukv_retrieve_params), i32, vp, vp, vp, vp, vp]
     lib.mukv_gather_union.argtypes = [vp, vp, i32, vp, i32, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.mukv_attend.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp, vp, i32, i32, vp, vp]
+    lib.mukv_prefill_workspace_size.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_int64)]
+    lib.mukv_prefill_attend.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp, vp, i32, i32, vp, vp, vp, C.c_int64, vp]
     lib.mukv_snapshot_size.argtypes = [vp, C.POINTER(C.c_int64)]
     lib.mukv_snapshot_save.argtypes = [vp, vp, C.c_int64, vp]
     lib.mukv_snapshot_load.argtypes = [vp, vp, C.c_int64, vp]
@@ -182,6 +184,18 @@ def mukv_gather_union(h, seg_ptr, k_seg, frm_ptr, k_frame, pat_ptr, k_patch, B, 
 def mukv_attend(h, layer, q_ptr, n_q, idx_ptr, k_frame, kl_ptr, vl_ptr, loff_ptr, B, causal_local, out_ptr, stream):
     _check(load().mukv_attend(h, layer, q_ptr, n_q, idx_ptr, k_frame, kl_ptr, vl_ptr, loff_ptr, B, causal_local, out_ptr,
                               stream), "mukv_attend")
+
+
+def mukv_prefill_workspace_size(h, n_q, k_frame, B):
+    n = C.c_int64(0)
+    _check(load().mukv_prefill_workspace_size(h, n_q, k_frame, B, C.byref(n)), "mukv_prefill_workspace_size")
+    return n.value
+
+
+def mukv_prefill_attend(h, layer, q_ptr, n_q, idx_ptr, k_frame, kl_ptr, vl_ptr, loff_ptr, B, causal_local, out_ptr, sig_ptr,
+                        ws_ptr, ws_bytes, stream):
+    _check(load().mukv_prefill_attend(h, layer, q_ptr, n_q, idx_ptr, k_frame, kl_ptr, vl_ptr, loff_ptr, B, causal_local,
+                                      out_ptr, sig_ptr, ws_ptr, ws_bytes, stream), "mukv_prefill_attend")
 
 
 def mukv_snapshot_size(h) -> int:
@@ -427,6 +441,25 @@ class MuKV:
                     _ptr(local_offsets), B, int(causal_local), _ptr(out), _stream())
         self._held.clear()
         return out
+
+    def prefill_attend(self, layer, q, frame_idx, k_local, v_local, local_offsets, causal_local=True, out=None,
+                       signal=None, workspace=None):
+        """As attend(), for many new tokens (the last n_q local rows of each question); also returns the
+        attention each new token receives, float32 [B][n_q].  workspace: a uint8 device tensor to reuse."""
+        B, n_q = q.shape[0], q.shape[1]
+        k_frame = 0 if frame_idx is None else frame_idx.shape[1]
+        need = mukv_prefill_workspace_size(self.h, n_q, k_frame, B)
+        if workspace is None or workspace.numel() < need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        if out is None:
+            out = torch.empty_like(q)
+        if signal is None:
+            signal = torch.empty(B, n_q, dtype=torch.float32, device=q.device)
+        mukv_prefill_attend(self.h, layer, _ptr(q), n_q, _ptr(frame_idx), k_frame, _ptr(k_local), _ptr(v_local),
+                            _ptr(local_offsets), B, int(causal_local), _ptr(out), _ptr(signal), _ptr(workspace),
+                            workspace.numel(), _stream())
+        self._held.clear()
+        return out, signal
 
     def gather_kv(self, frame_idx, order=MUKV_TEMPORAL, out=None):
         """frame_idx: int32 [B][k_frame] on the device.  Returns (k_out, v_out,

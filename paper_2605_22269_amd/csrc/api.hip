@@ -600,6 +600,54 @@ int mukv_attend(mukv_ctx *ctx, int32_t layer, const void *q, int32_t n_q, const 
     DeviceScope dev(c.cfg.device_id);
     if (!dev.ok) return MUKV_ERR_HIP;
     return mukv::launch_attend(c, layer, q, n_q, frame_idx, k_frame, k_local, v_local, local_offsets, B, causal_local, out,
+                               nullptr, nullptr, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
+               ? MUKV_OK
+               : MUKV_ERR_HIP;
+}
+
+static int prefill_shape_check(const Ctx &c, int32_t n_q, int32_t k_frame, int32_t B) {
+    if (B < 1 || n_q < 1 || k_frame < 0) return MUKV_ERR_INVALID_ARG;
+    if (B > c.cfg.max_questions) return MUKV_ERR_CAPACITY;
+    if (n_q > mukv::kPrefillMaxTokens || k_frame > mukv::kMaxGatherK) return MUKV_ERR_UNSUPPORTED;
+    // grid limits: (KV head, query tile) pairs along y, one merge workgroup per (question, token, head) along x
+    const int64_t n_qtiles = ((int64_t)n_q * c.group + 7) / 8;
+    if (n_qtiles * c.cfg.n_kv_heads > 65535 || (int64_t)B * n_q * c.cfg.n_q_heads > 0x7fffffff) return MUKV_ERR_UNSUPPORTED;
+    return MUKV_OK;
+}
+
+int mukv_prefill_workspace_size(const mukv_ctx *ctx, int32_t n_q, int32_t k_frame, int32_t B, int64_t *bytes_out) {
+    if (!ctx || !bytes_out) return MUKV_ERR_INVALID_ARG;
+    const int rc = prefill_shape_check(ctx->c, n_q, k_frame, B);
+    if (rc != MUKV_OK) return rc;
+    *bytes_out = mukv::prefill_workspace_bytes(ctx->c, n_q, B, k_frame);
+    return MUKV_OK;
+}
+
+int mukv_prefill_attend(mukv_ctx *ctx, int32_t layer, const void *q, int32_t n_q, const int32_t *frame_idx,
+                        int32_t k_frame, const void *k_local, const void *v_local, const int32_t *local_offsets,
+                        int32_t B, int32_t causal_local, void *out, float *att_signal_out, void *workspace,
+                        int64_t workspace_bytes, void *stream) {
+    if (!ctx || !q || !out || !att_signal_out || !workspace || !k_local || !v_local || !local_offsets)
+        return MUKV_ERR_INVALID_ARG;
+    Ctx &c = ctx->c;
+    if (layer < 0 || layer >= c.cfg.n_layers) return MUKV_ERR_INVALID_ARG;
+    if (causal_local != 0 && causal_local != 1) return MUKV_ERR_INVALID_ARG;
+    if (k_frame > 0 && !frame_idx) return MUKV_ERR_INVALID_ARG;
+    const int rc0 = prefill_shape_check(c, n_q, k_frame, B);
+    if (rc0 != MUKV_OK) return rc0;
+    if (workspace_bytes < mukv::prefill_workspace_bytes(c, n_q, B, k_frame)) return MUKV_ERR_CAPACITY;
+    if ((reinterpret_cast<uintptr_t>(q) & 15) || (reinterpret_cast<uintptr_t>(out) & 15) ||
+        (reinterpret_cast<uintptr_t>(k_local) & 15) || (reinterpret_cast<uintptr_t>(v_local) & 15) ||
+        (reinterpret_cast<uintptr_t>(workspace) & 15))
+        return MUKV_ERR_UNSUPPORTED;
+    {
+        const int rc = flush_pending(c, true, reinterpret_cast<hipStream_t>(stream));
+        if (rc != MUKV_OK) return rc;
+    }
+    DeviceScope dev(c.cfg.device_id);
+    if (!dev.ok) return MUKV_ERR_HIP;
+    return mukv::launch_attend(c, layer, q, n_q, frame_idx, k_frame, k_local, v_local, local_offsets, B, causal_local, out,
+                               att_signal_out, static_cast<float *>(workspace),
                                reinterpret_cast<hipStream_t>(stream)) == hipSuccess
                ? MUKV_OK
                : MUKV_ERR_HIP;

@@ -19,6 +19,13 @@
 // The split's (maximum, normaliser, unnormalised output) per query go to a scratch table;
 // attend_combine_kernel merges the splits and writes the output in the payload type.
 // Everything is summed in a fixed order: the result does not depend on timing.
+//
+// The prefill of new tokens (Sec. 3.2: they attend to the past cache and to themselves) is the same
+// computation with many query tokens, and yields Eq. 1 -- the attention each new token receives --
+// on the way: the merge also writes every query's log-sum-exp; prefill_colsum_kernel recomputes the
+// scores of a tile's queries against the new tokens' keys, turns them into softmax weights with
+// that log-sum-exp and adds them over the tile; prefill_signal_kernel adds the tiles and KV heads in
+// order and divides by Hq * n_q.  Scratch for it comes from the caller (a workspace argument).
 #include <climits>
 
 #include "mukv_internal.h"
@@ -390,8 +397,11 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
 }
 
 // out[b][i][h][:] = sum_s o_s 2^(m_s - m) / sum_s z_s 2^(m_s - m), m = max_s m_s; zero if no split saw a key
+// lse (may be null): log2 of the query's softmax denominator, in the scores' log2 units; +inf for a
+// query that sees no key, so that every weight computed from it is zero.
 template <typename T, int D>
-__global__ void attend_combine_kernel(const float *__restrict__ part, int n_split, T *__restrict__ out) {
+__global__ void attend_combine_kernel(const float *__restrict__ part, int n_split, T *__restrict__ out,
+                                      float *__restrict__ lse) {
     const int64_t row = blockIdx.x;
     const float *p = part + row * n_split * (D + 2);
     float m = -INFINITY;
@@ -407,35 +417,155 @@ __global__ void attend_combine_kernel(const float *__restrict__ part, int n_spli
             }
         }
         store_out(out + row * D + d, zs > 0.f ? os / zs : 0.f);
+        if (lse && d == 0) lse[row] = zs > 0.f ? m + __builtin_amdgcn_logf(zs) : INFINITY;
     }
 }
 
+// Softmax weights of a tile's queries on the new tokens (the last n_q local rows of the question),
+// added over the tile.  Grid (query tile, KV head, question).  The tile's queries sit in LDS as
+// scaled floats; a thread takes new token j, j + 256, ...: its key row against all queries of the tile.
+// colpart [B][Hkv][n_qtiles][n_q].
 template <typename T, int D>
-hipError_t launch_typed(const AttendArgs &a, int B, void *out, hipStream_t st) {
+__global__ __launch_bounds__(kThreads) void prefill_colsum_kernel(AttendArgs a, const float *__restrict__ lse,
+                                                                  float *__restrict__ colpart) {
+    constexpr int E = Row16<T>::E;
+    __shared__ float s_q[kTileQ][D];
+    __shared__ float s_l[kTileQ];
+    __shared__ int s_tok[kTileQ];
+    const int qt = blockIdx.x, g = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int n_queries = a.n_q * a.G;
+    const T *q = static_cast<const T *>(a.q);
+    for (int idx = tid; idx < kTileQ * D; idx += kThreads) {
+        const int n = idx / D, d = idx - n * D;
+        const int qq = qt * kTileQ + n;
+        float x = 0.f;
+        if (qq < n_queries) {
+            const int i = qq / a.G, h = g * a.G + qq % a.G;
+            float one[E];
+            Row16<T>::expand(load16(q + (((int64_t)b * a.n_q + i) * a.Hq + h) * D + (d / E) * E), one);
+            x = one[d % E] * a.scale_log2e;
+        }
+        s_q[n][d] = x;
+    }
+    if (tid < kTileQ) {
+        const int qq = qt * kTileQ + tid;
+        const bool ok = qq < n_queries;
+        const int i = ok ? qq / a.G : 0, h = g * a.G + (ok ? qq % a.G : 0);
+        s_l[tid] = ok ? lse[((int64_t)b * a.n_q + i) * a.Hq + h] : INFINITY;
+        s_tok[tid] = ok ? i : INT_MIN;
+    }
+    __syncthreads();
+    const int l0 = a.local_offsets[b];
+    int n_loc = a.local_offsets[b + 1] - l0;
+    if (n_loc < 0) n_loc = 0;
+    // the last token of the tile: with the causal mask no later new token gets anything from it
+    const int last_q = (qt * kTileQ + kTileQ - 1 < n_queries ? qt * kTileQ + kTileQ - 1 : n_queries - 1) / a.G;
+    const T *lk = static_cast<const T *>(a.k_local);
+    float *dst = colpart + (((int64_t)b * a.Hkv + g) * a.n_qtiles + qt) * a.n_q;
+    for (int j = tid; j < a.n_q; j += kThreads) {
+        const int r = n_loc - a.n_q + j; // local row of new token j
+        float acc = 0.f;
+        if (r >= 0 && !(a.causal && j > last_q)) {
+            const T *kp = lk + ((int64_t)(l0 + r) * a.Hkv + g) * D;
+            float sc[kTileQ];
+#pragma unroll
+            for (int n = 0; n < kTileQ; ++n) sc[n] = 0.f;
+#pragma unroll 4
+            for (int d0 = 0; d0 < D; d0 += E) {
+                float kx[E];
+                Row16<T>::expand(load16(kp + d0), kx);
+#pragma unroll
+                for (int n = 0; n < kTileQ; ++n)
+#pragma unroll
+                    for (int e = 0; e < E; ++e) sc[n] = fmaf(s_q[n][d0 + e], kx[e], sc[n]);
+            }
+#pragma unroll
+            for (int n = 0; n < kTileQ; ++n) { // token i sees new token j iff j <= i (or always, without the mask)
+                const bool sees = a.causal ? s_tok[n] >= j : s_tok[n] >= 0;
+                acc += sees ? __builtin_amdgcn_exp2f(sc[n] - s_l[n]) : 0.f;
+            }
+        }
+        dst[j] = acc;
+    }
+}
+
+// signal[b][j] = (sum over KV heads and query tiles, in that order, of colpart) / (Hq * n_q)
+__global__ __launch_bounds__(kThreads) void prefill_signal_kernel(const float *__restrict__ colpart, int n_terms, int n_q,
+                                                                  float inv, float *__restrict__ signal) {
+    const int b = blockIdx.y, j = blockIdx.x * kThreads + threadIdx.x;
+    if (j >= n_q) return;
+    const float *p = colpart + (int64_t)b * n_terms * n_q + j;
+    float s = 0.f;
+    for (int t = 0; t < n_terms; ++t) s += p[(int64_t)t * n_q];
+    signal[(int64_t)b * n_q + j] = s * inv;
+}
+
+struct PrefillOut { // all null for the plain attention call
+    float *lse, *colpart, *signal;
+};
+
+template <typename T, int D>
+hipError_t launch_typed(const AttendArgs &a, int B, void *out, const PrefillOut &po, hipStream_t st) {
     hipLaunchKernelGGL((attend_partial_kernel<T, D>), dim3(a.n_split, a.Hkv * a.n_qtiles, B), dim3(kThreads), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((attend_combine_kernel<T, D>), dim3((unsigned)(B * a.n_q * a.Hq)), dim3(D < 64 ? 64 : D), 0, st,
-                       a.part, a.n_split, static_cast<T *>(out));
+                       a.part, a.n_split, static_cast<T *>(out), po.lse);
+    if ((e = hipGetLastError()) != hipSuccess || !po.signal) return e;
+    hipLaunchKernelGGL((prefill_colsum_kernel<T, D>), dim3(a.n_qtiles, a.Hkv, B), dim3(kThreads), 0, st, a, po.lse,
+                       po.colpart);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(prefill_signal_kernel, dim3((a.n_q + kThreads - 1) / kThreads, B), dim3(kThreads), 0, st, po.colpart,
+                       a.Hkv * a.n_qtiles, a.n_q, 1.0f / ((float)a.Hq * (float)a.n_q), po.signal);
     return hipGetLastError();
 }
 
 template <typename T>
-hipError_t launch_by_dim(const AttendArgs &a, int D, int B, void *out, hipStream_t st) {
+hipError_t launch_by_dim(const AttendArgs &a, int D, int B, void *out, const PrefillOut &po, hipStream_t st) {
     switch (D) {
-    case 16: return launch_typed<T, 16>(a, B, out, st);
-    case 32: return launch_typed<T, 32>(a, B, out, st);
-    case 64: return launch_typed<T, 64>(a, B, out, st);
-    case 128: return launch_typed<T, 128>(a, B, out, st);
+    case 16: return launch_typed<T, 16>(a, B, out, po, st);
+    case 32: return launch_typed<T, 32>(a, B, out, po, st);
+    case 64: return launch_typed<T, 64>(a, B, out, po, st);
+    case 128: return launch_typed<T, 128>(a, B, out, po, st);
     default: return hipErrorInvalidValue;
     }
 }
 
+int split_count(int B, int Hkv, int n_qtiles, int k_frame, int *frames_per_split) {
+    // about three workgroups per compute unit (what fits at once): a workgroup walks its rows in
+    // dependent batches of loads, so shorter lists finish sooner; at most kAttendMaxSplit splits,
+    // at least one frame each
+    int64_t n_split = (3 * 256 + (int64_t)B * Hkv * n_qtiles - 1) / ((int64_t)B * Hkv * n_qtiles);
+    if (n_split > kAttendMaxSplit) n_split = kAttendMaxSplit;
+    if (n_split > k_frame) n_split = k_frame;
+    if (n_split < 1) n_split = 1;
+    *frames_per_split = k_frame > 0 ? (int)((k_frame + n_split - 1) / n_split) : 0;
+    if (k_frame > 0) n_split = (k_frame + *frames_per_split - 1) / *frames_per_split;
+    return (int)n_split;
+}
+
 } // namespace
 
+// Workspace of the prefill call, in floats: the splits' records, the log-sum-exps, the tiles' column sums.
+static void prefill_layout(const Ctx &c, int n_q, int B, int k_frame, int64_t *part, int64_t *lse, int64_t *colpart) {
+    const int n_qtiles = (n_q * c.group + kTileQ - 1) / kTileQ;
+    int fps;
+    const int n_split = split_count(B, c.cfg.n_kv_heads, n_qtiles, k_frame > 0 ? k_frame : 0, &fps);
+    *part = (int64_t)B * n_q * c.cfg.n_q_heads * n_split * (c.cfg.head_dim + 2);
+    *lse = (int64_t)B * n_q * c.cfg.n_q_heads;
+    *colpart = (int64_t)B * c.cfg.n_kv_heads * n_qtiles * n_q;
+}
+
+int64_t prefill_workspace_bytes(const Ctx &c, int n_q, int B, int k_frame) {
+    int64_t p, l, cp;
+    prefill_layout(c, n_q, B, k_frame, &p, &l, &cp);
+    return (p + l + cp) * (int64_t)sizeof(float);
+}
+
+// workspace == null: the plain attention call, records in the context's scratch, no signal.
 hipError_t launch_attend(const Ctx &c, int layer, const void *q, int n_q, const int32_t *frame_idx, int k_frame,
                          const void *k_local, const void *v_local, const int32_t *local_offsets, int B, int causal,
-                         void *out, hipStream_t st) {
+                         void *out, float *signal, float *workspace, hipStream_t st) {
     AttendArgs a;
     a.q = q;
     a.frame_idx = k_frame > 0 ? frame_idx : nullptr;
@@ -457,18 +587,18 @@ hipError_t launch_attend(const Ctx &c, int layer, const void *q, int n_q, const 
     a.n_qtiles = (n_q * c.group + kTileQ - 1) / kTileQ;
     a.causal = causal;
     a.scale_log2e = 1.4426950408889634f / sqrtf((float)c.cfg.head_dim);
-    // about three workgroups per compute unit (what fits at once): a workgroup walks its rows in
-    // dependent batches of loads, so shorter lists finish sooner; at most kAttendMaxSplit splits,
-    // at least one frame each
-    int n_split = (3 * 256 + B * a.Hkv * a.n_qtiles - 1) / (B * a.Hkv * a.n_qtiles);
-    if (n_split > kAttendMaxSplit) n_split = kAttendMaxSplit;
-    if (n_split > a.k_frame) n_split = a.k_frame;
-    if (n_split < 1) n_split = 1;
-    a.frames_per_split = a.k_frame > 0 ? (a.k_frame + n_split - 1) / n_split : 0;
-    if (a.k_frame > 0) n_split = (a.k_frame + a.frames_per_split - 1) / a.frames_per_split;
-    a.n_split = n_split;
-    return c.cfg.dtype == MUKV_BF16 ? launch_by_dim<uint16_t>(a, c.cfg.head_dim, B, out, st)
-                                    : launch_by_dim<float>(a, c.cfg.head_dim, B, out, st);
+    a.n_split = split_count(B, a.Hkv, a.n_qtiles, a.k_frame, &a.frames_per_split);
+    PrefillOut po{nullptr, nullptr, nullptr};
+    if (workspace) {
+        int64_t p, l, cp;
+        prefill_layout(c, n_q, B, k_frame, &p, &l, &cp);
+        a.part = workspace;
+        po.lse = workspace + p;
+        po.colpart = workspace + p + l;
+        po.signal = signal;
+    }
+    return c.cfg.dtype == MUKV_BF16 ? launch_by_dim<uint16_t>(a, c.cfg.head_dim, B, out, po, st)
+                                    : launch_by_dim<float>(a, c.cfg.head_dim, B, out, po, st);
 }
 
 } // namespace mukv

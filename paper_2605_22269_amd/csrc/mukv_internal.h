@@ -34,6 +34,7 @@ struct ChunkArgs;
 
 constexpr int kAttendMaxTokens = 16; // query tokens per question in one mukv_attend call
 constexpr int kAttendMaxSplit = 8;   // workgroups sharing the frame list of one (question, KV head)
+constexpr int kPrefillMaxTokens = 8192; // new tokens per question in one mukv_prefill_attend call
 
 struct Ctx {
     mukv_config cfg;
@@ -209,7 +210,8 @@ inline hipError_t allow_dynamic_lds(const void *kernel, size_t bytes, int device
 bool att_mfma_supported(const mukv_config &c);
 hipError_t launch_attend(const Ctx &c, int layer, const void *q, int n_q, const int32_t *frame_idx, int k_frame,
                          const void *k_local, const void *v_local, const int32_t *local_offsets, int B, int causal,
-                         void *out, hipStream_t st);
+                         void *out, float *signal, float *workspace, hipStream_t st);
+int64_t prefill_workspace_bytes(const Ctx &c, int n_q, int B, int k_frame);
 
 // LDS bytes the generic attention kernel needs for P tokens of D features when it accumulates
 // in a type of r_size bytes.

@@ -233,5 +233,34 @@ class Pair:
             worst = max(worst, err)
         return worst
 
+    def check_prefill(self, layer, n_q, frame_idx, old_lens, causal=True, seed=0):
+        """Prefill of n_q new tokens per question behind old_lens[b] older local rows, over the kept rows
+        of frame_idx[b]: output and received-attention signal against the oracle.  Returns the GPU's
+        (out, signal) and the largest errors."""
+        w, tol = self.w, TOL[self.w.dtype]
+        B = len(old_lens)
+        g = torch.Generator().manual_seed(seed)
+        q = torch.randn(B, n_q, w.n_q_heads, w.head_dim, generator=g).to(w.torch_dtype)
+        fi = None if frame_idx is None else torch.tensor(frame_idx, dtype=torch.int32, device="cuda")
+        offs = np.zeros(B + 1, np.int32)
+        offs[1:] = np.cumsum([n + n_q for n in old_lens])
+        kl = torch.randn(int(offs[-1]), w.n_kv_heads, w.head_dim, generator=g).to(w.torch_dtype)
+        vl = torch.randn(int(offs[-1]), w.n_kv_heads, w.head_dim, generator=g).to(w.torch_dtype)
+        out, sig = self.gpu.prefill_attend(layer, q.cuda(), fi, kl.cuda(), vl.cuda(), torch.from_numpy(offs).cuda(), causal)
+        torch.cuda.synchronize()
+        got, got_sig = to_f64(np_view(out.cpu())), sig.cpu().numpy().astype(np.float64)
+        worst = worst_sig = 0.0
+        for b in range(B):
+            kb, vb = np_view(kl[offs[b]:offs[b + 1]]), np_view(vl[offs[b]:offs[b + 1]])
+            want, want_sig = self.orc.prefill_attend(layer, np_view(q[b]), [] if frame_idx is None else frame_idx[b], kb, vb,
+                                                     causal)
+            err = float(np.abs(got[b] - want).max()) / max(1.0, float(np.abs(want).max()))
+            assert err <= tol, (b, err)
+            # the signal is fp32 arithmetic on the same payload values on both sides
+            err_sig = float(np.abs(got_sig[b] - want_sig).max())
+            assert err_sig <= 1e-6, (b, err_sig)
+            worst, worst_sig = max(worst, err), max(worst_sig, err_sig)
+        return out, sig, worst, worst_sig
+
     def close(self):
         self.gpu.close()

@@ -936,3 +936,77 @@ def test_large_unit_argument_errors():
     assert e.value.status == mk.MUKV_ERR_UNSUPPORTED
     assert g.state()["n_frames"] == 0
     g.close()
+
+
+# --------------------- prefill of new tokens that also yields Eq. 1 (Sec. 3.2, Sec. 3.3) -----
+@pytest.mark.parametrize("name,frames,kw,n_q,old", [
+    ("tiny", 12, {}, 49, [0, 5]),                       # fp32 payload, one frame of new tokens
+    ("7b", 10, {"n_layers": 2}, 196, [0, 3]),           # bf16, matrix-core scores, G = 7
+    ("72b", 12, {"n_layers": 2}, 2 * 64 + 5, [7]),      # G = 8, ragged
+    ("tiny", 6, {"head_dim": 16, "dtype": "bf16", "n_kv_heads": 2}, 30, [0, 1, 40]),   # bf16 on the VALU path
+])
+def test_prefill_attention_and_received_signal(name, frames, kw, n_q, old):
+    w = W[name].scaled(n_frames=frames, n_questions=len(old), **kw)
+    p = Pair(w, seed=400, chunk=4)
+    p.ingest()
+    p.gpu.flush()
+    fi = [[(3 * b + 1) % frames, -1, (5 * b + 2) % frames] for b in range(len(old))]
+    for causal in (True, False):
+        _, _, e_out, e_sig = p.check_prefill(w.n_layers - 1, n_q, fi, old, causal, seed=401)
+        print(f"{name} n_q={n_q} causal={causal}: out err {e_out:.2e}, signal err {e_sig:.2e}")
+    p.check_prefill(0, n_q, None, old, True, seed=402)   # no past cache at all
+    p.close()
+
+
+def test_prefill_signal_feeds_the_compression():
+    # one stream, chunk by chunk: prefill of the chunk's tokens over frames already in the cache -> its
+    # signal, handed to mukv_compress_chunk.  The oracle is given the same float32 signal, so the keep
+    # must agree bit for bit; the signal itself is checked against the oracle's within 1e-5.
+    w = W["7b"].scaled(n_frames=12, n_layers=2)
+    P, chunk = w.tokens_per_frame, 2
+    p = Pair(w, seed=410, chunk=chunk)
+    ls = w.n_layers - 1
+    for c0 in range(0, w.n_frames, chunk):
+        k, v, q = p.stream.next_chunk(chunk)
+        past = [[f for f in (c0 - 1, c0 - 4) if f >= 0] + [-1] * 2][0][:2]
+        ql = q.transpose(0, 1).contiguous()                       # [n][Hq][D]
+        kl, vl = k[ls].transpose(0, 1).contiguous(), v[ls].transpose(0, 1).contiguous()
+        offs = torch.tensor([0, chunk * P], dtype=torch.int32).cuda()
+        fi = torch.tensor([past], dtype=torch.int32).cuda()
+        _, sig = p.gpu.prefill_attend(ls, ql[None].cuda(), fi, kl.cuda(), vl.cuda(), offs, True)
+        torch.cuda.synchronize()
+        _, want = p.orc.prefill_attend(ls, np_view(ql), past, np_view(kl), np_view(vl), True)
+        assert np.abs(sig[0].cpu().numpy() - want).max() <= 1e-5
+        att = sig.reshape(chunk, P).contiguous()
+        kd, vd = k.cuda(), v.cuda()
+        p.keep_alive += [kd, vd, att]
+        p.sig_orc.append(p.orc.compress_chunk(np_view(k), np_view(v), att=att.cpu().numpy().astype(np.float64)))
+        p.sig_gpu.append(p.gpu.compress_chunk(kd, vd, att_signal=att, want_signals=True))
+    p.check_compress()
+    p.close()
+
+
+def test_prefill_argument_errors():
+    w = W["tiny"].scaled(n_frames=4)
+    p = Pair(w, seed=420, chunk=4)
+    p.ingest()
+    g = p.gpu
+    q = torch.zeros(1, 8, w.n_q_heads, w.head_dim, device="cuda")
+    kl = torch.zeros(8, w.n_kv_heads, w.head_dim, device="cuda")
+    offs = torch.tensor([0, 8], dtype=torch.int32, device="cuda")
+    need = mk.mukv_prefill_workspace_size(g.h, 8, 0, 1)
+    assert need > 0
+    small = torch.empty(need - 4, dtype=torch.uint8, device="cuda")
+    out, sig = torch.empty_like(q), torch.empty(1, 8, device="cuda")
+    with pytest.raises(mk.MuKVError) as e:
+        mk.mukv_prefill_attend(g.h, 0, q.data_ptr(), 8, None, 0, kl.data_ptr(), kl.data_ptr(), offs.data_ptr(), 1, 1,
+                               out.data_ptr(), sig.data_ptr(), small.data_ptr(), small.numel(), None)
+    assert e.value.status == mk.MUKV_ERR_CAPACITY
+    with pytest.raises(mk.MuKVError) as e:      # the new tokens are local rows: they cannot be left out
+        mk.mukv_prefill_attend(g.h, 0, q.data_ptr(), 8, None, 0, None, None, None, 1, 1, out.data_ptr(), sig.data_ptr(),
+                               small.data_ptr(), need, None)
+    assert e.value.status == mk.MUKV_ERR_INVALID_ARG
+    with pytest.raises(mk.MuKVError) as e:
+        mk.mukv_prefill_workspace_size(g.h, 8193, 0, 1)
+    assert e.value.status == mk.MUKV_ERR_UNSUPPORTED
+    p.close()
