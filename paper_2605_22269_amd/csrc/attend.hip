@@ -500,6 +500,283 @@ __global__ __launch_bounds__(kThreads) void prefill_signal_kernel(const float *_
     signal[(int64_t)b * n_q + j] = s * inv;
 }
 
+// ------------------------------------------------------------------------------------------
+// The prefill on the matrix cores (bf16 rows of 128 features): both products of the attention are
+// dense contractions here, 64 queries -- (token, head of the KV group) pairs -- against every row.
+// One workgroup of four waves per (64 queries, KV head, question); rows in steps of 32, staged
+// through LDS (double-buffered, the next step's rows are in flight in registers meanwhile):
+//   scores   wave w owns queries 16w..16w+15: S = Q K^T with v_mfma_f32_16x16x32_bf16, the queries
+//            as the A operand in registers, the keys as the B operand from LDS (a lane: one key row,
+//            8 features).  A lane then holds one key (lane % 16) for four queries (4 * (lane / 16) + r),
+//            so the softmax statistics of a query are reductions over the 16 lanes of a row.
+//            Running maximum and normaliser stay in that wave's registers; the weights go to LDS as
+//            bf16, the factor that rescales what was summed so far as float.
+//   values   wave w owns output features 32w..32w+31 of all 64 queries: O += P V with the weights as
+//            the A operand (a lane: one query, 8 rows) and the values as the B operand (a lane: one
+//            feature, 8 rows, fetched from LDS as eight 2-byte reads).
+// Rows of padded strides 272 B (keys, values) and 80 B (weights) keep the 16-byte operand reads
+// free of bank conflicts.
+// Second loop, Eq. 1: with maximum and normaliser final, the scores against the NEW tokens' keys are
+// formed once more and their softmax weights added over the workgroup's queries: one row of
+// colpart [B][Hkv][query tile][n_q] per workgroup, summed later in a fixed order.
+// ------------------------------------------------------------------------------------------
+constexpr int kFQ = 64, kFK = 32, kFD = 128;
+constexpr int kRowStride = kFD * 2 + 16; // bytes of a staged key / value row
+constexpr int kPStride = kFK * 2 + 16;   // bytes of a row of weights
+
+__global__ __launch_bounds__(256) void prefill_flash_kernel(AttendArgs a, uint16_t *__restrict__ out,
+                                                            float *__restrict__ colpart, int n_tiles) {
+    using T = uint16_t;
+    __shared__ __align__(16) unsigned char s_k[2][kFK * kRowStride];
+    __shared__ __align__(16) unsigned char s_v[2][kFK * kRowStride];
+    __shared__ __align__(16) unsigned char s_p[kFQ * kPStride];
+    __shared__ int s_ft[2][kFK];
+    __shared__ float s_corr[kFQ];
+    __shared__ float s_fin[2][kFQ];
+    __shared__ float s_col[4][kFK];
+    __shared__ int s_frame[kMaxGatherK]; // the question's frames; -1: names no frame of the cache
+    const int qt = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane & 15, lg = lane >> 4;
+    const int n_queries = a.n_q * a.G;
+    const T *q = static_cast<const T *>(a.q);
+    for (int i = tid; i < a.k_frame; i += 256) {
+        const int f = a.frame_idx[(int64_t)b * a.k_frame + i];
+        s_frame[i] = (f >= 0 && f < a.n_frames) ? f : -1;
+    }
+    __syncthreads();
+
+    // the wave's 16 queries as the A operand; token of the four queries this lane holds scores for
+    bf16x8 qa[kFD / 32];
+    {
+        const int qq = qt * kFQ + 16 * wave + lr;
+        const bool ok = qq < n_queries;
+        const int i = ok ? qq / a.G : 0, h = g * a.G + (ok ? qq % a.G : 0);
+        const T *qp = q + (((int64_t)b * a.n_q + i) * a.Hq + h) * kFD + 8 * lg;
+#pragma unroll
+        for (int kk = 0; kk < kFD / 32; ++kk) {
+            raw16 u = load16(qp + 32 * kk);
+            if (!ok) u = raw16{0u, 0u, 0u, 0u};
+            qa[kk] = __builtin_bit_cast(bf16x8, u);
+        }
+    }
+    int tok[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int qq = qt * kFQ + 16 * wave + 4 * lg + r;
+        tok[r] = qq < n_queries ? qq / a.G : INT_MIN;
+    }
+
+    const int n_ret = a.k_frame * a.kappa;
+    const int l0 = a.local_offsets[b];
+    int n_loc = a.local_offsets[b + 1] - l0;
+    if (n_loc < 0) n_loc = 0;
+    const int total = n_ret + n_loc;
+    const T *sk = static_cast<const T *>(a.store_k) + (int64_t)g * a.store_cap * kFD;
+    const T *sv = static_cast<const T *>(a.store_v) + (int64_t)g * a.store_cap * kFD;
+    const T *lk = static_cast<const T *>(a.k_local), *lv = static_cast<const T *>(a.v_local);
+
+    // Row r of [retrieved rows, local rows]: where it lives and the first token that sees it.
+    // A row that lives nowhere reads the slab's first row and is seen by nobody.
+    auto locate = [&](int r, const T **kp, const T **vp) -> int {
+        if (r < n_ret) {
+            const int slot = r / a.kappa;
+            const int f = s_frame[slot];
+            if (f >= 0) {
+                const int64_t row = (int64_t)f * a.kappa + (r - slot * a.kappa);
+                *kp = sk + row * kFD;
+                *vp = sv + row * kFD;
+                return 0;
+            }
+        } else if (r < total) {
+            const int j = r - n_ret;
+            const int64_t off = ((int64_t)(l0 + j) * a.Hkv + g) * kFD;
+            *kp = lk + off;
+            *vp = lv + off;
+            return a.causal ? j - (n_loc - a.n_q) : 0;
+        }
+        *kp = sk;
+        *vp = sv;
+        return INT_MAX;
+    };
+    // staging: thread -> rows tid / 16 and tid / 16 + 16 of the step, 16-byte piece tid % 16
+    const int st_row = tid >> 4, st_piece = tid & 15;
+    // the next step's rows are in flight in registers while a step is computed (a deeper queue of
+    // loads cost occupancy and gained nothing)
+    raw16 pk[2], pv[2];
+    int pft[2];
+    auto fetch = [&](int r0, bool with_v) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const T *kp, *vp;
+            pft[u] = locate(r0 + st_row + 16 * u, &kp, &vp);
+            pk[u] = load16(kp + 8 * st_piece);
+            if (with_v) pv[u] = load16(vp + 8 * st_piece);
+        }
+    };
+    auto put = [&](int buf, bool with_v) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int off = (st_row + 16 * u) * kRowStride + 16 * st_piece;
+            *reinterpret_cast<raw16 *>(s_k[buf] + off) = pk[u];
+            if (with_v) *reinterpret_cast<raw16 *>(s_v[buf] + off) = pv[u];
+            if (st_piece == 0) s_ft[buf][st_row + 16 * u] = pft[u];
+        }
+    };
+    // scores of the wave's queries against the step's 32 rows: sc[kb][r] for key 16 kb + lr, query 4 lg + r
+    auto scores = [&](int buf, f32x4 (&sc)[2]) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            sc[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const unsigned char *kp = s_k[buf] + (16 * kb + lr) * kRowStride + 16 * lg;
+#pragma unroll
+            for (int kk = 0; kk < kFD / 32; ++kk) {
+                const bf16x8 bk = __builtin_bit_cast(bf16x8, *reinterpret_cast<const raw16 *>(kp + 64 * kk));
+                sc[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[kk], bk, sc[kb], 0, 0, 0);
+            }
+        }
+    };
+
+    float m_run[4], l_run[4];
+    f32x4 o[4][2];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        m_run[r] = -INFINITY;
+        l_run[r] = 0.f;
+    }
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb)
+#pragma unroll
+        for (int db = 0; db < 2; ++db) o[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // with the causal mask the rows after the workgroup's last token are seen by none of its queries
+    const int last_q = (qt * kFQ + kFQ - 1 < n_queries ? qt * kFQ + kFQ - 1 : n_queries - 1) / a.G;
+    int n_seen = total;
+    if (a.causal && n_ret + n_loc - a.n_q + last_q + 1 < total) n_seen = n_ret + n_loc - a.n_q + last_q + 1;
+    const int n_steps = n_seen > 0 ? (n_seen + kFK - 1) / kFK : 0;
+    if (n_steps > 0) fetch(0, true);
+    for (int t = 0; t < n_steps; ++t) {
+        const int buf = t & 1;
+        put(buf, true);
+        __syncthreads(); // step t is staged; every wave is done with step t-1
+        if (t + 1 < n_steps) fetch((t + 1) * kFK, true);
+        f32x4 sc[2];
+        scores(buf, sc);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float s0 = tok[r] >= s_ft[buf][lr] ? sc[0][r] * a.scale_log2e : -INFINITY;
+            float s1 = tok[r] >= s_ft[buf][16 + lr] ? sc[1][r] * a.scale_log2e : -INFINITY;
+            const float m_new = fmaxf(m_run[r], row16_max(fmaxf(s0, s1)));
+            const float corr = m_run[r] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run[r] - m_new);
+            const float p0 = s0 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s0 - m_new);
+            const float p1 = s1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s1 - m_new);
+            l_run[r] = l_run[r] * corr + row16_sum(p0 + p1);
+            m_run[r] = m_new;
+            const int qrow = 16 * wave + 4 * lg + r;
+            if (lr == 0) s_corr[qrow] = corr;
+            *reinterpret_cast<uint16_t *>(s_p + qrow * kPStride + 2 * lr) = bf16_round(p0);
+            *reinterpret_cast<uint16_t *>(s_p + qrow * kPStride + 2 * (16 + lr)) = bf16_round(p1);
+        }
+        __syncthreads(); // weights and factors of step t are in LDS
+        bf16x8 bv[2];
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+            const unsigned char *vp = s_v[buf] + (8 * lg) * kRowStride + 2 * (32 * wave + 16 * db + lr);
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t lo = *reinterpret_cast<const uint16_t *>(vp + (2 * e) * kRowStride);
+                const uint32_t hi = *reinterpret_cast<const uint16_t *>(vp + (2 * e + 1) * kRowStride);
+                w[e] = lo | (hi << 16);
+            }
+            bv[db] = __builtin_bit_cast(bf16x8, raw16{w[0], w[1], w[2], w[3]});
+        }
+#pragma unroll
+        for (int qb = 0; qb < 4; ++qb) {
+            const bf16x8 ap = __builtin_bit_cast(bf16x8, *reinterpret_cast<const raw16 *>(s_p + (16 * qb + lr) * kPStride + 16 * lg));
+            float corr[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) corr[r] = s_corr[16 * qb + 4 * lg + r];
+#pragma unroll
+            for (int db = 0; db < 2; ++db) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) o[qb][db][r] *= corr[r];
+                o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap, bv[db], o[qb][db], 0, 0, 0);
+            }
+        }
+    }
+    // ---- final statistics to LDS, output ----
+    __syncthreads();
+    if (lr == 0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            s_fin[0][16 * wave + 4 * lg + r] = m_run[r];
+            s_fin[1][16 * wave + 4 * lg + r] = l_run[r];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int n = 16 * qb + 4 * lg + r;
+            const int qq = qt * kFQ + n;
+            if (qq >= n_queries) continue;
+            const float l = s_fin[1][n];
+            const float inv = l > 0.f ? 1.0f / l : 0.f;
+            const int i = qq / a.G, h = g * a.G + qq % a.G;
+            uint16_t *op = out + (((int64_t)b * a.n_q + i) * a.Hq + h) * kFD + 32 * wave + lr;
+            op[0] = bf16_round(o[qb][0][r] * inv);
+            op[16] = bf16_round(o[qb][1][r] * inv);
+        }
+    }
+    if (!colpart) return;
+
+    // ---- Eq. 1: weights on the new tokens, added over the workgroup's queries ----
+    float lse[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) lse[r] = l_run[r] > 0.f ? m_run[r] + __builtin_amdgcn_logf(l_run[r]) : INFINITY;
+    float *dst = colpart + (((int64_t)b * a.Hkv + g) * n_tiles + qt) * a.n_q;
+    // new token j is local row n_loc - n_q + j, i.e. row r_new0 + j of the row sequence (it may not exist)
+    const int r_new0 = n_ret + n_loc - a.n_q;
+    const int j_end = a.causal ? (last_q + 1 < a.n_q ? last_q + 1 : a.n_q) : a.n_q; // later tokens get nothing from here
+    for (int j = j_end + tid; j < a.n_q; j += 256) dst[j] = 0.f;
+    const int n_steps2 = (j_end + kFK - 1) / kFK;
+    auto fetch_new = [&](int j0) { // rows below n_ret would be retrieved rows: a new token without a row is seen by nobody
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int r = r_new0 + j0 + st_row + 16 * u;
+            const T *kp, *vp;
+            pft[u] = r >= n_ret ? locate(r, &kp, &vp) : (kp = sk, INT_MAX);
+            pk[u] = load16(kp + 8 * st_piece);
+        }
+    };
+    __syncthreads(); // the staging buffers are free again
+    if (n_steps2 > 0) fetch_new(0);
+    for (int t = 0; t < n_steps2; ++t) {
+        const int buf = t & 1;
+        put(buf, false);
+        __syncthreads();
+        if (t + 1 < n_steps2) fetch_new((t + 1) * kFK);
+        f32x4 sc[2];
+        scores(buf, sc);
+        float c0 = 0.f, c1 = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            c0 += tok[r] >= s_ft[buf][lr] ? __builtin_amdgcn_exp2f(sc[0][r] * a.scale_log2e - lse[r]) : 0.f;
+            c1 += tok[r] >= s_ft[buf][16 + lr] ? __builtin_amdgcn_exp2f(sc[1][r] * a.scale_log2e - lse[r]) : 0.f;
+        }
+        c0 = xrow_sum(c0);
+        c1 = xrow_sum(c1);
+        if (lg == 0) {
+            s_col[wave][lr] = c0;
+            s_col[wave][16 + lr] = c1;
+        }
+        __syncthreads();
+        if (tid < kFK && t * kFK + tid < j_end)
+            dst[t * kFK + tid] = (s_col[0][tid] + s_col[1][tid]) + (s_col[2][tid] + s_col[3][tid]);
+    }
+}
+
 struct PrefillOut { // all null for the plain attention call
     float *lse, *colpart, *signal;
 };
@@ -596,6 +873,16 @@ hipError_t launch_attend(const Ctx &c, int layer, const void *q, int n_q, const 
         po.lse = workspace + p;
         po.colpart = workspace + p + l;
         po.signal = signal;
+    }
+    if (workspace && c.cfg.dtype == MUKV_BF16 && c.cfg.head_dim == kFD) { // the prefill on the matrix cores
+        const int n_tiles = (n_q * c.group + kFQ - 1) / kFQ;
+        hipLaunchKernelGGL(prefill_flash_kernel, dim3(n_tiles, a.Hkv, B), dim3(256), 0, st, a, static_cast<uint16_t *>(out),
+                           po.colpart, n_tiles);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(prefill_signal_kernel, dim3((n_q + kThreads - 1) / kThreads, B), dim3(kThreads), 0, st, po.colpart,
+                           a.Hkv * n_tiles, n_q, 1.0f / ((float)a.Hq * (float)n_q), po.signal);
+        return hipGetLastError();
     }
     return c.cfg.dtype == MUKV_BF16 ? launch_by_dim<uint16_t>(a, c.cfg.head_dim, B, out, po, st)
                                     : launch_by_dim<float>(a, c.cfg.head_dim, B, out, po, st);
