@@ -535,6 +535,8 @@ __global__ __launch_bounds__(256) void prefill_flash_kernel(AttendArgs a, uint16
     __shared__ float s_fin[2][kFQ];
     __shared__ float s_col[4][kFK];
     __shared__ int s_frame[kMaxGatherK]; // the question's frames; -1: names no frame of the cache
+    __shared__ int64_t s_toff[2][kFK];   // where the rows of the next two steps live
+    __shared__ int s_tft[2][kFK];
     const int qt = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane & 15, lg = lane >> 4;
     const int n_queries = a.n_q * a.G;
@@ -575,28 +577,27 @@ __global__ __launch_bounds__(256) void prefill_flash_kernel(AttendArgs a, uint16
     const T *sv = static_cast<const T *>(a.store_v) + (int64_t)g * a.store_cap * kFD;
     const T *lk = static_cast<const T *>(a.k_local), *lv = static_cast<const T *>(a.v_local);
 
-    // Row r of [retrieved rows, local rows]: where it lives and the first token that sees it.
-    // A row that lives nowhere reads the slab's first row and is seen by nobody.
-    auto locate = [&](int r, const T **kp, const T **vp) -> int {
-        if (r < n_ret) {
+    // Row r of [retrieved rows, local rows]: where it lives and the first token that sees it, worked out
+    // by one thread per row two steps ahead and handed to the staging threads through a small table.
+    // Entry: element offset in the store slab (>= 0) or ~offset in the local rows (< 0).  A row that
+    // lives nowhere (or below r_min) reads the slab's first row and is seen by nobody.
+    auto tabulate = [&](int set, int r, int r_min) { // threads tid < kFK, r = first row of the step + tid
+        int64_t off = 0;
+        int ft = INT_MAX;
+        if (r >= r_min && r < n_ret) {
             const int slot = r / a.kappa;
             const int f = s_frame[slot];
             if (f >= 0) {
-                const int64_t row = (int64_t)f * a.kappa + (r - slot * a.kappa);
-                *kp = sk + row * kFD;
-                *vp = sv + row * kFD;
-                return 0;
+                off = ((int64_t)f * a.kappa + (r - slot * a.kappa)) * kFD;
+                ft = 0;
             }
-        } else if (r < total) {
+        } else if (r >= r_min && r < total) {
             const int j = r - n_ret;
-            const int64_t off = ((int64_t)(l0 + j) * a.Hkv + g) * kFD;
-            *kp = lk + off;
-            *vp = lv + off;
-            return a.causal ? j - (n_loc - a.n_q) : 0;
+            off = ~(((int64_t)(l0 + j) * a.Hkv + g) * kFD);
+            ft = a.causal ? j - (n_loc - a.n_q) : 0;
         }
-        *kp = sk;
-        *vp = sv;
-        return INT_MAX;
+        s_toff[set][tid] = off;
+        s_tft[set][tid] = ft;
     };
     // staging: thread -> rows tid / 16 and tid / 16 + 16 of the step, 16-byte piece tid % 16
     const int st_row = tid >> 4, st_piece = tid & 15;
@@ -604,13 +605,15 @@ __global__ __launch_bounds__(256) void prefill_flash_kernel(AttendArgs a, uint16
     // loads cost occupancy and gained nothing)
     raw16 pk[2], pv[2];
     int pft[2];
-    auto fetch = [&](int r0, bool with_v) {
+    auto fetch = [&](int set, bool with_v) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const T *kp, *vp;
-            pft[u] = locate(r0 + st_row + 16 * u, &kp, &vp);
-            pk[u] = load16(kp + 8 * st_piece);
-            if (with_v) pv[u] = load16(vp + 8 * st_piece);
+            const int64_t e = s_toff[set][st_row + 16 * u];
+            pft[u] = s_tft[set][st_row + 16 * u];
+            const bool local = e < 0;
+            const int64_t off = (local ? ~e : e) + 8 * st_piece;
+            pk[u] = load16((local ? lk : sk) + off);
+            if (with_v) pv[u] = load16((local ? lv : sv) + off);
         }
     };
     auto put = [&](int buf, bool with_v) {
@@ -653,12 +656,18 @@ __global__ __launch_bounds__(256) void prefill_flash_kernel(AttendArgs a, uint16
     int n_seen = total;
     if (a.causal && n_ret + n_loc - a.n_q + last_q + 1 < total) n_seen = n_ret + n_loc - a.n_q + last_q + 1;
     const int n_steps = n_seen > 0 ? (n_seen + kFK - 1) / kFK : 0;
+    if (tid < kFK) {
+        tabulate(0, tid, 0);
+        tabulate(1, kFK + tid, 0);
+    }
+    __syncthreads();
     if (n_steps > 0) fetch(0, true);
     for (int t = 0; t < n_steps; ++t) {
         const int buf = t & 1;
         put(buf, true);
         __syncthreads(); // step t is staged; every wave is done with step t-1
-        if (t + 1 < n_steps) fetch((t + 1) * kFK, true);
+        if (t + 1 < n_steps) fetch(buf ^ 1, true);
+        if (tid < kFK && t + 2 < n_steps) tabulate(buf, (t + 2) * kFK + tid, 0);
         f32x4 sc[2];
         scores(buf, sc);
 #pragma unroll
@@ -741,22 +750,20 @@ __global__ __launch_bounds__(256) void prefill_flash_kernel(AttendArgs a, uint16
     const int j_end = a.causal ? (last_q + 1 < a.n_q ? last_q + 1 : a.n_q) : a.n_q; // later tokens get nothing from here
     for (int j = j_end + tid; j < a.n_q; j += 256) dst[j] = 0.f;
     const int n_steps2 = (j_end + kFK - 1) / kFK;
-    auto fetch_new = [&](int j0) { // rows below n_ret would be retrieved rows: a new token without a row is seen by nobody
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int r = r_new0 + j0 + st_row + 16 * u;
-            const T *kp, *vp;
-            pft[u] = r >= n_ret ? locate(r, &kp, &vp) : (kp = sk, INT_MAX);
-            pk[u] = load16(kp + 8 * st_piece);
-        }
-    };
-    __syncthreads(); // the staging buffers are free again
-    if (n_steps2 > 0) fetch_new(0);
+    __syncthreads(); // the staging buffers and the row table are free again
+    // rows below n_ret would be retrieved rows: a new token without a row of its own is seen by nobody
+    if (tid < kFK) {
+        tabulate(0, r_new0 + tid, n_ret);
+        tabulate(1, r_new0 + kFK + tid, n_ret);
+    }
+    __syncthreads();
+    if (n_steps2 > 0) fetch(0, false);
     for (int t = 0; t < n_steps2; ++t) {
         const int buf = t & 1;
         put(buf, false);
         __syncthreads();
-        if (t + 1 < n_steps2) fetch_new((t + 1) * kFK);
+        if (t + 1 < n_steps2) fetch(buf ^ 1, false);
+        if (tid < kFK && t + 2 < n_steps2) tabulate(buf, r_new0 + (t + 2) * kFK + tid, n_ret);
         f32x4 sc[2];
         scores(buf, sc);
         float c0 = 0.f, c1 = 0.f;
