@@ -455,6 +455,46 @@ def main():
         seg.close()
         del kb, vb, qb, att_u
 
+    # ---- the step before the path (Sec. 3.2 / Eq. 1): the prefill of a frame's, or a chunk's, new tokens at one
+    # layer over [kept rows of the 32 retrieved frames, the new tokens themselves], which also emits the attention
+    # each new token receives -- the att_signal of mukv_compress_chunk with no second pass over Q and K ----
+    if a.workload == "hour" and not a.frames:
+        res["prefill_attention"] = {"retrieved_rows": w.k_frame * kappa, "layers_timed": 1}
+        for n_new in (1, chunk):
+            n_q = n_new * P
+            q_new = qs[0][:, :n_q].transpose(0, 1).contiguous()[None]          # [1][n_q][Hq][D]
+            k_new = ks[0][L - 1][:, :n_q].transpose(0, 1).contiguous()         # [n_q][Hkv][D]
+            v_new = vs[0][L - 1][:, :n_q].transpose(0, 1).contiguous()
+            lo_new = torch.tensor([0, n_q], dtype=torch.int32, device=dev)
+            ws = torch.empty(mk.mukv_prefill_workspace_size(ctx.h, n_q, w.k_frame, 1), dtype=torch.uint8, device=dev)
+            o_new, s_new = torch.empty_like(q_new), torch.empty(1, n_q, dtype=torch.float32, device=dev)
+
+            def prefill_layer():
+                ctx.prefill_attend(L - 1, q_new, r_out["frame_idx"][:1], k_new, v_new, lo_new, True, out=o_new,
+                                   signal=s_new, workspace=ws)
+
+            prefill_layer()
+            torch.cuda.synchronize()
+            p_us, how = timed(prefill_layer, 10) * 1e3, "eager"
+            if not a.no_graph:
+                try:
+                    pgraph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(pgraph):
+                        for _ in range(8):
+                            prefill_layer()
+                    torch.cuda.synchronize()
+                    pgraph.replay()
+                    p_us, how = timed(pgraph.replay, 10) * 1e3 / 8, "hipgraph (8 calls per replay)"
+                except Exception as e:
+                    print(f"bench.py: capture of the prefill call failed ({e}); eager timing kept", file=sys.stderr)
+            rows_ret = w.k_frame * kappa
+            flop = 2 * 2 * Hq * D * (n_q * rows_ret + n_q * (n_q + 1) / 2)        # QK^T and PV under the causal mask
+            res["prefill_attention"][f"{n_q}_new_tokens"] = {
+                "launch": how, "us_per_layer_call": p_us, "workspace_MB": ws.numel() / 1e6,
+                "roofline": {"bound": "mfma", "achieved": flop / (p_us * 1e-6) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                             "frac": flop / (p_us * 1e-6) / 1e12 / 2500.0, "flop_per_call": flop}}
+            del ws, o_new, s_new, q_new, k_new, v_new
+
     # ---- the attention signal handed over by the caller (the paper takes it from the prefill that
     # produced the KV, "without additional computation"): the same stream, Eq. 1 skipped, Q not read --
     if a.workload == "hour" and not a.frames:

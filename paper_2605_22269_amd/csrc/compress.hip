@@ -1198,13 +1198,16 @@ struct FreqPart {
     int n_wg;     // n_frames * bpf
 };
 
-template <typename T, int D>
+// kUnit: the unit is several frames (P > kMaxP), whose frequency workgroups per unit are a run-time
+// number; a frame's are the constant 7.  (The two cases also show up under their own names in a
+// kernel trace.)
+template <typename T, int D, bool kUnit>
 __global__ __launch_bounds__(256) void copy_freq_kernel(CompactArgs ca, int copy_gx, FreqPart fp, int period) {
     const int b = blockIdx.x;
     const int q = b / period, r = b - q * period;
     if (r == 0 && q < fp.n_wg) {
         freq_body<T, float, D>(fp.k, fp.map, fp.k_off, fp.sh, fp.st, fp.Hkv, fp.P, nullptr, nullptr, fp.out,
-                               q % fp.n_frames, q / fp.n_frames, fp.n_frames, fp.bpf);
+                               q % fp.n_frames, q / fp.n_frames, fp.n_frames, kUnit ? fp.bpf : 7);
     } else {
         const int before = q + (r > 0) < fp.n_wg ? q + (r > 0) : fp.n_wg; // frequency workgroups with a lower number
         const int cid = b - before;
@@ -1490,8 +1493,15 @@ static hipError_t launch_copy_freq(const Ctx &c, const ChunkArgs &prev, int mode
     const int64_t total = n_copy + fp.n_wg;
     if (total > 0x7fffffff) return hipErrorInvalidValue;
     const int period = (int)(total / fp.n_wg); // >= 1; frequency workgroups at 0, period, 2*period, ...
-#define MUKV_COPY_FREQ(DD) \
-    hipLaunchKernelGGL((copy_freq_kernel<T, DD>), dim3((unsigned)total), dim3(256), 0, st, k, gx, fp, period)
+#define MUKV_COPY_FREQ(DD)                                                                                         \
+    do {                                                                                                           \
+        if (fp.P > kMaxP)                                                                                          \
+            hipLaunchKernelGGL((copy_freq_kernel<T, DD, true>), dim3((unsigned)total), dim3(256), 0, st, k, gx, fp, \
+                               period);                                                                            \
+        else                                                                                                       \
+            hipLaunchKernelGGL((copy_freq_kernel<T, DD, false>), dim3((unsigned)total), dim3(256), 0, st, k, gx,   \
+                               fp, period);                                                                        \
+    } while (0)
     switch (c.cfg.head_dim) {
     case 128: MUKV_COPY_FREQ(128); break;
     case 64: MUKV_COPY_FREQ(64); break;

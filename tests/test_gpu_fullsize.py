@@ -169,6 +169,27 @@ def check_decode(w, gpu, ref, hits, layers, n_q=1, n_local=32, seed=0):
     return worst
 
 
+def check_prefill(w, gpu, ref, hits, layer, n_q, n_old=0, seed=0):
+    """The step before the path at full size: the prefill of n_q new tokens of one question over the kept rows
+    of the frames in hits plus n_old older local rows; output and received-attention signal (Eq. 1)."""
+    g = torch.Generator().manual_seed(seed)
+    q = torch.randn(1, n_q, w.n_q_heads, w.head_dim, generator=g).to(w.torch_dtype)
+    kl = torch.randn(n_old + n_q, w.n_kv_heads, w.head_dim, generator=g).to(w.torch_dtype)
+    vl = torch.randn(n_old + n_q, w.n_kv_heads, w.head_dim, generator=g).to(w.torch_dtype)
+    lo = torch.tensor([0, n_old + n_q], dtype=torch.int32).cuda()
+    idx = torch.tensor([list(hits)], dtype=torch.int32, device="cuda")
+    out, sig = gpu.prefill_attend(layer, q.cuda(), idx, kl.cuda(), vl.cuda(), lo, True)
+    torch.cuda.synchronize()
+    got = np_view(out.cpu())
+    got = (got.astype(np.uint32) << 16).view(np.float32).astype(np.float64) if got.dtype == np.uint16 else got.astype(np.float64)
+    want, want_sig = ref.prefill_attend(layer, np_view(q[0]), list(hits), np_view(kl), np_view(vl), True)
+    err = float(np.abs(got[0] - want).max()) / max(1.0, float(np.abs(want).max()))
+    err_sig = float(np.abs(sig[0].cpu().numpy().astype(np.float64) - want_sig).max())
+    assert err <= (2e-2 if w.dtype == "bf16" else 1e-5), err
+    assert err_sig <= 1e-6, err_sig
+    return err, err_sig
+
+
 def test_config2_7b_256_frames():
     w = W["7b"]
     gpu, ref, info = run_full(w, seed=1002)
@@ -176,6 +197,9 @@ def test_config2_7b_256_frames():
     for mode in (mk.MUKV_SEMI, mk.MUKV_HIER, mk.MUKV_PARALLEL):
         hits = check_questions(w, gpu, ref, [synth.random_question(w, w.question_tokens, 77)], mode)
     print("7b: decode attention over the retrieved rows, worst error", check_decode(w, gpu, ref, hits, (0, w.n_layers - 1), seed=5))
+    print("7b: prefill of one frame / of a chunk of 8 frames over the retrieved rows, (output, signal) errors",
+          check_prefill(w, gpu, ref, hits[0], w.n_layers - 1, w.tokens_per_frame, n_old=40, seed=8),
+          check_prefill(w, gpu, ref, hits[0], 0, 8 * w.tokens_per_frame, seed=9))
     gpu.close()
 
 
