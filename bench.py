@@ -496,7 +496,7 @@ def main():
             del ws, o_new, s_new, q_new, k_new, v_new
 
     # ---- the attention signal handed over by the caller (the paper takes it from the prefill that
-    # produced the KV, "without additional computation"): the same stream, Eq. 1 skipped, Q not read --
+    # produced the KV, at no extra cost): the same stream, Eq. 1 skipped, Q not read --
     if a.workload == "hour" and not a.frames:
         ctx.reset()
         att_sigs = []
