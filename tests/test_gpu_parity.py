@@ -549,6 +549,9 @@ def test_seeded_sweep_of_small_shapes(i):
     out, _ = p.check_retrieve(qs, mk.MUKV_SEMI, w.k_seg, w.k_frame, w.lambda_frame)
     idx = [[int(x) for x in row] for row in out["frame_idx"].cpu().numpy()]
     p.check_attend(i % w.n_layers, 1 + i % 5, idx, [1 + i % 5 + (3 * i + b) % 9 for b in range(3)], causal=bool(i % 2), seed=i)
+    # the prefill of a few frames' worth of new tokens over the same retrieved frames, behind 0..8 older rows
+    p.check_prefill((i + 1) % w.n_layers, (1 + i % 3) * w.tokens_per_frame + i % 2, idx, [(5 * i + 3 * b) % 9 for b in range(3)],
+                    causal=bool((i // 2) % 2), seed=900 + i)
     p.close()
 
 
