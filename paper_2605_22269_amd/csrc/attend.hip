@@ -489,15 +489,36 @@ __global__ __launch_bounds__(kThreads) void prefill_colsum_kernel(AttendArgs a, 
     }
 }
 
-// signal[b][j] = (sum over KV heads and query tiles, in that order, of colpart) / (Hq * n_q)
+// signal[b][j] = (sum over KV heads and query tiles of colpart) / (Hq * n_q), in a fixed order: 32 columns
+// per workgroup, the terms of a column split into 8 contiguous runs (one per group of 32 threads, 8 loads
+// in flight), the runs joined in order.
+constexpr int kSigCols = 32, kSigRuns = kThreads / kSigCols;
 __global__ __launch_bounds__(kThreads) void prefill_signal_kernel(const float *__restrict__ colpart, int n_terms, int n_q,
                                                                   float inv, float *__restrict__ signal) {
-    const int b = blockIdx.y, j = blockIdx.x * kThreads + threadIdx.x;
-    if (j >= n_q) return;
-    const float *p = colpart + (int64_t)b * n_terms * n_q + j;
+    __shared__ float s_run[kSigRuns][kSigCols];
+    const int b = blockIdx.y, col = threadIdx.x % kSigCols, run = threadIdx.x / kSigCols;
+    const int j = blockIdx.x * kSigCols + col;
+    const int per = (n_terms + kSigRuns - 1) / kSigRuns;
+    const int t0 = run * per, t1 = t0 + per < n_terms ? t0 + per : n_terms;
     float s = 0.f;
-    for (int t = 0; t < n_terms; ++t) s += p[(int64_t)t * n_q];
-    signal[(int64_t)b * n_q + j] = s * inv;
+    if (j < n_q) {
+        const float *p = colpart + (int64_t)b * n_terms * n_q + j;
+        for (int t = t0; t < t1; t += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)(t + u < t1 ? t + u : t1 - 1) * n_q];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += t + u < t1 ? v[u] : 0.f;
+        }
+    }
+    s_run[run][col] = s;
+    __syncthreads();
+    if (run == 0 && j < n_q) {
+        float tot = s_run[0][col];
+#pragma unroll
+        for (int r = 1; r < kSigRuns; ++r) tot += s_run[r][col];
+        signal[(int64_t)b * n_q + j] = tot * inv;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -799,7 +820,7 @@ hipError_t launch_typed(const AttendArgs &a, int B, void *out, const PrefillOut 
     hipLaunchKernelGGL((prefill_colsum_kernel<T, D>), dim3(a.n_qtiles, a.Hkv, B), dim3(kThreads), 0, st, a, po.lse,
                        po.colpart);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(prefill_signal_kernel, dim3((a.n_q + kThreads - 1) / kThreads, B), dim3(kThreads), 0, st, po.colpart,
+    hipLaunchKernelGGL(prefill_signal_kernel, dim3((a.n_q + kSigCols - 1) / kSigCols, B), dim3(kThreads), 0, st, po.colpart,
                        a.Hkv * a.n_qtiles, a.n_q, 1.0f / ((float)a.Hq * (float)a.n_q), po.signal);
     return hipGetLastError();
 }
@@ -887,7 +908,7 @@ hipError_t launch_attend(const Ctx &c, int layer, const void *q, int n_q, const 
                            po.colpart, n_tiles);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(prefill_signal_kernel, dim3((n_q + kThreads - 1) / kThreads, B), dim3(kThreads), 0, st, po.colpart,
+        hipLaunchKernelGGL(prefill_signal_kernel, dim3((n_q + kSigCols - 1) / kSigCols, B), dim3(kThreads), 0, st, po.colpart,
                            a.Hkv * n_tiles, n_q, 1.0f / ((float)a.Hq * (float)n_q), po.signal);
         return hipGetLastError();
     }
