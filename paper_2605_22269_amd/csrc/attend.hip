@@ -542,10 +542,11 @@ __global__ __launch_bounds__(kThreads) void prefill_signal_kernel(const float *_
 // colpart [B][Hkv][query tile][n_q] per workgroup, summed later in a fixed order.
 // ------------------------------------------------------------------------------------------
 constexpr int kFQ = 64, kFK = 32, kFD = 128;
+constexpr float kHidden = -1e30f, kFloor = -1e20f; // score of a row a query may not see; least running maximum
 constexpr int kRowStride = kFD * 2 + 16; // bytes of a staged key / value row
 constexpr int kPStride = kFK * 2 + 16;   // bytes of a row of weights
 
-__global__ __launch_bounds__(256) void prefill_flash_kernel(AttendArgs a, uint16_t *__restrict__ out,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void prefill_flash_kernel(AttendArgs a, uint16_t *__restrict__ out,
                                                             float *__restrict__ colpart, int n_tiles) {
     using T = uint16_t;
     __shared__ __align__(16) unsigned char s_k[2][kFK * kRowStride];
@@ -553,6 +554,7 @@ __global__ __launch_bounds__(256) void prefill_flash_kernel(AttendArgs a, uint16
     __shared__ __align__(16) unsigned char s_p[kFQ * kPStride];
     __shared__ int s_ft[2][kFK];
     __shared__ float s_corr[kFQ];
+    __shared__ int s_chg[4]; // per block of 16 queries: did a running maximum move in this step
     __shared__ float s_fin[2][kFQ];
     __shared__ float s_col[4][kFK];
     __shared__ int s_frame[kMaxGatherK]; // the question's frames; -1: names no frame of the cache
@@ -664,7 +666,7 @@ __global__ __launch_bounds__(256) void prefill_flash_kernel(AttendArgs a, uint16
     f32x4 o[4][2];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        m_run[r] = -INFINITY;
+        m_run[r] = kFloor;
         l_run[r] = 0.f;
     }
 #pragma unroll
@@ -691,20 +693,31 @@ __global__ __launch_bounds__(256) void prefill_flash_kernel(AttendArgs a, uint16
         if (tid < kFK && t + 2 < n_steps) tabulate(buf, (t + 2) * kFK + tid, 0);
         f32x4 sc[2];
         scores(buf, sc);
+        // Scores stay unscaled (the factor to log2 units sits in the exponent's multiply-add); a row a query
+        // may not see scores kHidden, and running maxima never drop below kFloor: exp2 of the difference is an
+        // exact zero for hidden rows, no select needed, and a query that has seen nothing yet sums zeros.
+        const int ft0 = s_ft[buf][lr], ft1 = s_ft[buf][16 + lr];
+        bool moved = false;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            float s0 = tok[r] >= s_ft[buf][lr] ? sc[0][r] * a.scale_log2e : -INFINITY;
-            float s1 = tok[r] >= s_ft[buf][16 + lr] ? sc[1][r] * a.scale_log2e : -INFINITY;
-            const float m_new = fmaxf(m_run[r], row16_max(fmaxf(s0, s1)));
-            const float corr = m_run[r] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run[r] - m_new);
-            const float p0 = s0 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s0 - m_new);
-            const float p1 = s1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s1 - m_new);
+            const float s0 = tok[r] >= ft0 ? sc[0][r] : kHidden;
+            const float s1 = tok[r] >= ft1 ? sc[1][r] : kHidden;
+            const float m_new = fmaxf(m_run[r], row16_max(fmaxf(s0, s1)) * a.scale_log2e);
+            const float corr = __builtin_amdgcn_exp2f(m_run[r] - m_new);
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(s0, a.scale_log2e, -m_new));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(s1, a.scale_log2e, -m_new));
             l_run[r] = l_run[r] * corr + row16_sum(p0 + p1);
+            moved |= m_new != m_run[r];
             m_run[r] = m_new;
             const int qrow = 16 * wave + 4 * lg + r;
             if (lr == 0) s_corr[qrow] = corr;
             *reinterpret_cast<uint16_t *>(s_p + qrow * kPStride + 2 * lr) = bf16_round(p0);
             *reinterpret_cast<uint16_t *>(s_p + qrow * kPStride + 2 * (16 + lr)) = bf16_round(p1);
+        }
+        // most steps leave the running maxima of the wave's 16 queries where they were: nothing to rescale then
+        {
+            const bool any_moved = __builtin_amdgcn_ballot_w64(moved) != 0;
+            if (lane == 0) s_chg[wave] = any_moved;
         }
         __syncthreads(); // weights and factors of step t are in LDS
         bf16x8 bv[2];
@@ -723,15 +736,17 @@ __global__ __launch_bounds__(256) void prefill_flash_kernel(AttendArgs a, uint16
 #pragma unroll
         for (int qb = 0; qb < 4; ++qb) {
             const bf16x8 ap = __builtin_bit_cast(bf16x8, *reinterpret_cast<const raw16 *>(s_p + (16 * qb + lr) * kPStride + 16 * lg));
-            float corr[4];
+            if (s_chg[qb]) {
+                float corr[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) corr[r] = s_corr[16 * qb + 4 * lg + r];
+                for (int r = 0; r < 4; ++r) corr[r] = s_corr[16 * qb + 4 * lg + r];
 #pragma unroll
-            for (int db = 0; db < 2; ++db) {
+                for (int db = 0; db < 2; ++db)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) o[qb][db][r] *= corr[r];
-                o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap, bv[db], o[qb][db], 0, 0, 0);
+                    for (int r = 0; r < 4; ++r) o[qb][db][r] *= corr[r];
             }
+#pragma unroll
+            for (int db = 0; db < 2; ++db) o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap, bv[db], o[qb][db], 0, 0, 0);
         }
     }
     // ---- final statistics to LDS, output ----
