@@ -1013,3 +1013,77 @@ def test_prefill_argument_errors():
         mk.mukv_prefill_workspace_size(g.h, 8193, 0, 1)
     assert e.value.status == mk.MUKV_ERR_UNSUPPORTED
     p.close()
+
+
+def test_large_units_snapshot_and_graph_replay_with_prefill():
+    # units of 600 tokens: snapshot / restore in the middle of the stream; then the whole step -- reset, chunks with
+    # the signal handed over (batched, copy put off, every unit re-scored), retrieval, prefill attention over
+    # the retrieved units -- captured once and replayed with other work in between
+    w = _unit_workload("bf16", 600, 3, 0.4, 0.7, 8, head_dim=128, n_kv_heads=2, n_q_heads=4)
+    kw = {"batch_chunks": 2, "overlap_copy": 1, "refine_margin": 10.0}
+    p = Pair(w, seed=340, chunk=2, with_q=False, gpu_kw=kw)
+    p.ingest(4, att_seed=7340)
+    snap = p.gpu.snapshot()
+    other = gpu_context(w, max_frames=8, max_chunk_frames=2, **kw)
+    other.restore(snap)
+    assert torch.equal(other.snapshot(), snap)
+    p.gpu.close()
+    p.gpu = other
+    p.ingest(4, att_seed=7340)
+    p.check_compress()
+
+    P = w.tokens_per_frame
+    chunks = []
+    st2 = synth.SynthStream(w, 340, device="cpu", with_q=False)      # the same stream again, for the captured step
+    for c in range(4):
+        k, v, _ = st2.next_chunk(2)
+        att = synth.handed_over_attention(2, P, 7340 + 2 * c)
+        chunks.append((k.cuda(), v.cuda(), att.cuda()))
+    qt = synth.random_question(w, 9, 345)
+    qd, offs = qt.cuda(), torch.tensor([0, 9], dtype=torch.int32, device="cuda")
+    r_out = {"seg_idx": torch.empty(1, 1, dtype=torch.int32, device="cuda"), "seg_score": torch.empty(1, 1, device="cuda"),
+             "frame_idx": torch.empty(1, 2, dtype=torch.int32, device="cuda"), "frame_score": torch.empty(1, 2, device="cuda")}
+    gen = torch.Generator().manual_seed(346)
+    n_q = 70
+    q_new = torch.randn(1, n_q, w.n_q_heads, w.head_dim, generator=gen).to(w.torch_dtype)
+    k_loc = torch.randn(n_q + 3, w.n_kv_heads, w.head_dim, generator=gen).to(w.torch_dtype)
+    v_loc = torch.randn(n_q + 3, w.n_kv_heads, w.head_dim, generator=gen).to(w.torch_dtype)
+    q_d, k_d, v_d = q_new.cuda(), k_loc.cuda(), v_loc.cuda()
+    l_off = torch.tensor([0, n_q + 3], dtype=torch.int32, device="cuda")
+    ws = torch.empty(mk.mukv_prefill_workspace_size(p.gpu.h, n_q, 2, 1), dtype=torch.uint8, device="cuda")
+    o_out, s_out = torch.empty_like(q_d), torch.empty(1, n_q, device="cuda")
+
+    def step():
+        p.gpu.reset()
+        for k, v, att in chunks:
+            p.gpu.compress_chunk(k, v, None, att_signal=att)
+        p.gpu.retrieve(qd, offs, mode=mk.MUKV_SEMI, k_seg=1, k_frame=2, lambda_frame=0.3, out=r_out)
+        p.gpu.prefill_attend(1, q_d, r_out["frame_idx"], k_d, v_d, l_off, True, out=o_out, signal=s_out, workspace=ws)
+
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    want = p.orc.retrieve(np_view(qt), orc.RetrieveParams(orc.SEMI, 1, 2, 0.3))
+    o_want, s_want = p.orc.prefill_attend(1, np_view(q_new[0]), want["frame_idx"], np_view(k_loc), np_view(v_loc), True)
+    for replay in range(3):
+        p.gpu.reset()                                 # eager work between the replays: as many frames (the frame
+        for c in (3, 1, 0, 2):                        # count lives on the host), other contents
+            p.gpu.compress_chunk(*chunks[c][:2], None, att_signal=chunks[(c + 1) % 4][2])
+        p.gpu.flush()
+        o_out.zero_()
+        s_out.fill_(-1)
+        r_out["frame_idx"].fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        st = p.gpu.state()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(st["kept_idx"].cpu().numpy(), p.orc.kept, err_msg=f"replay {replay}")
+        assert int(st["refined"].sum()) == 8
+        np.testing.assert_array_equal(r_out["frame_idx"][0].cpu().numpy(), want["frame_idx"])
+        assert np.abs(to_f64(np_view(o_out[0].cpu())) - o_want).max() <= 2e-2 * max(1.0, np.abs(o_want).max())
+        assert np.abs(s_out[0].cpu().numpy() - s_want).max() <= 1e-6
+    p.close()
