@@ -112,6 +112,10 @@ __device__ __forceinline__ void store_out(float *p, float x) { *p = x; }
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) {
@@ -526,12 +530,13 @@ __global__ __launch_bounds__(kThreads) void prefill_signal_kernel(const float *_
 // dense contractions here, 64 queries -- (token, head of the KV group) pairs -- against every row.
 // One workgroup of four waves per (64 queries, KV head, question); rows in steps of 32, staged
 // through LDS (double-buffered, the next step's rows are in flight in registers meanwhile):
-//   scores   wave w owns queries 16w..16w+15: S = Q K^T with v_mfma_f32_16x16x32_bf16, the queries
-//            as the A operand in registers, the keys as the B operand from LDS (a lane: one key row,
-//            8 features).  A lane then holds one key (lane % 16) for four queries (4 * (lane / 16) + r),
-//            so the softmax statistics of a query are reductions over the 16 lanes of a row.
+//   scores   wave w owns queries 16w..16w+15: S^T = K Q^T with v_mfma_f32_16x16x32_bf16, the keys as
+//            the A operand from LDS (a lane: one key row, 8 features), the queries as the B operand in
+//            registers.  A lane then holds ONE query (lane % 16) and eight rows of the step
+//            (16 kb + 4 * (lane / 16) + r), so the softmax statistics of a query are mostly in-lane
+//            work, joined over the four lanes that share the query by two register swaps.
 //            Running maximum and normaliser stay in that wave's registers; the weights go to LDS as
-//            bf16, the factor that rescales what was summed so far as float.
+//            bf16 (four of a query at a time), the factor that rescales what was summed so far as float.
 //   values   wave w owns output features 32w..32w+31 of all 64 queries: O += P V with the weights as
 //            the A operand (a lane: one query, 8 rows) and the values as the B operand (a lane: one
 //            feature, 8 rows, fetched from LDS as eight 2-byte reads).
@@ -552,7 +557,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     __shared__ __align__(16) unsigned char s_k[2][kFK * kRowStride];
     __shared__ __align__(16) unsigned char s_v[2][kFK * kRowStride];
     __shared__ __align__(16) unsigned char s_p[kFQ * kPStride];
-    __shared__ int s_ft[2][kFK];
+    __shared__ __align__(16) int s_ft[2][kFK];
     __shared__ float s_corr[kFQ];
     __shared__ int s_chg[4]; // per block of 16 queries: did a running maximum move in this step
     __shared__ float s_fin[2][kFQ];
@@ -584,12 +589,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             qa[kk] = __builtin_bit_cast(bf16x8, u);
         }
     }
-    int tok[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int qq = qt * kFQ + 16 * wave + 4 * lg + r;
-        tok[r] = qq < n_queries ? qq / a.G : INT_MIN;
-    }
+    // token of the query this lane holds scores for (nothing is visible to a query that does not exist)
+    const int tokq = qt * kFQ + 16 * wave + lr < n_queries ? (qt * kFQ + 16 * wave + lr) / a.G : INT_MIN;
 
     const int n_ret = a.k_frame * a.kappa;
     const int l0 = a.local_offsets[b];
@@ -648,7 +649,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             if (st_piece == 0) s_ft[buf][st_row + 16 * u] = pft[u];
         }
     };
-    // scores of the wave's queries against the step's 32 rows: sc[kb][r] for key 16 kb + lr, query 4 lg + r
+    // scores of the wave's queries against the step's 32 rows: sc[kb][r] for row 16 kb + 4 lg + r, query lr
     auto scores = [&](int buf, f32x4 (&sc)[2]) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
@@ -657,18 +658,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 #pragma unroll
             for (int kk = 0; kk < kFD / 32; ++kk) {
                 const bf16x8 bk = __builtin_bit_cast(bf16x8, *reinterpret_cast<const raw16 *>(kp + 64 * kk));
-                sc[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[kk], bk, sc[kb], 0, 0, 0);
+                sc[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bk, qa[kk], sc[kb], 0, 0, 0);
             }
         }
     };
 
-    float m_run[4], l_run[4];
+    float m_run = kFloor, l_run = 0.f; // of query 16 * wave + lr
     f32x4 o[4][2];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        m_run[r] = kFloor;
-        l_run[r] = 0.f;
-    }
 #pragma unroll
     for (int qb = 0; qb < 4; ++qb)
 #pragma unroll
@@ -696,23 +692,36 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         // Scores stay unscaled (the factor to log2 units sits in the exponent's multiply-add); a row a query
         // may not see scores kHidden, and running maxima never drop below kFloor: exp2 of the difference is an
         // exact zero for hidden rows, no select needed, and a query that has seen nothing yet sums zeros.
-        const int ft0 = s_ft[buf][lr], ft1 = s_ft[buf][16 + lr];
-        bool moved = false;
+        float sv[8];
+        {
+            const i32x4 f0 = *reinterpret_cast<const i32x4 *>(&s_ft[buf][4 * lg]);
+            const i32x4 f1 = *reinterpret_cast<const i32x4 *>(&s_ft[buf][16 + 4 * lg]);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float s0 = tok[r] >= ft0 ? sc[0][r] : kHidden;
-            const float s1 = tok[r] >= ft1 ? sc[1][r] : kHidden;
-            const float m_new = fmaxf(m_run[r], row16_max(fmaxf(s0, s1)) * a.scale_log2e);
-            const float corr = __builtin_amdgcn_exp2f(m_run[r] - m_new);
-            const float p0 = __builtin_amdgcn_exp2f(fmaf(s0, a.scale_log2e, -m_new));
-            const float p1 = __builtin_amdgcn_exp2f(fmaf(s1, a.scale_log2e, -m_new));
-            l_run[r] = l_run[r] * corr + row16_sum(p0 + p1);
-            moved |= m_new != m_run[r];
-            m_run[r] = m_new;
-            const int qrow = 16 * wave + 4 * lg + r;
-            if (lr == 0) s_corr[qrow] = corr;
-            *reinterpret_cast<uint16_t *>(s_p + qrow * kPStride + 2 * lr) = bf16_round(p0);
-            *reinterpret_cast<uint16_t *>(s_p + qrow * kPStride + 2 * (16 + lr)) = bf16_round(p1);
+            for (int r = 0; r < 4; ++r) {
+                sv[r] = tokq >= f0[r] ? sc[0][r] : kHidden;
+                sv[4 + r] = tokq >= f1[r] ? sc[1][r] : kHidden;
+            }
+        }
+        float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+        const float m_new = fmaxf(m_run, xrow_max(mx) * a.scale_log2e);
+        const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+        float pw[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pw[i] = __builtin_amdgcn_exp2f(fmaf(sv[i], a.scale_log2e, -m_new));
+        l_run = l_run * corr + xrow_sum(((pw[0] + pw[1]) + (pw[2] + pw[3])) + ((pw[4] + pw[5]) + (pw[6] + pw[7])));
+        const bool moved = m_new != m_run;
+        m_run = m_new;
+        {
+            const int qrow = 16 * wave + lr;
+            if (lg == 0) s_corr[qrow] = corr;
+            // rows 4 lg .. 4 lg + 3 and 16 + 4 lg .. of the query's weights, rounded to bf16 two at a time
+            u32x2 w0, w1;
+            w0[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pw[0], pw[1]}, bf16x2));
+            w0[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pw[2], pw[3]}, bf16x2));
+            w1[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pw[4], pw[5]}, bf16x2));
+            w1[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pw[6], pw[7]}, bf16x2));
+            *reinterpret_cast<u32x2 *>(s_p + qrow * kPStride + 8 * lg) = w0;
+            *reinterpret_cast<u32x2 *>(s_p + qrow * kPStride + 32 + 8 * lg) = w1;
         }
         // most steps leave the running maxima of the wave's 16 queries where they were: nothing to rescale then
         {
@@ -751,12 +760,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     }
     // ---- final statistics to LDS, output ----
     __syncthreads();
-    if (lr == 0) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            s_fin[0][16 * wave + 4 * lg + r] = m_run[r];
-            s_fin[1][16 * wave + 4 * lg + r] = l_run[r];
-        }
+    if (lg == 0) {
+        s_fin[0][16 * wave + lr] = m_run;
+        s_fin[1][16 * wave + lr] = l_run;
     }
     __syncthreads();
 #pragma unroll
@@ -777,9 +783,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     if (!colpart) return;
 
     // ---- Eq. 1: weights on the new tokens, added over the workgroup's queries ----
-    float lse[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) lse[r] = l_run[r] > 0.f ? m_run[r] + __builtin_amdgcn_logf(l_run[r]) : INFINITY;
+    const float lse = l_run > 0.f ? m_run + __builtin_amdgcn_logf(l_run) : INFINITY; // of query 16 * wave + lr
     float *dst = colpart + (((int64_t)b * a.Hkv + g) * n_tiles + qt) * a.n_q;
     // new token j is local row n_loc - n_q + j, i.e. row r_new0 + j of the row sequence (it may not exist)
     const int r_new0 = n_ret + n_loc - a.n_q;
@@ -802,17 +806,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         if (tid < kFK && t + 2 < n_steps2) tabulate(buf, r_new0 + (t + 2) * kFK + tid, n_ret);
         f32x4 sc[2];
         scores(buf, sc);
-        float c0 = 0.f, c1 = 0.f;
+        {   // the lane's weights on rows 16 kb + 4 lg + r, added over the 16 queries of the wave (the lanes of a row)
+            const i32x4 f0 = *reinterpret_cast<const i32x4 *>(&s_ft[buf][4 * lg]);
+            const i32x4 f1 = *reinterpret_cast<const i32x4 *>(&s_ft[buf][16 + 4 * lg]);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            c0 += tok[r] >= s_ft[buf][lr] ? __builtin_amdgcn_exp2f(sc[0][r] * a.scale_log2e - lse[r]) : 0.f;
-            c1 += tok[r] >= s_ft[buf][16 + lr] ? __builtin_amdgcn_exp2f(sc[1][r] * a.scale_log2e - lse[r]) : 0.f;
-        }
-        c0 = xrow_sum(c0);
-        c1 = xrow_sum(c1);
-        if (lg == 0) {
-            s_col[wave][lr] = c0;
-            s_col[wave][16 + lr] = c1;
+            for (int r = 0; r < 4; ++r) {
+                float c0 = tokq >= f0[r] ? __builtin_amdgcn_exp2f(fmaf(sc[0][r], a.scale_log2e, -lse)) : 0.f;
+                float c1 = tokq >= f1[r] ? __builtin_amdgcn_exp2f(fmaf(sc[1][r], a.scale_log2e, -lse)) : 0.f;
+                c0 = row16_sum(c0);
+                c1 = row16_sum(c1);
+                if (lr == 0) {
+                    s_col[wave][4 * lg + r] = c0;
+                    s_col[wave][16 + 4 * lg + r] = c1;
+                }
+            }
         }
         __syncthreads();
         if (tid < kFK && t * kFK + tid < j_end)
