@@ -348,7 +348,10 @@ int mukv_attend(mukv_ctx *ctx, int32_t layer, const void *q, int32_t n_q, const 
  * its attention signal from that prefill at no extra cost).  The attention is
  * that of mukv_attend -- same arguments, same visibility rules -- for up to
  * 8192 query tokens per question; the new tokens are the LAST n_q local rows
- * of the question (local rows before them, if any, are older context).
+ * of the question (local rows before them, if any, are older context).  A
+ * question should own at least n_q local rows; new tokens without a row of
+ * their own (fewer local rows than n_q) receive a signal of zero and are
+ * attended to by nobody.
  *
  *   att_signal_out  device float [B][n_q]: for new token j of question b the
  *                   mean over the Hq heads and the n_q query tokens of the
