@@ -1087,3 +1087,29 @@ def test_large_units_snapshot_and_graph_replay_with_prefill():
         assert np.abs(to_f64(np_view(o_out[0].cpu())) - o_want).max() <= 2e-2 * max(1.0, np.abs(o_want).max())
         assert np.abs(s_out[0].cpu().numpy() - s_want).max() <= 1e-6
     p.close()
+
+
+@pytest.mark.parametrize("name,kw", [("7b", {"n_layers": 2}), ("tiny", {})])
+def test_prefill_with_fewer_local_rows_than_new_tokens(name, kw):
+    # 20 query tokens but only 12 local rows: the first 8 tokens have no row of their own -- they see the
+    # retrieved rows only (the oracle's attention without local rows) and receive no attention
+    w = W[name].scaled(n_frames=8, **kw)
+    p = Pair(w, seed=430, chunk=4)
+    p.ingest()
+    gen = torch.Generator().manual_seed(431)
+    q = torch.randn(1, 20, w.n_q_heads, w.head_dim, generator=gen).to(w.torch_dtype)
+    kl = torch.randn(12, w.n_kv_heads, w.head_dim, generator=gen).to(w.torch_dtype)
+    vl = torch.randn(12, w.n_kv_heads, w.head_dim, generator=gen).to(w.torch_dtype)
+    fi = torch.tensor([[5, 1]], dtype=torch.int32, device="cuda")
+    out, sig = p.gpu.prefill_attend(0, q.cuda(), fi, kl.cuda(), vl.cuda(), torch.tensor([0, 12], dtype=torch.int32).cuda(), True)
+    torch.cuda.synchronize()
+    sig = sig[0].cpu().numpy()
+    assert np.all(sig[:8] == 0.0) and np.all(sig[8:] > 0.0)
+    got = to_f64(np_view(out[0].cpu()))
+    want = p.orc.attend(0, np_view(q[0, :8]), [5, 1])
+    assert np.abs(got[:8] - want).max() <= mk_tol(w) * max(1.0, np.abs(want).max())
+    # the last 12 tokens are an ordinary prefill of 12 tokens
+    want12, sig12 = p.orc.prefill_attend(0, np_view(q[0, 8:]), [5, 1], np_view(kl), np_view(vl), True)
+    assert np.abs(got[8:] - want12).max() <= mk_tol(w) * max(1.0, np.abs(want12).max())
+    assert np.abs(sig[8:] * 20 / 12 - sig12).max() <= 1e-6      # the mean runs over the 20 query rows of the call
+    p.close()
