@@ -546,20 +546,25 @@ __global__ __launch_bounds__(kThreads) void prefill_signal_kernel(const float *_
 // formed once more and their softmax weights added over the workgroup's queries: one row of
 // colpart [B][Hkv][query tile][n_q] per workgroup, summed later in a fixed order.
 // ------------------------------------------------------------------------------------------
-constexpr int kFQ = 64, kFK = 32, kFD = 128;
+constexpr int kFK = 32, kFD = 128;
 constexpr float kHidden = -1e30f, kFloor = -1e20f; // score of a row a query may not see; least running maximum
 constexpr int kRowStride = kFD * 2 + 16; // bytes of a staged key / value row
 constexpr int kPStride = kFK * 2 + 16;   // bytes of a row of weights
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void prefill_flash_kernel(AttendArgs a, uint16_t *__restrict__ out,
-                                                            float *__restrict__ colpart, int n_tiles) {
+// QB: blocks of 16 queries per wave (64 * QB queries per workgroup).  With two blocks a key or value
+// operand fetched from LDS serves twice the matrix instructions; with one there are twice the
+// workgroups, which is what a short prefill needs.
+template <int QB>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QB == 1 ? 3 : 2, QB == 1 ? 3 : 2))) void prefill_flash_kernel(
+    AttendArgs a, uint16_t *__restrict__ out, float *__restrict__ colpart, int n_tiles) {
     using T = uint16_t;
+    constexpr int kFQ = 64 * QB, NQB = 4 * QB; // queries, blocks of 16 queries per workgroup
     __shared__ __align__(16) unsigned char s_k[2][kFK * kRowStride];
     __shared__ __align__(16) unsigned char s_v[2][kFK * kRowStride];
     __shared__ __align__(16) unsigned char s_p[kFQ * kPStride];
     __shared__ __align__(16) int s_ft[2][kFK];
     __shared__ float s_corr[kFQ];
-    __shared__ int s_chg[4]; // per block of 16 queries: did a running maximum move in this step
+    __shared__ int s_chg[NQB]; // per block of 16 queries: did a running maximum move in this step
     __shared__ float s_fin[2][kFQ];
     __shared__ float s_col[4][kFK];
     __shared__ int s_frame[kMaxGatherK]; // the question's frames; -1: names no frame of the cache
@@ -576,21 +581,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     __syncthreads();
 
     // the wave's 16 queries as the A operand; token of the four queries this lane holds scores for
-    bf16x8 qa[kFD / 32];
-    {
-        const int qq = qt * kFQ + 16 * wave + lr;
+    // the wave's blocks are QB * wave + i; block n holds queries 16 n .. 16 n + 15 of the tile
+    bf16x8 qa[QB][kFD / 32];
+    int tokq[QB]; // token of the query this lane holds scores for (nothing is visible to a query that does not exist)
+#pragma unroll
+    for (int i = 0; i < QB; ++i) {
+        const int qq = qt * kFQ + 16 * (QB * wave + i) + lr;
         const bool ok = qq < n_queries;
-        const int i = ok ? qq / a.G : 0, h = g * a.G + (ok ? qq % a.G : 0);
-        const T *qp = q + (((int64_t)b * a.n_q + i) * a.Hq + h) * kFD + 8 * lg;
+        const int ti = ok ? qq / a.G : 0, h = g * a.G + (ok ? qq % a.G : 0);
+        const T *qp = q + (((int64_t)b * a.n_q + ti) * a.Hq + h) * kFD + 8 * lg;
 #pragma unroll
         for (int kk = 0; kk < kFD / 32; ++kk) {
             raw16 u = load16(qp + 32 * kk);
             if (!ok) u = raw16{0u, 0u, 0u, 0u};
-            qa[kk] = __builtin_bit_cast(bf16x8, u);
+            qa[i][kk] = __builtin_bit_cast(bf16x8, u);
         }
+        tokq[i] = ok ? ti : INT_MIN;
     }
-    // token of the query this lane holds scores for (nothing is visible to a query that does not exist)
-    const int tokq = qt * kFQ + 16 * wave + lr < n_queries ? (qt * kFQ + 16 * wave + lr) / a.G : INT_MIN;
 
     const int n_ret = a.k_frame * a.kappa;
     const int l0 = a.local_offsets[b];
@@ -649,24 +656,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             if (st_piece == 0) s_ft[buf][st_row + 16 * u] = pft[u];
         }
     };
-    // scores of the wave's queries against the step's 32 rows: sc[kb][r] for row 16 kb + 4 lg + r, query lr
-    auto scores = [&](int buf, f32x4 (&sc)[2]) {
+    // scores of the wave's queries against the step's 32 rows: sc[i][kb][r] for row 16 kb + 4 lg + r, query lr of block i
+    auto scores = [&](int buf, f32x4 (&sc)[QB][2]) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
-            sc[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < QB; ++i) sc[i][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
             const unsigned char *kp = s_k[buf] + (16 * kb + lr) * kRowStride + 16 * lg;
 #pragma unroll
             for (int kk = 0; kk < kFD / 32; ++kk) {
                 const bf16x8 bk = __builtin_bit_cast(bf16x8, *reinterpret_cast<const raw16 *>(kp + 64 * kk));
-                sc[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bk, qa[kk], sc[kb], 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < QB; ++i) sc[i][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bk, qa[i][kk], sc[i][kb], 0, 0, 0);
             }
         }
     };
 
-    float m_run = kFloor, l_run = 0.f; // of query 16 * wave + lr
-    f32x4 o[4][2];
+    float m_run[QB], l_run[QB]; // of query lr of the wave's blocks
 #pragma unroll
-    for (int qb = 0; qb < 4; ++qb)
+    for (int i = 0; i < QB; ++i) {
+        m_run[i] = kFloor;
+        l_run[i] = 0.f;
+    }
+    f32x4 o[NQB][2];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
         for (int db = 0; db < 2; ++db) o[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -687,32 +701,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         __syncthreads(); // step t is staged; every wave is done with step t-1
         if (t + 1 < n_steps) fetch(buf ^ 1, true);
         if (tid < kFK && t + 2 < n_steps) tabulate(buf, (t + 2) * kFK + tid, 0);
-        f32x4 sc[2];
+        f32x4 sc[QB][2];
         scores(buf, sc);
         // Scores stay unscaled (the factor to log2 units sits in the exponent's multiply-add); a row a query
         // may not see scores kHidden, and running maxima never drop below kFloor: exp2 of the difference is an
         // exact zero for hidden rows, no select needed, and a query that has seen nothing yet sums zeros.
-        float sv[8];
-        {
-            const i32x4 f0 = *reinterpret_cast<const i32x4 *>(&s_ft[buf][4 * lg]);
-            const i32x4 f1 = *reinterpret_cast<const i32x4 *>(&s_ft[buf][16 + 4 * lg]);
+        const i32x4 f0 = *reinterpret_cast<const i32x4 *>(&s_ft[buf][4 * lg]);
+        const i32x4 f1 = *reinterpret_cast<const i32x4 *>(&s_ft[buf][16 + 4 * lg]);
+#pragma unroll
+        for (int i = 0; i < QB; ++i) {
+            float sv[8];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                sv[r] = tokq >= f0[r] ? sc[0][r] : kHidden;
-                sv[4 + r] = tokq >= f1[r] ? sc[1][r] : kHidden;
+                sv[r] = tokq[i] >= f0[r] ? sc[i][0][r] : kHidden;
+                sv[4 + r] = tokq[i] >= f1[r] ? sc[i][1][r] : kHidden;
             }
-        }
-        float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-        const float m_new = fmaxf(m_run, xrow_max(mx) * a.scale_log2e);
-        const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
-        float pw[8];
+            const float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+            const float m_new = fmaxf(m_run[i], xrow_max(mx) * a.scale_log2e);
+            const float corr = __builtin_amdgcn_exp2f(m_run[i] - m_new);
+            float pw[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) pw[i] = __builtin_amdgcn_exp2f(fmaf(sv[i], a.scale_log2e, -m_new));
-        l_run = l_run * corr + xrow_sum(((pw[0] + pw[1]) + (pw[2] + pw[3])) + ((pw[4] + pw[5]) + (pw[6] + pw[7])));
-        const bool moved = m_new != m_run;
-        m_run = m_new;
-        {
-            const int qrow = 16 * wave + lr;
+            for (int e = 0; e < 8; ++e) pw[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], a.scale_log2e, -m_new));
+            l_run[i] = l_run[i] * corr + xrow_sum(((pw[0] + pw[1]) + (pw[2] + pw[3])) + ((pw[4] + pw[5]) + (pw[6] + pw[7])));
+            const bool moved = m_new != m_run[i];
+            m_run[i] = m_new;
+            const int qrow = 16 * (QB * wave + i) + lr;
             if (lg == 0) s_corr[qrow] = corr;
             // rows 4 lg .. 4 lg + 3 and 16 + 4 lg .. of the query's weights, rounded to bf16 two at a time
             u32x2 w0, w1;
@@ -722,11 +735,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             w1[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pw[6], pw[7]}, bf16x2));
             *reinterpret_cast<u32x2 *>(s_p + qrow * kPStride + 8 * lg) = w0;
             *reinterpret_cast<u32x2 *>(s_p + qrow * kPStride + 32 + 8 * lg) = w1;
-        }
-        // most steps leave the running maxima of the wave's 16 queries where they were: nothing to rescale then
-        {
+            // most steps leave the running maxima of a block's 16 queries where they were: nothing to rescale then
             const bool any_moved = __builtin_amdgcn_ballot_w64(moved) != 0;
-            if (lane == 0) s_chg[wave] = any_moved;
+            if (lane == 0) s_chg[QB * wave + i] = any_moved;
         }
         __syncthreads(); // weights and factors of step t are in LDS
         bf16x8 bv[2];
@@ -743,7 +754,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             bv[db] = __builtin_bit_cast(bf16x8, raw16{w[0], w[1], w[2], w[3]});
         }
 #pragma unroll
-        for (int qb = 0; qb < 4; ++qb) {
+        for (int qb = 0; qb < NQB; ++qb) {
             const bf16x8 ap = __builtin_bit_cast(bf16x8, *reinterpret_cast<const raw16 *>(s_p + (16 * qb + lr) * kPStride + 16 * lg));
             if (s_chg[qb]) {
                 float corr[4];
@@ -761,12 +772,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     // ---- final statistics to LDS, output ----
     __syncthreads();
     if (lg == 0) {
-        s_fin[0][16 * wave + lr] = m_run;
-        s_fin[1][16 * wave + lr] = l_run;
+#pragma unroll
+        for (int i = 0; i < QB; ++i) {
+            s_fin[0][16 * (QB * wave + i) + lr] = m_run[i];
+            s_fin[1][16 * (QB * wave + i) + lr] = l_run[i];
+        }
     }
     __syncthreads();
 #pragma unroll
-    for (int qb = 0; qb < 4; ++qb) {
+    for (int qb = 0; qb < NQB; ++qb) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int n = 16 * qb + 4 * lg + r;
@@ -783,7 +797,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     if (!colpart) return;
 
     // ---- Eq. 1: weights on the new tokens, added over the workgroup's queries ----
-    const float lse = l_run > 0.f ? m_run + __builtin_amdgcn_logf(l_run) : INFINITY; // of query 16 * wave + lr
+    float lse[QB]; // of query lr of the wave's blocks
+#pragma unroll
+    for (int i = 0; i < QB; ++i) lse[i] = l_run[i] > 0.f ? m_run[i] + __builtin_amdgcn_logf(l_run[i]) : INFINITY;
     float *dst = colpart + (((int64_t)b * a.Hkv + g) * n_tiles + qt) * a.n_q;
     // new token j is local row n_loc - n_q + j, i.e. row r_new0 + j of the row sequence (it may not exist)
     const int r_new0 = n_ret + n_loc - a.n_q;
@@ -804,15 +820,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         __syncthreads();
         if (t + 1 < n_steps2) fetch(buf ^ 1, false);
         if (tid < kFK && t + 2 < n_steps2) tabulate(buf, r_new0 + (t + 2) * kFK + tid, n_ret);
-        f32x4 sc[2];
+        f32x4 sc[QB][2];
         scores(buf, sc);
-        {   // the lane's weights on rows 16 kb + 4 lg + r, added over the 16 queries of the wave (the lanes of a row)
+        {   // the lane's weights on rows 16 kb + 4 lg + r, added over the queries of the wave (its blocks, the lanes of a row)
             const i32x4 f0 = *reinterpret_cast<const i32x4 *>(&s_ft[buf][4 * lg]);
             const i32x4 f1 = *reinterpret_cast<const i32x4 *>(&s_ft[buf][16 + 4 * lg]);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                float c0 = tokq >= f0[r] ? __builtin_amdgcn_exp2f(fmaf(sc[0][r], a.scale_log2e, -lse)) : 0.f;
-                float c1 = tokq >= f1[r] ? __builtin_amdgcn_exp2f(fmaf(sc[1][r], a.scale_log2e, -lse)) : 0.f;
+                float c0 = 0.f, c1 = 0.f;
+#pragma unroll
+                for (int i = 0; i < QB; ++i) {
+                    c0 += tokq[i] >= f0[r] ? __builtin_amdgcn_exp2f(fmaf(sc[i][0][r], a.scale_log2e, -lse[i])) : 0.f;
+                    c1 += tokq[i] >= f1[r] ? __builtin_amdgcn_exp2f(fmaf(sc[i][1][r], a.scale_log2e, -lse[i])) : 0.f;
+                }
                 c0 = row16_sum(c0);
                 c1 = row16_sum(c1);
                 if (lr == 0) {
@@ -925,9 +945,16 @@ hipError_t launch_attend(const Ctx &c, int layer, const void *q, int n_q, const 
         po.signal = signal;
     }
     if (workspace && c.cfg.dtype == MUKV_BF16 && c.cfg.head_dim == kFD) { // the prefill on the matrix cores
-        const int n_tiles = (n_q * c.group + kFQ - 1) / kFQ;
-        hipLaunchKernelGGL(prefill_flash_kernel, dim3(n_tiles, a.Hkv, B), dim3(256), 0, st, a, static_cast<uint16_t *>(out),
-                           po.colpart, n_tiles);
+        // 128-query tiles once they still fill the chip about twice over, 64-query tiles for shorter prefills
+        const int64_t n_queries = (int64_t)n_q * c.group;
+        const bool wide = (n_queries + 127) / 128 * a.Hkv * B >= 2 * 256;
+        const int n_tiles = (int)((n_queries + (wide ? 127 : 63)) / (wide ? 128 : 64));
+        if (wide)
+            hipLaunchKernelGGL(prefill_flash_kernel<2>, dim3(n_tiles, a.Hkv, B), dim3(256), 0, st, a,
+                               static_cast<uint16_t *>(out), po.colpart, n_tiles);
+        else
+            hipLaunchKernelGGL(prefill_flash_kernel<1>, dim3(n_tiles, a.Hkv, B), dim3(256), 0, st, a,
+                               static_cast<uint16_t *>(out), po.colpart, n_tiles);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(prefill_signal_kernel, dim3((n_q + kSigCols - 1) / kSigCols, B), dim3(kThreads), 0, st, po.colpart,

@@ -961,6 +961,18 @@ def test_prefill_attention_and_received_signal(name, frames, kw, n_q, old):
     p.close()
 
 
+def test_prefill_of_a_long_unit_takes_the_wide_tiles():
+    # enough queries for 128-query tiles to fill the chip twice over (72B head layout: 8 KV heads x 8)
+    w = W["72b"].scaled(n_frames=6, n_layers=1, n_questions=1)
+    p = Pair(w, seed=440, chunk=3)
+    p.ingest()
+    n_q = 1100                                   # 8800 queries per KV head: 69 tiles x 8 heads >= 512 workgroups, ragged
+    for causal in (True, False):
+        _, _, e_out, e_sig = p.check_prefill(0, n_q, [[4, 0, -1]], [9], causal, seed=441)
+        print(f"wide tiles, causal={causal}: out err {e_out:.2e}, signal err {e_sig:.2e}")
+    p.close()
+
+
 def test_prefill_signal_feeds_the_compression():
     # one stream, chunk by chunk: prefill of the chunk's tokens over frames already in the cache -> its
     # signal, handed to mukv_compress_chunk.  The oracle is given the same float32 signal, so the keep
