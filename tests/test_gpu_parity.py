@@ -1125,3 +1125,25 @@ def test_prefill_with_fewer_local_rows_than_new_tokens(name, kw):
     assert np.abs(got[8:] - want12).max() <= mk_tol(w) * max(1.0, np.abs(want12).max())
     assert np.abs(sig[8:] * 20 / 12 - sig12).max() <= 1e-6      # the mean runs over the 20 query rows of the call
     p.close()
+
+
+@pytest.mark.parametrize("i", range(16))
+def test_seeded_sweep_of_large_units(i):
+    # units of 257..8192 tokens nobody picked by hand: super-patch counts, keep ratios, signal mixes, payloads,
+    # head sizes, launch modes; the signal handed over; then retrieval over units and attention on that cache
+    rng = np.random.default_rng(9000 + i)
+    P = int(rng.integers(257, 8193)) if i % 4 else int(rng.choice([257, 512, 4096, 6272, 8192]))
+    hkv = int(rng.choice([1, 2, 4]))
+    units = int(rng.integers(2, 7))
+    kw = {"batch_chunks": int(rng.choice([1, 2])), "overlap_copy": int(rng.integers(0, 2)),
+          "refine_margin": float(rng.choice([-1.0, 0.0, 10.0]))}
+    w = _unit_workload(str(rng.choice(["bf16", "f32"])), P, int(rng.choice([1, 2, 7, 32])), float(rng.choice([0.05, 0.3, 0.8, 1.0])),
+                       float(rng.choice([0.0, 0.5, 0.8, 1.0])), units, frames_per_segment=int(rng.choice([1, 2, 3])),
+                       n_layers=int(rng.integers(1, 3)), n_kv_heads=hkv, n_q_heads=hkv * int(rng.choice([1, 2])),
+                       head_dim=int(rng.choice([16, 32, 64, 128])))
+    p = Pair(w, seed=9100 + i, chunk=int(rng.integers(1, 3)), with_q=False, gpu_kw=kw)
+    p.ingest(att_seed=9200 + i)
+    p.check_compress()
+    p.check_retrieve(questions_for(w, [5, 9], 9300 + i), mk.MUKV_SEMI, 1, 2, 0.3)
+    p.check_attend(0, 2, [[0, units - 1], [units - 1, -1]], [4, 2], True, seed=i)
+    p.close()
