@@ -554,9 +554,14 @@ constexpr int kPStride = kFK * 2 + 16;   // bytes of a row of weights
 // QB: blocks of 16 queries per wave (64 * QB queries per workgroup).  With two blocks a key or value
 // operand fetched from LDS serves twice the matrix instructions; with one there are twice the
 // workgroups, which is what a short prefill needs.
-template <int QB>
+// MODE 0: all of it in one launch.  A short prefill has too few tiles to fill the chip, so its rows are
+// split over n_split workgroups per tile -- MODE 1: the split's (maximum, normaliser, unnormalised output)
+// go to the records attend_combine_kernel merges (aux = records), no second loop -- and the second loop
+// runs as a launch of its own once the merged log-sum-exps exist -- MODE 2 (aux = log-sum-exps), its
+// steps split over the same number of workgroups.
+template <int QB, int MODE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QB == 1 ? 3 : 2, QB == 1 ? 3 : 2))) void prefill_flash_kernel(
-    AttendArgs a, uint16_t *__restrict__ out, float *__restrict__ colpart, int n_tiles) {
+    AttendArgs a, uint16_t *__restrict__ out, float *__restrict__ colpart, int n_tiles, float *__restrict__ aux, int n_split) {
     using T = uint16_t;
     constexpr int kFQ = 64 * QB, NQB = 4 * QB; // queries, blocks of 16 queries per workgroup
     __shared__ __align__(16) unsigned char s_k[2][kFK * kRowStride];
@@ -570,7 +575,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QB == 1 ? 3
     __shared__ int s_frame[kMaxGatherK]; // the question's frames; -1: names no frame of the cache
     __shared__ int64_t s_toff[2][kFK];   // where the rows of the next two steps live
     __shared__ int s_tft[2][kFK];
-    const int qt = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int qt = MODE == 0 ? blockIdx.x : blockIdx.x / n_split, sp = MODE == 0 ? 0 : blockIdx.x % n_split;
+    const int g = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane & 15, lg = lane >> 4;
     const int n_queries = a.n_q * a.G;
     const T *q = static_cast<const T *>(a.q);
@@ -584,6 +590,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QB == 1 ? 3
     // the wave's blocks are QB * wave + i; block n holds queries 16 n .. 16 n + 15 of the tile
     bf16x8 qa[QB][kFD / 32];
     int tokq[QB]; // token of the query this lane holds scores for (nothing is visible to a query that does not exist)
+    float lse_in[QB];
 #pragma unroll
     for (int i = 0; i < QB; ++i) {
         const int qq = qt * kFQ + 16 * (QB * wave + i) + lr;
@@ -597,6 +604,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QB == 1 ? 3
             qa[i][kk] = __builtin_bit_cast(bf16x8, u);
         }
         tokq[i] = ok ? ti : INT_MIN;
+        if constexpr (MODE == 2) lse_in[i] = ok ? aux[((int64_t)b * a.n_q + ti) * a.Hq + h] : INFINITY;
     }
 
     const int n_ret = a.k_frame * a.kappa;
@@ -688,15 +696,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QB == 1 ? 3
     const int last_q = (qt * kFQ + kFQ - 1 < n_queries ? qt * kFQ + kFQ - 1 : n_queries - 1) / a.G;
     int n_seen = total;
     if (a.causal && n_ret + n_loc - a.n_q + last_q + 1 < total) n_seen = n_ret + n_loc - a.n_q + last_q + 1;
-    const int n_steps = n_seen > 0 ? (n_seen + kFK - 1) / kFK : 0;
-    if (tid < kFK) {
-        tabulate(0, tid, 0);
-        tabulate(1, kFK + tid, 0);
+    const int n_steps_all = n_seen > 0 ? (n_seen + kFK - 1) / kFK : 0;
+    // this workgroup's steps: all of them, or its share of them
+    const int per_split = MODE == 1 ? (n_steps_all + n_split - 1) / n_split : n_steps_all;
+    const int t_lo = MODE == 1 ? sp * per_split : 0;
+    const int n_steps = MODE == 2 ? 0 : (t_lo + per_split < n_steps_all ? t_lo + per_split : n_steps_all);
+    if (MODE != 2 && tid < kFK) {
+        tabulate(0, t_lo * kFK + tid, 0);
+        tabulate(1, (t_lo + 1) * kFK + tid, 0);
     }
     __syncthreads();
-    if (n_steps > 0) fetch(0, true);
-    for (int t = 0; t < n_steps; ++t) {
-        const int buf = t & 1;
+    if (t_lo < n_steps) fetch(0, true);
+    for (int t = t_lo; t < n_steps; ++t) {
+        const int buf = (t - t_lo) & 1;
         put(buf, true);
         __syncthreads(); // step t is staged; every wave is done with step t-1
         if (t + 1 < n_steps) fetch(buf ^ 1, true);
@@ -769,53 +781,77 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QB == 1 ? 3
             for (int db = 0; db < 2; ++db) o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap, bv[db], o[qb][db], 0, 0, 0);
         }
     }
-    // ---- final statistics to LDS, output ----
-    __syncthreads();
-    if (lg == 0) {
+    float lse[QB]; // of query lr of the wave's blocks
+    if constexpr (MODE != 2) {
+        // ---- final statistics to LDS, output ----
+        __syncthreads();
+        if (lg == 0) {
 #pragma unroll
-        for (int i = 0; i < QB; ++i) {
-            s_fin[0][16 * (QB * wave + i) + lr] = m_run[i];
-            s_fin[1][16 * (QB * wave + i) + lr] = l_run[i];
+            for (int i = 0; i < QB; ++i) {
+                s_fin[0][16 * (QB * wave + i) + lr] = m_run[i];
+                s_fin[1][16 * (QB * wave + i) + lr] = l_run[i];
+            }
         }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int n = 16 * qb + 4 * lg + r;
-            const int qq = qt * kFQ + n;
-            if (qq >= n_queries) continue;
-            const float l = s_fin[1][n];
-            const float inv = l > 0.f ? 1.0f / l : 0.f;
-            const int i = qq / a.G, h = g * a.G + qq % a.G;
-            uint16_t *op = out + (((int64_t)b * a.n_q + i) * a.Hq + h) * kFD + 32 * wave + lr;
-            op[0] = bf16_round(o[qb][0][r] * inv);
-            op[16] = bf16_round(o[qb][1][r] * inv);
+        __syncthreads();
+        if constexpr (MODE == 1) { // the split's record of every query: [0] maximum, [1] normaliser, [2..] unnormalised output
+            if (tid < kFQ && qt * kFQ + tid < n_queries) {
+                const int qq = qt * kFQ + tid;
+                const int i = qq / a.G, h = g * a.G + qq % a.G;
+                float *rec = aux + ((((int64_t)b * a.n_q + i) * a.Hq + h) * n_split + sp) * (kFD + 2);
+                rec[0] = s_fin[0][tid];
+                rec[1] = s_fin[1][tid];
+            }
         }
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int n = 16 * qb + 4 * lg + r;
+                const int qq = qt * kFQ + n;
+                if (qq >= n_queries) continue;
+                const int i = qq / a.G, h = g * a.G + qq % a.G;
+                if constexpr (MODE == 1) {
+                    float *rec = aux + ((((int64_t)b * a.n_q + i) * a.Hq + h) * n_split + sp) * (kFD + 2) + 2 + 32 * wave + lr;
+                    rec[0] = o[qb][0][r];
+                    rec[16] = o[qb][1][r];
+                } else {
+                    const float l = s_fin[1][n];
+                    const float inv = l > 0.f ? 1.0f / l : 0.f;
+                    uint16_t *op = out + (((int64_t)b * a.n_q + i) * a.Hq + h) * kFD + 32 * wave + lr;
+                    op[0] = bf16_round(o[qb][0][r] * inv);
+                    op[16] = bf16_round(o[qb][1][r] * inv);
+                }
+            }
+        }
+        if (MODE == 1 || !colpart) return;
+#pragma unroll
+        for (int i = 0; i < QB; ++i) lse[i] = l_run[i] > 0.f ? m_run[i] + __builtin_amdgcn_logf(l_run[i]) : INFINITY;
+    } else {
+#pragma unroll
+        for (int i = 0; i < QB; ++i) lse[i] = lse_in[i];
     }
-    if (!colpart) return;
 
     // ---- Eq. 1: weights on the new tokens, added over the workgroup's queries ----
-    float lse[QB]; // of query lr of the wave's blocks
-#pragma unroll
-    for (int i = 0; i < QB; ++i) lse[i] = l_run[i] > 0.f ? m_run[i] + __builtin_amdgcn_logf(l_run[i]) : INFINITY;
     float *dst = colpart + (((int64_t)b * a.Hkv + g) * n_tiles + qt) * a.n_q;
     // new token j is local row n_loc - n_q + j, i.e. row r_new0 + j of the row sequence (it may not exist)
     const int r_new0 = n_ret + n_loc - a.n_q;
     const int j_end = a.causal ? (last_q + 1 < a.n_q ? last_q + 1 : a.n_q) : a.n_q; // later tokens get nothing from here
-    for (int j = j_end + tid; j < a.n_q; j += 256) dst[j] = 0.f;
-    const int n_steps2 = (j_end + kFK - 1) / kFK;
+    if (sp == 0)
+        for (int j = j_end + tid; j < a.n_q; j += 256) dst[j] = 0.f;
+    const int n_steps2_all = (j_end + kFK - 1) / kFK;
+    const int per2 = MODE == 2 ? (n_steps2_all + n_split - 1) / n_split : n_steps2_all;
+    const int t2_lo = MODE == 2 ? sp * per2 : 0;
+    const int n_steps2 = t2_lo + per2 < n_steps2_all ? t2_lo + per2 : n_steps2_all;
     __syncthreads(); // the staging buffers and the row table are free again
     // rows below n_ret would be retrieved rows: a new token without a row of its own is seen by nobody
     if (tid < kFK) {
-        tabulate(0, r_new0 + tid, n_ret);
-        tabulate(1, r_new0 + kFK + tid, n_ret);
+        tabulate(0, r_new0 + t2_lo * kFK + tid, n_ret);
+        tabulate(1, r_new0 + (t2_lo + 1) * kFK + tid, n_ret);
     }
     __syncthreads();
-    if (n_steps2 > 0) fetch(0, false);
-    for (int t = 0; t < n_steps2; ++t) {
-        const int buf = t & 1;
+    if (t2_lo < n_steps2) fetch(0, false);
+    for (int t = t2_lo; t < n_steps2; ++t) {
+        const int buf = (t - t2_lo) & 1;
         put(buf, false);
         __syncthreads();
         if (t + 1 < n_steps2) fetch(buf ^ 1, false);
@@ -893,11 +929,34 @@ int split_count(int B, int Hkv, int n_qtiles, int k_frame, int *frames_per_split
 
 } // namespace
 
+static bool flash_shape(const Ctx &c) { return c.cfg.dtype == MUKV_BF16 && c.cfg.head_dim == kFD; }
+static bool flash_wide(const Ctx &c, int n_q, int B) { // 128-query tiles once they still fill the chip about twice over
+    return (((int64_t)n_q * c.group + 127) / 128) * c.cfg.n_kv_heads * B >= 2 * 256;
+}
+// Workgroups that share the rows of one 64-query tile of the matrix-core prefill: 1 unless the tiles alone
+// leave most of the chip idle (about three workgroups per compute unit are wanted, at least four steps each).
+static int flash_split(const Ctx &c, int n_q, int B, int k_frame) {
+    if (flash_wide(c, n_q, B)) return 1;
+    const int64_t wgs = (((int64_t)n_q * c.group + 63) / 64) * c.cfg.n_kv_heads * B;
+    if (wgs >= 384) return 1;
+    const int64_t steps = ((int64_t)(k_frame > 0 ? k_frame : 0) * c.kappa + n_q + kFK - 1) / kFK;
+    int64_t n = (768 + wgs - 1) / wgs;
+    if (n > kAttendMaxSplit) n = kAttendMaxSplit;
+    if (n > steps / 4) n = steps / 4;
+    return n < 1 ? 1 : (int)n;
+}
+
 // Workspace of the prefill call, in floats: the splits' records, the log-sum-exps, the tiles' column sums.
 static void prefill_layout(const Ctx &c, int n_q, int B, int k_frame, int64_t *part, int64_t *lse, int64_t *colpart) {
     const int n_qtiles = (n_q * c.group + kTileQ - 1) / kTileQ;
-    int fps;
-    const int n_split = split_count(B, c.cfg.n_kv_heads, n_qtiles, k_frame > 0 ? k_frame : 0, &fps);
+    int n_split;
+    if (flash_shape(c)) {
+        n_split = flash_split(c, n_q, B, k_frame);
+        if (n_split == 1) n_split = 0; // one launch does it all: no records
+    } else {
+        int fps;
+        n_split = split_count(B, c.cfg.n_kv_heads, n_qtiles, k_frame > 0 ? k_frame : 0, &fps);
+    }
     *part = (int64_t)B * n_q * c.cfg.n_q_heads * n_split * (c.cfg.head_dim + 2);
     *lse = (int64_t)B * n_q * c.cfg.n_q_heads;
     *colpart = (int64_t)B * c.cfg.n_kv_heads * n_qtiles * n_q;
@@ -944,19 +1003,30 @@ hipError_t launch_attend(const Ctx &c, int layer, const void *q, int n_q, const 
         po.colpart = workspace + p + l;
         po.signal = signal;
     }
-    if (workspace && c.cfg.dtype == MUKV_BF16 && c.cfg.head_dim == kFD) { // the prefill on the matrix cores
-        // 128-query tiles once they still fill the chip about twice over, 64-query tiles for shorter prefills
+    if (workspace && flash_shape(c)) { // the prefill on the matrix cores
         const int64_t n_queries = (int64_t)n_q * c.group;
-        const bool wide = (n_queries + 127) / 128 * a.Hkv * B >= 2 * 256;
+        const bool wide = flash_wide(c, n_q, B);
+        const int n_fs = flash_split(c, n_q, B, k_frame);
         const int n_tiles = (int)((n_queries + (wide ? 127 : 63)) / (wide ? 128 : 64));
-        if (wide)
-            hipLaunchKernelGGL(prefill_flash_kernel<2>, dim3(n_tiles, a.Hkv, B), dim3(256), 0, st, a,
-                               static_cast<uint16_t *>(out), po.colpart, n_tiles);
-        else
-            hipLaunchKernelGGL(prefill_flash_kernel<1>, dim3(n_tiles, a.Hkv, B), dim3(256), 0, st, a,
-                               static_cast<uint16_t *>(out), po.colpart, n_tiles);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
+        uint16_t *o16 = static_cast<uint16_t *>(out);
+        hipError_t e;
+        if (wide) {
+            hipLaunchKernelGGL((prefill_flash_kernel<2, 0>), dim3(n_tiles, a.Hkv, B), dim3(256), 0, st, a, o16, po.colpart,
+                               n_tiles, nullptr, 1);
+        } else if (n_fs == 1) {
+            hipLaunchKernelGGL((prefill_flash_kernel<1, 0>), dim3(n_tiles, a.Hkv, B), dim3(256), 0, st, a, o16, po.colpart,
+                               n_tiles, nullptr, 1);
+        } else { // rows shared by n_fs workgroups per tile, merged, then the column sums from the merged log-sum-exps
+            hipLaunchKernelGGL((prefill_flash_kernel<1, 1>), dim3(n_tiles * n_fs, a.Hkv, B), dim3(256), 0, st, a, o16,
+                               nullptr, n_tiles, workspace, n_fs);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            hipLaunchKernelGGL((attend_combine_kernel<uint16_t, kFD>), dim3((unsigned)(B * n_q * a.Hq)), dim3(kFD), 0, st,
+                               workspace, n_fs, o16, po.lse);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            hipLaunchKernelGGL((prefill_flash_kernel<1, 2>), dim3(n_tiles * n_fs, a.Hkv, B), dim3(256), 0, st, a, o16,
+                               po.colpart, n_tiles, po.lse, n_fs);
+        }
+        if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(prefill_signal_kernel, dim3((n_q + kSigCols - 1) / kSigCols, B), dim3(kThreads), 0, st, po.colpart,
                            a.Hkv * n_tiles, n_q, 1.0f / ((float)a.Hq * (float)n_q), po.signal);
         return hipGetLastError();
