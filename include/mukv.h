@@ -365,7 +365,10 @@ int mukv_attend(mukv_ctx *ctx, int32_t layer, const void *q, int32_t n_q, const 
  *                   undefined afterwards.  The call allocates nothing.
  *
  * Arithmetic in fp32, sums in a fixed order; `out` is rounded to the payload
- * dtype.  Errors: INVALID_ARG (null pointers: here the local rows and both
+ * dtype.  For bf16 payloads with D = 128 both products run on the matrix
+ * cores: the softmax weights enter the value product rounded to bf16 (the
+ * normaliser and att_signal_out use the unrounded fp32 weights).
+ * Errors: INVALID_ARG (null pointers: here the local rows and both
  * outputs are required), CAPACITY (B > max_questions, workspace too small),
  * UNSUPPORTED (n_q > 8192, k_frame > 1024, n_q * Hq > 524 280, alignment).
  */
