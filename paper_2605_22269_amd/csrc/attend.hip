@@ -695,7 +695,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QB == 1 ? 3
     // with the causal mask the rows after the workgroup's last token are seen by none of its queries
     const int last_q = (qt * kFQ + kFQ - 1 < n_queries ? qt * kFQ + kFQ - 1 : n_queries - 1) / a.G;
     int n_seen = total;
-    if (a.causal && n_ret + n_loc - a.n_q + last_q + 1 < total) n_seen = n_ret + n_loc - a.n_q + last_q + 1;
+    if (a.causal) {
+        // local rows up to the tile's last token; the retrieved rows are seen by every token, also by
+        // tokens that have no local row of their own (fewer local rows than new tokens)
+        int ns = n_ret + n_loc - a.n_q + last_q + 1;
+        if (ns < n_ret) ns = n_ret;
+        if (ns < total) n_seen = ns;
+    }
     const int n_steps_all = n_seen > 0 ? (n_seen + kFK - 1) / kFK : 0;
     // this workgroup's steps: all of them, or its share of them
     const int per_split = MODE == 1 ? (n_steps_all + n_split - 1) / n_split : n_steps_all;
@@ -959,7 +965,9 @@ static void prefill_layout(const Ctx &c, int n_q, int B, int k_frame, int64_t *p
     }
     *part = (int64_t)B * n_q * c.cfg.n_q_heads * n_split * (c.cfg.head_dim + 2);
     *lse = (int64_t)B * n_q * c.cfg.n_q_heads;
-    *colpart = (int64_t)B * c.cfg.n_kv_heads * n_qtiles * n_q;
+    // column sums per (KV head, query tile): the matrix-core prefill has tiles of 64 (or 128) queries
+    const int64_t n_coltiles = flash_shape(c) ? ((int64_t)n_q * c.group + 63) / 64 : n_qtiles;
+    *colpart = (int64_t)B * c.cfg.n_kv_heads * n_coltiles * n_q;
 }
 
 int64_t prefill_workspace_bytes(const Ctx &c, int n_q, int B, int k_frame) {

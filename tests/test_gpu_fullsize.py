@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 import torch
 
-from mukv_testlib import TOL, gpu_context, np_view, oracle_config
+from mukv_testlib import TOL, gpu_context, np_view, oracle_config, out_err
 from oracle import oracle as orc
 from paper_2605_22269_amd import binding as mk
 from paper_2605_22269_amd import synth
@@ -163,7 +163,7 @@ def check_decode(w, gpu, ref, hits, layers, n_q=1, n_local=32, seed=0):
         for b in range(B):
             want = ref.attend(layer, np_view(q[b]), hits[b], np_view(kl[b * n_local:(b + 1) * n_local]),
                               np_view(vl[b * n_local:(b + 1) * n_local]), True)
-            err = float(np.abs(got[b] - want).max()) / max(1.0, float(np.abs(want).max()))
+            err = out_err(got[b], want)
             assert err <= (2e-2 if w.dtype == "bf16" else 1e-5), (layer, b, err)
             worst = max(worst, err)
     return worst
@@ -183,7 +183,7 @@ def check_prefill(w, gpu, ref, hits, layer, n_q, n_old=0, seed=0):
     got = np_view(out.cpu())
     got = (got.astype(np.uint32) << 16).view(np.float32).astype(np.float64) if got.dtype == np.uint16 else got.astype(np.float64)
     want, want_sig = ref.prefill_attend(layer, np_view(q[0]), list(hits), np_view(kl), np_view(vl), True)
-    err = float(np.abs(got[0] - want).max()) / max(1.0, float(np.abs(want).max()))
+    err = out_err(got[0], want)
     err_sig = float(np.abs(sig[0].cpu().numpy().astype(np.float64) - want_sig).max())
     assert err <= (2e-2 if w.dtype == "bf16" else 1e-5), err
     assert err_sig <= 1e-6, err_sig
