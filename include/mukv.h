@@ -379,6 +379,29 @@ int mukv_prefill_attend(mukv_ctx *ctx, int32_t layer, const void *q, int32_t n_q
                         int64_t workspace_bytes, void *stream);
 
 /*
+ * mukv_prefill_attend for callers that cannot allocate device memory and so
+ * have no workspace to hand over: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments without the
+ * workspace, same kernels, same results.  The scratch is a fixed array of
+ * MUKV_STATIC_SCRATCH_BYTES in the library's device image, one copy per GPU,
+ * held until the process ends; the call allocates and frees nothing.
+ *
+ * A call whose mukv_prefill_workspace_size() exceeds MUKV_STATIC_SCRATCH_BYTES
+ * returns MUKV_ERR_CAPACITY and launches nothing (in the 7B head layout one
+ * frame of 196 new tokens over 32 retrieved frames needs 23 MB, a chunk of
+ * 1568 tokens 5 MB).  Every call on a GPU -- of any context, on any stream --
+ * uses that GPU's one array: calls that overlap in time on one GPU race and
+ * must be ordered by the caller (one stream, or events).  Nothing in the
+ * array has to start at zero; it keeps the last call's contents.
+ * Errors otherwise as for mukv_prefill_attend.
+ */
+#define MUKV_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+int mukv_prefill_attend_static(mukv_ctx *ctx, int32_t layer, const void *q, int32_t n_q, const int32_t *frame_idx,
+                               int32_t k_frame, const void *k_local, const void *v_local,
+                               const int32_t *local_offsets, int32_t B, int32_t causal_local, void *out,
+                               float *att_signal_out, void *stream);
+
+/*
  * Snapshot of the cache (the offline memory of Sec. 3.3 is persistent state):
  * the kept K/V rows, kept positions, block keys and running segment sums of
  * the frames ingested so far, in one host buffer, so that a stream can be

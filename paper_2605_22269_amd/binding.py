@@ -71,7 +71,8 @@ class mukv_profile(C.Structure):
 
 EXPORTS = ("mukv_create", "mukv_destroy", "mukv_reset", "mukv_flush", "mukv_compress_chunk", "mukv_retrieve",
            "mukv_retrieve_patches", "mukv_retrieve_at", "mukv_gather_kv", "mukv_gather_patches", "mukv_gather_union",
-           "mukv_attend", "mukv_prefill_workspace_size", "mukv_prefill_attend", "mukv_snapshot_size", "mukv_snapshot_save", "mukv_snapshot_load", "mukv_profile_begin", "mukv_profile_end",
+           "mukv_attend", "mukv_prefill_workspace_size", "mukv_prefill_attend", "mukv_prefill_attend_static",
+           "mukv_snapshot_size", "mukv_snapshot_save", "mukv_snapshot_load", "mukv_profile_begin", "mukv_profile_end",
            "mukv_plain_copy", "mukv_get_state", "mukv_strerror")
 
 _lib = None
@@ -102,6 +103,7 @@ def load():
     lib.mukv_attend.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp, vp, i32, i32, vp, vp]
     lib.mukv_prefill_workspace_size.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_int64)]
     lib.mukv_prefill_attend.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp, vp, i32, i32, vp, vp, vp, C.c_int64, vp]
+    lib.mukv_prefill_attend_static.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp, vp, i32, i32, vp, vp, vp]
     lib.mukv_snapshot_size.argtypes = [vp, C.POINTER(C.c_int64)]
     lib.mukv_snapshot_save.argtypes = [vp, vp, C.c_int64, vp]
     lib.mukv_snapshot_load.argtypes = [vp, vp, C.c_int64, vp]
@@ -196,6 +198,15 @@ def mukv_prefill_attend(h, layer, q_ptr, n_q, idx_ptr, k_frame, kl_ptr, vl_ptr, 
                         ws_ptr, ws_bytes, stream):
     _check(load().mukv_prefill_attend(h, layer, q_ptr, n_q, idx_ptr, k_frame, kl_ptr, vl_ptr, loff_ptr, B, causal_local,
                                       out_ptr, sig_ptr, ws_ptr, ws_bytes, stream), "mukv_prefill_attend")
+
+
+MUKV_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
+
+
+def mukv_prefill_attend_static(h, layer, q_ptr, n_q, idx_ptr, k_frame, kl_ptr, vl_ptr, loff_ptr, B, causal_local, out_ptr,
+                               sig_ptr, stream):
+    _check(load().mukv_prefill_attend_static(h, layer, q_ptr, n_q, idx_ptr, k_frame, kl_ptr, vl_ptr, loff_ptr, B,
+                                             causal_local, out_ptr, sig_ptr, stream), "mukv_prefill_attend_static")
 
 
 def mukv_snapshot_size(h) -> int:
@@ -458,6 +469,16 @@ class MuKV:
         mukv_prefill_attend(self.h, layer, _ptr(q), n_q, _ptr(frame_idx), k_frame, _ptr(k_local), _ptr(v_local),
                             _ptr(local_offsets), B, int(causal_local), _ptr(out), _ptr(signal), _ptr(workspace),
                             workspace.numel(), _stream())
+        self._held.clear()
+        return out, signal
+
+    def prefill_attend_static(self, layer, q, frame_idx, k_local, v_local, local_offsets, causal_local, out, signal):
+        """prefill_attend() on the library's fixed per-GPU scratch: allocates nothing, so `out` (like q) and
+        `signal` (float32 [B][n_q]) are the caller's."""
+        B, n_q = q.shape[0], q.shape[1]
+        k_frame = 0 if frame_idx is None else frame_idx.shape[1]
+        mukv_prefill_attend_static(self.h, layer, _ptr(q), n_q, _ptr(frame_idx), k_frame, _ptr(k_local), _ptr(v_local),
+                                   _ptr(local_offsets), B, int(causal_local), _ptr(out), _ptr(signal), _stream())
         self._held.clear()
         return out, signal
 

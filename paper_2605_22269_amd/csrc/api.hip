@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -80,6 +81,29 @@ int validate_config(const mukv_config *cfg) {
 }
 
 bool mfma_supported(const mukv_config &c) { return mukv::att_mfma_supported(c); }
+
+// Scratch of mukv_prefill_attend_static, for callers that may not allocate: one array per GPU in the
+// library's device image, held until the process ends.  `scratch` itself is only the host-side
+// handle of the symbol; the array's device address differs from GPU to GPU and is looked up once per
+// device (with that device current) and kept in g_scratch_ptr, which is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[MUKV_STATIC_SCRATCH_BYTES];
+void *g_scratch_ptr[mukv::kMaxDevices];
+std::mutex g_scratch_lock;
+
+// The calling thread's current device must be `device`.
+hipError_t static_scratch(int device, void **ptr) {
+    if (device < 0 || device >= mukv::kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = p;
+    }
+    *ptr = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 // most kept tokens one super-patch can hold: the last super-patch is the longest
 int patch_cap(const Ctx &c) {
@@ -199,6 +223,10 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     DeviceScope dev(cfg->device_id);
     if (!dev.ok) return MUKV_ERR_HIP;
 
+    {
+        void *unused = nullptr; // the static scratch's address on this device, resolved once here
+        if (static_scratch(cfg->device_id, &unused) != hipSuccess) return MUKV_ERR_HIP;
+    }
     mukv_ctx *h = new (std::nothrow) mukv_ctx();
     if (!h) return MUKV_ERR_HIP;
     Ctx &c = h->c;
@@ -649,6 +677,36 @@ int mukv_prefill_attend(mukv_ctx *ctx, int32_t layer, const void *q, int32_t n_q
     return mukv::launch_attend(c, layer, q, n_q, frame_idx, k_frame, k_local, v_local, local_offsets, B, causal_local, out,
                                att_signal_out, static_cast<float *>(workspace),
                                reinterpret_cast<hipStream_t>(stream)) == hipSuccess
+               ? MUKV_OK
+               : MUKV_ERR_HIP;
+}
+
+int mukv_prefill_attend_static(mukv_ctx *ctx, int32_t layer, const void *q, int32_t n_q, const int32_t *frame_idx,
+                               int32_t k_frame, const void *k_local, const void *v_local, const int32_t *local_offsets,
+                               int32_t B, int32_t causal_local, void *out, float *att_signal_out, void *stream) {
+    if (!ctx || !q || !out || !att_signal_out || !k_local || !v_local || !local_offsets) return MUKV_ERR_INVALID_ARG;
+    Ctx &c = ctx->c;
+    if (layer < 0 || layer >= c.cfg.n_layers) return MUKV_ERR_INVALID_ARG;
+    if (causal_local != 0 && causal_local != 1) return MUKV_ERR_INVALID_ARG;
+    if (k_frame > 0 && !frame_idx) return MUKV_ERR_INVALID_ARG;
+    const int rc0 = prefill_shape_check(c, n_q, k_frame, B);
+    if (rc0 != MUKV_OK) return rc0;
+    if (mukv::prefill_workspace_bytes(c, n_q, B, k_frame) > (int64_t)MUKV_STATIC_SCRATCH_BYTES) return MUKV_ERR_CAPACITY;
+    if ((reinterpret_cast<uintptr_t>(q) & 15) || (reinterpret_cast<uintptr_t>(out) & 15) ||
+        (reinterpret_cast<uintptr_t>(k_local) & 15) || (reinterpret_cast<uintptr_t>(v_local) & 15))
+        return MUKV_ERR_UNSUPPORTED;
+    {
+        const int rc = flush_pending(c, true, reinterpret_cast<hipStream_t>(stream));
+        if (rc != MUKV_OK) return rc;
+    }
+    DeviceScope dev(c.cfg.device_id);
+    if (!dev.ok) return MUKV_ERR_HIP;
+    void *ws = nullptr; // this device's copy of the array (resolved at mukv_create; a look-up here)
+    if (static_scratch(c.cfg.device_id, &ws) != hipSuccess) return MUKV_ERR_HIP;
+    // every float of the scratch that a kernel of this call reads was written by an earlier kernel of
+    // the same call, so what the previous call left behind needs no clearing
+    return mukv::launch_attend(c, layer, q, n_q, frame_idx, k_frame, k_local, v_local, local_offsets, B, causal_local, out,
+                               att_signal_out, static_cast<float *>(ws), reinterpret_cast<hipStream_t>(stream)) == hipSuccess
                ? MUKV_OK
                : MUKV_ERR_HIP;
 }
