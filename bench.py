@@ -25,10 +25,22 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
-# HBM bytes actually moved per algorithmic byte, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs on the 1-hour shape (512 frames per launch), calibrated with a plain copy kernel; the
-# summary of those runs is kept under profiles/.
-TRAFFIC_PER_ALGORITHMIC = {"compact": 1409.5 / 1409.2, "copy_freq": 1513.7 / 1512.4, "gather": 88.2 / 88.08}
+# HBM bytes actually moved per algorithmic byte, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# on the 1-hour shape, calibrated with a plain copy kernel.  The figures live in ONE place: lines
+# "traffic_ratio <kernel> <moved MB> / <algorithmic MB>" of the summary of those runs under profiles/.
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "traffic_probe_hbm_counters.md")
+
+
+def traffic_ratios():
+    out = {}
+    try:
+        for line in open(TRAFFIC_SUMMARY):
+            t = line.split()
+            if len(t) >= 5 and t[0] == "traffic_ratio" and t[3] == "/":
+                out[t[1]] = float(t[2]) / float(t[4])
+    except (OSError, ValueError):
+        pass
+    return out
 
 
 def cpu_model():
@@ -212,9 +224,23 @@ def main():
     b_tok = 2 * Hkv * D * esz                      # K+V bytes of one token in one layer
     copy_frame = 2 * kappa * L * b_tok             # kept rows of one frame, read + written
     freq_frame = P * Hkv * D * esz                 # scoring-layer keys of one frame, read once
-    per_batch = a.batch_chunks * chunk
-    batches = [min(per_batch, n_frames - f0) for f0 in range(0, n_frames, per_batch)]
-    if a.overlap_copy and prof["copy_freq"]["launches"]:
+    # frames per batch, by the library's rule: batch_chunks chunks each, the first two batches of a stream 3/8 of
+    # that when the copies are put off (they have no copy to share a launch with)
+    batches, left = [], n_chunks
+    while left:
+        lim = a.batch_chunks * 3 // 8 if (a.overlap_copy and a.batch_chunks >= 8 and len(batches) < 2) else a.batch_chunks
+        batches.append(min(lim, left))
+        left -= batches[-1]
+    batches = [min(b * chunk, n_frames - sum(batches[:i]) * chunk) for i, b in enumerate(batches)]
+    att_frame = P * D * esz * (Hq + Hkv)           # queries and keys of the scoring layer, read once
+    chain_ok = [n * Hq >= 1792 for n in batches]    # batches the one-launch chain takes (the library's own rule)
+    if a.overlap_copy and prof["chain"]["launches"]:
+        # ONE launch per batch: the rows of batch i-2 copied, Eq. 2-3 and Eq. 1 of batch i
+        dom, dom_kernel = "chain", "chain_kernel"
+        idx = [i for i in range(len(batches)) if chain_ok[i]]
+        assert prof[dom]["launches"] == len(idx)
+        dom_bytes = sum((copy_frame * batches[i - 2] if i >= 2 else 0) + att_frame * batches[i] for i in idx) / len(idx)
+    elif a.overlap_copy and prof["copy_freq"]["launches"]:
         # the launch that copies batch i-2's rows and computes batch i's frequency signal
         dom, dom_kernel = "copy_freq", "copy_freq_kernel"
         assert prof[dom]["launches"] == len(batches) - 2
@@ -226,6 +252,7 @@ def main():
     dom_gbs = dom_bytes / (dom_us * 1e-6) / 1e9
     gather_bytes = 2 * B * w.k_frame * kappa * L * b_tok
     gather_us = per_kernel["gather"]
+    ratios = traffic_ratios()
     gather_gbs = gather_bytes / (gather_us * 1e-6) / 1e9
     # whole-path algorithmic bytes: signals' inputs + kept rows in and out
     path_bytes_frame = P * D * esz * (Hq + Hkv) + 2 * kappa * L * b_tok
@@ -260,11 +287,11 @@ def main():
         "kernel_us": per_kernel,
         "roofline": {"kernel": dom_kernel, "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS,
-                     "traffic": dom_bytes * TRAFFIC_PER_ALGORITHMIC[dom],
+                     "traffic": dom_bytes * ratios[dom] if dom in ratios else None,
                      "bytes_per_launch": dom_bytes, "us_per_launch": dom_us},
         "roofline_gather": {"kernel": "gather_kv_kernel", "bound": "hbm", "achieved": gather_gbs, "peak": HBM_PEAK_GBS,
                             "unit": "GB/s", "frac": gather_gbs / HBM_PEAK_GBS,
-                            "traffic": gather_bytes * TRAFFIC_PER_ALGORITHMIC["gather"],
+                            "traffic": gather_bytes * ratios["gather"] if "gather" in ratios else None,
                             "bytes_per_launch": gather_bytes, "us_per_launch": gather_us},
         "setup_s": {"generate_stream": t_gen},
         # the paper's device-independent proxies (Sec. 4.1): tokens held in the cache, tokens handed to the LLM

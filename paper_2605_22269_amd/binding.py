@@ -62,7 +62,7 @@ class mukv_state(C.Structure):
     ]
 
 
-KERNEL_NAMES = ("att", "freq", "select", "refine", "compact", "poolq", "score", "rerank", "gather", "copy_freq")
+KERNEL_NAMES = ("att", "freq", "select", "refine", "compact", "poolq", "score", "rerank", "gather", "copy_freq", "chain")
 
 
 class mukv_profile(C.Structure):

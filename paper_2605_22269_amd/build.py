@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmukv.so")
-SOURCES = ["api.hip", "compress.hip", "att_mfma.hip", "retrieve.hip", "attend.hip"]  # traffic_probe.cpp is a separate program
+SOURCES = ["api.hip", "compress.hip", "att_mfma.hip", "retrieve.hip", "attend.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [
@@ -28,13 +28,13 @@ def build_lib(verbose: bool = False) -> str:
     return LIB
 
 
-PROBE = os.path.join(PKG, "traffic_probe")
+PROBE = os.path.join(ROOT, "traffic_probe")  # measurement driver, beside bench.py, not part of the library
 
 
 def build_probe(verbose: bool = False) -> str:
     """Small torch-free driver used for rocprofv3 hardware-counter runs (see profiles/)."""
-    cmd = [HIPCC, "-O2", "-std=c++17", "-I", os.path.join(ROOT, "include"), os.path.join(CSRC, "traffic_probe.cpp"),
-           "-o", PROBE, "-L", PKG, "-lmukv", "-Wl,-rpath,$ORIGIN"]
+    cmd = [HIPCC, "-O2", "-std=c++17", "-I", os.path.join(ROOT, "include"), os.path.join(ROOT, "traffic_probe.cpp"),
+           "-o", PROBE, "-L", PKG, "-lmukv", "-Wl,-rpath,$ORIGIN/paper_2605_22269_amd"]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
@@ -45,7 +45,7 @@ def stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(ROOT, "include", "mukv.h")]
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(ROOT, "include", h) for h in ("mukv.h", "mukv_measure.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

@@ -68,7 +68,7 @@ int validate_config(const mukv_config *cfg) {
     if ((int64_t)cfg->n_kv_heads * cfg->head_dim > 1024) return MUKV_ERR_UNSUPPORTED;
     const int esz = cfg->dtype == MUKV_BF16 ? 2 : 4;
     if (!large_unit &&
-        mukv::att_generic_lds_bytes(cfg->tokens_per_frame, cfg->head_dim, sizeof(double)) > 160 * 1024)
+        mukv::att_generic_lds_bytes(cfg->tokens_per_frame, cfg->head_dim, sizeof(double), sizeof(float)) > 160 * 1024)
         return MUKV_ERR_UNSUPPORTED;
     if ((cfg->head_dim * esz) % 16) return MUKV_ERR_UNSUPPORTED;
     if (((int64_t)cfg->max_frames + cfg->frames_per_segment - 1) / cfg->frames_per_segment > 65536)
@@ -123,6 +123,8 @@ void free_all(Ctx &c) {
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (c.side) (void)hipStreamDestroy(c.side);
+    for (hipEvent_t ev : c.ev_keep)
+        if (ev) (void)hipEventDestroy(ev);
     if (c.ev_fork) (void)hipEventDestroy(c.ev_fork);
     for (hipEvent_t ev : c.ev_join)
         if (ev) (void)hipEventDestroy(ev);
@@ -289,6 +291,9 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(dalloc(&c.flag_count, 2));
     if (e == hipSuccess) ok(hipMemset(c.flag_count, 0, 2 * sizeof(int32_t)));
     ok(hipStreamCreateWithFlags(&c.side, hipStreamNonBlocking));
+    c.split_side = cfg->overlap_copy != 0 && cfg->tokens_per_frame <= mukv::kMaxP;
+    if (c.split_side)
+        for (int par = 0; par < 2; ++par) ok(hipEventCreateWithFlags(&c.ev_keep[par], hipEventDisableTiming));
     ok(hipEventCreateWithFlags(&c.ev_fork, hipEventDisableTiming));
     c.deferred = new (std::nothrow) mukv::ChunkArgs[2];
     ok(hipEventCreateWithFlags(&c.ev_copy, hipEventDisableTiming));
@@ -382,12 +387,22 @@ int mukv_reset(mukv_ctx *ctx) {
     if (!ctx) return MUKV_ERR_INVALID_ARG;
     ctx->c.n_frames = 0;
     ctx->c.n_done = 0;
+    ctx->c.batches_since_reset = 0;
     ctx->c.pending->clear();
     if (ctx->c.n_deferred) { // the rows they would have copied are forgotten with the rest
         DeviceScope dev(ctx->c.cfg.device_id);
         if (!dev.ok || mukv::drop_deferred(ctx->c) != hipSuccess) return MUKV_ERR_HIP;
     }
     return MUKV_OK;
+}
+
+// Chunks that make the next batch.  With overlap_copy the copy of a batch's rows shares a launch with
+// the signals of the batch after next, so the first two batches of a stream have no copy to run beside
+// and the last two copies no signals: those first two batches are cut to 3/8 of batch_chunks, which
+// moves most of their work into launches that do have a copy beside them.
+static int batch_limit(const Ctx &c) {
+    if (c.cfg.overlap_copy && c.batch_chunks >= 8 && c.batches_since_reset < 2) return c.batch_chunks * 3 / 8;
+    return c.batch_chunks;
 }
 
 // Enqueues the kernels for every chunk gathered so far (on the stream they were submitted with).
@@ -430,6 +445,7 @@ static int flush_pending(Ctx &c, bool join, hipStream_t join_stream) {
     c.batch_parity ^= 1;
     c.pending->clear();
     c.n_done += nf;
+    ++c.batches_since_reset;
     DeviceScope dev(c.cfg.device_id);
     if (!dev.ok) return MUKV_ERR_HIP;
     if (mukv::launch_compress(c, a, c.p_stream) != hipSuccess) return MUKV_ERR_HIP;
@@ -500,7 +516,7 @@ int mukv_compress_chunk(mukv_ctx *ctx, const void *k, const void *v, const mukv_
     c.p_q_st = q_st;
     c.pending->push_back(pc);
     c.n_frames += n_frames;
-    if ((int)c.pending->size() >= c.batch_chunks) return flush_pending(c, false, nullptr);
+    if ((int)c.pending->size() >= batch_limit(c)) return flush_pending(c, false, nullptr);
     return MUKV_OK;
 }
 

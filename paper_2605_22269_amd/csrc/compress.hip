@@ -9,6 +9,9 @@
 //                                      the same three steps in fp64, only for frames whose
 //                                      fp32 selection margin is below the threshold
 //   compact                            copy of the kept rows of all layers; segment keys
+#include <cstring>
+
+#include "att_mfma_dev.h"
 #include "mukv_internal.h"
 
 namespace mukv {
@@ -126,12 +129,13 @@ __device__ __forceinline__ void freq_body(const PtrTable &ktab, const FrameMap &
     const int slot = find_slot(map, f);
     const T *k = reinterpret_cast<const T *>(ktab.p[slot]) + k_off + (int64_t)(f - map.fstart[slot]) * P * st;
     // the workgroup's waves walk over the frame's tokens, GROUPS tokens per wave and step
-    const int stride = bpf * 4 * GROUPS;
+    const int n_waves = blockDim.x >> 6;
+    const int stride = bpf * n_waves * GROUPS;
     // Up to four heads of a token are transformed together (independent butterflies hide the
     // lane-exchange latency), and the key elements of the next group are loaded before the
     // current group is computed.
     constexpr int GH = 4;
-    const int t_first = (by * 4 + wave) * GROUPS;
+    const int t_first = (by * n_waves + wave) * GROUPS;
     auto load_group = [&](int t0, int g0, T *a0, T *a1) {
         const int tok = t0 + sub < P ? t0 + sub : P - 1;
         const T *r = k + (int64_t)tok * st + 2 * p;
@@ -352,6 +356,28 @@ __device__ __forceinline__ double exp_t(double x) { return exp(x); }
 
 constexpr int kGenQ = 16; // queries per round of a workgroup: 4 waves x 4
 
+// How the generic attention kernel keeps a frame's keys in LDS.  The fp32 pass, which runs on every
+// frame, keeps them expanded to float (its inner loop lives on LDS bandwidth).  The fp64 pass runs on a
+// few listed frames beside the next batch's kernels, whose workgroups leave less than half of a compute
+// unit's LDS free: it keeps bf16 keys as they are (half the room; the expansion is a shift).
+template <typename T, typename R>
+struct KeyStage {
+    typedef float type;
+    static constexpr int pad = 4;
+};
+template <>
+struct KeyStage<uint16_t, double> {
+    typedef uint16_t type;
+    static constexpr int pad = 8;
+};
+__device__ __forceinline__ float4 key4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ float4 key4(const uint16_t *p) {
+    const uint2 raw = *reinterpret_cast<const uint2 *>(p);
+    return make_float4(__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xffff0000u), __uint_as_float(raw.y << 16),
+                       __uint_as_float(raw.y & 0xffff0000u));
+}
+__device__ __forceinline__ void stage_keys(u32x4 raw, uint16_t *dst) { *reinterpret_cast<u32x4 *>(dst) = raw; }
+
 template <typename T, typename R>
 __global__ __launch_bounds__(256) void att_generic_kernel(PtrTable qtab, PtrTable ktab, FrameMap map, int64_t k_off,
                                                           int64_t q_sh, int64_t q_st, int64_t k_sh, int64_t k_st,
@@ -365,12 +391,11 @@ __global__ __launch_bounds__(256) void att_generic_kernel(PtrTable qtab, PtrTabl
     const int n_e = flag_list ? *flag_count : (int)gridDim.x;
     for (int e_idx = blockIdx.x; e_idx < n_e; e_idx += gridDim.x) {
     const int f = flag_list ? flag_list[e_idx] : e_idx;
-    const int ldk = D + 4; // 16-byte aligned rows; 4-word lane stride keeps 16 lanes on distinct banks
-    float *Ks = reinterpret_cast<float *>(smem_raw);   // [P][D+4]
-    float *qs = Ks + (size_t)P * ldk;                   // [kGenQ][D]
-    size_t n_fl = (size_t)P * ldk + kGenQ * D;
-    n_fl += n_fl & 1;
-    R *part = reinterpret_cast<R *>(Ks + n_fl);        // [4][P], 8-byte aligned
+    typedef typename KeyStage<T, R>::type KT;
+    const int ldk = D + KeyStage<T, R>::pad; // 16-byte aligned rows; 4-word lane stride keeps 16 lanes on distinct banks
+    KT *Ks = reinterpret_cast<KT *>(smem_raw);          // [P][ldk]
+    float *qs = reinterpret_cast<float *>(smem_raw + att_generic_key_bytes(P, D, sizeof(KT))); // [kGenQ][D]
+    R *part = reinterpret_cast<R *>(qs + kGenQ * D);    // [4][P], 8-byte aligned
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int slot = find_slot(map, f);
@@ -397,7 +422,10 @@ __global__ __launch_bounds__(256) void att_generic_kernel(PtrTable qtab, PtrTabl
             const int u = u0 + b * 256;
             if (u < n_ku) {
                 const int j = u / upr, c = u - j * upr;
-                unpack_to_float<T>(raw[b], Ks + j * ldk + c * EPU);
+                if constexpr (sizeof(KT) == sizeof(float))
+                    unpack_to_float<T>(raw[b], reinterpret_cast<float *>(Ks) + j * ldk + c * EPU);
+                else
+                    stage_keys(raw[b], Ks + j * ldk + c * EPU);
             }
         }
     }
@@ -433,7 +461,7 @@ __global__ __launch_bounds__(256) void att_generic_kernel(PtrTable qtab, PtrTabl
 #pragma unroll
             for (int u = 0; u < 4; ++u) qv[u] = *reinterpret_cast<const float4 *>(qr + u * D + d);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) kv[t] = *reinterpret_cast<const float4 *>(Ks + jrow[t] + d);
+            for (int t = 0; t < 4; ++t) kv[t] = key4(Ks + jrow[t] + d);
 #pragma unroll
             for (int t = 0; t < 4; ++t)
 #pragma unroll
@@ -1084,6 +1112,9 @@ struct CompactArgs {
     double *ssum_k, *ssum_v;     // running exact sums per segment
     int64_t frame0;
     float *rep_seg_k, *rep_seg_v;
+    // copy by runs (copy_run_body): the batch's slots all hold fpc frames (the last one may hold fewer)
+    int n_frames, fpc;
+    uint32_t magic_kappa, magic_fpc; // floor(2^32 / d) + 1: n / d = umulhi(n, magic) while n * d < 2^32
 };
 
 // Adds the batch's exact per-frame sums to a segment's running fp64 sums and refreshes its keys.
@@ -1091,12 +1122,16 @@ struct CompactArgs {
 // slice one batch of independent loads, the four partial sums joined through LDS (the sums are
 // exact, so their order does not matter).
 constexpr int kSegChan = 64;
-__device__ __forceinline__ void segment_update(const CompactArgs &a, int job) {
-    __shared__ double part_k[4][kSegChan], part_v[4][kSegChan];
+constexpr int kSegLdsDoubles = 2 * 4 * kSegChan; // LDS the caller lends: part_k[4][64], part_v[4][64]
+__device__ __forceinline__ void segment_update(const CompactArgs &a, int job, double *lds) {
+    double(*part_k)[kSegChan] = reinterpret_cast<double(*)[kSegChan]>(lds);
+    double(*part_v)[kSegChan] = reinterpret_cast<double(*)[kSegChan]>(lds + 4 * kSegChan);
     const int n_cg = (a.C + kSegChan - 1) / kSegChan;
     const int s = a.seg_first + job / n_cg;
     const int c = (job % n_cg) * kSegChan + (threadIdx.x & (kSegChan - 1));
+    // up to four slices of frames side by side: the first 256 threads of the workgroup, or all of a smaller one
     const int slice = threadIdx.x / kSegChan;
+    const int n_slices = blockDim.x >= 4 * kSegChan ? 4 : (int)blockDim.x / kSegChan;
     const int64_t f0 = (int64_t)s * a.F;
     const int64_t f1 = (f0 + a.F < a.n_total) ? f0 + a.F : a.n_total;
     const int64_t fa = f0 > a.frame0 ? f0 : a.frame0; // first frame of the segment in this batch
@@ -1104,24 +1139,28 @@ __device__ __forceinline__ void segment_update(const CompactArgs &a, int job) {
     const double den = (double)(f1 - f0) * (double)a.kappa;
     const int cc = c < a.C ? c : a.C - 1;
     double sk = 0.0, sv = 0.0;
-    for (int64_t fb = fa + slice; fb < f1; fb += 32) {
+    for (int64_t fb = fa + slice; slice < n_slices && fb < f1; fb += 8 * n_slices) {
         double tk[8], tv[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int64_t fr = fb + 4 * u < f1 ? fb + 4 * u : f1 - 1; // clamped: loads stay unconditional
+            const int64_t fr = fb + n_slices * u < f1 ? fb + n_slices * u : f1 - 1; // clamped: loads stay unconditional
             tk[u] = a.fsum_k[fr * a.C + cc];
             tv[u] = a.fsum_v[fr * a.C + cc];
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            if (fb + 4 * u < f1) {
+            if (fb + n_slices * u < f1) {
                 sk += tk[u];
                 sv += tv[u];
             }
         }
     }
-    part_k[slice][threadIdx.x & (kSegChan - 1)] = sk;
-    part_v[slice][threadIdx.x & (kSegChan - 1)] = sv;
+    if (slice < 4) { // slices that do not exist contribute zeros
+        part_k[slice][threadIdx.x & (kSegChan - 1)] = sk;
+        part_v[slice][threadIdx.x & (kSegChan - 1)] = sv;
+    }
+    if (n_slices < 4 && threadIdx.x < kSegChan)
+        for (int sl = n_slices; sl < 4; ++sl) part_k[sl][threadIdx.x] = part_v[sl][threadIdx.x] = 0.0;
     __syncthreads();
     if (slice == 0 && c < a.C) {
         sk = (fresh ? 0.0 : a.ssum_k[(int64_t)s * a.C + c]) + ((part_k[0][threadIdx.x] + part_k[1][threadIdx.x]) + (part_k[2][threadIdx.x] + part_k[3][threadIdx.x]));
@@ -1135,9 +1174,9 @@ __device__ __forceinline__ void segment_update(const CompactArgs &a, int job) {
 
 // Work of workgroup (gx_i, y) of compact_kernel's grid.
 template <typename V, int ITER>
-__device__ __forceinline__ void compact_body(const CompactArgs &a, int gx_i, int y) {
+__device__ __forceinline__ void compact_body(const CompactArgs &a, int gx_i, int y, double *seg_lds, int NT = 256) {
     if (y >= a.n_slab) {
-        if (gx_i == 0) segment_update(a, y - a.n_slab);
+        if (gx_i == 0) segment_update(a, y - a.n_slab, seg_lds);
         return;
     }
     const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
@@ -1145,7 +1184,7 @@ __device__ __forceinline__ void compact_body(const CompactArgs &a, int gx_i, int
     const int slot = gx_i / a.bps, bx = gx_i - slot * a.bps;
     const int f_lo = a.map.fstart[slot];
     const int n_units = (a.map.fstart[slot + 1] - f_lo) * a.units_per_frame;
-    if (bx * (256 * ITER) >= n_units) return;
+    if (bx * (NT * ITER) >= n_units) return;
     const unsigned char *src = reinterpret_cast<const unsigned char *>(kv ? a.v.p[slot] : a.k.p[slot]) +
                                (int64_t)l * a.sl_b + (int64_t)g * a.sh_b;
     unsigned char *dst = (kv ? a.store_v : a.store_k) + ((int64_t)l * a.Hkv + g) * a.slab_b + a.dst_off_b +
@@ -1156,30 +1195,79 @@ __device__ __forceinline__ void compact_body(const CompactArgs &a, int gx_i, int
     // row reads) so that they overlap; only the stores are predicated.
     V tmp[ITER];
     int row_tok[ITER];
-    const int u0 = bx * (256 * ITER) + threadIdx.x;
+    const int u0 = bx * (NT * ITER) + threadIdx.x;
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
-        int u = u0 + it * 256;
+        int u = u0 + it * NT;
         u = u < n_units ? u : n_units - 1;
         row_tok[it] = src_tok[u >> a.log_upr];
     }
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
-        int u = u0 + it * 256;
+        int u = u0 + it * NT;
         u = u < n_units ? u : n_units - 1;
         const int tok = row_tok[it] < 0 ? 0 : row_tok[it]; // -1: a frame left to the fp64 pass
         tmp[it] = *reinterpret_cast<const V *>(src + (int64_t)tok * a.st_b + (int64_t)(u & mask) * sizeof(V));
     }
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
-        const int u = u0 + it * 256;
+        const int u = u0 + it * NT;
+        if (u < n_units && row_tok[it] >= 0) *reinterpret_cast<V *>(dst + (int64_t)u * sizeof(V)) = tmp[it];
+    }
+}
+
+// The same copy cut into runs of blockDim.x * ITER consecutive 16-byte units of a slab's destination,
+// whatever slots they come from: workgroup (run, y) moves units run * blockDim.x * ITER ... of slab y.
+// For batches whose slots hold the same number of frames (a stream fed in equal chunks), so that a unit's
+// slot is a division; a lane looks up its row and its chunk's base pointer (the tables are kernel
+// arguments: a load from the argument block) side by side, then all its rows are in flight together.
+// (A workgroup that walks several such runs as a software pipeline -- look-ups two rounds ahead of the
+// stores, two rounds of rows in flight -- was measured beside the attention workgroups and was slower
+// for every pipeline length: 497-577 us against 466-483 us for the launch with a full copy.)
+template <int ITER>
+__device__ __forceinline__ void copy_run_body(const CompactArgs &a, int run, int y) {
+    typedef u32x4 V;
+    const int NT = blockDim.x;
+    const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
+    const int kv = rem / a.Hkv, g = rem - kv * a.Hkv;
+    const int n_units = a.n_frames * a.units_per_frame;
+    const int u0 = run * (NT * ITER) + threadIdx.x;
+    if (run * (NT * ITER) >= n_units) return;
+    const int64_t slab_src = (int64_t)l * a.sl_b + (int64_t)g * a.sh_b;
+    unsigned char *dst = (kv ? a.store_v : a.store_k) + ((int64_t)l * a.Hkv + g) * a.slab_b + a.dst_off_b;
+    const void *const *tab = kv ? a.v.p : a.k.p;
+    const int mask = (1 << a.log_upr) - 1;
+    int row_tok[ITER];
+    const unsigned char *base[ITER];
+    V tmp[ITER];
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        int u = u0 + it * NT;
+        u = u < n_units ? u : n_units - 1;
+        const unsigned row = (unsigned)u >> a.log_upr;       // kept row of the batch: frame * kappa + rank
+        row_tok[it] = a.src_tok[row];
+        const unsigned f = __umulhi(row, a.magic_kappa);     // batch frame
+        const unsigned slot = __umulhi(f, a.magic_fpc);
+        base[it] = static_cast<const unsigned char *>(tab[slot]);
+    }
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        int u = u0 + it * NT;
+        u = u < n_units ? u : n_units - 1;
+        const int tok = row_tok[it] < 0 ? 0 : row_tok[it];
+        tmp[it] = *reinterpret_cast<const V *>(base[it] + slab_src + (int64_t)tok * a.st_b + (int64_t)(u & mask) * sizeof(V));
+    }
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        const int u = u0 + it * NT;
         if (u < n_units && row_tok[it] >= 0) *reinterpret_cast<V *>(dst + (int64_t)u * sizeof(V)) = tmp[it];
     }
 }
 
 template <typename V, int ITER>
 __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a) {
-    compact_body<V, ITER>(a, blockIdx.x, blockIdx.y);
+    __shared__ double seg_lds[kSegLdsDoubles];
+    compact_body<V, ITER>(a, blockIdx.x, blockIdx.y, seg_lds);
 }
 
 // overlap_copy: the copy of the previous batch's kept rows (HBM bound) and the frequency signal of
@@ -1203,6 +1291,7 @@ struct FreqPart {
 // kernel trace.)
 template <typename T, int D, bool kUnit>
 __global__ __launch_bounds__(256) void copy_freq_kernel(CompactArgs ca, int copy_gx, FreqPart fp, int period) {
+    __shared__ double seg_lds[kSegLdsDoubles];
     const int b = blockIdx.x;
     const int q = b / period, r = b - q * period;
     if (r == 0 && q < fp.n_wg) {
@@ -1213,9 +1302,60 @@ __global__ __launch_bounds__(256) void copy_freq_kernel(CompactArgs ca, int copy
         const int cid = b - before;
         const int n_rows = copy_gx * ca.n_slab; // then one workgroup per segment job
         if (cid < n_rows)
-            compact_body<u32x4, kFusedCopyIter>(ca, cid % copy_gx, cid / copy_gx);
+            compact_body<u32x4, kFusedCopyIter>(ca, cid % copy_gx, cid / copy_gx, seg_lds);
         else
-            segment_update(ca, cid - n_rows);
+            segment_update(ca, cid - n_rows, seg_lds);
+    }
+}
+
+// overlap_copy with the matrix-core attention kernel: ONE launch per batch carries the copy of an earlier
+// batch's kept rows (HBM bound), the frequency signal of the new batch (arithmetic bound, little
+// traffic) and the attention signal of the new batch (arithmetic and issue bound while it streams all
+// the queries), so that on every compute unit waves waiting for memory and waves busy with arithmetic
+// are resident together and the launch as a whole runs at the pace of its HBM traffic.
+// The attention workgroup fixes the launch shape: its block size (64 * waves) and its LDS (80 KB for
+// 196 tokens), so two workgroups of any kind share a compute unit; the copy workgroups make up for
+// their small number with ITER 16-byte loads in flight per lane.  No workgroup here owns static LDS: the
+// segment jobs borrow the dynamic block.
+// 1-D grid.  Attention workgroups -- by far the longest -- sit at multiples of att_period inside the
+// first part of the grid so that the last of them starts well before the end; among the others every
+// freq_period-th is a frequency workgroup.  Both periods are odd: workgroup b lands on XCD b % 8, and an
+// even period would put a whole kind of work on half of the chip.
+struct ChainMap {
+    int n_att, att_period;   // attention workgroups at b = i * att_period, i < n_att
+    int n_freq, freq_period; // among the rest (in order): frequency workgroups at r = i * freq_period, i < n_freq
+    int copy_gx, n_copy_rows; // then compact_kernel's (copy_gx, n_slab) grid, then the segment jobs
+};
+
+template <int ITER, bool RUNS>
+__global__ __launch_bounds__(448) __attribute__((amdgpu_waves_per_eu(4, 4))) void chain_kernel(CompactArgs ca, FreqPart fp, PtrTable qtab,
+                                                                                              AttMfmaArgs aa, ChainMap cm) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const int b = blockIdx.x;
+    const int ia = b / cm.att_period;
+    if (ia < cm.n_att && b == ia * cm.att_period) {
+        att_mfma_body(qtab, fp.k, fp.map, aa, ia / aa.n_part, ia % aa.n_part, smem_raw);
+        return;
+    }
+    // attention workgroups with a lower number: those at 0, att_period, ... below b
+    const int a_before = ia + 1 < cm.n_att ? ia + 1 : cm.n_att;
+    const int r = b - a_before;
+    const int jf = r / cm.freq_period;
+    if (jf < cm.n_freq && r == jf * cm.freq_period) {
+        freq_body<uint16_t, float, 128>(fp.k, fp.map, fp.k_off, fp.sh, fp.st, fp.Hkv, fp.P, nullptr, nullptr, fp.out,
+                                        jf % fp.n_frames, jf / fp.n_frames, fp.n_frames, fp.bpf);
+        return;
+    }
+    const int f_before = jf + 1 < cm.n_freq ? jf + 1 : cm.n_freq;
+    const int cid = r - f_before;
+    double *seg_lds = reinterpret_cast<double *>(smem_raw);
+    if (cid < cm.n_copy_rows) {
+        if constexpr (RUNS)
+            copy_run_body<ITER>(ca, cid % cm.copy_gx, cid / cm.copy_gx);
+        else
+            compact_body<u32x4, ITER>(ca, cid % cm.copy_gx, cid / cm.copy_gx, seg_lds, blockDim.x);
+    } else {
+        segment_update(ca, cid - cm.n_copy_rows, seg_lds);
     }
 }
 
@@ -1227,7 +1367,8 @@ __global__ __launch_bounds__(256) void compact_listed_kernel(CompactArgs a, cons
                                                              const int32_t *__restrict__ flag_count) {
     const int y = blockIdx.y;
     if (y >= a.n_slab) {
-        if (blockIdx.x == 0 && blockIdx.z == 0) segment_update(a, y - a.n_slab);
+        __shared__ double seg_lds[kSegLdsDoubles];
+        if (blockIdx.x == 0 && blockIdx.z == 0) segment_update(a, y - a.n_slab, seg_lds);
         return;
     }
     const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
@@ -1316,10 +1457,8 @@ static hipError_t launch_freq(const Ctx &c, const ChunkArgs &a, bool listed, R *
     return hipGetLastError();
 }
 
-size_t att_generic_lds_bytes(int P, int D, size_t r_size) {
-    size_t floats = (size_t)P * (D + 4) + kGenQ * D;
-    floats += floats & 1;
-    return floats * 4 + (size_t)4 * P * r_size;
+size_t att_generic_lds_bytes(int P, int D, size_t r_size, size_t key_size) {
+    return att_generic_key_bytes(P, D, key_size) + (size_t)kGenQ * D * 4 + (size_t)4 * P * r_size;
 }
 
 template <typename T, typename R>
@@ -1329,7 +1468,7 @@ static hipError_t launch_att_generic(const Ctx &c, const ChunkArgs &a, bool list
     const int q_per_block = 2 * kGenQ; // two rounds per workgroup
     const int qsplit = (P + q_per_block - 1) / q_per_block;
     *n_part = c.cfg.n_q_heads * qsplit;
-    const size_t lds = att_generic_lds_bytes(P, D, sizeof(R));
+    const size_t lds = att_generic_lds_bytes(P, D, sizeof(R), sizeof(typename KeyStage<T, R>::type));
     static bool lds_ok[kMaxDevices]; // per instantiation
     const hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(&att_generic_kernel<T, R>), 160 * 1024,
                                             c.cfg.device_id, lds_ok);
@@ -1374,7 +1513,8 @@ static hipError_t launch_select(const Ctx &c, const ChunkArgs &a, const R *att, 
     s.kept_idx = c.kept_idx;
     // with overlap_copy the rows chosen by the fp64 pass replace the marks of the first pass: the
     // copy, which comes later, then takes every frame in one go
-    s.src_tok = (pass2 && !c.cfg.overlap_copy) ? c.src_tok2 : c.src_tok[a.parity];
+    // (a batch's main copy comes after its fp64 pass only with overlap_copy on units of several frames)
+    s.src_tok = (pass2 && (!c.cfg.overlap_copy || c.split_side)) ? c.src_tok2 : c.src_tok[a.parity];
     s.rep_frame_k = c.rep_frame_k;
     s.rep_frame_v = c.rep_frame_v;
     s.rep_patch_k = c.rep_patch_k;
@@ -1408,7 +1548,8 @@ static int ilog2(int x) {
 // mode 0: every frame + segment update (no re-scoring, or a copy that comes after it); 1: main copy, frames on the re-scoring
 // list skipped, no segment update; 2: listed frames only (rows from the fp64 pass) + segment update
 constexpr int kCompactIter = 4;
-static void compact_args(const Ctx &c, const ChunkArgs &a, int mode, int iter, CompactArgs &k, int &gx, int &gy) {
+static void compact_args(const Ctx &c, const ChunkArgs &a, int mode, int iter, CompactArgs &k, int &gx, int &gy,
+                         int threads = 256) {
     const int esz = c.esz, D = c.cfg.head_dim;
     const int row_b = D * esz;
     k.k = a.k;
@@ -1452,7 +1593,7 @@ static void compact_args(const Ctx &c, const ChunkArgs &a, int mode, int iter, C
         const int n = a.map.fstart[s + 1] - a.map.fstart[s];
         max_slot_frames = n > max_slot_frames ? n : max_slot_frames;
     }
-    k.bps = (max_slot_frames * k.units_per_frame + 256 * iter - 1) / (256 * iter);
+    k.bps = (max_slot_frames * k.units_per_frame + threads * iter - 1) / (threads * iter);
     gx = k.bps * a.map.n_slots;
     gy = k.n_slab + (mode == 0 ? n_seg_jobs : 0);
 }
@@ -1513,6 +1654,118 @@ static hipError_t launch_copy_freq(const Ctx &c, const ChunkArgs &prev, int mode
     return hipGetLastError();
 }
 
+// One launch for the copy of batch `prev` (null: none is due yet), Eq. 2-3 and Eq. 1 of batch `a`.
+static bool chain_supported(const Ctx &c, const ChunkArgs &a) {
+    // the matrix-core attention in its many-frames layout (a KV group per workgroup), the feature-axis
+    // indicator, frames as units
+    return c.use_mfma && c.cfg.freq_axis == MUKV_FREQ_FEATURE && c.cfg.tokens_per_frame <= kMaxP &&
+           att_mfma_many(c, a.n_frames);
+}
+
+static int odd_at_most(int64_t x) { // largest odd number <= x, at least 1
+    if (x < 1) return 1;
+    if (x > 0x3fffffff) x = 0x3fffffff;
+    return (int)((x & 1) ? x : x - 1);
+}
+
+static hipError_t launch_chain(const Ctx &c, const ChunkArgs *prev, int copy_mode, const ChunkArgs &a, bool need_fft,
+                               int *n_part, hipStream_t st) {
+    AttMfmaArgs aa;
+    int waves;
+    size_t lds;
+    att_mfma_plan(c, a, c.att_part[a.parity], &aa, &waves, &lds);
+    *n_part = aa.n_part;
+    const int threads = waves * 64;
+    CompactArgs k;
+    std::memset(&k, 0, sizeof(k));
+    int gx = 0, gy = 0, iter = 4;
+    bool runs = false;
+    if (prev) {
+        // equal slots (all but the last): the copy is cut into runs of the destination, 16 units per lane
+        const int fpc = prev->map.fstart[1] - prev->map.fstart[0];
+        runs = fpc > 1 && c.kappa > 1; // (the reciprocal of 1 does not fit the 32-bit multiplier)
+        for (int s = 0; s < prev->map.n_slots && runs; ++s) {
+            const int n = prev->map.fstart[s + 1] - prev->map.fstart[s];
+            runs = s + 1 < prev->map.n_slots ? n == fpc : (n >= 1 && n <= fpc);
+        }
+        runs = runs && (int64_t)prev->n_frames * c.kappa * c.kappa < (1ll << 32) && (int64_t)prev->n_frames * fpc < (1ll << 32);
+    }
+    if (prev && runs) {
+        iter = 16;
+        compact_args(c, *prev, copy_mode, iter, k, gx, gy, threads);
+        k.n_frames = prev->n_frames;
+        k.fpc = prev->map.fstart[1] - prev->map.fstart[0];
+        k.magic_kappa = (uint32_t)((1ull << 32) / (uint32_t)c.kappa) + 1u;
+        k.magic_fpc = (uint32_t)((1ull << 32) / (uint32_t)k.fpc) + 1u;
+        const int64_t per_wg = (int64_t)threads * iter;
+        gx = (int)(((int64_t)k.n_frames * k.units_per_frame + per_wg - 1) / per_wg);
+    } else if (prev) {
+        // 16-byte units a lane moves: as many as the longest slot gives every lane of one workgroup,
+        // within what the attention kernel's register budget leaves (16)
+        int max_slot_frames = 0;
+        for (int s = 0; s < prev->map.n_slots; ++s) {
+            const int n = prev->map.fstart[s + 1] - prev->map.fstart[s];
+            max_slot_frames = n > max_slot_frames ? n : max_slot_frames;
+        }
+        const int64_t units = (int64_t)max_slot_frames * c.kappa * (c.cfg.head_dim * c.esz / 16);
+        const int cand[3] = {16, 7, 4};
+        int64_t best = -1;
+        for (int ci = 0; ci < 3; ++ci) {
+            const int64_t per_wg = (int64_t)threads * cand[ci];
+            const int64_t lanes = (units + per_wg - 1) / per_wg * per_wg; // unit slots launched per (slot, slab)
+            if (best < 0 || lanes * 20 < best * 19) { // a smaller count only when it saves more than 5 % of the lanes
+                best = lanes;
+                iter = cand[ci];
+            }
+        }
+        compact_args(c, *prev, copy_mode, iter, k, gx, gy, threads);
+    }
+    FreqPart fp;
+    fp.k = a.k;
+    fp.map = a.map;
+    fp.k_off = (int64_t)c.ls * a.kv_sl;
+    fp.sh = a.kv_sh;
+    fp.st = a.kv_st;
+    fp.Hkv = c.cfg.n_kv_heads;
+    fp.P = c.cfg.tokens_per_frame;
+    fp.out = c.fft_sig[a.parity];
+    fp.n_frames = a.n_frames;
+    fp.bpf = 4; // with 7 waves per workgroup: 28 tokens of a frame side by side, as in the kernel of its own
+    fp.n_wg = need_fft ? a.n_frames * fp.bpf : 0;
+    ChainMap cm;
+    cm.n_att = a.n_frames * aa.n_part;
+    cm.n_freq = fp.n_wg;
+    cm.copy_gx = gx > 0 ? gx : 1;
+    cm.n_copy_rows = gx * k.n_slab;
+    const int64_t n_copy = (int64_t)cm.n_copy_rows + (prev ? gy - k.n_slab : 0);
+    const int64_t total = (int64_t)cm.n_att + cm.n_freq + n_copy;
+    if (total > 0x7fffffff) return hipErrorInvalidValue;
+    // attention workgroups over the first 7/8 of the grid: the last one to start still has an eighth of
+    // the launch to finish in
+    cm.att_period = odd_at_most(total * 7 / 8 / cm.n_att);
+    cm.freq_period = cm.n_freq ? odd_at_most((total - cm.n_att) / cm.n_freq) : 1;
+#define MUKV_CHAIN(IT, RUNS)                                                                                          \
+    do {                                                                                                              \
+        static bool lds_ok[kMaxDevices];                                                                              \
+        const hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void *>(&chain_kernel<IT, RUNS>),              \
+                                                kAttMfmaMaxLds, c.cfg.device_id, lds_ok);                             \
+        if (ea != hipSuccess) return ea;                                                                              \
+        hipLaunchKernelGGL((chain_kernel<IT, RUNS>), dim3((unsigned)total), dim3(threads), lds, st, k, fp, a.q, aa,   \
+                           cm);                                                                                       \
+    } while (0)
+    if (runs) {
+        MUKV_CHAIN(16, true);
+    } else {
+        switch (iter) {
+        case 16: MUKV_CHAIN(16, false); break;
+        case 7: MUKV_CHAIN(7, false); break;
+        default: MUKV_CHAIN(4, false); break;
+        }
+    }
+#undef MUKV_CHAIN
+    return hipGetLastError();
+}
+
 static hipError_t wait_side(Ctx &c, int parity, hipStream_t st) {
     if (c.side_pending[parity]) {
         hipError_t e = hipStreamWaitEvent(st, c.ev_join[parity], 0);
@@ -1522,9 +1775,58 @@ static hipError_t wait_side(Ctx &c, int parity, hipStream_t st) {
     return hipSuccess;
 }
 
+static hipError_t wait_keep(Ctx &c, int parity, hipStream_t st) {
+    if (c.keep_pending[parity]) {
+        hipError_t e = hipStreamWaitEvent(st, c.ev_keep[parity], 0);
+        if (e != hipSuccess) return e;
+        c.keep_pending[parity] = false;
+    }
+    return hipSuccess;
+}
+
 static hipError_t wait_side_all(Ctx &c, hipStream_t st) {
-    const hipError_t e = wait_side(c, 0, st);
-    return e != hipSuccess ? e : wait_side(c, 1, st);
+    hipError_t e;
+    for (int par = 0; par < 2; ++par) {
+        if ((e = wait_keep(c, par, st)) != hipSuccess) return e;
+        if ((e = wait_side(c, par, st)) != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// split_side: on `side`, behind ev_fork, the keep of batch `a` -- ev_keep marks its end, which is all
+// the copy of the batch's rows waits for -- and then, with re-scoring on, the fp64 chain: Eq. 1-4 redone
+// for the listed frames, their rows copied (the main copy skips them), the batch's segment keys, the
+// list emptied.  One stream for both: the next batch's keep is enqueued behind this chain, which has
+// that batch's whole launch to finish in.  (A second library stream for the chain, forked from `side`
+// inside a stream capture, ended a capture with a crash in the runtime and is not used.)
+template <typename T>
+static hipError_t launch_split_side(Ctx &c, const ChunkArgs &a, int n_part) {
+    hipError_t e;
+    const int par = a.parity;
+    const bool need_att = c.cfg.alpha != 0.0 && !a.have_att_in;
+    const bool need_fft = c.cfg.alpha != 1.0;
+    if ((e = hipStreamWaitEvent(c.side, c.ev_fork, 0)) != hipSuccess) return e;
+    {
+        ProfScope ps(c, MUKV_K_SELECT, c.side);
+        if ((e = launch_select<T, float>(c, a, c.att_part[par], n_part, c.fft_sig[par], 0, c.side)) != hipSuccess) return e;
+    }
+    if ((e = hipEventRecord(c.ev_keep[par], c.side)) != hipSuccess) return e;
+    c.keep_pending[par] = true;
+    if (c.margin_thr > 0.0) {
+        ProfScope ps(c, MUKV_K_REFINE, c.side);
+        int n_part64 = c.cfg.n_q_heads;
+        if (need_att)
+            if ((e = launch_att_generic<T, double>(c, a, true, c.att64, &n_part64, c.side)) != hipSuccess) return e;
+        if (need_fft)
+            if ((e = launch_freq<T, double>(c, a, true, c.fft64, c.side)) != hipSuccess) return e;
+        if ((e = launch_select<T, double>(c, a, c.att64, n_part64, c.fft64, 1, c.side)) != hipSuccess) return e;
+        if ((e = launch_compact(c, a, 2, c.side)) != hipSuccess) return e;
+        hipLaunchKernelGGL(clear_count_kernel, dim3(1), dim3(1), 0, c.side, c.flag_count + par);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if ((e = hipEventRecord(c.ev_join[par], c.side)) != hipSuccess) return e;
+    c.side_pending[par] = true;
+    return hipSuccess;
 }
 
 // The side stream's share of a batch, behind ev_fork (recorded on the caller's stream once the
@@ -1570,6 +1872,11 @@ static hipError_t launch_side(Ctx &c, const ChunkArgs &a, bool with_keep, int n_
 // its keep, on the side stream, must have finished.
 static hipError_t launch_deferred_copy(Ctx &c, const ChunkArgs &d, hipStream_t st) {
     hipError_t e;
+    if (c.split_side) { // the keep is enough; re-scored frames and segment keys are the fp64 chain's
+        if ((e = wait_keep(c, d.parity, st)) != hipSuccess) return e;
+        ProfScope ps(c, MUKV_K_COMPACT, st);
+        return launch_compact(c, d, c.margin_thr > 0.0 ? 1 : 0, st);
+    }
     if ((e = wait_side(c, d.parity, st)) != hipSuccess) return e;
     ProfScope ps(c, MUKV_K_COMPACT, st);
     return launch_compact(c, d, 0, st);
@@ -1617,14 +1924,33 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
     // This batch's parity was last used two batches ago: that batch's keep and fp64 chain must be
     // through with the scratch (they have had a whole batch of launches to do so), and its rows
     // may now be copied.
-    if ((e = wait_side(c, a.parity, st)) != hipSuccess) return e;
+    // (split_side: the keep alone -- the fp64 chain has streams and scratch of its own)
+    if ((e = c.split_side ? wait_keep(c, a.parity, st) : wait_side(c, a.parity, st)) != hipSuccess) return e;
     const bool have_old = c.n_deferred == 2;
+    // split_side: the main copy skips the frames on the re-scoring list and leaves the segment keys to the fp64 chain
+    const int copy_mode = (c.split_side && rescoring) ? 1 : 0;
+    if (overlap && need_att && chain_supported(c, a)) {
+        // one launch: the rows of batch n-2, both signals of this batch
+        {
+            ProfScope ps(c, MUKV_K_CHAIN, st);
+            if ((e = launch_chain(c, have_old ? &c.deferred[0] : nullptr, copy_mode, a, need_fft, &n_part, st)) != hipSuccess) return e;
+        }
+        if (have_old) {
+            c.deferred[0] = c.deferred[1];
+            c.n_deferred = 1;
+        }
+        if ((e = hipEventRecord(c.ev_fork, st)) != hipSuccess) return e;
+        if ((e = launch_split_side<T>(c, a, n_part)) != hipSuccess) return e;
+        c.deferred[c.n_deferred++] = a;
+        c.deferred_stream = st;
+        return hipSuccess;
+    }
     if (have_old && need_fft && c.cfg.freq_axis == MUKV_FREQ_FEATURE) {
         // the copy shares its launch with this batch's frequency kernel: HBM-bound beside
         // arithmetic-bound work (the attention kernel streams all the queries and gains nothing
         // beside a copy)
         ProfScope ps(c, MUKV_K_COPY_FREQ, st);
-        if ((e = launch_copy_freq<T>(c, c.deferred[0], 0, a, st)) != hipSuccess) return e;
+        if ((e = launch_copy_freq<T>(c, c.deferred[0], copy_mode, a, st)) != hipSuccess) return e;
     } else {
         if (have_old)
             if ((e = launch_deferred_copy(c, c.deferred[0], st)) != hipSuccess) return e;
@@ -1647,7 +1973,7 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
     }
     if (overlap) { // keep on the side stream; the copy waits for the batch after next (or a flush / retrieve / gather call)
         if ((e = hipEventRecord(c.ev_fork, st)) != hipSuccess) return e;
-        if ((e = launch_side<T>(c, a, true, n_part)) != hipSuccess) return e;
+        if ((e = c.split_side ? launch_split_side<T>(c, a, n_part) : launch_side<T>(c, a, true, n_part)) != hipSuccess) return e;
         c.deferred[c.n_deferred++] = a;
         c.deferred_stream = st;
         return hipSuccess;

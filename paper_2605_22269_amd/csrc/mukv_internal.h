@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "mukv.h"
+#include "mukv_measure.h"
 
 namespace mukv {
 
@@ -46,6 +47,7 @@ struct Ctx {
     int64_t n_frames;  // frames submitted so far (host-side append position)
     int64_t n_done;    // frames whose kernels have been enqueued
     int batch_chunks;  // chunks gathered before a chain of launches goes out
+    int batches_since_reset; // batches launched since the stream began (see batch_limit)
     int max_batch_frames;
     std::vector<PendingChunk> *pending;
     int64_t p_kv_sl, p_kv_sh, p_kv_st, p_q_sh, p_q_st; // strides shared by the pending chunks
@@ -76,6 +78,13 @@ struct Ctx {
     hipEvent_t ev_join[2];            // the side stream's work for the batch of that parity is enqueued
     hipEvent_t ev_copy;               // the copies that were put off are enqueued (orders another stream after them)
     bool side_pending[2];             // ev_join recorded and not yet waited for by the caller's stream
+    // overlap_copy with frames as units: `side` carries the keep of a batch and then its fp64 re-scoring
+    // chain; ev_keep marks the end of the keep, so that the copy of the batch's rows (two batches later,
+    // on the caller's stream) waits for the keep alone; the re-scored frames' rows and the segment keys
+    // follow with the fp64 chain
+    bool split_side;
+    hipEvent_t ev_keep[2];            // the keep of the batch of that parity is enqueued
+    bool keep_pending[2];             // ev_keep recorded and not yet waited for by the caller's stream
     ChunkArgs *deferred;              // overlap_copy: the (at most two) batches whose row copy is still to be
     int n_deferred;                   // launched, the older one first
     hipStream_t deferred_stream;      // stream those batches were submitted on
@@ -214,8 +223,12 @@ hipError_t launch_attend(const Ctx &c, int layer, const void *q, int n_q, const 
 int64_t prefill_workspace_bytes(const Ctx &c, int n_q, int B, int k_frame);
 
 // LDS bytes the generic attention kernel needs for P tokens of D features when it accumulates
-// in a type of r_size bytes.
-size_t att_generic_lds_bytes(int P, int D, size_t r_size);
+// in a type of r_size bytes and keeps the keys as elements of key_size bytes.
+size_t att_generic_lds_bytes(int P, int D, size_t r_size, size_t key_size);
+// bytes of the staged keys: rows of D + 16 / key_size elements, rounded up to 8 bytes
+__host__ __device__ inline size_t att_generic_key_bytes(int P, int D, size_t key_size) {
+    return ((size_t)P * (D + 16 / key_size) * key_size + 7) & ~(size_t)7;
+}
 
 // ---- small device helpers ----
 __device__ __forceinline__ float to_float(uint16_t bits) { return __uint_as_float((uint32_t)bits << 16); }

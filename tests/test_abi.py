@@ -23,7 +23,7 @@ def good_cfg(**kw):
 
 
 def test_header_symbols_are_exported():
-    text = open(os.path.join(ROOT, "include", "mukv.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("mukv.h", "mukv_measure.h"))
     declared = set(re.findall(r"^(?:int|const char \*)\s*(mukv_\w+)\(", text, flags=re.M))
     assert declared == set(mk.EXPORTS)
     lib = mk.load()
@@ -90,7 +90,7 @@ def test_binding_struct_sizes_match_header_layout(tmp_path):
     structs = {"mukv_config": mk.mukv_config, "mukv_retrieve_params": mk.mukv_retrieve_params,
                "mukv_strides": mk.mukv_strides, "mukv_state": mk.mukv_state,
                "mukv_signals_out": mk.mukv_signals_out, "mukv_profile": mk.mukv_profile}
-    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "mukv.h"', 'int main(void) {']
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "mukv.h"', '#include "mukv_measure.h"', 'int main(void) {']
     for name, st in structs.items():
         lines.append(f'printf("{name} %zu\\n", sizeof({name}));')
         for fname, _ in st._fields_:

@@ -18,6 +18,7 @@
 #include <vector>
 
 #include "mukv.h"
+#include "mukv_measure.h"
 
 #define CK(x)                                                                          \
     do {                                                                               \
