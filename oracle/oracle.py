@@ -501,10 +501,11 @@ class OracleMuKV:
     def gather(self, frame_idx, order=TEMPORAL):
         """Concatenate the stored K,V of the selected frames (Sec. 3.5): returns
         (K, V, n_tokens), K and V [L][Hkv][len(frame_idx)*kappa][D] with the
-        unused tail zero.  Entries equal to -1 are skipped."""
+        unused tail zero.  Entries that name no frame of the cache (the -1 padding,
+        numbers >= n_frames) are skipped."""
         sk, sv = self.store()
         kap = self.kappa
-        sel = [int(f) for f in frame_idx if f >= 0]
+        sel = [int(f) for f in frame_idx if 0 <= f < self.n_frames]
         if order == TEMPORAL:
             sel = sorted(sel)
         L, Hkv, _, D = sk.shape
@@ -514,3 +515,89 @@ class OracleMuKV:
             ko[:, :, slot * kap:(slot + 1) * kap] = sk[:, :, f * kap:(f + 1) * kap]
             vo[:, :, slot * kap:(slot + 1) * kap] = sv[:, :, f * kap:(f + 1) * kap]
         return ko, vo, len(sel) * kap
+
+
+# ----------------------------------------------------------------------------
+# three independently compressed stores searched together (Sec. 3.3 last two
+# paragraphs, Sec. 3.4 stage 2, Sec. 4.1 hyper-parameters)
+# ----------------------------------------------------------------------------
+def retrieve_units(store: OracleMuKV, q_tokens, k, lam=0.0, g_in=None, n_global=0, n_visible=-1):
+    """Sec. 3.4 over the blocks of ONE store, a block being a unit of that store's
+    compression (its Eq. 5 key = mean of the unit's kept scoring-layer keys, held
+    as float32): Eq. 6-7 scores s of the visible units against the question.
+      g_in is None (the coarsest store, lambda_g = 0): the top-k units by s; also
+        returns the global query g = mean of the keys of the first n_global
+        (0 -> k) of them, which stage 2 applies to the finer stores.
+      g_in given: stage 1 keeps the top-2k units by s, stage 2 gives each candidate
+        gamma = cos(its key, g_in) and s~ = (1 - lam) s + lam gamma (Eq. 8), and the
+        top-k by s~ are returned (equal s~: the lower unit number).
+    Returns dict(idx [k] int32 padded with -1, score [k], s, g)."""
+    c = store.cfg
+    n_all = store.n_frames
+    nv = n_all if n_visible < 0 else min(n_visible, n_all)
+    keys32 = store.rep_frame_k[:nv].astype(np.float32)
+    q = pool_question(q_tokens)                                    # Eq. 6
+    s = score_blocks(q, keys32, c.n_q_heads, c.n_kv_heads, c.head_dim)  # Eq. 7
+    score = np.zeros(k)
+    if g_in is None:
+        idx, n = topk(s, k)
+        n_glob = min(n_global if n_global > 0 else k, n)
+        g = keys32[idx[:n_glob]].astype(np.float64).mean(axis=0) if n_glob else np.zeros(keys32.shape[1])
+        score[:n] = s[idx[:n]]
+        return {"idx": idx, "score": score, "s": s, "g": g}
+    cand, nc = topk(s, 2 * k)                                      # stage 1
+    gamma = consistency(np.asarray(g_in, np.float64), keys32, cand[:nc])  # stage 2
+    s_tilde = np.full(nv, -np.inf)
+    s_tilde[cand[:nc]] = (1.0 - lam) * s[cand[:nc]] + lam * gamma  # Eq. 8
+    mask = np.zeros(nv, np.uint8)
+    mask[cand[:nc]] = 1
+    idx, n = topk(s_tilde, k, mask)
+    score[:n] = s_tilde[idx[:n]]
+    return {"idx": idx, "score": score, "s": s, "g": np.asarray(g_in, np.float64), "cand": cand, "gamma": gamma}
+
+
+def retrieve_multi(stores, q_tokens, ks, lams, n_global=0):
+    """The question against several stores, coarsest first: stores[0] (segment units)
+    is ranked by its stage-1 scores and supplies the global query; every other store
+    is reranked with it (Eq. 8 with its own lambda_g) -- the paper's patch / frame /
+    segment stores with k_g = 20 / 32 / 12 and lambda_g = 0.3 / 0.3 / 0 are
+    stores = [segment, frame, patch], ks = [12, 32, 20], lams = [0, 0.3, 0.3].
+    Returns the list of retrieve_units results."""
+    out = [retrieve_units(stores[0], q_tokens, ks[0], n_global=n_global)]
+    for st, k, lam in zip(stores[1:], ks[1:], lams[1:]):
+        out.append(retrieve_units(st, q_tokens, k, lam, g_in=out[0]["g"]))
+    return out
+
+
+def gather_multi(stores, idx_lists, units_per_step, rows_cap=None):
+    """The decode context of Sec. 3.5 from several stores: the kept rows of the chosen
+    units of every store, in temporal order -- ascending time step (unit u of store i
+    belongs to step u // units_per_step[i]), within a step the stores in the order
+    given (coarse to fine) and a store's units ascending; a unit listed twice is
+    copied once, entries that name no unit are skipped.  All stores share L, Hkv, D.
+    Returns (K, V, n_rows), K and V [L][Hkv][rows_cap][D] with the unused tail zero;
+    when the context holds more than rows_cap rows only the first rows_cap are copied."""
+    entries = set()
+    for i, (st, idx) in enumerate(zip(stores, idx_lists)):
+        for u in idx:
+            if 0 <= u < st.n_frames:
+                entries.add((int(u) // units_per_step[i], i, int(u)))
+    ks, vs = [], []
+    for _, i, u in sorted(entries):
+        sk, sv = stores[i].store()
+        kap = stores[i].kappa
+        ks.append(sk[:, :, u * kap:(u + 1) * kap])
+        vs.append(sv[:, :, u * kap:(u + 1) * kap])
+    sk0, _ = stores[0].store()
+    L, Hkv, _, D = sk0.shape
+    n_rows = sum(x.shape[2] for x in ks)
+    if rows_cap is None:
+        rows_cap = max(n_rows, 1)
+    ko = np.zeros((L, Hkv, rows_cap, D), sk0.dtype)
+    vo = np.zeros_like(ko)
+    if ks:
+        kc, vc = np.concatenate(ks, axis=2), np.concatenate(vs, axis=2)
+        n = min(n_rows, rows_cap)
+        ko[:, :, :n], vo[:, :, :n] = kc[:, :, :n], vc[:, :, :n]
+    return ko, vo, n_rows
+

@@ -599,6 +599,192 @@ class TestRetrieval:
         np.testing.assert_array_equal(ko2[:, :, :n], sk[:, :, rows2])
 
 
+class TestRetrievalLooseEnds:
+    """Branches of the retrieval and of the gathers that the pins above leave out."""
+
+    def _state(self, n_frames=24):
+        cfg = tiny_cfg(frames_per_segment=4)
+        k, v, q = tiny_stream(cfg, n_frames, seed=3)
+        return cfg, run_stream(cfg, k, v, q, 8)
+
+    def test_global_query_of_the_first_n_segments_by_hand(self):
+        # n_global = 1: the global query is the single best segment's key, not the mean of the top k_seg
+        cfg, o = self._state()
+        qt = rng.standard_normal((5, 4, 16)).astype(np.float32)
+        r1 = o.retrieve(qt, orc.RetrieveParams(orc.SEMI, 3, 4, lambda_frame=0.6, n_global=1))
+        r3 = o.retrieve(qt, orc.RetrieveParams(orc.SEMI, 3, 4, lambda_frame=0.6, n_global=0))
+        sseg, s = r1["s_seg"], r1["s_frm"]
+        best = sorted(range(6), key=lambda i: (-sseg[i], i))
+        seg32 = o.seg_reps().astype(np.float32).astype(np.float64)
+        np.testing.assert_allclose(r1["g"], seg32[best[0]], atol=0)
+        np.testing.assert_allclose(r3["g"], seg32[best[:3]].mean(axis=0), atol=1e-15)
+        reps = o.rep_frame_k.astype(np.float32).astype(np.float64)
+        cand = sorted(range(24), key=lambda i: (-s[i], i))[:8]
+        for r, g in ((r1, seg32[best[0]]), (r3, seg32[best[:3]].mean(axis=0))):
+            st = [0.4 * s[j] + 0.6 * (reps[j] @ g) / np.linalg.norm(reps[j]) / np.linalg.norm(g) for j in cand]
+            order = sorted(range(8), key=lambda c: (-st[c], cand[c]))[:4]
+            assert list(r["frame_idx"]) == [cand[c] for c in order]
+        # the two global queries differ, and with lambda = 0.6 so do the reranked scores
+        assert np.abs(r1["frame_score"] - r3["frame_score"]).max() > 1e-6
+        # n_global beyond the stage-1 segment candidates is clamped to them
+        r9 = o.retrieve(qt, orc.RetrieveParams(orc.SEMI, 3, 4, lambda_frame=0.6, n_global=99))
+        np.testing.assert_allclose(r9["g"], seg32[best[:6]].mean(axis=0), atol=1e-15)
+
+    def test_gather_skips_numbers_that_name_no_frame(self):
+        cfg, o = self._state(n_frames=10)
+        sk, sv = o.store()
+        kap = o.kappa
+        ko, vo, n = o.gather(np.array([7, 10, -1, 3, 4096, -5], np.int32))
+        assert n == 2 * kap
+        rows = np.concatenate([np.arange(f * kap, (f + 1) * kap) for f in (3, 7)])
+        np.testing.assert_array_equal(ko[:, :, :n], sk[:, :, rows])
+        np.testing.assert_array_equal(vo[:, :, :n], sv[:, :, rows])
+        assert ko.shape[2] == 6 * kap and not ko[:, :, n:].any() and not vo[:, :, n:].any()
+
+    def test_attend_skips_numbers_that_name_no_frame(self):
+        cfg, o = self._state(n_frames=10)
+        q = rng.standard_normal((2, 4, 16)).astype(np.float32)
+        a = o.attend(1, q, [7, 3])
+        b = o.attend(1, q, [10, 7, -1, 3, 4096])
+        np.testing.assert_array_equal(a, b)
+        assert np.abs(a).max() > 0
+
+
+class TestThreeStores:
+    """Sec. 3.3 (granularity-adaptive compression) and Sec. 3.4 stage 2 with the paper's three
+    independently compressed caches: a segment store (units of O = F*P tokens), a frame store
+    (the middle frame of every segment, P tokens) and a patch store (the S super-patches of
+    that frame, floor(P/S) tokens each)."""
+
+    def _stores(self, T, P=12, F=2, S=3, rhos=(0.8, 0.25, 0.5), alphas=(0.8, 0.7, 0.5), seed=41, dtype="f32"):
+        """T time steps; one K/V stream of T*F frames; store i is fed its own view of it."""
+        base = tiny_cfg(tokens_per_frame=P, frames_per_segment=F)
+        k, v, _ = tiny_stream(base, T * F, dtype=dtype, seed=seed)
+        mid = F // 2
+        tok_seg = np.arange(T * F * P)
+        tok_frm = np.concatenate([(t * F + mid) * P + np.arange(P) for t in range(T)])
+        units = (P * F, P, P // S)
+        stores = []
+        for i, (toks, u) in enumerate(zip((tok_seg, tok_frm, tok_frm), units)):
+            if i == 2:   # the S super-patches of the middle frame, floor(P/S) tokens each (Sec. 3.2)
+                toks = np.concatenate([(t * F + mid) * P + np.arange(S * u) for t in range(T)])
+            cfg = tiny_cfg(tokens_per_frame=u, frames_per_segment=1, superpatches_per_frame=1, keep_ratio=rhos[i],
+                           alpha=alphas[i])
+            o = orc.OracleMuKV(cfg)
+            n_units = toks.shape[0] // u
+            att = np.random.default_rng(seed + i).random((n_units, u))
+            o.compress_chunk(np.ascontiguousarray(k[:, :, toks]), np.ascontiguousarray(v[:, :, toks]), att=att)
+            stores.append(o)
+        return stores, k, v, (tok_seg, tok_frm)
+
+    def test_paper_default_run_gathers_the_printed_token_count(self):
+        # Sec. 4.1: P = 196, F = 4, S = 4, rho = 0.8 / 0.1 / 0.1 and k_g = 12 / 32 / 20 for segment / frame /
+        # patch; Table 1 prints 8.3K inference tokens for it: 12 * 627 + 32 * 19 + 20 * 4 = 8212
+        gold = json.load(open(os.path.join(GOLDEN, "paper_token_counts.json")))
+        hp = gold["hyper_parameters"]
+        P, F, S = hp["P"], hp["F"], hp["S"]
+        rho, kg = hp["rho"], hp["k_g"]
+        T = 36  # time steps: more than 32 frames, 12 segments and 20 of the 4 T super-patches
+        base = orc.OracleConfig(1, 2, 1, 16, P, F)
+        w = synth.Workload("t", 1, 2, 1, 16, "bf16", T * F, P, F)
+        kt, vt, _ = synth.SynthStream(w, 77).next_chunk(T * F)
+        k, v = synth.as_numpy(kt), synth.as_numpy(vt)
+        mid = F // 2
+        tok_frm = np.concatenate([(t * F + mid) * P + np.arange(P) for t in range(T)])
+        tok_pat = np.concatenate([(t * F + mid) * P + np.arange(S * (P // S)) for t in range(T)])
+        views = ((np.arange(T * F * P), P * F, rho["segment"], 0.8), (tok_frm, P, rho["frame"], 0.7),
+                 (tok_pat, P // S, rho["patch"], 0.5))
+        stores = []
+        for i, (toks, u, r, al) in enumerate(views):
+            o = orc.OracleMuKV(orc.OracleConfig(1, 2, 1, 16, u, 1, 1, r, al))
+            att = np.random.default_rng(500 + i).random((toks.shape[0] // u, u))
+            o.compress_chunk(np.ascontiguousarray(k[:, :, toks]), np.ascontiguousarray(v[:, :, toks]), att=att)
+            stores.append(o)
+        assert [o.kappa for o in stores] == [627, 19, 4]
+        assert [o.n_frames for o in stores] == [T, T, S * T]
+        qt = rng.standard_normal((9, 2, 16)).astype(np.float32)
+        res = orc.retrieve_multi(stores, qt, [kg["segment"], kg["frame"], kg["patch"]], [0.0, 0.3, 0.3])
+        assert all((r["idx"] >= 0).all() for r in res)
+        ko, vo, n = orc.gather_multi(stores, [r["idx"] for r in res], [1, 1, S])
+        assert n == 12 * 627 + 32 * 19 + 20 * 4 == 8212
+        assert abs(n / 1000 - gold["inference_tokens"]["mukv_printed_K"]) <= 0.1    # 8.2K against the printed 8.3K
+        assert ko.shape == (1, 1, 8212, 16)
+
+    def test_rerank_of_the_finer_stores_by_hand(self):
+        stores, k, v, _ = self._stores(T=9)
+        qt = rng.standard_normal((4, 4, 16)).astype(np.float32)
+        ks, lams = [2, 3, 4], [0.0, 0.3, 0.6]
+        res = orc.retrieve_multi(stores, qt, ks, lams, n_global=2)
+        # the literal definitions with numpy: the query expanded over the grouped heads, plain cosines
+        q = qt.astype(np.float64).mean(axis=0).reshape(-1)                       # [Hq*D]
+
+        def cosines(o):
+            keys = o.rep_frame_k.astype(np.float32).astype(np.float64)           # [n][Hkv*D]
+            wide = np.repeat(keys.reshape(len(keys), 2, 16), 2, axis=1).reshape(len(keys), -1)   # each KV head twice
+            return keys, wide @ q / np.linalg.norm(wide, axis=1) / np.linalg.norm(q)
+        keys0, s0 = cosines(stores[0])
+        top0 = sorted(range(len(s0)), key=lambda i: (-s0[i], i))
+        assert list(res[0]["idx"]) == top0[:2]
+        g = keys0[top0[:2]].mean(axis=0)
+        np.testing.assert_allclose(res[0]["g"], g, atol=1e-15)
+        for i in (1, 2):
+            keys, s = cosines(stores[i])
+            cand = sorted(range(len(s)), key=lambda j: (-s[j], j))[:2 * ks[i]]
+            gam = [keys[j] @ g / np.linalg.norm(keys[j]) / np.linalg.norm(g) for j in cand]
+            st = [(1 - lams[i]) * s[j] + lams[i] * gm for j, gm in zip(cand, gam)]
+            order = sorted(range(len(cand)), key=lambda c: (-st[c], cand[c]))[:ks[i]]
+            assert list(res[i]["idx"]) == [cand[c] for c in order]
+            np.testing.assert_allclose(res[i]["score"], [st[c] for c in order], atol=1e-14)
+
+    def test_without_the_consistency_term_every_store_keeps_its_stage_one_ranking(self):
+        stores, *_ = self._stores(T=8)
+        qt = rng.standard_normal((3, 4, 16)).astype(np.float32)
+        res = orc.retrieve_multi(stores, qt, [3, 3, 5], [0.0, 0.0, 0.0])
+        for o, r, kk in zip(stores, res, [3, 3, 5]):
+            s = r["s"]
+            assert list(r["idx"]) == sorted(range(len(s)), key=lambda j: (-s[j], j))[:kk]
+
+    def test_a_unit_whose_key_is_the_global_query_is_fully_consistent(self):
+        stores, *_ = self._stores(T=6)
+        qt = rng.standard_normal((3, 4, 16)).astype(np.float32)
+        g = stores[1].rep_frame_k[4].astype(np.float32).astype(np.float64)
+        r = orc.retrieve_units(stores[1], qt, 6, lam=1.0, g_in=g)             # lambda = 1: the ranking is gamma alone
+        assert r["idx"][0] == 4 and r["score"][0] == pytest.approx(1.0, abs=1e-12)
+
+    def test_more_units_asked_for_than_exist(self):
+        stores, *_ = self._stores(T=3)
+        qt = rng.standard_normal((3, 4, 16)).astype(np.float32)
+        res = orc.retrieve_multi(stores, qt, [5, 5, 12], [0.0, 0.3, 0.3])
+        assert sorted(res[0]["idx"][:3]) == [0, 1, 2] and list(res[0]["idx"][3:]) == [-1, -1]
+        assert sorted(res[2]["idx"][:9]) == list(range(9)) and list(res[2]["idx"][9:]) == [-1, -1, -1]
+
+    def test_the_context_is_the_kept_rows_in_temporal_order(self):
+        T, P, F, S = 7, 12, 2, 3
+        stores, k, v, (tok_seg, tok_frm) = self._stores(T=T, P=P, F=F, S=S, dtype="bf16")
+        seg, frm, pat = [5, 1, -1], [6, 1, 1, 3], [3 * S + 2, 1 * S + 0, 99, 5 * S + 1]
+        ko, vo, n = orc.gather_multi(stores, [seg, frm, pat], [1, 1, S])
+        # straight from the inputs: per time step the segment's kept tokens, the middle frame's, the super-patches'
+        mid, u = F // 2, P // S
+        want = []
+        for t in range(T):
+            if t in seg:
+                want += [t * F * P + j for j in stores[0].kept[t]]
+            if t in frm:
+                want += [(t * F + mid) * P + j for j in stores[1].kept[t]]
+            for sp in range(S):
+                if t * S + sp in pat:
+                    want += [(t * F + mid) * P + sp * u + j for j in stores[2].kept[t * S + sp]]
+        assert n == len(want) == 2 * stores[0].kappa + 3 * stores[1].kappa + 3 * stores[2].kappa
+        np.testing.assert_array_equal(ko[:, :, :n], k[:, :, want])
+        np.testing.assert_array_equal(vo[:, :, :n], v[:, :, want])
+        # a cap below the context cuts it; above, the tail stays zero
+        kc, _, n2 = orc.gather_multi(stores, [seg, frm, pat], [1, 1, S], rows_cap=10)
+        assert n2 == n and kc.shape[2] == 10
+        np.testing.assert_array_equal(kc, ko[:, :, :10])
+        kz, vz, _ = orc.gather_multi(stores, [seg, frm, pat], [1, 1, S], rows_cap=n + 5)
+        assert not kz[:, :, n:].any() and not vz[:, :, n:].any()
+
+
 class TestPatchLevel:
     """Super-patches as the fine level of the search and of the gather (Sec. 3.2, 3.4)."""
 
