@@ -448,6 +448,73 @@ int mukv_gather_union(mukv_ctx *ctx, const int32_t *seg_idx, int32_t k_seg, cons
                       int32_t *n_tokens_out, void *stream);
 
 /*
+ * Retrieval over several independently compressed stores (Sec. 3.3,
+ * granularity-adaptive compression: the patch-, frame- and segment-level caches
+ * are pruned on their own, each with its rho and alpha; Sec. 3.4: the question
+ * is scored against every cache, and stage 2 applies the global query taken
+ * from the segment-level cache to the candidates of the finer ones; Sec. 4.1:
+ * k_g = 20 / 32 / 12 and lambda_g = 0.3 / 0.3 / 0 for patch / frame / segment).
+ * A store is a context whose unit of compression (tokens_per_frame) is that
+ * granularity's block -- a segment of F*P tokens, a frame of P, a super-patch of
+ * floor(P/S) -- fed by its own mukv_compress_chunk calls.  The blocks searched
+ * here are the store's units, each with its Eq. 5 key; the store's own segment
+ * level takes no part.
+ *
+ * mukv_retrieve_units scores the visible units of ONE store against the
+ * questions (Eq. 6-7) and selects k of them per question:
+ *   global_query_in == NULL  (the coarsest store, lambda_g = 0): the k best by
+ *       the stage-1 score.  If global_query_out != NULL it receives, per
+ *       question, the mean of the keys of the first n_global of them (0: all
+ *       k; fewer if fewer units exist) -- the global query of stage 2.
+ *   global_query_in != NULL  (a finer store): stage 1 keeps the 2k best units,
+ *       stage 2 gives each gamma = cos(its key, the question's global query)
+ *       and s~ = (1 - lambda_g) s + lambda_g gamma (Eq. 8); the k best by s~
+ *       are returned (equal s~: the lower unit number).
+ *
+ *   q_tokens, q_offsets, B    as for mukv_retrieve
+ *   n_visible_units           units that precede the questions (timestamp); < 0: all
+ *   global_query_in / _out    device double [B][H_kv*D], 8-byte aligned; at most
+ *                             one of them non-NULL
+ *   idx_out                   device int32 [B][k], rank order, padded with -1
+ *   score_out                 device float [B][k] (s, or s~), may be NULL
+ *
+ * The calls for the stores of one question batch are ordered by the stream:
+ * first the store that writes the global query, then those that read it.
+ * Errors: INVALID_ARG, CAPACITY (B > max_questions), UNSUPPORTED (2k > 1024,
+ * alignment).
+ */
+int mukv_retrieve_units(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, int32_t B, int32_t k,
+                        double lambda_g, int32_t n_visible_units, const double *global_query_in, int32_t n_global,
+                        double *global_query_out, int32_t *idx_out, float *score_out, void *stream);
+
+/*
+ * One decode context from several stores (Sec. 3.5: the retrieved blocks of
+ * all granularities are loaded as the context of Eq. 9): the kept rows of the
+ * chosen units of every store, in temporal order -- ascending time step, unit u
+ * of store i belonging to step u / units_per_step[i]; within a step the stores
+ * in the order given (coarse to fine) and a store's units ascending.  A unit
+ * listed twice is copied once; entries that name no unit of their store (-1
+ * padding, numbers past the units held) are skipped.
+ *
+ *   ctxs            host array of n_ctx (1..4) contexts with the same n_layers,
+ *                   n_kv_heads, head_dim, dtype and device
+ *   unit_idx        host array of n_ctx device pointers, int32 [B][k[i]] each
+ *   k               host int32 [n_ctx]; the k[i] add up to at most 3072
+ *   units_per_step  host int32 [n_ctx], >= 1 (the paper's stores: 1, 1, S)
+ *   rows_cap        rows of the output per (layer, head)
+ *   k_out, v_out    device [B][L][H_kv][rows_cap][D], payload dtype; rows past
+ *                   the context are zero-filled, rows past rows_cap dropped
+ *   n_tokens_out    device int32 [B]: rows of the whole context.  May be NULL.
+ *
+ * The plan lives in ctxs[0]: calls that share it must not overlap.
+ * Errors: INVALID_ARG, SHAPE (stores of different models), CAPACITY
+ * (B > max_questions of ctxs[0]), UNSUPPORTED.
+ */
+int mukv_gather_multi(mukv_ctx *const *ctxs, int32_t n_ctx, const int32_t *const *unit_idx, const int32_t *k,
+                      const int32_t *units_per_step, int32_t B, int32_t rows_cap, void *k_out, void *v_out,
+                      int32_t *n_tokens_out, void *stream);
+
+/*
  * Packs the stored K,V of the selected frames of each question into a dense
  * decode context (the retrieved part of R_k, R_v in Eq. 9).
  *

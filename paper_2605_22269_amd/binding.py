@@ -70,7 +70,7 @@ class mukv_profile(C.Structure):
 
 
 EXPORTS = ("mukv_create", "mukv_destroy", "mukv_reset", "mukv_flush", "mukv_compress_chunk", "mukv_retrieve",
-           "mukv_retrieve_patches", "mukv_retrieve_at", "mukv_gather_kv", "mukv_gather_patches", "mukv_gather_union",
+           "mukv_retrieve_patches", "mukv_retrieve_at", "mukv_retrieve_units", "mukv_gather_multi", "mukv_gather_kv", "mukv_gather_patches", "mukv_gather_union",
            "mukv_attend", "mukv_prefill_workspace_size", "mukv_prefill_attend", "mukv_prefill_attend_static",
            "mukv_snapshot_size", "mukv_snapshot_save", "mukv_snapshot_load", "mukv_profile_begin", "mukv_profile_end",
            "mukv_plain_copy", "mukv_get_state", "mukv_strerror")
@@ -101,6 +101,9 @@ def load():
     lib.mukv_retrieve_at.argtypes = [vp, vp, vp, vp, i32, C.POINTER(mukv_retrieve_params), i32, vp, vp, vp, vp, vp]
     lib.mukv_gather_union.argtypes = [vp, vp, i32, vp, i32, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.mukv_attend.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp, vp, i32, i32, vp, vp]
+    lib.mukv_retrieve_units.argtypes = [vp, vp, vp, i32, i32, C.c_double, i32, vp, i32, vp, vp, vp, vp]
+    lib.mukv_gather_multi.argtypes = [C.POINTER(vp), i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(i32), i32, i32, vp, vp,
+                                      vp, vp]
     lib.mukv_prefill_workspace_size.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_int64)]
     lib.mukv_prefill_attend.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp, vp, i32, i32, vp, vp, vp, C.c_int64, vp]
     lib.mukv_prefill_attend_static.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp, vp, i32, i32, vp, vp, vp]
@@ -117,6 +120,23 @@ def load():
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
+
+
+def gather_multi(stores, idx_list, units_per_step, rows_cap):
+    """One decode context from several MuKV stores: idx_list[i] int32 [B][k_i] device tensors of chosen units.
+    Returns (k_out, v_out, n_tokens) with k_out, v_out [B][L][Hkv][rows_cap][D]."""
+    s0 = stores[0]
+    B = idx_list[0].shape[0]
+    dev = idx_list[0].device
+    shape = (B, s0.cfg.n_layers, s0.cfg.n_kv_heads, rows_cap, s0.cfg.head_dim)
+    ko = torch.empty(shape, dtype=s0.dtype, device=dev)
+    vo = torch.empty(shape, dtype=s0.dtype, device=dev)
+    nt = torch.empty(B, dtype=torch.int32, device=dev)
+    mukv_gather_multi([s.h for s in stores], [_ptr(i) for i in idx_list], [int(i.shape[1]) for i in idx_list],
+                      list(units_per_step), B, rows_cap, _ptr(ko), _ptr(vo), _ptr(nt), _stream())
+    for s in stores:
+        s._held.clear()
+    return ko, vo, nt
 
 
 class MuKVError(RuntimeError):
@@ -186,6 +206,23 @@ def mukv_gather_union(h, seg_ptr, k_seg, frm_ptr, k_frame, pat_ptr, k_patch, B, 
 def mukv_attend(h, layer, q_ptr, n_q, idx_ptr, k_frame, kl_ptr, vl_ptr, loff_ptr, B, causal_local, out_ptr, stream):
     _check(load().mukv_attend(h, layer, q_ptr, n_q, idx_ptr, k_frame, kl_ptr, vl_ptr, loff_ptr, B, causal_local, out_ptr,
                               stream), "mukv_attend")
+
+
+def mukv_retrieve_units(h, q_ptr, off_ptr, B, k, lambda_g, n_visible, g_in_ptr, n_global, g_out_ptr, idx_ptr, score_ptr,
+                        stream):
+    _check(load().mukv_retrieve_units(h, q_ptr, off_ptr, B, k, lambda_g, n_visible, g_in_ptr, n_global, g_out_ptr,
+                                      idx_ptr, score_ptr, stream), "mukv_retrieve_units")
+
+
+def mukv_gather_multi(handles, idx_ptrs, ks, units_per_step, B, rows_cap, k_out_ptr, v_out_ptr, n_tok_ptr, stream):
+    n = len(handles)
+    raw = lambda p: p.value if isinstance(p, C.c_void_p) else p
+    hs = (C.c_void_p * n)(*[raw(h) for h in handles])
+    ips = (C.c_void_p * n)(*[raw(p) for p in idx_ptrs])
+    kk = (C.c_int32 * n)(*ks)
+    ups = (C.c_int32 * n)(*units_per_step)
+    _check(load().mukv_gather_multi(hs, n, ips, kk, ups, B, rows_cap, k_out_ptr, v_out_ptr, n_tok_ptr, stream),
+           "mukv_gather_multi")
 
 
 def mukv_prefill_workspace_size(h, n_q, k_frame, B):
@@ -481,6 +518,20 @@ class MuKV:
                                    _ptr(local_offsets), B, int(causal_local), _ptr(out), _ptr(signal), _stream())
         self._held.clear()
         return out, signal
+
+    def retrieve_units(self, q_tokens, q_offsets, k, lambda_g=0.0, g_in=None, n_global=0, want_g=False, n_visible=-1):
+        """This context's units as the blocks of one of several stores.  g_in None: the k best by the stage-1
+        score (want_g: also the global query, float64 [B][C]); g_in given: stage 1, Eq. 8 with it, the k best.
+        Returns dict(idx int32 [B][k], score float32 [B][k], g)."""
+        B = q_offsets.numel() - 1
+        dev = q_tokens.device
+        idx = torch.empty(B, k, dtype=torch.int32, device=dev)
+        score = torch.empty(B, k, dtype=torch.float32, device=dev)
+        g_out = torch.empty(B, self.cfg.n_kv_heads * self.cfg.head_dim, dtype=torch.float64, device=dev) if want_g else None
+        mukv_retrieve_units(self.h, _ptr(q_tokens), _ptr(q_offsets), B, k, float(lambda_g), n_visible, _ptr(g_in),
+                            n_global, _ptr(g_out), _ptr(idx), _ptr(score), _stream())
+        self._held.clear()
+        return {"idx": idx, "score": score, "g": g_out}
 
     def gather_kv(self, frame_idx, order=MUKV_TEMPORAL, out=None):
         """frame_idx: int32 [B][k_frame] on the device.  Returns (k_out, v_out,

@@ -117,7 +117,7 @@ void free_all(Ctx &c) {
                     c.rep_patch_v, c.rep_seg_k, c.rep_seg_v, c.cnt_patch,   c.fsum_k,      c.fsum_v,
                     c.ssum_k,      c.ssum_v,    c.margin,      c.refined,   c.att_part[0], c.att_part[1], c.fft_sig[0], c.fft_sig[1],     c.att64,       c.fft64,
                     c.src_tok[0],  c.src_tok[1],   c.src_tok2,    c.flag_list[0], c.flag_list[1], c.flag_count, c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail,
-                    c.u_mask,      c.u_entry,     c.u_count,   c.attend_part, c.tw32, c.tw64, c.tok_part};
+                    c.u_mask,      c.u_entry,     c.u_count,   c.attend_part, c.tw32, c.tw64, c.tok_part, c.m_entry, c.m_count};
     // nothing of the library's own may still be running on what is freed below
     if (c.side) (void)hipStreamSynchronize(c.side);
     for (void *p : ptrs)
@@ -305,6 +305,8 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     ok(dalloc(&c.u_mask, MQ * MF));
     ok(dalloc(&c.u_entry, MQ * MF * 3));
     ok(dalloc(&c.u_count, MQ * 2));
+    ok(dalloc(&c.m_entry, MQ * (size_t)mukv::kMaxMultiEntries * 3));
+    ok(dalloc(&c.m_count, MQ * 2));
     ok(dalloc(&c.attend_part, MQ * mukv::kAttendMaxTokens * cfg->n_q_heads * mukv::kAttendMaxSplit * (size_t)(cfg->head_dim + 2)));
     if (cfg->freq_axis == MUKV_FREQ_TOKEN) {
         // rows 0..P/2 of the DFT matrix over the frame's tokens, columns 0..P/2 (the others mirror
@@ -546,6 +548,9 @@ static int retrieve_any(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_of
     a.nv = (int)nv;
     a.ns = (int)((nv + c.cfg.frames_per_segment - 1) / c.cfg.frames_per_segment);
     a.patches = patches;
+    a.units = 0;
+    a.g_in = nullptr;
+    a.g_out = nullptr;
     a.seg_idx = seg_idx_out;
     a.seg_score = seg_score_out;
     a.frm_idx = fine_idx_out;
@@ -598,6 +603,94 @@ int mukv_gather_patches(mukv_ctx *ctx, const int32_t *patch_idx, int32_t B, int3
                                        n_tokens_out, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
                ? MUKV_OK
                : MUKV_ERR_HIP;
+}
+
+int mukv_retrieve_units(mukv_ctx *ctx, const void *q_tokens, const int32_t *q_offsets, int32_t B, int32_t k,
+                        double lambda_g, int32_t n_visible_units, const double *global_query_in, int32_t n_global,
+                        double *global_query_out, int32_t *idx_out, float *score_out, void *stream) {
+    if (!ctx || !q_tokens || !q_offsets || !idx_out) return MUKV_ERR_INVALID_ARG;
+    Ctx &c = ctx->c;
+    if (B < 1 || k < 1 || n_global < 0) return MUKV_ERR_INVALID_ARG;
+    if (!(lambda_g >= 0.0) || lambda_g > 1.0) return MUKV_ERR_INVALID_ARG;
+    if (global_query_in && global_query_out) return MUKV_ERR_INVALID_ARG; // a store either supplies the global query or takes it
+    if (B > c.cfg.max_questions) return MUKV_ERR_CAPACITY;
+    if (2 * k > mukv::kMaxCand) return MUKV_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(global_query_in) & 7) || (reinterpret_cast<uintptr_t>(global_query_out) & 7))
+        return MUKV_ERR_UNSUPPORTED;
+    {
+        const int rc = flush_pending(c, true, reinterpret_cast<hipStream_t>(stream));
+        if (rc != MUKV_OK) return rc;
+    }
+    mukv::RetrieveArgs a;
+    a.q_tokens = q_tokens;
+    a.q_offsets = q_offsets;
+    a.B = B;
+    a.p.mode = MUKV_SEMI;
+    a.p.k_seg = 1;
+    a.p.k_frame = k;
+    a.p.n_global = n_global;
+    a.p.n_visible_frames = n_visible_units;
+    a.p.lambda_frame = lambda_g;
+    int64_t nv = n_visible_units < 0 ? c.n_frames : n_visible_units;
+    if (nv > c.n_frames) nv = c.n_frames;
+    a.nv_q = nullptr;
+    a.nv = (int)nv;
+    a.ns = 0; // the blocks are this store's units; its own segment level takes no part
+    a.patches = false;
+    a.units = global_query_in ? 2 : 1;
+    a.g_in = global_query_in;
+    a.g_out = global_query_out;
+    a.seg_idx = nullptr;
+    a.seg_score = nullptr;
+    a.frm_idx = idx_out;
+    a.frm_score = score_out;
+    DeviceScope dev(c.cfg.device_id);
+    if (!dev.ok) return MUKV_ERR_HIP;
+    return mukv::launch_retrieve(c, a, reinterpret_cast<hipStream_t>(stream)) == hipSuccess ? MUKV_OK : MUKV_ERR_HIP;
+}
+
+int mukv_gather_multi(mukv_ctx *const *ctxs, int32_t n_ctx, const int32_t *const *unit_idx, const int32_t *k,
+                      const int32_t *units_per_step, int32_t B, int32_t rows_cap, void *k_out, void *v_out,
+                      int32_t *n_tokens_out, void *stream) {
+    if (!ctxs || !unit_idx || !k || !units_per_step || !k_out || !v_out) return MUKV_ERR_INVALID_ARG;
+    if (n_ctx < 1 || n_ctx > mukv::kMaxStores || B < 1 || rows_cap < 1) return MUKV_ERR_INVALID_ARG;
+    int64_t total = 0;
+    for (int i = 0; i < n_ctx; ++i) {
+        if (!ctxs[i] || k[i] < 0 || units_per_step[i] < 1 || (k[i] > 0 && !unit_idx[i])) return MUKV_ERR_INVALID_ARG;
+        total += k[i];
+    }
+    if (total > mukv::kMaxMultiEntries) return MUKV_ERR_UNSUPPORTED;
+    Ctx &c0 = ctxs[0]->c;
+    if (B > c0.cfg.max_questions) return MUKV_ERR_CAPACITY;
+    for (int i = 1; i < n_ctx; ++i) { // one decode context: the stores hold rows of one model on one device
+        const mukv_config &x = ctxs[i]->c.cfg;
+        if (x.n_layers != c0.cfg.n_layers || x.n_kv_heads != c0.cfg.n_kv_heads || x.head_dim != c0.cfg.head_dim ||
+            x.dtype != c0.cfg.dtype)
+            return MUKV_ERR_SHAPE;
+        if (x.device_id != c0.cfg.device_id) return MUKV_ERR_UNSUPPORTED;
+    }
+    if ((reinterpret_cast<uintptr_t>(k_out) & 15) || (reinterpret_cast<uintptr_t>(v_out) & 15)) return MUKV_ERR_UNSUPPORTED;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    for (int i = 0; i < n_ctx; ++i) {
+        const int rc = flush_pending(ctxs[i]->c, true, st);
+        if (rc != MUKV_OK) return rc;
+    }
+    mukv::MultiArgs a;
+    a.n_ctx = n_ctx;
+    for (int i = 0; i < n_ctx; ++i) {
+        a.c[i] = &ctxs[i]->c;
+        a.idx[i] = k[i] > 0 ? unit_idx[i] : nullptr;
+        a.k[i] = k[i];
+        a.ups[i] = units_per_step[i];
+    }
+    a.B = B;
+    a.rows_cap = rows_cap;
+    a.k_out = k_out;
+    a.v_out = v_out;
+    a.n_tokens_out = n_tokens_out;
+    DeviceScope dev(c0.cfg.device_id);
+    if (!dev.ok) return MUKV_ERR_HIP;
+    return mukv::launch_gather_multi(a, st) == hipSuccess ? MUKV_OK : MUKV_ERR_HIP;
 }
 
 int mukv_gather_kv(mukv_ctx *ctx, const int32_t *frame_idx, int32_t B, int32_t k_frame, int32_t order,

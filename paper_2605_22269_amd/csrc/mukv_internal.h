@@ -17,6 +17,8 @@ constexpr int kMaxP = 256;        // tokens per frame the per-frame kernels are 
 constexpr int kMaxUnit = 8192;    // tokens of a unit of several frames ranked as one (attention signal handed over)
 constexpr int kMaxCand = 1024;    // stage-1 candidates (2*k) held in LDS by the rerank kernel
 constexpr int kMaxGatherK = 1024; // selected frames per question the gather kernel can plan
+constexpr int kMaxStores = 4;         // stores searched together (the paper has three: segment, frame, patch)
+constexpr int kMaxMultiEntries = 3072; // units per question the gather over several stores can plan
 
 // one chunk handed to mukv_compress_chunk and not yet launched
 struct PendingChunk {
@@ -98,6 +100,9 @@ struct Ctx {
     uint32_t *u_mask;  // [max_questions][max_frames] super-patches of a frame chosen at any level
     int32_t *u_entry;  // [max_questions][max_frames][3] chosen frames in time order: frame, mask, first output row
     int32_t *u_count;  // [max_questions][2] entries, rows
+    // gather over several stores (this context being the first of them): chosen units in temporal order
+    int32_t *m_entry;  // [max_questions][kMaxMultiEntries][3] store, unit, first output row
+    int32_t *m_count;  // [max_questions][2] entries, rows
     // token-axis frequency signal: cos and -sin of 2*pi*m*j/P for rows and token pairs 0..P/2,
     // [P/2+1][P/2+1][2]; per (batch frame, group of 64 features, row) sums of |Z|: the fp32 pass
     // uses the first tok_part_half bytes, the fp64 pass the rest
@@ -160,6 +165,10 @@ struct RetrieveArgs {
     int ns;      // visible segments
     bool patches; // fine level of the search: super-patches instead of frames (k_frame, lambda_frame apply to it)
     const int32_t *nv_q; // device [B] per-question timestamps, or null (then nv / ns hold for every question)
+    int units;           // 0: segments and frames of this context; 1 / 2: the context's units as the blocks of one of
+                         // several stores (1: ranked by stage 1, global query out; 2: reranked with g_in), ns = 0
+    const double *g_in;  // device [B][C_kv]
+    double *g_out;       // device [B][C_kv] or null
     int32_t *seg_idx;
     float *seg_score;
     int32_t *frm_idx;
@@ -182,6 +191,16 @@ struct UnionArgs {
     int32_t *n_tokens_out;
 };
 hipError_t launch_gather_union(Ctx &c, const UnionArgs &a, hipStream_t st);
+
+struct MultiArgs {
+    const Ctx *c[kMaxStores];
+    const int32_t *idx[kMaxStores]; // device [B][k[i]] or null
+    int k[kMaxStores], ups[kMaxStores];
+    int n_ctx, B, rows_cap;
+    void *k_out, *v_out;
+    int32_t *n_tokens_out;
+};
+hipError_t launch_gather_multi(const MultiArgs &a, hipStream_t st);
 
 // Brackets the launches of one scope with HIP events when the context is profiling.
 struct ProfScope {

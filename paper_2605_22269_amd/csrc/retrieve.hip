@@ -584,6 +584,12 @@ struct RerankArgs {
     const int32_t *nv_q; // per-question timestamps (visible frames), or null: nv / ns / tail_cut above hold for all
     int n_all, kpf, Ff;  // ingested frames, fine keys per frame, frames per segment (used with nv_q)
     int cache_cap; // entries of the LDS key cache (dynamic shared memory)
+    // one store's units as the blocks (several stores searched together): 0 = off; 1 = the coarsest
+    // store: top k_frame units by their stage-1 scores, and their first n_global keys' mean to g_out;
+    // 2 = a finer store: stage 1, then Eq. 8 with the global query g_in, final top k_frame
+    int units;
+    const double *g_in; // [B][C]
+    double *g_out;      // [B][C] or null
     double lambda;
     int32_t *seg_idx, *frm_idx;
     float *seg_score, *frm_score;
@@ -633,6 +639,31 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
         }
     };
 
+    if (a.units == 1) {
+        const int m_u = block_topk(frm_key, a.nv, a.k_frame, cand_frm, sh, kcache, cap);
+        for (int r = tid; r < a.k_frame; r += kSelThreads) {
+            frm_out[r] = r < m_u ? cand_frm[r] : -1;
+            if (frm_sc) frm_sc[r] = r < m_u ? (float)s_frm[cand_frm[r]] : 0.f;
+        }
+        if (a.g_out) { // the global query for the finer stores: mean of the first n_glob chosen keys
+            int n_glob = a.n_global > 0 ? a.n_global : a.k_frame;
+            n_glob = min(n_glob, m_u);
+            for (int c = tid; c < a.C; c += kSelThreads) {
+                double sum = 0.0;
+                for (int r0 = 0; r0 < n_glob; r0 += 8) { // batches of 8 independent loads, summed in list order
+                    float x[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        x[u] = a.rep_frame[(int64_t)cand_frm[r0 + u < n_glob ? r0 + u : n_glob - 1] * a.C + c];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (r0 + u < n_glob) sum += (double)x[u];
+                }
+                a.g_out[(int64_t)b * a.C + c] = n_glob > 0 ? sum / (double)n_glob : 0.0;
+            }
+        }
+        return;
+    }
     if (a.mode != MUKV_SEMI) {
         const int m_s = block_topk(seg_key, a.ns, a.k_seg, cand_seg, sh, kcache, cap);
         for (int r = tid; r < a.k_seg && a.seg_idx; r += kSelThreads) {
@@ -661,10 +692,13 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
     }
 
     // ---- semi-hierarchical ----
-    const int m_s = block_topk(seg_key, a.ns, 2 * a.k_seg, cand_seg, sh, kcache, cap);
-    for (int r = tid; r < a.k_seg && a.seg_idx; r += kSelThreads) { // lambda = 0 for segments: stage-1 order stands
-        seg_out[r] = r < m_s ? cand_seg[r] : -1;
-        if (seg_sc) seg_sc[r] = r < m_s ? (float)s_seg[cand_seg[r]] : 0.f;
+    int m_s = 0;
+    if (a.units == 0) {
+        m_s = block_topk(seg_key, a.ns, 2 * a.k_seg, cand_seg, sh, kcache, cap);
+        for (int r = tid; r < a.k_seg && a.seg_idx; r += kSelThreads) { // lambda = 0 for segments: stage-1 order stands
+            seg_out[r] = r < m_s ? cand_seg[r] : -1;
+            if (seg_sc) seg_sc[r] = r < m_s ? (float)s_seg[cand_seg[r]] : 0.f;
+        }
     }
     const int m_f = block_topk(frm_key, a.nv, 2 * a.k_frame, order, sh, kcache, cap);
     // candidates in ascending frame order, so that equal reranked scores resolve to the lowest frame
@@ -674,10 +708,14 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
         for (int u = 0; u < m_f; ++u) pos += order[u] < me;
         cand_frm[pos] = me;
     }
-    // global query: mean of the first n_glob stage-1 segment keys
+    // global query: handed over (it comes from a coarser store), or the mean of the first n_glob stage-1 segment keys
     int n_glob = a.n_global > 0 ? a.n_global : a.k_seg;
     n_glob = min(n_glob, m_s);
     for (int c = tid; c < a.C; c += kSelThreads) {
+        if (a.units == 2) {
+            gvec[c] = a.g_in[(int64_t)b * a.C + c];
+            continue;
+        }
         double s = 0.0;
         for (int r0 = 0; r0 < n_glob; r0 += 8) { // batches of 8 independent loads, summed in list order
             float x[8];
@@ -1062,6 +1100,133 @@ __global__ __launch_bounds__(256) void gather_union_kernel(UnionGatherArgs a) {
         *reinterpret_cast<cp_u32x4 *>(z0 + u * 16) = cp_u32x4{0u, 0u, 0u, 0u};
 }
 
+// The decode context from several independently compressed stores (Sec. 3.3: one cache per granularity;
+// Sec. 3.5: what was retrieved is loaded as the context): the kept rows of the chosen units of every
+// store in temporal order -- ascending time step (unit u of store i belongs to step u / ups[i]), within
+// a step the stores in the order given and a store's units ascending; a unit listed twice is taken
+// once, entries that name no unit are skipped.  multi_plan: one workgroup per question orders the
+// entries by counting (key = step, store, unit) and adds up the rows in front of each; multi_gather:
+// workgroups walk the ordered entries, each a dense run of kappa_i rows of its store's slab.
+struct MultiStore {
+    const unsigned char *store_k, *store_v;
+    int64_t slab_b;  // bytes of one (layer, head) slab
+    int64_t n_units; // units held
+    int kappa;
+};
+struct MultiPlanArgs {
+    const int32_t *idx[kMaxStores];
+    int k[kMaxStores], ups[kMaxStores], kappa[kMaxStores];
+    int64_t n_units[kMaxStores];
+    int n_ctx;
+    int32_t *entry, *count;
+};
+
+__global__ __launch_bounds__(kPlanThreads) void multi_plan_kernel(MultiPlanArgs a) {
+    __shared__ uint64_t key[kMaxMultiEntries]; // (step, store, unit), or kNoKey for an entry that is skipped
+    __shared__ bool repeat[kMaxMultiEntries];
+    __shared__ int n_sh, rows_sh;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    int n = 0;
+    for (int i = 0; i < a.n_ctx; ++i) n += a.k[i];
+    if (tid == 0) n_sh = rows_sh = 0;
+    int base = 0;
+    for (int i = 0; i < a.n_ctx; ++i) {
+        for (int t = tid; t < a.k[i]; t += kPlanThreads) {
+            const int u = a.idx[i][(int64_t)b * a.k[i] + t];
+            const bool ok = u >= 0 && u < a.n_units[i];
+            key[base + t] = ok ? ((uint64_t)(unsigned)(u / a.ups[i]) << 34) | ((uint64_t)i << 32) | (unsigned)u : kNoKey;
+        }
+        base += a.k[i];
+    }
+    __syncthreads();
+    // a unit listed twice is taken once: later repeats leave the list
+    for (int t = tid; t < n; t += kPlanThreads) {
+        const uint64_t kt = key[t];
+        bool rep = false;
+        for (int u = 0; u < t; ++u) rep |= key[u] == kt;
+        repeat[t] = rep;
+    }
+    __syncthreads();
+    for (int t = tid; t < n; t += kPlanThreads)
+        if (repeat[t]) key[t] = kNoKey;
+    __syncthreads();
+    int32_t *entry = a.entry + (int64_t)b * kMaxMultiEntries * 3;
+    int mine = 0, mine_rows = 0;
+    for (int t = tid; t < n; t += kPlanThreads) {
+        const uint64_t kt = key[t];
+        if (kt == kNoKey) continue;
+        int pos = 0, row = 0;
+        for (int u = 0; u < n; ++u) { // entries ahead of this one, and the rows they bring
+            const uint64_t ku = key[u];
+            const bool ahead = ku < kt; // (kNoKey is the largest key: skipped entries are ahead of nobody)
+            pos += ahead;
+            row += ahead ? a.kappa[(int)((ku >> 32) & 3u)] : 0;
+        }
+        const int st = (int)((kt >> 32) & 3u);
+        entry[3 * pos] = st;
+        entry[3 * pos + 1] = (int)(unsigned)(kt & 0xffffffffu);
+        entry[3 * pos + 2] = row;
+        ++mine;
+        mine_rows += a.kappa[st];
+    }
+    if (mine) {
+        atomicAdd(&n_sh, mine);
+        atomicAdd(&rows_sh, mine_rows);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        a.count[2 * b] = n_sh;
+        a.count[2 * b + 1] = rows_sh;
+    }
+}
+
+struct MultiGatherArgs {
+    MultiStore s[kMaxStores];
+    const int32_t *entry, *count;
+    unsigned char *k_out, *v_out;
+    int32_t *n_tokens_out;
+    int row_b, upr_log, rows_cap;
+    int L, Hkv;
+};
+
+__global__ __launch_bounds__(256) void multi_gather_kernel(MultiGatherArgs a) {
+    const int tid = threadIdx.x, b = blockIdx.z, y = blockIdx.y;
+    const int n_ent = a.count[2 * b], n_rows = a.count[2 * b + 1];
+    if (a.n_tokens_out && blockIdx.x == 0 && y == 0 && tid == 0) a.n_tokens_out[b] = n_rows;
+    const int32_t *entry = a.entry + (int64_t)b * kMaxMultiEntries * 3;
+    const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
+    const int kv = rem / a.Hkv, g = rem - kv * a.Hkv;
+    unsigned char *dst = (kv ? a.v_out : a.k_out) + (((int64_t)b * a.L + l) * a.Hkv + g) * ((int64_t)a.rows_cap * a.row_b);
+    const int upr = 1 << a.upr_log;
+    for (int e = blockIdx.x; e < n_ent; e += gridDim.x) {
+        const int st = entry[3 * e], unit = entry[3 * e + 1], out_row = entry[3 * e + 2];
+        const MultiStore &ms = a.s[st];
+        const int c = ms.kappa;
+        const int c_fit = out_row + c <= a.rows_cap ? c : (a.rows_cap > out_row ? a.rows_cap - out_row : 0);
+        const unsigned char *s0 = (kv ? ms.store_v : ms.store_k) + ((int64_t)l * a.Hkv + g) * ms.slab_b +
+                                  (int64_t)unit * c * a.row_b;
+        unsigned char *d0 = dst + (int64_t)out_row * a.row_b;
+        const int n_u = c_fit * upr;
+        for (int u0 = tid; u0 < n_u; u0 += 4 * 256) { // four 16-byte pieces in flight per lane
+            cp_u32x4 x[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int u = u0 + j * 256 < n_u ? u0 + j * 256 : n_u - 1;
+                x[j] = *reinterpret_cast<const cp_u32x4 *>(s0 + (int64_t)u * 16);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (u0 + j * 256 < n_u) *reinterpret_cast<cp_u32x4 *>(d0 + (int64_t)(u0 + j * 256) * 16) = x[j];
+        }
+    }
+    // rows past the context are zero
+    const int first = n_rows < a.rows_cap ? n_rows : a.rows_cap;
+    const int64_t n_zero = (int64_t)(a.rows_cap - first) * upr;
+    unsigned char *z0 = dst + (int64_t)first * a.row_b;
+    for (int64_t u = (int64_t)blockIdx.x * 256 + tid; u < n_zero; u += (int64_t)gridDim.x * 256)
+        *reinterpret_cast<cp_u32x4 *>(z0 + u * 16) = cp_u32x4{0u, 0u, 0u, 0u};
+}
+
 // Plain streaming copy, 4 x 16 bytes per thread: the calibration kernel for traffic counters.
 __global__ __launch_bounds__(256) void plain_copy_kernel(const cp_u32x4 *__restrict__ src, cp_u32x4 *__restrict__ dst,
                                                          int64_t n_units) {
@@ -1185,7 +1350,10 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
     r.kpf = kpf;
     r.Ff = F;
     r.tail_cut = tail_cut;
-    r.mode = a.p.mode;
+    r.units = a.units;
+    r.g_in = a.g_in;
+    r.g_out = a.g_out;
+    r.mode = a.units ? (int)MUKV_SEMI : a.p.mode;
     r.k_seg = a.p.k_seg;
     r.k_frame = a.p.k_frame;
     r.n_global = a.p.n_global;
@@ -1314,6 +1482,45 @@ hipError_t launch_gather_union(Ctx &c, const UnionArgs &a, hipStream_t st) {
     g.L = c.cfg.n_layers;
     g.Hkv = c.cfg.n_kv_heads;
     hipLaunchKernelGGL(gather_union_kernel, dim3(64, c.cfg.n_layers * 2 * c.cfg.n_kv_heads, a.B), dim3(256), 0, st, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_multi(const MultiArgs &a, hipStream_t st) {
+    const Ctx &c0 = *a.c[0];
+    MultiPlanArgs p;
+    MultiGatherArgs g;
+    for (int i = 0; i < kMaxStores; ++i) {
+        const bool on = i < a.n_ctx;
+        p.idx[i] = on ? a.idx[i] : nullptr;
+        p.k[i] = on && a.idx[i] ? a.k[i] : 0;
+        p.ups[i] = on ? a.ups[i] : 1;
+        p.kappa[i] = on ? a.c[i]->kappa : 0;
+        p.n_units[i] = on ? a.c[i]->n_frames : 0;
+        g.s[i].store_k = on ? reinterpret_cast<const unsigned char *>(a.c[i]->store_k) : nullptr;
+        g.s[i].store_v = on ? reinterpret_cast<const unsigned char *>(a.c[i]->store_v) : nullptr;
+        g.s[i].slab_b = on ? a.c[i]->store_cap * (int64_t)(c0.cfg.head_dim * c0.esz) : 0;
+        g.s[i].n_units = p.n_units[i];
+        g.s[i].kappa = p.kappa[i];
+    }
+    p.n_ctx = a.n_ctx;
+    p.entry = c0.m_entry;
+    p.count = c0.m_count;
+    hipLaunchKernelGGL(multi_plan_kernel, dim3(a.B), dim3(kPlanThreads), 0, st, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    g.entry = c0.m_entry;
+    g.count = c0.m_count;
+    g.k_out = reinterpret_cast<unsigned char *>(a.k_out);
+    g.v_out = reinterpret_cast<unsigned char *>(a.v_out);
+    g.n_tokens_out = a.n_tokens_out;
+    g.row_b = c0.cfg.head_dim * c0.esz;
+    int upr = g.row_b / 16, lg = 0;
+    while ((1 << lg) < upr) ++lg;
+    g.upr_log = lg;
+    g.rows_cap = a.rows_cap;
+    g.L = c0.cfg.n_layers;
+    g.Hkv = c0.cfg.n_kv_heads;
+    hipLaunchKernelGGL(multi_gather_kernel, dim3(64, c0.cfg.n_layers * 2 * c0.cfg.n_kv_heads, a.B), dim3(256), 0, st, g);
     return hipGetLastError();
 }
 

@@ -1152,3 +1152,117 @@ def test_seeded_sweep_of_large_units(i):
     p.check_retrieve(questions_for(w, [5, 9], 9300 + i), mk.MUKV_SEMI, 1, 2, 0.3)
     p.check_attend(0, 2, [[0, units - 1], [units - 1, -1]], [4, 2], True, seed=i)
     p.close()
+
+
+# ------------- three independently compressed stores searched together (Sec. 3.3-3.4, Sec. 4.1) -----
+def _three_stores(P, F, S, T, rhos, alphas, head, dtype, seed, gpu_kw=None):
+    """One K/V stream of T time steps of F frames; store 0 takes the segments (units of F*P tokens), store 1
+    the middle frame of every segment (P tokens), store 2 that frame's S super-patches (P // S tokens each).
+    Every store has its own rho and alpha and is handed its attention signal.  Returns the Pairs and k, v."""
+    base = W["tiny"].scaled(dtype=dtype, tokens_per_frame=P, frames_per_segment=F, n_frames=T * F, spike_prob=0.05, **head)
+    k, v, _ = synth.SynthStream(base, seed, device="cpu", with_q=False).next_chunk(T * F)
+    mid, u_p = F // 2, P // S
+    tok = [torch.arange(T * F * P),
+           torch.cat([(t * F + mid) * P + torch.arange(P) for t in range(T)]),
+           torch.cat([(t * F + mid) * P + torch.arange(S * u_p) for t in range(T)])]
+    pairs = []
+    for i, unit in enumerate((F * P, P, u_p)):
+        n_units = tok[i].numel() // unit
+        w = base.scaled(tokens_per_frame=unit, frames_per_segment=1, superpatches_per_frame=1, keep_ratio=rhos[i],
+                        alpha=alphas[i], n_frames=n_units, n_questions=3)
+        p = Pair(w, seed=seed, chunk=n_units, with_q=False, gpu_kw=gpu_kw)
+        ki, vi = k[:, :, tok[i]].contiguous(), v[:, :, tok[i]].contiguous()
+        att = synth.handed_over_attention(n_units, unit, seed + 10 + i)
+        p.orc.compress_chunk(np_view(ki), np_view(vi), att=att.numpy().astype(np.float64))
+        kd, vd, ad = ki.cuda(), vi.cuda(), att.cuda()
+        p.keep_alive += [kd, vd, ad]
+        p.gpu.compress_chunk(kd, vd, att_signal=ad)
+        pairs.append(p)
+    torch.cuda.synchronize()
+    return pairs, base
+
+
+def _check_three_stores(pairs, base, qs, ks, lams, ups, n_global=0, rows_cap=None):
+    B = len(qs)
+    qt = torch.cat(qs).contiguous().cuda()
+    offs = torch.tensor(np.concatenate([[0], np.cumsum([q.shape[0] for q in qs])]), dtype=torch.int32, device="cuda")
+    g0 = pairs[0].gpu.retrieve_units(qt, offs, ks[0], n_global=n_global, want_g=True)
+    got = [g0] + [p.gpu.retrieve_units(qt, offs, k, lam, g_in=g0["g"]) for p, k, lam in zip(pairs[1:], ks[1:], lams[1:])]
+    kap = [p.orc.kappa for p in pairs]
+    cap = rows_cap or sum(k * c for k, c in zip(ks, kap))
+    ko, vo, nt = mk.gather_multi([p.gpu for p in pairs], [g["idx"] for g in got], ups, cap)
+    torch.cuda.synchronize()
+    for b in range(B):
+        want = orc.retrieve_multi([p.orc for p in pairs], np_view(qs[b]), ks, lams, n_global=n_global)
+        np.testing.assert_allclose(g0["g"][b].cpu().numpy(), want[0]["g"], rtol=0, atol=1e-14)
+        for i in range(3):
+            np.testing.assert_array_equal(got[i]["idx"][b].cpu().numpy(), want[i]["idx"], err_msg=f"store {i} question {b}")
+            assert np.abs(got[i]["score"][b].cpu().numpy() - want[i]["score"]).max() <= 1e-5
+        kw, vw, n = orc.gather_multi([p.orc for p in pairs], [w_["idx"] for w_ in want], ups, rows_cap=cap)
+        assert int(nt[b]) == n
+        np.testing.assert_array_equal(np_view(ko[b].cpu()), kw)
+        np.testing.assert_array_equal(np_view(vo[b].cpu()), vw)
+    return got
+
+
+@pytest.mark.parametrize("dtype,head", [("f32", dict(n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=32)),
+                                        ("bf16", dict(n_layers=2, n_q_heads=28, n_kv_heads=4, head_dim=128))])
+def test_three_stores_retrieved_together(dtype, head):
+    P, F, S, T = 24, 2, 3, 11
+    pairs, base = _three_stores(P, F, S, T, (0.8, 0.25, 0.5), (0.8, 0.7, 0.5), head, dtype, seed=7700)
+    qs = [synth.random_question(base, n, 7710 + i) for i, n in enumerate([5, 12, 3])]
+    _check_three_stores(pairs, base, qs, [3, 5, 6], [0.0, 0.3, 0.3], [1, 1, S])
+    _check_three_stores(pairs, base, qs, [3, 5, 6], [0.0, 0.9, 0.0], [1, 1, S], n_global=1)
+    # more asked for than exists (padding), and an output too short for the context
+    _check_three_stores(pairs, base, qs, [14, 20, 40], [0.0, 0.3, 0.3], [1, 1, S], rows_cap=50)
+    # repeated and out-of-range entries in the lists given to the gather
+    idx = [torch.tensor([[4, 4, -1, 99]] * 3, dtype=torch.int32, device="cuda"),
+           torch.tensor([[10, 0, 10]] * 3, dtype=torch.int32, device="cuda"),
+           torch.tensor([[32, 1, 33, 1, 7]] * 3, dtype=torch.int32, device="cuda")]
+    ko, vo, nt = mk.gather_multi([p.gpu for p in pairs], idx, [1, 1, S], 200)
+    torch.cuda.synchronize()
+    kw, vw, n = orc.gather_multi([p.orc for p in pairs], [i[0].cpu().numpy() for i in idx], [1, 1, S], rows_cap=200)
+    assert int(nt[0]) == n
+    np.testing.assert_array_equal(np_view(ko[2].cpu()), kw)
+    np.testing.assert_array_equal(np_view(vo[0].cpu()), vw)
+    for p in pairs:
+        p.close()
+
+
+def test_three_stores_with_the_paper_hyper_parameters():
+    # Sec. 4.1: P = 196, F = 4, S = 4; rho = 0.8 / 0.1 / 0.1, alpha = 0.8 / 0.7 / 0.5, k_g = 12 / 32 / 20 and
+    # lambda_g = 0 / 0.3 / 0.3 for segment / frame / patch; Table 1: 8.3K tokens loaded per question
+    # (12 * 627 + 32 * 19 + 20 * 4 = 8212), in the 7B head layout
+    head = dict(n_layers=2, n_q_heads=28, n_kv_heads=4, head_dim=128)
+    pairs, base = _three_stores(196, 4, 4, 40, (0.8, 0.1, 0.1), (0.8, 0.7, 0.5), head, "bf16", seed=7800)
+    assert [p.orc.kappa for p in pairs] == [627, 19, 4]
+    qs = [synth.random_question(base, n, 7810 + i) for i, n in enumerate([32, 16])]
+    got = _check_three_stores(pairs, base, qs, [12, 32, 20], [0.0, 0.3, 0.3], [1, 1, 4])
+    ko, vo, nt = mk.gather_multi([p.gpu for p in pairs], [g["idx"] for g in got], [1, 1, 4], 8212)
+    torch.cuda.synchronize()
+    assert nt.cpu().tolist() == [8212, 8212]
+    for p in pairs:
+        p.close()
+
+
+def test_three_stores_argument_errors():
+    head = dict(n_layers=1, n_q_heads=4, n_kv_heads=2, head_dim=32)
+    pairs, base = _three_stores(12, 2, 3, 4, (0.8, 0.5, 0.5), (0.8, 0.7, 0.5), head, "f32", seed=7900)
+    other = gpu_context(base.scaled(n_layers=2, n_frames=4), max_frames=4, max_chunk_frames=4)
+    idx = torch.zeros(1, 2, dtype=torch.int32, device="cuda")
+    with pytest.raises(mk.MuKVError) as e:                       # stores of different models
+        mk.gather_multi([pairs[0].gpu, other], [idx, idx], [1, 1], 16)
+    assert e.value.status == mk.MUKV_ERR_SHAPE
+    with pytest.raises(mk.MuKVError) as e:                       # more entries than the plan holds
+        mk.gather_multi([pairs[0].gpu], [torch.zeros(1, 3073, dtype=torch.int32, device="cuda")], [1], 16)
+    assert e.value.status == mk.MUKV_ERR_UNSUPPORTED
+    qt = synth.random_question(base, 4, 1).cuda()
+    offs = torch.tensor([0, 4], dtype=torch.int32, device="cuda")
+    g = torch.zeros(1, 64, dtype=torch.float64, device="cuda")
+    with pytest.raises(mk.MuKVError) as e:                       # a store either supplies the global query or takes it
+        mk.mukv_retrieve_units(pairs[1].gpu.h, qt.data_ptr(), offs.data_ptr(), 1, 2, 0.3, -1, g.data_ptr(), 0, g.data_ptr(),
+                               idx.data_ptr(), None, None)
+    assert e.value.status == mk.MUKV_ERR_INVALID_ARG
+    other.close()
+    for p in pairs:
+        p.close()
