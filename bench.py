@@ -71,6 +71,10 @@ def parse():
                     help="axis of the transform in the frequency indicator (mukv_config.freq_axis); "
                          "the default is the reading the build takes, 'token' the other one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--core-only", action="store_true",
+                    help="print the step's own figures and stop (no extras, no other configurations, no oracle timing)")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short passes over the 7B-class and 72B-class streams that the default run appends")
     ap.add_argument("--cpu-sample-frames", type=int, default=2048)
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="size in MiB of the plain-copy reference run (default 1024)")
@@ -306,6 +310,11 @@ def main():
                           "note": "the paper reports no compression throughput and no retrieval or KV-loading "
                                   "latency in isolation, hence vs_baseline is null"},
     }
+
+    if a.core_only:
+        ctx.close()
+        print(json.dumps(res))
+        return
 
     # ---- the same cache under 64 concurrent questions of 16..64 tokens (one batched call each) --
     if B == 1:
@@ -590,6 +599,30 @@ def main():
                                "sample": f"first {ref.n_frames} frames of the same stream through the oracle's "
                                          f"compress_chunk ({t_cpu:.1f} s) on {cpu_model()}"}
     ctx.close()
+
+    # ---- the other stream shapes of the task (7B-class short stream, 72B-class hour), each as a short run of
+    # this same program in a process of its own once this one has given its memory back ----
+    if a.workload == "hour" and not a.frames and not a.no_other_configs:
+        import subprocess
+
+        K = V = Q = ks = vs = qs = g_out = None   # (the side runs would fit beside them as well: 40 + 85 GB of 288)
+        torch.cuda.empty_cache()
+        res["other_configs"] = {}
+        for wl in ("7b", "72b"):
+            cmd = [sys.executable, os.path.abspath(__file__), "--workload", wl, "--core-only", "--steps", "3", "--warmup", "1",
+                   "--batch-chunks", str(a.batch_chunks), "--overlap-copy", str(a.overlap_copy), "--seed", str(a.seed)]
+            try:
+                out = subprocess.run(cmd, check=True, capture_output=True, text=True, timeout=240).stdout.strip().splitlines()
+                r = json.loads(out[-1])
+                res["other_configs"][wl] = {
+                    "workload": r["config"]["workload"], "visual_tokens_per_s": r["value"], "ms_per_step": r["ms_per_step"],
+                    "path_hbm_frac_of_peak": r["path_hbm"]["frac_of_peak"],
+                    "path_algorithmic_bytes_per_token": r["path_hbm"]["algorithmic_bytes_per_token"],
+                    "retrieve_gather_ms_per_question": r["retrieve_gather_ms_per_question"],
+                    "dominant_kernel": r["roofline"]["kernel"], "dominant_kernel_frac": r["roofline"]["frac"],
+                    "gather_frac": r["roofline_gather"]["frac"], "steps": r["steps"]}
+            except Exception as e:   # a failed side run must not lose the main line
+                res["other_configs"][wl] = {"error": repr(e)[:300]}
     print(json.dumps(res))
 
 

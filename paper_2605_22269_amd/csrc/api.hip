@@ -66,6 +66,7 @@ int validate_config(const mukv_config *cfg) {
     const bool large_unit = cfg->tokens_per_frame > mukv::kMaxP;
     if (large_unit && cfg->freq_axis != MUKV_FREQ_FEATURE) return MUKV_ERR_UNSUPPORTED;
     if ((int64_t)cfg->n_kv_heads * cfg->head_dim > 1024) return MUKV_ERR_UNSUPPORTED;
+    if (cfg->n_q_heads / cfg->n_kv_heads > 1024) return MUKV_ERR_UNSUPPORTED; // the question pooling holds 4 * G partial sums per feature in LDS
     const int esz = cfg->dtype == MUKV_BF16 ? 2 : 4;
     if (!large_unit &&
         mukv::att_generic_lds_bytes(cfg->tokens_per_frame, cfg->head_dim, sizeof(double), sizeof(float)) > 160 * 1024)
@@ -298,7 +299,7 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     c.deferred = new (std::nothrow) mukv::ChunkArgs[2];
     ok(hipEventCreateWithFlags(&c.ev_copy, hipEventDisableTiming));
     ok(dalloc(&c.qbar, MQ * C));
-    ok(dalloc(&c.qq, MQ * cfg->n_kv_heads));
+    ok(dalloc(&c.qq, MQ * cfg->n_kv_heads * (size_t)(cfg->head_dim / mukv::pool_slice(c.group, cfg->head_dim))));
     ok(dalloc(&c.s_frm, MQ * MF * S)); // room for the super-patch level
     ok(dalloc(&c.s_seg, MQ * (size_t)c.max_segments));
     ok(dalloc(&c.seg_tail, MQ * C));

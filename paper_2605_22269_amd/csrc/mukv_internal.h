@@ -92,7 +92,7 @@ struct Ctx {
     hipStream_t deferred_stream;      // stream those batches were submitted on
     // retrieval scratch (device)
     double *qbar;    // [max_questions][c_kv]  group-summed mean query
-    double *qq;      // [max_questions][Hkv]   partial squared norms of the mean query
+    double *qq;      // [max_questions][Hkv * D / pool_slice]   partial squared norms of the mean query
     double *s_frm;   // [max_questions][max_frames]
     double *s_seg;   // [max_questions][max_segments]
     float *seg_tail; // [max_questions][c_kv] key of the segment cut by a question's timestamp
@@ -176,6 +176,7 @@ struct RetrieveArgs {
 };
 
 hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st);
+int pool_slice(int G, int D); // features per workgroup of the question pooling
 
 hipError_t launch_gather(Ctx &c, const int32_t *frame_idx, int B, int k_frame, int order, void *k_out,
                          void *v_out, int32_t *n_tokens_out, hipStream_t st);

@@ -18,29 +18,32 @@ typedef unsigned int cp_u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kSelThreads = 512;
 
 // ------------------------------------------------------------------------------------------
-// Eq. 6.  grid (B, Hkv).  Each workgroup averages the question's tokens for the G query heads
-// of one KV head, then sums those heads: with keys repeated G times over their group (grouped
-// query attention), q . expand(r) = sum_g (sum_{h in g} q_h) . r_g.  Also the group's share of
-// |q|^2.
+// Eq. 6.  grid (B, Hkv, D / dz).  Each workgroup averages the question's tokens for a slice of dz
+// features of the G query heads of one KV head, then sums those heads: with keys repeated G times
+// over their group (grouped query attention), q . expand(r) = sum_g (sum_{h in g} q_h) . r_g.
+// Also the slice's share of |q|^2.  dz is chosen so that G * dz elements are one pass of the
+// workgroup's 256 element lanes: the call is a chain of dependent memory round trips, and the fewer
+// a workgroup makes the sooner the scores can start.
 // ------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(1024) void pool_question_kernel(const T *__restrict__ q_tokens,
                                                              const int32_t *__restrict__ q_off, int Hq, int Hkv, int D,
-                                                             int G, double *__restrict__ qbar,
+                                                             int G, int dz, double *__restrict__ qbar,
                                                              double *__restrict__ qq) {
     // threads: 256 element lanes x 4 token slices; slice t takes tokens t, t+4, ... in batches of
     // 8 independent loads.  Token sums are exact in fp64, so the split does not change the result.
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    double *part = reinterpret_cast<double *>(smem_raw); // [4][G*D]
+    double *part = reinterpret_cast<double *>(smem_raw); // [4][G*dz]
     __shared__ double red[16];
-    const int b = blockIdx.x, g = blockIdx.y, tid = threadIdx.x;
+    const int b = blockIdx.x, g = blockIdx.y, z = blockIdx.z, tid = threadIdx.x;
     const int el = tid & 255, ts = tid >> 8;
     const int t0 = q_off[b], t1 = q_off[b + 1];
     const int nq = t1 - t0;
-    const int GD = G * D;
+    const int GD = G * dz, d0 = z * dz;
     const int64_t tstride = (int64_t)Hq * D;
     for (int e = el; e < GD; e += 256) {
-        const T *p = q_tokens + ((int64_t)t0 * Hq + (int64_t)g * G) * D + e;
+        const int hl = e / dz, dd = e - hl * dz;
+        const T *p = q_tokens + ((int64_t)t0 * Hq + (int64_t)g * G + hl) * D + d0 + dd;
         double s = 0.0;
         for (int tb = ts; tb < nq; tb += 32) {
             float v[8];
@@ -68,11 +71,11 @@ __global__ __launch_bounds__(1024) void pool_question_kernel(const T *__restrict
     sq = wave_sum(sq);
     if ((tid & 63) == 0) red[tid >> 6] = sq;
     __syncthreads();
-    if (tid == 0) qq[(int64_t)b * Hkv + g] = ((red[0] + red[1]) + red[2]) + red[3];
-    for (int d = tid; d < D; d += 1024) {
+    if (tid == 0) qq[((int64_t)b * Hkv + g) * gridDim.z + z] = ((red[0] + red[1]) + red[2]) + red[3];
+    for (int dd = tid; dd < dz; dd += 1024) {
         double s = 0.0;
-        for (int hl = 0; hl < G; ++hl) s += part[hl * D + d];
-        qbar[((int64_t)b * Hkv + g) * D + d] = s;
+        for (int hl = 0; hl < G; ++hl) s += part[hl * dz + dd];
+        qbar[((int64_t)b * Hkv + g) * D + d0 + dd] = s;
     }
 }
 
@@ -91,6 +94,7 @@ struct ScoreArgs {
     double *s_frm, *s_seg;
     float *seg_tail;
     int nv, ns, B, C, Hkv, G, F, kappa;
+    int n_qq; // partial squared norms of the pooled query per question
     int nf; // keys of the fine level in rep_frame / s_frm: the visible frames, or their super-patches
     int tail_cut; // 1: segment ns-1 must be rebuilt from frames [ (ns-1)*F, nv )
     int64_t ld_frm, ld_seg;
@@ -154,7 +158,7 @@ __global__ __launch_bounds__(256) void score_blocks_kernel(ScoreArgs a) {
         if (lane < 4 && b < a.B) {
             const double d = lane == 0 ? dot[0] : (lane == 1 ? dot[1] : (lane == 2 ? dot[2] : dot[3]));
             double qn = 0.0;
-            for (int g = 0; g < a.Hkv; ++g) qn += a.qq[(int64_t)b * a.Hkv + g];
+            for (int g = 0; g < a.n_qq; ++g) qn += a.qq[(int64_t)b * a.n_qq + g];
             double sc = 0.0;
             if (rr > 0.0 && qn > 0.0) sc = d / (sqrt(qn) * sqrt((double)a.G * rr));
             if (is_seg)
@@ -192,7 +196,7 @@ __global__ __launch_bounds__(256) void seg_tail_kernel(ScoreArgs a) {
 // rerank kernel in seg_tail[b]) and replaces its score.
 struct TailArgs {
     const int32_t *nv_q;
-    int n_all, F, kappa, C, Hkv, G;
+    int n_all, F, kappa, C, Hkv, G, n_qq;
     const double *fsum, *qbar, *qq;
     double *s_seg;
     int64_t ld_seg;
@@ -229,7 +233,7 @@ __global__ __launch_bounds__(256) void tail_fix_kernel(TailArgs a) {
         dot = (red[0] + red[1]) + (red[2] + red[3]);
         rr = (red[4] + red[5]) + (red[6] + red[7]);
         double qn = 0.0;
-        for (int g = 0; g < a.Hkv; ++g) qn += a.qq[(int64_t)b * a.Hkv + g];
+        for (int g = 0; g < a.n_qq; ++g) qn += a.qq[(int64_t)b * a.n_qq + g];
         double sc = 0.0;
         if (rr > 0.0 && qn > 0.0) sc = dot / (sqrt(qn) * sqrt((double)a.G * rr));
         a.s_seg[(int64_t)b * a.ld_seg + ns - 1] = sc;
@@ -281,7 +285,7 @@ __global__ __launch_bounds__(256) void score_blocks_mfma_kernel(ScoreArgs a) {
         rr += lane_xor<16>(rr);
         rr += lane_xor<32>(rr);
         double qn = 0.0;
-        for (int g = 0; g < a.Hkv; ++g) qn += a.qq[(int64_t)bq * a.Hkv + g];
+        for (int g = 0; g < a.n_qq; ++g) qn += a.qq[(int64_t)bq * a.n_qq + g];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int rw = 4 * r + kq; // tile row of result register r
@@ -819,7 +823,7 @@ struct GatherArgs {
     int64_t n_frames;
 };
 
-template <int ITER>
+template <int ITER, int ROUNDS>
 __global__ __launch_bounds__(256) void gather_kv_kernel(GatherArgs a) {
     __shared__ int slot_frame[kMaxGatherK];
     __shared__ int n_valid_sh;
@@ -861,23 +865,37 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(GatherArgs a) {
     const unsigned char *src = (kv ? a.store_v : a.store_k) + ((int64_t)l * a.Hkv + g) * a.slab_b;
     unsigned char *dst = (kv ? a.v_out : a.k_out) + (((int64_t)b * a.L + l) * a.Hkv + g) * (a.k_frame * a.frame_b);
     const int n_units = a.k_frame * a.units_per_frame;
-    // unconditional loads on clamped unit numbers / slot 0's frame, zero selected afterwards
-    cp_u32x4 tmp[ITER];
-    const int u0 = blockIdx.x * (256 * ITER) + tid;
+    // ROUNDS rounds of ITER 16-byte pieces per lane; the loads of round r+1 are issued before the stores of
+    // round r, so that reads and writes of the launch overlap (its workgroups all start together and would
+    // otherwise all read, then all write).  Loads are unconditional on clamped unit numbers / slot 0's
+    // frame, the zero for an empty slot is selected afterwards.
+    cp_u32x4 tmp[2][ITER];
     const int fr_any = n_valid > 0 ? slot_frame[0] : 0;
+    auto load_round = [&](int r, cp_u32x4(&t)[ITER]) {
+        const int u0 = (blockIdx.x * ROUNDS + r) * (256 * ITER) + tid;
 #pragma unroll
-    for (int it = 0; it < ITER; ++it) {
-        int u = u0 + it * 256;
-        u = u < n_units ? u : n_units - 1;
-        const int slot = u / a.units_per_frame, part = u - slot * a.units_per_frame;
-        const int fr = slot_frame[slot];
-        const cp_u32x4 x = *reinterpret_cast<const cp_u32x4 *>(src + (int64_t)(fr >= 0 ? fr : fr_any) * a.frame_b + (int64_t)part * 16);
-        tmp[it] = fr >= 0 ? x : cp_u32x4{0u, 0u, 0u, 0u};
-    }
+        for (int it = 0; it < ITER; ++it) {
+            int u = u0 + it * 256;
+            u = u < n_units ? u : n_units - 1;
+            const int slot = u / a.units_per_frame, part = u - slot * a.units_per_frame;
+            const int fr = slot_frame[slot];
+            const cp_u32x4 x = *reinterpret_cast<const cp_u32x4 *>(src + (int64_t)(fr >= 0 ? fr : fr_any) * a.frame_b + (int64_t)part * 16);
+            t[it] = fr >= 0 ? x : cp_u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    auto store_round = [&](int r, const cp_u32x4(&t)[ITER]) {
+        const int u0 = (blockIdx.x * ROUNDS + r) * (256 * ITER) + tid;
 #pragma unroll
-    for (int it = 0; it < ITER; ++it) {
-        const int u = u0 + it * 256;
-        if (u < n_units) *reinterpret_cast<cp_u32x4 *>(dst + (int64_t)u * 16) = tmp[it];
+        for (int it = 0; it < ITER; ++it) {
+            const int u = u0 + it * 256;
+            if (u < n_units) *reinterpret_cast<cp_u32x4 *>(dst + (int64_t)u * 16) = t[it];
+        }
+    };
+    load_round(0, tmp[0]);
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+        if (r + 1 < ROUNDS) load_round(r + 1, tmp[(r + 1) & 1]);
+        store_round(r, tmp[r & 1]);
     }
 }
 
@@ -1255,18 +1273,27 @@ hipError_t launch_plain_copy(void *dst, const void *src, int64_t bytes, hipStrea
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
+// Features per workgroup of the question pooling: the largest power of two with G * dz <= 256 (one pass
+// of the workgroup's element lanes), at least 1, at most D.
+int pool_slice(int G, int D) {
+    int dz = 1;
+    while (dz * 2 <= D && G * dz * 2 <= 256) dz *= 2;
+    return dz;
+}
+
 hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
     const int Hq = c.cfg.n_q_heads, Hkv = c.cfg.n_kv_heads, D = c.cfg.head_dim, G = c.group;
-    const size_t lds = (size_t)4 * G * D * sizeof(double);
+    const int dz = pool_slice(G, D), n_z = D / dz;
+    const size_t lds = (size_t)4 * G * dz * sizeof(double);
     hipError_t e;
     {
     ProfScope ps(c, MUKV_K_POOLQ, st);
     if (c.cfg.dtype == MUKV_BF16)
-        hipLaunchKernelGGL((pool_question_kernel<uint16_t>), dim3(a.B, Hkv), dim3(1024), lds, st,
-                           reinterpret_cast<const uint16_t *>(a.q_tokens), a.q_offsets, Hq, Hkv, D, G, c.qbar, c.qq);
+        hipLaunchKernelGGL((pool_question_kernel<uint16_t>), dim3(a.B, Hkv, n_z), dim3(1024), lds, st,
+                           reinterpret_cast<const uint16_t *>(a.q_tokens), a.q_offsets, Hq, Hkv, D, G, dz, c.qbar, c.qq);
     else
-        hipLaunchKernelGGL((pool_question_kernel<float>), dim3(a.B, Hkv), dim3(1024), lds, st,
-                           reinterpret_cast<const float *>(a.q_tokens), a.q_offsets, Hq, Hkv, D, G, c.qbar, c.qq);
+        hipLaunchKernelGGL((pool_question_kernel<float>), dim3(a.B, Hkv, n_z), dim3(1024), lds, st,
+                           reinterpret_cast<const float *>(a.q_tokens), a.q_offsets, Hq, Hkv, D, G, dz, c.qbar, c.qq);
     e = hipGetLastError();
     }
     if (e != hipSuccess) return e;
@@ -1290,6 +1317,7 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
         s.fsum = c.fsum_k;
         s.qbar = c.qbar;
         s.qq = c.qq;
+        s.n_qq = Hkv * n_z;
         s.s_frm = c.s_frm;
         s.s_seg = c.s_seg;
         s.seg_tail = c.seg_tail;
@@ -1325,6 +1353,7 @@ hipError_t launch_retrieve(Ctx &c, const RetrieveArgs &a, hipStream_t st) {
             t.fsum = c.fsum_k;
             t.qbar = c.qbar;
             t.qq = c.qq;
+            t.n_qq = Hkv * n_z;
             t.s_seg = c.s_seg;
             t.ld_seg = c.max_segments;
             t.seg_tail = c.seg_tail;
@@ -1402,10 +1431,11 @@ hipError_t launch_gather(Ctx &c, const int32_t *frame_idx, int B, int k_frame, i
     g.kappa = c.kappa;
     g.n_frames = c.n_frames;
     const int n_units = k_frame * g.units_per_frame;
-    constexpr int ITER = 8; // 16-byte pieces per thread: fewer, longer workgroups amortise the slot plan
-    const int gx = (n_units + 256 * ITER - 1) / (256 * ITER);
+    // 16-byte pieces per thread: 4 rounds of 4, two rounds in flight; fewer, longer workgroups amortise the slot plan
+    constexpr int ITER = 4, ROUNDS = 4;
+    const int gx = (n_units + 256 * ITER * ROUNDS - 1) / (256 * ITER * ROUNDS);
     ProfScope ps(c, MUKV_K_GATHER, st);
-    hipLaunchKernelGGL((gather_kv_kernel<ITER>), dim3(gx, c.cfg.n_layers * 2 * c.cfg.n_kv_heads, B), dim3(256), 0, st, g);
+    hipLaunchKernelGGL((gather_kv_kernel<ITER, ROUNDS>), dim3(gx, c.cfg.n_layers * 2 * c.cfg.n_kv_heads, B), dim3(256), 0, st, g);
     return hipGetLastError();
 }
 

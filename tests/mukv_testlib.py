@@ -59,6 +59,8 @@ class Pair:
         self.chunk = chunk or w.chunk_frames
         self.n = frames or w.n_frames
         self.gpu = gpu_context(w, max_frames=self.n, max_chunk_frames=self.chunk, **(gpu_kw or {}))
+        margin = (gpu_kw or {}).get("refine_margin", -1.0)
+        self.refine_margin = 1e-5 if margin < 0 else margin   # the library's default threshold
         self.orc = orc.OracleMuKV(oracle_config(w, **(orc_kw or {})))
         self.stream = synth.SynthStream(w, seed, device="cpu", with_q=with_q)
         self.sig_gpu, self.sig_orc = [], []
@@ -110,6 +112,22 @@ class Pair:
         assert st["n_frames"] == self.orc.n_frames
         np.testing.assert_array_equal(st["kept_idx"].cpu().numpy(), self.orc.kept)       # bit-exact indices
         n, kap = self.orc.n_frames, self.orc.kappa
+        # the selection in isolation: the oracle's keep applied to the GPU's OWN fused scores gives the GPU's
+        # indices for every frame decided in fp32; a frame decided by the fp64 pass had its boundary gap
+        # below the threshold (which is why it was re-scored)
+        refined = st["refined"].cpu().numpy().astype(bool)
+        gpu_kept = st["kept_idx"].cpu().numpy()
+        f0 = 0
+        for sg in self.sig_gpu:
+            fused = sg["fused"].cpu().numpy().astype(np.float64)
+            own = orc.keep(fused, kap)
+            for i in range(fused.shape[0]):
+                if not refined[f0 + i]:
+                    np.testing.assert_array_equal(own[i], gpu_kept[f0 + i], err_msg=f"frame {f0 + i}")
+                elif kap < fused.shape[1] and self.refine_margin < 1.0:
+                    srt = np.sort(fused[i])[::-1]
+                    assert srt[kap - 1] - srt[kap] <= self.refine_margin + 1e-6, f"frame {f0 + i}"
+            f0 += fused.shape[0]
         gk, gv = self.gpu.store_rows(0, n * kap)
         ok, ov = self.orc.store()
         np.testing.assert_array_equal(np_view(gk), ok)                                    # byte copy

@@ -108,6 +108,26 @@ def test_batches_of_sixteen_or_more_questions(name, frames):
     p.close()
 
 
+def test_gather_and_attend_skip_numbers_that_name_no_frame():
+    # -1 is the padding of a short retrieval; numbers at or past the frames held are skipped the same way
+    w = W["7b"].scaled(n_frames=10, n_layers=2, n_questions=2)
+    p = Pair(w, seed=8, chunk=5)
+    p.ingest()
+    p.check_compress()
+    lists = [[7, 10, -1, 3, 4096, -5], [-1, 11, 12, 2**31 - 1, 0, 9]]
+    idx = torch.tensor(lists, dtype=torch.int32, device="cuda")
+    for order in (mk.MUKV_TEMPORAL, mk.MUKV_AS_GIVEN):
+        kg, vg, nt = p.gpu.gather_kv(idx, order=order)
+        torch.cuda.synchronize()
+        for b in range(2):
+            ko, vo, n = p.orc.gather(np.array(lists[b], np.int64), order=orc.TEMPORAL if order == mk.MUKV_TEMPORAL else orc.AS_GIVEN)
+            assert int(nt[b]) == n == 2 * p.orc.kappa
+            np.testing.assert_array_equal(np_view(kg[b].cpu()), ko)
+            np.testing.assert_array_equal(np_view(vg[b].cpu()), vo)
+    p.check_attend(1, 2, lists, [3, 2], True, seed=9)
+    p.close()
+
+
 # ------------------------------------------------------ 72B shape, short stream -----------
 def test_72b_shape_short_stream():
     w = W["72b"].scaled(n_frames=40, n_layers=3)   # kappa 8 of 64; one full 32-frame segment + 8
