@@ -118,7 +118,7 @@ void free_all(Ctx &c) {
                     c.rep_patch_v, c.rep_seg_k, c.rep_seg_v, c.cnt_patch,   c.fsum_k,      c.fsum_v,
                     c.ssum_k,      c.ssum_v,    c.margin,      c.refined,   c.att_part[0], c.att_part[1], c.fft_sig[0], c.fft_sig[1],     c.att64,       c.fft64,
                     c.src_tok[0],  c.src_tok[1],   c.src_tok2,    c.flag_list[0], c.flag_list[1], c.flag_count, c.qbar,      c.qq,        c.s_frm,       c.s_seg,       c.seg_tail,
-                    c.u_mask,      c.u_entry,     c.u_count,   c.attend_part, c.tw32, c.tw64, c.tok_part, c.m_entry, c.m_count};
+                    c.u_mask,      c.u_entry,     c.u_count,   c.attend_part, c.tw32, c.tw64, c.tok_part, c.m_entry, c.m_count, c.dft_tab};
     // nothing of the library's own may still be running on what is freed below
     if (c.side) (void)hipStreamSynchronize(c.side);
     for (void *p : ptrs)
@@ -280,9 +280,14 @@ int mukv_create(const mukv_config *cfg, mukv_ctx **out) {
     const size_t n_part_max = P > (size_t)mukv::kMaxP ? 0 : Hq * ((P + 31) / 32 > 2 ? (P + 31) / 32 : 2);
     for (int par = 0; par < 2; ++par) {
         ok(dalloc(&c.att_part[par], MC * n_part_max * P));
-        ok(dalloc(&c.fft_sig[par], MC * P));
+        ok(dalloc(&c.fft_sig[par], MC * P * (c.use_mfma ? (size_t)cfg->n_kv_heads : 1)));
         ok(dalloc(&c.src_tok[par], MC * c.kappa));
         ok(hipEventCreateWithFlags(&c.ev_join[par], hipEventDisableTiming));
+    }
+    if (c.use_mfma && cfg->freq_axis == MUKV_FREQ_FEATURE) {
+        const std::vector<uint16_t> tab = mukv::dft_operand_table();
+        ok(dalloc(&c.dft_tab, tab.size()));
+        if (e == hipSuccess) ok(hipMemcpy(c.dft_tab, tab.data(), tab.size() * sizeof(uint16_t), hipMemcpyHostToDevice));
     }
     ok(dalloc(&c.att64, MC * n_part_max * P));
     ok(dalloc(&c.fft64, MC * P));

@@ -1,5 +1,9 @@
 // Eq. 1 (attention received per token) on the CDNA4 matrix cores as a launch of its own: the kernel
 // around att_mfma_body (att_mfma_dev.h) and its launcher.
+#include <cmath>
+#include <cstring>
+#include <vector>
+
 #include "att_mfma_dev.h"
 
 namespace mukv {
@@ -40,6 +44,46 @@ void att_mfma_plan(const Ctx &c, const ChunkArgs &a, float *out, AttMfmaArgs *aa
     aa->causal = c.cfg.causal;
     aa->scale_log2e = 1.4426950408889634f / sqrtf((float)c.cfg.head_dim);
     aa->out = out;
+    aa->dft = nullptr;
+    aa->fft_out = nullptr;
+}
+
+// The matrix of the length-128 transform of real keys as matrix-core B operands (see freq_mfma_phase):
+// [split 3][column tile 8][feature slice 4][lane 64][8] bf16; entry j of lane (lr, lg) of (tile ct,
+// slice kk) is W[d = 32 kk + 8 lg + j][c = 16 ct + lr], W[d][c] = cos(2 pi c d / 128) for c <= 64 and
+// sin(2 pi (c - 64) d / 128) above; split 0 is W rounded to bf16, split 1 the rounded rest, split 2
+// the rounded rest of that.
+static uint16_t bf16_rne(float x) {
+    uint32_t u;
+    std::memcpy(&u, &x, 4);
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+static float bf16_to_float(uint16_t b) {
+    const uint32_t u = (uint32_t)b << 16;
+    float x;
+    std::memcpy(&x, &u, 4);
+    return x;
+}
+std::vector<uint16_t> dft_operand_table() {
+    std::vector<uint16_t> t((size_t)kDftSplits * 8 * 4 * kDftOperand);
+    for (int ct = 0; ct < 8; ++ct)
+        for (int kk = 0; kk < 4; ++kk)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int j = 0; j < 8; ++j) {
+                    const int d = 32 * kk + 8 * (lane >> 4) + j, col = 16 * ct + (lane & 15);
+                    const int m = col <= 64 ? col : col - 64;
+                    const int r = (m * d) % 128; // the angle, reduced exactly
+                    const double ang = 2.0 * 3.14159265358979323846 * (double)r / 128.0;
+                    double w = col <= 64 ? std::cos(ang) : std::sin(ang);
+                    if (col <= 64 && (r % 32) == 0) w = (r == 0) ? 1.0 : (r == 64 ? -1.0 : 0.0); // exact zeros and ones
+                    if (col > 64 && (r % 64) == 0) w = 0.0;
+                    for (int sp = 0; sp < kDftSplits; ++sp) {
+                        const uint16_t b = bf16_rne((float)w);
+                        t[((((size_t)sp * 8 + ct) * 4 + kk) * 64 + lane) * 8 + j] = b;
+                        w -= (double)bf16_to_float(b);
+                    }
+                }
+    return t;
 }
 
 hipError_t launch_att_mfma(const Ctx &c, const ChunkArgs &a, float *out, int *n_part, hipStream_t st) {

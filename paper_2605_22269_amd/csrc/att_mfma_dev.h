@@ -136,7 +136,80 @@ struct AttMfmaArgs {
     int P, nt, G, hpw, causal, pair, n_split, n_part;
     float scale_log2e;
     float *out; // [batch frame][n_part][P] partial column sums
+    // Eq. 2-3 on the way (layout with a KV group per workgroup only): the frequency indicator of the
+    // staged keys, per KV head, to fft_out [batch frame][Hkv][P] as sum_m |Z[m]| (not yet divided by
+    // Hkv * D); dft = the transform's matrix as bf16 operands (see dft_operand_table).  Null: not computed.
+    const uint16_t *dft;
+    float *fft_out;
 };
+
+// Eq. 2-3 for the frame's keys of one KV head, from the key tiles already staged in LDS, as a matrix
+// product on the matrix cores: Z = K W with W [128 features x 128 columns], column c <= 64 the cosine
+// of bin c, column 64 + m the sine of bin m (1 <= m <= 63); the keys are real, so bins m and 128 - m
+// have the same magnitude and sum_m |Z[m]| = |Z[0]| + |Z[64]| + 2 sum_{0<m<64} |Z[m]|.
+// The keys are bf16 and go in as they are; W is split into three bf16 terms (hi + mid + lo carry 24
+// bits of every entry) and the three products accumulate in fp32, every single product being exact.
+// A key tile is the A operand exactly as the attention reads it as its B operand (lane = row lr, 8
+// features from 8 * lg of every 32); the W operands come from a table in memory that every workgroup
+// shares (lane-major: one 16-byte load per lane and operand).  In the result a lane holds bin column
+// lr of four tokens; the cosine tile ct and the sine tile ct + 4 put a bin's real and imaginary part
+// in the same lane (bin 0's lane gets Re Z[0] and Re Z[64]).  Wave w takes token tiles w and
+// w + n_waves and loads every W operand once for both.
+constexpr int kDftSplits = 3;
+constexpr int kDftOperand = 64 * 8; // bf16 elements of one operand: 64 lanes x 8
+__device__ __forceinline__ void freq_mfma_phase(const unsigned char *Ks, const int (&off)[4], const uint16_t *__restrict__ dft,
+                                                int w, int n_waves, int lane, int nt, int P, float *__restrict__ out) {
+    const int lr = lane & 15, lg = lane >> 4;
+    const int tA = w, tB = w + n_waves;
+    if (tA >= nt) return;
+    const bool two = tB < nt;
+    bf16x8 ka[2][4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        ka[0][kk] = *reinterpret_cast<const bf16x8 *>(Ks + tA * kTileB + off[kk]);
+        ka[1][kk] = *reinterpret_cast<const bf16x8 *>(Ks + (two ? tB : tA) * kTileB + off[kk]);
+    }
+    float tok[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    const bf16x8 *tab = reinterpret_cast<const bf16x8 *>(dft) + lane;
+#pragma unroll 1
+    for (int ct = 0; ct < 4; ++ct) {
+        f32x4 re[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, im[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int sp = kDftSplits - 1; sp >= 0; --sp) { // the smallest terms first
+            bf16x8 wr[4], wi[4];
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                wr[kk] = tab[((sp * 8 + ct) * 4 + kk) * 64];
+                wi[kk] = tab[((sp * 8 + ct + 4) * 4 + kk) * 64];
+            }
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    re[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][kk], wr[kk], re[t], 0, 0, 0);
+                    im[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][kk], wi[kk], im[t], 0, 0, 0);
+                }
+            }
+        }
+        const bool ends = ct == 0 && lr == 0; // this lane holds Re Z[0] and Re Z[64]
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float x = re[t][r], y = im[t][r];
+                const float mid = 2.0f * __builtin_sqrtf(fmaf(x, x, y * y));
+                tok[t][r] += ends ? fabsf(x) + fabsf(y) : mid;
+            }
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float v = row16_sum(tok[t][r]);
+            const int token = 16 * (t ? tB : tA) + 4 * lg + r;
+            if (lr == 0 && token < P && (t == 0 || two)) out[token] = v;
+        }
+}
 
 // True when a batch is long enough for the layout with a whole KV group per workgroup.
 bool att_mfma_many(const Ctx &c, int n_frames);
@@ -219,14 +292,17 @@ __device__ __forceinline__ void att_mfma_body(const PtrTable &qtab, const PtrTab
     }
     __syncthreads();
 
-    float acc[kMaxTiles];
-#pragma unroll
-    for (int c = 0; c < kMaxTiles; ++c) acc[c] = 0.f;
-
     JobArgs ja;
     ja.k_lds = Ks;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) ja.off[kk] = lr * kRowB + (((4 * kk + lg) ^ lr) << 4);
+    if (aa.fft_out && pair) // (pair: every key tile is staged and this workgroup is the only one of its (frame, KV head))
+        freq_mfma_phase(Ks, ja.off, aa.dft, w, n_threads >> 6, lane, nt, P, aa.fft_out + ((int64_t)f * (aa.n_part / n_split) + g) * P);
+
+    float acc[kMaxTiles];
+#pragma unroll
+    for (int c = 0; c < kMaxTiles; ++c) acc[c] = 0.f;
+
     ja.scale_log2e = scale_log2e;
     const bool tail = (P & 15) != 0;
     for (int job = 0; job < n_jobs; ++job) {

@@ -530,6 +530,8 @@ struct SelectArgs {
     PtrTable att_in;    // per slot: caller-supplied float [n][P]
     bool have_att_in;
     const R *fft;       // [n_frames][P], or NULL (alpha == 1)
+    int fft_parts;      // > 0: fft is [n_frames][fft_parts][P] partial sums (one per KV head), to be added in order
+    R fft_scale;        //      and scaled by this (1 / (Hkv * D))
     R alpha;
     int P, kappa, S, Hkv, D;
     int64_t frame0;
@@ -615,7 +617,15 @@ __global__ __launch_bounds__(256) void select_pool_kernel(SelectArgs<R> a) {
             av *= a.att_scale;
         }
     }
-    if (valid && a.alpha != (R)1) fv = a.fft[(int64_t)f * P + j];
+    if (valid && a.alpha != (R)1) {
+        if (a.fft_parts > 0) {
+            R sum = 0;
+            for (int pt = 0; pt < a.fft_parts; ++pt) sum += a.fft[((int64_t)f * a.fft_parts + pt) * P + j];
+            fv = sum * a.fft_scale;
+        } else {
+            fv = a.fft[(int64_t)f * P + j];
+        }
+    }
     if (valid && dbg_att) dbg_att[(int64_t)lf * P + j] = (float)av;
     if (valid && dbg_fft) dbg_fft[(int64_t)lf * P + j] = (float)fv;
 
@@ -1484,7 +1494,7 @@ hipError_t launch_att_mfma(const Ctx &c, const ChunkArgs &a, float *out, int *n_
 
 template <typename T, typename R>
 static hipError_t launch_select(const Ctx &c, const ChunkArgs &a, const R *att, int n_part, const R *fft, int pass2,
-                                hipStream_t st) {
+                                hipStream_t st, int fft_parts = 0) {
     SelectArgs<R> s;
     const bool need_att = c.cfg.alpha != 0.0;
     s.att = (need_att && !a.have_att_in) ? att : nullptr;
@@ -1493,6 +1503,8 @@ static hipError_t launch_select(const Ctx &c, const ChunkArgs &a, const R *att, 
     s.att_in = a.att_in;
     s.have_att_in = need_att && a.have_att_in;
     s.fft = (c.cfg.alpha != 1.0) ? fft : nullptr;
+    s.fft_parts = fft_parts;
+    s.fft_scale = (R)(1.0 / ((double)c.cfg.n_kv_heads * (double)c.cfg.head_dim));
     s.alpha = (R)c.cfg.alpha;
     s.P = c.cfg.tokens_per_frame;
     s.kappa = c.kappa;
@@ -1669,12 +1681,20 @@ static int odd_at_most(int64_t x) { // largest odd number <= x, at least 1
 }
 
 static hipError_t launch_chain(const Ctx &c, const ChunkArgs *prev, int copy_mode, const ChunkArgs &a, bool need_fft,
-                               int *n_part, hipStream_t st) {
+                               int *n_part, int *fft_parts, hipStream_t st) {
     AttMfmaArgs aa;
     int waves;
     size_t lds;
     att_mfma_plan(c, a, c.att_part[a.parity], &aa, &waves, &lds);
     *n_part = aa.n_part;
+    // Eq. 2-3 by the attention workgroups themselves, from the keys they have staged anyway: no second read
+    // of the keys, no frequency workgroups
+    const bool fused_fft = need_fft && c.dft_tab != nullptr;
+    if (fused_fft) {
+        aa.dft = c.dft_tab;
+        aa.fft_out = c.fft_sig[a.parity];
+    }
+    *fft_parts = fused_fft ? c.cfg.n_kv_heads : 0;
     const int threads = waves * 64;
     CompactArgs k;
     std::memset(&k, 0, sizeof(k));
@@ -1731,7 +1751,7 @@ static hipError_t launch_chain(const Ctx &c, const ChunkArgs *prev, int copy_mod
     fp.out = c.fft_sig[a.parity];
     fp.n_frames = a.n_frames;
     fp.bpf = 4; // with 7 waves per workgroup: 28 tokens of a frame side by side, as in the kernel of its own
-    fp.n_wg = need_fft ? a.n_frames * fp.bpf : 0;
+    fp.n_wg = (need_fft && !fused_fft) ? a.n_frames * fp.bpf : 0;
     ChainMap cm;
     cm.n_att = a.n_frames * aa.n_part;
     cm.n_freq = fp.n_wg;
@@ -1800,7 +1820,7 @@ static hipError_t wait_side_all(Ctx &c, hipStream_t st) {
 // that batch's whole launch to finish in.  (A second library stream for the chain, forked from `side`
 // inside a stream capture, ended a capture with a crash in the runtime and is not used.)
 template <typename T>
-static hipError_t launch_split_side(Ctx &c, const ChunkArgs &a, int n_part) {
+static hipError_t launch_split_side(Ctx &c, const ChunkArgs &a, int n_part, int fft_parts = 0) {
     hipError_t e;
     const int par = a.parity;
     const bool need_att = c.cfg.alpha != 0.0 && !a.have_att_in;
@@ -1808,7 +1828,7 @@ static hipError_t launch_split_side(Ctx &c, const ChunkArgs &a, int n_part) {
     if ((e = hipStreamWaitEvent(c.side, c.ev_fork, 0)) != hipSuccess) return e;
     {
         ProfScope ps(c, MUKV_K_SELECT, c.side);
-        if ((e = launch_select<T, float>(c, a, c.att_part[par], n_part, c.fft_sig[par], 0, c.side)) != hipSuccess) return e;
+        if ((e = launch_select<T, float>(c, a, c.att_part[par], n_part, c.fft_sig[par], 0, c.side, fft_parts)) != hipSuccess) return e;
     }
     if ((e = hipEventRecord(c.ev_keep[par], c.side)) != hipSuccess) return e;
     c.keep_pending[par] = true;
@@ -1917,7 +1937,7 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
     const bool need_fft = c.cfg.alpha != 1.0;
     const bool overlap = c.cfg.overlap_copy != 0;
     const bool rescoring = c.margin_thr > 0.0;
-    int n_part = c.cfg.n_q_heads;
+    int n_part = c.cfg.n_q_heads, fft_parts = 0;
     // copies put off on another stream cannot share a launch with this batch
     if (c.n_deferred && c.deferred_stream != st)
         if ((e = join_streams(c, st)) != hipSuccess) return e;
@@ -1933,14 +1953,14 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
         // one launch: the rows of batch n-2, both signals of this batch
         {
             ProfScope ps(c, MUKV_K_CHAIN, st);
-            if ((e = launch_chain(c, have_old ? &c.deferred[0] : nullptr, copy_mode, a, need_fft, &n_part, st)) != hipSuccess) return e;
+            if ((e = launch_chain(c, have_old ? &c.deferred[0] : nullptr, copy_mode, a, need_fft, &n_part, &fft_parts, st)) != hipSuccess) return e;
         }
         if (have_old) {
             c.deferred[0] = c.deferred[1];
             c.n_deferred = 1;
         }
         if ((e = hipEventRecord(c.ev_fork, st)) != hipSuccess) return e;
-        if ((e = launch_split_side<T>(c, a, n_part)) != hipSuccess) return e;
+        if ((e = launch_split_side<T>(c, a, n_part, fft_parts)) != hipSuccess) return e;
         c.deferred[c.n_deferred++] = a;
         c.deferred_stream = st;
         return hipSuccess;

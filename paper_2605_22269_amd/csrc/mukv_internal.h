@@ -69,7 +69,8 @@ struct Ctx {
     // (two of each, by batch parity: with overlap_copy the keep of a batch runs beside the next
     // batch's kernels)
     float *att_part[2]; // [max_batch_frames][n_part][P]
-    float *fft_sig[2];  // [max_batch_frames][P]
+    float *fft_sig[2];  // [max_batch_frames][P], or [max_batch_frames][Hkv][P] per-head sums (matrix-core path)
+    uint16_t *dft_tab;  // matrix-core operands of the feature-axis transform (matrix-core attention, D = 128), or null
     double *att64;    // [max_chunk_frames][Hq][P] partial fp64 attention of re-scored frames
     double *fft64;    // [max_chunk_frames][P]
     int32_t *src_tok[2]; // [max_batch_frames*kappa] chunk-local token of every kept row
@@ -237,6 +238,9 @@ inline hipError_t allow_dynamic_lds(const void *kernel, size_t bytes, int device
 
 // True when the matrix-core attention kernel covers this configuration.
 bool att_mfma_supported(const mukv_config &c);
+// The length-128 transform's matrix as matrix-core operands (bf16 bits), for the frequency indicator
+// that the matrix-core attention workgroups compute on the way.
+std::vector<uint16_t> dft_operand_table();
 hipError_t launch_attend(const Ctx &c, int layer, const void *q, int n_q, const int32_t *frame_idx, int k_frame,
                          const void *k_local, const void *v_local, const int32_t *local_offsets, int B, int causal,
                          void *out, float *signal, float *workspace, hipStream_t st);
