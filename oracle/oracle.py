@@ -36,13 +36,38 @@ SEMI, HIER, PARALLEL = 0, 1, 2
 TEMPORAL, AS_GIVEN = 0, 1
 
 
-def build(force: bool = False) -> str:
-    """Compile the C half with gcc (-O2, OpenMP on the outer loops only)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _LIB, _SRC, "-lm"]
-        )
-    return _LIB
+_LIB_SAN = os.path.join(_HERE, "libmukv_oracle_san.so")
+_DRIVER = os.path.join(_HERE, "sanitize_driver.c")
+# MUKV_ORACLE_SANITIZE=1 in the environment makes every test that uses the oracle run its C half from a
+# build instrumented with UndefinedBehaviorSanitizer (any report aborts the process)
+_SANITIZE = os.environ.get("MUKV_ORACLE_SANITIZE", "0") not in ("", "0")
+
+
+def build(force: bool = False, sanitize: bool = False) -> str:
+    """Compile the C half with gcc (-O2, OpenMP on the outer loops only).  sanitize: a second library
+    built -O1 -g with -fsanitize=undefined,bounds,float-divide-by-zero and no recovery, for CPU test
+    runs (host code only; AddressSanitizer needs its runtime first in the process and so runs from an
+    executable of its own: sanitizer_selftest)."""
+    out = _LIB_SAN if sanitize else _LIB
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        flags = (["-O1", "-g", "-fsanitize=undefined,bounds,float-divide-by-zero", "-fno-sanitize-recover=all"]
+                 if sanitize else ["-O2"])
+        subprocess.check_call(["gcc", *flags, "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", out, _SRC, "-lm"])
+    return out
+
+
+def sanitizer_selftest() -> str:
+    """Builds sanitize_driver.c + mukv_oracle.c with AddressSanitizer and UndefinedBehaviorSanitizer
+    (runtime linked statically into the executable) and runs it: every function of the C half on heap
+    blocks of exactly the documented sizes.  Returns the driver's output; raises if it reports anything."""
+    exe = os.path.join(_HERE, "sanitize_driver")
+    subprocess.check_call(["gcc", "-O1", "-g", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                           "-static-libasan", "-Wall", "-o", exe, _DRIVER, _SRC, "-lm"])
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
+    if r.returncode != 0:
+        raise RuntimeError(f"sanitizer run failed ({r.returncode}):\n{r.stdout}\n{r.stderr}")
+    return r.stdout
 
 
 _lib = None
@@ -51,7 +76,7 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        _lib = ctypes.CDLL(build(sanitize=_SANITIZE))
         _lib.orc_cos.restype = ctypes.c_double
     return _lib
 

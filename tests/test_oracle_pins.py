@@ -1090,3 +1090,9 @@ class TestPrefillAttend:
         vl = rng.standard_normal((n_q, 2, 16)).astype(np.float32)
         _, sig = o.prefill_attend(0, q, [], kl, vl, True)
         np.testing.assert_allclose(sig, [(1 + 1 / 2 + 1 / 3) / 3, (1 / 2 + 1 / 3) / 3, (1 / 3) / 3], atol=1e-15)
+
+
+def test_c_half_runs_clean_under_address_and_undefined_behaviour_sanitizers():
+    # every function of mukv_oracle.c on heap blocks of exactly the documented sizes, in an executable
+    # instrumented with ASan + UBSan; MUKV_ORACLE_SANITIZE=1 runs all of these pins on a UBSan build too
+    assert "ok" in orc.sanitizer_selftest()
