@@ -1417,6 +1417,17 @@ __global__ __launch_bounds__(256) void compact_listed_kernel(CompactArgs a, cons
 
 __global__ void clear_count_kernel(int32_t *count) { *count = 0; }
 
+// Puts every unit of the batch on the re-scoring list (units of several frames go straight to the fp64 pass).
+__global__ void list_all_kernel(int32_t *list, int32_t *count, int n) {
+    for (int i = threadIdx.x; i < n; i += blockDim.x) list[i] = i;
+    if (threadIdx.x == 0) *count = n;
+}
+
+// A unit of several frames ranks thousands of min-max-normalised scores: the gap at the keep boundary is
+// below the re-scoring threshold for practically every unit, so an fp32 keep would be overruled every
+// time.  With re-scoring on, such units skip the fp32 pass: every unit is listed and the fp64 pass decides.
+static bool direct_fp64(const Ctx &c) { return c.cfg.tokens_per_frame > kMaxP && c.margin_thr > 0.0; }
+
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
@@ -1864,7 +1875,11 @@ static hipError_t launch_side(Ctx &c, const ChunkArgs &a, bool with_keep, int n_
     const bool need_att = c.cfg.alpha != 0.0 && !a.have_att_in;
     const bool need_fft = c.cfg.alpha != 1.0;
     if ((e = hipStreamWaitEvent(c.side, c.ev_fork, 0)) != hipSuccess) return e;
-    if (with_keep) {
+    if (direct_fp64(c)) {
+        hipLaunchKernelGGL(list_all_kernel, dim3(1), dim3(256), 0, c.side, c.flag_list[a.parity], c.flag_count + a.parity,
+                           a.n_frames);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    } else if (with_keep) {
         ProfScope ps(c, MUKV_K_SELECT, c.side);
         if ((e = launch_select<T, float>(c, a, c.att_part[a.parity], n_part, c.fft_sig[a.parity], 0, c.side)) != hipSuccess)
             return e;
@@ -1934,7 +1949,8 @@ template <typename T>
 static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
     hipError_t e;
     const bool need_att = c.cfg.alpha != 0.0 && !a.have_att_in;
-    const bool need_fft = c.cfg.alpha != 1.0;
+    const bool direct64 = direct_fp64(c); // no fp32 pass at all: its frequency signal is not needed either
+    const bool need_fft = c.cfg.alpha != 1.0 && !direct64;
     const bool overlap = c.cfg.overlap_copy != 0;
     const bool rescoring = c.margin_thr > 0.0;
     int n_part = c.cfg.n_q_heads, fft_parts = 0;
@@ -1997,6 +2013,11 @@ static hipError_t compress_typed(Ctx &c, const ChunkArgs &a, hipStream_t st) {
         c.deferred[c.n_deferred++] = a;
         c.deferred_stream = st;
         return hipSuccess;
+    }
+    if (direct64) { // everything of this batch is the fp64 chain's: keep, rows of every unit, segment keys
+        if ((e = hipEventRecord(c.ev_fork, st)) != hipSuccess) return e;
+        if ((e = launch_side<T>(c, a, false, n_part)) != hipSuccess) return e;
+        return wait_side(c, a.parity, st);
     }
     {
         ProfScope ps(c, MUKV_K_SELECT, st);

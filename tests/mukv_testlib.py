@@ -124,7 +124,7 @@ class Pair:
             for i in range(fused.shape[0]):
                 if not refined[f0 + i]:
                     np.testing.assert_array_equal(own[i], gpu_kept[f0 + i], err_msg=f"frame {f0 + i}")
-                elif kap < fused.shape[1] and self.refine_margin < 1.0:
+                elif kap < fused.shape[1] <= 256 and self.refine_margin < 1.0:   # (units above 256 tokens all go to the fp64 pass)
                     srt = np.sort(fused[i])[::-1]
                     assert srt[kap - 1] - srt[kap] <= self.refine_margin + 1e-6, f"frame {f0 + i}"
             f0 += fused.shape[0]
