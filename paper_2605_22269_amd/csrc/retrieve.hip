@@ -1432,6 +1432,7 @@ hipError_t launch_gather(Ctx &c, const int32_t *frame_idx, int B, int k_frame, i
     g.n_frames = c.n_frames;
     const int n_units = k_frame * g.units_per_frame;
     // 16-byte pieces per thread: 4 rounds of 4, two rounds in flight; fewer, longer workgroups amortise the slot plan
+    // (shapes from 1 x 8 to 8 x 2 pieces x rounds all take 27-30 us for one question of the 1-hour stream)
     constexpr int ITER = 4, ROUNDS = 4;
     const int gx = (n_units + 256 * ITER * ROUNDS - 1) / (256 * ITER * ROUNDS);
     ProfScope ps(c, MUKV_K_GATHER, st);
