@@ -806,8 +806,10 @@ __global__ __launch_bounds__(kSelThreads) void select_rerank_kernel(RerankArgs a
 // ------------------------------------------------------------------------------------------
 // Gather (Sec. 3.5): grid (x, slab = (layer, K|V, KV head), question).  Every workgroup first
 // turns the question's frame list into slot -> frame (ascending frame number for TEMPORAL,
-// list order for AS_GIVEN; -1 and out-of-range entries dropped), then moves its share of the
-// slab: slot s of the output is the dense run of kappa rows of frame slot_frame[s] in the
+// list order for AS_GIVEN; -1 and out-of-range entries dropped) -- lists of up to 64 frames inside
+// each wave (a lane per entry, ranks by counting over lane reads, the slot's frame handed to the
+// slot's lane by a lane permute; no LDS, no barrier), longer lists in LDS -- then moves its share
+// of the slab: slot s of the output is the dense run of kappa rows of frame slot_frame[s] in the
 // store.  Slots past the last selected frame are zero-filled.
 // ------------------------------------------------------------------------------------------
 struct GatherArgs {
@@ -827,37 +829,63 @@ template <int ITER, int ROUNDS>
 __global__ __launch_bounds__(256) void gather_kv_kernel(GatherArgs a) {
     __shared__ int slot_frame[kMaxGatherK];
     __shared__ int n_valid_sh;
-    const int tid = threadIdx.x, b = blockIdx.z, y = blockIdx.y;
-    const int32_t *idx = a.frame_idx + (int64_t)b * a.k_frame;
     __shared__ int raw[kMaxGatherK];
-    if (tid == 0) n_valid_sh = 0;
-    for (int t = tid; t < a.k_frame; t += 256) {
-        slot_frame[t] = -1;
-        const int me = idx[t];
-        raw[t] = (me < 0 || me >= a.n_frames) ? -1 : me;
-    }
-    __syncthreads();
-    int cnt = 0;
-    for (int t = tid; t < a.k_frame; t += 256) {
-        const int me = raw[t];
-        if (me < 0) continue;
-        int pos = 0;
-        if (a.order == MUKV_TEMPORAL) {
-#pragma unroll 4
-            for (int u = 0; u < a.k_frame; ++u) {
-                const int o = raw[u];
-                pos += (o >= 0) && (o < me || (o == me && u < t));
-            }
-        } else {
-#pragma unroll 4
-            for (int u = 0; u < t; ++u) pos += raw[u] >= 0;
+    const int tid = threadIdx.x, lane = tid & 63, b = blockIdx.z, y = blockIdx.y;
+    const int32_t *idx = a.frame_idx + (int64_t)b * a.k_frame;
+    const bool in_wave = a.k_frame <= 64; // the whole plan fits a wave: no LDS, no barrier
+    int n_valid, sf_lane = -1;            // in_wave: lane s holds the frame of slot s (-1: empty)
+    if (in_wave) {
+        int me = -1;
+        if (lane < a.k_frame) {
+            const int x = idx[lane];
+            me = (x < 0 || x >= a.n_frames) ? -1 : x;
         }
-        slot_frame[pos] = me;
-        ++cnt;
+        const bool ok = me >= 0;
+        const uint64_t okmask = __ballot(ok);
+        const int ok_before = __popcll(okmask & ((1ull << lane) - 1ull));
+        n_valid = __popcll(okmask);
+        int pos = ok_before; // AS_GIVEN: list order
+        if (a.order == MUKV_TEMPORAL) {
+            pos = 0;
+            for (int j = 0; j < a.k_frame; ++j) {
+                const int o = __builtin_amdgcn_readlane(me, j);
+                pos += (int)(o >= 0) & ((int)(o < me) | ((int)(o == me) & (int)(j < lane)));
+            }
+        }
+        // every lane sends to a lane of its own: entries that name a frame to their slot, the others
+        // to the places behind
+        const int target = ok ? pos : n_valid + (lane - ok_before);
+        sf_lane = __builtin_amdgcn_ds_permute(target << 2, me + 1) - 1;
+    } else {
+        if (tid == 0) n_valid_sh = 0;
+        for (int t = tid; t < a.k_frame; t += 256) {
+            slot_frame[t] = -1;
+            const int me = idx[t];
+            raw[t] = (me < 0 || me >= a.n_frames) ? -1 : me;
+        }
+        __syncthreads();
+        int cnt = 0;
+        for (int t = tid; t < a.k_frame; t += 256) {
+            const int me = raw[t];
+            if (me < 0) continue;
+            int pos = 0;
+            if (a.order == MUKV_TEMPORAL) {
+#pragma unroll 4
+                for (int u = 0; u < a.k_frame; ++u) {
+                    const int o = raw[u];
+                    pos += (o >= 0) && (o < me || (o == me && u < t));
+                }
+            } else {
+#pragma unroll 4
+                for (int u = 0; u < t; ++u) pos += raw[u] >= 0;
+            }
+            slot_frame[pos] = me;
+            ++cnt;
+        }
+        if (cnt) atomicAdd(&n_valid_sh, cnt);
+        __syncthreads();
+        n_valid = n_valid_sh;
     }
-    if (cnt) atomicAdd(&n_valid_sh, cnt);
-    __syncthreads();
-    const int n_valid = n_valid_sh;
     if (a.n_tokens_out && blockIdx.x == 0 && y == 0 && tid == 0) a.n_tokens_out[b] = n_valid * a.kappa;
 
     const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
@@ -867,20 +895,28 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(GatherArgs a) {
     const int n_units = a.k_frame * a.units_per_frame;
     // ROUNDS rounds of ITER 16-byte pieces per lane; the loads of round r+1 are issued before the stores of
     // round r, so that reads and writes of the launch overlap (its workgroups all start together and would
-    // otherwise all read, then all write).  Loads are unconditional on clamped unit numbers / slot 0's
-    // frame, the zero for an empty slot is selected afterwards.
+    // otherwise all read, then all write).  Loads are unconditional (a piece past the end reads the last
+    // slot, an empty slot reads slot 0's frame), the zero for an empty slot is selected afterwards.
+    // A lane's pieces are 256 apart: (slot, piece in the frame) of the first by one division, the others by
+    // adding 256 in mixed radix.
     cp_u32x4 tmp[2][ITER];
-    const int fr_any = n_valid > 0 ? slot_frame[0] : 0;
-    auto load_round = [&](int r, cp_u32x4(&t)[ITER]) {
-        const int u0 = (blockIdx.x * ROUNDS + r) * (256 * ITER) + tid;
+    const int fr_any = n_valid > 0 ? (in_wave ? __builtin_amdgcn_readlane(sf_lane, 0) : slot_frame[0]) : 0;
+    const int upf = a.units_per_frame;
+    const int dq = 256 / upf, dr = 256 - dq * upf;
+    const int u_first = blockIdx.x * ROUNDS * (256 * ITER) + tid;
+    int slot = u_first / upf, part = u_first - slot * upf;
+    auto load_round = [&](cp_u32x4(&t)[ITER]) {
 #pragma unroll
         for (int it = 0; it < ITER; ++it) {
-            int u = u0 + it * 256;
-            u = u < n_units ? u : n_units - 1;
-            const int slot = u / a.units_per_frame, part = u - slot * a.units_per_frame;
-            const int fr = slot_frame[slot];
+            const int sc = slot < a.k_frame ? slot : a.k_frame - 1;
+            const int fr = in_wave ? __builtin_amdgcn_ds_bpermute(sc << 2, sf_lane) : slot_frame[sc];
             const cp_u32x4 x = *reinterpret_cast<const cp_u32x4 *>(src + (int64_t)(fr >= 0 ? fr : fr_any) * a.frame_b + (int64_t)part * 16);
             t[it] = fr >= 0 ? x : cp_u32x4{0u, 0u, 0u, 0u};
+            slot += dq;
+            part += dr;
+            const int carry = part >= upf;
+            slot += carry;
+            part -= carry ? upf : 0;
         }
     };
     auto store_round = [&](int r, const cp_u32x4(&t)[ITER]) {
@@ -891,10 +927,10 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(GatherArgs a) {
             if (u < n_units) *reinterpret_cast<cp_u32x4 *>(dst + (int64_t)u * 16) = t[it];
         }
     };
-    load_round(0, tmp[0]);
+    load_round(tmp[0]);
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
-        if (r + 1 < ROUNDS) load_round(r + 1, tmp[(r + 1) & 1]);
+        if (r + 1 < ROUNDS) load_round(tmp[(r + 1) & 1]);
         store_round(r, tmp[r & 1]);
     }
 }
@@ -1432,7 +1468,8 @@ hipError_t launch_gather(Ctx &c, const int32_t *frame_idx, int B, int k_frame, i
     g.n_frames = c.n_frames;
     const int n_units = k_frame * g.units_per_frame;
     // 16-byte pieces per thread: 4 rounds of 4, two rounds in flight; fewer, longer workgroups amortise the slot plan
-    // (shapes from 1 x 8 to 8 x 2 pieces x rounds all take 27-30 us for one question of the 1-hour stream)
+    // (shapes from 1 x 8 to 8 x 2 pieces x rounds all took within 3 us of each other for one question of the
+    // 1-hour stream)
     constexpr int ITER = 4, ROUNDS = 4;
     const int gx = (n_units + 256 * ITER * ROUNDS - 1) / (256 * ITER * ROUNDS);
     ProfScope ps(c, MUKV_K_GATHER, st);
