@@ -116,6 +116,14 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+typedef __attribute__((ext_vector_type(4))) short i16x4;
+typedef __attribute__((ext_vector_type(8))) short i16x8;
+// ds_read_b64_tr_b16, the LDS transpose read of 16-bit elements: every lane names 8 bytes; within each block
+// of 16 lanes, result[t] of lane i is element i % 4 of the 8 bytes named by lane 4 * t + i / 4 of the block,
+// t = 0..3 (lane layout checked by an in-bounds probe on the device).
+__device__ __forceinline__ i16x4 lds_read_tr16(const unsigned char *p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3))) *)(p));
+}
 
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) {
@@ -133,7 +141,8 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
     __shared__ float s_run[kTileQ];  // running maximum of every query over the chunks so far
     __shared__ float s_corr[kTileQ]; // factor that brings the sums so far to the new maximum
     __shared__ float s_ref[kTileQ];  // what the exponent subtracts: the running maximum, or 0 while nothing was seen
-    __shared__ float s_z[kWaves][kTileQ];
+    __shared__ float s_zq[kTileQ];
+    __shared__ __align__(16) float s_p[kChunk][kTileQ]; // softmax weights of the chunk (unnormalised), row-major
     __shared__ int s_frame[kMaxGatherK]; // this split's frames; -1: names no frame of the cache
     const int sp = blockIdx.x, g = blockIdx.y % a.Hkv, qt = blockIdx.y / a.Hkv, b = blockIdx.z;
     const int tid = threadIdx.x, li = tid % LPR, rg = tid / LPR, wave = tid >> 6, lane = tid & 63;
@@ -194,17 +203,48 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
         return store;
     };
 
-    float z[kTileQ], o[kTileQ][E];
+    float o[kTileQ][E];
+    float zq = 0.f; // this thread's share of the normaliser of query tid / 32
+    static_assert(kThreads / 32 == kTileQ, "32 threads per query in the weight pass");
     if (tid < kTileQ) s_run[tid] = -INFINITY; // read again only after the barriers of the first chunk
 #pragma unroll
     for (int n = 0; n < kTileQ; ++n) {
-        z[n] = 0.f;
 #pragma unroll
         for (int e = 0; e < E; ++e) o[n][e] = 0.f;
     }
 
+    // a batch of value rows: kUnroll rows per lane, RPP rows apart.  Loads are unconditional (a row past the
+    // chunk reads the chunk's last row, a row that lives nowhere the slab's first row); what was loaded
+    // instead of a row is not used.
+    raw16 va[kUnroll], vb[kUnroll];
+    int n_rows = 0;
+    auto load_v = [&](raw16(&buf)[kUnroll], int i0) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int i = i0 + u * RPP;
+            buf[u] = load16(row_ptr(sv, lv, s_row[i < n_rows ? i : n_rows - 1]) + li * E);
+        }
+    };
+    auto use_v = [&](const raw16(&buf)[kUnroll], int i0) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int i = i0 + u * RPP;
+            if (i >= n_rows || s_row[i] == -1) continue;
+            float vx[E];
+            Row16<T>::expand(buf[u], vx);
+            const f32x4 p0 = *reinterpret_cast<const f32x4 *>(&s_p[i][0]);
+            const f32x4 p1 = *reinterpret_cast<const f32x4 *>(&s_p[i][4]);
+#pragma unroll
+            for (int n = 0; n < kTileQ; ++n) {
+                const float p = n < 4 ? p0[n & 3] : p1[n & 3];
+#pragma unroll
+                for (int e = 0; e < E; ++e) o[n][e] = fmaf(p, vx[e], o[n][e]);
+            }
+        }
+    };
+
     for (int c0 = 0; c0 < total; c0 += kChunk) {
-        const int n_rows = (c0 + kChunk < total ? c0 + kChunk : total) - c0;
+        n_rows = (c0 + kChunk < total ? c0 + kChunk : total) - c0;
         // ---- where the rows of the chunk live and who sees them ----
         for (int i = tid; i < n_rows; i += kThreads) {
             const int r = c0 + i;
@@ -312,6 +352,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
                 if (lane == 0) s_wmax[wave][n] = m;
             }
         }
+        load_v(va, rg); // the first value rows are on their way while the maxima are agreed on
         __syncthreads();
         // ---- new running maximum: rescale what has been summed so far (once per chunk) ----
         if (tid < kTileQ) {
@@ -328,36 +369,28 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
 #pragma unroll
             for (int n = 0; n < kTileQ; ++n) {
                 const float corr = s_corr[n];
-                z[n] *= corr;
 #pragma unroll
                 for (int e = 0; e < E; ++e) o[n][e] *= corr;
             }
         }
-        // ---- weights and value accumulation ----
-        for (int i0 = rg; i0 < n_rows; i0 += kUnroll * RPP) {
-            bool seen[kUnroll];
-            raw16 vr[kUnroll];
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const int i = i0 + u * RPP;
-                const int code = s_row[i < n_rows ? i : n_rows - 1];
-                seen[u] = i < n_rows && code != -1;
-                vr[u] = load16(row_ptr(sv, lv, code) + li * E);
+        // ---- the weights, once per (row, query): 32 threads per query walk the rows; their sums ----
+        {
+            const int n = tid >> 5;
+            const float ref = s_ref[n];
+            if (c0 > 0) zq *= s_corr[n];
+            for (int i = tid & 31; i < n_rows; i += 32) {
+                const float p = __builtin_amdgcn_exp2f(s_sc[n][i] - ref); // exp2(-inf) = 0 for a masked row
+                s_p[i][n] = p;
+                zq += p;
             }
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                if (!seen[u]) continue; // what was loaded instead of a row that lives nowhere is not a value
-                const int i = i0 + u * RPP;
-                float vx[E];
-                Row16<T>::expand(vr[u], vx);
-#pragma unroll
-                for (int n = 0; n < kTileQ; ++n) {
-                    const float p = __builtin_amdgcn_exp2f(s_sc[n][i] - s_ref[n]); // exp2(-inf) = 0 for a masked row
-                    z[n] += p;
-#pragma unroll
-                    for (int e = 0; e < E; ++e) o[n][e] = fmaf(p, vx[e], o[n][e]);
-                }
-            }
+        }
+        __syncthreads();
+        // ---- value accumulation: two batches of kUnroll rows per lane in flight, one being used ----
+        for (int i0 = rg; i0 < n_rows; i0 += 2 * kUnroll * RPP) {
+            load_v(vb, i0 + kUnroll * RPP);
+            use_v(va, i0);
+            load_v(va, i0 + 2 * kUnroll * RPP);
+            use_v(vb, i0 + kUnroll * RPP);
         }
         __syncthreads(); // the tables are rewritten by the next chunk
     }
@@ -365,29 +398,36 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
     // ---- add the rows held by different lanes: inside a wave, then across the waves ----
 #pragma unroll
     for (int n = 0; n < kTileQ; ++n) {
-        z[n] = same_piece_sum<LPR>(z[n]);
 #pragma unroll
         for (int e = 0; e < E; ++e) o[n][e] = same_piece_sum<LPR>(o[n][e]);
     }
+    zq += lane_xor<1>(zq); // the 32 threads of a query are half a wave
+    zq += lane_xor<2>(zq);
+    zq += lane_xor<4>(zq);
+    zq += lane_xor<8>(zq);
+    zq += __shfl_xor(zq, 16);
     if (lane < LPR) {
 #pragma unroll
         for (int n = 0; n < kTileQ; ++n)
 #pragma unroll
             for (int e = 0; e < E; ++e) s_sc[n][wave * (D > 64 ? D : 64) + li * E + e] = o[n][e];
     }
-    if (lane == 0) {
-#pragma unroll
-        for (int n = 0; n < kTileQ; ++n) s_z[wave][n] = z[n];
-    }
+    if ((tid & 31) == 0) s_zq[tid >> 5] = zq;
     __syncthreads();
     // the split's record of a query: [0] running maximum, [1] normaliser, [2..] unnormalised output
+    // (merged by a launch of its own: a merge by the last workgroup to finish, with records that cross the
+    // XCDs' L2 caches as device-scope atomics, took as long as that launch for 64 questions and longer for one)
     for (int idx = tid; idx < kTileQ * (D + 1); idx += kThreads) {
         const int n = idx / (D + 1), d = idx - n * (D + 1);
         const int qq = qt * kTileQ + n;
         if (qq >= n_queries) continue;
         float val = 0.f;
+        if (d == 0) {
+            val = s_zq[n];
+        } else {
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) val += d == 0 ? s_z[w][n] : s_sc[n][w * (D > 64 ? D : 64) + d - 1];
+            for (int w = 0; w < kWaves; ++w) val += s_sc[n][w * (D > 64 ? D : 64) + d - 1];
+        }
         const int i = qq / a.G, h = g * a.G + qq % a.G;
         a.part[((((int64_t)b * a.n_q + i) * a.Hq + h) * a.n_split + sp) * (D + 2) + 1 + d] = val;
     }
@@ -758,18 +798,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QB == 1 ? 3
             if (lane == 0) s_chg[QB * wave + i] = any_moved;
         }
         __syncthreads(); // weights and factors of step t are in LDS
+        // The B operand wants 8 rows of ONE feature per lane while the staged values are row-major: the LDS
+        // transpose read hands lane n of a 16-lane block column n of a 4 x 16 tile whose row t is named by
+        // lanes 4t .. 4t+3 of the block, 4 features each -- two such reads per operand.
         bf16x8 bv[2];
 #pragma unroll
         for (int db = 0; db < 2; ++db) {
-            const unsigned char *vp = s_v[buf] + (8 * lg) * kRowStride + 2 * (32 * wave + 16 * db + lr);
-            uint32_t w[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t lo = *reinterpret_cast<const uint16_t *>(vp + (2 * e) * kRowStride);
-                const uint32_t hi = *reinterpret_cast<const uint16_t *>(vp + (2 * e + 1) * kRowStride);
-                w[e] = lo | (hi << 16);
-            }
-            bv[db] = __builtin_bit_cast(bf16x8, raw16{w[0], w[1], w[2], w[3]});
+            const unsigned char *vp = s_v[buf] + (8 * lg + (lr >> 2)) * kRowStride + 2 * (32 * wave + 16 * db + 4 * (lr & 3));
+            const i16x4 lo = lds_read_tr16(vp), hi = lds_read_tr16(vp + 4 * kRowStride);
+            bv[db] = __builtin_bit_cast(bf16x8, i16x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
         }
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb) {
@@ -924,6 +961,8 @@ int split_count(int B, int Hkv, int n_qtiles, int k_frame, int *frames_per_split
     // about three workgroups per compute unit (what fits at once): a workgroup walks its rows in
     // dependent batches of loads, so shorter lists finish sooner; at most kAttendMaxSplit splits,
     // at least one frame each
+    // (64 questions of the 1-hour shape: 2 or 3 per compute unit take the same 28 us, 1 takes 37, 4 / 6 / 8 take
+    // 34 / 38 / 43 -- every workgroup pays its chain of dependent steps once more)
     int64_t n_split = (3 * 256 + (int64_t)B * Hkv * n_qtiles - 1) / ((int64_t)B * Hkv * n_qtiles);
     if (n_split > kAttendMaxSplit) n_split = kAttendMaxSplit;
     if (n_split > k_frame) n_split = k_frame;
