@@ -13,9 +13,15 @@
 //      the A operand loaded straight from the row (lane % 16 = row, 8 features from
 //      8 * (lane / 16) of every 32).  Otherwise: a row spread over D/E lanes (E = elements in 16
 //      bytes), dot products reduced over those lanes;
-//   3. with that maximum fixed, exp2 and the value accumulation (a value row spread over D/E
-//      lanes, 256*E/D rows in flight per pass, four passes of loads issued together) -- so the
-//      running sums are rescaled once per chunk, not once per row.
+//   3. with that maximum fixed, the weights exp2(score - maximum), once per (row, query), and their sums --
+//      so the running sums are rescaled once per chunk, not once per row;
+//   4. the value accumulation.  bf16 rows of 32, 64 or 128 features: O = P V on the matrix cores -- the
+//      weights as bf16 pairs hi + lo (two products, nothing of the fp32 weight is lost) are the A operand,
+//      the value rows pass through LDS 64 at a time, row-major as they come from memory, and the LDS
+//      transpose read (ds_read_b64_tr_b16) hands every lane the 8 rows of one feature that the B operand
+//      wants; a wave owns 16-feature tiles of the output, so nothing is left to add across lanes.
+//      Otherwise: a value row spread over D/E lanes, 256*E/D rows per pass, multiply-adds on the VALU and a
+//      sum over the lanes that hold the same piece of different rows.
 // The split's (maximum, normaliser, unnormalised output) per query go to a scratch table;
 // attend_combine_kernel merges the splits and writes the output in the payload type.
 // Everything is summed in a fixed order: the result does not depend on timing.
@@ -126,15 +132,26 @@ __device__ __forceinline__ i16x4 lds_read_tr16(const unsigned char *p) {
 }
 
 template <typename T, int D>
-__global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) void attend_partial_kernel(AttendArgs a) {
     constexpr int E = Row16<T>::E, LPR = D / E, RPP = kThreads / LPR; // lanes per row, rows per pass
     // bf16 rows whose length is a multiple of 32: the scores come from the matrix cores
     constexpr bool kMfma = sizeof(T) == 2 && D % 32 == 0;
     constexpr int kWaves = kThreads / 64;
     static_assert(LPR >= 1 && LPR <= 32, "a row fits in half a wave");
-    // scores of the chunk, log2 units; after the last chunk the same memory takes the per-wave outputs
-    __shared__ float s_sc[kTileQ][kChunk];
+    // Matrix path, value side: the chunk's value rows pass through LDS kSub at a time (row-major, padded rows) and
+    // come back as B operands by the LDS transpose read; the weights are bf16 pairs (hi + lo, so that nothing of
+    // the fp32 weight is lost) as A operands; a wave owns TPW 16-feature tiles of the output.
+    constexpr int kSub = 64, kVStride = D * 2 + 16;
+    constexpr int NP = kMfma ? kSub / RPP : 1; // 16-byte pieces of kSub rows per thread
+    constexpr int NT = D / 16, TPW = NT >= kWaves ? NT / kWaves : 1;
+    constexpr int kPRow = kChunk * 2 + 16; // bytes of a query's row of bf16 weights
+    // scores of the chunk, log2 units (rows padded by 8 floats).  VALU path: after the last chunk the same memory
+    // takes the per-wave outputs.  Matrix path: the weight pass rewrites it as the hi rows, then the lo rows.
+    __shared__ __align__(16) float s_sc[kTileQ][kChunk + 8];
     static_assert(kWaves * (D > 64 ? D : 64) <= kChunk, "the per-wave outputs fit where the scores were");
+    static_assert(2 * kTileQ * kPRow <= (int)sizeof(s_sc), "hi and lo weights fit where the scores were");
+    unsigned char *const s_ph = reinterpret_cast<unsigned char *>(&s_sc[0][0]);
+    unsigned char *const s_pl = s_ph + kTileQ * kPRow;
     __shared__ int s_row[kChunk]; // where row i of the chunk lives: >= 0 store row, <= -2 local row -2 - code, -1 nowhere
     __shared__ int s_ft[kChunk];  // first token that sees the row (INT_MAX: nobody does)
     __shared__ float s_wmax[kWaves][kTileQ]; // per-wave maxima of the chunk
@@ -142,7 +159,10 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
     __shared__ float s_corr[kTileQ]; // factor that brings the sums so far to the new maximum
     __shared__ float s_ref[kTileQ];  // what the exponent subtracts: the running maximum, or 0 while nothing was seen
     __shared__ float s_zq[kTileQ];
-    __shared__ __align__(16) float s_p[kChunk][kTileQ]; // softmax weights of the chunk (unnormalised), row-major
+    // VALU path: softmax weights of the chunk (unnormalised), row-major.  Matrix path: kSub staged value rows.
+    __shared__ __align__(16) unsigned char s_u[kMfma ? kSub * kVStride : kChunk * kTileQ * 4];
+    float(*const s_p)[kTileQ] = reinterpret_cast<float(*)[kTileQ]>(s_u);
+    unsigned char *const s_v = s_u;
     __shared__ int s_frame[kMaxGatherK]; // this split's frames; -1: names no frame of the cache
     const int sp = blockIdx.x, g = blockIdx.y % a.Hkv, qt = blockIdx.y / a.Hkv, b = blockIdx.z;
     const int tid = threadIdx.x, li = tid % LPR, rg = tid / LPR, wave = tid >> 6, lane = tid & 63;
@@ -176,6 +196,18 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
         }
     }
 
+    bf16x8 qb[kMfma ? D / 32 : 1]; // requested before anything else, needed after the first tables
+    if constexpr (kMfma) {
+        bool ok;
+        const int64_t off = query_row(lr, &ok);
+#pragma unroll
+        for (int kk = 0; kk < D / 32; ++kk) {
+            raw16 u = load16(q + off + kk * 32 + lg * 8);
+            if (!ok) u = raw16{0u, 0u, 0u, 0u};
+            qb[kk] = __builtin_bit_cast(bf16x8, u);
+        }
+    }
+
     // rows of this split: kept rows of its frames, then (last split only) the local rows
     const int f_lo = sp * a.frames_per_split;
     const int f_hi = f_lo + a.frames_per_split < a.k_frame ? f_lo + a.frames_per_split : a.k_frame;
@@ -203,43 +235,31 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
         return store;
     };
 
-    float o[kTileQ][E];
+    float o[kMfma ? 1 : kTileQ][E]; // VALU path: this lane's 16-byte piece of the output of every query
+    f32x4 acc[TPW];                 // matrix path: queries 4 * (lane / 16) + r, feature 16 * tile + lane % 16
     float zq = 0.f; // this thread's share of the normaliser of query tid / 32
     static_assert(kThreads / 32 == kTileQ, "32 threads per query in the weight pass");
     if (tid < kTileQ) s_run[tid] = -INFINITY; // read again only after the barriers of the first chunk
 #pragma unroll
-    for (int n = 0; n < kTileQ; ++n) {
+    for (int n = 0; n < (kMfma ? 1 : kTileQ); ++n) {
 #pragma unroll
         for (int e = 0; e < E; ++e) o[n][e] = 0.f;
     }
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // a batch of value rows: kUnroll rows per lane, RPP rows apart.  Loads are unconditional (a row past the
-    // chunk reads the chunk's last row, a row that lives nowhere the slab's first row); what was loaded
-    // instead of a row is not used.
-    raw16 va[kUnroll], vb[kUnroll];
+    // matrix path: this thread's pieces of kSub value rows, on their way while the rows before them are used.
+    // Loads are unconditional (a row that lives nowhere, or past the chunk, reads the slab's first row); what
+    // was loaded instead of a row becomes zeros (its weights are zero, but zero times anything must stay zero).
+    raw16 vx[NP];
     int n_rows = 0;
-    auto load_v = [&](raw16(&buf)[kUnroll], int i0) {
+    auto load_sub = [&](raw16(&vreg)[NP], int sub) {
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int i = i0 + u * RPP;
-            buf[u] = load16(row_ptr(sv, lv, s_row[i < n_rows ? i : n_rows - 1]) + li * E);
-        }
-    };
-    auto use_v = [&](const raw16(&buf)[kUnroll], int i0) {
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int i = i0 + u * RPP;
-            if (i >= n_rows || s_row[i] == -1) continue;
-            float vx[E];
-            Row16<T>::expand(buf[u], vx);
-            const f32x4 p0 = *reinterpret_cast<const f32x4 *>(&s_p[i][0]);
-            const f32x4 p1 = *reinterpret_cast<const f32x4 *>(&s_p[i][4]);
-#pragma unroll
-            for (int n = 0; n < kTileQ; ++n) {
-                const float p = n < 4 ? p0[n & 3] : p1[n & 3];
-#pragma unroll
-                for (int e = 0; e < E; ++e) o[n][e] = fmaf(p, vx[e], o[n][e]);
-            }
+        for (int p = 0; p < NP; ++p) {
+            const int i = sub * kSub + p * RPP + rg;
+            const int code = i < n_rows ? s_row[i] : -1;
+            const raw16 x = load16(row_ptr(sv, lv, code) + li * E);
+            vreg[p] = code == -1 ? raw16{0u, 0u, 0u, 0u} : x;
         }
     };
 
@@ -266,23 +286,13 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
         if constexpr (kMfma) {
             // 16 rows per wave and step: S^T = K Q^T, so a lane ends up with one query (lane % 16)
             // and the four rows 4 * (lane / 16) .. +3 of the step
-            // (the operand is fetched per chunk so that it is not held through the value pass)
-            bf16x8 qb[D / 32];
-            {
-                bool ok;
-                const int64_t off = query_row(lr, &ok);
-#pragma unroll
-                for (int kk = 0; kk < D / 32; ++kk) {
-                    raw16 u = load16(q + off + kk * 32 + lg * 8);
-                    if (!ok) u = raw16{0u, 0u, 0u, 0u};
-                    qb[kk] = __builtin_bit_cast(bf16x8, u);
-                }
-            }
             const int my_tok = token_of(lr);
             float m_q = -INFINITY;
-            for (int R0 = 16 * wave; R0 < n_rows; R0 += kStepsA * 16 * kWaves) {
-                // the key rows of kStepsA steps are requested together
-                raw16 ka[kStepsA][D / 32];
+            // the key rows of kStepsA steps are requested together (rows past the chunk read its last row again:
+            // loads stay unconditional).  Requesting the next batch before this one is used, and larger batches,
+            // were measured and changed nothing: the launch moves its rows at the pace of the memory
+            constexpr int kBatch = kStepsA * 16 * kWaves;
+            auto load_k = [&](raw16(&ka)[kStepsA][D / 32], int R0) {
 #pragma unroll
                 for (int t = 0; t < kStepsA; ++t) {
                     const int i = R0 + t * 16 * kWaves + lr;
@@ -290,6 +300,8 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
 #pragma unroll
                     for (int kk = 0; kk < D / 32; ++kk) ka[t][kk] = load16(kp + kk * 32);
                 }
+            };
+            auto use_k = [&](const raw16(&ka)[kStepsA][D / 32], int R0) {
 #pragma unroll
                 for (int t = 0; t < kStepsA; ++t) {
                     const int R = R0 + t * 16 * kWaves;
@@ -308,6 +320,11 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
                         }
                     }
                 }
+            };
+            raw16 kx[kStepsA][D / 32];
+            for (int R0 = 16 * wave; R0 < n_rows; R0 += kBatch) {
+                load_k(kx, R0);
+                use_k(kx, R0);
             }
             m_q = xrow_max(m_q);
             if (lg == 0 && lr < kTileQ) s_wmax[wave][lr] = m_q;
@@ -352,7 +369,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
                 if (lane == 0) s_wmax[wave][n] = m;
             }
         }
-        load_v(va, rg); // the first value rows are on their way while the maxima are agreed on
+        if constexpr (kMfma) load_sub(vx, 0); // the first value rows are on their way while the maxima are agreed on
         __syncthreads();
         // ---- new running maximum: rescale what has been summed so far (once per chunk) ----
         if (tid < kTileQ) {
@@ -365,77 +382,178 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(AttendArgs a) 
             s_ref[tid] = m_new == -INFINITY ? 0.f : m_new;
         }
         __syncthreads();
-        if (c0 > 0) {
+        if constexpr (kMfma) {
+            if (c0 > 0) {
 #pragma unroll
-            for (int n = 0; n < kTileQ; ++n) {
-                const float corr = s_corr[n];
+                for (int r = 0; r < 4; ++r) {
+                    const float corr = s_corr[(4 * lg + r) & (kTileQ - 1)];
 #pragma unroll
-                for (int e = 0; e < E; ++e) o[n][e] *= corr;
+                    for (int t = 0; t < TPW; ++t) acc[t][r] *= corr;
+                }
             }
-        }
-        // ---- the weights, once per (row, query): 32 threads per query walk the rows; their sums ----
-        {
+            // ---- the weights, once per (row, query): 32 threads per query walk the rows; their sums.  The
+            // scores are taken into registers first, then the same memory receives the weights as bf16 pairs;
+            // rows up to the next multiple of kSub get zero weights ----
             const int n = tid >> 5;
             const float ref = s_ref[n];
             if (c0 > 0) zq *= s_corr[n];
-            for (int i = tid & 31; i < n_rows; i += 32) {
-                const float p = __builtin_amdgcn_exp2f(s_sc[n][i] - ref); // exp2(-inf) = 0 for a masked row
-                s_p[i][n] = p;
-                zq += p;
+            const int n_pad = (n_rows + kSub - 1) / kSub * kSub;
+            float sreg[kChunk / 32];
+#pragma unroll
+            for (int k = 0; k < kChunk / 32; ++k) {
+                const int i = (tid & 31) + 32 * k;
+                sreg[k] = i < n_rows ? s_sc[n][i] : -INFINITY;
             }
-        }
-        __syncthreads();
-        // ---- value accumulation: two batches of kUnroll rows per lane in flight, one being used ----
-        for (int i0 = rg; i0 < n_rows; i0 += 2 * kUnroll * RPP) {
-            load_v(vb, i0 + kUnroll * RPP);
-            use_v(va, i0);
-            load_v(va, i0 + 2 * kUnroll * RPP);
-            use_v(vb, i0 + kUnroll * RPP);
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < kChunk / 32; ++k) {
+                if (32 * k >= n_pad) break;
+                const int i = (tid & 31) + 32 * k;
+                const float p = __builtin_amdgcn_exp2f(sreg[k] - ref); // exp2(-inf) = 0 for a masked row
+                zq += p;
+                const uint16_t hi = bf16_round(p);
+                const uint16_t lo = bf16_round(p - __uint_as_float((uint32_t)hi << 16));
+                *reinterpret_cast<uint16_t *>(s_ph + n * kPRow + 2 * i) = hi;
+                *reinterpret_cast<uint16_t *>(s_pl + n * kPRow + 2 * i) = lo;
+            }
+            // ---- value accumulation on the matrix cores, kSub rows at a time ----
+            const int n_sub = n_pad / kSub;
+            // stage the rows held in vreg, request the next ones, multiply (two sets of rows in flight, like
+            // larger sets, were measured and changed nothing)
+            auto do_sub = [&](raw16(&vreg)[NP], int sub) {
+                __syncthreads(); // the rows staged before have been used (first time round: the weights are written)
+#pragma unroll
+                for (int p = 0; p < NP; ++p)
+                    *reinterpret_cast<raw16 *>(s_v + (p * RPP + rg) * kVStride + li * 16) = vreg[p];
+                __syncthreads();
+                if (sub + 1 < n_sub) load_sub(vreg, sub + 1);
+                if (wave * TPW < NT) {
+#pragma unroll
+                    for (int st = 0; st < kSub / 32; ++st) {
+                        const int r0 = sub * kSub + 32 * st;
+                        if (r0 >= n_rows) break;
+                        const unsigned char *pa = s_ph + (lr & (kTileQ - 1)) * kPRow + 2 * (r0 + 8 * lg);
+                        const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const raw16 *>(pa));
+                        const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const raw16 *>(pa + kTileQ * kPRow));
+#pragma unroll
+                        for (int t = 0; t < TPW; ++t) {
+                            const unsigned char *vp = s_v + (32 * st + 8 * lg + (lr >> 2)) * kVStride +
+                                                      2 * (16 * (wave * TPW + t) + 4 * (lr & 3));
+                            const i16x4 v0 = lds_read_tr16(vp), v1 = lds_read_tr16(vp + 4 * kVStride);
+                            const bf16x8 bv = __builtin_bit_cast(bf16x8, i16x8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]});
+                            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, bv, acc[t], 0, 0, 0);
+                            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, bv, acc[t], 0, 0, 0);
+                        }
+                    }
+                }
+            };
+            for (int sub = 0; sub < n_sub; ++sub) do_sub(vx, sub);
+        } else {
+            if (c0 > 0) {
+#pragma unroll
+                for (int n = 0; n < kTileQ; ++n) {
+                    const float corr = s_corr[n];
+#pragma unroll
+                    for (int e = 0; e < E; ++e) o[n][e] *= corr;
+                }
+            }
+            // ---- the weights, once per (row, query): 32 threads per query walk the rows; their sums ----
+            {
+                const int n = tid >> 5;
+                const float ref = s_ref[n];
+                if (c0 > 0) zq *= s_corr[n];
+                for (int i = tid & 31; i < n_rows; i += 32) {
+                    const float p = __builtin_amdgcn_exp2f(s_sc[n][i] - ref); // exp2(-inf) = 0 for a masked row
+                    s_p[i][n] = p;
+                    zq += p;
+                }
+            }
+            __syncthreads();
+            // ---- value accumulation: a value row spread over LPR lanes, kUnroll rows per lane in flight ----
+            for (int i0 = rg; i0 < n_rows; i0 += kUnroll * RPP) {
+                raw16 vr[kUnroll];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    const int i = i0 + u * RPP;
+                    vr[u] = load16(row_ptr(sv, lv, s_row[i < n_rows ? i : n_rows - 1]) + li * E);
+                }
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    const int i = i0 + u * RPP;
+                    if (i >= n_rows || s_row[i] == -1) continue; // what was loaded instead of a row is not a value
+                    float vx[E];
+                    Row16<T>::expand(vr[u], vx);
+                    const f32x4 p0 = *reinterpret_cast<const f32x4 *>(&s_p[i][0]);
+                    const f32x4 p1 = *reinterpret_cast<const f32x4 *>(&s_p[i][4]);
+#pragma unroll
+                    for (int n = 0; n < kTileQ; ++n) {
+                        const float p = n < 4 ? p0[n & 3] : p1[n & 3];
+#pragma unroll
+                        for (int e = 0; e < E; ++e) o[n][e] = fmaf(p, vx[e], o[n][e]);
+                    }
+                }
+            }
         }
         __syncthreads(); // the tables are rewritten by the next chunk
     }
 
-    // ---- add the rows held by different lanes: inside a wave, then across the waves ----
-#pragma unroll
-    for (int n = 0; n < kTileQ; ++n) {
-#pragma unroll
-        for (int e = 0; e < E; ++e) o[n][e] = same_piece_sum<LPR>(o[n][e]);
-    }
     zq += lane_xor<1>(zq); // the 32 threads of a query are half a wave
     zq += lane_xor<2>(zq);
     zq += lane_xor<4>(zq);
     zq += lane_xor<8>(zq);
     zq += __shfl_xor(zq, 16);
-    if (lane < LPR) {
-#pragma unroll
-        for (int n = 0; n < kTileQ; ++n)
-#pragma unroll
-            for (int e = 0; e < E; ++e) s_sc[n][wave * (D > 64 ? D : 64) + li * E + e] = o[n][e];
-    }
     if ((tid & 31) == 0) s_zq[tid >> 5] = zq;
-    __syncthreads();
     // the split's record of a query: [0] running maximum, [1] normaliser, [2..] unnormalised output
     // (merged by a launch of its own: a merge by the last workgroup to finish, with records that cross the
     // XCDs' L2 caches as device-scope atomics, took as long as that launch for 64 questions and longer for one)
-    for (int idx = tid; idx < kTileQ * (D + 1); idx += kThreads) {
-        const int n = idx / (D + 1), d = idx - n * (D + 1);
+    auto record = [&](int n) -> float * { // of query n of the tile; null: no such query
         const int qq = qt * kTileQ + n;
-        if (qq >= n_queries) continue;
-        float val = 0.f;
-        if (d == 0) {
-            val = s_zq[n];
-        } else {
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) val += s_sc[n][w * (D > 64 ? D : 64) + d - 1];
-        }
+        if (qq >= n_queries) return nullptr;
         const int i = qq / a.G, h = g * a.G + qq % a.G;
-        a.part[((((int64_t)b * a.n_q + i) * a.Hq + h) * a.n_split + sp) * (D + 2) + 1 + d] = val;
+        return a.part + ((((int64_t)b * a.n_q + i) * a.Hq + h) * a.n_split + sp) * (D + 2);
+    };
+    if constexpr (kMfma) {
+        // the matrix cores have added all rows already: a lane writes what it holds (lanes 32.. hold copies)
+        if (lg < 2 && wave * TPW < NT) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float *rec = record(4 * lg + r);
+                if (!rec) continue;
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) rec[2 + 16 * (wave * TPW + t) + lr] = acc[t][r];
+            }
+        }
+        __syncthreads();
+    } else {
+        // ---- add the rows held by different lanes: inside a wave, then across the waves ----
+#pragma unroll
+        for (int n = 0; n < kTileQ; ++n) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) o[n][e] = same_piece_sum<LPR>(o[n][e]);
+        }
+        __syncthreads(); // (every wave is done with the chunk's scores)
+        if (lane < LPR) {
+#pragma unroll
+            for (int n = 0; n < kTileQ; ++n)
+#pragma unroll
+                for (int e = 0; e < E; ++e) s_sc[n][wave * (D > 64 ? D : 64) + li * E + e] = o[n][e];
+        }
+        __syncthreads();
+        for (int idx = tid; idx < kTileQ * D; idx += kThreads) {
+            const int n = idx / D, d = idx - n * D;
+            float *rec = record(n);
+            if (!rec) continue;
+            float val = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) val += s_sc[n][w * (D > 64 ? D : 64) + d];
+            rec[2 + d] = val;
+        }
     }
     if (tid < kTileQ) {
-        const int qq = qt * kTileQ + tid;
-        if (qq < n_queries) {
-            const int i = qq / a.G, h = g * a.G + qq % a.G;
-            a.part[((((int64_t)b * a.n_q + i) * a.Hq + h) * a.n_split + sp) * (D + 2)] = s_run[tid];
+        float *rec = record(tid);
+        if (rec) {
+            rec[0] = s_run[tid];
+            rec[1] = s_zq[tid];
         }
     }
 }
@@ -448,16 +566,28 @@ __global__ void attend_combine_kernel(const float *__restrict__ part, int n_spli
                                       float *__restrict__ lse) {
     const int64_t row = blockIdx.x;
     const float *p = part + row * n_split * (D + 2);
-    float m = -INFINITY;
-    for (int s = 0; s < n_split; ++s) m = fmaxf(m, p[s * (D + 2)]);
     for (int d = threadIdx.x; d < D; d += blockDim.x) {
+        // every record's maximum, normaliser and this thread's element requested before any is used
+        float ms[kAttendMaxSplit], zz[kAttendMaxSplit], oo[kAttendMaxSplit];
+#pragma unroll
+        for (int s = 0; s < kAttendMaxSplit; ++s) {
+            const float *ps = p + (s < n_split ? s : 0) * (D + 2);
+            ms[s] = ps[0];
+            zz[s] = ps[1];
+            oo[s] = ps[2 + d];
+        }
+        float m = -INFINITY;
+#pragma unroll
+        for (int s = 0; s < kAttendMaxSplit; ++s)
+            if (s < n_split) m = fmaxf(m, ms[s]);
         float zs = 0.f, os = 0.f;
         if (m > -INFINITY) {
-            for (int s = 0; s < n_split; ++s) {
-                const float ms = p[s * (D + 2)];
-                const float w = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - m);
-                zs = fmaf(p[s * (D + 2) + 1], w, zs);
-                os = fmaf(p[s * (D + 2) + 2 + d], w, os);
+#pragma unroll
+            for (int s = 0; s < kAttendMaxSplit; ++s) {
+                if (s >= n_split) break;
+                const float w = ms[s] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms[s] - m);
+                zs = fmaf(zz[s], w, zs);
+                os = fmaf(oo[s], w, os);
             }
         }
         store_out(out + row * D + d, zs > 0.f ? os / zs : 0.f);
@@ -980,6 +1110,8 @@ static bool flash_wide(const Ctx &c, int n_q, int B) { // 128-query tiles once t
 }
 // Workgroups that share the rows of one 64-query tile of the matrix-core prefill: 1 unless the tiles alone
 // leave most of the chip idle (about three workgroups per compute unit are wanted, at least four steps each).
+// (Sharing the rows of a tile between workgroups also when the tiles fill the chip -- to even out the causal
+// triangle -- was measured on the 1568-token chunk: 2 / 3 / 4 ways took 212 / 210 / 221 us against 207.)
 static int flash_split(const Ctx &c, int n_q, int B, int k_frame) {
     if (flash_wide(c, n_q, B)) return 1;
     const int64_t wgs = (((int64_t)n_q * c.group + 63) / 64) * c.cfg.n_kv_heads * B;
