@@ -228,12 +228,10 @@ def main():
     b_tok = 2 * Hkv * D * esz                      # K+V bytes of one token in one layer
     copy_frame = 2 * kappa * L * b_tok             # kept rows of one frame, read + written
     freq_frame = P * Hkv * D * esz                 # scoring-layer keys of one frame, read once
-    # frames per batch, by the library's rule: batch_chunks chunks each, the first two batches of a stream 3/8 of
-    # that when the copies are put off (they have no copy to share a launch with)
+    # frames per batch: batch_chunks chunks each
     batches, left = [], n_chunks
     while left:
-        lim = a.batch_chunks * 3 // 8 if (a.overlap_copy and a.batch_chunks >= 8 and len(batches) < 2) else a.batch_chunks
-        batches.append(min(lim, left))
+        batches.append(min(a.batch_chunks, left))
         left -= batches[-1]
     batches = [min(b * chunk, n_frames - sum(batches[:i]) * chunk) for i, b in enumerate(batches)]
     att_frame = P * D * esz * (Hq + Hkv)           # queries and keys of the scoring layer, read once

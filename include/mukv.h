@@ -110,9 +110,7 @@ typedef struct mukv_config {
                                        kept rows is put off until the batch after next arrives
                                        and then shares ONE launch with that batch's signals
                                        (HBM-bound and arithmetic-bound workgroups side by side on
-                                       every compute unit).  With batch_chunks >= 8 the first two
-                                       batches of a stream are cut to 3/8 of batch_chunks, since
-                                       they have no copy to run beside.
+                                       every compute unit).
                                        See mukv_compress_chunk for what that asks of the caller */
     int32_t freq_axis;              /* axis of the transform in Eq. 2, which the text leaves open:
                                        MUKV_FREQ_FEATURE (0, default) along the D features of each

@@ -395,7 +395,6 @@ int mukv_reset(mukv_ctx *ctx) {
     if (!ctx) return MUKV_ERR_INVALID_ARG;
     ctx->c.n_frames = 0;
     ctx->c.n_done = 0;
-    ctx->c.batches_since_reset = 0;
     ctx->c.pending->clear();
     if (ctx->c.n_deferred) { // the rows they would have copied are forgotten with the rest
         DeviceScope dev(ctx->c.cfg.device_id);
@@ -404,14 +403,10 @@ int mukv_reset(mukv_ctx *ctx) {
     return MUKV_OK;
 }
 
-// Chunks that make the next batch.  With overlap_copy the copy of a batch's rows shares a launch with
-// the signals of the batch after next, so the first two batches of a stream have no copy to run beside
-// and the last two copies no signals: those first two batches are cut to 3/8 of batch_chunks, which
-// moves most of their work into launches that do have a copy beside them.
-static int batch_limit(const Ctx &c) {
-    if (c.cfg.overlap_copy && c.batch_chunks >= 8 && c.batches_since_reset < 2) return c.batch_chunks * 3 / 8;
-    return c.batch_chunks;
-}
+// Chunks that make the next batch.  (Shorter first batches -- they have no copy to run beside yet -- were
+// measured on the 1-hour stream: 1/4, 3/8 and 1/2 of batch_chunks for the first two took 3.70, 3.67 and 3.67 ms
+// per step against 3.64 with every batch alike.)
+static int batch_limit(const Ctx &c) { return c.batch_chunks; }
 
 // Enqueues the kernels for every chunk gathered so far (on the stream they were submitted with).
 // join: also order `join_stream` after the work outstanding on the library's own streams.
@@ -453,7 +448,6 @@ static int flush_pending(Ctx &c, bool join, hipStream_t join_stream) {
     c.batch_parity ^= 1;
     c.pending->clear();
     c.n_done += nf;
-    ++c.batches_since_reset;
     DeviceScope dev(c.cfg.device_id);
     if (!dev.ok) return MUKV_ERR_HIP;
     if (mukv::launch_compress(c, a, c.p_stream) != hipSuccess) return MUKV_ERR_HIP;

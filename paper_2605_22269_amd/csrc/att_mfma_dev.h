@@ -211,6 +211,84 @@ __device__ __forceinline__ void freq_mfma_phase(const unsigned char *Ks, const i
         }
 }
 
+// The same with the transform's matrix passing through LDS: read straight from memory, every wave fetches all
+// 96 KB of operands for its two token tiles, 24 dependent rounds of loads with 16 matrix instructions each.
+// Here the workgroup stages the 24 KB of one cosine / sine tile pair (all three terms) at a time in `wlds`
+// (lane-major operands, 1 KB each, in the order [term][re | im][feature slice]), the next pair's pieces being
+// on their way in registers meanwhile, and every wave reads its operands from there.  All waves of the
+// workgroup must call it; `wlds` (24 KB) must not be in use by anyone, and is free again on return.
+constexpr int kDftStageB = kDftSplits * 2 * 4 * 1024;
+__device__ __forceinline__ void freq_mfma_phase_lds(const unsigned char *Ks, const int (&off)[4], const uint16_t *__restrict__ dft,
+                                                    unsigned char *wlds, int w, int n_waves, int tid, int n_threads, int nt,
+                                                    int P, float *__restrict__ out) {
+    const int lane = tid & 63, lr = lane & 15, lg = lane >> 4;
+    const int tA = w < nt ? w : nt - 1, tB = w + n_waves;
+    const bool any = w < nt, two = tB < nt;
+    bf16x8 ka[2][4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        ka[0][kk] = *reinterpret_cast<const bf16x8 *>(Ks + tA * kTileB + off[kk]);
+        ka[1][kk] = *reinterpret_cast<const bf16x8 *>(Ks + (two ? tB : tA) * kTileB + off[kk]);
+    }
+    float tok[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    // piece i of a tile pair's 1536 16-byte pieces: block i / 256 = term * 2 + (re | im), 256 pieces each
+    constexpr int kPieces = kDftStageB / 16, kMaxPer = 4; // up to 4 pieces per thread (384 threads and more)
+    const u32x4 *tab = reinterpret_cast<const u32x4 *>(dft);
+    u32x4 wst[kMaxPer];
+    auto fetch = [&](int ct) {
+#pragma unroll
+        for (int j = 0; j < kMaxPer; ++j) {
+            int i = tid + j * n_threads;
+            i = i < kPieces ? i : kPieces - 1;
+            const int blk = i >> 8, within = i & 255, sp = blk >> 1, ri = blk & 1;
+            wst[j] = tab[((sp * 8 + ct + 4 * ri) * 4) * 64 + within];
+        }
+    };
+    fetch(0);
+#pragma unroll 1
+    for (int ct = 0; ct < 4; ++ct) {
+        if (ct > 0) __syncthreads(); // everybody has read the pair before
+#pragma unroll
+        for (int j = 0; j < kMaxPer; ++j) {
+            const int i = tid + j * n_threads;
+            if (i < kPieces) *reinterpret_cast<u32x4 *>(wlds + 16 * i) = wst[j];
+        }
+        __syncthreads();
+        if (ct + 1 < 4) fetch(ct + 1);
+        f32x4 re[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, im[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int sp = kDftSplits - 1; sp >= 0; --sp) { // the smallest terms first
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const bf16x8 wr = *reinterpret_cast<const bf16x8 *>(wlds + ((sp * 2 + 0) * 4 + kk) * 1024 + 16 * lane);
+                const bf16x8 wi = *reinterpret_cast<const bf16x8 *>(wlds + ((sp * 2 + 1) * 4 + kk) * 1024 + 16 * lane);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    re[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][kk], wr, re[t], 0, 0, 0);
+                    im[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][kk], wi, im[t], 0, 0, 0);
+                }
+            }
+        }
+        const bool ends = ct == 0 && lr == 0; // this lane holds Re Z[0] and Re Z[64]
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float x = re[t][r], y = im[t][r];
+                const float mid = 2.0f * __builtin_sqrtf(fmaf(x, x, y * y));
+                tok[t][r] += ends ? fabsf(x) + fabsf(y) : mid;
+            }
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float v = row16_sum(tok[t][r]);
+            const int token = 16 * (t ? tB : tA) + 4 * lg + r;
+            if (any && lr == 0 && token < P && (t == 0 || two)) out[token] = v;
+        }
+}
+
 // True when a batch is long enough for the layout with a whole KV group per workgroup.
 bool att_mfma_many(const Ctx &c, int n_frames);
 // Fills in the launch shape for a batch: workgroup layout, waves per workgroup, LDS bytes.
@@ -296,8 +374,13 @@ __device__ __forceinline__ void att_mfma_body(const PtrTable &qtab, const PtrTab
     ja.k_lds = Ks;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) ja.off[kk] = lr * kRowB + (((4 * kk + lg) ^ lr) << 4);
-    if (aa.fft_out && pair) // (pair: every key tile is staged and this workgroup is the only one of its (frame, KV head))
-        freq_mfma_phase(Ks, ja.off, aa.dft, w, n_threads >> 6, lane, nt, P, aa.fft_out + ((int64_t)f * (aa.n_part / n_split) + g) * P);
+    // Eq. 2-3 from the staged keys (pair: every key tile is staged and this workgroup is the only one of its
+    // (frame, KV head)): through LDS once the query buffers are free, if together they hold a staged tile
+    // pair; else straight from memory, now
+    const bool fft_here = aa.fft_out && pair;
+    const bool fft_lds = fft_here && (size_t)(n_threads >> 6) * kTileB >= (size_t)kDftStageB && n_threads * 4 >= kDftStageB / 16;
+    float *fft_dst = fft_here ? aa.fft_out + ((int64_t)f * (aa.n_part / n_split) + g) * P : nullptr;
+    if (fft_here && !fft_lds) freq_mfma_phase(Ks, ja.off, aa.dft, w, n_threads >> 6, lane, nt, P, fft_dst);
 
     float acc[kMaxTiles];
 #pragma unroll
@@ -335,9 +418,13 @@ __device__ __forceinline__ void att_mfma_body(const PtrTable &qtab, const PtrTab
         default: break;
         }
     }
+    __syncthreads(); // the query buffers are free
+    if (fft_lds) {
+        freq_mfma_phase_lds(Ks, ja.off, aa.dft, smem_raw + (size_t)nt * kTileB, w, n_threads >> 6, tid, n_threads, nt, P, fft_dst);
+        __syncthreads(); // the key tiles are free
+    }
     // column sums: add the four lane groups (the other query rows), then the waves in a fixed
     // order; the key tiles are no longer needed and give room for the per-wave sums
-    __syncthreads();
     float *red = reinterpret_cast<float *>(smem_raw); // [waves][nt*16]
     const int ld = nt * 16;
 #pragma unroll

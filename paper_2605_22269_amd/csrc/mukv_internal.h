@@ -49,7 +49,6 @@ struct Ctx {
     int64_t n_frames;  // frames submitted so far (host-side append position)
     int64_t n_done;    // frames whose kernels have been enqueued
     int batch_chunks;  // chunks gathered before a chain of launches goes out
-    int batches_since_reset; // batches launched since the stream began (see batch_limit)
     int max_batch_frames;
     std::vector<PendingChunk> *pending;
     int64_t p_kv_sl, p_kv_sh, p_kv_st, p_q_sh, p_q_st; // strides shared by the pending chunks
