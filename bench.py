@@ -418,6 +418,50 @@ def main():
                                            "gather_bytes_q0": 2 * u_tok * L * b_tok}
     del ug_out
 
+    # ---- three independently compressed stores (Sec. 3.3, Sec. 4.1): segment units of 4 frames (rho 0.8,
+    # alpha 0.8), the middle frame of each (0.1, 0.7) and that frame's 4 super-patches (0.1, 0.5), each a context
+    # of its own fed from the same resident stream with the attention signal handed over; the question ranks the
+    # segment store (k = 12), whose global query reranks the frame (k = 32) and patch (k = 20) stores, and one
+    # gather packs the 12 * 627 + 32 * 19 + 20 * 4 = 8212 kept rows in temporal order ----
+    if a.workload == "hour" and not a.frames and chunk % 4 == 0 and P % 4 == 0:
+        Fs, Ts = 4, n_frames // 4
+        specs = [(Fs * P, 0.8, 0.8, Ts, chunk // Fs), (P, 0.1, 0.7, Ts, 1), (P // 4, 0.1, 0.5, Ts * 4, 4)]
+        stores = [mk.MuKV(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, tokens_per_frame=u, frames_per_segment=1,
+                          superpatches_per_frame=1, dtype=w.torch_dtype, keep_ratio=rho, alpha=al, max_frames=nu,
+                          max_chunk_frames=mc, max_questions=B, batch_chunks=1, overlap_copy=0)
+                  for u, rho, al, nu, mc in specs]
+        sig = [synth.handed_over_attention(nu, u, a.seed + 70 + i, tie_fraction=0.0).to(dev) for i, (u, _, _, nu, _) in enumerate(specs)]
+        per = chunk // Fs  # time steps per chunk of the stream
+        for c in range(n_chunks):
+            stores[0].compress_chunk(ks[c], vs[c], None, att_signal=sig[0][c * per:(c + 1) * per])
+            for j in range(per):
+                t, lo = c * per + j, (j * Fs + Fs // 2) * P
+                kf, vf = ks[c][:, :, lo:lo + P], vs[c][:, :, lo:lo + P]
+                stores[1].compress_chunk(kf, vf, None, att_signal=sig[1][t:t + 1])
+                stores[2].compress_chunk(kf, vf, None, att_signal=sig[2][4 * t:4 * t + 4])
+        for st_ in stores:
+            st_.flush()
+        torch.cuda.synchronize()
+        kap3 = [st_.kappa for st_ in stores]
+        k3 = [12, 32, 20]
+        cap3 = sum(k * c for k, c in zip(k3, kap3))
+
+        def three_stores():
+            g0 = stores[0].retrieve_units(q_tokens, offs, k3[0], want_g=True)
+            g1 = stores[1].retrieve_units(q_tokens, offs, k3[1], 0.3, g_in=g0["g"])
+            g2 = stores[2].retrieve_units(q_tokens, offs, k3[2], 0.3, g_in=g0["g"])
+            return mk.gather_multi(stores, [g0["idx"], g1["idx"], g2["idx"]], [1, 1, 4], cap3)
+
+        out3 = three_stores()
+        t3 = timed(three_stores, 20)
+        torch.cuda.synchronize()
+        n3 = int(out3[2][0])
+        res["retrieve_gather_three_stores"] = {"units": [sp[3] for sp in specs], "unit_tokens": [sp[0] for sp in specs],
+                                               "kept_per_unit": kap3, "k": k3, "ms_per_batch": t3, "launch": "eager calls",
+                                               "tokens_gathered_q0": n3, "gather_bytes_q0": 2 * n3 * L * b_tok,
+                                               "gather_GBs_over_whole_call": 2 * n3 * L * b_tok / (t3 * 1e-3) / 1e9}
+        del out3, stores, sig
+
     res["retrieve_gather_super_patches"] = {"k_patch": 20, "keys_scored": n_frames * w.superpatches_per_frame,
                                             "ms_per_batch": pms, "ms_per_question": pms / B,
                                             "tokens_gathered_q0": int(pg_out[2][0])}
