@@ -1243,42 +1243,68 @@ struct MultiGatherArgs {
     int L, Hkv;
 };
 
-__global__ __launch_bounds__(256) void multi_gather_kernel(MultiGatherArgs a) {
+// Grid (x, slab = (layer, K|V, KV head), question): workgroup x moves output rows x * rows_per_wg ... of its slab,
+// whatever entries they belong to (a segment unit's hundreds of rows are shared by several workgroups, a
+// super-patch unit's four rows are a fraction of one): the entries' first output rows sit in LDS, a lane finds
+// the entry of its first row by bisection and walks on from there; a lane holds one 16-byte piece of
+// kMultiIter rows, all requested before the first is stored.  Rows past the context are zero.
+constexpr int kMultiIter = 8;
+__global__ __launch_bounds__(256) void multi_gather_kernel(MultiGatherArgs a, int rows_per_wg) {
+    __shared__ int e_start[kMaxMultiEntries + 1];
     const int tid = threadIdx.x, b = blockIdx.z, y = blockIdx.y;
     const int n_ent = a.count[2 * b], n_rows = a.count[2 * b + 1];
     if (a.n_tokens_out && blockIdx.x == 0 && y == 0 && tid == 0) a.n_tokens_out[b] = n_rows;
     const int32_t *entry = a.entry + (int64_t)b * kMaxMultiEntries * 3;
+    for (int e = tid; e < n_ent; e += 256) e_start[e] = entry[3 * e + 2];
+    if (tid == 0) e_start[n_ent] = n_rows;
+    __syncthreads();
     const int l = y / (2 * a.Hkv), rem = y - l * 2 * a.Hkv;
     const int kv = rem / a.Hkv, g = rem - kv * a.Hkv;
     unsigned char *dst = (kv ? a.v_out : a.k_out) + (((int64_t)b * a.L + l) * a.Hkv + g) * ((int64_t)a.rows_cap * a.row_b);
-    const int upr = 1 << a.upr_log;
-    for (int e = blockIdx.x; e < n_ent; e += gridDim.x) {
-        const int st = entry[3 * e], unit = entry[3 * e + 1], out_row = entry[3 * e + 2];
-        const MultiStore &ms = a.s[st];
-        const int c = ms.kappa;
-        const int c_fit = out_row + c <= a.rows_cap ? c : (a.rows_cap > out_row ? a.rows_cap - out_row : 0);
-        const unsigned char *s0 = (kv ? ms.store_v : ms.store_k) + ((int64_t)l * a.Hkv + g) * ms.slab_b +
-                                  (int64_t)unit * c * a.row_b;
-        unsigned char *d0 = dst + (int64_t)out_row * a.row_b;
-        const int n_u = c_fit * upr;
-        for (int u0 = tid; u0 < n_u; u0 += 4 * 256) { // four 16-byte pieces in flight per lane
-            cp_u32x4 x[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int u = u0 + j * 256 < n_u ? u0 + j * 256 : n_u - 1;
-                x[j] = *reinterpret_cast<const cp_u32x4 *>(s0 + (int64_t)u * 16);
+    const int64_t slab = (int64_t)l * a.Hkv + g;
+    const int upr = 1 << a.upr_log, rpp = 256 >> a.upr_log; // pieces per row, rows per pass of the workgroup
+    const int piece = tid & (upr - 1), rsub = tid >> a.upr_log;
+    const int r_lo = blockIdx.x * rows_per_wg;
+    const int r_hi = r_lo + rows_per_wg < a.rows_cap ? r_lo + rows_per_wg : a.rows_cap;
+    const int n_copy = n_ent > 0 ? (n_rows < a.rows_cap ? n_rows : a.rows_cap) : 0; // rows that hold something
+    for (int r0 = r_lo + rsub; r0 < r_hi; r0 += kMultiIter * rpp) {
+        // entry of the lane's first row: the last one that starts at or before it
+        int e = 0;
+        if (r0 < n_copy) {
+            int lo = 0, hi = n_ent - 1;
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (e_start[mid] <= r0)
+                    lo = mid;
+                else
+                    hi = mid - 1;
             }
+            e = lo;
+        }
+        cp_u32x4 x[kMultiIter];
+        bool live[kMultiIter];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (u0 + j * 256 < n_u) *reinterpret_cast<cp_u32x4 *>(d0 + (int64_t)(u0 + j * 256) * 16) = x[j];
+        for (int it = 0; it < kMultiIter; ++it) {
+            const int r = r0 + it * rpp;
+            live[it] = r < r_hi && r < n_copy;
+            x[it] = cp_u32x4{0u, 0u, 0u, 0u};
+            if (n_copy > 0) { // (uniform) loads are unconditional on a clamped row
+                const int rc = live[it] ? r : n_copy - 1;
+                while (e + 1 < n_ent && e_start[e + 1] <= rc) ++e;
+                const MultiStore &ms = a.s[entry[3 * e]];
+                const unsigned char *src = (kv ? ms.store_v : ms.store_k) + slab * ms.slab_b +
+                                           ((int64_t)entry[3 * e + 1] * ms.kappa + (rc - e_start[e])) * a.row_b + piece * 16;
+                x[it] = *reinterpret_cast<const cp_u32x4 *>(src);
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < kMultiIter; ++it) {
+            const int r = r0 + it * rpp;
+            if (r < r_hi)
+                *reinterpret_cast<cp_u32x4 *>(dst + (int64_t)r * a.row_b + piece * 16) =
+                    live[it] ? x[it] : cp_u32x4{0u, 0u, 0u, 0u};
         }
     }
-    // rows past the context are zero
-    const int first = n_rows < a.rows_cap ? n_rows : a.rows_cap;
-    const int64_t n_zero = (int64_t)(a.rows_cap - first) * upr;
-    unsigned char *z0 = dst + (int64_t)first * a.row_b;
-    for (int64_t u = (int64_t)blockIdx.x * 256 + tid; u < n_zero; u += (int64_t)gridDim.x * 256)
-        *reinterpret_cast<cp_u32x4 *>(z0 + u * 16) = cp_u32x4{0u, 0u, 0u, 0u};
 }
 
 // Plain streaming copy, 4 x 16 bytes per thread: the calibration kernel for traffic counters.
@@ -1588,7 +1614,13 @@ hipError_t launch_gather_multi(const MultiArgs &a, hipStream_t st) {
     g.rows_cap = a.rows_cap;
     g.L = c0.cfg.n_layers;
     g.Hkv = c0.cfg.n_kv_heads;
-    hipLaunchKernelGGL(multi_gather_kernel, dim3(64, c0.cfg.n_layers * 2 * c0.cfg.n_kv_heads, a.B), dim3(256), 0, st, g);
+    // one pass of kMultiIter rows per lane and workgroup, where the output is short enough for the grid
+    const int rpp = 256 >> lg;
+    int rows_per_wg = kMultiIter * rpp;
+    if ((a.rows_cap + rows_per_wg - 1) / rows_per_wg > 4096) rows_per_wg = (a.rows_cap + 4095) / 4096;
+    const int gx = a.rows_cap > 0 ? (a.rows_cap + rows_per_wg - 1) / rows_per_wg : 1;
+    hipLaunchKernelGGL(multi_gather_kernel, dim3(gx, c0.cfg.n_layers * 2 * c0.cfg.n_kv_heads, a.B), dim3(256), 0, st, g,
+                       rows_per_wg);
     return hipGetLastError();
 }
 
