@@ -244,6 +244,31 @@ def test_gather_orders_and_padding():
     p.close()
 
 
+@pytest.mark.parametrize("k_frame", [1, 63, 64, 65, 130])
+def test_gather_list_lengths_around_a_wave(k_frame):
+    # lists of up to 64 entries are planned inside a wave, longer ones in LDS: same bytes either way, with
+    # padding, numbers past the cache and a frame named twice in the list
+    w = W["tiny"].scaled(n_frames=80, n_layers=2, n_questions=2)
+    p = Pair(w, seed=43, chunk=16)
+    p.ingest()
+    rng = np.random.default_rng(k_frame)
+    lists = np.stack([rng.permutation(80)[:k_frame] if k_frame <= 80 else rng.integers(0, 80, k_frame) for _ in range(2)])
+    if k_frame >= 3:
+        lists[0, 1] = -1
+        lists[1, 0] = 80
+        lists[1, k_frame - 1] = lists[1, k_frame - 2]
+    idx = torch.tensor(lists, dtype=torch.int32, device="cuda")
+    for order, oorder in ((mk.MUKV_TEMPORAL, orc.TEMPORAL), (mk.MUKV_AS_GIVEN, orc.AS_GIVEN)):
+        kg, vg, nt = p.gpu.gather_kv(idx, order)
+        torch.cuda.synchronize()
+        for b in range(2):
+            ko, vo, n = p.orc.gather(lists[b].astype(np.int64), oorder)
+            assert int(nt[b]) == n
+            np.testing.assert_array_equal(np_view(kg[b]), ko)
+            np.testing.assert_array_equal(np_view(vg[b]), vo)
+    p.close()
+
+
 def test_determinism_bitwise():
     w = W["7b"].scaled(n_frames=8, n_layers=2)
     outs = []
